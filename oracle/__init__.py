@@ -1,0 +1,224 @@
+"""ECF8 CPU oracle -- TEST INFRASTRUCTURE ONLY.
+
+ctypes front end of the plain-C oracle in this directory.  Only ``tests/``,
+``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py`` may
+import this package; the product never does, and this package never imports the
+product.  All arrays are numpy ``uint8``/``uint64`` on the host.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_DIR = os.path.dirname(os.path.abspath(__file__))
+_SRC = [os.path.join(_DIR, f) for f in ("ecf8_oracle.c", "ecf8_container.c", "paper_alg1.c", "gemm_ref.c")]
+_LIB = os.path.join(_DIR, "libecf8_oracle.so")
+
+MSB_FIRST = 0
+LSB_FIRST = 1
+
+OK = 0
+E_ARG, E_FORMAT, E_CAPACITY, E_CODE, E_META = -1, -2, -3, -4, -5
+
+
+def build(force=True):
+    """Compile the oracle with gcc (-O2, no vectorisation flags)."""
+    srcs = [s for s in _SRC if os.path.exists(s)]
+    if not force and os.path.exists(_LIB) and all(
+            os.path.getmtime(_LIB) >= os.path.getmtime(s) for s in srcs):
+        return _LIB
+    cmd = ["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-Wall", "-Wextra", "-o", _LIB] + srcs + ["-lm"]
+    subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build(force=False)
+        _lib = ctypes.CDLL(_LIB)
+        _lib.orc_entropy_bits.restype = ctypes.c_double
+        _lib.orc_stream_bits.restype = ctypes.c_uint64
+        _lib.orc_container_size.restype = ctypes.c_uint64
+        _lib.orc_container_size.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint32]
+    return _lib
+
+
+def _p(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _u8(a):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.uint8
+    return a.reshape(-1)
+
+
+def histogram(x):
+    x = _u8(x)
+    freq = np.zeros(16, dtype=np.uint64)
+    lib().orc_histogram(_p(x), ctypes.c_uint64(x.size), _p(freq))
+    return freq
+
+
+def entropy_bits(freq):
+    freq = np.ascontiguousarray(freq, dtype=np.uint64)
+    return float(lib().orc_entropy_bits(_p(freq)))
+
+
+def huffman_lengths(freq):
+    freq = np.ascontiguousarray(freq, dtype=np.uint64)
+    assert freq.size == 16
+    ln = np.zeros(16, dtype=np.uint8)
+    rc = lib().orc_huffman_lengths(_p(freq), _p(ln))
+    if rc < 0:
+        raise ValueError("orc_huffman_lengths: %d" % rc)
+    return ln
+
+
+def canonical_codes(lengths):
+    lengths = np.ascontiguousarray(lengths, dtype=np.uint8)
+    code = np.zeros(16, dtype=np.uint16)
+    rc = lib().orc_canonical_codes(_p(lengths), _p(code))
+    if rc:
+        raise ValueError("orc_canonical_codes: %d" % rc)
+    return code
+
+
+def stream_bits(freq, lengths):
+    freq = np.ascontiguousarray(freq, dtype=np.uint64)
+    lengths = np.ascontiguousarray(lengths, dtype=np.uint8)
+    return int(lib().orc_stream_bits(_p(freq), _p(lengths)))
+
+
+def encode_exponents(x, lengths, codes, order=MSB_FIRST):
+    """Bit-serial encoder; returns (stream bytes, nbits)."""
+    x = _u8(x)
+    lengths = np.ascontiguousarray(lengths, dtype=np.uint8)
+    codes = np.ascontiguousarray(codes, dtype=np.uint16)
+    cap = (x.size * 15 + 7) // 8 + 1
+    stream = np.zeros(cap, dtype=np.uint8)
+    nbits = ctypes.c_uint64(0)
+    rc = lib().orc_encode_exponents(_p(x), ctypes.c_uint64(x.size), _p(lengths), _p(codes),
+                                    ctypes.c_int(order), _p(stream), ctypes.c_uint64(cap),
+                                    ctypes.byref(nbits), ctypes.c_uint64(0), None)
+    if rc:
+        raise ValueError("orc_encode_exponents: %d" % rc)
+    nb = int(nbits.value)
+    return stream[: (nb + 7) // 8].copy(), nb
+
+
+def pack_nibbles_paper(x):
+    x = _u8(x)
+    packed = np.zeros((x.size + 1) // 2, dtype=np.uint8)
+    lib().orc_pack_nibbles_paper(_p(x), ctypes.c_uint64(x.size), _p(packed))
+    return packed
+
+
+def decode_serial(stream, nbits, lengths, packed, n, order=MSB_FIRST):
+    stream = _u8(stream)
+    packed = _u8(packed)
+    lengths = np.ascontiguousarray(lengths, dtype=np.uint8)
+    out = np.zeros(n, dtype=np.uint8)
+    rc = lib().orc_decode_serial(_p(stream), ctypes.c_uint64(nbits), ctypes.c_int(order),
+                                 _p(lengths), _p(packed), ctypes.c_uint64(n), _p(out))
+    if rc:
+        raise ValueError("orc_decode_serial: %d" % rc)
+    return out
+
+
+def roundtrip(x):
+    """decode(encode(x)) entirely inside the oracle; returns (out, nbits, lengths)."""
+    x = _u8(x)
+    out = np.zeros(x.size, dtype=np.uint8)
+    nbits = ctypes.c_uint64(0)
+    ln = np.zeros(16, dtype=np.uint8)
+    rc = lib().orc_roundtrip(_p(x), ctypes.c_uint64(x.size), _p(out), ctypes.byref(nbits), _p(ln))
+    if rc:
+        raise ValueError("orc_roundtrip: %d" % rc)
+    return out, int(nbits.value), ln
+
+
+def container_encode(x, rows, cols, lane_syms):
+    x = _u8(x)
+    assert x.size == rows * cols
+    cap = int(lib().orc_container_size(x.size, x.size * 15, lane_syms)) + 256
+    blob = np.zeros(cap, dtype=np.uint8)
+    size = ctypes.c_uint64(0)
+    rc = lib().orc_container_encode(_p(x), ctypes.c_uint64(rows), ctypes.c_uint64(cols),
+                                    ctypes.c_uint32(lane_syms), _p(blob), ctypes.c_uint64(cap),
+                                    ctypes.byref(size))
+    if rc:
+        raise ValueError("orc_container_encode: %d" % rc)
+    return blob[: int(size.value)].copy()
+
+
+def container_decode(blob):
+    """Returns (decoded bytes, stream_bits); raises ValueError(code) on any inconsistency."""
+    blob = _u8(blob)
+    if blob.size < 256:
+        raise ValueError("orc_container_decode: %d" % E_FORMAT)
+    n = int(np.frombuffer(blob[16:24].tobytes(), dtype="<u8")[0])
+    out = np.zeros(max(n, 1), dtype=np.uint8)
+    n_out = ctypes.c_uint64(0)
+    bits = ctypes.c_uint64(0)
+    rc = lib().orc_container_decode(_p(blob), ctypes.c_uint64(blob.size), _p(out),
+                                    ctypes.c_uint64(out.size), ctypes.byref(n_out), ctypes.byref(bits))
+    if rc:
+        raise ValueError("orc_container_decode: %d" % rc)
+    return out[: int(n_out.value)], int(bits.value)
+
+
+def paper_build_lut(lengths, codes, width=8):
+    """Cascaded table with `width`-bit rows; returns (rows x 2^width uint8 array, n_luts)."""
+    lengths = np.ascontiguousarray(lengths, dtype=np.uint8)
+    codes = np.ascontiguousarray(codes, dtype=np.uint16)
+    lut = np.zeros(18 * 256, dtype=np.uint8)
+    n_luts = ctypes.c_uint32(0)
+    rc = lib().orc_paper_build_lut_w(_p(lengths), _p(codes), ctypes.c_uint32(width), _p(lut), ctypes.byref(n_luts))
+    if rc:
+        raise ValueError("orc_paper_build_lut_w: %d" % rc)
+    k = int(n_luts.value)
+    return lut[: k * (1 << width)].reshape(k, 1 << width).copy(), k
+
+
+def paper_alg1_roundtrip(x, T=256):
+    """Encode x into the paper's own container (B=8) and decode it with the
+    Algorithm 1 emulator.  Returns (outputs, dict of the container's arrays)."""
+    x = _u8(x)
+    n = x.size
+    freq = histogram(x)
+    ln0 = huffman_lengths(freq)
+    bits = stream_bits(freq, ln0)
+    n_bytes = ctypes.c_uint64(0)
+    n_blocks = ctypes.c_uint64(0)
+    alloc = ctypes.c_uint64(0)
+    gbytes = ctypes.c_uint64(0)
+    lib().orc_paper_sizes(ctypes.c_uint64(bits), ctypes.c_uint32(T), ctypes.byref(n_bytes),
+                          ctypes.byref(n_blocks), ctypes.byref(alloc), ctypes.byref(gbytes))
+    ln = np.zeros(16, dtype=np.uint8)
+    lut = np.zeros(18 * 256, dtype=np.uint8)
+    n_luts = ctypes.c_uint32(0)
+    encoded = np.zeros(int(alloc.value), dtype=np.uint8)
+    packed = np.zeros((n + 1) // 2, dtype=np.uint8)
+    outpos = np.zeros(int(n_blocks.value) + 1, dtype=np.int64)
+    gaps = np.zeros(int(gbytes.value), dtype=np.uint8)
+    nb2 = ctypes.c_uint64(0)
+    nbl2 = ctypes.c_uint64(0)
+    rc = lib().orc_paper_encode(_p(x), ctypes.c_uint64(n), ctypes.c_uint32(T), _p(ln), _p(lut),
+                                ctypes.byref(n_luts), _p(encoded), ctypes.c_uint64(encoded.size),
+                                ctypes.byref(nb2), _p(packed), _p(outpos), _p(gaps), ctypes.byref(nbl2))
+    if rc:
+        raise ValueError("orc_paper_encode: %d" % rc)
+    out = np.zeros(n, dtype=np.uint8)
+    rc = lib().orc_paper_alg1_decode(_p(lut), n_luts, _p(encoded), nb2, _p(packed), _p(outpos), _p(gaps),
+                                     nbl2, ctypes.c_uint32(T), ctypes.c_uint64(n), _p(out))
+    if rc:
+        raise ValueError("orc_paper_alg1_decode: %d" % rc)
+    return out, dict(lengths=ln, lut=lut, n_luts=int(n_luts.value), encoded=encoded,
+                     n_bytes=int(nb2.value), packed=packed, outpos=outpos, gaps=gaps,
+                     n_blocks=int(nbl2.value), stream_bits=bits)

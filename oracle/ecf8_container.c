@@ -1,0 +1,284 @@
+/*
+ * ECF8 CPU oracle, part 2 -- TEST INFRASTRUCTURE ONLY.
+ *
+ * Slow reader and writer of the chunked ECF8 container, written from the
+ * container's format description alone (byte offsets below), sharing no code
+ * or header with the product.  The container replaces the paper's
+ * synchronisation metadata (Section 3.1: per-thread gaps and per-block output
+ * positions, Table 4 "gaps"/"outpos") by a sampling of codeword start
+ * positions: the stream itself is still the plain in-order concatenation of
+ * the codewords (Section 3.1, "continuous bitstream").
+ *
+ * Container (all integers little-endian):
+ *   header, 256 bytes:
+ *     0   u32 magic 0x38464345 ("ECF8")     4   u32 version (1)
+ *     8   u64 total_size                    16  u64 n_elem
+ *     24  u64 rows                          32  u64 cols
+ *     40  u32 lane_syms N                   44  u32 lanes_per_chunk (64)
+ *     48  u64 n_chunks = ceil(n_elem/(64N)) 56  u64 stream_bits
+ *     64  u8  code_len[16]
+ *     80  u64 off_chunk_bit   88 u64 off_lane_bits
+ *     96  u64 off_stream      104 u64 off_plane
+ *     112 u64 stream_bytes    120 u64 plane_bytes
+ *     128 u64 freq[16]
+ *   chunk_bit : u64[n_chunks+1]   start bit of the first codeword of chunk c;
+ *                                 last entry = stream_bits
+ *   lane_bits : u16[n_chunks*64]  total code bits of the (up to N) elements
+ *                                 [c*64N + l*N, +N) clipped to n_elem
+ *   stream    : stream_bytes bytes; stream bit i = bit (i&7) of byte (i>>3);
+ *               each codeword is written first-bit-first (its most
+ *               significant bit first); codes are canonical from code_len,
+ *               ordered by (length, symbol); zero padded,
+ *               stream_bytes = roundup16(ceil(stream_bits/8) + 8)
+ *   plane     : sign/mantissa nibbles q = sign<<3 | mantissa (Table 4,
+ *               "packed"), regrouped: element i sits in byte
+ *               (i/8)*4 + (i%4), low nibble when (i%8) < 4, else high
+ *               nibble; plane_bytes = n_chunks*32N, zero padded
+ *   every section starts at a multiple of 256 bytes.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORC_NSYM 16
+#define ORC_LSB_FIRST 1
+#define ORC_OK 0
+#define ORC_E_ARG (-1)
+#define ORC_E_FORMAT (-2)
+#define ORC_E_CAPACITY (-3)
+#define ORC_E_CODE (-4)
+#define ORC_E_META (-5)
+
+/* from ecf8_oracle.c */
+void orc_split(uint8_t v, uint8_t *s, uint8_t *e, uint8_t *m);
+uint8_t orc_join(uint8_t s, uint8_t e, uint8_t m);
+void orc_histogram(const uint8_t *x, uint64_t n, uint64_t freq[ORC_NSYM]);
+int orc_huffman_lengths(const uint64_t freq[ORC_NSYM], uint8_t len[ORC_NSYM]);
+int orc_canonical_codes(const uint8_t len[ORC_NSYM], uint16_t code[ORC_NSYM]);
+uint64_t orc_stream_bits(const uint64_t freq[ORC_NSYM], const uint8_t len[ORC_NSYM]);
+int orc_encode_exponents(const uint8_t *x, uint64_t n, const uint8_t len[ORC_NSYM],
+                         const uint16_t code[ORC_NSYM], int order, uint8_t *stream,
+                         uint64_t stream_cap_bytes, uint64_t *nbits_out,
+                         uint64_t mark_every, uint64_t *marks);
+int orc_decode_symbols(const uint8_t *stream, uint64_t nbits, int order,
+                       const uint8_t len[ORC_NSYM], uint64_t n, uint8_t *sym_out);
+
+static uint64_t rd64(const uint8_t *p)
+{
+    uint64_t v = 0;
+    for (int i = 7; i >= 0; i--) v = (v << 8) | p[i];
+    return v;
+}
+static uint32_t rd32(const uint8_t *p)
+{
+    return (uint32_t)p[0] | ((uint32_t)p[1] << 8) | ((uint32_t)p[2] << 16) | ((uint32_t)p[3] << 24);
+}
+static uint32_t rd16(const uint8_t *p) { return (uint32_t)p[0] | ((uint32_t)p[1] << 8); }
+static void wr64(uint8_t *p, uint64_t v) { for (int i = 0; i < 8; i++) p[i] = (uint8_t)(v >> (8 * i)); }
+static void wr32(uint8_t *p, uint32_t v) { for (int i = 0; i < 4; i++) p[i] = (uint8_t)(v >> (8 * i)); }
+static void wr16(uint8_t *p, uint32_t v) { p[0] = (uint8_t)v; p[1] = (uint8_t)(v >> 8); }
+static uint64_t up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+
+static uint64_t plane_byte_index(uint64_t i) { return (i / 8) * 4 + (i % 4); }
+static int plane_is_high(uint64_t i) { return (i % 8) >= 4; }
+
+/* Size in bytes the container of an n-element tensor takes when the stream
+ * has `stream_bits` bits and lanes hold N symbols. */
+uint64_t orc_container_size(uint64_t n, uint64_t stream_bits, uint32_t N)
+{
+    uint64_t chunk = 64ull * N;
+    uint64_t n_chunks = (n + chunk - 1) / chunk;
+    uint64_t sz = 256;
+    sz = up(sz, 256) + 8 * (n_chunks + 1);
+    sz = up(sz, 256) + 2 * n_chunks * 64;
+    sz = up(sz, 256) + up((stream_bits + 7) / 8 + 8, 16);
+    sz = up(sz, 256) + n_chunks * 32ull * N;
+    return up(sz, 256);
+}
+
+/* Writer: encodes x (rows*cols raw E4M3 bytes) into blob (capacity cap).
+ * Follows Section 3.1 for histogram, optimal code and in-order stream. */
+int orc_container_encode(const uint8_t *x, uint64_t rows, uint64_t cols, uint32_t N,
+                         uint8_t *blob, uint64_t cap, uint64_t *size_out)
+{
+    uint64_t n = rows * cols;
+    if (n == 0 || N == 0 || (N % 16) != 0 || N > 256) return ORC_E_ARG;
+    uint64_t freq[ORC_NSYM];
+    uint8_t len[ORC_NSYM];
+    uint16_t code[ORC_NSYM];
+    orc_histogram(x, n, freq);
+    int rc = orc_huffman_lengths(freq, len);
+    if (rc < 0) return rc;
+    rc = orc_canonical_codes(len, code);
+    if (rc) return rc;
+    uint64_t bits = orc_stream_bits(freq, len);
+    uint64_t total = orc_container_size(n, bits, N);
+    if (total > cap) return ORC_E_CAPACITY;
+    memset(blob, 0, total);
+
+    uint64_t chunk = 64ull * N;
+    uint64_t n_chunks = (n + chunk - 1) / chunk;
+    uint64_t off_cb = 256;
+    uint64_t off_lb = up(off_cb + 8 * (n_chunks + 1), 256);
+    uint64_t off_st = up(off_lb + 2 * n_chunks * 64, 256);
+    uint64_t st_bytes = up((bits + 7) / 8 + 8, 16);
+    uint64_t off_pl = up(off_st + st_bytes, 256);
+    uint64_t pl_bytes = n_chunks * 32ull * N;
+
+    wr32(blob + 0, 0x38464345u);
+    wr32(blob + 4, 1);
+    wr64(blob + 8, total);
+    wr64(blob + 16, n);
+    wr64(blob + 24, rows);
+    wr64(blob + 32, cols);
+    wr32(blob + 40, N);
+    wr32(blob + 44, 64);
+    wr64(blob + 48, n_chunks);
+    wr64(blob + 56, bits);
+    for (int i = 0; i < ORC_NSYM; i++) blob[64 + i] = len[i];
+    wr64(blob + 80, off_cb);
+    wr64(blob + 88, off_lb);
+    wr64(blob + 96, off_st);
+    wr64(blob + 104, off_pl);
+    wr64(blob + 112, st_bytes);
+    wr64(blob + 120, pl_bytes);
+    for (int i = 0; i < ORC_NSYM; i++) wr64(blob + 128 + 8 * i, freq[i]);
+
+    /* stream + the start bit of every lane (every N-th symbol) */
+    uint64_t n_lanes = (n + N - 1) / N;
+    uint64_t *marks = (uint64_t *)calloc(n_lanes + 1, sizeof(uint64_t));
+    if (!marks) return ORC_E_CAPACITY;
+    uint64_t got = 0;
+    rc = orc_encode_exponents(x, n, len, code, ORC_LSB_FIRST, blob + off_st, st_bytes, &got, N, marks);
+    if (rc == ORC_OK && got != bits) rc = ORC_E_FORMAT;
+    if (rc) { free(marks); return rc; }
+    marks[n_lanes] = bits;
+    for (uint64_t c = 0; c < n_chunks; c++) {
+        uint64_t first_lane = c * 64;
+        wr64(blob + off_cb + 8 * c, marks[first_lane]);
+        for (uint64_t l = 0; l < 64; l++) {
+            uint64_t gl = first_lane + l;
+            uint64_t lb = gl < n_lanes ? marks[gl + 1] - marks[gl] : 0;
+            wr16(blob + off_lb + 2 * (c * 64 + l), (uint32_t)lb);
+        }
+    }
+    wr64(blob + off_cb + 8 * n_chunks, bits);
+    free(marks);
+
+    /* regrouped nibble plane */
+    for (uint64_t i = 0; i < n; i++) {
+        uint8_t s, e, m;
+        orc_split(x[i], &s, &e, &m);
+        uint8_t q = (uint8_t)((s << 3) | m);
+        uint8_t *b = blob + off_pl + plane_byte_index(i);
+        if (plane_is_high(i)) *b |= (uint8_t)(q << 4);
+        else *b |= q;
+    }
+    *size_out = total;
+    return ORC_OK;
+}
+
+/* Reader: decodes a container to out[n_elem].  Two independent passes:
+ *  (1) a metadata-free bit-serial decode of the whole stream from bit 0;
+ *  (2) a lane-by-lane bit-serial decode that starts every lane at
+ *      chunk_bit[c] + sum of lane_bits of the lanes before it in the chunk.
+ * Both must agree symbol for symbol and every lane must end exactly where
+ * the next one starts; otherwise ORC_E_META.  stream_bits_out/lenbar are
+ * returned for the size checks. */
+int orc_container_decode(const uint8_t *blob, uint64_t size, uint8_t *out, uint64_t out_cap,
+                         uint64_t *n_out, uint64_t *stream_bits_out)
+{
+    if (size < 256) return ORC_E_FORMAT;
+    if (rd32(blob) != 0x38464345u || rd32(blob + 4) != 1) return ORC_E_FORMAT;
+    uint64_t total = rd64(blob + 8), n = rd64(blob + 16);
+    uint64_t rows = rd64(blob + 24), cols = rd64(blob + 32);
+    uint32_t N = rd32(blob + 40), L = rd32(blob + 44);
+    uint64_t n_chunks = rd64(blob + 48), bits = rd64(blob + 56);
+    uint8_t len[ORC_NSYM];
+    for (int i = 0; i < ORC_NSYM; i++) len[i] = blob[64 + i];
+    uint64_t off_cb = rd64(blob + 80), off_lb = rd64(blob + 88);
+    uint64_t off_st = rd64(blob + 96), off_pl = rd64(blob + 104);
+    uint64_t st_bytes = rd64(blob + 112), pl_bytes = rd64(blob + 120);
+    if (total != size || n == 0 || rows * cols != n) return ORC_E_FORMAT;
+    if (L != 64 || N == 0 || (N % 16) != 0 || N > 256) return ORC_E_FORMAT;
+    uint64_t chunk = 64ull * N;
+    if (n_chunks != (n + chunk - 1) / chunk) return ORC_E_FORMAT;
+    if ((off_cb | off_lb | off_st | off_pl) % 256) return ORC_E_FORMAT;
+    if (off_cb < 256 || off_cb + 8 * (n_chunks + 1) > off_lb) return ORC_E_FORMAT;
+    if (off_lb + 2 * n_chunks * 64 > off_st) return ORC_E_FORMAT;
+    if (st_bytes != up((bits + 7) / 8 + 8, 16) || off_st + st_bytes > off_pl) return ORC_E_FORMAT;
+    if (pl_bytes != n_chunks * 32ull * N || off_pl + pl_bytes > total) return ORC_E_FORMAT;
+    if (out_cap < n) return ORC_E_CAPACITY;
+
+    const uint8_t *stream = blob + off_st;
+    /* padding after the last stream bit must be zero */
+    for (uint64_t b = bits; b < st_bytes * 8; b++)
+        if ((stream[b >> 3] >> (b & 7)) & 1) return ORC_E_FORMAT;
+
+    /* histogram in the header must reproduce stream_bits with these lengths */
+    uint64_t fsum = 0, wsum = 0;
+    for (int i = 0; i < ORC_NSYM; i++) {
+        uint64_t f = rd64(blob + 128 + 8 * i);
+        fsum += f;
+        wsum += f * len[i];
+        if (f > 0 && len[i] == 0) return ORC_E_FORMAT;
+    }
+    if (fsum != n || wsum != bits) return ORC_E_FORMAT;
+
+    /* pass 1: no metadata */
+    uint8_t *sym = (uint8_t *)malloc(n);
+    uint8_t *lane_sym = (uint8_t *)malloc(N);
+    if (!sym || !lane_sym) { free(sym); free(lane_sym); return ORC_E_CAPACITY; }
+    int rc = orc_decode_symbols(stream, bits, ORC_LSB_FIRST, len, n, sym);
+    if (rc) { free(sym); free(lane_sym); return rc; }
+
+    /* pass 2: lane by lane through the metadata */
+    if (rd64(blob + off_cb) != 0 || rd64(blob + off_cb + 8 * n_chunks) != bits) rc = ORC_E_META;
+    for (uint64_t c = 0; c < n_chunks && rc == ORC_OK; c++) {
+        uint64_t pos = rd64(blob + off_cb + 8 * c);
+        for (uint64_t l = 0; l < 64 && rc == ORC_OK; l++) {
+            uint64_t first = c * chunk + l * N;
+            uint64_t cnt = first >= n ? 0 : (n - first < N ? n - first : N);
+            uint64_t lb = rd16(blob + off_lb + 2 * (c * 64 + l));
+            if (cnt == 0) { if (lb != 0) rc = ORC_E_META; continue; }
+            if (pos + lb > bits) { rc = ORC_E_META; break; }
+            /* decode exactly cnt symbols from the lane's own window of lb bits,
+             * addressed relative to the whole stream so bit numbering is shared */
+            {
+                /* a private copy of the window makes "ends exactly at lb" checkable
+                 * with the same strict decoder */
+                uint64_t wbytes = (lb + 7) / 8 + 1;
+                uint8_t *wbuf = (uint8_t *)calloc(wbytes, 1);
+                if (!wbuf) { rc = ORC_E_CAPACITY; break; }
+                for (uint64_t b = 0; b < lb; b++)
+                    if ((stream[(pos + b) >> 3] >> ((pos + b) & 7)) & 1)
+                        wbuf[b >> 3] |= (uint8_t)(1u << (b & 7));
+                int r2 = orc_decode_symbols(wbuf, lb, ORC_LSB_FIRST, len, cnt, lane_sym);
+                free(wbuf);
+                if (r2) { rc = ORC_E_META; break; }
+            }
+            if (memcmp(lane_sym, sym + first, cnt) != 0) { rc = ORC_E_META; break; }
+            pos += lb;
+        }
+        if (rc == ORC_OK && pos != rd64(blob + off_cb + 8 * (c + 1))) rc = ORC_E_META;
+    }
+
+    if (rc == ORC_OK) {
+        const uint8_t *plane = blob + off_pl;
+        for (uint64_t i = 0; i < n; i++) {
+            uint8_t b = plane[plane_byte_index(i)];
+            uint8_t q = plane_is_high(i) ? (uint8_t)(b >> 4) : (uint8_t)(b & 15);
+            out[i] = orc_join((uint8_t)(q >> 3), sym[i], (uint8_t)(q & 7));
+        }
+        /* padding nibbles beyond n must be zero */
+        for (uint64_t i = n; i < n_chunks * chunk; i++) {
+            uint8_t b = plane[plane_byte_index(i)];
+            uint8_t q = plane_is_high(i) ? (uint8_t)(b >> 4) : (uint8_t)(b & 15);
+            if (q) { rc = ORC_E_FORMAT; break; }
+        }
+    }
+    free(sym);
+    free(lane_sym);
+    if (rc == ORC_OK) { *n_out = n; *stream_bits_out = bits; }
+    return rc;
+}
