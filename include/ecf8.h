@@ -1,0 +1,178 @@
+/*
+ * ecf8.h -- C ABI of the MI355X-native ECF8 library.
+ *
+ * ECF8 (paper Section 3) stores FP8 E4M3 weights losslessly as
+ *   - a prefix-coded stream of the 4-bit exponent fields (optimal Huffman code
+ *     over the tensor's own exponent histogram, Section 3.1 "Huffman code
+ *     generation"),
+ *   - the raw sign+mantissa nibbles (Table 4, "packed"),
+ *   - synchronisation metadata that lets independent GPU lanes start decoding
+ *     in the middle of the stream (Section 3.1 "Encoding and synchronization
+ *     metadata generation"),
+ * and reconstructs the exact bytes on the GPU just before use (Section 3.2,
+ * Algorithm 1; Section 3.3).
+ *
+ * Boundary: plain pointers and sizes only.  "host" pointers are ordinary CPU
+ * memory; "device" pointers are HIP device memory of the current device that
+ * the CALLER owns (e.g. a PyTorch tensor's data_ptr()).  The library keeps no
+ * device memory of its own, never allocates or frees device memory, never
+ * synchronises the device, and uses no global atomics.  `stream` arguments are
+ * a hipStream_t passed as void* (NULL = the default stream).
+ *
+ * All functions return ECF8_OK (0) or a negative ECF8_E_* code; nothing throws
+ * or aborts across this boundary.
+ *
+ * Container ("blob"), all integers little-endian, every section at a multiple
+ * of 256 bytes from the start of the blob:
+ *   header (256 B): see struct ecf8_header
+ *   chunk_bit : u64[n_chunks+1]  stream bit at which chunk c's first codeword
+ *                                starts; last entry = stream_bits
+ *   lane_bits : u16[n_chunks*64] code bits of lane l of chunk c, i.e. of
+ *                                elements [c*64N + l*N, +N) clipped to n_elem
+ *                                (N = lane_syms); 0 for empty lanes
+ *   stream    : the codewords of elements 0..n_elem-1 concatenated in order;
+ *               stream bit i is bit (i & 7) of byte (i >> 3); a codeword's
+ *               first (most significant) bit comes first; codes are the
+ *               canonical code of code_len[] ordered by (length, symbol);
+ *               zero padded to stream_bytes = roundup16(ceil(bits/8) + 8)
+ *   plane     : nibbles q = sign<<3 | mantissa; element i lives in byte
+ *               (i/8)*4 + (i%4), low nibble if (i%8) < 4 else high nibble;
+ *               zero padded to n_chunks*32N bytes
+ * A chunk is 64 lanes of N symbols: one wavefront decodes one chunk, one lane
+ * decodes N consecutive elements.
+ */
+#ifndef ECF8_H
+#define ECF8_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ECF8_OK 0
+#define ECF8_E_ARG (-1)      /* null pointer, zero size, unsupported option      */
+#define ECF8_E_FORMAT (-2)   /* blob is not a valid container                    */
+#define ECF8_E_CAPACITY (-3) /* an output buffer is too small                    */
+#define ECF8_E_ALIGN (-4)    /* a device pointer is not 16-byte aligned          */
+#define ECF8_E_HIP (-5)      /* the HIP runtime reported an error at launch      */
+#define ECF8_E_NOMEM (-6)    /* host allocation failed                           */
+
+#define ECF8_MAGIC 0x38464345u /* "ECF8" */
+#define ECF8_VERSION 1u
+#define ECF8_LANES 64u         /* lanes per chunk = wavefront width              */
+
+/* The first 256 bytes of every blob. */
+typedef struct ecf8_header {
+    uint32_t magic;           /* ECF8_MAGIC                                      */
+    uint32_t version;         /* ECF8_VERSION                                    */
+    uint64_t total_size;      /* bytes of the whole blob                         */
+    uint64_t n_elem;          /* rows * cols                                     */
+    uint64_t rows, cols;
+    uint32_t lane_syms;       /* N: symbols per lane, one of 32, 64, 128         */
+    uint32_t lanes_per_chunk; /* ECF8_LANES                                      */
+    uint64_t n_chunks;        /* ceil(n_elem / (64 N))                           */
+    uint64_t stream_bits;     /* sum over elements of their code length          */
+    uint8_t code_len[16];     /* code length of exponent field x, 0 = absent     */
+    uint64_t off_chunk_bit, off_lane_bits, off_stream, off_plane;
+    uint64_t stream_bytes, plane_bytes;
+    uint64_t freq[16];        /* exponent histogram p(x) * n_elem                */
+} ecf8_header;
+
+typedef struct ecf8_encode_opts {
+    uint32_t lane_syms; /* 0 = default (64)                                      */
+    uint32_t n_threads; /* host threads for encoding, 0 = all hardware threads   */
+} ecf8_encode_opts;
+
+typedef struct ecf8_stats {
+    double entropy_bits;    /* H of the exponent histogram                       */
+    double avg_code_bits;   /* stream_bits / n_elem                              */
+    double bits_per_weight; /* 8 * total_size / n_elem, metadata included        */
+    double ratio;           /* total_size / n_elem                               */
+    uint32_t max_code_len;
+    uint32_t n_symbols;     /* distinct exponent fields present                  */
+} ecf8_stats;
+
+typedef struct ecf8_blob ecf8_blob; /* host object owning one encoded container   */
+
+/*
+ * ecf8_encode (Section 3.1, all three stages).  HOST ONLY.
+ * Reads rows*cols raw E4M3 bytes (row-major; every byte value is legal: the
+ * codec treats bits 6..3 as an opaque symbol, so zeros, subnormals and NaN
+ * encodings round-trip), builds the histogram, an optimal prefix code
+ * (lengths <= 15 with 16 symbols), the stream, the lane/chunk metadata and
+ * the nibble plane.  *out receives a new blob the caller frees with
+ * ecf8_blob_free.  rows*cols == 0 -> ECF8_E_ARG.
+ */
+int ecf8_encode(const uint8_t *fp8_host, uint64_t rows, uint64_t cols,
+                const ecf8_encode_opts *opts, ecf8_blob **out);
+void ecf8_blob_free(ecf8_blob *blob);
+const void *ecf8_blob_data(const ecf8_blob *blob); /* host pointer, 256-byte aligned */
+uint64_t ecf8_blob_size(const ecf8_blob *blob);
+
+/*
+ * Header parse + structural checks of a container held in HOST memory
+ * (sizes, offsets, alignment, code lengths satisfy Kraft).  Fills *hdr, which
+ * is what the decode calls need on the host at launch time.
+ */
+int ecf8_blob_describe(const void *blob_host, uint64_t size, ecf8_header *hdr);
+
+/*
+ * Full metadata check of a HOST container before it is trusted on the device:
+ * describe() plus chunk_bit monotone and consistent with lane_bits, lane_bits
+ * <= 15 N, histogram consistent with stream_bits, zero padding.  The decode
+ * calls do not read device memory from the host, so validate on the host
+ * before uploading.
+ */
+int ecf8_blob_validate(const void *blob_host, uint64_t size);
+
+int ecf8_blob_stats(const ecf8_header *hdr, ecf8_stats *stats);
+
+/*
+ * ecf8_decode (Section 3.2 / Algorithm 1: compressed buffers in, exact FP8
+ * tensor out).  d_blob: DEVICE copy of the blob described by *hdr (16-byte
+ * aligned).  d_out: DEVICE buffer of out_capacity >= n_elem bytes, 16-byte
+ * aligned; exactly n_elem bytes are written.  Asynchronous on `stream`.
+ */
+int ecf8_decode(const ecf8_header *hdr, const void *d_blob, void *d_out,
+                uint64_t out_capacity, void *stream);
+
+/* One tensor of a batch as the kernel reads it from DEVICE memory. */
+typedef struct ecf8_batch_item {
+    uint64_t d_blob;       /* device address of the tensor's blob                */
+    uint64_t d_out;        /* device address of its output buffer                */
+    uint64_t n_elem;
+    uint64_t n_chunks;
+    uint64_t first_chunk;  /* chunks of all earlier items of the batch           */
+    uint64_t off_chunk_bit, off_lane_bits, off_stream, off_plane;
+    uint64_t stream_bytes;
+    uint8_t code_len[16];
+    uint64_t reserved[4];
+} ecf8_batch_item; /* 128 bytes */
+
+/*
+ * ecf8_batch_prepare: HOST.  Fills items_host[0..n) from the headers and the
+ * device addresses; the caller copies the array to device memory once and
+ * keeps it.  All tensors of a batch must share lane_syms.  *total_chunks
+ * receives the chunk count of the whole batch.
+ */
+int ecf8_batch_prepare(const ecf8_header *hdrs, const void *const *d_blobs,
+                       void *const *d_outs, const uint64_t *out_capacities,
+                       uint32_t n_tensors, ecf8_batch_item *items_host,
+                       uint64_t *total_chunks, uint32_t *lane_syms);
+
+/*
+ * ecf8_decode_batched: many tensors in ONE launch (the per-layer decode of
+ * Section 3.3 collapsed over a layer's matrices / an MoE layer's experts).
+ * d_items: DEVICE array written by ecf8_batch_prepare (16-byte aligned).
+ */
+int ecf8_decode_batched(const ecf8_batch_item *d_items, uint32_t n_tensors,
+                        uint64_t total_chunks, uint32_t lane_syms, void *stream);
+
+const char *ecf8_strerror(int code);
+uint32_t ecf8_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ECF8_H */

@@ -1,0 +1,390 @@
+// ECF8 -> FP8 decode kernels for gfx950 (MI355X), wave64.
+//
+// What is computed is Algorithm 1 of the paper (block-level decompression:
+// load the compressed span, locate each lane's first codeword, decode through
+// a lookup table held next to the ALUs, merge the sign/mantissa nibble, write
+// back coalesced).  How it is computed is specific to CDNA4:
+//
+//  * one wavefront decodes one chunk = 64 lanes x N consecutive elements; the
+//    encoder recorded how many stream bits each lane's N codewords take, so a
+//    DPP prefix scan over those 64 numbers gives every lane its start bit and
+//    its output position is l*N by construction.  The paper's first decoding
+//    pass, which exists only to count symbols per thread, is gone;
+//  * the chunk's span of the stream is copied to LDS with dwordx4 loads, 1 KiB
+//    contiguous per wave instruction, and lanes pull 32-bit windows from LDS;
+//  * the code table is a 4096-entry LDS table indexed by the next 12 stream
+//    bits that yields up to four symbols per lookup, already shifted to their
+//    place in the output byte; codewords longer than 12 bits take a second
+//    level (a 16-entry canonical match).  It is built in the kernel from the
+//    16 code lengths, so a tensor's table costs 16 bytes of HBM traffic;
+//  * decoded bytes are appended to a per-lane LDS region with unaligned dword
+//    writes, then read back transposed so that each store instruction of the
+//    wave writes 1 KiB of contiguous output, merged with the nibble plane that
+//    was fetched (coalesced, 512 B per instruction) before decoding started;
+//  * persistent workgroups walk contiguous chunk ranges, so a table is built
+//    once per (workgroup, tensor) and no global atomics are needed.
+#include "ecf8.h"
+
+#include <hip/hip_runtime.h>
+
+#include <mutex>
+
+namespace {
+
+constexpr int TB = 12;                 // first-level table index bits
+constexpr int TBL_ENTRIES = 1 << TB;
+
+// Table entry (one dword), for k = 1..4 symbols decoded from the index bits:
+//   byte i bits 3..6 : exponent field of symbol i, in its output position
+//   bits 0..2        : k
+//   bits 7..10       : stream bits consumed by the k symbols
+// The control fields sit in bits the merge masks off (0x78 per byte keeps the
+// exponent only).  Entry 0 means "first codeword is longer than TB bits".
+constexpr uint32_t EXP_MASK = 0x78787878u;
+
+#define GLOBAL __attribute__((address_space(1))) // HBM pointers: global_load/store, not flat
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+struct KArgs {
+    ecf8_batch_item single;               // used when items == nullptr
+    const GLOBAL ecf8_batch_item *items;  // device array for the batched call
+    uint32_t n_items;
+    uint64_t total_chunks;
+};
+
+// code_len[16] travels as two 64-bit words (one byte per symbol)
+__device__ __forceinline__ uint32_t len_of(uint64_t lo, uint64_t hi, int s)
+{
+    return (uint32_t)((s < 8 ? lo >> (8 * s) : hi >> (8 * (s - 8))) & 0xff);
+}
+
+template <int N>
+struct Cfg {
+    static constexpr int STAGE = N * 32 + 64;         // bytes of stream staged per chunk
+    static constexpr int LANE_STRIDE = N + 4;         // output region per lane (+3 overshoot, dword aligned)
+    static constexpr int OUTREG = 64 * LANE_STRIDE;
+    static constexpr int WAVE_BYTES = STAGE + OUTREG;
+    static constexpr int PIECES = N / 16;             // 16-byte pieces per lane
+};
+
+__device__ __forceinline__ uint32_t lds_load_u32(const uint8_t *p)
+{
+    uint32_t v;
+    __builtin_memcpy(&v, p, 4); // LDS takes unaligned dword accesses on gfx950
+    return v;
+}
+
+__device__ __forceinline__ void lds_store_u32(uint8_t *p, uint32_t v)
+{
+    __builtin_memcpy(p, &v, 4);
+}
+
+// Inclusive wave64 prefix sum with DPP row shifts and row broadcasts.
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x)
+{
+    uint32_t v = x;
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x111, 0xf, 0xf, false); // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x112, 0xf, 0xf, false); // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x114, 0xf, 0xf, false); // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x118, 0xf, 0xf, false); // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x142, 0xa, 0xf, false); // row_bcast:15 -> rows 1,3
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x143, 0xc, 0xf, false); // row_bcast:31 -> rows 2,3
+    return v;
+}
+
+// Second level: the codeword at the bottom of `bits` (stream order, >= 15 valid
+// bits) is longer than TB.  Match it against the long canonical codes.
+__device__ __forceinline__ uint32_t decode_long(uint32_t bits, const uint32_t *s_len, const uint32_t *s_code)
+{
+    uint32_t v = __brev(bits) >> 17;          // next 15 bits, first bit most significant
+    uint32_t e = 1u | (15u << 7);             // no match (corrupt stream): skip 15 bits, exponent 0
+    for (int s = 0; s < 16; s++) {
+        uint32_t l = s_len[s];
+        if (l > TB && (v >> (15 - l)) == s_code[s]) e = ((uint32_t)s << 3) | 1u | (l << 7);
+    }
+    return e;
+}
+
+// Builds the first-level table and the per-symbol (length, code) arrays in LDS
+// from the 16 code lengths.  `tmp` is TBL_ENTRIES u16 of scratch LDS.
+__device__ void build_tables(uint64_t len_lo, uint64_t len_hi, uint32_t *tbl, uint32_t *s_len, uint32_t *s_code,
+                             uint16_t *tmp, int tid, int nthreads)
+{
+    if (tid < 16) {
+        uint32_t l = len_of(len_lo, len_hi, tid);
+        uint32_t code = 0;
+#pragma unroll
+        for (int j = 0; j < 16; j++) {
+            uint32_t lj = len_of(len_lo, len_hi, j);
+            if (lj != 0 && lj < l) code += 1u << (l - lj);     // all shorter codes precede
+            else if (lj == l && j < tid) code += 1;            // same length: by symbol value
+        }
+        s_len[tid] = l;
+        s_code[tid] = code;
+    }
+    for (int i = tid; i < TBL_ENTRIES; i += nthreads) tmp[i] = 0;
+    __syncthreads();
+    // single-symbol table: every index whose low bits spell the codeword (first bit = bit 0)
+    for (int s = 0; s < 16; s++) {
+        uint32_t l = s_len[s];
+        if (l == 0 || l > TB) continue;
+        uint32_t r = __brev(s_code[s]) >> (32 - l);
+        uint32_t reps = 1u << (TB - l);
+        for (uint32_t j = tid; j < reps; j += nthreads) tmp[r | (j << l)] = (uint16_t)(s | (l << 4));
+    }
+    __syncthreads();
+    for (int idx = tid; idx < TBL_ENTRIES; idx += nthreads) {
+        uint32_t cur = idx, used = 0, k = 0, e = 0;
+        for (int i = 0; i < 4; i++) {
+            uint32_t t = tmp[cur];
+            uint32_t l = t >> 4;
+            if (l == 0 || used + l > TB) break;   // long code, or it needs bits beyond the index
+            e |= (t & 15u) << (8 * i + 3);
+            used += l;
+            cur >>= l;
+            k++;
+        }
+        tbl[idx] = k ? (e | k | (used << 7)) : 0u;
+    }
+    __syncthreads();
+}
+
+template <int N, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
+{
+    using C = Cfg<N>;
+    __shared__ __attribute__((aligned(16))) uint32_t tbl[TBL_ENTRIES];
+    __shared__ uint32_t s_len[16], s_code[16];
+    __shared__ __attribute__((aligned(16))) uint8_t wave_mem[WAVES][C::WAVE_BYTES];
+    static_assert(sizeof(wave_mem) >= TBL_ENTRIES * 2, "table scratch aliases the wave regions");
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    uint8_t *stage = wave_mem[wave];
+    uint8_t *outreg = wave_mem[wave] + C::STAGE;
+
+    // contiguous range of the batch's chunks for this workgroup
+    const uint64_t G = gridDim.x, g = blockIdx.x;
+    uint64_t c = a.total_chunks * g / G;
+    const uint64_t c_end = a.total_chunks * (g + 1) / G;
+
+    while (c < c_end) {
+        // which tensor holds chunk c (uniform)
+        uint64_t d_blob, d_out, n_elem, n_chunks, first_chunk, off_cb, off_lb, off_st, off_pl, st_bytes;
+        uint64_t len_lo, len_hi;
+        if (a.items) {
+            uint32_t lo = 0, hi = a.n_items - 1;
+            while (lo < hi) {
+                uint32_t mid = (lo + hi + 1) >> 1;
+                if (a.items[mid].first_chunk <= c) lo = mid; else hi = mid - 1;
+            }
+            const GLOBAL ecf8_batch_item *p = a.items + lo;
+            d_blob = p->d_blob; d_out = p->d_out; n_elem = p->n_elem; n_chunks = p->n_chunks;
+            first_chunk = p->first_chunk; off_cb = p->off_chunk_bit; off_lb = p->off_lane_bits;
+            off_st = p->off_stream; off_pl = p->off_plane; st_bytes = p->stream_bytes;
+            const GLOBAL uint64_t *cl8 = (const GLOBAL uint64_t *)p->code_len;
+            len_lo = cl8[0]; len_hi = cl8[1];
+        } else {
+            d_blob = a.single.d_blob; d_out = a.single.d_out; n_elem = a.single.n_elem;
+            n_chunks = a.single.n_chunks; first_chunk = 0; off_cb = a.single.off_chunk_bit;
+            off_lb = a.single.off_lane_bits; off_st = a.single.off_stream; off_pl = a.single.off_plane;
+            st_bytes = a.single.stream_bytes;
+            __builtin_memcpy(&len_lo, a.single.code_len, 8);
+            __builtin_memcpy(&len_hi, a.single.code_len + 8, 8);
+        }
+        const uint64_t t_end = first_chunk + n_chunks;
+        const uint64_t seg_end = c_end < t_end ? c_end : t_end;
+        if (seg_end <= c) break; // item table does not cover chunk c: stop rather than spin
+        GLOBAL uint8_t *out = (GLOBAL uint8_t *)d_out;
+        const GLOBAL uint64_t *chunk_bit = (const GLOBAL uint64_t *)(d_blob + off_cb);
+        const GLOBAL uint16_t *lane_bits = (const GLOBAL uint16_t *)(d_blob + off_lb);
+        const GLOBAL uint8_t *stream = (const GLOBAL uint8_t *)(d_blob + off_st);
+        const GLOBAL uint8_t *plane = (const GLOBAL uint8_t *)(d_blob + off_pl);
+
+        __syncthreads(); // every wave is done with the previous tensor's table and its scratch
+        build_tables(len_lo, len_hi, tbl, s_len, s_code, (uint16_t *)&wave_mem[0][0], tid, WAVES * 64);
+
+        for (uint64_t cg = c + wave; cg < seg_end; cg += WAVES) {
+            const uint64_t cl = cg - first_chunk;             // chunk index inside the tensor
+            const uint64_t elem0 = cl * (64ull * N);             // first element of the chunk
+            const uint64_t b0 = chunk_bit[cl], b1 = chunk_bit[cl + 1];
+
+            // lane start bit = chunk start + exclusive scan of the lanes' bit counts
+            const uint32_t lb = lane_bits[cl * 64 + lane];
+            const uint32_t rel = wave_incl_scan(lb) - lb;
+
+            // symbols this lane owns (ragged last chunk)
+            const uint64_t lane_first = elem0 + (uint64_t)lane * N;
+            const uint32_t nsym = lane_first >= n_elem ? 0u
+                                  : (uint32_t)min((uint64_t)N, n_elem - lane_first);
+
+            // nibble plane of the chunk, in the order the write-back wants it
+            u32x2 pl[C::PIECES];
+            const GLOBAL u32x2 *plane_c = (const GLOBAL u32x2 *)(plane + cl * (32ull * N));
+#pragma unroll
+            for (int j = 0; j < C::PIECES; j++) pl[j] = plane_c[j * 64 + lane];
+
+            // stage the chunk's span of the stream (16-byte aligned start, +4 bytes look-ahead)
+            uint64_t byte_end = min(((b1 + 7) >> 3) + 4, st_bytes);
+            uint64_t byte0 = min((b0 >> 3) & ~15ull, byte_end);
+            const uint32_t span = (uint32_t)min(byte_end - byte0, (uint64_t)0x7fffffff);
+            const bool staged = span <= (uint32_t)C::STAGE;
+            const uint32_t bit_in = (uint32_t)(b0 - byte0 * 8) + rel; // lane start, bits from byte0
+
+            uint8_t *optr = outreg + lane * C::LANE_STRIDE;
+            uint8_t *const oend = optr + nsym;
+
+            if (staged) {
+                for (uint32_t i = lane * 16; i < span; i += 64 * 16)
+                    *(u32x4 *)(stage + i) = *(const GLOBAL u32x4 *)(stream + byte0 + i);
+                uint32_t bp = bit_in;
+                while (optr < oend) {
+                    uint32_t w = lds_load_u32(stage + (bp >> 3)) >> (bp & 7);
+                    uint32_t e = tbl[w & (TBL_ENTRIES - 1)];
+                    if (__builtin_expect((e & 7u) == 0, 0)) e = decode_long(w, s_len, s_code);
+                    lds_store_u32(optr, e);
+                    optr += e & 7u;
+                    bp += (e >> 7) & 15u;
+                }
+            } else {
+                // span larger than the staging buffer (a chunk that codes far worse than
+                // 4 bits per symbol): same loop, windows read straight from global memory
+                const GLOBAL uint8_t *sp = stream + byte0;
+                uint32_t bp = bit_in;
+                while (optr < oend) {
+                    const GLOBAL uint8_t *q = sp + (bp >> 3);
+                    uint32_t w = ((uint32_t)q[0] | ((uint32_t)q[1] << 8) | ((uint32_t)q[2] << 16) |
+                                  ((uint32_t)q[3] << 24)) >> (bp & 7);
+                    uint32_t e = tbl[w & (TBL_ENTRIES - 1)];
+                    if (__builtin_expect((e & 7u) == 0, 0)) e = decode_long(w, s_len, s_code);
+                    lds_store_u32(optr, e);
+                    optr += e & 7u;
+                    bp += (e >> 7) & 15u;
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+
+            // write-back: piece p = 16 consecutive output bytes; lane takes p = j*64 + lane
+#pragma unroll
+            for (int j = 0; j < C::PIECES; j++) {
+                const int p = j * 64 + lane;
+                const uint8_t *src = outreg + (p / C::PIECES) * C::LANE_STRIDE + (p % C::PIECES) * 16;
+                const uint32_t s0 = *(const uint32_t *)(src), s1 = *(const uint32_t *)(src + 4);
+                const uint32_t s2 = *(const uint32_t *)(src + 8), s3 = *(const uint32_t *)(src + 12);
+                const uint32_t p0 = pl[j].x, p1 = pl[j].y;
+                u32x4 d;
+                // byte = exponent<<3 | sign<<7 | mantissa  (Algorithm 1, byte assembly)
+                d.x = (s0 & EXP_MASK) | (p0 & 0x07070707u) | ((p0 & 0x08080808u) << 4);
+                d.y = (s1 & EXP_MASK) | ((p0 >> 4) & 0x07070707u) | (p0 & 0x80808080u);
+                d.z = (s2 & EXP_MASK) | (p1 & 0x07070707u) | ((p1 & 0x08080808u) << 4);
+                d.w = (s3 & EXP_MASK) | ((p1 >> 4) & 0x07070707u) | (p1 & 0x80808080u);
+                const uint64_t o = elem0 + (uint64_t)p * 16;
+                if (o + 16 <= n_elem) {
+                    *(GLOBAL u32x4 *)(out + o) = d;
+                } else if (o < n_elem) {
+                    for (uint32_t b = 0; b < 16 && o + b < n_elem; b++) {
+                        const uint32_t wsel = b >> 2;
+                        const uint32_t word = wsel == 0 ? d.x : wsel == 1 ? d.y : wsel == 2 ? d.z : d.w;
+                        out[o + b] = (uint8_t)(word >> (8 * (b & 3)));
+                    }
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+        c = seg_end;
+    }
+}
+
+struct DevInfo {
+    int cus = 0;
+};
+
+int device_cus()
+{
+    static std::mutex m;
+    static DevInfo info[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return -1;
+    std::lock_guard<std::mutex> lk(m);
+    if (info[dev].cus == 0) {
+        hipDeviceProp_t p;
+        if (hipGetDeviceProperties(&p, dev) != hipSuccess) return -1;
+        info[dev].cus = p.multiProcessorCount > 0 ? p.multiProcessorCount : 1;
+    }
+    return info[dev].cus;
+}
+
+template <int N, int WAVES>
+int launch(const KArgs &a, int wgs_per_cu, hipStream_t s)
+{
+    int cus = device_cus();
+    if (cus <= 0) return ECF8_E_HIP;
+    uint64_t want = (a.total_chunks + WAVES - 1) / WAVES;       // at least one chunk per wave
+    uint64_t cap = (uint64_t)cus * wgs_per_cu;
+    uint32_t grid = (uint32_t)(want < cap ? want : cap);
+    if (grid == 0) grid = 1;
+    hipLaunchKernelGGL((ecf8_decode_kernel<N, WAVES>), dim3(grid), dim3(WAVES * 64), 0, s, a);
+    return hipGetLastError() == hipSuccess ? ECF8_OK : ECF8_E_HIP;
+}
+
+int dispatch(const KArgs &a, uint32_t lane_syms, hipStream_t s)
+{
+    switch (lane_syms) {
+    case 32: return launch<32, 8>(a, 3, s);
+    case 64: return launch<64, 8>(a, 2, s);
+    case 128: return launch<128, 4>(a, 2, s);
+    default: return ECF8_E_ARG;
+    }
+}
+
+} // namespace
+
+extern "C" {
+
+int ecf8_decode(const ecf8_header *h, const void *d_blob, void *d_out, uint64_t out_capacity, void *stream)
+{
+    if (!h || !d_blob || !d_out) return ECF8_E_ARG;
+    if (h->magic != ECF8_MAGIC || h->version != ECF8_VERSION || h->n_elem == 0 || h->n_chunks == 0 ||
+        h->lanes_per_chunk != ECF8_LANES)
+        return ECF8_E_FORMAT;
+    if (h->n_chunks != (h->n_elem + 64ull * h->lane_syms - 1) / (64ull * h->lane_syms)) return ECF8_E_FORMAT;
+    if (h->off_plane + h->plane_bytes > h->total_size || h->off_stream + h->stream_bytes > h->off_plane ||
+        h->plane_bytes != h->n_chunks * 32ull * h->lane_syms)
+        return ECF8_E_FORMAT;
+    if (out_capacity < h->n_elem) return ECF8_E_CAPACITY;
+    if (((uintptr_t)d_blob | (uintptr_t)d_out) & 15) return ECF8_E_ALIGN;
+    KArgs a{};
+    a.single.d_blob = (uint64_t)(uintptr_t)d_blob;
+    a.single.d_out = (uint64_t)(uintptr_t)d_out;
+    a.single.n_elem = h->n_elem;
+    a.single.n_chunks = h->n_chunks;
+    a.single.first_chunk = 0;
+    a.single.off_chunk_bit = h->off_chunk_bit;
+    a.single.off_lane_bits = h->off_lane_bits;
+    a.single.off_stream = h->off_stream;
+    a.single.off_plane = h->off_plane;
+    a.single.stream_bytes = h->stream_bytes;
+    for (int i = 0; i < 16; i++) a.single.code_len[i] = h->code_len[i];
+    a.items = nullptr;
+    a.n_items = 1;
+    a.total_chunks = h->n_chunks;
+    return dispatch(a, h->lane_syms, (hipStream_t)stream);
+}
+
+int ecf8_decode_batched(const ecf8_batch_item *d_items, uint32_t n_tensors, uint64_t total_chunks,
+                        uint32_t lane_syms, void *stream)
+{
+    if (!d_items || n_tensors == 0 || total_chunks == 0) return ECF8_E_ARG;
+    if ((uintptr_t)d_items & 15) return ECF8_E_ALIGN;
+    KArgs a{};
+    a.items = (const GLOBAL ecf8_batch_item *)(uintptr_t)d_items;
+    a.n_items = n_tensors;
+    a.total_chunks = total_chunks;
+    return dispatch(a, lane_syms, (hipStream_t)stream);
+}
+
+} // extern "C"

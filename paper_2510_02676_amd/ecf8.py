@@ -1,0 +1,210 @@
+"""Thin Python binding of the ECF8 C-ABI library (argument marshalling only).
+
+Names follow ``include/ecf8.h``.  PyTorch appears here only as the owner of
+device memory and of the current HIP stream; every step of the decode path
+runs inside ``libecf8.so``.  Importing this module fails loudly when the
+library has not been built (``python -m paper_2510_02676_amd.build``).
+"""
+import ctypes
+import os
+
+import numpy as np
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libecf8.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError("libecf8.so is not built: run `python -m paper_2510_02676_amd.build` "
+                      "(or __graft_entry__.build()) first; there is no fallback path")
+_lib = ctypes.CDLL(LIB_PATH)
+
+OK, E_ARG, E_FORMAT, E_CAPACITY, E_ALIGN, E_HIP, E_NOMEM = 0, -1, -2, -3, -4, -5, -6
+
+
+class Header(ctypes.Structure):
+    """struct ecf8_header: the first 256 bytes of a blob."""
+    _fields_ = [("magic", ctypes.c_uint32), ("version", ctypes.c_uint32),
+                ("total_size", ctypes.c_uint64), ("n_elem", ctypes.c_uint64),
+                ("rows", ctypes.c_uint64), ("cols", ctypes.c_uint64),
+                ("lane_syms", ctypes.c_uint32), ("lanes_per_chunk", ctypes.c_uint32),
+                ("n_chunks", ctypes.c_uint64), ("stream_bits", ctypes.c_uint64),
+                ("code_len", ctypes.c_uint8 * 16),
+                ("off_chunk_bit", ctypes.c_uint64), ("off_lane_bits", ctypes.c_uint64),
+                ("off_stream", ctypes.c_uint64), ("off_plane", ctypes.c_uint64),
+                ("stream_bytes", ctypes.c_uint64), ("plane_bytes", ctypes.c_uint64),
+                ("freq", ctypes.c_uint64 * 16)]
+
+
+class EncodeOpts(ctypes.Structure):
+    _fields_ = [("lane_syms", ctypes.c_uint32), ("n_threads", ctypes.c_uint32)]
+
+
+class Stats(ctypes.Structure):
+    _fields_ = [("entropy_bits", ctypes.c_double), ("avg_code_bits", ctypes.c_double),
+                ("bits_per_weight", ctypes.c_double), ("ratio", ctypes.c_double),
+                ("max_code_len", ctypes.c_uint32), ("n_symbols", ctypes.c_uint32)]
+
+
+class BatchItem(ctypes.Structure):
+    _fields_ = [("d_blob", ctypes.c_uint64), ("d_out", ctypes.c_uint64), ("n_elem", ctypes.c_uint64),
+                ("n_chunks", ctypes.c_uint64), ("first_chunk", ctypes.c_uint64),
+                ("off_chunk_bit", ctypes.c_uint64), ("off_lane_bits", ctypes.c_uint64),
+                ("off_stream", ctypes.c_uint64), ("off_plane", ctypes.c_uint64),
+                ("stream_bytes", ctypes.c_uint64), ("code_len", ctypes.c_uint8 * 16),
+                ("reserved", ctypes.c_uint64 * 4)]
+
+
+assert ctypes.sizeof(Header) == 256 and ctypes.sizeof(BatchItem) == 128
+
+_vp, _u64, _u32 = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32
+_lib.ecf8_encode.argtypes = [_vp, _u64, _u64, ctypes.POINTER(EncodeOpts), ctypes.POINTER(_vp)]
+_lib.ecf8_blob_free.argtypes = [_vp]
+_lib.ecf8_blob_free.restype = None
+_lib.ecf8_blob_data.argtypes = [_vp]
+_lib.ecf8_blob_data.restype = _vp
+_lib.ecf8_blob_size.argtypes = [_vp]
+_lib.ecf8_blob_size.restype = _u64
+_lib.ecf8_blob_describe.argtypes = [_vp, _u64, ctypes.POINTER(Header)]
+_lib.ecf8_blob_validate.argtypes = [_vp, _u64]
+_lib.ecf8_blob_stats.argtypes = [ctypes.POINTER(Header), ctypes.POINTER(Stats)]
+_lib.ecf8_decode.argtypes = [ctypes.POINTER(Header), _vp, _vp, _u64, _vp]
+_lib.ecf8_batch_prepare.argtypes = [ctypes.POINTER(Header), ctypes.POINTER(_vp), ctypes.POINTER(_vp),
+                                    ctypes.POINTER(_u64), _u32, ctypes.POINTER(BatchItem),
+                                    ctypes.POINTER(_u64), ctypes.POINTER(_u32)]
+_lib.ecf8_decode_batched.argtypes = [_vp, _u32, _u64, _u32, _vp]
+_lib.ecf8_strerror.argtypes = [ctypes.c_int]
+_lib.ecf8_strerror.restype = ctypes.c_char_p
+_lib.ecf8_version.restype = _u32
+
+
+class Ecf8Error(RuntimeError):
+    def __init__(self, fn, code):
+        self.code = code
+        super().__init__("%s: %s (%d)" % (fn, _lib.ecf8_strerror(code).decode(), code))
+
+
+def _check(fn, rc):
+    if rc != OK:
+        raise Ecf8Error(fn, rc)
+
+
+def _host_u8(x):
+    if isinstance(x, torch.Tensor):
+        if x.device.type != "cpu":
+            x = x.cpu()
+        if x.dtype != torch.uint8:
+            x = x.view(torch.uint8)
+        x = x.contiguous().numpy()
+    x = np.ascontiguousarray(x)
+    if x.dtype != np.uint8:
+        raise TypeError("expected raw FP8 bytes (uint8)")
+    return x
+
+
+class Blob:
+    """Host object owning one encoded container (an ``ecf8_blob``)."""
+
+    def __init__(self, handle):
+        self._h = handle
+        self.size = int(_lib.ecf8_blob_size(handle))
+        self._ptr = _lib.ecf8_blob_data(handle)
+        self.header = blob_describe(self._ptr, self.size)
+
+    def numpy(self):
+        """Zero-copy uint8 view of the container bytes; the view keeps this object alive."""
+        buf = (ctypes.c_uint8 * self.size).from_address(self._ptr)
+        buf._owner = self
+        return np.frombuffer(buf, dtype=np.uint8)
+
+    def to(self, device):
+        """Copy of the container in device memory (a uint8 tensor the caller owns)."""
+        return torch.from_numpy(self.numpy()).to(device)
+
+    def stats(self):
+        return blob_stats(self.header)
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            _lib.ecf8_blob_free(self._h)
+            self._h = None
+
+
+def ecf8_encode(fp8, rows=None, cols=None, lane_syms=0, n_threads=0):
+    """CPU encoder: raw E4M3 bytes (host tensor / array) -> Blob."""
+    x = _host_u8(fp8)
+    if rows is None:
+        rows, cols = (x.shape if x.ndim == 2 else (1, x.size))
+    if rows * cols != x.size:
+        raise Ecf8Error("ecf8_encode", E_ARG)
+    opts = EncodeOpts(lane_syms, n_threads)
+    h = _vp()
+    _check("ecf8_encode", _lib.ecf8_encode(x.ctypes.data, rows, cols, ctypes.byref(opts), ctypes.byref(h)))
+    return Blob(h)
+
+
+def blob_describe(ptr_or_array, size=None):
+    if isinstance(ptr_or_array, np.ndarray):
+        size = ptr_or_array.size
+        ptr_or_array = ptr_or_array.ctypes.data
+    hdr = Header()
+    _check("ecf8_blob_describe", _lib.ecf8_blob_describe(ptr_or_array, size, ctypes.byref(hdr)))
+    return hdr
+
+
+def blob_validate(arr):
+    arr = np.ascontiguousarray(arr, dtype=np.uint8)
+    _check("ecf8_blob_validate", _lib.ecf8_blob_validate(arr.ctypes.data, arr.size))
+
+
+def blob_stats(hdr):
+    st = Stats()
+    _check("ecf8_blob_stats", _lib.ecf8_blob_stats(ctypes.byref(hdr), ctypes.byref(st)))
+    return {k: getattr(st, k) for k, _ in Stats._fields_}
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def ecf8_decode(hdr, d_blob, d_out=None, stream=None):
+    """GPU decode of one tensor.  d_blob: uint8 device tensor holding the blob."""
+    if d_out is None:
+        d_out = torch.empty((hdr.rows, hdr.cols), dtype=torch.uint8, device=d_blob.device)
+    _check("ecf8_decode", _lib.ecf8_decode(ctypes.byref(hdr), d_blob.data_ptr(), d_out.data_ptr(),
+                                           d_out.numel(), _stream_ptr(stream)))
+    return d_out
+
+
+class Batch:
+    """Device-resident item table for ecf8_decode_batched (built once, reused)."""
+
+    def __init__(self, hdrs, d_blobs, d_outs):
+        n = len(hdrs)
+        H = (Header * n)(*hdrs)
+        B = (_vp * n)(*[t.data_ptr() for t in d_blobs])
+        O = (_vp * n)(*[t.data_ptr() for t in d_outs])
+        C = (_u64 * n)(*[t.numel() for t in d_outs])
+        items = (BatchItem * n)()
+        total = _u64(0)
+        ls = _u32(0)
+        _check("ecf8_batch_prepare", _lib.ecf8_batch_prepare(H, B, O, C, n, items, ctypes.byref(total),
+                                                             ctypes.byref(ls)))
+        host = np.frombuffer(items, dtype=np.uint8).copy()
+        self.d_items = torch.from_numpy(host).to(d_blobs[0].device)
+        self.n = n
+        self.total_chunks = int(total.value)
+        self.lane_syms = int(ls.value)
+        self._keep = (list(d_blobs), list(d_outs))
+
+
+def ecf8_decode_batched(batch, stream=None):
+    _check("ecf8_decode_batched", _lib.ecf8_decode_batched(batch.d_items.data_ptr(), batch.n,
+                                                           batch.total_chunks, batch.lane_syms,
+                                                           _stream_ptr(stream)))
+
+
+def version():
+    return int(_lib.ecf8_version())

@@ -1,0 +1,126 @@
+"""CPU-side tests of the library: the C ABI loads and exports what the header
+declares, and the host encoder's containers are read back by the oracle's
+independent reader.  No GPU call is made here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2510_02676_amd import ecf8, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _rand_bytes(n, seed, conc=0.4):
+    rng = np.random.default_rng(seed)
+    p = rng.dirichlet(np.ones(16) * conc)
+    e = rng.choice(16, size=n, p=p).astype(np.uint8)
+    return ((rng.integers(0, 2, n, dtype=np.uint8) << 7) | (e << 3) | rng.integers(0, 8, n, dtype=np.uint8)).astype(np.uint8)
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "ecf8.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(ecf8_[a-z_0-9]+)\s*\(", text))
+    assert {"ecf8_encode", "ecf8_decode", "ecf8_decode_batched"} <= names
+    lib = ctypes.CDLL(ecf8.LIB_PATH)
+    for n in sorted(names):
+        assert hasattr(lib, n), n
+    assert ecf8.version() == 1
+
+
+@pytest.mark.parametrize("lane_syms", [32, 64, 128])
+@pytest.mark.parametrize("n", [1, 7, 16, 2047, 2048, 4096, 4097, 8191, 8193, 100003])
+def test_encoder_container_read_by_oracle(orc, lane_syms, n):
+    x = _rand_bytes(n, n + lane_syms)
+    blob = ecf8.ecf8_encode(x, 1, n, lane_syms=lane_syms)
+    arr = blob.numpy()
+    ecf8.blob_validate(arr)
+    dec, bits = orc.container_decode(arr)
+    assert np.array_equal(dec, x)
+    f = orc.histogram(x)
+    assert bits == orc.stream_bits(f, orc.huffman_lengths(f)) == blob.header.stream_bits
+    assert list(blob.header.freq) == [int(v) for v in f]
+    assert blob.size == orc.lib().orc_container_size(n, bits, lane_syms)
+
+
+def test_every_byte_value_and_special_histograms(orc):
+    cases = [np.arange(256, dtype=np.uint8).repeat(40),
+             np.full(5000, 0x80, dtype=np.uint8),                       # one symbol: -0 everywhere
+             np.array([0x38, 0xB8, 0x3C, 0x00], dtype=np.uint8),
+             np.concatenate([np.full(9000, 0x38, np.uint8), np.array([0x7F, 0xFF], np.uint8)])]
+    fib = [1, 1]
+    while len(fib) < 16:
+        fib.append(fib[-1] + fib[-2])
+    deep = np.repeat(np.arange(16, dtype=np.uint8) << 3, fib)
+    np.random.default_rng(0).shuffle(deep)
+    cases.append(deep)                                                  # code lengths up to 15
+    for x in cases:
+        blob = ecf8.ecf8_encode(x, 1, x.size)
+        dec, _ = orc.container_decode(blob.numpy())
+        assert np.array_equal(dec, x)
+    assert max(ecf8.ecf8_encode(deep, 1, deep.size).header.code_len) == 15
+
+
+def test_hand_example_bytes_in_the_product_container():
+    x = np.array([0x38, 0xB8, 0x3C, 0x00], dtype=np.uint8)
+    b = ecf8.ecf8_encode(x, 2, 2)
+    a, h = b.numpy(), b.header
+    assert h.stream_bits == 4 and h.rows == 2 and h.cols == 2
+    assert a[h.off_stream] == 0x07
+    assert list(a[h.off_plane:h.off_plane + 4]) == [0x00, 0x08, 0x04, 0x00]
+
+
+def test_threads_do_not_change_the_blob():
+    x = _rand_bytes(1_500_001, 5)
+    a = ecf8.ecf8_encode(x, 1, x.size, n_threads=1).numpy().copy()
+    for t in (2, 3, 8):
+        assert np.array_equal(a, ecf8.ecf8_encode(x, 1, x.size, n_threads=t).numpy())
+
+
+def test_synthetic_config0_compresses_like_the_paper_band(orc):
+    w = synth.make(synth.config0()[0], seed=0).numpy()
+    b = ecf8.ecf8_encode(w)
+    st = b.stats()
+    assert st["entropy_bits"] <= st["avg_code_bits"] < st["entropy_bits"] + 1
+    assert 0.75 < st["ratio"] < 0.93           # memory saving in the paper's 9.8-26.9 % range (Table 1)
+    dec, _ = orc.container_decode(b.numpy())
+    assert np.array_equal(dec, w.reshape(-1))
+
+
+def test_error_paths():
+    x = _rand_bytes(1000, 1)
+    with pytest.raises(ecf8.Ecf8Error) as e:
+        ecf8.ecf8_encode(x, 0, 0)
+    assert e.value.code == ecf8.E_ARG
+    with pytest.raises(ecf8.Ecf8Error):
+        ecf8.ecf8_encode(x, 1, 1000, lane_syms=48)
+    good = ecf8.ecf8_encode(x, 10, 100).numpy().copy()
+    ecf8.blob_validate(good)
+    for off, val in [(0, 0), (4, 9), (40, 16), (56, 1), (64, 0), (16, 7)]:
+        bad = good.copy()
+        bad[off] = val
+        with pytest.raises(ecf8.Ecf8Error) as e:
+            ecf8.blob_validate(bad)
+        assert e.value.code == ecf8.E_FORMAT
+    with pytest.raises(ecf8.Ecf8Error):
+        ecf8.blob_describe(good[:100].copy())
+    with pytest.raises(ecf8.Ecf8Error):
+        ecf8.blob_validate(good[:-256].copy())
+    h = ecf8.blob_describe(good)
+    bad = good.copy()
+    bad[h.off_lane_bits] ^= 1
+    with pytest.raises(ecf8.Ecf8Error):
+        ecf8.blob_validate(bad)
+    bad = good.copy()
+    bad[h.off_chunk_bit + 8] ^= 2
+    with pytest.raises(ecf8.Ecf8Error):
+        ecf8.blob_validate(bad)
+    # decode argument checks that need no device: null pointers, capacity, alignment
+    lib = ctypes.CDLL(ecf8.LIB_PATH)
+    assert lib.ecf8_decode(None, None, None, 0, None) == ecf8.E_ARG
+    assert lib.ecf8_decode(ctypes.byref(h), ctypes.c_void_p(4096), ctypes.c_void_p(8192), ctypes.c_uint64(10), None) == ecf8.E_CAPACITY
+    assert lib.ecf8_decode(ctypes.byref(h), ctypes.c_void_p(4097), ctypes.c_void_p(8192), ctypes.c_uint64(1000), None) == ecf8.E_ALIGN
+    assert lib.ecf8_decode_batched(None, 1, 1, 64, None) == ecf8.E_ARG
