@@ -1,0 +1,181 @@
+#!/usr/bin/env python3
+"""ECF8 decode benchmark on one MI355X.
+
+One step = one pass of the whole hot path over the workload: every layer of the
+stack is decoded from its resident compressed blobs to exact FP8 bytes, one
+ecf8_decode_batched launch per layer (the layer's matrices in one launch).
+Inputs are seeded synthetic alpha-stable FP8 weights; blobs and
+output buffers are resident in HBM before the timed region starts.
+
+Prints ONE JSON line: decoded FP8 GB/s as `value`, plus the roofline of the
+decode kernel and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def algorithmic_bytes(h):
+    """Bytes the method itself must move for one tensor: stream + nibble plane +
+    lane/chunk metadata + header read, n_elem written."""
+    rd = (h.stream_bits + 7) // 8 + (h.n_elem + 1) // 2 + 8 * (h.n_chunks + 1) + 2 * 64 * h.n_chunks + 256
+    return rd, h.n_elem
+
+
+def build_workload(name, seed, lane_syms, layers):
+    from paper_2510_02676_amd import ecf8, synth
+    if name == "config1":
+        specs = synth.config1(seed, layers)
+        group = lambda s: s["layer"]
+        desc = "8B-class dense LLM stack, %d layers x 7 matrices" % layers
+    elif name == "config3":
+        specs = synth.config3(layers)
+        group = lambda s: s["block"]
+        desc = "14B-class DiT stack, %d blocks x 11 matrices" % layers
+    elif name == "config0":
+        specs = synth.config0()
+        group = lambda s: 0
+        desc = "single 1024x1024 matrix"
+    else:
+        raise SystemExit("unknown workload " + name)
+    dev = "cuda:0"
+    groups = {}
+    t0 = time.time()
+    for s in specs:
+        w = synth.make(s, seed, device=dev)                       # uint8 (rows, cols) on the GPU
+        blob = ecf8.ecf8_encode(w.cpu(), s["rows"], s["cols"], lane_syms=lane_syms)
+        d_blob = blob.to(dev)
+        d_out = torch.empty((s["rows"], s["cols"]), dtype=torch.uint8, device=dev)
+        groups.setdefault(group(s), []).append(dict(spec=s, w=w, hdr=blob.header, d_blob=d_blob, d_out=d_out))
+    batches = []
+    for g in sorted(groups):
+        ts = groups[g]
+        batches.append((ecf8.Batch([t["hdr"] for t in ts], [t["d_blob"] for t in ts], [t["d_out"] for t in ts]), ts))
+    return batches, desc, time.time() - t0
+
+
+def cpu_baseline(batches, budget_syms=440_000_000):
+    """The oracle's bit-serial tree-walk decoder, single thread, on the first
+    tensors of the workload (about 10 s of CPU work)."""
+    import oracle
+    tot_syms, tot_t, names = 0, 0.0, []
+    for _, ts in batches:
+        for t in ts:
+            if tot_syms >= budget_syms:
+                break
+            x = t["w"].cpu().numpy().reshape(-1)
+            f = oracle.histogram(x)
+            ln = oracle.huffman_lengths(f)
+            codes = oracle.canonical_codes(ln)
+            stream, nbits = oracle.encode_exponents(x, ln, codes, oracle.MSB_FIRST)
+            packed = oracle.pack_nibbles_paper(x)
+            t0 = time.perf_counter()
+            out = oracle.decode_serial(stream, nbits, ln, packed, x.size, oracle.MSB_FIRST)
+            tot_t += time.perf_counter() - t0
+            if not np.array_equal(out, x):
+                raise SystemExit("oracle round trip failed on " + t["spec"]["name"])
+            tot_syms += x.size
+            names.append(t["spec"]["name"])
+        if tot_syms >= budget_syms:
+            break
+    return {"value": round(tot_syms / tot_t / 1e9, 4), "unit": "GB/s decoded FP8", "cores": 1, "kind": "oracle",
+            "sample": "bit-serial decode of %d tensors (%s..%s), %d weights, %.1f s" % (
+                len(names), names[0], names[-1], tot_syms, tot_t)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="config1")
+    ap.add_argument("--layers", type=int, default=0, help="0 = the full stack of the workload")
+    ap.add_argument("--lane-syms", type=int, default=0, help="0 = library default")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        raise SystemExit("this build runs on ONE GPU: tensors are independent and shard with no exchange "
+                         "(see DESIGN.md); --gpus %d is not supported" % a.gpus)
+    if not torch.cuda.is_available():
+        raise SystemExit("no GPU visible: the decode path has no CPU fallback")
+    from paper_2510_02676_amd import ecf8
+
+    layers = a.layers or {"config1": 32, "config3": 40, "config0": 1}[a.workload]
+    batches, desc, t_setup = build_workload(a.workload, a.seed, a.lane_syms, layers)
+    hdrs = [t["hdr"] for _, ts in batches for t in ts]
+    n_total = sum(h.n_elem for h in hdrs)
+    blob_total = sum(h.total_size for h in hdrs)
+    rd_total = sum(algorithmic_bytes(h)[0] for h in hdrs)
+    alg_total = rd_total + n_total
+
+    stream = torch.cuda.current_stream()
+
+    def step():
+        for b, _ in batches:
+            ecf8.ecf8_decode_batched(b, stream)
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    # parity of what the timed launches produce: exact bytes of every tensor
+    bad = [t["spec"]["name"] for _, ts in batches for t in ts if not torch.equal(t["d_out"], t["w"])]
+    if bad:
+        raise SystemExit("decode mismatch on " + ", ".join(bad[:5]))
+
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(a.steps):
+        step()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    dev_s = e0.elapsed_time(e1) * 1e-3
+    sec_per_step = wall / a.steps
+    n_launch = len(batches) * a.steps
+    launch_s = dev_s / n_launch                       # average duration of one decode launch (HIP events)
+    alg_per_launch = alg_total / len(batches)
+    achieved = alg_per_launch / launch_s / 1e9
+
+    out = {
+        "metric": "decoded FP8 GB/s (ECF8 -> exact FP8 E4M3 bytes)",
+        "value": round(n_total / sec_per_step / 1e9, 2),
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(sec_per_step * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "config": {"workload": "%s: %s" % (a.workload, desc), "weights": n_total,
+                   "launches_per_step": len(batches), "lane_syms": hdrs[0].lane_syms, "seed": a.seed},
+        "compression_ratio": round(blob_total / n_total, 5),
+        "memory_saving_pct": round(100 * (1 - blob_total / n_total), 2),
+        "avg_code_bits": round(sum(h.stream_bits for h in hdrs) / n_total, 4),
+        "compressed_read_GBps": round(rd_total / sec_per_step / 1e9, 2),
+        "total_moved_GBps": round(alg_total / sec_per_step / 1e9, 2),
+        "pct_of_hbm_peak": round(100 * alg_total / sec_per_step / 1e9 / HBM_PEAK_GBPS, 2),
+        "bit_exact": True,
+        "setup_s": round(t_setup, 1),
+        "roofline": {"bound": "hbm", "kernel": "ecf8_decode_kernel", "achieved": round(achieved, 2),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "avg_launch_us": round(launch_s * 1e6, 2),
+                     "algorithmic_bytes_per_launch": int(alg_per_launch), "traffic": None},
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(batches)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -7,20 +7,27 @@
 //
 //  * one wavefront decodes one chunk = 64 lanes x N consecutive elements; the
 //    encoder recorded how many stream bits each lane's N codewords take, so a
-//    DPP prefix scan over those 64 numbers gives every lane its start bit and
+//    DPP prefix scan over those 64 numbers gives every lane its start bit, and
 //    its output position is l*N by construction.  The paper's first decoding
 //    pass, which exists only to count symbols per thread, is gone;
 //  * the chunk's span of the stream is copied to LDS with dwordx4 loads, 1 KiB
-//    contiguous per wave instruction, and lanes pull 32-bit windows from LDS;
-//  * the code table is a 4096-entry LDS table indexed by the next 12 stream
-//    bits that yields up to four symbols per lookup, already shifted to their
-//    place in the output byte; codewords longer than 12 bits take a second
-//    level (a 16-entry canonical match).  It is built in the kernel from the
-//    16 code lengths, so a tensor's table costs 16 bytes of HBM traffic;
-//  * decoded bytes are appended to a per-lane LDS region with unaligned dword
-//    writes, then read back transposed so that each store instruction of the
-//    wave writes 1 KiB of contiguous output, merged with the nibble plane that
-//    was fetched (coalesced, 512 B per instruction) before decoding started;
+//    contiguous per wave instruction; lanes pull aligned 64-bit windows from
+//    LDS (unaligned LDS accesses serialise per lane on this chip, so every LDS
+//    access here is naturally aligned);
+//  * the code table is a 2^TB-entry LDS table of 16-bit entries indexed by the
+//    next TB stream bits; one lookup yields TWO symbols, already shifted to
+//    their place in the output bytes, and the bits they consume.  A lane
+//    always decodes four symbols (two lookups) per step, so every lane of the
+//    wave runs the same number of steps, nothing diverges, and each step ends
+//    in one aligned dword write.  Pairs that do not fit in TB bits and
+//    codewords longer than TB bits take a second level (per-symbol walk that
+//    reuses the table's first-symbol fields, then a 16-entry canonical match).
+//    The table is built in the kernel from the 16 code lengths, so a tensor's
+//    table costs 16 bytes of HBM traffic;
+//  * decoded bytes are read back from LDS transposed, so that each store
+//    instruction of the wave writes 1 KiB of contiguous output, merged with the
+//    nibble plane that was fetched (coalesced, 512 B per instruction) before
+//    decoding started;
 //  * persistent workgroups walk contiguous chunk ranges, so a table is built
 //    once per (workgroup, tensor) and no global atomics are needed.
 #include "ecf8.h"
@@ -31,15 +38,19 @@
 
 namespace {
 
-constexpr int TB = 12;                 // first-level table index bits
+constexpr int TB = 14;                 // table index bits
 constexpr int TBL_ENTRIES = 1 << TB;
+constexpr uint32_t TBL_MASK = TBL_ENTRIES - 1;
 
-// Table entry (one dword), for k = 1..4 symbols decoded from the index bits:
-//   byte i bits 3..6 : exponent field of symbol i, in its output position
-//   bits 0..2        : k
-//   bits 7..10       : stream bits consumed by the k symbols
-// The control fields sit in bits the merge masks off (0x78 per byte keeps the
-// exponent only).  Entry 0 means "first codeword is longer than TB bits".
+// Table entry (16 bits) for index bits b0 b1 ... (b0 = next stream bit):
+//   bits 3..6   : exponent field of the first symbol  (output position of byte 0)
+//   bits 11..14 : exponent field of the second symbol (output position of byte 1)
+//   bits 7..10  : stream bits consumed by both symbols; 0 = the pair does not
+//                 fit in TB bits (second level decides)
+//   bits 0..2,15: code length of the first symbol alone (low 3 bits, high bit);
+//                 0 = the first codeword is longer than TB bits
+// Control fields sit in bits the merge masks off (0x78 per byte keeps the
+// exponent field only).
 constexpr uint32_t EXP_MASK = 0x78787878u;
 
 #define GLOBAL __attribute__((address_space(1))) // HBM pointers: global_load/store, not flat
@@ -59,26 +70,22 @@ __device__ __forceinline__ uint32_t len_of(uint64_t lo, uint64_t hi, int s)
     return (uint32_t)((s < 8 ? lo >> (8 * s) : hi >> (8 * (s - 8))) & 0xff);
 }
 
-template <int N>
+template <int N, int WAVES>
 struct Cfg {
     static constexpr int STAGE = N * 32 + 64;         // bytes of stream staged per chunk
-    static constexpr int LANE_STRIDE = N + 4;         // output region per lane (+3 overshoot, dword aligned)
+    static constexpr int LANE_STRIDE = N + 4;         // output region per lane; odd dword count spreads banks
     static constexpr int OUTREG = 64 * LANE_STRIDE;
     static constexpr int WAVE_BYTES = STAGE + OUTREG;
     static constexpr int PIECES = N / 16;             // 16-byte pieces per lane
+    static constexpr int QUADS = N / 4;               // decode steps per lane
+    // LDS map (byte offsets into one array)
+    static constexpr int OFF_TBL = 0;
+    static constexpr int OFF_SYM = OFF_TBL + TBL_ENTRIES * 2;  // s_len[16], s_code[16]
+    static constexpr int OFF_WAVES = OFF_SYM + 128;
+    static constexpr int TOTAL = OFF_WAVES + WAVES * WAVE_BYTES;
+    static_assert(WAVES * WAVE_BYTES >= TBL_ENTRIES * 2, "table-build scratch aliases the wave regions");
+    static_assert(TOTAL <= 160 * 1024, "LDS of one gfx950 CU");
 };
-
-__device__ __forceinline__ uint32_t lds_load_u32(const uint8_t *p)
-{
-    uint32_t v;
-    __builtin_memcpy(&v, p, 4); // LDS takes unaligned dword accesses on gfx950
-    return v;
-}
-
-__device__ __forceinline__ void lds_store_u32(uint8_t *p, uint32_t v)
-{
-    __builtin_memcpy(p, &v, 4);
-}
 
 // Inclusive wave64 prefix sum with DPP row shifts and row broadcasts.
 __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x)
@@ -93,22 +100,27 @@ __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x)
     return v;
 }
 
-// Second level: the codeword at the bottom of `bits` (stream order, >= 15 valid
-// bits) is longer than TB.  Match it against the long canonical codes.
-__device__ __forceinline__ uint32_t decode_long(uint32_t bits, const uint32_t *s_len, const uint32_t *s_code)
+// One symbol the careful way.  `bits`: stream bits from the current position
+// (>= 15 valid).  Returns exponent | length << 8.
+__device__ __forceinline__ uint32_t decode_one(uint32_t bits, const uint16_t *tbl, const uint32_t *s_len,
+                                               const uint32_t *s_code)
 {
+    uint32_t e = tbl[bits & TBL_MASK];
+    uint32_t l = (e & 7u) | ((e >> 12) & 8u);
+    if (l) return ((e >> 3) & 15u) | (l << 8);
+    // longer than TB bits: match against the long canonical codes
     uint32_t v = __brev(bits) >> 17;          // next 15 bits, first bit most significant
-    uint32_t e = 1u | (15u << 7);             // no match (corrupt stream): skip 15 bits, exponent 0
+    uint32_t r = 15u << 8;                    // no match (corrupt stream): skip 15 bits, exponent 0
     for (int s = 0; s < 16; s++) {
-        uint32_t l = s_len[s];
-        if (l > TB && (v >> (15 - l)) == s_code[s]) e = ((uint32_t)s << 3) | 1u | (l << 7);
+        uint32_t ls = s_len[s];
+        if (ls > TB && (v >> (15 - ls)) == s_code[s]) r = (uint32_t)s | (ls << 8);
     }
-    return e;
+    return r;
 }
 
-// Builds the first-level table and the per-symbol (length, code) arrays in LDS
-// from the 16 code lengths.  `tmp` is TBL_ENTRIES u16 of scratch LDS.
-__device__ void build_tables(uint64_t len_lo, uint64_t len_hi, uint32_t *tbl, uint32_t *s_len, uint32_t *s_code,
+// Builds the pair table and the per-symbol (length, code) arrays in LDS from
+// the 16 code lengths.  `tmp` is TBL_ENTRIES u16 of scratch LDS.
+__device__ void build_tables(uint64_t len_lo, uint64_t len_hi, uint16_t *tbl, uint32_t *s_len, uint32_t *s_code,
                              uint16_t *tmp, int tid, int nthreads)
 {
     if (tid < 16) {
@@ -135,17 +147,16 @@ __device__ void build_tables(uint64_t len_lo, uint64_t len_hi, uint32_t *tbl, ui
     }
     __syncthreads();
     for (int idx = tid; idx < TBL_ENTRIES; idx += nthreads) {
-        uint32_t cur = idx, used = 0, k = 0, e = 0;
-        for (int i = 0; i < 4; i++) {
-            uint32_t t = tmp[cur];
-            uint32_t l = t >> 4;
-            if (l == 0 || used + l > TB) break;   // long code, or it needs bits beyond the index
-            e |= (t & 15u) << (8 * i + 3);
-            used += l;
-            cur >>= l;
-            k++;
+        uint32_t t1 = tmp[idx];
+        uint32_t l1 = t1 >> 4;
+        uint32_t e = 0;
+        if (l1) {
+            e = ((t1 & 15u) << 3) | (l1 & 7u) | ((l1 & 8u) << 12);
+            uint32_t t2 = tmp[idx >> l1];
+            uint32_t l2 = t2 >> 4;
+            if (l2 && l1 + l2 <= TB) e |= ((t2 & 15u) << 11) | ((l1 + l2) << 7);
         }
-        tbl[idx] = k ? (e | k | (used << 7)) : 0u;
+        tbl[idx] = (uint16_t)e;
     }
     __syncthreads();
 }
@@ -153,17 +164,19 @@ __device__ void build_tables(uint64_t len_lo, uint64_t len_hi, uint32_t *tbl, ui
 template <int N, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
 {
-    using C = Cfg<N>;
-    __shared__ __attribute__((aligned(16))) uint32_t tbl[TBL_ENTRIES];
-    __shared__ uint32_t s_len[16], s_code[16];
-    __shared__ __attribute__((aligned(16))) uint8_t wave_mem[WAVES][C::WAVE_BYTES];
-    static_assert(sizeof(wave_mem) >= TBL_ENTRIES * 2, "table scratch aliases the wave regions");
+    using C = Cfg<N, WAVES>;
+    __shared__ __attribute__((aligned(16))) uint8_t smem[C::TOTAL];
+    uint16_t *tbl = (uint16_t *)(smem + C::OFF_TBL);
+    uint32_t *s_len = (uint32_t *)(smem + C::OFF_SYM);
+    uint32_t *s_code = s_len + 16;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    uint8_t *stage = wave_mem[wave];
-    uint8_t *outreg = wave_mem[wave] + C::STAGE;
+    const uint32_t stage_off = C::OFF_WAVES + wave * C::WAVE_BYTES;   // byte offsets into smem
+    const uint32_t outreg_off = stage_off + C::STAGE;
+    uint8_t *stage = smem + stage_off;
+    uint8_t *outreg = smem + outreg_off;
 
     // contiguous range of the batch's chunks for this workgroup
     const uint64_t G = gridDim.x, g = blockIdx.x;
@@ -204,10 +217,10 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
         const GLOBAL uint8_t *plane = (const GLOBAL uint8_t *)(d_blob + off_pl);
 
         __syncthreads(); // every wave is done with the previous tensor's table and its scratch
-        build_tables(len_lo, len_hi, tbl, s_len, s_code, (uint16_t *)&wave_mem[0][0], tid, WAVES * 64);
+        build_tables(len_lo, len_hi, tbl, s_len, s_code, (uint16_t *)(smem + C::OFF_WAVES), tid, WAVES * 64);
 
         for (uint64_t cg = c + wave; cg < seg_end; cg += WAVES) {
-            const uint64_t cl = cg - first_chunk;             // chunk index inside the tensor
+            const uint64_t cl = cg - first_chunk;                // chunk index inside the tensor
             const uint64_t elem0 = cl * (64ull * N);             // first element of the chunk
             const uint64_t b0 = chunk_bit[cl], b1 = chunk_bit[cl + 1];
 
@@ -215,53 +228,71 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
             const uint32_t lb = lane_bits[cl * 64 + lane];
             const uint32_t rel = wave_incl_scan(lb) - lb;
 
-            // symbols this lane owns (ragged last chunk)
-            const uint64_t lane_first = elem0 + (uint64_t)lane * N;
-            const uint32_t nsym = lane_first >= n_elem ? 0u
-                                  : (uint32_t)min((uint64_t)N, n_elem - lane_first);
-
             // nibble plane of the chunk, in the order the write-back wants it
             u32x2 pl[C::PIECES];
             const GLOBAL u32x2 *plane_c = (const GLOBAL u32x2 *)(plane + cl * (32ull * N));
 #pragma unroll
             for (int j = 0; j < C::PIECES; j++) pl[j] = plane_c[j * 64 + lane];
 
-            // stage the chunk's span of the stream (16-byte aligned start, +4 bytes look-ahead)
-            uint64_t byte_end = min(((b1 + 7) >> 3) + 4, st_bytes);
-            uint64_t byte0 = min((b0 >> 3) & ~15ull, byte_end);
-            const uint32_t span = (uint32_t)min(byte_end - byte0, (uint64_t)0x7fffffff);
-            const bool staged = span <= (uint32_t)C::STAGE;
+            // the chunk's span of the stream: 16-byte aligned start, 8 bytes of look-ahead
+            uint64_t byte_end = ((b1 + 7) >> 3) + 8;
+            if (byte_end > st_bytes) byte_end = st_bytes;
+            uint64_t byte0 = (b0 >> 3) & ~15ull;
+            if (byte0 > byte_end) byte0 = byte_end;
+            const uint64_t span64 = byte_end - byte0;
             const uint32_t bit_in = (uint32_t)(b0 - byte0 * 8) + rel; // lane start, bits from byte0
 
-            uint8_t *optr = outreg + lane * C::LANE_STRIDE;
-            uint8_t *const oend = optr + nsym;
-
-            if (staged) {
+            if (span64 <= (uint64_t)C::STAGE) {
+                const uint32_t span = (uint32_t)span64;
                 for (uint32_t i = lane * 16; i < span; i += 64 * 16)
                     *(u32x4 *)(stage + i) = *(const GLOBAL u32x4 *)(stream + byte0 + i);
-                uint32_t bp = bit_in;
-                while (optr < oend) {
-                    uint32_t w = lds_load_u32(stage + (bp >> 3)) >> (bp & 7);
-                    uint32_t e = tbl[w & (TBL_ENTRIES - 1)];
-                    if (__builtin_expect((e & 7u) == 0, 0)) e = decode_long(w, s_len, s_code);
-                    lds_store_u32(optr, e);
-                    optr += e & 7u;
-                    bp += (e >> 7) & 15u;
+                // bp: LDS bit address (smem-relative) of the lane's next codeword
+                uint32_t bp = stage_off * 8 + bit_in;
+                uint8_t *orow = outreg + lane * C::LANE_STRIDE;
+#pragma unroll 4
+                for (int q = 0; q < C::QUADS; q++) {
+                    const uint32_t aw = (bp >> 3) & ~3u;
+                    const uint32_t d0 = *(const uint32_t *)(smem + aw);
+                    const uint32_t d1 = *(const uint32_t *)(smem + aw + 4);
+                    const uint32_t w = __builtin_amdgcn_alignbit(d1, d0, bp);   // 32 stream bits from bp
+                    const uint32_t e1 = tbl[w & TBL_MASK];
+                    const uint32_t n1 = (e1 >> 7) & 15u;
+                    const uint32_t e2 = tbl[(w >> n1) & TBL_MASK];
+                    const uint32_t n2 = (e2 >> 7) & 15u;
+                    uint32_t o = e1 | (e2 << 16);
+                    uint32_t adv = n1 + n2;
+                    // n1 == 0 makes the second lookup repeat the first, so n2 == 0 covers both
+                    if (__builtin_expect(n2 == 0, 0)) {
+                        uint32_t b = bp;
+                        o = 0;
+#pragma unroll 1
+                        for (int i = 0; i < 4; i++) {
+                            const uint32_t ai = (b >> 3) & ~3u;
+                            const uint32_t x0 = *(const uint32_t *)(smem + ai);
+                            const uint32_t x1 = *(const uint32_t *)(smem + ai + 4);
+                            const uint32_t r = decode_one(__builtin_amdgcn_alignbit(x1, x0, b), tbl, s_len, s_code);
+                            o |= (r & 15u) << (8 * i + 3);
+                            b += r >> 8;
+                        }
+                        adv = b - bp;
+                    }
+                    *(uint32_t *)(orow + 4 * q) = o;
+                    bp += adv;
                 }
             } else {
-                // span larger than the staging buffer (a chunk that codes far worse than
-                // 4 bits per symbol): same loop, windows read straight from global memory
+                // A chunk that codes far worse than 4 bits per symbol does not fit the staging
+                // buffer: walk it symbol by symbol with windows read straight from HBM.
+                const uint64_t lane_first = elem0 + (uint64_t)lane * N;
+                const uint32_t nsym = lane_first >= n_elem ? 0u
+                                      : (uint32_t)((n_elem - lane_first) < (uint64_t)N ? (n_elem - lane_first) : N);
                 const GLOBAL uint8_t *sp = stream + byte0;
-                uint32_t bp = bit_in;
-                while (optr < oend) {
-                    const GLOBAL uint8_t *q = sp + (bp >> 3);
-                    uint32_t w = ((uint32_t)q[0] | ((uint32_t)q[1] << 8) | ((uint32_t)q[2] << 16) |
-                                  ((uint32_t)q[3] << 24)) >> (bp & 7);
-                    uint32_t e = tbl[w & (TBL_ENTRIES - 1)];
-                    if (__builtin_expect((e & 7u) == 0, 0)) e = decode_long(w, s_len, s_code);
-                    lds_store_u32(optr, e);
-                    optr += e & 7u;
-                    bp += (e >> 7) & 15u;
+                uint32_t b = bit_in;
+                uint8_t *orow = outreg + lane * C::LANE_STRIDE;
+                for (uint32_t i = 0; i < nsym; i++) {
+                    const GLOBAL uint32_t *q = (const GLOBAL uint32_t *)(sp + ((b >> 3) & ~3u));
+                    const uint32_t r = decode_one(__builtin_amdgcn_alignbit(q[1], q[0], b), tbl, s_len, s_code);
+                    orow[i] = (uint8_t)((r & 15u) << 3);
+                    b += r >> 8;
                 }
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -299,23 +330,19 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
     }
 }
 
-struct DevInfo {
-    int cus = 0;
-};
-
 int device_cus()
 {
     static std::mutex m;
-    static DevInfo info[64];
+    static int cus[64];
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return -1;
     std::lock_guard<std::mutex> lk(m);
-    if (info[dev].cus == 0) {
+    if (cus[dev] == 0) {
         hipDeviceProp_t p;
         if (hipGetDeviceProperties(&p, dev) != hipSuccess) return -1;
-        info[dev].cus = p.multiProcessorCount > 0 ? p.multiProcessorCount : 1;
+        cus[dev] = p.multiProcessorCount > 0 ? p.multiProcessorCount : 1;
     }
-    return info[dev].cus;
+    return cus[dev];
 }
 
 template <int N, int WAVES>
@@ -334,9 +361,9 @@ int launch(const KArgs &a, int wgs_per_cu, hipStream_t s)
 int dispatch(const KArgs &a, uint32_t lane_syms, hipStream_t s)
 {
     switch (lane_syms) {
-    case 32: return launch<32, 8>(a, 3, s);
-    case 64: return launch<64, 8>(a, 2, s);
-    case 128: return launch<128, 4>(a, 2, s);
+    case 32: return launch<32, 16>(a, 1, s);
+    case 64: return launch<64, 16>(a, 1, s);
+    case 128: return launch<128, 8>(a, 1, s);
     default: return ECF8_E_ARG;
     }
 }

@@ -124,9 +124,9 @@ class Blob:
     def stats(self):
         return blob_stats(self.header)
 
-    def __del__(self):
+    def __del__(self, _free=_lib.ecf8_blob_free):
         if getattr(self, "_h", None):
-            _lib.ecf8_blob_free(self._h)
+            _free(self._h)
             self._h = None
 
 
