@@ -27,10 +27,14 @@
  *   header (256 B): see struct ecf8_header
  *   chunk_bit : u64[n_chunks+1]  stream bit at which chunk c's first codeword
  *                                starts; last entry = stream_bits
- *   lane_bits : u16[n_chunks*64] code bits of lane l of chunk c, i.e. of
- *                                elements [c*64N + l*N, +N) clipped to n_elem
- *                                (N = lane_syms); 0 for empty lanes
- *   stream    : the codewords of elements 0..n_elem-1 concatenated in order;
+ *   lane_bits : u16[n_chunks*64] code bits of lane l of chunk c (N = lane_syms
+ *                                symbols, fewer in the ragged last chunk);
+ *                                0 for empty lanes
+ *   stream    : the codewords concatenated chunk by chunk, inside a chunk lane
+ *               by lane; lane l of chunk c codes, in this order, the
+ *               16-element pieces l, l+64, l+128, ... of the chunk, i.e. its
+ *               k-th symbol is element c*64N + ((k/16)*64 + l)*16 + k%16
+ *               (elements >= n_elem do not exist and are skipped);
  *               stream bit i is bit (i & 7) of byte (i >> 3); a codeword's
  *               first (most significant) bit comes first; codes are the
  *               canonical code of code_len[] ordered by (length, symbol);
@@ -38,8 +42,8 @@
  *   plane     : nibbles q = sign<<3 | mantissa; element i lives in byte
  *               (i/8)*4 + (i%4), low nibble if (i%8) < 4 else high nibble;
  *               zero padded to n_chunks*32N bytes
- * A chunk is 64 lanes of N symbols: one wavefront decodes one chunk, one lane
- * decodes N consecutive elements.
+ * A chunk is 64 lanes of N symbols: one wavefront decodes one chunk; in every
+ * decode step the 64 lanes produce 64 adjacent 16-byte pieces of the output.
  */
 #ifndef ECF8_H
 #define ECF8_H

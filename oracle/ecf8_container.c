@@ -6,8 +6,9 @@
  * or header with the product.  The container replaces the paper's
  * synchronisation metadata (Section 3.1: per-thread gaps and per-block output
  * positions, Table 4 "gaps"/"outpos") by a sampling of codeword start
- * positions: the stream itself is still the plain in-order concatenation of
- * the codewords (Section 3.1, "continuous bitstream").
+ * positions, and orders the codewords inside a chunk lane by lane so that the
+ * 64 lanes of a wavefront produce adjacent output in the same step; the stream
+ * is still one continuous concatenation of codewords (Section 3.1).
  *
  * Container (all integers little-endian):
  *   header, 256 bytes:
@@ -23,13 +24,15 @@
  *     128 u64 freq[16]
  *   chunk_bit : u64[n_chunks+1]   start bit of the first codeword of chunk c;
  *                                 last entry = stream_bits
- *   lane_bits : u16[n_chunks*64]  total code bits of the (up to N) elements
- *                                 [c*64N + l*N, +N) clipped to n_elem
+ *   lane_bits : u16[n_chunks*64]  total code bits of lane l of chunk c
  *   stream    : stream_bytes bytes; stream bit i = bit (i&7) of byte (i>>3);
- *               each codeword is written first-bit-first (its most
- *               significant bit first); codes are canonical from code_len,
- *               ordered by (length, symbol); zero padded,
- *               stream_bytes = roundup16(ceil(stream_bits/8) + 8)
+ *               codewords chunk by chunk, inside a chunk lane by lane; the
+ *               k-th symbol (k = 0..N-1) of lane l of chunk c is element
+ *               c*64N + ((k/16)*64 + l)*16 + k%16; elements >= n_elem do not
+ *               exist and are skipped; each codeword is written
+ *               first-bit-first (its most significant bit first); codes are
+ *               canonical from code_len, ordered by (length, symbol); zero
+ *               padded, stream_bytes = roundup16(ceil(stream_bits/8) + 8)
  *   plane     : sign/mantissa nibbles q = sign<<3 | mantissa (Table 4,
  *               "packed"), regrouped: element i sits in byte
  *               (i/8)*4 + (i%4), low nibble when (i%8) < 4, else high
@@ -78,6 +81,12 @@ static void wr64(uint8_t *p, uint64_t v) { for (int i = 0; i < 8; i++) p[i] = (u
 static void wr32(uint8_t *p, uint32_t v) { for (int i = 0; i < 4; i++) p[i] = (uint8_t)(v >> (8 * i)); }
 static void wr16(uint8_t *p, uint32_t v) { p[0] = (uint8_t)v; p[1] = (uint8_t)(v >> 8); }
 static uint64_t up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+
+/* element coded by the k-th symbol of lane l of chunk c */
+static uint64_t lane_element(uint64_t c, uint64_t l, uint64_t k, uint32_t N)
+{
+    return c * 64ull * N + ((k / 16) * 64 + l) * 16 + (k % 16);
+}
 
 static uint64_t plane_byte_index(uint64_t i) { return (i / 8) * 4 + (i % 4); }
 static int plane_is_high(uint64_t i) { return (i % 8) >= 4; }
@@ -144,26 +153,34 @@ int orc_container_encode(const uint8_t *x, uint64_t rows, uint64_t cols, uint32_
     wr64(blob + 120, pl_bytes);
     for (int i = 0; i < ORC_NSYM; i++) wr64(blob + 128 + 8 * i, freq[i]);
 
-    /* stream + the start bit of every lane (every N-th symbol) */
-    uint64_t n_lanes = (n + N - 1) / N;
-    uint64_t *marks = (uint64_t *)calloc(n_lanes + 1, sizeof(uint64_t));
-    if (!marks) return ORC_E_CAPACITY;
-    uint64_t got = 0;
-    rc = orc_encode_exponents(x, n, len, code, ORC_LSB_FIRST, blob + off_st, st_bytes, &got, N, marks);
-    if (rc == ORC_OK && got != bits) rc = ORC_E_FORMAT;
-    if (rc) { free(marks); return rc; }
-    marks[n_lanes] = bits;
+    /* the input in stream order, and the code bits of every lane */
+    uint8_t *xs = (uint8_t *)malloc(n);
+    if (!xs) return ORC_E_CAPACITY;
+    uint64_t j = 0, pos = 0;
     for (uint64_t c = 0; c < n_chunks; c++) {
-        uint64_t first_lane = c * 64;
-        wr64(blob + off_cb + 8 * c, marks[first_lane]);
+        wr64(blob + off_cb + 8 * c, pos);
         for (uint64_t l = 0; l < 64; l++) {
-            uint64_t gl = first_lane + l;
-            uint64_t lb = gl < n_lanes ? marks[gl + 1] - marks[gl] : 0;
+            uint64_t lb = 0;
+            for (uint64_t k = 0; k < N; k++) {
+                uint64_t e = lane_element(c, l, k, N);
+                if (e >= n) continue;
+                uint8_t sg, ex, mn;
+                orc_split(x[e], &sg, &ex, &mn);
+                lb += len[ex];
+                xs[j++] = x[e];
+            }
             wr16(blob + off_lb + 2 * (c * 64 + l), (uint32_t)lb);
+            pos += lb;
         }
     }
-    wr64(blob + off_cb + 8 * n_chunks, bits);
-    free(marks);
+    wr64(blob + off_cb + 8 * n_chunks, pos);
+    uint64_t got = 0;
+    rc = (j == n && pos == bits) ? ORC_OK : ORC_E_FORMAT;
+    if (rc == ORC_OK)
+        rc = orc_encode_exponents(xs, n, len, code, ORC_LSB_FIRST, blob + off_st, st_bytes, &got, 0, NULL);
+    free(xs);
+    if (rc == ORC_OK && got != bits) rc = ORC_E_FORMAT;
+    if (rc) return rc;
 
     /* regrouped nibble plane */
     for (uint64_t i = 0; i < n; i++) {
@@ -232,44 +249,49 @@ int orc_container_decode(const uint8_t *blob, uint64_t size, uint8_t *out, uint6
     int rc = orc_decode_symbols(stream, bits, ORC_LSB_FIRST, len, n, sym);
     if (rc) { free(sym); free(lane_sym); return rc; }
 
-    /* pass 2: lane by lane through the metadata */
+    /* pass 2: lane by lane through the metadata; lanes follow each other in stream order */
     if (rd64(blob + off_cb) != 0 || rd64(blob + off_cb + 8 * n_chunks) != bits) rc = ORC_E_META;
+    uint64_t sidx = 0; /* stream-order index of the lane's first symbol */
     for (uint64_t c = 0; c < n_chunks && rc == ORC_OK; c++) {
         uint64_t pos = rd64(blob + off_cb + 8 * c);
         for (uint64_t l = 0; l < 64 && rc == ORC_OK; l++) {
-            uint64_t first = c * chunk + l * N;
-            uint64_t cnt = first >= n ? 0 : (n - first < N ? n - first : N);
+            uint64_t cnt = 0;
+            for (uint64_t k = 0; k < N; k++)
+                if (lane_element(c, l, k, N) < n) cnt++;
             uint64_t lb = rd16(blob + off_lb + 2 * (c * 64 + l));
             if (cnt == 0) { if (lb != 0) rc = ORC_E_META; continue; }
             if (pos + lb > bits) { rc = ORC_E_META; break; }
-            /* decode exactly cnt symbols from the lane's own window of lb bits,
-             * addressed relative to the whole stream so bit numbering is shared */
-            {
-                /* a private copy of the window makes "ends exactly at lb" checkable
-                 * with the same strict decoder */
-                uint64_t wbytes = (lb + 7) / 8 + 1;
-                uint8_t *wbuf = (uint8_t *)calloc(wbytes, 1);
-                if (!wbuf) { rc = ORC_E_CAPACITY; break; }
-                for (uint64_t b = 0; b < lb; b++)
-                    if ((stream[(pos + b) >> 3] >> ((pos + b) & 7)) & 1)
-                        wbuf[b >> 3] |= (uint8_t)(1u << (b & 7));
-                int r2 = orc_decode_symbols(wbuf, lb, ORC_LSB_FIRST, len, cnt, lane_sym);
-                free(wbuf);
-                if (r2) { rc = ORC_E_META; break; }
-            }
-            if (memcmp(lane_sym, sym + first, cnt) != 0) { rc = ORC_E_META; break; }
+            /* a private copy of the lane's lb bits makes "ends exactly there" checkable
+             * with the same strict decoder */
+            uint64_t wbytes = (lb + 7) / 8 + 1;
+            uint8_t *wbuf = (uint8_t *)calloc(wbytes, 1);
+            if (!wbuf) { rc = ORC_E_CAPACITY; break; }
+            for (uint64_t b = 0; b < lb; b++)
+                if ((stream[(pos + b) >> 3] >> ((pos + b) & 7)) & 1)
+                    wbuf[b >> 3] |= (uint8_t)(1u << (b & 7));
+            int r2 = orc_decode_symbols(wbuf, lb, ORC_LSB_FIRST, len, cnt, lane_sym);
+            free(wbuf);
+            if (r2) { rc = ORC_E_META; break; }
+            if (memcmp(lane_sym, sym + sidx, cnt) != 0) { rc = ORC_E_META; break; }
+            sidx += cnt;
             pos += lb;
         }
         if (rc == ORC_OK && pos != rd64(blob + off_cb + 8 * (c + 1))) rc = ORC_E_META;
     }
+    if (rc == ORC_OK && sidx != n) rc = ORC_E_META;
 
     if (rc == ORC_OK) {
         const uint8_t *plane = blob + off_pl;
-        for (uint64_t i = 0; i < n; i++) {
-            uint8_t b = plane[plane_byte_index(i)];
-            uint8_t q = plane_is_high(i) ? (uint8_t)(b >> 4) : (uint8_t)(b & 15);
-            out[i] = orc_join((uint8_t)(q >> 3), sym[i], (uint8_t)(q & 7));
-        }
+        uint64_t j = 0;
+        for (uint64_t c = 0; c < n_chunks; c++)
+            for (uint64_t l = 0; l < 64; l++)
+                for (uint64_t k = 0; k < N; k++) {
+                    uint64_t i = lane_element(c, l, k, N);
+                    if (i >= n) continue;
+                    uint8_t b = plane[plane_byte_index(i)];
+                    uint8_t q = plane_is_high(i) ? (uint8_t)(b >> 4) : (uint8_t)(b & 15);
+                    out[i] = orc_join((uint8_t)(q >> 3), sym[j++], (uint8_t)(q & 7));
+                }
         /* padding nibbles beyond n must be zero */
         for (uint64_t i = n; i < n_chunks * chunk; i++) {
             uint8_t b = plane[plane_byte_index(i)];

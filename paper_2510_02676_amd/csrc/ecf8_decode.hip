@@ -5,11 +5,12 @@
 // a lookup table held next to the ALUs, merge the sign/mantissa nibble, write
 // back coalesced).  How it is computed is specific to CDNA4:
 //
-//  * one wavefront decodes one chunk = 64 lanes x N consecutive elements; the
-//    encoder recorded how many stream bits each lane's N codewords take, so a
-//    DPP prefix scan over those 64 numbers gives every lane its start bit, and
-//    its output position is l*N by construction.  The paper's first decoding
-//    pass, which exists only to count symbols per thread, is gone;
+//  * one wavefront decodes one chunk = 64 lanes x N elements; the encoder
+//    recorded how many stream bits each lane's N codewords take, so a DPP
+//    prefix scan over those 64 numbers gives every lane its start bit, and
+//    output positions are fixed by construction (lane l owns the 16-byte
+//    pieces l, l+64, ... of the chunk).  The paper's first decoding pass,
+//    which exists only to count symbols per thread, is gone;
 //  * the chunk's span of the stream is copied to LDS with dwordx4 loads, 1 KiB
 //    contiguous per wave instruction; lanes pull aligned 64-bit windows from
 //    LDS (unaligned LDS accesses serialise per lane on this chip, so every LDS
@@ -19,15 +20,16 @@
 //    their place in the output bytes, and the bits they consume.  A lane
 //    always decodes four symbols (two lookups) per step, so every lane of the
 //    wave runs the same number of steps, nothing diverges, and each step ends
-//    in one aligned dword write.  Pairs that do not fit in TB bits and
+//    with one finished output dword in a register.  Pairs that do not fit in TB bits and
 //    codewords longer than TB bits take a second level (per-symbol walk that
 //    reuses the table's first-symbol fields, then a 16-entry canonical match).
 //    The table is built in the kernel from the 16 code lengths, so a tensor's
 //    table costs 16 bytes of HBM traffic;
-//  * decoded bytes are read back from LDS transposed, so that each store
-//    instruction of the wave writes 1 KiB of contiguous output, merged with the
-//    nibble plane that was fetched (coalesced, 512 B per instruction) before
-//    decoding started;
+//  * after four steps a lane holds one 16-byte piece; the 64 lanes' pieces are
+//    adjacent, so each dwordx4 store instruction of the wave writes 1 KiB of
+//    contiguous output, merged in registers with the nibble plane that was
+//    fetched (coalesced, 512 B per instruction) a whole chunk earlier.  Decoded
+//    bytes never pass through LDS;
 //  * persistent workgroups walk contiguous chunk ranges, so a table is built
 //    once per (workgroup, tensor) and no global atomics are needed.
 #include "ecf8.h"
@@ -73,17 +75,14 @@ __device__ __forceinline__ uint32_t len_of(uint64_t lo, uint64_t hi, int s)
 template <int N, int WAVES>
 struct Cfg {
     static constexpr int STAGE = N * 32 + 64;         // bytes of stream staged per chunk
-    static constexpr int LANE_STRIDE = N + 4;         // output region per lane; odd dword count spreads banks
-    static constexpr int OUTREG = 64 * LANE_STRIDE;
-    static constexpr int WAVE_BYTES = STAGE + OUTREG;
-    static constexpr int PIECES = N / 16;             // 16-byte pieces per lane
-    static constexpr int QUADS = N / 4;               // decode steps per lane
+    static constexpr int PIECES = N / 16;             // 16-byte output pieces per lane
+    static constexpr int SEGS = (STAGE / 16 + 63) / 64;  // dwordx4 loads per lane that cover STAGE
     // LDS map (byte offsets into one array)
     static constexpr int OFF_TBL = 0;
     static constexpr int OFF_SYM = OFF_TBL + TBL_ENTRIES * 2;  // s_len[16], s_code[16]
     static constexpr int OFF_WAVES = OFF_SYM + 128;
-    static constexpr int TOTAL = OFF_WAVES + WAVES * WAVE_BYTES;
-    static_assert(WAVES * WAVE_BYTES >= TBL_ENTRIES * 2, "table-build scratch aliases the wave regions");
+    static constexpr int WAVES_BYTES = WAVES * STAGE > TBL_ENTRIES * 2 ? WAVES * STAGE : TBL_ENTRIES * 2;
+    static constexpr int TOTAL = OFF_WAVES + WAVES_BYTES;   // table-build scratch aliases the stages
     static_assert(TOTAL <= 160 * 1024, "LDS of one gfx950 CU");
 };
 
@@ -173,10 +172,8 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const uint32_t stage_off = C::OFF_WAVES + wave * C::WAVE_BYTES;   // byte offsets into smem
-    const uint32_t outreg_off = stage_off + C::STAGE;
+    const uint32_t stage_off = C::OFF_WAVES + wave * C::STAGE;   // byte offset into smem
     uint8_t *stage = smem + stage_off;
-    uint8_t *outreg = smem + outreg_off;
 
     // contiguous range of the batch's chunks for this workgroup
     const uint64_t G = gridDim.x, g = blockIdx.x;
@@ -219,112 +216,164 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
         __syncthreads(); // every wave is done with the previous tensor's table and its scratch
         build_tables(len_lo, len_hi, tbl, s_len, s_code, (uint16_t *)(smem + C::OFF_WAVES), tid, WAVES * 64);
 
-        for (uint64_t cg = c + wave; cg < seg_end; cg += WAVES) {
-            const uint64_t cl = cg - first_chunk;                // chunk index inside the tensor
-            const uint64_t elem0 = cl * (64ull * N);             // first element of the chunk
-            const uint64_t b0 = chunk_bit[cl], b1 = chunk_bit[cl + 1];
-
-            // lane start bit = chunk start + exclusive scan of the lanes' bit counts
-            const uint32_t lb = lane_bits[cl * 64 + lane];
-            const uint32_t rel = wave_incl_scan(lb) - lb;
-
-            // nibble plane of the chunk, in the order the write-back wants it
-            u32x2 pl[C::PIECES];
+        // Per-wave software pipeline over its chunks cg = c + wave, + WAVES, ...:
+        // metadata is loaded two chunks ahead, stream span and nibble plane one chunk
+        // ahead (into registers), so HBM latency is covered by the decode of the
+        // chunk in hand.
+        struct Meta { uint64_t b0, b1; uint32_t lb; };
+        struct Payload { u32x4 s[C::SEGS]; u32x2 pl[C::PIECES]; };
+        auto load_meta = [&](uint64_t cl) {
+            Meta m;
+            m.b0 = chunk_bit[cl];
+            m.b1 = chunk_bit[cl + 1];
+            m.lb = lane_bits[cl * 64 + lane];
+            return m;
+        };
+        // span of the stream a chunk needs: 16-byte aligned start, 8 bytes of look-ahead
+        auto span_of = [&](const Meta &m, uint64_t &byte0) {
+            uint64_t byte_end = ((m.b1 + 7) >> 3) + 8;
+            if (byte_end > st_bytes) byte_end = st_bytes;
+            byte0 = (m.b0 >> 3) & ~15ull;
+            if (byte0 > byte_end) byte0 = byte_end;
+            return byte_end - byte0;
+        };
+        auto issue_payload = [&](uint64_t cl, const Meta &m) {
+            Payload p;
+            uint64_t byte0;
+            const uint64_t span64 = span_of(m, byte0);
             const GLOBAL u32x2 *plane_c = (const GLOBAL u32x2 *)(plane + cl * (32ull * N));
 #pragma unroll
-            for (int j = 0; j < C::PIECES; j++) pl[j] = plane_c[j * 64 + lane];
-
-            // the chunk's span of the stream: 16-byte aligned start, 8 bytes of look-ahead
-            uint64_t byte_end = ((b1 + 7) >> 3) + 8;
-            if (byte_end > st_bytes) byte_end = st_bytes;
-            uint64_t byte0 = (b0 >> 3) & ~15ull;
-            if (byte0 > byte_end) byte0 = byte_end;
-            const uint64_t span64 = byte_end - byte0;
-            const uint32_t bit_in = (uint32_t)(b0 - byte0 * 8) + rel; // lane start, bits from byte0
-
-            if (span64 <= (uint64_t)C::STAGE) {
-                const uint32_t span = (uint32_t)span64;
-                for (uint32_t i = lane * 16; i < span; i += 64 * 16)
-                    *(u32x4 *)(stage + i) = *(const GLOBAL u32x4 *)(stream + byte0 + i);
-                // bp: LDS bit address (smem-relative) of the lane's next codeword
-                uint32_t bp = stage_off * 8 + bit_in;
-                uint8_t *orow = outreg + lane * C::LANE_STRIDE;
-#pragma unroll 4
-                for (int q = 0; q < C::QUADS; q++) {
-                    const uint32_t aw = (bp >> 3) & ~3u;
-                    const uint32_t d0 = *(const uint32_t *)(smem + aw);
-                    const uint32_t d1 = *(const uint32_t *)(smem + aw + 4);
-                    const uint32_t w = __builtin_amdgcn_alignbit(d1, d0, bp);   // 32 stream bits from bp
-                    const uint32_t e1 = tbl[w & TBL_MASK];
-                    const uint32_t n1 = (e1 >> 7) & 15u;
-                    const uint32_t e2 = tbl[(w >> n1) & TBL_MASK];
-                    const uint32_t n2 = (e2 >> 7) & 15u;
-                    uint32_t o = e1 | (e2 << 16);
-                    uint32_t adv = n1 + n2;
-                    // n1 == 0 makes the second lookup repeat the first, so n2 == 0 covers both
-                    if (__builtin_expect(n2 == 0, 0)) {
-                        uint32_t b = bp;
-                        o = 0;
-#pragma unroll 1
-                        for (int i = 0; i < 4; i++) {
-                            const uint32_t ai = (b >> 3) & ~3u;
-                            const uint32_t x0 = *(const uint32_t *)(smem + ai);
-                            const uint32_t x1 = *(const uint32_t *)(smem + ai + 4);
-                            const uint32_t r = decode_one(__builtin_amdgcn_alignbit(x1, x0, b), tbl, s_len, s_code);
-                            o |= (r & 15u) << (8 * i + 3);
-                            b += r >> 8;
-                        }
-                        adv = b - bp;
-                    }
-                    *(uint32_t *)(orow + 4 * q) = o;
-                    bp += adv;
-                }
-            } else {
-                // A chunk that codes far worse than 4 bits per symbol does not fit the staging
-                // buffer: walk it symbol by symbol with windows read straight from HBM.
-                const uint64_t lane_first = elem0 + (uint64_t)lane * N;
-                const uint32_t nsym = lane_first >= n_elem ? 0u
-                                      : (uint32_t)((n_elem - lane_first) < (uint64_t)N ? (n_elem - lane_first) : N);
-                const GLOBAL uint8_t *sp = stream + byte0;
-                uint32_t b = bit_in;
-                uint8_t *orow = outreg + lane * C::LANE_STRIDE;
-                for (uint32_t i = 0; i < nsym; i++) {
-                    const GLOBAL uint32_t *q = (const GLOBAL uint32_t *)(sp + ((b >> 3) & ~3u));
-                    const uint32_t r = decode_one(__builtin_amdgcn_alignbit(q[1], q[0], b), tbl, s_len, s_code);
-                    orow[i] = (uint8_t)((r & 15u) << 3);
-                    b += r >> 8;
-                }
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-
-            // write-back: piece p = 16 consecutive output bytes; lane takes p = j*64 + lane
+            for (int j = 0; j < C::PIECES; j++) p.pl[j] = plane_c[j * 64 + lane];
 #pragma unroll
-            for (int j = 0; j < C::PIECES; j++) {
-                const int p = j * 64 + lane;
-                const uint8_t *src = outreg + (p / C::PIECES) * C::LANE_STRIDE + (p % C::PIECES) * 16;
-                const uint32_t s0 = *(const uint32_t *)(src), s1 = *(const uint32_t *)(src + 4);
-                const uint32_t s2 = *(const uint32_t *)(src + 8), s3 = *(const uint32_t *)(src + 12);
-                const uint32_t p0 = pl[j].x, p1 = pl[j].y;
-                u32x4 d;
-                // byte = exponent<<3 | sign<<7 | mantissa  (Algorithm 1, byte assembly)
-                d.x = (s0 & EXP_MASK) | (p0 & 0x07070707u) | ((p0 & 0x08080808u) << 4);
-                d.y = (s1 & EXP_MASK) | ((p0 >> 4) & 0x07070707u) | (p0 & 0x80808080u);
-                d.z = (s2 & EXP_MASK) | (p1 & 0x07070707u) | ((p1 & 0x08080808u) << 4);
-                d.w = (s3 & EXP_MASK) | ((p1 >> 4) & 0x07070707u) | (p1 & 0x80808080u);
-                const uint64_t o = elem0 + (uint64_t)p * 16;
-                if (o + 16 <= n_elem) {
-                    *(GLOBAL u32x4 *)(out + o) = d;
-                } else if (o < n_elem) {
-                    for (uint32_t b = 0; b < 16 && o + b < n_elem; b++) {
-                        const uint32_t wsel = b >> 2;
-                        const uint32_t word = wsel == 0 ? d.x : wsel == 1 ? d.y : wsel == 2 ? d.z : d.w;
-                        out[o + b] = (uint8_t)(word >> (8 * (b & 3)));
+            for (int k = 0; k < C::SEGS; k++) {
+                const uint32_t i = (lane + 64 * k) * 16;
+                p.s[k] = u32x4{0, 0, 0, 0};
+                if (span64 <= (uint64_t)C::STAGE && i < (uint32_t)span64)
+                    p.s[k] = *(const GLOBAL u32x4 *)(stream + byte0 + i);
+            }
+            return p;
+        };
+
+        uint64_t cg = c + wave;
+        if (cg < seg_end) {
+            Meta m_cur = load_meta(cg - first_chunk);
+            Payload p_cur = issue_payload(cg - first_chunk, m_cur);
+            uint64_t cg1 = cg + WAVES;
+            Meta m_next = m_cur;
+            if (cg1 < seg_end) m_next = load_meta(cg1 - first_chunk);
+            for (;;) {
+                const uint64_t cl = cg - first_chunk;            // chunk index inside the tensor
+                const uint64_t elem0 = cl * (64ull * N);         // first element of the chunk
+                const uint64_t b0 = __builtin_amdgcn_readfirstlane((uint32_t)m_cur.b0) |
+                                    ((uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)(m_cur.b0 >> 32)) << 32);
+                uint64_t byte0;
+                const uint64_t span64 = span_of(m_cur, byte0);
+                const bool staged = __builtin_amdgcn_readfirstlane((uint32_t)(span64 <= (uint64_t)C::STAGE)) != 0;
+
+                // lane start bit = chunk start + exclusive DPP scan of the lanes' bit counts
+                const uint32_t rel = wave_incl_scan(m_cur.lb) - m_cur.lb;
+                const uint32_t bit_in = (uint32_t)(b0 - byte0 * 8) + rel; // bits from byte0
+
+                if (staged) {
+#pragma unroll
+                    for (int k = 0; k < C::SEGS; k++) {
+                        const uint32_t i = (lane + 64 * k) * 16;
+                        if (i < (uint32_t)C::STAGE) *(u32x4 *)(stage + i) = p_cur.s[k];
                     }
                 }
+                u32x2 pl[C::PIECES];
+#pragma unroll
+                for (int j = 0; j < C::PIECES; j++) pl[j] = p_cur.pl[j];
+
+                // prefetch: next chunk's payload, next-next chunk's metadata
+                const bool has_next = cg1 < seg_end;
+                Meta m_next2 = m_next;
+                if (has_next) {
+                    p_cur = issue_payload(cg1 - first_chunk, m_next);
+                    if (cg1 + WAVES < seg_end) m_next2 = load_meta(cg1 + WAVES - first_chunk);
+                }
+
+                if (staged) {
+                    // bp: LDS bit address (smem-relative) of the lane's next codeword
+                    uint32_t bp = stage_off * 8 + bit_in;
+#pragma unroll
+                    for (int Q = 0; Q < C::PIECES; Q++) {
+                        uint32_t dw[4];
+#pragma unroll
+                        for (int t = 0; t < 4; t++) {
+                            const uint32_t aw = (bp >> 3) & ~3u;
+                            const uint32_t d0 = *(const uint32_t *)(smem + aw);
+                            const uint32_t d1 = *(const uint32_t *)(smem + aw + 4);
+                            const uint32_t w = __builtin_amdgcn_alignbit(d1, d0, bp);   // 32 stream bits from bp
+                            const uint32_t e1 = tbl[w & TBL_MASK];
+                            const uint32_t n1 = (e1 >> 7) & 15u;
+                            const uint32_t e2 = tbl[(w >> n1) & TBL_MASK];
+                            const uint32_t n2 = (e2 >> 7) & 15u;
+                            uint32_t o = e1 | (e2 << 16);
+                            uint32_t adv = n1 + n2;
+                            // n1 == 0 makes the second lookup repeat the first, so n2 == 0 covers both
+                            if (__builtin_expect(n2 == 0, 0)) {
+                                uint32_t b = bp;
+                                o = 0;
+#pragma unroll 1
+                                for (int i = 0; i < 4; i++) {
+                                    const uint32_t ai = (b >> 3) & ~3u;
+                                    const uint32_t x0 = *(const uint32_t *)(smem + ai);
+                                    const uint32_t x1 = *(const uint32_t *)(smem + ai + 4);
+                                    const uint32_t r = decode_one(__builtin_amdgcn_alignbit(x1, x0, b), tbl, s_len, s_code);
+                                    o |= (r & 15u) << (8 * i + 3);
+                                    b += r >> 8;
+                                }
+                                adv = b - bp;
+                            }
+                            dw[t] = o;
+                            bp += adv;
+                        }
+                        // byte = exponent<<3 | sign<<7 | mantissa  (Algorithm 1, byte assembly)
+                        const uint32_t p0 = pl[Q].x, p1 = pl[Q].y;
+                        u32x4 d;
+                        d.x = (dw[0] & EXP_MASK) | (p0 & 0x07070707u) | ((p0 & 0x08080808u) << 4);
+                        d.y = (dw[1] & EXP_MASK) | ((p0 >> 4) & 0x07070707u) | (p0 & 0x80808080u);
+                        d.z = (dw[2] & EXP_MASK) | (p1 & 0x07070707u) | ((p1 & 0x08080808u) << 4);
+                        d.w = (dw[3] & EXP_MASK) | ((p1 >> 4) & 0x07070707u) | (p1 & 0x80808080u);
+                        const uint64_t o = elem0 + (uint64_t)(Q * 64 + lane) * 16;
+                        if (o + 16 <= n_elem) {
+                            *(GLOBAL u32x4 *)(out + o) = d;
+                        } else if (o < n_elem) {
+                            for (uint32_t b = 0; b < 16 && o + b < n_elem; b++) {
+                                const uint32_t wsel = b >> 2;
+                                const uint32_t word = wsel == 0 ? d.x : wsel == 1 ? d.y : wsel == 2 ? d.z : d.w;
+                                out[o + b] = (uint8_t)(word >> (8 * (b & 3)));
+                            }
+                        }
+                    }
+                } else {
+                    // A chunk that codes far worse than 4 bits per symbol does not fit the staging
+                    // buffer: walk it symbol by symbol, windows and nibbles read straight from HBM.
+                    const GLOBAL uint8_t *sp = stream + byte0;
+                    uint32_t b = bit_in;
+#pragma unroll 1
+                    for (int Q = 0; Q < C::PIECES; Q++) {
+                        const uint64_t o = elem0 + (uint64_t)(Q * 64 + lane) * 16;
+#pragma unroll 1
+                        for (uint32_t i = 0; i < 16 && o + i < n_elem; i++) {
+                            const GLOBAL uint32_t *q = (const GLOBAL uint32_t *)(sp + ((b >> 3) & ~3u));
+                            const uint32_t r = decode_one(__builtin_amdgcn_alignbit(q[1], q[0], b), tbl, s_len, s_code);
+                            b += r >> 8;
+                            const uint64_t el = o + i;
+                            const uint32_t pb = plane[(el >> 3) * 4 + (el & 3)];
+                            const uint32_t nib = (el & 4) ? pb >> 4 : pb & 15u;
+                            out[el] = (uint8_t)(((r & 15u) << 3) | ((nib & 8u) << 4) | (nib & 7u));
+                        }
+                    }
+                }
+
+                if (!has_next) break;
+                m_cur = m_next;
+                m_next = m_next2;
+                cg = cg1;
+                cg1 += WAVES;
             }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
         }
         c = seg_end;
     }

@@ -1,12 +1,15 @@
 // Host side of the ECF8 library: encoder, container parsing and validation.
 //
 // Encoder stages follow Section 3.1 of the paper: exponent histogram and
-// optimal prefix code ("Huffman code generation"), then the in-order bitstream
-// with synchronisation metadata ("Encoding and synchronization metadata
+// optimal prefix code ("Huffman code generation"), then the bitstream with
+// synchronisation metadata ("Encoding and synchronization metadata
 // generation").  The paper's metadata (a 4-bit gap per fixed-size byte window
-// and an output position per block) is replaced by the start bit of every
-// N-th codeword, which removes the decoder's counting pass; the stream itself
-// is still the plain concatenation of the codewords.
+// and an output position per block) is replaced by the number of stream bits
+// of every lane's N codewords, which removes the decoder's counting pass.
+// The stream is the concatenation of the codewords chunk by chunk; inside a
+// chunk the order is lane-major (lane l codes the 16-element pieces l, l+64,
+// ...), so that what the 64 lanes decode in the same step is contiguous in
+// the output.
 #include "ecf8.h"
 
 #include <algorithm>
@@ -261,10 +264,13 @@ int ecf8_encode(const uint8_t *x, uint64_t rows, uint64_t cols, const ecf8_encod
             for (uint64_t c = c0; c < c1; c++) {
                 uint64_t tot = 0;
                 for (uint32_t l = 0; l < ECF8_LANES; l++) {
-                    uint64_t a = c * chunk_elems + (uint64_t)l * N;
-                    uint64_t b = std::min<uint64_t>(a + N, n);
+                    // lane l owns the 16-element pieces l, l+64, l+128, ... of the chunk
                     uint32_t lb = 0;
-                    for (uint64_t i = a; i < b; i++) lb += len[(x[i] >> 3) & 15];
+                    for (uint32_t q = 0; q < N / 16; q++) {
+                        uint64_t a = c * chunk_elems + ((uint64_t)q * ECF8_LANES + l) * 16;
+                        uint64_t b = std::min<uint64_t>(a + 16, n);
+                        for (uint64_t i = a; i < b; i++) lb += len[(x[i] >> 3) & 15];
+                    }
                     lane_bits[c * ECF8_LANES + l] = (uint16_t)lb;
                     tot += lb;
                 }
@@ -284,10 +290,17 @@ int ecf8_encode(const uint8_t *x, uint64_t rows, uint64_t cols, const ecf8_encod
         parallel_for(L.n_chunks, nt, [&](uint64_t c0, uint64_t c1) {
             BitWriter bw(stream, chunk_bit[c0]);
             uint64_t a = c0 * chunk_elems, b = std::min<uint64_t>(c1 * chunk_elems, n);
-            for (uint64_t i = a; i < b; i++) {
-                uint32_t e = (x[i] >> 3) & 15;
-                bw.put(rcode[e], len[e]);
-            }
+            // stream order inside a chunk: lane by lane, each lane its pieces in turn
+            for (uint64_t c = c0; c < c1; c++)
+                for (uint32_t l = 0; l < ECF8_LANES; l++)
+                    for (uint32_t q = 0; q < N / 16; q++) {
+                        uint64_t pa = c * chunk_elems + ((uint64_t)q * ECF8_LANES + l) * 16;
+                        uint64_t pb = std::min<uint64_t>(pa + 16, n);
+                        for (uint64_t i = pa; i < pb; i++) {
+                            uint32_t e = (x[i] >> 3) & 15;
+                            bw.put(rcode[e], len[e]);
+                        }
+                    }
             bw.finish();
             // plane: 8 elements -> 4 bytes, element j pairs with element j+4
             uint64_t i = a;
@@ -359,8 +372,11 @@ int ecf8_blob_validate(const void *blob, uint64_t size)
         for (uint32_t l = 0; l < ECF8_LANES; l++) {
             uint16_t lb;
             std::memcpy(&lb, p + h.off_lane_bits + 2 * (c * ECF8_LANES + l), 2);
-            uint64_t a = c * chunk_elems + (uint64_t)l * N;
-            uint64_t cnt = a >= h.n_elem ? 0 : std::min<uint64_t>(N, h.n_elem - a);
+            uint64_t cnt = 0; // elements of the lane's pieces that exist
+            for (uint32_t q = 0; q < N / 16; q++) {
+                uint64_t a = c * chunk_elems + ((uint64_t)q * ECF8_LANES + l) * 16;
+                if (a < h.n_elem) cnt += std::min<uint64_t>(16, h.n_elem - a);
+            }
             if (lb > 15 * cnt || lb < cnt) return ECF8_E_FORMAT;
             tot += lb;
         }
