@@ -99,6 +99,20 @@ __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x)
     return v;
 }
 
+// A codeword longer than TB bits (rarer than 2^-TB): match the next 15 stream
+// bits against the long canonical codes.  Returns exponent | length << 8.
+__device__ __noinline__ uint32_t decode_long(uint32_t bits, const uint32_t *s_len, const uint32_t *s_code)
+{
+    uint32_t v = __brev(bits) >> 17;          // next 15 bits, first bit most significant
+    uint32_t r = 15u << 8;                    // no match (corrupt stream): skip 15 bits, exponent 0
+#pragma unroll 1
+    for (int s = 0; s < 16; s++) {
+        uint32_t ls = s_len[s];
+        if (ls > TB && (v >> (15 - ls)) == s_code[s]) r = (uint32_t)s | (ls << 8);
+    }
+    return r;
+}
+
 // One symbol the careful way.  `bits`: stream bits from the current position
 // (>= 15 valid).  Returns exponent | length << 8.
 __device__ __forceinline__ uint32_t decode_one(uint32_t bits, const uint16_t *tbl, const uint32_t *s_len,
@@ -106,15 +120,22 @@ __device__ __forceinline__ uint32_t decode_one(uint32_t bits, const uint16_t *tb
 {
     uint32_t e = tbl[bits & TBL_MASK];
     uint32_t l = (e & 7u) | ((e >> 12) & 8u);
-    if (l) return ((e >> 3) & 15u) | (l << 8);
-    // longer than TB bits: match against the long canonical codes
-    uint32_t v = __brev(bits) >> 17;          // next 15 bits, first bit most significant
-    uint32_t r = 15u << 8;                    // no match (corrupt stream): skip 15 bits, exponent 0
-    for (int s = 0; s < 16; s++) {
-        uint32_t ls = s_len[s];
-        if (ls > TB && (v >> (15 - ls)) == s_code[s]) r = (uint32_t)s | (ls << 8);
-    }
-    return r;
+    if (__builtin_expect(l != 0, 1)) return ((e >> 3) & 15u) | (l << 8);
+    return decode_long(bits, s_len, s_code);
+}
+
+// Second level for one pair: the table entry `e` at the bottom of `bits` (32
+// valid stream bits) has no pair (the two codewords need more than TB bits, or
+// the first one alone does).  Decodes the two symbols one at a time and returns
+// them in `e` in pair-entry layout, their total length (up to 30) in `n`.
+__device__ __forceinline__ void pair_second_level(uint32_t bits, uint32_t &e, uint32_t &n, const uint16_t *tbl,
+                                                  const uint32_t *s_len, const uint32_t *s_code)
+{
+    const uint32_t r1 = decode_one(bits, tbl, s_len, s_code);
+    const uint32_t l1 = r1 >> 8;
+    const uint32_t r2 = decode_one(bits >> l1, tbl, s_len, s_code);
+    e = ((r1 & 15u) << 3) | ((r2 & 15u) << 11);
+    n = l1 + (r2 >> 8);
 }
 
 // Builds the pair table and the per-symbol (length, code) arrays in LDS from
@@ -305,29 +326,25 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
                             const uint32_t d0 = *(const uint32_t *)(smem + aw);
                             const uint32_t d1 = *(const uint32_t *)(smem + aw + 4);
                             const uint32_t w = __builtin_amdgcn_alignbit(d1, d0, bp);   // 32 stream bits from bp
-                            const uint32_t e1 = tbl[w & TBL_MASK];
-                            const uint32_t n1 = (e1 >> 7) & 15u;
-                            const uint32_t e2 = tbl[(w >> n1) & TBL_MASK];
-                            const uint32_t n2 = (e2 >> 7) & 15u;
-                            uint32_t o = e1 | (e2 << 16);
-                            uint32_t adv = n1 + n2;
-                            // n1 == 0 makes the second lookup repeat the first, so n2 == 0 covers both
-                            if (__builtin_expect(n2 == 0, 0)) {
-                                uint32_t b = bp;
-                                o = 0;
-#pragma unroll 1
-                                for (int i = 0; i < 4; i++) {
-                                    const uint32_t ai = (b >> 3) & ~3u;
-                                    const uint32_t x0 = *(const uint32_t *)(smem + ai);
-                                    const uint32_t x1 = *(const uint32_t *)(smem + ai + 4);
-                                    const uint32_t r = decode_one(__builtin_amdgcn_alignbit(x1, x0, b), tbl, s_len, s_code);
-                                    o |= (r & 15u) << (8 * i + 3);
-                                    b += r >> 8;
-                                }
-                                adv = b - bp;
+                            uint32_t e1 = tbl[w & TBL_MASK];
+                            uint32_t n1 = (e1 >> 7) & 15u;
+                            if (__builtin_expect(n1 == 0, 0)) pair_second_level(w, e1, n1, tbl, s_len, s_code);
+                            uint32_t w2 = w >> n1;                               // >= 18 valid bits unless n1 > 14
+                            uint32_t e2 = tbl[w2 & TBL_MASK];
+                            uint32_t n2 = (e2 >> 7) & 15u;
+                            if (__builtin_expect(n1 > 14 || n2 == 0, 0)) {
+                                // second level needs up to 30 bits: take a fresh window at bp + n1
+                                const uint32_t b2 = bp + n1;
+                                const uint32_t a2 = (b2 >> 3) & ~3u;
+                                const uint32_t y0 = *(const uint32_t *)(smem + a2);
+                                const uint32_t y1 = *(const uint32_t *)(smem + a2 + 4);
+                                w2 = __builtin_amdgcn_alignbit(y1, y0, b2);
+                                e2 = tbl[w2 & TBL_MASK];
+                                n2 = (e2 >> 7) & 15u;
+                                if (n2 == 0) pair_second_level(w2, e2, n2, tbl, s_len, s_code);
                             }
-                            dw[t] = o;
-                            bp += adv;
+                            dw[t] = (e1 & 0xffffu) | (e2 << 16);
+                            bp += n1 + n2;
                         }
                         // byte = exponent<<3 | sign<<7 | mantissa  (Algorithm 1, byte assembly)
                         const uint32_t p0 = pl[Q].x, p1 = pl[Q].y;
