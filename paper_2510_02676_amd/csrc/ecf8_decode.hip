@@ -275,13 +275,26 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
             return p;
         };
 
+        // The pipelined loop takes only chunks that are entirely inside the tensor, so its
+        // stores are unconditional: between the issue of a prefetch and its use every path
+        // holds the same stores, and the wait for the prefetch never drains them.  A chunk
+        // whose span does not fit the stage is decoded from stale LDS there (harmless garbage,
+        // in bounds) and redone by the generic pass below, as is a ragged last chunk.
+        const bool ragged_tail = (n_elem % (64ull * N)) != 0;
+        const uint64_t fast_end = (ragged_tail && seg_end == t_end) ? seg_end - 1 : seg_end;
+        bool any_oversize = false;
+
         uint64_t cg = c + wave;
-        if (cg < seg_end) {
+        if (cg < fast_end) {
             Meta m_cur = load_meta(cg - first_chunk);
             Payload p_cur = issue_payload(cg - first_chunk, m_cur);
             uint64_t cg1 = cg + WAVES;
             Meta m_next = m_cur;
-            if (cg1 < seg_end) m_next = load_meta(cg1 - first_chunk);
+            if (cg1 < fast_end) m_next = load_meta(cg1 - first_chunk);
+            // Drain the prologue's loads here (vmcnt(0), other counters untouched), so that
+            // the wait at the loop head is decided by the back edge alone, where the four
+            // stores of the previous chunk are younger than the prefetch and stay in flight.
+            __builtin_amdgcn_s_waitcnt(0x0F70);
             for (;;) {
                 const uint64_t cl = cg - first_chunk;            // chunk index inside the tensor
                 const uint64_t elem0 = cl * (64ull * N);         // first element of the chunk
@@ -290,99 +303,68 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
                 uint64_t byte0;
                 const uint64_t span64 = span_of(m_cur, byte0);
                 const bool staged = __builtin_amdgcn_readfirstlane((uint32_t)(span64 <= (uint64_t)C::STAGE)) != 0;
+                any_oversize |= !staged;
 
                 // lane start bit = chunk start + exclusive DPP scan of the lanes' bit counts
                 const uint32_t rel = wave_incl_scan(m_cur.lb) - m_cur.lb;
                 const uint32_t bit_in = (uint32_t)(b0 - byte0 * 8) + rel; // bits from byte0
 
-                if (staged) {
 #pragma unroll
-                    for (int k = 0; k < C::SEGS; k++) {
-                        const uint32_t i = (lane + 64 * k) * 16;
-                        if (i < (uint32_t)C::STAGE) *(u32x4 *)(stage + i) = p_cur.s[k];
-                    }
+                for (int k = 0; k < C::SEGS; k++) {
+                    const uint32_t i = (lane + 64 * k) * 16;
+                    if (i < (uint32_t)C::STAGE) *(u32x4 *)(stage + i) = p_cur.s[k];
                 }
                 u32x2 pl[C::PIECES];
 #pragma unroll
                 for (int j = 0; j < C::PIECES; j++) pl[j] = p_cur.pl[j];
 
                 // prefetch: next chunk's payload, next-next chunk's metadata
-                const bool has_next = cg1 < seg_end;
+                const bool has_next = cg1 < fast_end;
                 Meta m_next2 = m_next;
                 if (has_next) {
                     p_cur = issue_payload(cg1 - first_chunk, m_next);
-                    if (cg1 + WAVES < seg_end) m_next2 = load_meta(cg1 + WAVES - first_chunk);
+                    if (cg1 + WAVES < fast_end) m_next2 = load_meta(cg1 + WAVES - first_chunk);
                 }
 
-                if (staged) {
-                    // bp: LDS bit address (smem-relative) of the lane's next codeword
-                    uint32_t bp = stage_off * 8 + bit_in;
+                // bp: LDS bit address (smem-relative) of the lane's next codeword
+                uint32_t bp = stage_off * 8 + bit_in;   // oversize chunk: may point past LDS, reads return 0
 #pragma unroll
-                    for (int Q = 0; Q < C::PIECES; Q++) {
-                        uint32_t dw[4];
+                for (int Q = 0; Q < C::PIECES; Q++) {
+                    uint32_t dw[4];
 #pragma unroll
-                        for (int t = 0; t < 4; t++) {
-                            const uint32_t aw = (bp >> 3) & ~3u;
-                            const uint32_t d0 = *(const uint32_t *)(smem + aw);
-                            const uint32_t d1 = *(const uint32_t *)(smem + aw + 4);
-                            const uint32_t w = __builtin_amdgcn_alignbit(d1, d0, bp);   // 32 stream bits from bp
-                            uint32_t e1 = tbl[w & TBL_MASK];
-                            uint32_t n1 = (e1 >> 7) & 15u;
-                            if (__builtin_expect(n1 == 0, 0)) pair_second_level(w, e1, n1, tbl, s_len, s_code);
-                            uint32_t w2 = w >> n1;                               // >= 18 valid bits unless n1 > 14
-                            uint32_t e2 = tbl[w2 & TBL_MASK];
-                            uint32_t n2 = (e2 >> 7) & 15u;
-                            if (__builtin_expect(n1 > 14 || n2 == 0, 0)) {
-                                // second level needs up to 30 bits: take a fresh window at bp + n1
-                                const uint32_t b2 = bp + n1;
-                                const uint32_t a2 = (b2 >> 3) & ~3u;
-                                const uint32_t y0 = *(const uint32_t *)(smem + a2);
-                                const uint32_t y1 = *(const uint32_t *)(smem + a2 + 4);
-                                w2 = __builtin_amdgcn_alignbit(y1, y0, b2);
-                                e2 = tbl[w2 & TBL_MASK];
-                                n2 = (e2 >> 7) & 15u;
-                                if (n2 == 0) pair_second_level(w2, e2, n2, tbl, s_len, s_code);
-                            }
-                            dw[t] = (e1 & 0xffffu) | (e2 << 16);
-                            bp += n1 + n2;
+                    for (int t = 0; t < 4; t++) {
+                        const uint32_t aw = (bp >> 3) & ~3u;
+                        const uint32_t d0 = *(const uint32_t *)(smem + aw);
+                        const uint32_t d1 = *(const uint32_t *)(smem + aw + 4);
+                        const uint32_t w = __builtin_amdgcn_alignbit(d1, d0, bp);   // 32 stream bits from bp
+                        uint32_t e1 = tbl[w & TBL_MASK];
+                        uint32_t n1 = (e1 >> 7) & 15u;
+                        if (__builtin_expect(n1 == 0, 0)) pair_second_level(w, e1, n1, tbl, s_len, s_code);
+                        uint32_t w2 = w >> n1;                               // >= 18 valid bits unless n1 > 14
+                        uint32_t e2 = tbl[w2 & TBL_MASK];
+                        uint32_t n2 = (e2 >> 7) & 15u;
+                        if (__builtin_expect(n1 > 14 || n2 == 0, 0)) {
+                            // second level needs up to 30 bits: take a fresh window at bp + n1
+                            const uint32_t b2 = bp + n1;
+                            const uint32_t a2 = (b2 >> 3) & ~3u;
+                            const uint32_t y0 = *(const uint32_t *)(smem + a2);
+                            const uint32_t y1 = *(const uint32_t *)(smem + a2 + 4);
+                            w2 = __builtin_amdgcn_alignbit(y1, y0, b2);
+                            e2 = tbl[w2 & TBL_MASK];
+                            n2 = (e2 >> 7) & 15u;
+                            if (n2 == 0) pair_second_level(w2, e2, n2, tbl, s_len, s_code);
                         }
-                        // byte = exponent<<3 | sign<<7 | mantissa  (Algorithm 1, byte assembly)
-                        const uint32_t p0 = pl[Q].x, p1 = pl[Q].y;
-                        u32x4 d;
-                        d.x = (dw[0] & EXP_MASK) | (p0 & 0x07070707u) | ((p0 & 0x08080808u) << 4);
-                        d.y = (dw[1] & EXP_MASK) | ((p0 >> 4) & 0x07070707u) | (p0 & 0x80808080u);
-                        d.z = (dw[2] & EXP_MASK) | (p1 & 0x07070707u) | ((p1 & 0x08080808u) << 4);
-                        d.w = (dw[3] & EXP_MASK) | ((p1 >> 4) & 0x07070707u) | (p1 & 0x80808080u);
-                        const uint64_t o = elem0 + (uint64_t)(Q * 64 + lane) * 16;
-                        if (o + 16 <= n_elem) {
-                            *(GLOBAL u32x4 *)(out + o) = d;
-                        } else if (o < n_elem) {
-                            for (uint32_t b = 0; b < 16 && o + b < n_elem; b++) {
-                                const uint32_t wsel = b >> 2;
-                                const uint32_t word = wsel == 0 ? d.x : wsel == 1 ? d.y : wsel == 2 ? d.z : d.w;
-                                out[o + b] = (uint8_t)(word >> (8 * (b & 3)));
-                            }
-                        }
+                        dw[t] = (e1 & 0xffffu) | (e2 << 16);
+                        bp += n1 + n2;
                     }
-                } else {
-                    // A chunk that codes far worse than 4 bits per symbol does not fit the staging
-                    // buffer: walk it symbol by symbol, windows and nibbles read straight from HBM.
-                    const GLOBAL uint8_t *sp = stream + byte0;
-                    uint32_t b = bit_in;
-#pragma unroll 1
-                    for (int Q = 0; Q < C::PIECES; Q++) {
-                        const uint64_t o = elem0 + (uint64_t)(Q * 64 + lane) * 16;
-#pragma unroll 1
-                        for (uint32_t i = 0; i < 16 && o + i < n_elem; i++) {
-                            const GLOBAL uint32_t *q = (const GLOBAL uint32_t *)(sp + ((b >> 3) & ~3u));
-                            const uint32_t r = decode_one(__builtin_amdgcn_alignbit(q[1], q[0], b), tbl, s_len, s_code);
-                            b += r >> 8;
-                            const uint64_t el = o + i;
-                            const uint32_t pb = plane[(el >> 3) * 4 + (el & 3)];
-                            const uint32_t nib = (el & 4) ? pb >> 4 : pb & 15u;
-                            out[el] = (uint8_t)(((r & 15u) << 3) | ((nib & 8u) << 4) | (nib & 7u));
-                        }
-                    }
+                    // byte = exponent<<3 | sign<<7 | mantissa  (Algorithm 1, byte assembly)
+                    const uint32_t p0 = pl[Q].x, p1 = pl[Q].y;
+                    u32x4 d;
+                    d.x = (dw[0] & EXP_MASK) | (p0 & 0x07070707u) | ((p0 & 0x08080808u) << 4);
+                    d.y = (dw[1] & EXP_MASK) | ((p0 >> 4) & 0x07070707u) | (p0 & 0x80808080u);
+                    d.z = (dw[2] & EXP_MASK) | (p1 & 0x07070707u) | ((p1 & 0x08080808u) << 4);
+                    d.w = (dw[3] & EXP_MASK) | ((p1 >> 4) & 0x07070707u) | (p1 & 0x80808080u);
+                    *(GLOBAL u32x4 *)(out + elem0 + (uint64_t)(Q * 64 + lane) * 16) = d;
                 }
 
                 if (!has_next) break;
@@ -390,6 +372,39 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
                 m_next = m_next2;
                 cg = cg1;
                 cg1 += WAVES;
+            }
+        }
+
+        // Generic pass, symbol by symbol with windows and nibbles read straight from HBM:
+        // the ragged last chunk of the tensor, and chunks that code so much worse than 4 bits
+        // per symbol that their span did not fit the stage.
+        if (__builtin_amdgcn_readfirstlane((uint32_t)any_oversize) || fast_end != seg_end) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");   // the loop's stores land first
+            for (uint64_t cg2 = c + wave; cg2 < seg_end; cg2 += WAVES) {
+                const uint64_t cl = cg2 - first_chunk;
+                Meta m = load_meta(cl);
+                uint64_t byte0;
+                const uint64_t span64 = span_of(m, byte0);
+                const bool redo = cg2 >= fast_end || span64 > (uint64_t)C::STAGE;
+                if (!__builtin_amdgcn_readfirstlane((uint32_t)redo)) continue;
+                const uint64_t elem0 = cl * (64ull * N);
+                const uint32_t rel = wave_incl_scan(m.lb) - m.lb;
+                const GLOBAL uint8_t *sp = stream + byte0;
+                uint32_t b = (uint32_t)(m.b0 - byte0 * 8) + rel;
+#pragma unroll 1
+                for (int Q = 0; Q < C::PIECES; Q++) {
+                    const uint64_t o = elem0 + (uint64_t)(Q * 64 + lane) * 16;
+#pragma unroll 1
+                    for (uint32_t i = 0; i < 16 && o + i < n_elem; i++) {
+                        const GLOBAL uint32_t *q = (const GLOBAL uint32_t *)(sp + ((b >> 3) & ~3u));
+                        const uint32_t r = decode_one(__builtin_amdgcn_alignbit(q[1], q[0], b), tbl, s_len, s_code);
+                        b += r >> 8;
+                        const uint64_t el = o + i;
+                        const uint32_t pb = plane[(el >> 3) * 4 + (el & 3)];
+                        const uint32_t nib = (el & 4) ? pb >> 4 : pb & 15u;
+                        out[el] = (uint8_t)(((r & 15u) << 3) | ((nib & 8u) << 4) | (nib & 7u));
+                    }
+                }
             }
         }
         c = seg_end;
