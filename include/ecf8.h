@@ -30,15 +30,19 @@
  *   lane_bits : u16[n_chunks*64] code bits of lane l of chunk c (N = lane_syms
  *                                symbols, fewer in the ragged last chunk);
  *                                0 for empty lanes
- *   stream    : the codewords concatenated chunk by chunk, inside a chunk lane
- *               by lane; lane l of chunk c codes, in this order, the
- *               16-element pieces l, l+64, l+128, ... of the chunk, i.e. its
- *               k-th symbol is element c*64N + ((k/16)*64 + l)*16 + k%16
- *               (elements >= n_elem do not exist and are skipped);
- *               stream bit i is bit (i & 7) of byte (i >> 3); a codeword's
- *               first (most significant) bit comes first; codes are the
- *               canonical code of code_len[] ordered by (length, symbol);
- *               zero padded to stream_bytes = roundup16(ceil(bits/8) + 8)
+ *   stream    : the lanes' bits concatenated chunk by chunk, lane by lane;
+ *               stream bit i is bit (i & 7) of byte (i >> 3).  Lane l of chunk
+ *               c owns bits [S, S + lane_bits), S = chunk_bit[c] + lane_bits of
+ *               the chunk's earlier lanes, and codes the 16-element pieces
+ *               l, l+64, l+128, ... of the chunk: its k-th symbol is element
+ *               c*64N + ((k/16)*64 + l)*16 + k%16 (elements >= n_elem do not
+ *               exist and are skipped).  Symbols k < N/2 are written forward
+ *               from bit S upwards (a codeword's first = most significant bit
+ *               lowest), symbols k >= N/2 backward from bit S + lane_bits - 1
+ *               downwards (first bit highest); the two runs meet exactly.
+ *               Codes are the canonical code of code_len[] ordered by
+ *               (length, symbol); zero padded to
+ *               stream_bytes = roundup16(ceil(bits/8) + 8)
  *   plane     : nibbles q = sign<<3 | mantissa; element i lives in byte
  *               (i/8)*4 + (i%4), low nibble if (i%8) < 4 else high nibble;
  *               zero padded to n_chunks*32N bytes

@@ -26,13 +26,18 @@
  *                                 last entry = stream_bits
  *   lane_bits : u16[n_chunks*64]  total code bits of lane l of chunk c
  *   stream    : stream_bytes bytes; stream bit i = bit (i&7) of byte (i>>3);
- *               codewords chunk by chunk, inside a chunk lane by lane; the
- *               k-th symbol (k = 0..N-1) of lane l of chunk c is element
+ *               lanes follow each other chunk by chunk, lane by lane; lane l
+ *               of chunk c owns bits [S, S + lane_bits) where S = chunk_bit[c]
+ *               + the lane_bits of the chunk's earlier lanes.  The k-th
+ *               symbol (k = 0..N-1) of the lane is element
  *               c*64N + ((k/16)*64 + l)*16 + k%16; elements >= n_elem do not
- *               exist and are skipped; each codeword is written
- *               first-bit-first (its most significant bit first); codes are
- *               canonical from code_len, ordered by (length, symbol); zero
- *               padded, stream_bytes = roundup16(ceil(stream_bits/8) + 8)
+ *               exist and are skipped.  Symbols k < N/2 are coded FORWARD from
+ *               bit S upwards (a codeword's first = most significant bit at
+ *               the lowest position); symbols k >= N/2 are coded BACKWARD from
+ *               bit S + lane_bits - 1 downwards (first bit at the highest
+ *               position); the two runs meet exactly.  Codes are canonical
+ *               from code_len, ordered by (length, symbol); zero padded,
+ *               stream_bytes = roundup16(ceil(stream_bits/8) + 8)
  *   plane     : sign/mantissa nibbles q = sign<<3 | mantissa (Table 4,
  *               "packed"), regrouped: element i sits in byte
  *               (i/8)*4 + (i%4), low nibble when (i%8) < 4, else high
@@ -59,12 +64,9 @@ void orc_histogram(const uint8_t *x, uint64_t n, uint64_t freq[ORC_NSYM]);
 int orc_huffman_lengths(const uint64_t freq[ORC_NSYM], uint8_t len[ORC_NSYM]);
 int orc_canonical_codes(const uint8_t len[ORC_NSYM], uint16_t code[ORC_NSYM]);
 uint64_t orc_stream_bits(const uint64_t freq[ORC_NSYM], const uint8_t len[ORC_NSYM]);
-int orc_encode_exponents(const uint8_t *x, uint64_t n, const uint8_t len[ORC_NSYM],
-                         const uint16_t code[ORC_NSYM], int order, uint8_t *stream,
-                         uint64_t stream_cap_bytes, uint64_t *nbits_out,
-                         uint64_t mark_every, uint64_t *marks);
-int orc_decode_symbols(const uint8_t *stream, uint64_t nbits, int order,
-                       const uint8_t len[ORC_NSYM], uint64_t n, uint8_t *sym_out);
+int orc_decode_symbols_dir(const uint8_t *stream, int64_t start, int dir, int64_t lo, int64_t hi,
+                           int order, const uint8_t len[ORC_NSYM], uint64_t n, uint8_t *sym_out,
+                           int64_t *next);
 
 static uint64_t rd64(const uint8_t *p)
 {
@@ -153,10 +155,10 @@ int orc_container_encode(const uint8_t *x, uint64_t rows, uint64_t cols, uint32_
     wr64(blob + 120, pl_bytes);
     for (int i = 0; i < ORC_NSYM; i++) wr64(blob + 128 + 8 * i, freq[i]);
 
-    /* the input in stream order, and the code bits of every lane */
-    uint8_t *xs = (uint8_t *)malloc(n);
-    if (!xs) return ORC_E_CAPACITY;
-    uint64_t j = 0, pos = 0;
+    /* lane by lane: first half of the lane's symbols forward from its first bit,
+     * second half backward from its last bit */
+    uint8_t *stream = blob + off_st;
+    uint64_t pos = 0;
     for (uint64_t c = 0; c < n_chunks; c++) {
         wr64(blob + off_cb + 8 * c, pos);
         for (uint64_t l = 0; l < 64; l++) {
@@ -167,20 +169,25 @@ int orc_container_encode(const uint8_t *x, uint64_t rows, uint64_t cols, uint32_
                 uint8_t sg, ex, mn;
                 orc_split(x[e], &sg, &ex, &mn);
                 lb += len[ex];
-                xs[j++] = x[e];
             }
+            uint64_t fwd = pos, bwd = pos + lb; /* bwd: one past the next bit to write */
+            for (uint64_t k = 0; k < N; k++) {
+                uint64_t e = lane_element(c, l, k, N);
+                if (e >= n) continue;
+                uint8_t sg, ex, mn;
+                orc_split(x[e], &sg, &ex, &mn);
+                for (int bit = len[ex] - 1; bit >= 0; bit--) { /* first bit of the codeword = its MSB */
+                    uint64_t at = (k < N / 2) ? fwd++ : --bwd;
+                    if ((code[ex] >> bit) & 1) stream[at >> 3] |= (uint8_t)(1u << (at & 7));
+                }
+            }
+            if (fwd != bwd) return ORC_E_FORMAT;
             wr16(blob + off_lb + 2 * (c * 64 + l), (uint32_t)lb);
             pos += lb;
         }
     }
     wr64(blob + off_cb + 8 * n_chunks, pos);
-    uint64_t got = 0;
-    rc = (j == n && pos == bits) ? ORC_OK : ORC_E_FORMAT;
-    if (rc == ORC_OK)
-        rc = orc_encode_exponents(xs, n, len, code, ORC_LSB_FIRST, blob + off_st, st_bytes, &got, 0, NULL);
-    free(xs);
-    if (rc == ORC_OK && got != bits) rc = ORC_E_FORMAT;
-    if (rc) return rc;
+    if (pos != bits) return ORC_E_FORMAT;
 
     /* regrouped nibble plane */
     for (uint64_t i = 0; i < n; i++) {
@@ -242,56 +249,55 @@ int orc_container_decode(const uint8_t *blob, uint64_t size, uint8_t *out, uint6
     }
     if (fsum != n || wsum != bits) return ORC_E_FORMAT;
 
-    /* pass 1: no metadata */
-    uint8_t *sym = (uint8_t *)malloc(n);
+    /* lane by lane through the metadata: forward run, backward run, and the two
+     * must meet exactly; chunk starts must agree with the running sum */
+    uint8_t *sym = (uint8_t *)malloc(n);       /* decoded exponent of every element */
     uint8_t *lane_sym = (uint8_t *)malloc(N);
     if (!sym || !lane_sym) { free(sym); free(lane_sym); return ORC_E_CAPACITY; }
-    int rc = orc_decode_symbols(stream, bits, ORC_LSB_FIRST, len, n, sym);
-    if (rc) { free(sym); free(lane_sym); return rc; }
-
-    /* pass 2: lane by lane through the metadata; lanes follow each other in stream order */
+    int rc = ORC_OK;
     if (rd64(blob + off_cb) != 0 || rd64(blob + off_cb + 8 * n_chunks) != bits) rc = ORC_E_META;
-    uint64_t sidx = 0; /* stream-order index of the lane's first symbol */
+    uint64_t done = 0;
     for (uint64_t c = 0; c < n_chunks && rc == ORC_OK; c++) {
         uint64_t pos = rd64(blob + off_cb + 8 * c);
         for (uint64_t l = 0; l < 64 && rc == ORC_OK; l++) {
-            uint64_t cnt = 0;
+            uint64_t cntA = 0, cntB = 0;
             for (uint64_t k = 0; k < N; k++)
-                if (lane_element(c, l, k, N) < n) cnt++;
+                if (lane_element(c, l, k, N) < n) { if (k < N / 2) cntA++; else cntB++; }
             uint64_t lb = rd16(blob + off_lb + 2 * (c * 64 + l));
-            if (cnt == 0) { if (lb != 0) rc = ORC_E_META; continue; }
+            if (cntA + cntB == 0) { if (lb != 0) rc = ORC_E_META; continue; }
             if (pos + lb > bits) { rc = ORC_E_META; break; }
-            /* a private copy of the lane's lb bits makes "ends exactly there" checkable
-             * with the same strict decoder */
-            uint64_t wbytes = (lb + 7) / 8 + 1;
-            uint8_t *wbuf = (uint8_t *)calloc(wbytes, 1);
-            if (!wbuf) { rc = ORC_E_CAPACITY; break; }
-            for (uint64_t b = 0; b < lb; b++)
-                if ((stream[(pos + b) >> 3] >> ((pos + b) & 7)) & 1)
-                    wbuf[b >> 3] |= (uint8_t)(1u << (b & 7));
-            int r2 = orc_decode_symbols(wbuf, lb, ORC_LSB_FIRST, len, cnt, lane_sym);
-            free(wbuf);
-            if (r2) { rc = ORC_E_META; break; }
-            if (memcmp(lane_sym, sym + sidx, cnt) != 0) { rc = ORC_E_META; break; }
-            sidx += cnt;
+            int64_t endA = (int64_t)pos, endB = (int64_t)(pos + lb) - 1;
+            int r2 = orc_decode_symbols_dir(stream, (int64_t)pos, +1, (int64_t)pos, (int64_t)(pos + lb),
+                                            ORC_LSB_FIRST, len, cntA, lane_sym, &endA);
+            if (r2 == ORC_OK)
+                r2 = orc_decode_symbols_dir(stream, (int64_t)(pos + lb) - 1, -1, (int64_t)pos, (int64_t)(pos + lb),
+                                            ORC_LSB_FIRST, len, cntB, lane_sym + cntA, &endB);
+            if (r2 || endA != endB + 1) { rc = ORC_E_META; break; }
+            uint64_t j = 0;
+            for (uint64_t k = 0; k < N; k++) {
+                uint64_t e = lane_element(c, l, k, N);
+                if (e < n) { sym[e] = lane_sym[j++]; done++; }
+            }
             pos += lb;
         }
         if (rc == ORC_OK && pos != rd64(blob + off_cb + 8 * (c + 1))) rc = ORC_E_META;
     }
-    if (rc == ORC_OK && sidx != n) rc = ORC_E_META;
+    if (rc == ORC_OK && done != n) rc = ORC_E_META;
+    /* the decoded exponents must reproduce the header's histogram */
+    if (rc == ORC_OK) {
+        uint64_t cnt[ORC_NSYM] = {0};
+        for (uint64_t i = 0; i < n; i++) cnt[sym[i]]++;
+        for (int i = 0; i < ORC_NSYM; i++)
+            if (cnt[i] != rd64(blob + 128 + 8 * i)) rc = ORC_E_META;
+    }
 
     if (rc == ORC_OK) {
         const uint8_t *plane = blob + off_pl;
-        uint64_t j = 0;
-        for (uint64_t c = 0; c < n_chunks; c++)
-            for (uint64_t l = 0; l < 64; l++)
-                for (uint64_t k = 0; k < N; k++) {
-                    uint64_t i = lane_element(c, l, k, N);
-                    if (i >= n) continue;
-                    uint8_t b = plane[plane_byte_index(i)];
-                    uint8_t q = plane_is_high(i) ? (uint8_t)(b >> 4) : (uint8_t)(b & 15);
-                    out[i] = orc_join((uint8_t)(q >> 3), sym[j++], (uint8_t)(q & 7));
-                }
+        for (uint64_t i = 0; i < n; i++) {
+            uint8_t b = plane[plane_byte_index(i)];
+            uint8_t q = plane_is_high(i) ? (uint8_t)(b >> 4) : (uint8_t)(b & 15);
+            out[i] = orc_join((uint8_t)(q >> 3), sym[i], (uint8_t)(q & 7));
+        }
         /* padding nibbles beyond n must be zero */
         for (uint64_t i = n; i < n_chunks * chunk; i++) {
             uint8_t b = plane[plane_byte_index(i)];

@@ -344,6 +344,36 @@ int orc_decode_symbols(const uint8_t *stream, uint64_t nbits, int order,
     return ORC_OK;
 }
 
+/* Directional variant for containers whose lanes hold a forward and a backward
+ * run of codewords: decodes n symbols starting at bit `start`, stepping +1 or
+ * -1 per bit (a codeword's first bit is read first either way); bits outside
+ * [lo, hi) are an error.  *next receives the index of the next unread bit. */
+int orc_decode_symbols_dir(const uint8_t *stream, int64_t start, int dir, int64_t lo, int64_t hi,
+                           int order, const uint8_t len[ORC_NSYM], uint64_t n, uint8_t *sym_out,
+                           int64_t *next)
+{
+    uint16_t code[ORC_NSYM];
+    orc_tree t;
+    int rc = orc_canonical_codes(len, code);
+    if (rc) return rc;
+    rc = tree_build(&t, len, code);
+    if (rc) return rc;
+    int64_t pos = start;
+    for (uint64_t i = 0; i < n; i++) {
+        int node = 0;
+        while (t.sym[node] < 0) {
+            if (pos < lo || pos >= hi) return ORC_E_FORMAT;
+            int bit = get_bit(stream, (uint64_t)pos, order);
+            pos += dir;
+            node = t.child[node][bit];
+            if (node < 0) return ORC_E_CODE;
+        }
+        sym_out[i] = (uint8_t)t.sym[node];
+    }
+    *next = pos;
+    return ORC_OK;
+}
+
 /* Whole-tensor round trip in the paper's own terms: histogram -> lengths ->
  * canonical codes -> stream (Algorithm 1 bit order) + paper nibble plane ->
  * bit-serial decode.  out must hold n bytes.  Returns stream bits via *nbits. */

@@ -20,7 +20,10 @@
 //    their place in the output bytes, and the bits they consume.  A lane
 //    always decodes four symbols (two lookups) per step, so every lane of the
 //    wave runs the same number of steps, nothing diverges, and each step ends
-//    with one finished output dword in a register.  Pairs that do not fit in TB bits and
+//    with one finished output dword in a register.  A lane's bits hold two runs,
+//    one read forward from its first bit and one read backward from its last
+//    bit, so every lane advances two independent dependency chains at once
+//    (twice the LDS latency hidden per wave).  Pairs that do not fit in TB bits and
 //    codewords longer than TB bits take a second level (per-symbol walk that
 //    reuses the table's first-symbol fields, then a 16-entry canonical match).
 //    The table is built in the kernel from the 16 code lengths, so a tensor's
@@ -181,6 +184,96 @@ __device__ void build_tables(uint64_t len_lo, uint64_t len_hi, uint16_t *tbl, ui
     __syncthreads();
 }
 
+// 32 stream bits in reading order (bit 0 = next bit to read) from LDS.
+// DIR = +1: the bits [bp, bp+32);  DIR = -1: the bits bp-1, bp-2, ..., bp-32.
+template <int DIR>
+__device__ __forceinline__ uint32_t lds_window(const uint8_t *smem, uint32_t bp)
+{
+    const uint32_t p = DIR > 0 ? bp : bp - 32;
+    const uint32_t aw = (p >> 3) & ~3u;
+    const uint32_t d0 = *(const uint32_t *)(smem + aw);
+    const uint32_t d1 = *(const uint32_t *)(smem + aw + 4);
+    const uint32_t w = __builtin_amdgcn_alignbit(d1, d0, p);
+    return DIR > 0 ? w : __brev(w);
+}
+
+// One decode step of both runs of a lane: four symbols each = two table
+// lookups each.  The two runs are independent, and the common path is one
+// straight line, so their LDS round trips overlap; the second level for pairs
+// that do not fit TB bits is one shared, rarely taken branch.  Returns the four
+// exponent fields of each run in their output byte positions (other bits are
+// noise the merge masks off) and moves bpA / bpB past the codewords.
+__device__ __forceinline__ void quad_step2(const uint8_t *smem, const uint16_t *tbl, const uint32_t *s_len,
+                                           const uint32_t *s_code, uint32_t &bpA, uint32_t &bpB,
+                                           uint32_t &outA, uint32_t &outB)
+{
+    const uint32_t wA = lds_window<+1>(smem, bpA);
+    const uint32_t wB = lds_window<-1>(smem, bpB);
+    uint32_t eA1 = tbl[wA & TBL_MASK];
+    uint32_t eB1 = tbl[wB & TBL_MASK];
+    uint32_t nA1 = (eA1 >> 7) & 15u;
+    uint32_t nB1 = (eB1 >> 7) & 15u;
+    uint32_t eA2 = tbl[(wA >> nA1) & TBL_MASK];        // >= 18 valid bits left in the window
+    uint32_t eB2 = tbl[(wB >> nB1) & TBL_MASK];
+    uint32_t nA2 = (eA2 >> 7) & 15u;
+    uint32_t nB2 = (eB2 >> 7) & 15u;
+    // n1 == 0 makes the second lookup repeat the first, so n2 == 0 covers both pairs of a run
+    if (__builtin_expect(nA2 == 0 || nB2 == 0, 0)) {
+        if (nA2 == 0) {
+            if (nA1 == 0) pair_second_level(wA, eA1, nA1, tbl, s_len, s_code);
+            // the second level needs up to 30 bits: fresh window after the first pair
+            const uint32_t w2 = lds_window<+1>(smem, bpA + nA1);
+            eA2 = tbl[w2 & TBL_MASK];
+            nA2 = (eA2 >> 7) & 15u;
+            if (nA2 == 0) pair_second_level(w2, eA2, nA2, tbl, s_len, s_code);
+        }
+        if (nB2 == 0) {
+            if (nB1 == 0) pair_second_level(wB, eB1, nB1, tbl, s_len, s_code);
+            const uint32_t w2 = lds_window<-1>(smem, bpB - nB1);
+            eB2 = tbl[w2 & TBL_MASK];
+            nB2 = (eB2 >> 7) & 15u;
+            if (nB2 == 0) pair_second_level(w2, eB2, nB2, tbl, s_len, s_code);
+        }
+    }
+    bpA += nA1 + nA2;
+    bpB -= nB1 + nB2;
+    outA = (eA1 & 0xffffu) | (eA2 << 16);
+    outB = (eB1 & 0xffffu) | (eB2 << 16);
+}
+
+// byte = exponent<<3 | sign<<7 | mantissa  (Algorithm 1, byte assembly) for one
+// 16-byte piece: dw = four dwords of exponent fields, pl = the piece's 8 bytes
+// of the nibble plane (byte j of a dword: low nibble element j, high nibble
+// element j + 4 of that 8-element group).
+__device__ __forceinline__ u32x4 merge_piece(const uint32_t dw[4], u32x2 pl)
+{
+    const uint32_t p0 = pl.x, p1 = pl.y;
+    u32x4 d;
+    d.x = (dw[0] & EXP_MASK) | (p0 & 0x07070707u) | ((p0 & 0x08080808u) << 4);
+    d.y = (dw[1] & EXP_MASK) | ((p0 >> 4) & 0x07070707u) | (p0 & 0x80808080u);
+    d.z = (dw[2] & EXP_MASK) | (p1 & 0x07070707u) | ((p1 & 0x08080808u) << 4);
+    d.w = (dw[3] & EXP_MASK) | ((p1 >> 4) & 0x07070707u) | (p1 & 0x80808080u);
+    return d;
+}
+
+// 32 stream bits in reading order straight from HBM (generic pass).  `bit` is
+// relative to the 4-byte aligned pointer sp; DIR as in lds_window.
+template <int DIR>
+__device__ __forceinline__ uint32_t global_window(const GLOBAL uint8_t *sp, uint64_t bit)
+{
+    if (DIR > 0) {
+        const GLOBAL uint32_t *q = (const GLOBAL uint32_t *)(sp + ((bit >> 3) & ~3ull));
+        return __builtin_amdgcn_alignbit(q[1], q[0], (uint32_t)bit);
+    }
+    if (bit < 32) {   // fewer than 32 bits below: the missing ones are never consumed
+        const uint32_t d0 = *(const GLOBAL uint32_t *)sp;
+        return __brev(bit ? d0 << (32 - (uint32_t)bit) : 0u);
+    }
+    const uint64_t p = bit - 32;
+    const GLOBAL uint32_t *q = (const GLOBAL uint32_t *)(sp + ((p >> 3) & ~3ull));
+    return __brev(__builtin_amdgcn_alignbit(q[1], q[0], (uint32_t)p));
+}
+
 template <int N, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
 {
@@ -326,45 +419,20 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
                     if (cg1 + WAVES < fast_end) m_next2 = load_meta(cg1 + WAVES - first_chunk);
                 }
 
-                // bp: LDS bit address (smem-relative) of the lane's next codeword
-                uint32_t bp = stage_off * 8 + bit_in;   // oversize chunk: may point past LDS, reads return 0
+                // bpA: LDS bit address (smem-relative) of the forward run's next codeword;
+                // bpB: one past the backward run's next codeword (its first bit is bpB - 1)
+                uint32_t bpA = stage_off * 8 + bit_in;   // oversize chunk: may point past LDS, reads return 0
+                uint32_t bpB = bpA + m_cur.lb;
 #pragma unroll
-                for (int Q = 0; Q < C::PIECES; Q++) {
-                    uint32_t dw[4];
+                for (int Q = 0; Q < C::PIECES / 2; Q++) {
+                    uint32_t dwA[4], dwB[4];
 #pragma unroll
                     for (int t = 0; t < 4; t++) {
-                        const uint32_t aw = (bp >> 3) & ~3u;
-                        const uint32_t d0 = *(const uint32_t *)(smem + aw);
-                        const uint32_t d1 = *(const uint32_t *)(smem + aw + 4);
-                        const uint32_t w = __builtin_amdgcn_alignbit(d1, d0, bp);   // 32 stream bits from bp
-                        uint32_t e1 = tbl[w & TBL_MASK];
-                        uint32_t n1 = (e1 >> 7) & 15u;
-                        if (__builtin_expect(n1 == 0, 0)) pair_second_level(w, e1, n1, tbl, s_len, s_code);
-                        uint32_t w2 = w >> n1;                               // >= 18 valid bits unless n1 > 14
-                        uint32_t e2 = tbl[w2 & TBL_MASK];
-                        uint32_t n2 = (e2 >> 7) & 15u;
-                        if (__builtin_expect(n1 > 14 || n2 == 0, 0)) {
-                            // second level needs up to 30 bits: take a fresh window at bp + n1
-                            const uint32_t b2 = bp + n1;
-                            const uint32_t a2 = (b2 >> 3) & ~3u;
-                            const uint32_t y0 = *(const uint32_t *)(smem + a2);
-                            const uint32_t y1 = *(const uint32_t *)(smem + a2 + 4);
-                            w2 = __builtin_amdgcn_alignbit(y1, y0, b2);
-                            e2 = tbl[w2 & TBL_MASK];
-                            n2 = (e2 >> 7) & 15u;
-                            if (n2 == 0) pair_second_level(w2, e2, n2, tbl, s_len, s_code);
-                        }
-                        dw[t] = (e1 & 0xffffu) | (e2 << 16);
-                        bp += n1 + n2;
+                        quad_step2(smem, tbl, s_len, s_code, bpA, bpB, dwA[t], dwB[t]);
                     }
-                    // byte = exponent<<3 | sign<<7 | mantissa  (Algorithm 1, byte assembly)
-                    const uint32_t p0 = pl[Q].x, p1 = pl[Q].y;
-                    u32x4 d;
-                    d.x = (dw[0] & EXP_MASK) | (p0 & 0x07070707u) | ((p0 & 0x08080808u) << 4);
-                    d.y = (dw[1] & EXP_MASK) | ((p0 >> 4) & 0x07070707u) | (p0 & 0x80808080u);
-                    d.z = (dw[2] & EXP_MASK) | (p1 & 0x07070707u) | ((p1 & 0x08080808u) << 4);
-                    d.w = (dw[3] & EXP_MASK) | ((p1 >> 4) & 0x07070707u) | (p1 & 0x80808080u);
-                    *(GLOBAL u32x4 *)(out + elem0 + (uint64_t)(Q * 64 + lane) * 16) = d;
+                    *(GLOBAL u32x4 *)(out + elem0 + (uint64_t)(Q * 64 + lane) * 16) = merge_piece(dwA, pl[Q]);
+                    *(GLOBAL u32x4 *)(out + elem0 + (uint64_t)((Q + C::PIECES / 2) * 64 + lane) * 16) =
+                        merge_piece(dwB, pl[Q + C::PIECES / 2]);
                 }
 
                 if (!has_next) break;
@@ -390,15 +458,17 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
                 const uint64_t elem0 = cl * (64ull * N);
                 const uint32_t rel = wave_incl_scan(m.lb) - m.lb;
                 const GLOBAL uint8_t *sp = stream + byte0;
-                uint32_t b = (uint32_t)(m.b0 - byte0 * 8) + rel;
+                uint64_t bA = (m.b0 - byte0 * 8) + rel;   // forward run: next bit
+                uint64_t bB = bA + m.lb;                  // backward run: one past the next bit
 #pragma unroll 1
                 for (int Q = 0; Q < C::PIECES; Q++) {
                     const uint64_t o = elem0 + (uint64_t)(Q * 64 + lane) * 16;
+                    const bool fwd = Q < C::PIECES / 2;
 #pragma unroll 1
                     for (uint32_t i = 0; i < 16 && o + i < n_elem; i++) {
-                        const GLOBAL uint32_t *q = (const GLOBAL uint32_t *)(sp + ((b >> 3) & ~3u));
-                        const uint32_t r = decode_one(__builtin_amdgcn_alignbit(q[1], q[0], b), tbl, s_len, s_code);
-                        b += r >> 8;
+                        const uint32_t w = fwd ? global_window<+1>(sp, bA) : global_window<-1>(sp, bB);
+                        const uint32_t r = decode_one(w, tbl, s_len, s_code);
+                        if (fwd) bA += r >> 8; else bB -= r >> 8;
                         const uint64_t el = o + i;
                         const uint32_t pb = plane[(el >> 3) * 4 + (el & 3)];
                         const uint32_t nib = (el & 4) ? pb >> 4 : pb & 15u;

@@ -6,10 +6,12 @@
 // generation").  The paper's metadata (a 4-bit gap per fixed-size byte window
 // and an output position per block) is replaced by the number of stream bits
 // of every lane's N codewords, which removes the decoder's counting pass.
-// The stream is the concatenation of the codewords chunk by chunk; inside a
-// chunk the order is lane-major (lane l codes the 16-element pieces l, l+64,
-// ...), so that what the 64 lanes decode in the same step is contiguous in
-// the output.
+// The stream is the concatenation of the lanes' bits chunk by chunk, lane by
+// lane; lane l codes the 16-element pieces l, l+64, ... of its chunk, so that
+// what the 64 lanes decode in the same step is contiguous in the output.  The
+// first half of a lane's symbols is written forward from the lane's first bit,
+// the second half backward from its last bit: the decoder runs both halves as
+// two independent dependency chains without any extra metadata.
 #include "ecf8.h"
 
 #include <algorithm>
@@ -70,10 +72,11 @@ void huffman_lengths(const uint64_t freq[16], uint8_t len[16])
     }
 }
 
-// Canonical codes ordered by (length, symbol).  rcode = the codeword with its
-// bit order reversed, so that its first bit is bit 0 (the stream is filled
-// from the least significant bit of each byte upwards).
-bool canonical(const uint8_t len[16], uint32_t rcode[16])
+// Canonical codes ordered by (length, symbol).  code = the codeword as a number
+// (first bit most significant); rcode = the same with its bit order reversed, so
+// that its first bit is bit 0.  Forward runs place rcode at ascending stream
+// bits, backward runs place code so that its first bit is the highest.
+bool canonical(const uint8_t len[16], uint32_t rcode[16], uint32_t code_out[16] = nullptr)
 {
     uint32_t count[17] = {0}, next[17] = {0};
     for (int s = 0; s < 16; s++) { if (len[s] > 15) return false; count[len[s]]++; }
@@ -83,6 +86,7 @@ bool canonical(const uint8_t len[16], uint32_t rcode[16])
     uint64_t kraft = 0;
     for (int s = 0; s < 16; s++) {
         rcode[s] = 0;
+        if (code_out) code_out[s] = 0;
         int l = len[s];
         if (!l) continue;
         kraft += 1ull << (15 - l);
@@ -90,6 +94,7 @@ bool canonical(const uint8_t len[16], uint32_t rcode[16])
         uint32_t r = 0;
         for (int b = 0; b < l; b++) r |= ((c >> (l - 1 - b)) & 1u) << b;
         rcode[s] = r;
+        if (code_out) code_out[s] = c;
     }
     return kraft <= (1ull << 15) && kraft > 0;
 }
@@ -223,9 +228,9 @@ int ecf8_encode(const uint8_t *x, uint64_t rows, uint64_t cols, const ecf8_encod
             for (int s = 0; s < 16; s++) freq[s] += part[(size_t)t * 16 + s];
 
         uint8_t len[16];
-        uint32_t rcode[16];
+        uint32_t rcode[16], code[16];
         huffman_lengths(freq, len);
-        if (!canonical(len, rcode)) return ECF8_E_FORMAT;
+        if (!canonical(len, rcode, code)) return ECF8_E_FORMAT;
         uint64_t bits = 0;
         for (int s = 0; s < 16; s++) bits += freq[s] * len[s];
 
@@ -290,17 +295,37 @@ int ecf8_encode(const uint8_t *x, uint64_t rows, uint64_t cols, const ecf8_encod
         parallel_for(L.n_chunks, nt, [&](uint64_t c0, uint64_t c1) {
             BitWriter bw(stream, chunk_bit[c0]);
             uint64_t a = c0 * chunk_elems, b = std::min<uint64_t>(c1 * chunk_elems, n);
-            // stream order inside a chunk: lane by lane, each lane its pieces in turn
+            // A lane's bits are assembled in a local buffer: the first half of its pieces
+            // forward from bit 0, the second half backward from its last bit; then the
+            // buffer is appended to the stream.  Lanes follow each other lane by lane.
+            uint64_t lbuf[32]; // 2048 bits >= 15 bits * 128 symbols
+            const uint32_t P = N / 16;
             for (uint64_t c = c0; c < c1; c++)
-                for (uint32_t l = 0; l < ECF8_LANES; l++)
-                    for (uint32_t q = 0; q < N / 16; q++) {
+                for (uint32_t l = 0; l < ECF8_LANES; l++) {
+                    const uint32_t lb = lane_bits[c * ECF8_LANES + l];
+                    if (lb == 0) continue;
+                    const uint32_t words = (lb + 63) / 64;
+                    for (uint32_t wi = 0; wi < words; wi++) lbuf[wi] = 0;
+                    uint32_t fwd = 0, bwd = lb;
+                    auto put_local = [&](uint32_t at, uint32_t bits, uint32_t nb) {
+                        lbuf[at >> 6] |= (uint64_t)bits << (at & 63);
+                        if ((at & 63) + nb > 64) lbuf[(at >> 6) + 1] |= (uint64_t)bits >> (64 - (at & 63));
+                    };
+                    for (uint32_t q = 0; q < P; q++) {
                         uint64_t pa = c * chunk_elems + ((uint64_t)q * ECF8_LANES + l) * 16;
                         uint64_t pb = std::min<uint64_t>(pa + 16, n);
                         for (uint64_t i = pa; i < pb; i++) {
                             uint32_t e = (x[i] >> 3) & 15;
-                            bw.put(rcode[e], len[e]);
+                            if (q < P / 2) { put_local(fwd, rcode[e], len[e]); fwd += len[e]; }
+                            else { bwd -= len[e]; put_local(bwd, code[e], len[e]); }
                         }
                     }
+                    for (uint32_t at = 0; at < lb; at += 32) {
+                        uint32_t nb = std::min<uint32_t>(32, lb - at);
+                        uint64_t v = lbuf[at >> 6] >> (at & 63);
+                        bw.put((uint32_t)(nb == 32 ? v : (v & ((1ull << nb) - 1))), nb);
+                    }
+                }
             bw.finish();
             // plane: 8 elements -> 4 bytes, element j pairs with element j+4
             uint64_t i = a;
