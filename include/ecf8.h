@@ -23,8 +23,18 @@
  * or aborts across this boundary.
  *
  * Container ("blob"), all integers little-endian, every section at a multiple
- * of 256 bytes from the start of the blob:
+ * of 256 bytes from the start of the blob, in this order:
  *   header (256 B): see struct ecf8_header
+ *   table     : optional, u16[2^table_bits] (table_bits = 14), directly after
+ *               the header: the decoder's pair lookup table, stored with the
+ *               tensor like the paper's LUT array (Table 4) so that a workgroup
+ *               loads it instead of building it.  Entry i describes the
+ *               codewords spelled by the bits of i, bit 0 first: with (s1, l1)
+ *               the first codeword's symbol and length and (s2, l2) the next
+ *               one's,  bits 3..6 = s1, bits 0..2 and 15 = l1 (low three bits,
+ *               high bit), and, when l1 + l2 <= table_bits, bits 11..14 = s2
+ *               and bits 7..10 = l1 + l2, else those bits are 0; an entry
+ *               whose first codeword needs more than table_bits bits is 0
  *   chunk_bit : u64[n_chunks+1]  stream bit at which chunk c's first codeword
  *                                starts; last entry = stream_bits
  *   lane_bits : u16[n_chunks*64] code bits of lane l of chunk c (N = lane_syms
@@ -78,7 +88,7 @@ typedef struct ecf8_header {
     uint64_t n_elem;          /* rows * cols                                     */
     uint64_t rows, cols;
     uint32_t lane_syms;       /* N: symbols per lane, one of 32, 64, 128         */
-    uint32_t lanes_per_chunk; /* ECF8_LANES                                      */
+    uint32_t table_bits;      /* 0: no embedded table; 14: table section present */
     uint64_t n_chunks;        /* ceil(n_elem / (64 N))                           */
     uint64_t stream_bits;     /* sum over elements of their code length          */
     uint8_t code_len[16];     /* code length of exponent field x, 0 = absent     */
@@ -88,8 +98,11 @@ typedef struct ecf8_header {
 } ecf8_header;
 
 typedef struct ecf8_encode_opts {
-    uint32_t lane_syms; /* 0 = default (64)                                      */
-    uint32_t n_threads; /* host threads for encoding, 0 = all hardware threads   */
+    uint32_t lane_syms;  /* 0 = default (64)                                     */
+    uint32_t n_threads;  /* host threads for encoding, 0 = all hardware threads  */
+    uint32_t table_mode; /* 0 = embed the table when n_elem >= 2^22 (32 KiB is   */
+                         /* then < 0.8 % of the tensor), 1 = always, 2 = never   */
+    uint32_t reserved;
 } ecf8_encode_opts;
 
 typedef struct ecf8_stats {
@@ -128,7 +141,8 @@ int ecf8_blob_describe(const void *blob_host, uint64_t size, ecf8_header *hdr);
 /*
  * Full metadata check of a HOST container before it is trusted on the device:
  * describe() plus chunk_bit monotone and consistent with lane_bits, lane_bits
- * <= 15 N, histogram consistent with stream_bits, zero padding.  The decode
+ * <= 15 N, histogram consistent with stream_bits, zero padding, and an embedded
+ * table equal to the one code_len[] defines.  The decode
  * calls do not read device memory from the host, so validate on the host
  * before uploading.
  */
@@ -155,7 +169,8 @@ typedef struct ecf8_batch_item {
     uint64_t off_chunk_bit, off_lane_bits, off_stream, off_plane;
     uint64_t stream_bytes;
     uint8_t code_len[16];
-    uint64_t reserved[4];
+    uint64_t off_table;    /* 0 = the blob holds no table                        */
+    uint64_t reserved[3];
 } ecf8_batch_item; /* 128 bytes */
 
 /*

@@ -15,13 +15,20 @@
  *     0   u32 magic 0x38464345 ("ECF8")     4   u32 version (1)
  *     8   u64 total_size                    16  u64 n_elem
  *     24  u64 rows                          32  u64 cols
- *     40  u32 lane_syms N                   44  u32 lanes_per_chunk (64)
+ *     40  u32 lane_syms N                   44  u32 table_bits (0 or 14)
  *     48  u64 n_chunks = ceil(n_elem/(64N)) 56  u64 stream_bits
  *     64  u8  code_len[16]
  *     80  u64 off_chunk_bit   88 u64 off_lane_bits
  *     96  u64 off_stream      104 u64 off_plane
  *     112 u64 stream_bytes    120 u64 plane_bytes
  *     128 u64 freq[16]
+ *   table     : only when table_bits = 14: u16[2^14] directly after the header, a
+ *               decoder lookup table the reader only verifies.  Entry i
+ *               describes the codewords spelled by the bits of i, bit 0 first:
+ *               (s1, l1) the first codeword's symbol and length, (s2, l2) the
+ *               next one's; bits 3..6 = s1, bits 0..2 = l1 & 7, bit 15 = l1 >> 3,
+ *               and if l1 + l2 <= 14: bits 11..14 = s2, bits 7..10 = l1 + l2,
+ *               else those are 0; 0 if the first codeword needs more than 14 bits
  *   chunk_bit : u64[n_chunks+1]   start bit of the first codeword of chunk c;
  *                                 last entry = stream_bits
  *   lane_bits : u16[n_chunks*64]  total code bits of lane l of chunk c
@@ -143,7 +150,7 @@ int orc_container_encode(const uint8_t *x, uint64_t rows, uint64_t cols, uint32_
     wr64(blob + 24, rows);
     wr64(blob + 32, cols);
     wr32(blob + 40, N);
-    wr32(blob + 44, 64);
+    wr32(blob + 44, 0); /* this writer embeds no decoder table */
     wr64(blob + 48, n_chunks);
     wr64(blob + 56, bits);
     for (int i = 0; i < ORC_NSYM; i++) blob[64 + i] = len[i];
@@ -216,7 +223,7 @@ int orc_container_decode(const uint8_t *blob, uint64_t size, uint8_t *out, uint6
     if (rd32(blob) != 0x38464345u || rd32(blob + 4) != 1) return ORC_E_FORMAT;
     uint64_t total = rd64(blob + 8), n = rd64(blob + 16);
     uint64_t rows = rd64(blob + 24), cols = rd64(blob + 32);
-    uint32_t N = rd32(blob + 40), L = rd32(blob + 44);
+    uint32_t N = rd32(blob + 40), TBITS = rd32(blob + 44);
     uint64_t n_chunks = rd64(blob + 48), bits = rd64(blob + 56);
     uint8_t len[ORC_NSYM];
     for (int i = 0; i < ORC_NSYM; i++) len[i] = blob[64 + i];
@@ -224,11 +231,12 @@ int orc_container_decode(const uint8_t *blob, uint64_t size, uint8_t *out, uint6
     uint64_t off_st = rd64(blob + 96), off_pl = rd64(blob + 104);
     uint64_t st_bytes = rd64(blob + 112), pl_bytes = rd64(blob + 120);
     if (total != size || n == 0 || rows * cols != n) return ORC_E_FORMAT;
-    if (L != 64 || N == 0 || (N % 16) != 0 || N > 256) return ORC_E_FORMAT;
+    if ((TBITS != 0 && TBITS != 14) || N == 0 || (N % 16) != 0 || N > 256) return ORC_E_FORMAT;
+    uint64_t tbytes = TBITS ? (2ull << TBITS) : 0;
     uint64_t chunk = 64ull * N;
     if (n_chunks != (n + chunk - 1) / chunk) return ORC_E_FORMAT;
     if ((off_cb | off_lb | off_st | off_pl) % 256) return ORC_E_FORMAT;
-    if (off_cb < 256 || off_cb + 8 * (n_chunks + 1) > off_lb) return ORC_E_FORMAT;
+    if (off_cb != 256 + tbytes || off_cb + 8 * (n_chunks + 1) > off_lb) return ORC_E_FORMAT;
     if (off_lb + 2 * n_chunks * 64 > off_st) return ORC_E_FORMAT;
     if (st_bytes != up((bits + 7) / 8 + 8, 16) || off_st + st_bytes > off_pl) return ORC_E_FORMAT;
     if (pl_bytes != n_chunks * 32ull * N || off_pl + pl_bytes > total) return ORC_E_FORMAT;
@@ -248,6 +256,29 @@ int orc_container_decode(const uint8_t *blob, uint64_t size, uint8_t *out, uint6
         if (f > 0 && len[i] == 0) return ORC_E_FORMAT;
     }
     if (fsum != n || wsum != bits) return ORC_E_FORMAT;
+
+    /* an embedded decoder table must say what the code says: walk the bits of every
+     * index through the code, one codeword, then the next */
+    if (TBITS) {
+        for (uint32_t idx = 0; idx < (1u << TBITS); idx++) {
+            uint8_t ib[4] = {(uint8_t)idx, (uint8_t)(idx >> 8), 0, 0};
+            uint8_t two[2];
+            int64_t nx = 0;
+            uint32_t s1 = 0, l1 = 0, s2 = 0, l2 = 0;
+            if (orc_decode_symbols_dir(ib, 0, +1, 0, TBITS, ORC_LSB_FIRST, len, 1, two, &nx) == ORC_OK) {
+                s1 = two[0]; l1 = (uint32_t)nx;
+                if (orc_decode_symbols_dir(ib, nx, +1, 0, TBITS, ORC_LSB_FIRST, len, 1, two + 1, &nx) == ORC_OK) {
+                    s2 = two[1]; l2 = (uint32_t)nx - l1;
+                }
+            }
+            uint32_t want = 0;
+            if (l1) {
+                want = (s1 << 3) | (l1 & 7) | ((l1 >> 3) << 15);
+                if (l2) want |= (s2 << 11) | ((l1 + l2) << 7);
+            }
+            if (rd16(blob + 256 + 2 * idx) != want) return ORC_E_FORMAT;
+        }
+    }
 
     /* lane by lane through the metadata: forward run, backward run, and the two
      * must meet exactly; chunk starts must agree with the running sum */

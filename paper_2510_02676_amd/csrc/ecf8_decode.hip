@@ -26,16 +26,19 @@
 //    (twice the LDS latency hidden per wave).  Pairs that do not fit in TB bits and
 //    codewords longer than TB bits take a second level (per-symbol walk that
 //    reuses the table's first-symbol fields, then a 16-entry canonical match).
-//    The table is built in the kernel from the 16 code lengths, so a tensor's
-//    table costs 16 bytes of HBM traffic;
+//    The 32 KiB table is copied from the blob when the encoder embedded it (one
+//    L2-resident read per workgroup), else built in LDS from the 16 code lengths;
 //  * after four steps a lane holds one 16-byte piece; the 64 lanes' pieces are
 //    adjacent, so each dwordx4 store instruction of the wave writes 1 KiB of
 //    contiguous output, merged in registers with the nibble plane that was
 //    fetched (coalesced, 512 B per instruction) a whole chunk earlier.  Decoded
 //    bytes never pass through LDS;
-//  * persistent workgroups walk contiguous chunk ranges, so a table is built
-//    once per (workgroup, tensor) and no global atomics are needed.
+//  * persistent workgroups own contiguous chunk ranges, so a table is set up
+//    once per (workgroup, tensor); inside a workgroup the waves draw chunks
+//    from an LDS ticket counter (the hardware favours a SIMD's oldest wave, so
+//    equal static shares would finish up to 50 % apart).  No global atomics.
 #include "ecf8.h"
+#include "ecf8_table.h"
 
 #include <hip/hip_runtime.h>
 
@@ -43,7 +46,7 @@
 
 namespace {
 
-constexpr int TB = 14;                 // table index bits
+constexpr int TB = ECF8_TB;            // table index bits
 constexpr int TBL_ENTRIES = 1 << TB;
 constexpr uint32_t TBL_MASK = TBL_ENTRIES - 1;
 
@@ -83,7 +86,8 @@ struct Cfg {
     // LDS map (byte offsets into one array)
     static constexpr int OFF_TBL = 0;
     static constexpr int OFF_SYM = OFF_TBL + TBL_ENTRIES * 2;  // s_len[16], s_code[16]
-    static constexpr int OFF_WAVES = OFF_SYM + 128;
+    static constexpr int OFF_CTL = OFF_SYM + 128;              // ticket counter, oversize flag
+    static constexpr int OFF_WAVES = OFF_CTL + 16;
     static constexpr int WAVES_BYTES = WAVES * STAGE > TBL_ENTRIES * 2 ? WAVES * STAGE : TBL_ENTRIES * 2;
     static constexpr int TOTAL = OFF_WAVES + WAVES_BYTES;   // table-build scratch aliases the stages
     static_assert(TOTAL <= 160 * 1024, "LDS of one gfx950 CU");
@@ -143,8 +147,8 @@ __device__ __forceinline__ void pair_second_level(uint32_t bits, uint32_t &e, ui
 
 // Builds the pair table and the per-symbol (length, code) arrays in LDS from
 // the 16 code lengths.  `tmp` is TBL_ENTRIES u16 of scratch LDS.
-__device__ void build_tables(uint64_t len_lo, uint64_t len_hi, uint16_t *tbl, uint32_t *s_len, uint32_t *s_code,
-                             uint16_t *tmp, int tid, int nthreads)
+__device__ __forceinline__ void build_symbol_arrays(uint64_t len_lo, uint64_t len_hi, uint32_t *s_len,
+                                                    uint32_t *s_code, int tid)
 {
     if (tid < 16) {
         uint32_t l = len_of(len_lo, len_hi, tid);
@@ -158,6 +162,12 @@ __device__ void build_tables(uint64_t len_lo, uint64_t len_hi, uint16_t *tbl, ui
         s_len[tid] = l;
         s_code[tid] = code;
     }
+}
+
+__device__ void build_tables(uint64_t len_lo, uint64_t len_hi, uint16_t *tbl, uint32_t *s_len, uint32_t *s_code,
+                             uint16_t *tmp, int tid, int nthreads)
+{
+    build_symbol_arrays(len_lo, len_hi, s_len, s_code, tid);
     for (int i = tid; i < TBL_ENTRIES; i += nthreads) tmp[i] = 0;
     __syncthreads();
     // single-symbol table: every index whose low bits spell the codeword (first bit = bit 0)
@@ -170,16 +180,10 @@ __device__ void build_tables(uint64_t len_lo, uint64_t len_hi, uint16_t *tbl, ui
     }
     __syncthreads();
     for (int idx = tid; idx < TBL_ENTRIES; idx += nthreads) {
-        uint32_t t1 = tmp[idx];
-        uint32_t l1 = t1 >> 4;
-        uint32_t e = 0;
-        if (l1) {
-            e = ((t1 & 15u) << 3) | (l1 & 7u) | ((l1 & 8u) << 12);
-            uint32_t t2 = tmp[idx >> l1];
-            uint32_t l2 = t2 >> 4;
-            if (l2 && l1 + l2 <= TB) e |= ((t2 & 15u) << 11) | ((l1 + l2) << 7);
-        }
-        tbl[idx] = (uint16_t)e;
+        const uint32_t t1 = tmp[idx];
+        const uint32_t l1 = t1 >> 4;
+        const uint32_t t2 = l1 ? tmp[idx >> l1] : 0u;
+        tbl[idx] = ecf8_pair_entry(t1 & 15u, l1, t2 & 15u, t2 >> 4);
     }
     __syncthreads();
 }
@@ -282,6 +286,8 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
     uint16_t *tbl = (uint16_t *)(smem + C::OFF_TBL);
     uint32_t *s_len = (uint32_t *)(smem + C::OFF_SYM);
     uint32_t *s_code = s_len + 16;
+    uint32_t *s_ticket = (uint32_t *)(smem + C::OFF_CTL);
+    uint32_t *s_oversize = s_ticket + 1;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -297,7 +303,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
     while (c < c_end) {
         // which tensor holds chunk c (uniform)
         uint64_t d_blob, d_out, n_elem, n_chunks, first_chunk, off_cb, off_lb, off_st, off_pl, st_bytes;
-        uint64_t len_lo, len_hi;
+        uint64_t len_lo, len_hi, off_tbl;
         if (a.items) {
             uint32_t lo = 0, hi = a.n_items - 1;
             while (lo < hi) {
@@ -308,6 +314,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
             d_blob = p->d_blob; d_out = p->d_out; n_elem = p->n_elem; n_chunks = p->n_chunks;
             first_chunk = p->first_chunk; off_cb = p->off_chunk_bit; off_lb = p->off_lane_bits;
             off_st = p->off_stream; off_pl = p->off_plane; st_bytes = p->stream_bytes;
+            off_tbl = p->off_table;
             const GLOBAL uint64_t *cl8 = (const GLOBAL uint64_t *)p->code_len;
             len_lo = cl8[0]; len_hi = cl8[1];
         } else {
@@ -315,6 +322,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
             n_chunks = a.single.n_chunks; first_chunk = 0; off_cb = a.single.off_chunk_bit;
             off_lb = a.single.off_lane_bits; off_st = a.single.off_stream; off_pl = a.single.off_plane;
             st_bytes = a.single.stream_bytes;
+            off_tbl = a.single.off_table;
             __builtin_memcpy(&len_lo, a.single.code_len, 8);
             __builtin_memcpy(&len_hi, a.single.code_len + 8, 8);
         }
@@ -328,7 +336,16 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
         const GLOBAL uint8_t *plane = (const GLOBAL uint8_t *)(d_blob + off_pl);
 
         __syncthreads(); // every wave is done with the previous tensor's table and its scratch
-        build_tables(len_lo, len_hi, tbl, s_len, s_code, (uint16_t *)(smem + C::OFF_WAVES), tid, WAVES * 64);
+        if (tid == 0) { *s_ticket = 0; *s_oversize = 0; }
+        if (off_tbl) {
+            // the encoder embedded the table: copy it (L2-resident after the first workgroup)
+            const GLOBAL u32x4 *src = (const GLOBAL u32x4 *)(d_blob + off_tbl);
+            for (int i = tid; i < TBL_ENTRIES * 2 / 16; i += WAVES * 64) ((u32x4 *)tbl)[i] = src[i];
+            build_symbol_arrays(len_lo, len_hi, s_len, s_code, tid);
+            __syncthreads();
+        } else {
+            build_tables(len_lo, len_hi, tbl, s_len, s_code, (uint16_t *)(smem + C::OFF_WAVES), tid, WAVES * 64);
+        }
 
         // Per-wave software pipeline over its chunks cg = c + wave, + WAVES, ...:
         // metadata is loaded two chunks ahead, stream span and nibble plane one chunk
@@ -376,12 +393,19 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
         const bool ragged_tail = (n_elem % (64ull * N)) != 0;
         const uint64_t fast_end = (ragged_tail && seg_end == t_end) ? seg_end - 1 : seg_end;
         bool any_oversize = false;
+        // next chunk of this workgroup's range, drawn from the LDS ticket counter (wave-uniform)
+        auto draw = [&]() -> uint64_t {
+            uint32_t t = 0;
+            if (lane == 0) t = __hip_atomic_fetch_add(s_ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            return c + __builtin_amdgcn_readfirstlane(t);
+        };
 
-        uint64_t cg = c + wave;
+        uint64_t cg = draw();
         if (cg < fast_end) {
             Meta m_cur = load_meta(cg - first_chunk);
             Payload p_cur = issue_payload(cg - first_chunk, m_cur);
-            uint64_t cg1 = cg + WAVES;
+            uint64_t cg1 = draw();
+            uint64_t cg2 = fast_end;    // drawn when cg1 is taken up
             Meta m_next = m_cur;
             if (cg1 < fast_end) m_next = load_meta(cg1 - first_chunk);
             // Drain the prologue's loads here (vmcnt(0), other counters untouched), so that
@@ -416,7 +440,8 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
                 Meta m_next2 = m_next;
                 if (has_next) {
                     p_cur = issue_payload(cg1 - first_chunk, m_next);
-                    if (cg1 + WAVES < fast_end) m_next2 = load_meta(cg1 + WAVES - first_chunk);
+                    cg2 = draw();
+                    if (cg2 < fast_end) m_next2 = load_meta(cg2 - first_chunk);
                 }
 
                 // bpA: LDS bit address (smem-relative) of the forward run's next codeword;
@@ -439,14 +464,16 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
                 m_cur = m_next;
                 m_next = m_next2;
                 cg = cg1;
-                cg1 += WAVES;
+                cg1 = cg2;
             }
         }
+        if (any_oversize && lane == 0) *s_oversize = 1;
+        __syncthreads();
 
         // Generic pass, symbol by symbol with windows and nibbles read straight from HBM:
         // the ragged last chunk of the tensor, and chunks that code so much worse than 4 bits
         // per symbol that their span did not fit the stage.
-        if (__builtin_amdgcn_readfirstlane((uint32_t)any_oversize) || fast_end != seg_end) {
+        if (*s_oversize || fast_end != seg_end) {
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");   // the loop's stores land first
             for (uint64_t cg2 = c + wave; cg2 < seg_end; cg2 += WAVES) {
                 const uint64_t cl = cg2 - first_chunk;
@@ -527,7 +554,7 @@ int ecf8_decode(const ecf8_header *h, const void *d_blob, void *d_out, uint64_t 
 {
     if (!h || !d_blob || !d_out) return ECF8_E_ARG;
     if (h->magic != ECF8_MAGIC || h->version != ECF8_VERSION || h->n_elem == 0 || h->n_chunks == 0 ||
-        h->lanes_per_chunk != ECF8_LANES)
+        (h->table_bits != 0 && h->table_bits != ECF8_TB))
         return ECF8_E_FORMAT;
     if (h->n_chunks != (h->n_elem + 64ull * h->lane_syms - 1) / (64ull * h->lane_syms)) return ECF8_E_FORMAT;
     if (h->off_plane + h->plane_bytes > h->total_size || h->off_stream + h->stream_bytes > h->off_plane ||
@@ -546,6 +573,7 @@ int ecf8_decode(const ecf8_header *h, const void *d_blob, void *d_out, uint64_t 
     a.single.off_stream = h->off_stream;
     a.single.off_plane = h->off_plane;
     a.single.stream_bytes = h->stream_bytes;
+    a.single.off_table = h->table_bits ? 256 : 0;
     for (int i = 0; i < 16; i++) a.single.code_len[i] = h->code_len[i];
     a.items = nullptr;
     a.n_items = 1;

@@ -13,6 +13,7 @@
 // the second half backward from its last bit: the decoder runs both halves as
 // two independent dependency chains without any extra metadata.
 #include "ecf8.h"
+#include "ecf8_table.h"
 
 #include <algorithm>
 #include <cmath>
@@ -99,16 +100,34 @@ bool canonical(const uint8_t len[16], uint32_t rcode[16], uint32_t code_out[16] 
     return kraft <= (1ull << 15) && kraft > 0;
 }
 
+// The decoder's pair table (entry format in ecf8_table.h) from the code lengths.
+void build_pair_table(const uint8_t len[16], uint16_t *tbl)
+{
+    uint32_t rcode[16];
+    canonical(len, rcode);
+    std::vector<uint16_t> one(ECF8_TBL_ENTRIES, 0); // single-symbol facts: symbol | length << 4
+    for (uint32_t s = 0; s < 16; s++) {
+        uint32_t l = len[s];
+        if (l == 0 || l > ECF8_TB) continue;
+        for (uint32_t j = 0; j < (1u << (ECF8_TB - l)); j++) one[rcode[s] | (j << l)] = (uint16_t)(s | (l << 4));
+    }
+    for (uint32_t idx = 0; idx < ECF8_TBL_ENTRIES; idx++) {
+        uint32_t t1 = one[idx], l1 = t1 >> 4;
+        uint32_t t2 = l1 ? one[idx >> l1] : 0;
+        tbl[idx] = ecf8_pair_entry(t1 & 15u, l1, t2 & 15u, t2 >> 4);
+    }
+}
+
 struct Layout {
     uint64_t n_chunks, off_cb, off_lb, off_st, st_bytes, off_pl, pl_bytes, total;
 };
 
-Layout make_layout(uint64_t n, uint64_t bits, uint32_t N)
+Layout make_layout(uint64_t n, uint64_t bits, uint32_t N, uint32_t table_bits)
 {
     Layout L;
     uint64_t chunk = (uint64_t)ECF8_LANES * N;
     L.n_chunks = (n + chunk - 1) / chunk;
-    L.off_cb = 256;
+    L.off_cb = 256 + (table_bits ? (2ull << table_bits) : 0);
     L.off_lb = round_up(L.off_cb + 8 * (L.n_chunks + 1), 256);
     L.off_st = round_up(L.off_lb + 2 * L.n_chunks * ECF8_LANES, 256);
     L.st_bytes = round_up((bits + 7) / 8 + 8, 16);
@@ -166,9 +185,9 @@ int check_header(const ecf8_header &h, uint64_t size)
     if (h.magic != ECF8_MAGIC || h.version != ECF8_VERSION) return ECF8_E_FORMAT;
     if (h.total_size != size || h.n_elem == 0) return ECF8_E_FORMAT;
     if (h.rows == 0 || h.cols == 0 || h.n_elem / h.rows != h.cols || h.n_elem % h.rows) return ECF8_E_FORMAT;
-    if (h.lanes_per_chunk != ECF8_LANES || !lane_syms_ok(h.lane_syms)) return ECF8_E_FORMAT;
+    if ((h.table_bits != 0 && h.table_bits != ECF8_TB) || !lane_syms_ok(h.lane_syms)) return ECF8_E_FORMAT;
     if (h.stream_bits > h.n_elem * 15 || h.stream_bits < h.n_elem) return ECF8_E_FORMAT;
-    Layout L = make_layout(h.n_elem, h.stream_bits, h.lane_syms);
+    Layout L = make_layout(h.n_elem, h.stream_bits, h.lane_syms, h.table_bits);
     if (h.n_chunks != L.n_chunks || h.off_chunk_bit != L.off_cb || h.off_lane_bits != L.off_lb ||
         h.off_stream != L.off_st || h.off_plane != L.off_pl || h.stream_bytes != L.st_bytes ||
         h.plane_bytes != L.pl_bytes || h.total_size != L.total)
@@ -234,7 +253,10 @@ int ecf8_encode(const uint8_t *x, uint64_t rows, uint64_t cols, const ecf8_encod
         uint64_t bits = 0;
         for (int s = 0; s < 16; s++) bits += freq[s] * len[s];
 
-        Layout L = make_layout(n, bits, N);
+        const uint32_t tmode = opts ? opts->table_mode : 0;
+        if (tmode > 2) return ECF8_E_ARG;
+        const uint32_t table_bits = (tmode == 1 || (tmode == 0 && n >= (1ull << 22))) ? ECF8_TB : 0;
+        Layout L = make_layout(n, bits, N, table_bits);
         uint8_t *blob = (uint8_t *)std::aligned_alloc(256, L.total);
         if (!blob) return ECF8_E_NOMEM;
         std::memset(blob, 0, L.off_st); // header and metadata; payload sections are zeroed by their writers
@@ -246,7 +268,8 @@ int ecf8_encode(const uint8_t *x, uint64_t rows, uint64_t cols, const ecf8_encod
         h->rows = rows;
         h->cols = cols;
         h->lane_syms = N;
-        h->lanes_per_chunk = ECF8_LANES;
+        h->table_bits = table_bits;
+        if (table_bits) build_pair_table(len, (uint16_t *)(blob + 256));
         h->n_chunks = L.n_chunks;
         h->stream_bits = bits;
         std::memcpy(h->code_len, len, 16);
@@ -386,6 +409,11 @@ int ecf8_blob_validate(const void *blob, uint64_t size)
     if (rc) return rc;
     const uint8_t *p = (const uint8_t *)blob;
     const uint32_t N = h.lane_syms;
+    if (h.table_bits) {
+        std::vector<uint16_t> want(ECF8_TBL_ENTRIES);
+        build_pair_table(h.code_len, want.data());
+        if (std::memcmp(want.data(), p + 256, 2ull << h.table_bits) != 0) return ECF8_E_FORMAT;
+    }
     const uint64_t chunk_elems = (uint64_t)ECF8_LANES * N;
     uint64_t prev;
     std::memcpy(&prev, p + h.off_chunk_bit, 8);
@@ -467,6 +495,7 @@ int ecf8_batch_prepare(const ecf8_header *hdrs, const void *const *d_blobs, void
         it.off_stream = h.off_stream;
         it.off_plane = h.off_plane;
         it.stream_bytes = h.stream_bytes;
+        it.off_table = h.table_bits ? 256 : 0;
         std::memcpy(it.code_len, h.code_len, 16);
         first += h.n_chunks;
     }

@@ -27,7 +27,7 @@ class Header(ctypes.Structure):
     _fields_ = [("magic", ctypes.c_uint32), ("version", ctypes.c_uint32),
                 ("total_size", ctypes.c_uint64), ("n_elem", ctypes.c_uint64),
                 ("rows", ctypes.c_uint64), ("cols", ctypes.c_uint64),
-                ("lane_syms", ctypes.c_uint32), ("lanes_per_chunk", ctypes.c_uint32),
+                ("lane_syms", ctypes.c_uint32), ("table_bits", ctypes.c_uint32),
                 ("n_chunks", ctypes.c_uint64), ("stream_bits", ctypes.c_uint64),
                 ("code_len", ctypes.c_uint8 * 16),
                 ("off_chunk_bit", ctypes.c_uint64), ("off_lane_bits", ctypes.c_uint64),
@@ -37,7 +37,8 @@ class Header(ctypes.Structure):
 
 
 class EncodeOpts(ctypes.Structure):
-    _fields_ = [("lane_syms", ctypes.c_uint32), ("n_threads", ctypes.c_uint32)]
+    _fields_ = [("lane_syms", ctypes.c_uint32), ("n_threads", ctypes.c_uint32),
+                ("table_mode", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
 
 
 class Stats(ctypes.Structure):
@@ -52,7 +53,7 @@ class BatchItem(ctypes.Structure):
                 ("off_chunk_bit", ctypes.c_uint64), ("off_lane_bits", ctypes.c_uint64),
                 ("off_stream", ctypes.c_uint64), ("off_plane", ctypes.c_uint64),
                 ("stream_bytes", ctypes.c_uint64), ("code_len", ctypes.c_uint8 * 16),
-                ("reserved", ctypes.c_uint64 * 4)]
+                ("off_table", ctypes.c_uint64), ("reserved", ctypes.c_uint64 * 3)]
 
 
 assert ctypes.sizeof(Header) == 256 and ctypes.sizeof(BatchItem) == 128
@@ -130,14 +131,15 @@ class Blob:
             self._h = None
 
 
-def ecf8_encode(fp8, rows=None, cols=None, lane_syms=0, n_threads=0):
-    """CPU encoder: raw E4M3 bytes (host tensor / array) -> Blob."""
+def ecf8_encode(fp8, rows=None, cols=None, lane_syms=0, n_threads=0, table_mode=0):
+    """CPU encoder: raw E4M3 bytes (host tensor / array) -> Blob.
+    table_mode: 0 embed the decode table for tensors of >= 2^22 weights, 1 always, 2 never."""
     x = _host_u8(fp8)
     if rows is None:
         rows, cols = (x.shape if x.ndim == 2 else (1, x.size))
     if rows * cols != x.size:
         raise Ecf8Error("ecf8_encode", E_ARG)
-    opts = EncodeOpts(lane_syms, n_threads)
+    opts = EncodeOpts(lane_syms, n_threads, table_mode, 0)
     h = _vp()
     _check("ecf8_encode", _lib.ecf8_encode(x.ctypes.data, rows, cols, ctypes.byref(opts), ctypes.byref(h)))
     return Blob(h)

@@ -39,11 +39,13 @@ def _oracle_expected(orc, x):
     return exp
 
 
+@pytest.mark.parametrize("table_mode", [1, 2])
 @pytest.mark.parametrize("lane_syms", [32, 64, 128])
-def test_config0_parity(orc, lane_syms):
-    """configs[0]: 1024x1024, alpha 1.8, per-128x128 scaling, seed 0."""
+def test_config0_parity(orc, lane_syms, table_mode):
+    """configs[0]: 1024x1024, alpha 1.8, per-128x128 scaling, seed 0; with the pair table
+    embedded in the blob (1) and built in the kernel (2)."""
     w = synth.make(synth.config0()[0], seed=0).numpy().reshape(-1)
-    blob = ecf8.ecf8_encode(w, 1024, 1024, lane_syms=lane_syms)
+    blob = ecf8.ecf8_encode(w, 1024, 1024, lane_syms=lane_syms, table_mode=table_mode)
     got, guards = _gpu_decode_guarded(blob.numpy(), blob.header)
     assert guards
     assert np.array_equal(got, _oracle_expected(orc, w))
@@ -89,7 +91,7 @@ def _special_cases():
 @pytest.mark.parametrize("name", sorted(_special_cases()))
 def test_degenerate_and_extreme_inputs(orc, name, lane_syms):
     x = _special_cases()[name]
-    blob = ecf8.ecf8_encode(x, 1, x.size, lane_syms=lane_syms)
+    blob = ecf8.ecf8_encode(x, 1, x.size, lane_syms=lane_syms, table_mode=1 + (lane_syms == 64))
     got, guards = _gpu_decode_guarded(blob.numpy(), blob.header)
     assert guards
     assert np.array_equal(got, _oracle_expected(orc, x))
@@ -125,7 +127,7 @@ def test_batched_mixed_tensors(orc):
     """Many tensors, each with its own code, sizes from one lane to many chunks, one launch."""
     sizes = [5, 4096, 70_000, 1, 333_333, 8192 * 3, 1_000_000, 17, 250_000]
     xs = [_rand_bytes(n, 100 + i, conc=0.2 + 0.1 * i) for i, n in enumerate(sizes)]
-    blobs = [ecf8.ecf8_encode(x, 1, x.size) for x in xs]
+    blobs = [ecf8.ecf8_encode(x, 1, x.size, table_mode=1 + (i % 2)) for i, x in enumerate(xs)]
     d_blobs = [b.to(DEV) for b in blobs]
     pad = 256
     bufs = [torch.full((pad + x.size + pad,), 0x5A, dtype=torch.uint8, device=DEV) for x in xs]

@@ -46,6 +46,28 @@ def test_encoder_container_read_by_oracle(orc, lane_syms, n):
     assert blob.size == orc.lib().orc_container_size(n, bits, lane_syms)
 
 
+@pytest.mark.parametrize("n", [5, 4096, 100003])
+def test_embedded_table_is_what_the_code_says(orc, n):
+    """A blob with the decoder's pair table embedded: the oracle's reader rebuilds every
+    entry from the code by bit-serial walks and compares; so does the host validator."""
+    x = _rand_bytes(n, 900 + n, conc=0.15)          # skewed: long codes, pairs that do not fit
+    blob = ecf8.ecf8_encode(x, 1, n, table_mode=1)
+    arr = blob.numpy()
+    assert blob.header.table_bits == 14 and blob.header.off_chunk_bit == 256 + 32768
+    ecf8.blob_validate(arr)
+    dec, _ = orc.container_decode(arr)
+    assert np.array_equal(dec, x)
+    plain = ecf8.ecf8_encode(x, 1, n, table_mode=2)
+    assert plain.header.table_bits == 0 and blob.size == plain.size + 32768
+    for off in (256, 256 + 2 * 777, 256 + 32766):
+        bad = arr.copy()
+        bad[off] ^= 0x08
+        with pytest.raises(ecf8.Ecf8Error):
+            ecf8.blob_validate(bad)
+        with pytest.raises(ValueError):
+            orc.container_decode(bad)
+
+
 def test_every_byte_value_and_special_histograms(orc):
     cases = [np.arange(256, dtype=np.uint8).repeat(40),
              np.full(5000, 0x80, dtype=np.uint8),                       # one symbol: -0 everywhere
@@ -58,9 +80,11 @@ def test_every_byte_value_and_special_histograms(orc):
     np.random.default_rng(0).shuffle(deep)
     cases.append(deep)                                                  # code lengths up to 15
     for x in cases:
-        blob = ecf8.ecf8_encode(x, 1, x.size)
-        dec, _ = orc.container_decode(blob.numpy())
-        assert np.array_equal(dec, x)
+        for tm in (1, 2):
+            blob = ecf8.ecf8_encode(x, 1, x.size, table_mode=tm)
+            ecf8.blob_validate(blob.numpy())
+            dec, _ = orc.container_decode(blob.numpy())
+            assert np.array_equal(dec, x)
     assert max(ecf8.ecf8_encode(deep, 1, deep.size).header.code_len) == 15
 
 
