@@ -1,14 +1,17 @@
 #!/usr/bin/env python3
 """ECF8 decode benchmark on one MI355X.
 
-One step = one pass of the whole hot path over the workload: every layer of the
-stack is decoded from its resident compressed blobs to exact FP8 bytes, one
-ecf8_decode_batched launch per layer (the layer's matrices in one launch).
-Inputs are seeded synthetic alpha-stable FP8 weights; blobs and
-output buffers are resident in HBM before the timed region starts.
+One step = one pass of the whole hot path over the workload: every tensor of the
+stack is decoded from its resident compressed blob to exact FP8 bytes.  By
+default the whole stack goes through ONE ecf8_decode_batched launch per step
+(--launch stack); --launch layer issues one batched launch per layer/block
+instead, on --streams streams round-robin.  Inputs are seeded synthetic
+alpha-stable FP8 weights; blobs and output buffers are resident
+in HBM before the timed region starts.
 
-Prints ONE JSON line: decoded FP8 GB/s as `value`, plus the roofline of the
-decode kernel and the CPU oracle timed on a bounded sample.
+Prints ONE JSON line: decoded FP8 GB/s as `value`, the roofline of the decode
+kernel, the per-layer-launch rates measured after the timed region, and the CPU
+oracle timed on a bounded sample.
 """
 import argparse
 import json
@@ -32,7 +35,7 @@ def algorithmic_bytes(h):
     return rd, h.n_elem
 
 
-def build_workload(name, seed, lane_syms, layers):
+def build_workload(name, seed, lane_syms, layers, launch="layer"):
     from paper_2510_02676_amd import ecf8, synth
     if name == "config1":
         specs = synth.config1(seed, layers)
@@ -57,6 +60,8 @@ def build_workload(name, seed, lane_syms, layers):
         d_blob = blob.to(dev)
         d_out = torch.empty((s["rows"], s["cols"]), dtype=torch.uint8, device=dev)
         groups.setdefault(group(s), []).append(dict(spec=s, w=w, hdr=blob.header, d_blob=d_blob, d_out=d_out))
+    if launch == "stack":      # every tensor of the stack in ONE ecf8_decode_batched launch
+        groups = {0: [t for g in sorted(groups) for t in groups[g]]}
     batches = []
     for g in sorted(groups):
         ts = groups[g]
@@ -93,6 +98,51 @@ def cpu_baseline(batches, budget_syms=440_000_000):
                 len(names), names[0], names[-1], tot_syms, tot_t)}
 
 
+def profiled_traffic(workload, launch, lane_syms, layers_full):
+    """HBM bytes per launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary of this
+    exact workload, or None when no summary covers it."""
+    if not layers_full:
+        return None
+    path = os.path.join(ROOT, "profiles", "ecf8_decode_kernel_%s_%s.txt" % (workload, launch))
+    try:
+        text = open(path).read()
+    except OSError:
+        return None
+    if "workload=%s launch=%s lane_syms=%d" % (workload, launch, lane_syms) not in text:
+        return None
+    for line in text.splitlines():
+        if line.startswith("traffic_bytes_per_launch="):
+            return int(line.split("=")[1])
+    return None
+
+
+def per_layer_rates(tensors, alg_total, n_total, steps=10):
+    """The same stack decoded with one batched launch per layer/block, on one stream and
+    on two streams round-robin (the next layer's launch overlaps the previous one's tail)."""
+    from paper_2510_02676_amd import ecf8
+    key = "layer" if "layer" in tensors[0]["spec"] else "block"
+    groups = {}
+    for t in tensors:
+        groups.setdefault(t["spec"][key], []).append(t)
+    bs = [ecf8.Batch([t["hdr"] for t in ts], [t["d_blob"] for t in ts], [t["d_out"] for t in ts])
+          for _, ts in sorted(groups.items())]
+    res = {"launches_per_step": len(bs)}
+    for ns in (1, 2):
+        streams = [torch.cuda.current_stream()] + [torch.cuda.Stream() for _ in range(ns - 1)]
+        for it in range(2 + steps):
+            if it == 2:
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+            for i, b in enumerate(bs):
+                ecf8.ecf8_decode_batched(b, streams[i % ns])
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / steps
+        res["streams_%d" % ns] = {"decoded_GBps": round(n_total / dt / 1e9, 2),
+                                  "pct_of_hbm_peak": round(100 * alg_total / dt / 1e9 / HBM_PEAK_GBPS, 2),
+                                  "us_per_launch": round(dt / len(bs) * 1e6, 2)}
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -102,7 +152,14 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="0 = the full stack of the workload")
     ap.add_argument("--lane-syms", type=int, default=0, help="0 = library default")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--launch", default="stack", choices=["layer", "stack"],
+                    help="stack: the whole stack in one launch per step; "
+                         "layer: one batched launch per layer/block (as a per-layer decode hook would)")
+    ap.add_argument("--streams", type=int, default=1, help="streams for --launch layer (round-robin)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the per-layer-launch rates")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (a kernel of known traffic for profiler counters)")
     a = ap.parse_args()
     if a.gpus != 1:
         raise SystemExit("this build runs on ONE GPU: tensors are independent and shard with no exchange "
@@ -112,7 +169,7 @@ def main():
     from paper_2510_02676_amd import ecf8
 
     layers = a.layers or {"config1": 32, "config3": 40, "config0": 1}[a.workload]
-    batches, desc, t_setup = build_workload(a.workload, a.seed, a.lane_syms, layers)
+    batches, desc, t_setup = build_workload(a.workload, a.seed, a.lane_syms, layers, a.launch)
     hdrs = [t["hdr"] for _, ts in batches for t in ts]
     n_total = sum(h.n_elem for h in hdrs)
     blob_total = sum(h.total_size for h in hdrs)
@@ -120,10 +177,11 @@ def main():
     alg_total = rd_total + n_total
 
     stream = torch.cuda.current_stream()
+    side = [stream] + [torch.cuda.Stream() for _ in range(max(0, a.streams - 1))]
 
     def step():
-        for b, _ in batches:
-            ecf8.ecf8_decode_batched(b, stream)
+        for i, (b, _) in enumerate(batches):
+            ecf8.ecf8_decode_batched(b, side[i % len(side)] if a.launch == "layer" else stream)
 
     for _ in range(a.warmup):
         step()
@@ -142,7 +200,7 @@ def main():
     e1.record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    dev_s = e0.elapsed_time(e1) * 1e-3
+    dev_s = e0.elapsed_time(e1) * 1e-3 if len(side) == 1 or a.launch == "stack" else wall
     sec_per_step = wall / a.steps
     n_launch = len(batches) * a.steps
     launch_s = dev_s / n_launch                       # average duration of one decode launch (HIP events)
@@ -158,7 +216,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u8", "data": "synthetic",
         "config": {"workload": "%s: %s" % (a.workload, desc), "weights": n_total,
-                   "launches_per_step": len(batches), "lane_syms": hdrs[0].lane_syms, "seed": a.seed},
+                   "launches_per_step": len(batches), "launch": a.launch, "lane_syms": hdrs[0].lane_syms,
+                   "seed": a.seed},
         "compression_ratio": round(blob_total / n_total, 5),
         "memory_saving_pct": round(100 * (1 - blob_total / n_total), 2),
         "avg_code_bits": round(sum(h.stream_bits for h in hdrs) / n_total, 4),
@@ -170,8 +229,17 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "ecf8_decode_kernel", "achieved": round(achieved, 2),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "avg_launch_us": round(launch_s * 1e6, 2),
-                     "algorithmic_bytes_per_launch": int(alg_per_launch), "traffic": None},
+                     "algorithmic_bytes_per_launch": int(alg_per_launch),
+                     "traffic": profiled_traffic(a.workload, a.launch, hdrs[0].lane_syms, a.layers == 0)},
     }
+    if a.launch == "stack" and not a.no_extra and len(batches[0][1]) > 1:
+        out["per_layer_launch"] = per_layer_rates(batches[0][1], alg_total, n_total)
+    if a.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(7)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(batches)
     print(json.dumps(out))
