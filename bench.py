@@ -45,6 +45,10 @@ def build_workload(name, seed, lane_syms, layers, launch="layer"):
         specs = synth.config3(layers)
         group = lambda s: s["block"]
         desc = "14B-class DiT stack, %d blocks x 11 matrices" % layers
+    elif name == "config2":
+        specs = synth.config2(seed, layers)
+        group = lambda s: 0 if "expert" in s else 1
+        desc = "671B-class MoE layer, %d experts x 3 matrices + 2 attention projections" % layers
     elif name == "config0":
         specs = synth.config0()
         group = lambda s: 0
@@ -120,10 +124,10 @@ def per_layer_rates(tensors, alg_total, n_total, steps=10):
     """The same stack decoded with one batched launch per layer/block, on one stream and
     on two streams round-robin (the next layer's launch overlaps the previous one's tail)."""
     from paper_2510_02676_amd import ecf8
-    key = "layer" if "layer" in tensors[0]["spec"] else "block"
+    key = "layer" if "layer" in tensors[0]["spec"] else "block" if "block" in tensors[0]["spec"] else "expert"
     groups = {}
     for t in tensors:
-        groups.setdefault(t["spec"][key], []).append(t)
+        groups.setdefault(t["spec"].get(key, -1), []).append(t)
     bs = [ecf8.Batch([t["hdr"] for t in ts], [t["d_blob"] for t in ts], [t["d_out"] for t in ts])
           for _, ts in sorted(groups.items())]
     res = {"launches_per_step": len(bs)}
@@ -168,7 +172,7 @@ def main():
         raise SystemExit("no GPU visible: the decode path has no CPU fallback")
     from paper_2510_02676_amd import ecf8
 
-    layers = a.layers or {"config1": 32, "config3": 40, "config0": 1}[a.workload]
+    layers = a.layers or {"config1": 32, "config2": 256, "config3": 40, "config0": 1}[a.workload]
     batches, desc, t_setup = build_workload(a.workload, a.seed, a.lane_syms, layers, a.launch)
     hdrs = [t["hdr"] for _, ts in batches for t in ts]
     n_total = sum(h.n_elem for h in hdrs)

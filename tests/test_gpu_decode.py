@@ -156,3 +156,43 @@ def test_batch_argument_errors():
     with pytest.raises(ecf8.Ecf8Error) as e:
         ecf8.ecf8_decode(b64.header, d[0], torch.empty(5008, dtype=torch.uint8, device=DEV)[3:5003])
     assert e.value.code == ecf8.E_ALIGN
+
+
+# ---------------------------------------------------------------- full-size cases
+
+def _full_size_case(orc, specs, oracle_checks):
+    """Encode/ decode `specs` (full-size tensors, generated on the GPU) in ONE batched launch, the
+    launch configuration bench.py times.  Every output is compared with its input on the device
+    (decode(encode(x)) == x is the plain definition of the result); the tensors named in
+    `oracle_checks` are also compared with the oracle's own encode -> bit-serial decode."""
+    ts = []
+    for s in specs:
+        w = synth.make(s, 0, device=DEV)
+        b = ecf8.ecf8_encode(w.cpu(), s["rows"], s["cols"])
+        ts.append((s, w, b.header, b.to(DEV), torch.full_like(w, 0xEE)))
+    batch = ecf8.Batch([t[2] for t in ts], [t[3] for t in ts], [t[4] for t in ts])
+    ecf8.ecf8_decode_batched(batch)
+    torch.cuda.synchronize()
+    for s, w, h, _, out in ts:
+        assert torch.equal(out, w), s["name"]
+        if s["name"] in oracle_checks:
+            x = w.cpu().numpy().reshape(-1)
+            exp, nbits, _ = orc.roundtrip(x)
+            assert nbits == h.stream_bits
+            assert np.array_equal(out.cpu().numpy().reshape(-1), exp), s["name"]
+
+
+def test_config1_full_layer(orc):
+    """configs[1]: one full layer of the 8B-class stack (7 matrices, 218 M weights), one launch."""
+    _full_size_case(orc, synth.config1(0, 1), {"l0.k", "l0.q"})
+
+
+def test_config2_experts_and_attention(orc):
+    """configs[2]: six full-size expert matrices and the two attention projections in one launch."""
+    specs = synth.config2(0, 2)
+    _full_size_case(orc, specs, {"e0.gate", "e1.down"})
+
+
+def test_config3_full_block(orc):
+    """configs[3]: one full DiT block (11 matrices, 509 M weights, per-tensor scaling), one launch."""
+    _full_size_case(orc, synth.config3(1), {"b0.sa_q", "b0.ca_o"})
