@@ -222,3 +222,21 @@ def paper_alg1_roundtrip(x, T=256):
     return out, dict(lengths=ln, lut=lut, n_luts=int(n_luts.value), encoded=encoded,
                      n_bytes=int(nb2.value), packed=packed, outpos=outpos, gaps=gaps,
                      n_blocks=int(nbl2.value), stream_bits=bits)
+
+
+def e4m3_to_double(b):
+    lib().orc_e4m3_to_double.restype = ctypes.c_double
+    return float(lib().orc_e4m3_to_double(ctypes.c_uint8(int(b))))
+
+
+def gemm_ref(X, W):
+    """Y = X @ W.T for raw E4M3 bytes X (M, K), W (N, K) in fp64; returns (Y, sum |x w|)."""
+    X = np.ascontiguousarray(X, dtype=np.uint8)
+    W = np.ascontiguousarray(W, dtype=np.uint8)
+    M, K = X.shape
+    N, K2 = W.shape
+    assert K == K2
+    Y = np.zeros((M, N), dtype=np.float64)
+    A = np.zeros((M, N), dtype=np.float64)
+    lib().orc_gemm_ref(_p(X), _p(W), ctypes.c_uint64(M), ctypes.c_uint64(N), ctypes.c_uint64(K), _p(Y), _p(A))
+    return Y, A
