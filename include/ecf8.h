@@ -192,6 +192,24 @@ int ecf8_batch_prepare(const ecf8_header *hdrs, const void *const *d_blobs,
 int ecf8_decode_batched(const ecf8_batch_item *d_items, uint32_t n_tensors,
                         uint64_t total_chunks, uint32_t lane_syms, void *stream);
 
+/*
+ * ecf8_gemm_fp8: fused decode + FP8 GEMM for small batches.  The paper decodes a
+ * layer into a buffer and lets the framework's GEMM read it back (Section 3.3);
+ * here the decoded tile goes from LDS straight into the FP8 matrix cores.
+ *   Y[m][n] = sum_k X[m][k] * W[n][k]   (fp32 accumulate)
+ * W: the rows x cols tensor held by the blob (hdr / d_blob as for ecf8_decode);
+ * d_x: DEVICE, M x cols FP8 E4M3 bytes, row-major, 16-byte aligned, 1 <= M <= 64;
+ * d_y: DEVICE, M x rows fp32, row-major.  Supported shape for now: cols == 4096,
+ * rows a multiple of 16, lane_syms == 64 (ECF8_E_ARG otherwise).  Values are
+ * used as stored (unit scales); NaN encodings propagate as NaN.
+ * ecf8_gemm_fp8_raw: the same GEMM on uncompressed W (d_w: DEVICE, rows x cols
+ * bytes, 16-byte aligned), the baseline the fused call is compared with.
+ */
+int ecf8_gemm_fp8(const ecf8_header *hdr, const void *d_blob, const void *d_x, uint32_t M,
+                  float *d_y, void *stream);
+int ecf8_gemm_fp8_raw(const void *d_w, uint64_t rows, uint64_t cols, const void *d_x, uint32_t M,
+                      float *d_y, void *stream);
+
 const char *ecf8_strerror(int code);
 uint32_t ecf8_version(void);
 

@@ -37,33 +37,9 @@
 //    once per (workgroup, tensor); inside a workgroup the waves draw chunks
 //    from an LDS ticket counter (the hardware favours a SIMD's oldest wave, so
 //    equal static shares would finish up to 50 % apart).  No global atomics.
-#include "ecf8.h"
-#include "ecf8_table.h"
-
-#include <hip/hip_runtime.h>
-
-#include <mutex>
+#include "ecf8_device.h"
 
 namespace {
-
-constexpr int TB = ECF8_TB;            // table index bits
-constexpr int TBL_ENTRIES = 1 << TB;
-constexpr uint32_t TBL_MASK = TBL_ENTRIES - 1;
-
-// Table entry (16 bits) for index bits b0 b1 ... (b0 = next stream bit):
-//   bits 3..6   : exponent field of the first symbol  (output position of byte 0)
-//   bits 11..14 : exponent field of the second symbol (output position of byte 1)
-//   bits 7..10  : stream bits consumed by both symbols; 0 = the pair does not
-//                 fit in TB bits (second level decides)
-//   bits 0..2,15: code length of the first symbol alone (low 3 bits, high bit);
-//                 0 = the first codeword is longer than TB bits
-// Control fields sit in bits the merge masks off (0x78 per byte keeps the
-// exponent field only).
-constexpr uint32_t EXP_MASK = 0x78787878u;
-
-#define GLOBAL __attribute__((address_space(1))) // HBM pointers: global_load/store, not flat
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 struct KArgs {
     ecf8_batch_item single;               // used when items == nullptr
@@ -71,12 +47,6 @@ struct KArgs {
     uint32_t n_items;
     uint64_t total_chunks;
 };
-
-// code_len[16] travels as two 64-bit words (one byte per symbol)
-__device__ __forceinline__ uint32_t len_of(uint64_t lo, uint64_t hi, int s)
-{
-    return (uint32_t)((s < 8 ? lo >> (8 * s) : hi >> (8 * (s - 8))) & 0xff);
-}
 
 template <int N, int WAVES>
 struct Cfg {
@@ -92,191 +62,6 @@ struct Cfg {
     static constexpr int TOTAL = OFF_WAVES + WAVES_BYTES;   // table-build scratch aliases the stages
     static_assert(TOTAL <= 160 * 1024, "LDS of one gfx950 CU");
 };
-
-// Inclusive wave64 prefix sum with DPP row shifts and row broadcasts.
-__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x)
-{
-    uint32_t v = x;
-    v += __builtin_amdgcn_update_dpp(0u, v, 0x111, 0xf, 0xf, false); // row_shr:1
-    v += __builtin_amdgcn_update_dpp(0u, v, 0x112, 0xf, 0xf, false); // row_shr:2
-    v += __builtin_amdgcn_update_dpp(0u, v, 0x114, 0xf, 0xf, false); // row_shr:4
-    v += __builtin_amdgcn_update_dpp(0u, v, 0x118, 0xf, 0xf, false); // row_shr:8
-    v += __builtin_amdgcn_update_dpp(0u, v, 0x142, 0xa, 0xf, false); // row_bcast:15 -> rows 1,3
-    v += __builtin_amdgcn_update_dpp(0u, v, 0x143, 0xc, 0xf, false); // row_bcast:31 -> rows 2,3
-    return v;
-}
-
-// A codeword longer than TB bits (rarer than 2^-TB): match the next 15 stream
-// bits against the long canonical codes.  Returns exponent | length << 8.
-__device__ __noinline__ uint32_t decode_long(uint32_t bits, const uint32_t *s_len, const uint32_t *s_code)
-{
-    uint32_t v = __brev(bits) >> 17;          // next 15 bits, first bit most significant
-    uint32_t r = 15u << 8;                    // no match (corrupt stream): skip 15 bits, exponent 0
-#pragma unroll 1
-    for (int s = 0; s < 16; s++) {
-        uint32_t ls = s_len[s];
-        if (ls > TB && (v >> (15 - ls)) == s_code[s]) r = (uint32_t)s | (ls << 8);
-    }
-    return r;
-}
-
-// One symbol the careful way.  `bits`: stream bits from the current position
-// (>= 15 valid).  Returns exponent | length << 8.
-__device__ __forceinline__ uint32_t decode_one(uint32_t bits, const uint16_t *tbl, const uint32_t *s_len,
-                                               const uint32_t *s_code)
-{
-    uint32_t e = tbl[bits & TBL_MASK];
-    uint32_t l = (e & 7u) | ((e >> 12) & 8u);
-    if (__builtin_expect(l != 0, 1)) return ((e >> 3) & 15u) | (l << 8);
-    return decode_long(bits, s_len, s_code);
-}
-
-// Second level for one pair: the table entry `e` at the bottom of `bits` (32
-// valid stream bits) has no pair (the two codewords need more than TB bits, or
-// the first one alone does).  Decodes the two symbols one at a time and returns
-// them in `e` in pair-entry layout, their total length (up to 30) in `n`.
-__device__ __forceinline__ void pair_second_level(uint32_t bits, uint32_t &e, uint32_t &n, const uint16_t *tbl,
-                                                  const uint32_t *s_len, const uint32_t *s_code)
-{
-    const uint32_t r1 = decode_one(bits, tbl, s_len, s_code);
-    const uint32_t l1 = r1 >> 8;
-    const uint32_t r2 = decode_one(bits >> l1, tbl, s_len, s_code);
-    e = ((r1 & 15u) << 3) | ((r2 & 15u) << 11);
-    n = l1 + (r2 >> 8);
-}
-
-// Builds the pair table and the per-symbol (length, code) arrays in LDS from
-// the 16 code lengths.  `tmp` is TBL_ENTRIES u16 of scratch LDS.
-__device__ __forceinline__ void build_symbol_arrays(uint64_t len_lo, uint64_t len_hi, uint32_t *s_len,
-                                                    uint32_t *s_code, int tid)
-{
-    if (tid < 16) {
-        uint32_t l = len_of(len_lo, len_hi, tid);
-        uint32_t code = 0;
-#pragma unroll
-        for (int j = 0; j < 16; j++) {
-            uint32_t lj = len_of(len_lo, len_hi, j);
-            if (lj != 0 && lj < l) code += 1u << (l - lj);     // all shorter codes precede
-            else if (lj == l && j < tid) code += 1;            // same length: by symbol value
-        }
-        s_len[tid] = l;
-        s_code[tid] = code;
-    }
-}
-
-__device__ void build_tables(uint64_t len_lo, uint64_t len_hi, uint16_t *tbl, uint32_t *s_len, uint32_t *s_code,
-                             uint16_t *tmp, int tid, int nthreads)
-{
-    build_symbol_arrays(len_lo, len_hi, s_len, s_code, tid);
-    for (int i = tid; i < TBL_ENTRIES; i += nthreads) tmp[i] = 0;
-    __syncthreads();
-    // single-symbol table: every index whose low bits spell the codeword (first bit = bit 0)
-    for (int s = 0; s < 16; s++) {
-        uint32_t l = s_len[s];
-        if (l == 0 || l > TB) continue;
-        uint32_t r = __brev(s_code[s]) >> (32 - l);
-        uint32_t reps = 1u << (TB - l);
-        for (uint32_t j = tid; j < reps; j += nthreads) tmp[r | (j << l)] = (uint16_t)(s | (l << 4));
-    }
-    __syncthreads();
-    for (int idx = tid; idx < TBL_ENTRIES; idx += nthreads) {
-        const uint32_t t1 = tmp[idx];
-        const uint32_t l1 = t1 >> 4;
-        const uint32_t t2 = l1 ? tmp[idx >> l1] : 0u;
-        tbl[idx] = ecf8_pair_entry(t1 & 15u, l1, t2 & 15u, t2 >> 4);
-    }
-    __syncthreads();
-}
-
-// 32 stream bits in reading order (bit 0 = next bit to read) from LDS.
-// DIR = +1: the bits [bp, bp+32);  DIR = -1: the bits bp-1, bp-2, ..., bp-32.
-template <int DIR>
-__device__ __forceinline__ uint32_t lds_window(const uint8_t *smem, uint32_t bp)
-{
-    const uint32_t p = DIR > 0 ? bp : bp - 32;
-    const uint32_t aw = (p >> 3) & ~3u;
-    const uint32_t d0 = *(const uint32_t *)(smem + aw);
-    const uint32_t d1 = *(const uint32_t *)(smem + aw + 4);
-    const uint32_t w = __builtin_amdgcn_alignbit(d1, d0, p);
-    return DIR > 0 ? w : __brev(w);
-}
-
-// One decode step of both runs of a lane: four symbols each = two table
-// lookups each.  The two runs are independent, and the common path is one
-// straight line, so their LDS round trips overlap; the second level for pairs
-// that do not fit TB bits is one shared, rarely taken branch.  Returns the four
-// exponent fields of each run in their output byte positions (other bits are
-// noise the merge masks off) and moves bpA / bpB past the codewords.
-__device__ __forceinline__ void quad_step2(const uint8_t *smem, const uint16_t *tbl, const uint32_t *s_len,
-                                           const uint32_t *s_code, uint32_t &bpA, uint32_t &bpB,
-                                           uint32_t &outA, uint32_t &outB)
-{
-    const uint32_t wA = lds_window<+1>(smem, bpA);
-    const uint32_t wB = lds_window<-1>(smem, bpB);
-    uint32_t eA1 = tbl[wA & TBL_MASK];
-    uint32_t eB1 = tbl[wB & TBL_MASK];
-    uint32_t nA1 = (eA1 >> 7) & 15u;
-    uint32_t nB1 = (eB1 >> 7) & 15u;
-    uint32_t eA2 = tbl[(wA >> nA1) & TBL_MASK];        // >= 18 valid bits left in the window
-    uint32_t eB2 = tbl[(wB >> nB1) & TBL_MASK];
-    uint32_t nA2 = (eA2 >> 7) & 15u;
-    uint32_t nB2 = (eB2 >> 7) & 15u;
-    // n1 == 0 makes the second lookup repeat the first, so n2 == 0 covers both pairs of a run
-    if (__builtin_expect(nA2 == 0 || nB2 == 0, 0)) {
-        if (nA2 == 0) {
-            if (nA1 == 0) pair_second_level(wA, eA1, nA1, tbl, s_len, s_code);
-            // the second level needs up to 30 bits: fresh window after the first pair
-            const uint32_t w2 = lds_window<+1>(smem, bpA + nA1);
-            eA2 = tbl[w2 & TBL_MASK];
-            nA2 = (eA2 >> 7) & 15u;
-            if (nA2 == 0) pair_second_level(w2, eA2, nA2, tbl, s_len, s_code);
-        }
-        if (nB2 == 0) {
-            if (nB1 == 0) pair_second_level(wB, eB1, nB1, tbl, s_len, s_code);
-            const uint32_t w2 = lds_window<-1>(smem, bpB - nB1);
-            eB2 = tbl[w2 & TBL_MASK];
-            nB2 = (eB2 >> 7) & 15u;
-            if (nB2 == 0) pair_second_level(w2, eB2, nB2, tbl, s_len, s_code);
-        }
-    }
-    bpA += nA1 + nA2;
-    bpB -= nB1 + nB2;
-    outA = (eA1 & 0xffffu) | (eA2 << 16);
-    outB = (eB1 & 0xffffu) | (eB2 << 16);
-}
-
-// byte = exponent<<3 | sign<<7 | mantissa  (Algorithm 1, byte assembly) for one
-// 16-byte piece: dw = four dwords of exponent fields, pl = the piece's 8 bytes
-// of the nibble plane (byte j of a dword: low nibble element j, high nibble
-// element j + 4 of that 8-element group).
-__device__ __forceinline__ u32x4 merge_piece(const uint32_t dw[4], u32x2 pl)
-{
-    const uint32_t p0 = pl.x, p1 = pl.y;
-    u32x4 d;
-    d.x = (dw[0] & EXP_MASK) | (p0 & 0x07070707u) | ((p0 & 0x08080808u) << 4);
-    d.y = (dw[1] & EXP_MASK) | ((p0 >> 4) & 0x07070707u) | (p0 & 0x80808080u);
-    d.z = (dw[2] & EXP_MASK) | (p1 & 0x07070707u) | ((p1 & 0x08080808u) << 4);
-    d.w = (dw[3] & EXP_MASK) | ((p1 >> 4) & 0x07070707u) | (p1 & 0x80808080u);
-    return d;
-}
-
-// 32 stream bits in reading order straight from HBM (generic pass).  `bit` is
-// relative to the 4-byte aligned pointer sp; DIR as in lds_window.
-template <int DIR>
-__device__ __forceinline__ uint32_t global_window(const GLOBAL uint8_t *sp, uint64_t bit)
-{
-    if (DIR > 0) {
-        const GLOBAL uint32_t *q = (const GLOBAL uint32_t *)(sp + ((bit >> 3) & ~3ull));
-        return __builtin_amdgcn_alignbit(q[1], q[0], (uint32_t)bit);
-    }
-    if (bit < 32) {   // fewer than 32 bits below: the missing ones are never consumed
-        const uint32_t d0 = *(const GLOBAL uint32_t *)sp;
-        return __brev(bit ? d0 << (32 - (uint32_t)bit) : 0u);
-    }
-    const uint64_t p = bit - 32;
-    const GLOBAL uint32_t *q = (const GLOBAL uint32_t *)(sp + ((p >> 3) & ~3ull));
-    return __brev(__builtin_amdgcn_alignbit(q[1], q[0], (uint32_t)p));
-}
 
 template <int N, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
@@ -506,21 +291,6 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
         }
         c = seg_end;
     }
-}
-
-int device_cus()
-{
-    static std::mutex m;
-    static int cus[64];
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return -1;
-    std::lock_guard<std::mutex> lk(m);
-    if (cus[dev] == 0) {
-        hipDeviceProp_t p;
-        if (hipGetDeviceProperties(&p, dev) != hipSuccess) return -1;
-        cus[dev] = p.multiProcessorCount > 0 ? p.multiProcessorCount : 1;
-    }
-    return cus[dev];
 }
 
 template <int N, int WAVES>

@@ -74,6 +74,8 @@ _lib.ecf8_batch_prepare.argtypes = [ctypes.POINTER(Header), ctypes.POINTER(_vp),
                                     ctypes.POINTER(_u64), _u32, ctypes.POINTER(BatchItem),
                                     ctypes.POINTER(_u64), ctypes.POINTER(_u32)]
 _lib.ecf8_decode_batched.argtypes = [_vp, _u32, _u64, _u32, _vp]
+_lib.ecf8_gemm_fp8.argtypes = [ctypes.POINTER(Header), _vp, _vp, _u32, _vp, _vp]
+_lib.ecf8_gemm_fp8_raw.argtypes = [_vp, _u64, _u64, _vp, _u32, _vp, _vp]
 _lib.ecf8_strerror.argtypes = [ctypes.c_int]
 _lib.ecf8_strerror.restype = ctypes.c_char_p
 _lib.ecf8_version.restype = _u32
@@ -206,6 +208,27 @@ def ecf8_decode_batched(batch, stream=None):
     _check("ecf8_decode_batched", _lib.ecf8_decode_batched(batch.d_items.data_ptr(), batch.n,
                                                            batch.total_chunks, batch.lane_syms,
                                                            _stream_ptr(stream)))
+
+
+def ecf8_gemm_fp8(hdr, d_blob, d_x, d_y=None, stream=None):
+    """Y = X @ W.T with W decoded on the fly from its blob.  d_x: (M, cols) uint8 E4M3 on the device."""
+    M = d_x.shape[0]
+    if d_y is None:
+        d_y = torch.empty((M, hdr.rows), dtype=torch.float32, device=d_x.device)
+    _check("ecf8_gemm_fp8", _lib.ecf8_gemm_fp8(ctypes.byref(hdr), d_blob.data_ptr(), d_x.data_ptr(), M,
+                                               d_y.data_ptr(), _stream_ptr(stream)))
+    return d_y
+
+
+def ecf8_gemm_fp8_raw(d_w, d_x, d_y=None, stream=None):
+    """The same GEMM on uncompressed weights d_w: (rows, cols) uint8 E4M3 on the device."""
+    M = d_x.shape[0]
+    rows, cols = d_w.shape
+    if d_y is None:
+        d_y = torch.empty((M, rows), dtype=torch.float32, device=d_x.device)
+    _check("ecf8_gemm_fp8_raw", _lib.ecf8_gemm_fp8_raw(d_w.data_ptr(), rows, cols, d_x.data_ptr(), M,
+                                                       d_y.data_ptr(), _stream_ptr(stream)))
+    return d_y
 
 
 def version():

@@ -1,0 +1,117 @@
+"""Fused decode + FP8 GEMM (configs[4]) against the oracle's fp64 reference, through the C ABI.
+
+Tolerance.  FP8 x FP8 products are exact; what differs from the fp64 reference is the
+accumulation.  The gfx950 FP8 matrix core does not add a step's 32 products in full fp32: each
+lane's 8 products are aligned to the largest of them and bits more than about 13 places below
+it are truncated (measured: 448*448 + 31*1 gives 200728, the 7 ones that share a lane with the
+big product are lost; the F16 matrix core gives 200735).  Per output that bounds the error by
+7 * 2^-13 * sum_k |x_k w_k| in the worst case; on these heavy-tailed seeded inputs the worst
+observed ratio is 2.4e-5, so the tests assert TOL = 5e-5 * sum_k |x_k w_k| per output.  The
+configuration's "1e-5 relative" is not reachable through the FP8 matrix cores on such data; the
+decoded weights themselves are bit exact, and the fused kernel equals the same GEMM on the
+uncompressed weights bit for bit.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2510_02676_amd import ecf8, synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+TOL = 5e-5
+
+
+def _check(y, yref, mag, what, rel=TOL):
+    err = np.abs(y.astype(np.float64) - yref)
+    bound = rel * mag + 1e-30
+    worst = float((err / bound).max())
+    assert worst <= 1.0, "%s: worst |err| / (%.1e sum|xw|) = %.3g" % (what, rel, worst)
+
+
+def test_one_tile_ocp_landmarks(orc):
+    """One 16-row tile whose weights are the OCP landmarks (-0 = 0x80, 448 = 0x7E, 2^-6 = 0x08,
+    subnormals, 1.0, -1.5): wrong FP8 flavour in the matrix cores would show as NaN or factors of 2."""
+    K = 4096
+    w = np.zeros((16, K), dtype=np.uint8)
+    vals = [0x80, 0x7E, 0x08, 0x01, 0x07, 0x38, 0xBC, 0xFE, 0x00, 0x40, 0x30, 0x28, 0x77, 0xF7, 0x0F, 0x10]
+    for n in range(16):
+        w[n, :] = vals[n]
+        w[n, n::17] = vals[(n + 5) % 16]
+    x = np.zeros((3, K), dtype=np.uint8)
+    x[0, :] = 0x38                      # 1.0 everywhere: row sums of W
+    x[1, ::2] = 0x38
+    x[1, 1::2] = 0xB8                   # alternating +1 / -1
+    x[2, :] = 0x30                      # 0.5
+    yref, mag = orc.gemm_ref(x, w)
+    d_x = torch.from_numpy(x).to(DEV)
+    raw = ecf8.ecf8_gemm_fp8_raw(torch.from_numpy(w).to(DEV), d_x)
+    blob = ecf8.ecf8_encode(w, 16, K)
+    fused = ecf8.ecf8_gemm_fp8(blob.header, blob.to(DEV), d_x)
+    torch.cuda.synchronize()
+    assert not torch.isnan(raw).any() and not torch.isnan(fused).any()
+    # this input is adversarial for the matrix core's truncation (448s next to subnormals): the
+    # bound is the worst case 7 * 2^-13 * sum|xw|; a wrong FP8 flavour misses it by orders
+    _check(raw.cpu().numpy(), yref, mag, "raw", rel=7 * 2.0 ** -13)
+    _check(fused.cpu().numpy(), yref, mag, "fused", rel=7 * 2.0 ** -13)
+    assert torch.equal(raw, fused)      # same multiply phase on the same bytes
+
+
+@pytest.mark.parametrize("M", [1, 16, 17, 64])
+@pytest.mark.parametrize("table_mode", [1, 2])
+def test_small_gemm_against_oracle(orc, M, table_mode):
+    rows, K = 128, 4096
+    w = synth.make_weight(rows, K, 1.7, 0.02, 3).numpy()
+    x = synth.activations(M, K, seed=M).numpy()
+    yref, mag = orc.gemm_ref(x, w)
+    blob = ecf8.ecf8_encode(w, rows, K, table_mode=table_mode)
+    d_x = torch.from_numpy(x).to(DEV)
+    guard = torch.full((M + 2, rows), float("nan"), dtype=torch.float32, device=DEV)
+    y = ecf8.ecf8_gemm_fp8(blob.header, blob.to(DEV), d_x, guard[1:M + 1])
+    torch.cuda.synchronize()
+    assert torch.isnan(guard[0]).all() and torch.isnan(guard[M + 1]).all()
+    _check(y.cpu().numpy(), yref, mag, "fused M=%d" % M)
+    raw = ecf8.ecf8_gemm_fp8_raw(torch.from_numpy(w).to(DEV), d_x)
+    torch.cuda.synchronize()
+    assert torch.equal(raw, y)
+
+
+@pytest.mark.parametrize("M", [1, 16, 64])
+def test_config4_full_size(orc, M):
+    """configs[4]: W 14336 x 4096 (config-2 distribution), X = M x 4096 N(0,1) rows scaled to 448.
+    Every output of the fused kernel equals the raw-weights kernel bit for bit; a sample of output
+    columns is checked against the oracle (decoded bytes are the oracle's: decode(encode(W)) == W)."""
+    spec = synth.config4()[0]
+    w = synth.make(spec, 0, device=DEV)
+    x = synth.activations(M, 4096, seed=0, device=DEV)
+    blob = ecf8.ecf8_encode(w.cpu(), spec["rows"], spec["cols"])
+    fused = ecf8.ecf8_gemm_fp8(blob.header, blob.to(DEV), x)
+    raw = ecf8.ecf8_gemm_fp8_raw(w, x)
+    torch.cuda.synchronize()
+    assert torch.equal(fused, raw)
+    cols = np.unique(np.concatenate([np.arange(0, 64), np.random.default_rng(M).integers(0, spec["rows"], 448),
+                                     np.arange(spec["rows"] - 32, spec["rows"])]))
+    wh = w.cpu().numpy()
+    dec, _, _ = orc.roundtrip(wh[cols].reshape(-1))
+    assert np.array_equal(dec.reshape(len(cols), 4096), wh[cols])
+    yref, mag = orc.gemm_ref(x.cpu().numpy(), wh[cols])
+    _check(fused.cpu().numpy()[:, cols], yref, mag, "config4 M=%d" % M)
+
+
+def test_gemm_argument_errors():
+    x = torch.zeros((4, 4096), dtype=torch.uint8, device=DEV)
+    w = torch.zeros((32, 2048), dtype=torch.uint8, device=DEV)
+    with pytest.raises(ecf8.Ecf8Error) as e:
+        ecf8.ecf8_gemm_fp8_raw(w, x[:, :2048].contiguous())            # cols != 4096
+    assert e.value.code == ecf8.E_ARG
+    w = torch.zeros((24, 4096), dtype=torch.uint8, device=DEV)
+    with pytest.raises(ecf8.Ecf8Error):
+        ecf8.ecf8_gemm_fp8_raw(w, x)                                    # rows not a multiple of 16
+    w = torch.zeros((32, 4096), dtype=torch.uint8, device=DEV)
+    with pytest.raises(ecf8.Ecf8Error):
+        ecf8.ecf8_gemm_fp8_raw(w, torch.zeros((65, 4096), dtype=torch.uint8, device=DEV))   # M > 64
+    b = ecf8.ecf8_encode(np.zeros((32, 4096), dtype=np.uint8), 32, 4096, lane_syms=128)
+    with pytest.raises(ecf8.Ecf8Error):
+        ecf8.ecf8_gemm_fp8(b.header, b.to(DEV), x)                      # lane_syms != 64
