@@ -121,16 +121,8 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
         const GLOBAL uint8_t *plane = (const GLOBAL uint8_t *)(d_blob + off_pl);
 
         __syncthreads(); // every wave is done with the previous tensor's table and its scratch
-        if (tid == 0) { *s_ticket = 0; *s_oversize = 0; }
-        if (off_tbl) {
-            // the encoder embedded the table: copy it (L2-resident after the first workgroup)
-            const GLOBAL u32x4 *src = (const GLOBAL u32x4 *)(d_blob + off_tbl);
-            for (int i = tid; i < TBL_ENTRIES * 2 / 16; i += WAVES * 64) ((u32x4 *)tbl)[i] = src[i];
-            build_symbol_arrays(len_lo, len_hi, s_len, s_code, tid);
-            __syncthreads();
-        } else {
-            build_tables(len_lo, len_hi, tbl, s_len, s_code, (uint16_t *)(smem + C::OFF_WAVES), tid, WAVES * 64);
-        }
+        // the first two chunks of a wave are fixed (c + wave, c + WAVES + wave); later ones are drawn
+        if (tid == 0) { *s_ticket = 2 * WAVES; *s_oversize = 0; }
 
         // Per-wave software pipeline over its chunks cg = c + wave, + WAVES, ...:
         // metadata is loaded two chunks ahead, stream span and nibble plane one chunk
@@ -185,14 +177,44 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
             return c + __builtin_amdgcn_readfirstlane(t);
         };
 
-        uint64_t cg = draw();
+        // Start-up: the loads of the table, of the first chunks' metadata and of the first chunk's
+        // payload are all in flight before the table is written to LDS, so a workgroup pays about
+        // two HBM round trips, not four, before its first decode step.
+        uint64_t cg = c + wave;
+        uint64_t cg1 = cg + WAVES;
+        uint64_t cg2 = fast_end;    // drawn when cg1 is taken up
+        u32x4 tv[(TBL_ENTRIES * 2 / 16 + WAVES * 64 - 1) / (WAVES * 64)];
+        if (off_tbl) {
+            // the encoder embedded the table: copy it (L2-resident after the first workgroup)
+            const GLOBAL u32x4 *src = (const GLOBAL u32x4 *)(d_blob + off_tbl);
+#pragma unroll
+            for (int j = 0; j < (int)(sizeof(tv) / sizeof(tv[0])); j++) {
+                const int i = tid + j * WAVES * 64;
+                tv[j] = u32x4{0, 0, 0, 0};
+                if (i < TBL_ENTRIES * 2 / 16) tv[j] = src[i];
+            }
+        }
+        Meta m_cur{0, 0, 0}, m_next{0, 0, 0};
+        Payload p_cur;
         if (cg < fast_end) {
-            Meta m_cur = load_meta(cg - first_chunk);
-            Payload p_cur = issue_payload(cg - first_chunk, m_cur);
-            uint64_t cg1 = draw();
-            uint64_t cg2 = fast_end;    // drawn when cg1 is taken up
-            Meta m_next = m_cur;
+            m_cur = load_meta(cg - first_chunk);
+            m_next = m_cur;
             if (cg1 < fast_end) m_next = load_meta(cg1 - first_chunk);
+            p_cur = issue_payload(cg - first_chunk, m_cur);
+        }
+        if (off_tbl) {
+#pragma unroll
+            for (int j = 0; j < (int)(sizeof(tv) / sizeof(tv[0])); j++) {
+                const int i = tid + j * WAVES * 64;
+                if (i < TBL_ENTRIES * 2 / 16) ((u32x4 *)tbl)[i] = tv[j];
+            }
+            build_symbol_arrays(len_lo, len_hi, s_len, s_code, tid);
+            __syncthreads();
+        } else {
+            build_tables(len_lo, len_hi, tbl, s_len, s_code, (uint16_t *)(smem + C::OFF_WAVES), tid, WAVES * 64);
+        }
+
+        if (cg < fast_end) {
             // Drain the prologue's loads here (vmcnt(0), other counters untouched), so that
             // the wait at the loop head is decided by the back edge alone, where the four
             // stores of the previous chunk are younger than the prefetch and stay in flight.
@@ -311,7 +333,7 @@ int dispatch(const KArgs &a, uint32_t lane_syms, hipStream_t s)
     switch (lane_syms) {
     case 32: return launch<32, 16>(a, 1, s);
     case 64: return launch<64, 16>(a, 1, s);
-    case 128: return launch<128, 8>(a, 1, s);
+    case 128: return launch<128, 12>(a, 1, s);
     default: return ECF8_E_ARG;
     }
 }

@@ -214,7 +214,7 @@ int ecf8_encode(const uint8_t *x, uint64_t rows, uint64_t cols, const ecf8_encod
     if (!x || !out || rows == 0 || cols == 0) return ECF8_E_ARG;
     if (rows > (1ull << 40) / cols) return ECF8_E_ARG;
     const uint64_t n = rows * cols;
-    const uint32_t N = (opts && opts->lane_syms) ? opts->lane_syms : 64;
+    const uint32_t N = (opts && opts->lane_syms) ? opts->lane_syms : 128;
     if (!lane_syms_ok(N)) return ECF8_E_ARG;
     unsigned nt = (opts && opts->n_threads) ? opts->n_threads : std::thread::hardware_concurrency();
     if (nt == 0) nt = 1;

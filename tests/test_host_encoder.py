@@ -93,7 +93,7 @@ def test_hand_example_bytes_in_the_product_container():
     b = ecf8.ecf8_encode(x, 2, 2)
     a, h = b.numpy(), b.header
     assert h.stream_bits == 4 and h.rows == 2 and h.cols == 2
-    assert a[h.off_stream] == 0x07
+    assert h.lane_syms == 128 and a[h.off_stream] == 0x07
     assert list(a[h.off_plane:h.off_plane + 4]) == [0x00, 0x08, 0x04, 0x00]
 
 
