@@ -35,7 +35,7 @@ def algorithmic_bytes(h):
     return rd, h.n_elem
 
 
-def build_workload(name, seed, lane_syms, layers, launch="layer"):
+def build_workload(name, seed, lane_syms, layers, launch="layer", group_chunks=0):
     from paper_2510_02676_amd import ecf8, synth
     if name == "config1":
         specs = synth.config1(seed, layers)
@@ -60,7 +60,7 @@ def build_workload(name, seed, lane_syms, layers, launch="layer"):
     t0 = time.time()
     for s in specs:
         w = synth.make(s, seed, device=dev)                       # uint8 (rows, cols) on the GPU
-        blob = ecf8.ecf8_encode(w.cpu(), s["rows"], s["cols"], lane_syms=lane_syms)
+        blob = ecf8.ecf8_encode(w.cpu(), s["rows"], s["cols"], lane_syms=lane_syms, group_chunks=group_chunks)
         d_blob = blob.to(dev)
         d_out = torch.empty((s["rows"], s["cols"]), dtype=torch.uint8, device=dev)
         groups.setdefault(group(s), []).append(dict(spec=s, w=w, hdr=blob.header, d_blob=d_blob, d_out=d_out))
@@ -166,7 +166,7 @@ def bench_config4(a):
 
     spec = synth.config4()[0]
     w = synth.make(spec, a.seed, device="cuda:0")
-    blob = ecf8.ecf8_encode(w.cpu(), spec["rows"], spec["cols"], lane_syms=64)
+    blob = ecf8.ecf8_encode(w.cpu(), spec["rows"], spec["cols"], lane_syms=64, group_chunks=1)
     h, d_blob, wout = blob.header, blob.to("cuda:0"), torch.empty_like(w)
     res = {}
     for M in (1, 16, 64):
@@ -206,6 +206,7 @@ def main():
     ap.add_argument("--workload", default="config1")
     ap.add_argument("--layers", type=int, default=0, help="0 = the full stack of the workload")
     ap.add_argument("--lane-syms", type=int, default=0, help="0 = library default")
+    ap.add_argument("--group-chunks", type=int, default=0, help="chunks interleaved per group, 0 = library default")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--launch", default="stack", choices=["layer", "stack"],
                     help="stack: the whole stack in one launch per step; "
@@ -226,7 +227,7 @@ def main():
     if a.workload == "config4":
         return bench_config4(a)
     layers = a.layers or {"config1": 32, "config2": 256, "config3": 40, "config0": 1}[a.workload]
-    batches, desc, t_setup = build_workload(a.workload, a.seed, a.lane_syms, layers, a.launch)
+    batches, desc, t_setup = build_workload(a.workload, a.seed, a.lane_syms, layers, a.launch, a.group_chunks)
     hdrs = [t["hdr"] for _, ts in batches for t in ts]
     n_total = sum(h.n_elem for h in hdrs)
     blob_total = sum(h.total_size for h in hdrs)
@@ -274,6 +275,7 @@ def main():
         "dtype": "u8", "data": "synthetic",
         "config": {"workload": "%s: %s" % (a.workload, desc), "weights": n_total,
                    "launches_per_step": len(batches), "launch": a.launch, "lane_syms": hdrs[0].lane_syms,
+                   "group_chunks": hdrs[0].group_chunks,
                    "seed": a.seed},
         "compression_ratio": round(blob_total / n_total, 5),
         "memory_saving_pct": round(100 * (1 - blob_total / n_total), 2),

@@ -80,6 +80,17 @@ def huffman_lengths(freq):
     return ln
 
 
+def huffman_lengths_limited(freq, max_len):
+    """Cheapest prefix code with every length <= max_len (exhaustive search)."""
+    freq = np.ascontiguousarray(freq, dtype=np.uint64)
+    assert freq.size == 16
+    ln = np.zeros(16, dtype=np.uint8)
+    rc = lib().orc_huffman_lengths_limited(_p(freq), ctypes.c_int(max_len), _p(ln))
+    if rc < 0:
+        raise ValueError("orc_huffman_lengths_limited: %d" % rc)
+    return ln
+
+
 def canonical_codes(lengths):
     lengths = np.ascontiguousarray(lengths, dtype=np.uint8)
     code = np.zeros(16, dtype=np.uint16)
@@ -143,14 +154,16 @@ def roundtrip(x):
     return out, int(nbits.value), ln
 
 
-def container_encode(x, rows, cols, lane_syms):
+def container_encode(x, rows, cols, lane_syms, group_chunks=1, max_code_len=15):
     x = _u8(x)
     assert x.size == rows * cols
     cap = int(lib().orc_container_size(x.size, x.size * 15, lane_syms)) + 256
     blob = np.zeros(cap, dtype=np.uint8)
     size = ctypes.c_uint64(0)
     rc = lib().orc_container_encode(_p(x), ctypes.c_uint64(rows), ctypes.c_uint64(cols),
-                                    ctypes.c_uint32(lane_syms), _p(blob), ctypes.c_uint64(cap),
+                                    ctypes.c_uint32(lane_syms), ctypes.c_uint32(group_chunks),
+                                    ctypes.c_uint32(max_code_len), _p(blob),
+                                    ctypes.c_uint64(cap),
                                     ctypes.byref(size))
     if rc:
         raise ValueError("orc_container_encode: %d" % rc)

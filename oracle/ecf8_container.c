@@ -15,7 +15,8 @@
  *     0   u32 magic 0x38464345 ("ECF8")     4   u32 version (1)
  *     8   u64 total_size                    16  u64 n_elem
  *     24  u64 rows                          32  u64 cols
- *     40  u32 lane_syms N                   44  u32 table_bits (0 or 14)
+ *     40  u32 lane_syms N                   44  u16 table_bits (0 or 14)
+ *     46  u16 group_chunks G (power of two, 1..64)
  *     48  u64 n_chunks = ceil(n_elem/(64N)) 56  u64 stream_bits
  *     64  u8  code_len[16]
  *     80  u64 off_chunk_bit   88 u64 off_lane_bits
@@ -37,8 +38,13 @@
  *               of chunk c owns bits [S, S + lane_bits) where S = chunk_bit[c]
  *               + the lane_bits of the chunk's earlier lanes.  The k-th
  *               symbol (k = 0..N-1) of the lane is element
- *               c*64N + ((k/16)*64 + l)*16 + k%16; elements >= n_elem do not
- *               exist and are skipped.  Symbols k < N/2 are coded FORWARD from
+ *               base(c) + (k/16)*stride(c) + l*16 + k%16, where, with
+ *               F = n_elem / (G*64N) whole groups of G chunks,
+ *                 c <  G*F: base = (c - c%G)*64N + (c%G)*1024, stride = G*1024
+ *                 c >= G*F: base = c*64N,                      stride = 1024
+ *               (inside a whole group the 1024-element blocks of its G chunks
+ *               alternate; the rest of the tensor is chunk after chunk);
+ *               elements >= n_elem do not exist and are skipped.  Symbols k < N/2 are coded FORWARD from
  *               bit S upwards (a codeword's first = most significant bit at
  *               the lowest position); symbols k >= N/2 are coded BACKWARD from
  *               bit S + lane_bits - 1 downwards (first bit at the highest
@@ -69,6 +75,7 @@ void orc_split(uint8_t v, uint8_t *s, uint8_t *e, uint8_t *m);
 uint8_t orc_join(uint8_t s, uint8_t e, uint8_t m);
 void orc_histogram(const uint8_t *x, uint64_t n, uint64_t freq[ORC_NSYM]);
 int orc_huffman_lengths(const uint64_t freq[ORC_NSYM], uint8_t len[ORC_NSYM]);
+int orc_huffman_lengths_limited(const uint64_t freq[ORC_NSYM], int lmax, uint8_t len[ORC_NSYM]);
 int orc_canonical_codes(const uint8_t len[ORC_NSYM], uint16_t code[ORC_NSYM]);
 uint64_t orc_stream_bits(const uint64_t freq[ORC_NSYM], const uint8_t len[ORC_NSYM]);
 int orc_decode_symbols_dir(const uint8_t *stream, int64_t start, int dir, int64_t lo, int64_t hi,
@@ -91,10 +98,21 @@ static void wr32(uint8_t *p, uint32_t v) { for (int i = 0; i < 4; i++) p[i] = (u
 static void wr16(uint8_t *p, uint32_t v) { p[0] = (uint8_t)v; p[1] = (uint8_t)(v >> 8); }
 static uint64_t up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 
-/* element coded by the k-th symbol of lane l of chunk c */
-static uint64_t lane_element(uint64_t c, uint64_t l, uint64_t k, uint32_t N)
+/* element coded by the k-th symbol of lane l of chunk c of an n-element tensor */
+static uint64_t lane_element(uint64_t c, uint64_t l, uint64_t k, uint32_t N, uint32_t G, uint64_t n)
 {
-    return c * 64ull * N + ((k / 16) * 64 + l) * 16 + (k % 16);
+    uint64_t chunk = 64ull * N;
+    uint64_t whole_groups = n / (G * chunk);
+    uint64_t base, stride;
+    if (c < G * whole_groups) {
+        uint64_t slot = c % G;
+        base = (c - slot) * chunk + slot * 1024;
+        stride = (uint64_t)G * 1024;
+    } else {
+        base = c * chunk;
+        stride = 1024;
+    }
+    return base + (k / 16) * stride + l * 16 + (k % 16);
 }
 
 static uint64_t plane_byte_index(uint64_t i) { return (i / 8) * 4 + (i % 4); }
@@ -116,16 +134,19 @@ uint64_t orc_container_size(uint64_t n, uint64_t stream_bits, uint32_t N)
 
 /* Writer: encodes x (rows*cols raw E4M3 bytes) into blob (capacity cap).
  * Follows Section 3.1 for histogram, optimal code and in-order stream. */
-int orc_container_encode(const uint8_t *x, uint64_t rows, uint64_t cols, uint32_t N,
-                         uint8_t *blob, uint64_t cap, uint64_t *size_out)
+int orc_container_encode(const uint8_t *x, uint64_t rows, uint64_t cols, uint32_t N, uint32_t G,
+                         uint32_t max_code_len, uint8_t *blob, uint64_t cap, uint64_t *size_out)
 {
     uint64_t n = rows * cols;
     if (n == 0 || N == 0 || (N % 16) != 0 || N > 256) return ORC_E_ARG;
+    if (G == 0 || G > 64 || (G & (G - 1))) return ORC_E_ARG;
     uint64_t freq[ORC_NSYM];
     uint8_t len[ORC_NSYM];
     uint16_t code[ORC_NSYM];
     orc_histogram(x, n, freq);
-    int rc = orc_huffman_lengths(freq, len);
+    /* max_code_len >= 15 never binds with 16 symbols: plain Huffman (Section 3.1) */
+    int rc = max_code_len >= 15 ? orc_huffman_lengths(freq, len)
+                                : orc_huffman_lengths_limited(freq, (int)max_code_len, len);
     if (rc < 0) return rc;
     rc = orc_canonical_codes(len, code);
     if (rc) return rc;
@@ -150,7 +171,8 @@ int orc_container_encode(const uint8_t *x, uint64_t rows, uint64_t cols, uint32_
     wr64(blob + 24, rows);
     wr64(blob + 32, cols);
     wr32(blob + 40, N);
-    wr32(blob + 44, 0); /* this writer embeds no decoder table */
+    wr16(blob + 44, 0); /* this writer embeds no decoder table */
+    wr16(blob + 46, G);
     wr64(blob + 48, n_chunks);
     wr64(blob + 56, bits);
     for (int i = 0; i < ORC_NSYM; i++) blob[64 + i] = len[i];
@@ -171,7 +193,7 @@ int orc_container_encode(const uint8_t *x, uint64_t rows, uint64_t cols, uint32_
         for (uint64_t l = 0; l < 64; l++) {
             uint64_t lb = 0;
             for (uint64_t k = 0; k < N; k++) {
-                uint64_t e = lane_element(c, l, k, N);
+                uint64_t e = lane_element(c, l, k, N, G, n);
                 if (e >= n) continue;
                 uint8_t sg, ex, mn;
                 orc_split(x[e], &sg, &ex, &mn);
@@ -179,7 +201,7 @@ int orc_container_encode(const uint8_t *x, uint64_t rows, uint64_t cols, uint32_
             }
             uint64_t fwd = pos, bwd = pos + lb; /* bwd: one past the next bit to write */
             for (uint64_t k = 0; k < N; k++) {
-                uint64_t e = lane_element(c, l, k, N);
+                uint64_t e = lane_element(c, l, k, N, G, n);
                 if (e >= n) continue;
                 uint8_t sg, ex, mn;
                 orc_split(x[e], &sg, &ex, &mn);
@@ -223,7 +245,7 @@ int orc_container_decode(const uint8_t *blob, uint64_t size, uint8_t *out, uint6
     if (rd32(blob) != 0x38464345u || rd32(blob + 4) != 1) return ORC_E_FORMAT;
     uint64_t total = rd64(blob + 8), n = rd64(blob + 16);
     uint64_t rows = rd64(blob + 24), cols = rd64(blob + 32);
-    uint32_t N = rd32(blob + 40), TBITS = rd32(blob + 44);
+    uint32_t N = rd32(blob + 40), TBITS = rd16(blob + 44), G = rd16(blob + 46);
     uint64_t n_chunks = rd64(blob + 48), bits = rd64(blob + 56);
     uint8_t len[ORC_NSYM];
     for (int i = 0; i < ORC_NSYM; i++) len[i] = blob[64 + i];
@@ -232,6 +254,7 @@ int orc_container_decode(const uint8_t *blob, uint64_t size, uint8_t *out, uint6
     uint64_t st_bytes = rd64(blob + 112), pl_bytes = rd64(blob + 120);
     if (total != size || n == 0 || rows * cols != n) return ORC_E_FORMAT;
     if ((TBITS != 0 && TBITS != 14) || N == 0 || (N % 16) != 0 || N > 256) return ORC_E_FORMAT;
+    if (G == 0 || G > 64 || (G & (G - 1))) return ORC_E_FORMAT;
     uint64_t tbytes = TBITS ? (2ull << TBITS) : 0;
     uint64_t chunk = 64ull * N;
     if (n_chunks != (n + chunk - 1) / chunk) return ORC_E_FORMAT;
@@ -293,7 +316,7 @@ int orc_container_decode(const uint8_t *blob, uint64_t size, uint8_t *out, uint6
         for (uint64_t l = 0; l < 64 && rc == ORC_OK; l++) {
             uint64_t cntA = 0, cntB = 0;
             for (uint64_t k = 0; k < N; k++)
-                if (lane_element(c, l, k, N) < n) { if (k < N / 2) cntA++; else cntB++; }
+                if (lane_element(c, l, k, N, G, n) < n) { if (k < N / 2) cntA++; else cntB++; }
             uint64_t lb = rd16(blob + off_lb + 2 * (c * 64 + l));
             if (cntA + cntB == 0) { if (lb != 0) rc = ORC_E_META; continue; }
             if (pos + lb > bits) { rc = ORC_E_META; break; }
@@ -306,7 +329,7 @@ int orc_container_decode(const uint8_t *blob, uint64_t size, uint8_t *out, uint6
             if (r2 || endA != endB + 1) { rc = ORC_E_META; break; }
             uint64_t j = 0;
             for (uint64_t k = 0; k < N; k++) {
-                uint64_t e = lane_element(c, l, k, N);
+                uint64_t e = lane_element(c, l, k, N, G, n);
                 if (e < n) { sym[e] = lane_sym[j++]; done++; }
             }
             pos += lb;

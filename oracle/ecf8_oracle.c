@@ -144,6 +144,79 @@ int orc_huffman_lengths(const uint64_t freq[ORC_NSYM], uint8_t len[ORC_NSYM])
 }
 
 /* ------------------------------------------------------------------ */
+/* O3b: code lengths under a cap (Section 3.1 caps the code length and  */
+/* adjusts the frequencies to get there; the reading taken here is the  */
+/* best any such adjustment can reach): among all prefix codes with     */
+/* every length <= lmax, one that minimises sum f(x) * len(x).  Written */
+/* out as a search: in a cheapest code a more frequent symbol is never  */
+/* longer than a less frequent one (swapping the two would not cost     */
+/* more), so it is enough to walk the symbols from most to least        */
+/* frequent, try every non-decreasing length sequence whose Kraft sum   */
+/* stays <= 1, and keep the cheapest.  One distinct symbol: length 1.   */
+/* Returns the maximum length, or a negative error (lmax too small for  */
+/* the number of symbols, lmax > 15).                                   */
+/* ------------------------------------------------------------------ */
+typedef struct {
+    int k, lmax;
+    uint64_t f[ORC_NSYM];
+    int cur[ORC_NSYM], best[ORC_NSYM];
+    uint64_t best_cost;
+    int found;
+} orc_ll_search;
+
+static void orc_ll_walk(orc_ll_search *S, int i, int minlen, uint64_t used, uint64_t cost)
+{
+    /* used: Kraft sum so far in units of 2^-lmax */
+    const uint64_t cap = 1ull << S->lmax;
+    if (S->found && cost >= S->best_cost) return;
+    if (i == S->k) {
+        S->best_cost = cost;
+        S->found = 1;
+        for (int j = 0; j < S->k; j++) S->best[j] = S->cur[j];
+        return;
+    }
+    for (int l = minlen; l <= S->lmax; l++) {
+        uint64_t u = used + (1ull << (S->lmax - l));
+        /* every later symbol needs at least one unit */
+        if (u + (uint64_t)(S->k - i - 1) > cap) continue;
+        S->cur[i] = l;
+        orc_ll_walk(S, i + 1, l, u, cost + S->f[i] * (uint64_t)l);
+    }
+}
+
+int orc_huffman_lengths_limited(const uint64_t freq[ORC_NSYM], int lmax, uint8_t len[ORC_NSYM])
+{
+    orc_ll_search S;
+    int order[ORC_NSYM];
+    S.k = 0;
+    for (int i = 0; i < ORC_NSYM; i++) {
+        len[i] = 0;
+        if (freq[i] > 0) order[S.k++] = i;
+    }
+    if (S.k == 0 || lmax < 1 || lmax > 15) return ORC_E_ARG;
+    if (S.k == 1) { len[order[0]] = 1; return 1; }
+    if ((1 << lmax) < S.k) return ORC_E_ARG;
+    /* most frequent first (insertion sort, ties by symbol value) */
+    for (int a = 1; a < S.k; a++) {
+        int v = order[a], b = a - 1;
+        while (b >= 0 && freq[order[b]] < freq[v]) { order[b + 1] = order[b]; b--; }
+        order[b + 1] = v;
+    }
+    for (int j = 0; j < S.k; j++) S.f[j] = freq[order[j]];
+    S.lmax = lmax;
+    S.found = 0;
+    S.best_cost = 0;
+    orc_ll_walk(&S, 0, 1, 0, 0);
+    if (!S.found) return ORC_E_ARG;
+    int maxlen = 0;
+    for (int j = 0; j < S.k; j++) {
+        len[order[j]] = (uint8_t)S.best[j];
+        if (S.best[j] > maxlen) maxlen = S.best[j];
+    }
+    return maxlen;
+}
+
+/* ------------------------------------------------------------------ */
 /* O4: canonical code assignment.  The paper leaves the 0/1 labelling  */
 /* of the tree open; the reading taken: order symbols by (length,      */
 /* symbol value), first code all zeros, each next code = previous + 1  */

@@ -41,6 +41,11 @@
 
 namespace {
 
+// Stream, plane and output are touched exactly once: nontemporal accesses keep them from
+// displacing the table and the metadata in L2.
+#define LD_STREAM(p) __builtin_nontemporal_load(p)
+#define ST_STREAM(v, p) __builtin_nontemporal_store((v), (p))
+
 struct KArgs {
     ecf8_batch_item single;               // used when items == nullptr
     const GLOBAL ecf8_batch_item *items;  // device array for the batched call
@@ -81,14 +86,19 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
     uint8_t *stage = smem + stage_off;
 
     // contiguous range of the batch's chunks for this workgroup
-    const uint64_t G = gridDim.x, g = blockIdx.x;
-    uint64_t c = a.total_chunks * g / G;
-    const uint64_t c_end = a.total_chunks * (g + 1) / G;
+    // (cut at multiples of 64 chunks when there is enough work, so that the waves of a
+    // workgroup share the interleaved groups of the layout)
+    const uint64_t NWG = gridDim.x, wg = blockIdx.x;
+    const uint64_t unit = a.total_chunks >= NWG * 128 ? 64 : 1;
+    const uint64_t units = (a.total_chunks + unit - 1) / unit;
+    uint64_t c = units * wg / NWG * unit;
+    uint64_t c_end = units * (wg + 1) / NWG * unit;
+    if (c_end > a.total_chunks) c_end = a.total_chunks;
 
     while (c < c_end) {
         // which tensor holds chunk c (uniform)
         uint64_t d_blob, d_out, n_elem, n_chunks, first_chunk, off_cb, off_lb, off_st, off_pl, st_bytes;
-        uint64_t len_lo, len_hi, off_tbl;
+        uint64_t len_lo, len_hi, off_tbl, group;
         if (a.items) {
             uint32_t lo = 0, hi = a.n_items - 1;
             while (lo < hi) {
@@ -99,7 +109,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
             d_blob = p->d_blob; d_out = p->d_out; n_elem = p->n_elem; n_chunks = p->n_chunks;
             first_chunk = p->first_chunk; off_cb = p->off_chunk_bit; off_lb = p->off_lane_bits;
             off_st = p->off_stream; off_pl = p->off_plane; st_bytes = p->stream_bytes;
-            off_tbl = p->off_table;
+            off_tbl = p->off_table; group = p->group_chunks;
             const GLOBAL uint64_t *cl8 = (const GLOBAL uint64_t *)p->code_len;
             len_lo = cl8[0]; len_hi = cl8[1];
         } else {
@@ -107,7 +117,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
             n_chunks = a.single.n_chunks; first_chunk = 0; off_cb = a.single.off_chunk_bit;
             off_lb = a.single.off_lane_bits; off_st = a.single.off_stream; off_pl = a.single.off_plane;
             st_bytes = a.single.stream_bytes;
-            off_tbl = a.single.off_table;
+            off_tbl = a.single.off_table; group = a.single.group_chunks;
             __builtin_memcpy(&len_lo, a.single.code_len, 8);
             __builtin_memcpy(&len_hi, a.single.code_len + 8, 8);
         }
@@ -119,6 +129,18 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
         const GLOBAL uint16_t *lane_bits = (const GLOBAL uint16_t *)(d_blob + off_lb);
         const GLOBAL uint8_t *stream = (const GLOBAL uint8_t *)(d_blob + off_st);
         const GLOBAL uint8_t *plane = (const GLOBAL uint8_t *)(d_blob + off_pl);
+        // Element layout: chunk cl's piece q of lane l starts at element
+        // base + q*stride + l*16.  Chunks of whole groups of `group` chunks are interleaved
+        // KiB by KiB (a wave's consecutive pieces lie group KiB apart, the other waves of
+        // the workgroup fill the gaps: HBM serves that markedly faster than a wave
+        // walking 1 KiB steps); the rest of the tensor is chunk-major.
+        if (group == 0) group = 1;
+        const uint64_t grouped = (n_elem / (64ull * N)) & ~(group - 1);   // chunks in whole groups (group is a power of two)
+        auto chunk_base = [&](uint64_t cl) -> uint64_t {
+            const uint64_t w = cl & (group - 1);
+            return cl < grouped ? (cl - w) * (64ull * N) + w * 1024 : cl * (64ull * N);
+        };
+        auto chunk_stride = [&](uint64_t cl) -> uint32_t { return cl < grouped ? (uint32_t)group * 1024u : 1024u; };
 
         __syncthreads(); // every wave is done with the previous tensor's table and its scratch
         // the first two chunks of a wave are fixed (c + wave, c + WAVES + wave); later ones are drawn
@@ -149,15 +171,16 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
             Payload p;
             uint64_t byte0;
             const uint64_t span64 = span_of(m, byte0);
-            const GLOBAL u32x2 *plane_c = (const GLOBAL u32x2 *)(plane + cl * (32ull * N));
+            const GLOBAL uint8_t *plane_c = plane + chunk_base(cl) / 2 + lane * 8;
+            const uint32_t pstride = chunk_stride(cl) / 2;
 #pragma unroll
-            for (int j = 0; j < C::PIECES; j++) p.pl[j] = plane_c[j * 64 + lane];
+            for (int j = 0; j < C::PIECES; j++) p.pl[j] = LD_STREAM((const GLOBAL u32x2 *)(plane_c + j * pstride));
 #pragma unroll
             for (int k = 0; k < C::SEGS; k++) {
                 const uint32_t i = (lane + 64 * k) * 16;
                 p.s[k] = u32x4{0, 0, 0, 0};
                 if (span64 <= (uint64_t)C::STAGE && i < (uint32_t)span64)
-                    p.s[k] = *(const GLOBAL u32x4 *)(stream + byte0 + i);
+                    p.s[k] = LD_STREAM((const GLOBAL u32x4 *)(stream + byte0 + i));
             }
             return p;
         };
@@ -221,7 +244,8 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
             __builtin_amdgcn_s_waitcnt(0x0F70);
             for (;;) {
                 const uint64_t cl = cg - first_chunk;            // chunk index inside the tensor
-                const uint64_t elem0 = cl * (64ull * N);         // first element of the chunk
+                GLOBAL uint8_t *out_c = out + chunk_base(cl) + lane * 16;   // this lane's piece 0
+                const uint32_t ostride = chunk_stride(cl);
                 const uint64_t b0 = __builtin_amdgcn_readfirstlane((uint32_t)m_cur.b0) |
                                     ((uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)(m_cur.b0 >> 32)) << 32);
                 uint64_t byte0;
@@ -262,9 +286,9 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
                     for (int t = 0; t < 4; t++) {
                         quad_step2(smem, tbl, s_len, s_code, bpA, bpB, dwA[t], dwB[t]);
                     }
-                    *(GLOBAL u32x4 *)(out + elem0 + (uint64_t)(Q * 64 + lane) * 16) = merge_piece(dwA, pl[Q]);
-                    *(GLOBAL u32x4 *)(out + elem0 + (uint64_t)((Q + C::PIECES / 2) * 64 + lane) * 16) =
-                        merge_piece(dwB, pl[Q + C::PIECES / 2]);
+                    ST_STREAM(merge_piece(dwA, pl[Q]), (GLOBAL u32x4 *)(out_c + Q * ostride));
+                    ST_STREAM(merge_piece(dwB, pl[Q + C::PIECES / 2]),
+                              (GLOBAL u32x4 *)(out_c + (Q + C::PIECES / 2) * ostride));
                 }
 
                 if (!has_next) break;
@@ -289,14 +313,15 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
                 const uint64_t span64 = span_of(m, byte0);
                 const bool redo = cg2 >= fast_end || span64 > (uint64_t)C::STAGE;
                 if (!__builtin_amdgcn_readfirstlane((uint32_t)redo)) continue;
-                const uint64_t elem0 = cl * (64ull * N);
+                const uint64_t elem0 = chunk_base(cl);
+                const uint32_t estride = chunk_stride(cl);
                 const uint32_t rel = wave_incl_scan(m.lb) - m.lb;
                 const GLOBAL uint8_t *sp = stream + byte0;
                 uint64_t bA = (m.b0 - byte0 * 8) + rel;   // forward run: next bit
                 uint64_t bB = bA + m.lb;                  // backward run: one past the next bit
 #pragma unroll 1
                 for (int Q = 0; Q < C::PIECES; Q++) {
-                    const uint64_t o = elem0 + (uint64_t)(Q * 64 + lane) * 16;
+                    const uint64_t o = elem0 + (uint64_t)Q * estride + lane * 16;
                     const bool fwd = Q < C::PIECES / 2;
 #pragma unroll 1
                     for (uint32_t i = 0; i < 16 && o + i < n_elem; i++) {
@@ -346,7 +371,8 @@ int ecf8_decode(const ecf8_header *h, const void *d_blob, void *d_out, uint64_t 
 {
     if (!h || !d_blob || !d_out) return ECF8_E_ARG;
     if (h->magic != ECF8_MAGIC || h->version != ECF8_VERSION || h->n_elem == 0 || h->n_chunks == 0 ||
-        (h->table_bits != 0 && h->table_bits != ECF8_TB))
+        (h->table_bits != 0 && h->table_bits != ECF8_TB) || h->group_chunks == 0 || h->group_chunks > 64 ||
+        (h->group_chunks & (h->group_chunks - 1)))
         return ECF8_E_FORMAT;
     if (h->n_chunks != (h->n_elem + 64ull * h->lane_syms - 1) / (64ull * h->lane_syms)) return ECF8_E_FORMAT;
     if (h->off_plane + h->plane_bytes > h->total_size || h->off_stream + h->stream_bytes > h->off_plane ||
@@ -366,6 +392,7 @@ int ecf8_decode(const ecf8_header *h, const void *d_blob, void *d_out, uint64_t 
     a.single.off_plane = h->off_plane;
     a.single.stream_bytes = h->stream_bytes;
     a.single.off_table = h->table_bits ? 256 : 0;
+    a.single.group_chunks = h->group_chunks;
     for (int i = 0; i < 16; i++) a.single.code_len[i] = h->code_len[i];
     a.items = nullptr;
     a.n_items = 1;

@@ -277,7 +277,7 @@ int ecf8_gemm_fp8(const ecf8_header *h, const void *d_blob, const void *d_x, uin
     if (!h || !d_blob) return ECF8_E_ARG;
     if (h->magic != ECF8_MAGIC || h->version != ECF8_VERSION || (h->table_bits != 0 && h->table_bits != ECF8_TB))
         return ECF8_E_FORMAT;
-    if (h->lane_syms != GN) return ECF8_E_ARG;
+    if (h->lane_syms != GN || h->group_chunks != 1) return ECF8_E_ARG;   // one chunk = one row of W
     int rc = check_gemm_args(h->rows, h->cols, d_x, M, d_y);
     if (rc) return rc;
     if (h->n_elem != h->rows * h->cols || h->n_chunks != h->rows) return ECF8_E_FORMAT;

@@ -33,6 +33,16 @@ namespace {
 inline uint64_t round_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 
 bool lane_syms_ok(uint32_t n) { return n == 32 || n == 64 || n == 128; }
+bool group_ok(uint32_t g) { return g >= 1 && g <= 64 && (g & (g - 1)) == 0; }
+
+// Where chunk c's pieces lie: piece q of lane l starts at element base + q*stride + l*16.
+// Chunks of whole groups are interleaved KiB by KiB, the rest of the tensor is chunk-major.
+struct ChunkMap {
+    uint64_t E, G, grouped; // elements per chunk, chunks per group, chunks that lie in whole groups
+    ChunkMap(uint64_t n, uint32_t N, uint32_t group) : E(64ull * N), G(group), grouped(n / (group * 64ull * N) * group) {}
+    uint64_t base(uint64_t c) const { return c < grouped ? (c - c % G) * E + (c % G) * 1024 : c * E; }
+    uint64_t stride(uint64_t c) const { return c < grouped ? G * 1024 : 1024; }
+};
 
 // Optimal prefix-code lengths by the two-queue method: leaves sorted by weight
 // in one queue, merged nodes (created in non-decreasing weight) in a second;
@@ -185,7 +195,8 @@ int check_header(const ecf8_header &h, uint64_t size)
     if (h.magic != ECF8_MAGIC || h.version != ECF8_VERSION) return ECF8_E_FORMAT;
     if (h.total_size != size || h.n_elem == 0) return ECF8_E_FORMAT;
     if (h.rows == 0 || h.cols == 0 || h.n_elem / h.rows != h.cols || h.n_elem % h.rows) return ECF8_E_FORMAT;
-    if ((h.table_bits != 0 && h.table_bits != ECF8_TB) || !lane_syms_ok(h.lane_syms)) return ECF8_E_FORMAT;
+    if ((h.table_bits != 0 && h.table_bits != ECF8_TB) || !lane_syms_ok(h.lane_syms) || !group_ok(h.group_chunks))
+        return ECF8_E_FORMAT;
     if (h.stream_bits > h.n_elem * 15 || h.stream_bits < h.n_elem) return ECF8_E_FORMAT;
     Layout L = make_layout(h.n_elem, h.stream_bits, h.lane_syms, h.table_bits);
     if (h.n_chunks != L.n_chunks || h.off_chunk_bit != L.off_cb || h.off_lane_bits != L.off_lb ||
@@ -215,7 +226,9 @@ int ecf8_encode(const uint8_t *x, uint64_t rows, uint64_t cols, const ecf8_encod
     if (rows > (1ull << 40) / cols) return ECF8_E_ARG;
     const uint64_t n = rows * cols;
     const uint32_t N = (opts && opts->lane_syms) ? opts->lane_syms : 128;
-    if (!lane_syms_ok(N)) return ECF8_E_ARG;
+    const uint32_t group = (opts && opts->group_chunks) ? opts->group_chunks : 32;
+    if (!lane_syms_ok(N) || !group_ok(group)) return ECF8_E_ARG;
+    const ChunkMap map(n, N, group);
     unsigned nt = (opts && opts->n_threads) ? opts->n_threads : std::thread::hardware_concurrency();
     if (nt == 0) nt = 1;
     if (nt > 64) nt = 64;
@@ -268,7 +281,8 @@ int ecf8_encode(const uint8_t *x, uint64_t rows, uint64_t cols, const ecf8_encod
         h->rows = rows;
         h->cols = cols;
         h->lane_syms = N;
-        h->table_bits = table_bits;
+        h->table_bits = (uint16_t)table_bits;
+        h->group_chunks = (uint16_t)group;
         if (table_bits) build_pair_table(len, (uint16_t *)(blob + 256));
         h->n_chunks = L.n_chunks;
         h->stream_bits = bits;
@@ -292,10 +306,9 @@ int ecf8_encode(const uint8_t *x, uint64_t rows, uint64_t cols, const ecf8_encod
             for (uint64_t c = c0; c < c1; c++) {
                 uint64_t tot = 0;
                 for (uint32_t l = 0; l < ECF8_LANES; l++) {
-                    // lane l owns the 16-element pieces l, l+64, l+128, ... of the chunk
                     uint32_t lb = 0;
                     for (uint32_t q = 0; q < N / 16; q++) {
-                        uint64_t a = c * chunk_elems + ((uint64_t)q * ECF8_LANES + l) * 16;
+                        uint64_t a = map.base(c) + q * map.stride(c) + l * 16;
                         uint64_t b = std::min<uint64_t>(a + 16, n);
                         for (uint64_t i = a; i < b; i++) lb += len[(x[i] >> 3) & 15];
                     }
@@ -335,7 +348,7 @@ int ecf8_encode(const uint8_t *x, uint64_t rows, uint64_t cols, const ecf8_encod
                         if ((at & 63) + nb > 64) lbuf[(at >> 6) + 1] |= (uint64_t)bits >> (64 - (at & 63));
                     };
                     for (uint32_t q = 0; q < P; q++) {
-                        uint64_t pa = c * chunk_elems + ((uint64_t)q * ECF8_LANES + l) * 16;
+                        uint64_t pa = map.base(c) + q * map.stride(c) + l * 16;
                         uint64_t pb = std::min<uint64_t>(pa + 16, n);
                         for (uint64_t i = pa; i < pb; i++) {
                             uint32_t e = (x[i] >> 3) & 15;
@@ -414,7 +427,7 @@ int ecf8_blob_validate(const void *blob, uint64_t size)
         build_pair_table(h.code_len, want.data());
         if (std::memcmp(want.data(), p + 256, 2ull << h.table_bits) != 0) return ECF8_E_FORMAT;
     }
-    const uint64_t chunk_elems = (uint64_t)ECF8_LANES * N;
+    const ChunkMap map(h.n_elem, N, h.group_chunks);
     uint64_t prev;
     std::memcpy(&prev, p + h.off_chunk_bit, 8);
     if (prev != 0) return ECF8_E_FORMAT;
@@ -427,7 +440,7 @@ int ecf8_blob_validate(const void *blob, uint64_t size)
             std::memcpy(&lb, p + h.off_lane_bits + 2 * (c * ECF8_LANES + l), 2);
             uint64_t cnt = 0; // elements of the lane's pieces that exist
             for (uint32_t q = 0; q < N / 16; q++) {
-                uint64_t a = c * chunk_elems + ((uint64_t)q * ECF8_LANES + l) * 16;
+                uint64_t a = map.base(c) + q * map.stride(c) + l * 16;
                 if (a < h.n_elem) cnt += std::min<uint64_t>(16, h.n_elem - a);
             }
             if (lb > 15 * cnt || lb < cnt) return ECF8_E_FORMAT;
@@ -496,6 +509,7 @@ int ecf8_batch_prepare(const ecf8_header *hdrs, const void *const *d_blobs, void
         it.off_plane = h.off_plane;
         it.stream_bytes = h.stream_bytes;
         it.off_table = h.table_bits ? 256 : 0;
+        it.group_chunks = h.group_chunks;
         std::memcpy(it.code_len, h.code_len, 16);
         first += h.n_chunks;
     }

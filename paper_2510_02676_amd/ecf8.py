@@ -27,7 +27,7 @@ class Header(ctypes.Structure):
     _fields_ = [("magic", ctypes.c_uint32), ("version", ctypes.c_uint32),
                 ("total_size", ctypes.c_uint64), ("n_elem", ctypes.c_uint64),
                 ("rows", ctypes.c_uint64), ("cols", ctypes.c_uint64),
-                ("lane_syms", ctypes.c_uint32), ("table_bits", ctypes.c_uint32),
+                ("lane_syms", ctypes.c_uint32), ("table_bits", ctypes.c_uint16), ("group_chunks", ctypes.c_uint16),
                 ("n_chunks", ctypes.c_uint64), ("stream_bits", ctypes.c_uint64),
                 ("code_len", ctypes.c_uint8 * 16),
                 ("off_chunk_bit", ctypes.c_uint64), ("off_lane_bits", ctypes.c_uint64),
@@ -38,7 +38,7 @@ class Header(ctypes.Structure):
 
 class EncodeOpts(ctypes.Structure):
     _fields_ = [("lane_syms", ctypes.c_uint32), ("n_threads", ctypes.c_uint32),
-                ("table_mode", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+                ("table_mode", ctypes.c_uint32), ("group_chunks", ctypes.c_uint32)]
 
 
 class Stats(ctypes.Structure):
@@ -53,7 +53,8 @@ class BatchItem(ctypes.Structure):
                 ("off_chunk_bit", ctypes.c_uint64), ("off_lane_bits", ctypes.c_uint64),
                 ("off_stream", ctypes.c_uint64), ("off_plane", ctypes.c_uint64),
                 ("stream_bytes", ctypes.c_uint64), ("code_len", ctypes.c_uint8 * 16),
-                ("off_table", ctypes.c_uint64), ("reserved", ctypes.c_uint64 * 3)]
+                ("off_table", ctypes.c_uint64), ("group_chunks", ctypes.c_uint64),
+                ("reserved", ctypes.c_uint64 * 2)]
 
 
 assert ctypes.sizeof(Header) == 256 and ctypes.sizeof(BatchItem) == 128
@@ -133,15 +134,16 @@ class Blob:
             self._h = None
 
 
-def ecf8_encode(fp8, rows=None, cols=None, lane_syms=0, n_threads=0, table_mode=0):
+def ecf8_encode(fp8, rows=None, cols=None, lane_syms=0, n_threads=0, table_mode=0, group_chunks=0):
     """CPU encoder: raw E4M3 bytes (host tensor / array) -> Blob.
-    table_mode: 0 embed the decode table for tensors of >= 2^22 weights, 1 always, 2 never."""
+    table_mode: 0 embed the decode table for tensors of >= 2^22 weights, 1 always, 2 never.
+    group_chunks: chunks interleaved per group (0 = default 32; 1 = chunk-major, what the fused GEMM needs)."""
     x = _host_u8(fp8)
     if rows is None:
         rows, cols = (x.shape if x.ndim == 2 else (1, x.size))
     if rows * cols != x.size:
         raise Ecf8Error("ecf8_encode", E_ARG)
-    opts = EncodeOpts(lane_syms, n_threads, table_mode, 0)
+    opts = EncodeOpts(lane_syms, n_threads, table_mode, group_chunks)
     h = _vp()
     _check("ecf8_encode", _lib.ecf8_encode(x.ctypes.data, rows, cols, ctypes.byref(opts), ctypes.byref(h)))
     return Blob(h)

@@ -97,11 +97,24 @@ def test_degenerate_and_extreme_inputs(orc, name, lane_syms):
     assert np.array_equal(got, _oracle_expected(orc, x))
 
 
-@pytest.mark.parametrize("lane_syms", [64, 128])
-def test_oracle_written_container_decodes_on_gpu(orc, lane_syms):
+@pytest.mark.parametrize("lane_syms,group", [(32, 1), (32, 64), (64, 2), (64, 32), (128, 1), (128, 8), (128, 64)])
+def test_group_widths(orc, lane_syms, group):
+    """Every interleave width the format allows next to the default: whole groups, then
+    chunk-major chunks, then a ragged last chunk."""
+    n = 1_000_003 if group < 64 else 2_300_017
+    x = _rand_bytes(n, 5 * lane_syms + group)
+    blob = ecf8.ecf8_encode(x, 1, n, lane_syms=lane_syms, group_chunks=group, table_mode=1 + (group % 3 == 1))
+    assert blob.header.group_chunks == group
+    got, guards = _gpu_decode_guarded(blob.numpy(), blob.header)
+    assert guards
+    assert np.array_equal(got, _oracle_expected(orc, x))
+
+
+@pytest.mark.parametrize("lane_syms,group", [(64, 1), (64, 4), (128, 32)])
+def test_oracle_written_container_decodes_on_gpu(orc, lane_syms, group):
     """Interop: a container written by the oracle's writer (its own tie-breaks)."""
-    x = _rand_bytes(200_003, 9)
-    arr = orc.container_encode(x, 1, x.size, lane_syms)
+    x = _rand_bytes(600_003, 9)
+    arr = orc.container_encode(x, 1, x.size, lane_syms, group)
     hdr = ecf8.blob_describe(arr)
     ecf8.blob_validate(arr)
     got, guards = _gpu_decode_guarded(arr, hdr)

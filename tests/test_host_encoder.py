@@ -46,6 +46,54 @@ def test_encoder_container_read_by_oracle(orc, lane_syms, n):
     assert blob.size == orc.lib().orc_container_size(n, bits, lane_syms)
 
 
+@pytest.mark.parametrize("lane_syms,group,n", [
+    (32, 2, 4096), (32, 4, 8192), (32, 4, 8193), (32, 4, 3 * 8192 + 5000), (32, 64, 300001),
+    (64, 32, 2 * 131072 + 70001), (64, 8, 100003), (128, 32, 262144 + 12345), (128, 2, 16384 * 3 - 1),
+    (128, 32, 262143), (128, 1, 50000)])
+def test_grouped_layout_read_by_oracle(orc, lane_syms, group, n):
+    """Whole groups interleaved, the rest chunk-major: product writer against the oracle's reader,
+    and the oracle's writer against the product's validator (the bitstreams may differ only where
+    the two Huffman tie-breaks differ, so the blobs are not compared byte by byte)."""
+    x = _rand_bytes(n, n + lane_syms + group)
+    blob = ecf8.ecf8_encode(x, 1, n, lane_syms=lane_syms, group_chunks=group)
+    assert blob.header.group_chunks == group
+    arr = blob.numpy()
+    ecf8.blob_validate(arr)
+    dec, bits = orc.container_decode(arr)
+    assert np.array_equal(dec, x) and bits == blob.header.stream_bits
+    theirs = orc.container_encode(x, 1, n, lane_syms, group)
+    ecf8.blob_validate(theirs)
+    assert ecf8.blob_describe(theirs).group_chunks == group
+    dec2, _ = orc.container_decode(theirs)
+    assert np.array_equal(dec2, x)
+
+
+def test_group_interleave_is_block_by_block():
+    """The layout stated from scratch for one whole group of two chunks (N = 32): the four
+    1024-element blocks alternate between the chunks, lane l owns elements [16 l, 16 l + 16) of
+    each of its blocks; lane_bits must be the code bits of exactly those elements."""
+    n = 4096
+    x = _rand_bytes(n, 77)
+    b = ecf8.ecf8_encode(x, 1, n, lane_syms=32, group_chunks=2)
+    a, h = b.numpy(), b.header
+    assert h.n_chunks == 2
+    length = np.array(list(h.code_len), dtype=np.int64)
+    bits_of = length[(x >> 3) & 15]
+    lane_bits = a[h.off_lane_bits:h.off_lane_bits + 2 * 128].view("<u2")
+    for c in range(2):
+        for l in range(64):
+            want = sum(int(bits_of[blk * 1024 + 16 * l: blk * 1024 + 16 * l + 16].sum()) for blk in (c, c + 2))
+            assert lane_bits[c * 64 + l] == want
+    # the same tensor chunk-major: chunk c owns blocks 2c and 2c+1
+    b1 = ecf8.ecf8_encode(x, 1, n, lane_syms=32, group_chunks=1)
+    a1, h1 = b1.numpy(), b1.header
+    lane_bits1 = a1[h1.off_lane_bits:h1.off_lane_bits + 2 * 128].view("<u2")
+    for c in range(2):
+        for l in range(64):
+            want = sum(int(bits_of[blk * 1024 + 16 * l: blk * 1024 + 16 * l + 16].sum()) for blk in (2 * c, 2 * c + 1))
+            assert lane_bits1[c * 64 + l] == want
+
+
 @pytest.mark.parametrize("n", [5, 4096, 100003])
 def test_embedded_table_is_what_the_code_says(orc, n):
     """A blob with the decoder's pair table embedded: the oracle's reader rebuilds every
@@ -93,7 +141,7 @@ def test_hand_example_bytes_in_the_product_container():
     b = ecf8.ecf8_encode(x, 2, 2)
     a, h = b.numpy(), b.header
     assert h.stream_bits == 4 and h.rows == 2 and h.cols == 2
-    assert h.lane_syms == 128 and a[h.off_stream] == 0x07
+    assert h.lane_syms == 128 and h.group_chunks == 32 and a[h.off_stream] == 0x07
     assert list(a[h.off_plane:h.off_plane + 4]) == [0x00, 0x08, 0x04, 0x00]
 
 
@@ -121,9 +169,13 @@ def test_error_paths():
     assert e.value.code == ecf8.E_ARG
     with pytest.raises(ecf8.Ecf8Error):
         ecf8.ecf8_encode(x, 1, 1000, lane_syms=48)
+    for g in (3, 128):
+        with pytest.raises(ecf8.Ecf8Error) as e:
+            ecf8.ecf8_encode(x, 1, 1000, group_chunks=g)
+        assert e.value.code == ecf8.E_ARG
     good = ecf8.ecf8_encode(x, 10, 100).numpy().copy()
     ecf8.blob_validate(good)
-    for off, val in [(0, 0), (4, 9), (40, 16), (56, 1), (64, 0), (16, 7)]:
+    for off, val in [(0, 0), (4, 9), (40, 16), (46, 0), (46, 3), (56, 1), (64, 0), (16, 7)]:
         bad = good.copy()
         bad[off] = val
         with pytest.raises(ecf8.Ecf8Error) as e:

@@ -116,6 +116,63 @@ def test_huffman_is_optimal_by_brute_force(orc, seed):
     assert orc.stream_bits(freq, ln) == _brute_force_cost(fr)
 
 
+def _brute_force_cost_limited(freqs, lmax):
+    best = None
+    for ls in itertools.product(range(1, lmax + 1), repeat=len(freqs)):
+        if sum(2.0 ** -l for l in ls) <= 1.0 + 1e-12:
+            c = sum(f * l for f, l in zip(freqs, ls))
+            best = c if best is None or c < best else best
+    return best
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_length_limited_code_is_optimal_by_brute_force(orc, seed):
+    """min over ALL length vectors <= lmax satisfying Kraft == the oracle's capped cost (k <= 6),
+    on skewed histograms where the cap binds."""
+    rng = np.random.default_rng(2000 + seed)
+    k = int(rng.integers(2, 7))
+    fr = [int(v) for v in (2.0 ** rng.uniform(0, 12, size=k)).astype(np.int64) + 1]
+    if seed % 6 == 0:
+        fr = [1, 1, 2, 3, 5, 8][:k]            # Fibonacci: the uncapped tree is a chain
+    pos = sorted(int(v) for v in rng.choice(16, size=k, replace=False))
+    freq = np.zeros(16, dtype=np.uint64)
+    for p_, f in zip(pos, fr):
+        freq[p_] = f
+    lo = int(np.ceil(np.log2(k)))
+    for lmax in range(max(lo, 1), 6):
+        ln = orc.huffman_lengths_limited(freq, lmax)
+        assert ln.max() <= lmax and all((ln[i] > 0) == (freq[i] > 0) for i in range(16))
+        assert sum(2.0 ** -int(l) for l in ln if l) <= 1.0
+        assert orc.stream_bits(freq, ln) == _brute_force_cost_limited(fr, lmax)
+
+
+def test_length_limited_code_special_cases(orc):
+    fib = np.array([1, 1, 2, 3, 5, 8, 13, 21, 34, 55, 89, 144, 233, 377, 610, 987], dtype=np.uint64)
+    # a cap that does not bind gives the Huffman cost; costs never fall as the cap tightens
+    assert orc.stream_bits(fib, orc.huffman_lengths_limited(fib, 15)) == orc.stream_bits(fib, orc.huffman_lengths(fib))
+    costs = [orc.stream_bits(fib, orc.huffman_lengths_limited(fib, L)) for L in range(4, 16)]
+    assert all(a >= b for a, b in zip(costs, costs[1:])) and costs[0] > costs[-1]
+    # 16 symbols under a cap of 4: the only code is the fixed-length one
+    assert list(orc.huffman_lengths_limited(fib, 4)) == [4] * 16
+    # Kraft holds with equality for every cap (a cheapest code wastes no code space)
+    for L in range(4, 16):
+        ln = orc.huffman_lengths_limited(fib, L)
+        assert sum(1 << (15 - int(l)) for l in ln) == 1 << 15 and ln.max() <= L
+    # hand case: frequencies 8 4 2 1 1 under cap 3: lengths 1 3 3 3 3 cost 32, or 2 2 2 3 3 cost 34 -> 32;
+    # uncapped Huffman gives 1 2 3 4 4 cost 30
+    f = np.zeros(16, dtype=np.uint64)
+    f[[2, 4, 6, 8, 10]] = [8, 4, 2, 1, 1]
+    assert orc.stream_bits(f, orc.huffman_lengths(f)) == 30
+    assert orc.stream_bits(f, orc.huffman_lengths_limited(f, 3)) == 32
+    one = np.zeros(16, dtype=np.uint64)
+    one[5] = 77
+    assert list(orc.huffman_lengths_limited(one, 7)) == [0] * 5 + [1] + [0] * 10
+    with pytest.raises(ValueError):
+        orc.huffman_lengths_limited(fib, 3)     # 16 symbols do not fit 3 bits
+    with pytest.raises(ValueError):
+        orc.huffman_lengths_limited(np.zeros(16, dtype=np.uint64), 7)
+
+
 def test_fig2_worked_example(orc):
     """Figure 2: 'aaabbcddeeeee' costs 29 bits; the drawn tree's 2-bit cascaded
     table has root {e, e, a, ->1} and sub-table {b, b, c, d}."""
@@ -279,6 +336,43 @@ def test_container_roundtrip_and_metadata(orc, lane_syms, n):
     lb = np.frombuffer(blob[off_lb:off_lb + 128 * n_chunks].tobytes(), "<u2").reshape(n_chunks, 64)
     assert cb[0] == 0 and cb[-1] == bits
     assert np.array_equal(np.diff(cb.astype(np.int64)), lb.sum(axis=1))
+
+
+@pytest.mark.parametrize("lane_syms,group,n", [(32, 2, 4096), (32, 4, 8192 * 2 + 3000), (64, 8, 2 * 32768 + 4097),
+                                               (128, 32, 262144 + 9000), (16, 64, 3 * 65536 + 1)])
+def test_container_group_interleave(orc, lane_syms, group, n):
+    """Whole groups of G chunks are interleaved block by block, the rest is chunk after chunk.
+    The expected ownership is stated as array reshapes (axes: piece, chunk-in-group, lane, byte),
+    not with the container's index formula."""
+    rng = np.random.default_rng(n + group)
+    p = rng.dirichlet(np.ones(16) * 0.4)
+    x = _bytes_from(rng.choice(16, size=n, p=p), rng)
+    blob = orc.container_encode(x, 1, n, lane_syms, group)
+    dec, bits = orc.container_decode(blob)
+    assert np.array_equal(dec, x)
+    ln = orc.huffman_lengths(orc.histogram(x)).astype(np.int64)
+    chunk = 64 * lane_syms
+    n_chunks = -(-n // chunk)
+    pieces = lane_syms // 16
+    padded = np.zeros(n_chunks * chunk, dtype=np.int64)
+    padded[:n] = ln[(x >> 3) & 15]                 # code bits per element, 0 for elements that do not exist
+    whole = n // (group * chunk)
+    want = np.zeros((n_chunks, 64), dtype=np.int64)
+    for g in range(whole):
+        blk = padded[g * group * chunk:(g + 1) * group * chunk].reshape(pieces, group, 64, 16)
+        want[g * group:(g + 1) * group] = blk.sum(axis=(0, 3))
+    for c in range(whole * group, n_chunks):
+        want[c] = padded[c * chunk:(c + 1) * chunk].reshape(pieces, 64, 16).sum(axis=(0, 2))
+    hdr = np.frombuffer(blob[:256].tobytes(), "<u8")
+    off_lb = int(hdr[11])
+    lb = np.frombuffer(blob[off_lb:off_lb + 128 * n_chunks].tobytes(), "<u2").reshape(n_chunks, 64)
+    assert np.array_equal(lb.astype(np.int64), want)
+    with pytest.raises(ValueError):
+        orc.container_encode(x, 1, n, lane_syms, 3)
+    bad = blob.copy()
+    bad[46] = 0
+    with pytest.raises(ValueError):
+        orc.container_decode(bad)
 
 
 def test_container_reader_catches_tampering(orc):
