@@ -117,6 +117,14 @@ typedef struct ecf8_encode_opts {
     uint32_t table_mode; /* 0 = embed the table when n_elem >= 2^22 (32 KiB is   */
                          /* then < 0.8 % of the tensor), 1 = always, 2 = never   */
     uint32_t group_chunks; /* 0 = default (32); 1 is what ecf8_gemm_fp8 needs      */
+    uint32_t max_code_len; /* cap on the code length, 4..15; 0 = default (7 = half */
+                           /* the decoder's table index, so that two codewords     */
+                           /* always resolve in one lookup and the decode kernels  */
+                           /* take their branch-free form).  Section 3.1 caps the  */
+                           /* length too (at 16, by adjusting frequencies); here   */
+                           /* the capped code is the cheapest one (package-merge). */
+                           /* 15 never binds: plain Huffman                        */
+    uint32_t reserved[3];
 } ecf8_encode_opts;
 
 typedef struct ecf8_stats {
@@ -135,7 +143,7 @@ typedef struct ecf8_blob ecf8_blob; /* host object owning one encoded container 
  * Reads rows*cols raw E4M3 bytes (row-major; every byte value is legal: the
  * codec treats bits 6..3 as an opaque symbol, so zeros, subnormals and NaN
  * encodings round-trip), builds the histogram, an optimal prefix code
- * (lengths <= 15 with 16 symbols), the stream, the lane/chunk metadata and
+ * (lengths <= opts->max_code_len), the stream, the lane/chunk metadata and
  * the nibble plane.  *out receives a new blob the caller frees with
  * ecf8_blob_free.  rows*cols == 0 -> ECF8_E_ARG.
  */
@@ -188,24 +196,31 @@ typedef struct ecf8_batch_item {
     uint64_t reserved[2];
 } ecf8_batch_item; /* 128 bytes */
 
+/* What a batched launch needs to know on the host. */
+typedef struct ecf8_batch_info {
+    uint64_t total_chunks;  /* chunks of all tensors of the batch                 */
+    uint32_t lane_syms;     /* N, shared by all tensors of the batch              */
+    uint32_t max_code_len;  /* longest codeword of any tensor of the batch        */
+} ecf8_batch_info;
+
 /*
  * ecf8_batch_prepare: HOST.  Fills items_host[0..n) from the headers and the
  * device addresses; the caller copies the array to device memory once and
- * keeps it.  All tensors of a batch must share lane_syms.  *total_chunks
- * receives the chunk count of the whole batch.
+ * keeps it, together with *info.  All tensors of a batch must share lane_syms.
  */
 int ecf8_batch_prepare(const ecf8_header *hdrs, const void *const *d_blobs,
                        void *const *d_outs, const uint64_t *out_capacities,
                        uint32_t n_tensors, ecf8_batch_item *items_host,
-                       uint64_t *total_chunks, uint32_t *lane_syms);
+                       ecf8_batch_info *info);
 
 /*
  * ecf8_decode_batched: many tensors in ONE launch (the per-layer decode of
  * Section 3.3 collapsed over a layer's matrices / an MoE layer's experts).
- * d_items: DEVICE array written by ecf8_batch_prepare (16-byte aligned).
+ * d_items: DEVICE array written by ecf8_batch_prepare (16-byte aligned);
+ * info: HOST, as filled by ecf8_batch_prepare for exactly these items.
  */
 int ecf8_decode_batched(const ecf8_batch_item *d_items, uint32_t n_tensors,
-                        uint64_t total_chunks, uint32_t lane_syms, void *stream);
+                        const ecf8_batch_info *info, void *stream);
 
 /*
  * ecf8_gemm_fp8: fused decode + FP8 GEMM for small batches.  The paper decodes a

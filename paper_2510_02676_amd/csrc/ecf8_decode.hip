@@ -51,6 +51,7 @@ struct KArgs {
     const GLOBAL ecf8_batch_item *items;  // device array for the batched call
     uint32_t n_items;
     uint64_t total_chunks;
+    uint32_t max_code_len;                // longest codeword of any tensor of the launch
 };
 
 template <int N, int WAVES>
@@ -68,7 +69,9 @@ struct Cfg {
     static_assert(TOTAL <= 160 * 1024, "LDS of one gfx950 CU");
 };
 
-template <int N, int WAVES>
+// PAIRFIT: every tensor of the launch has codewords of at most TB/2 bits (the encoder's
+// default cap), so the pipelined loop needs no second level and is one straight line.
+template <int N, int WAVES, bool PAIRFIT>
 __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
 {
     using C = Cfg<N, WAVES>;
@@ -279,16 +282,33 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
                 // bpB: one past the backward run's next codeword (its first bit is bpB - 1)
                 uint32_t bpA = stage_off * 8 + bit_in;   // oversize chunk: may point past LDS, reads return 0
                 uint32_t bpB = bpA + m_cur.lb;
+                // PAIRFIT: the chunk's pieces are kept in registers and stored in one burst at
+                // its end.  Together with the interleaved layout the workgroup's waves then
+                // write runs of adjacent KiBs close in time, which HBM takes ~15 % faster than
+                // single KiBs trickling out of every wave as they are decoded; the general
+                // kernel has no registers to spare for that.
+                u32x4 ov[PAIRFIT ? C::PIECES : 1];
 #pragma unroll
                 for (int Q = 0; Q < C::PIECES / 2; Q++) {
                     uint32_t dwA[4], dwB[4];
 #pragma unroll
                     for (int t = 0; t < 4; t++) {
-                        quad_step2(smem, tbl, s_len, s_code, bpA, bpB, dwA[t], dwB[t]);
+                        quad_step2<PAIRFIT>(smem, tbl, s_len, s_code, bpA, bpB, dwA[t], dwB[t]);
                     }
-                    ST_STREAM(merge_piece(dwA, pl[Q]), (GLOBAL u32x4 *)(out_c + Q * ostride));
-                    ST_STREAM(merge_piece(dwB, pl[Q + C::PIECES / 2]),
-                              (GLOBAL u32x4 *)(out_c + (Q + C::PIECES / 2) * ostride));
+                    if constexpr (PAIRFIT) {
+                        ov[Q] = merge_piece(dwA, pl[Q]);
+                        ov[Q + C::PIECES / 2] = merge_piece(dwB, pl[Q + C::PIECES / 2]);
+                    } else {
+                        ST_STREAM(merge_piece(dwA, pl[Q]), (GLOBAL u32x4 *)(out_c + Q * ostride));
+                        ST_STREAM(merge_piece(dwB, pl[Q + C::PIECES / 2]),
+                                  (GLOBAL u32x4 *)(out_c + (Q + C::PIECES / 2) * ostride));
+                    }
+                }
+                if constexpr (PAIRFIT) {
+                    __builtin_amdgcn_sched_barrier(0);   // keep the stores together, after the decode
+#pragma unroll
+                    for (int Q = 0; Q < C::PIECES; Q++) ST_STREAM(ov[Q], (GLOBAL u32x4 *)(out_c + Q * ostride));
+                    __builtin_amdgcn_sched_barrier(0);
                 }
 
                 if (!has_next) break;
@@ -340,8 +360,8 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
     }
 }
 
-template <int N, int WAVES>
-int launch(const KArgs &a, int wgs_per_cu, hipStream_t s)
+template <int N, int WAVES, bool PAIRFIT>
+int launch_as(const KArgs &a, int wgs_per_cu, hipStream_t s)
 {
     int cus = device_cus();
     if (cus <= 0) return ECF8_E_HIP;
@@ -349,16 +369,21 @@ int launch(const KArgs &a, int wgs_per_cu, hipStream_t s)
     uint64_t cap = (uint64_t)cus * wgs_per_cu;
     uint32_t grid = (uint32_t)(want < cap ? want : cap);
     if (grid == 0) grid = 1;
-    hipLaunchKernelGGL((ecf8_decode_kernel<N, WAVES>), dim3(grid), dim3(WAVES * 64), 0, s, a);
+    hipLaunchKernelGGL((ecf8_decode_kernel<N, WAVES, PAIRFIT>), dim3(grid), dim3(WAVES * 64), 0, s, a);
     return hipGetLastError() == hipSuccess ? ECF8_OK : ECF8_E_HIP;
 }
 
+// Workgroup shapes.  General kernel: as many waves as the registers allow (its second level
+// makes it latency-bound).  PAIRFIT kernel: N = 128 runs 8 waves of ~200 VGPRs, which is what
+// holding a chunk's 8 output pieces for the store burst takes; it has compute to spare.
 int dispatch(const KArgs &a, uint32_t lane_syms, hipStream_t s)
 {
+    if (a.max_code_len == 0 || a.max_code_len > 15) return ECF8_E_ARG;
+    const bool pairfit = 2 * a.max_code_len <= (uint32_t)TB;
     switch (lane_syms) {
-    case 32: return launch<32, 16>(a, 1, s);
-    case 64: return launch<64, 16>(a, 1, s);
-    case 128: return launch<128, 12>(a, 1, s);
+    case 32: return pairfit ? launch_as<32, 16, true>(a, 1, s) : launch_as<32, 16, false>(a, 1, s);
+    case 64: return pairfit ? launch_as<64, 16, true>(a, 1, s) : launch_as<64, 16, false>(a, 1, s);
+    case 128: return pairfit ? launch_as<128, 8, true>(a, 1, s) : launch_as<128, 12, false>(a, 1, s);
     default: return ECF8_E_ARG;
     }
 }
@@ -397,19 +422,21 @@ int ecf8_decode(const ecf8_header *h, const void *d_blob, void *d_out, uint64_t 
     a.items = nullptr;
     a.n_items = 1;
     a.total_chunks = h->n_chunks;
+    for (int i = 0; i < 16; i++) a.max_code_len = h->code_len[i] > a.max_code_len ? h->code_len[i] : a.max_code_len;
     return dispatch(a, h->lane_syms, (hipStream_t)stream);
 }
 
-int ecf8_decode_batched(const ecf8_batch_item *d_items, uint32_t n_tensors, uint64_t total_chunks,
-                        uint32_t lane_syms, void *stream)
+int ecf8_decode_batched(const ecf8_batch_item *d_items, uint32_t n_tensors, const ecf8_batch_info *info,
+                        void *stream)
 {
-    if (!d_items || n_tensors == 0 || total_chunks == 0) return ECF8_E_ARG;
+    if (!d_items || !info || n_tensors == 0 || info->total_chunks == 0) return ECF8_E_ARG;
     if ((uintptr_t)d_items & 15) return ECF8_E_ALIGN;
     KArgs a{};
     a.items = (const GLOBAL ecf8_batch_item *)(uintptr_t)d_items;
     a.n_items = n_tensors;
-    a.total_chunks = total_chunks;
-    return dispatch(a, lane_syms, (hipStream_t)stream);
+    a.total_chunks = info->total_chunks;
+    a.max_code_len = info->max_code_len;
+    return dispatch(a, info->lane_syms, (hipStream_t)stream);
 }
 
 } // extern "C"

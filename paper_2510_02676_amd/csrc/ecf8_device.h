@@ -153,6 +153,10 @@ __device__ __forceinline__ uint32_t lds_window(const uint8_t *smem, uint32_t bp)
 // that do not fit TB bits is one shared, rarely taken branch.  Returns the four
 // exponent fields of each run in their output byte positions (other bits are
 // noise the merge masks off) and moves bpA / bpB past the codewords.
+// PAIRFIT: no codeword is longer than TB/2 bits, so every pair is in the table and
+// the second level is compiled out (a blob that breaks the promise decodes to wrong
+// bytes, in bounds).
+template <bool PAIRFIT>
 __device__ __forceinline__ void quad_step2(const uint8_t *smem, const uint16_t *tbl, const uint32_t *s_len,
                                            const uint32_t *s_code, uint32_t &bpA, uint32_t &bpB,
                                            uint32_t &outA, uint32_t &outB)
@@ -168,7 +172,7 @@ __device__ __forceinline__ void quad_step2(const uint8_t *smem, const uint16_t *
     uint32_t nA2 = (eA2 >> 7) & 15u;
     uint32_t nB2 = (eB2 >> 7) & 15u;
     // n1 == 0 makes the second lookup repeat the first, so n2 == 0 covers both pairs of a run
-    if (__builtin_expect(nA2 == 0 || nB2 == 0, 0)) {
+    if (!PAIRFIT && __builtin_expect(nA2 == 0 || nB2 == 0, 0)) {
         if (nA2 == 0) {
             if (nA1 == 0) pair_second_level(wA, eA1, nA1, tbl, s_len, s_code);
             // the second level needs up to 30 bits: fresh window after the first pair

@@ -195,7 +195,7 @@ __global__ __launch_bounds__(GWAVES * 64) void ecf8_gemm_kernel(GArgs a)
                 for (int Q = 0; Q < GPIECES / 2; Q++) {
                     uint32_t dwA[4], dwB[4];
 #pragma unroll
-                    for (int t = 0; t < 4; t++) quad_step2(smem, tbl, s_len, s_code, bpA, bpB, dwA[t], dwB[t]);
+                    for (int t = 0; t < 4; t++) quad_step2<false>(smem, tbl, s_len, s_code, bpA, bpB, dwA[t], dwB[t]);
                     *(u32x4 *)(trow + (Q * 64 + lane) * 16) = merge_piece(dwA, pl[rr][Q]);
                     *(u32x4 *)(trow + ((Q + GPIECES / 2) * 64 + lane) * 16) = merge_piece(dwB, pl[rr][Q + GPIECES / 2]);
                 }

@@ -83,6 +83,36 @@ void huffman_lengths(const uint64_t freq[16], uint8_t len[16])
     }
 }
 
+// Cheapest code with every length <= lmax (package-merge): every symbol is a coin of weight
+// f at each of the lmax levels; level by level from the deepest, neighbouring pairs of the
+// sorted list are packaged and merged with the next level's coins; the 2k-2 cheapest items
+// of the last list say how often each symbol was taken = its code length.  A package is its
+// weight plus a 4-bit counter per symbol (a symbol enters at most once per level, lmax <= 15).
+void capped_lengths(const uint64_t freq[16], uint32_t lmax, uint8_t len[16])
+{
+    huffman_lengths(freq, len);
+    uint32_t mx = 0, k = 0;
+    for (int s = 0; s < 16; s++) { mx = std::max<uint32_t>(mx, len[s]); k += freq[s] != 0; }
+    if (mx <= lmax || k < 2) return;   // the cap does not bind
+    struct Item { uint64_t w, taken; };
+    std::vector<Item> coins;
+    for (int s = 0; s < 16; s++)
+        if (freq[s]) coins.push_back({freq[s], 1ull << (4 * s)});
+    auto by_weight = [](const Item &a, const Item &b) { return a.w < b.w; };
+    std::stable_sort(coins.begin(), coins.end(), by_weight);
+    std::vector<Item> cur = coins, next;
+    for (uint32_t level = 1; level < lmax; level++) {
+        next.clear();
+        for (size_t i = 0; i + 1 < cur.size(); i += 2) next.push_back({cur[i].w + cur[i + 1].w, cur[i].taken + cur[i + 1].taken});
+        std::vector<Item> merged(coins.size() + next.size());
+        std::merge(coins.begin(), coins.end(), next.begin(), next.end(), merged.begin(), by_weight);
+        cur.swap(merged);
+    }
+    uint64_t taken = 0;
+    for (size_t i = 0; i < 2 * (size_t)k - 2; i++) taken += cur[i].taken;
+    for (int s = 0; s < 16; s++) len[s] = (uint8_t)((taken >> (4 * s)) & 15);
+}
+
 // Canonical codes ordered by (length, symbol).  code = the codeword as a number
 // (first bit most significant); rcode = the same with its bit order reversed, so
 // that its first bit is bit 0.  Forward runs place rcode at ascending stream
@@ -227,7 +257,8 @@ int ecf8_encode(const uint8_t *x, uint64_t rows, uint64_t cols, const ecf8_encod
     const uint64_t n = rows * cols;
     const uint32_t N = (opts && opts->lane_syms) ? opts->lane_syms : 128;
     const uint32_t group = (opts && opts->group_chunks) ? opts->group_chunks : 32;
-    if (!lane_syms_ok(N) || !group_ok(group)) return ECF8_E_ARG;
+    const uint32_t lmax = (opts && opts->max_code_len) ? opts->max_code_len : ECF8_TB / 2;
+    if (!lane_syms_ok(N) || !group_ok(group) || lmax < 4 || lmax > 15) return ECF8_E_ARG;
     const ChunkMap map(n, N, group);
     unsigned nt = (opts && opts->n_threads) ? opts->n_threads : std::thread::hardware_concurrency();
     if (nt == 0) nt = 1;
@@ -261,7 +292,7 @@ int ecf8_encode(const uint8_t *x, uint64_t rows, uint64_t cols, const ecf8_encod
 
         uint8_t len[16];
         uint32_t rcode[16], code[16];
-        huffman_lengths(freq, len);
+        capped_lengths(freq, lmax, len);
         if (!canonical(len, rcode, code)) return ECF8_E_FORMAT;
         uint64_t bits = 0;
         for (int s = 0; s < 16; s++) bits += freq[s] * len[s];
@@ -483,11 +514,11 @@ int ecf8_blob_stats(const ecf8_header *h, ecf8_stats *s)
 }
 
 int ecf8_batch_prepare(const ecf8_header *hdrs, const void *const *d_blobs, void *const *d_outs,
-                       const uint64_t *caps, uint32_t n, ecf8_batch_item *items,
-                       uint64_t *total_chunks, uint32_t *lane_syms)
+                       const uint64_t *caps, uint32_t n, ecf8_batch_item *items, ecf8_batch_info *info)
 {
-    if (!hdrs || !d_blobs || !d_outs || !caps || !items || !total_chunks || !lane_syms || n == 0) return ECF8_E_ARG;
+    if (!hdrs || !d_blobs || !d_outs || !caps || !items || !info || n == 0) return ECF8_E_ARG;
     uint64_t first = 0;
+    uint32_t max_len = 0;
     for (uint32_t i = 0; i < n; i++) {
         const ecf8_header &h = hdrs[i];
         int rc = check_header(h, h.total_size);
@@ -511,10 +542,12 @@ int ecf8_batch_prepare(const ecf8_header *hdrs, const void *const *d_blobs, void
         it.off_table = h.table_bits ? 256 : 0;
         it.group_chunks = h.group_chunks;
         std::memcpy(it.code_len, h.code_len, 16);
+        for (int s = 0; s < 16; s++) max_len = std::max<uint32_t>(max_len, h.code_len[s]);
         first += h.n_chunks;
     }
-    *total_chunks = first;
-    *lane_syms = hdrs[0].lane_syms;
+    info->total_chunks = first;
+    info->lane_syms = hdrs[0].lane_syms;
+    info->max_code_len = max_len;
     return ECF8_OK;
 }
 

@@ -38,7 +38,8 @@ class Header(ctypes.Structure):
 
 class EncodeOpts(ctypes.Structure):
     _fields_ = [("lane_syms", ctypes.c_uint32), ("n_threads", ctypes.c_uint32),
-                ("table_mode", ctypes.c_uint32), ("group_chunks", ctypes.c_uint32)]
+                ("table_mode", ctypes.c_uint32), ("group_chunks", ctypes.c_uint32),
+                ("max_code_len", ctypes.c_uint32), ("reserved", ctypes.c_uint32 * 3)]
 
 
 class Stats(ctypes.Structure):
@@ -57,6 +58,11 @@ class BatchItem(ctypes.Structure):
                 ("reserved", ctypes.c_uint64 * 2)]
 
 
+class BatchInfo(ctypes.Structure):
+    _fields_ = [("total_chunks", ctypes.c_uint64), ("lane_syms", ctypes.c_uint32),
+                ("max_code_len", ctypes.c_uint32)]
+
+
 assert ctypes.sizeof(Header) == 256 and ctypes.sizeof(BatchItem) == 128
 
 _vp, _u64, _u32 = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32
@@ -73,8 +79,8 @@ _lib.ecf8_blob_stats.argtypes = [ctypes.POINTER(Header), ctypes.POINTER(Stats)]
 _lib.ecf8_decode.argtypes = [ctypes.POINTER(Header), _vp, _vp, _u64, _vp]
 _lib.ecf8_batch_prepare.argtypes = [ctypes.POINTER(Header), ctypes.POINTER(_vp), ctypes.POINTER(_vp),
                                     ctypes.POINTER(_u64), _u32, ctypes.POINTER(BatchItem),
-                                    ctypes.POINTER(_u64), ctypes.POINTER(_u32)]
-_lib.ecf8_decode_batched.argtypes = [_vp, _u32, _u64, _u32, _vp]
+                                    ctypes.POINTER(BatchInfo)]
+_lib.ecf8_decode_batched.argtypes = [_vp, _u32, ctypes.POINTER(BatchInfo), _vp]
 _lib.ecf8_gemm_fp8.argtypes = [ctypes.POINTER(Header), _vp, _vp, _u32, _vp, _vp]
 _lib.ecf8_gemm_fp8_raw.argtypes = [_vp, _u64, _u64, _vp, _u32, _vp, _vp]
 _lib.ecf8_strerror.argtypes = [ctypes.c_int]
@@ -134,16 +140,18 @@ class Blob:
             self._h = None
 
 
-def ecf8_encode(fp8, rows=None, cols=None, lane_syms=0, n_threads=0, table_mode=0, group_chunks=0):
+def ecf8_encode(fp8, rows=None, cols=None, lane_syms=0, n_threads=0, table_mode=0, group_chunks=0,
+                max_code_len=0):
     """CPU encoder: raw E4M3 bytes (host tensor / array) -> Blob.
     table_mode: 0 embed the decode table for tensors of >= 2^22 weights, 1 always, 2 never.
-    group_chunks: chunks interleaved per group (0 = default 32; 1 = chunk-major, what the fused GEMM needs)."""
+    group_chunks: chunks interleaved per group (0 = default 32; 1 = chunk-major, what the fused GEMM needs).
+    max_code_len: cap on the code length (0 = default 7; 15 = plain Huffman)."""
     x = _host_u8(fp8)
     if rows is None:
         rows, cols = (x.shape if x.ndim == 2 else (1, x.size))
     if rows * cols != x.size:
         raise Ecf8Error("ecf8_encode", E_ARG)
-    opts = EncodeOpts(lane_syms, n_threads, table_mode, group_chunks)
+    opts = EncodeOpts(lane_syms, n_threads, table_mode, group_chunks, max_code_len)
     h = _vp()
     _check("ecf8_encode", _lib.ecf8_encode(x.ctypes.data, rows, cols, ctypes.byref(opts), ctypes.byref(h)))
     return Blob(h)
@@ -194,22 +202,20 @@ class Batch:
         O = (_vp * n)(*[t.data_ptr() for t in d_outs])
         C = (_u64 * n)(*[t.numel() for t in d_outs])
         items = (BatchItem * n)()
-        total = _u64(0)
-        ls = _u32(0)
-        _check("ecf8_batch_prepare", _lib.ecf8_batch_prepare(H, B, O, C, n, items, ctypes.byref(total),
-                                                             ctypes.byref(ls)))
+        self.info = BatchInfo()
+        _check("ecf8_batch_prepare", _lib.ecf8_batch_prepare(H, B, O, C, n, items, ctypes.byref(self.info)))
         host = np.frombuffer(items, dtype=np.uint8).copy()
         self.d_items = torch.from_numpy(host).to(d_blobs[0].device)
         self.n = n
-        self.total_chunks = int(total.value)
-        self.lane_syms = int(ls.value)
+        self.total_chunks = int(self.info.total_chunks)
+        self.lane_syms = int(self.info.lane_syms)
+        self.max_code_len = int(self.info.max_code_len)
         self._keep = (list(d_blobs), list(d_outs))
 
 
 def ecf8_decode_batched(batch, stream=None):
     _check("ecf8_decode_batched", _lib.ecf8_decode_batched(batch.d_items.data_ptr(), batch.n,
-                                                           batch.total_chunks, batch.lane_syms,
-                                                           _stream_ptr(stream)))
+                                                           ctypes.byref(batch.info), _stream_ptr(stream)))
 
 
 def ecf8_gemm_fp8(hdr, d_blob, d_x, d_y=None, stream=None):

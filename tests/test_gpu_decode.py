@@ -39,13 +39,16 @@ def _oracle_expected(orc, x):
     return exp
 
 
+@pytest.mark.parametrize("max_code_len", [0, 15])
 @pytest.mark.parametrize("table_mode", [1, 2])
 @pytest.mark.parametrize("lane_syms", [32, 64, 128])
-def test_config0_parity(orc, lane_syms, table_mode):
+def test_config0_parity(orc, lane_syms, table_mode, max_code_len):
     """configs[0]: 1024x1024, alpha 1.8, per-128x128 scaling, seed 0; with the pair table
-    embedded in the blob (1) and built in the kernel (2)."""
+    embedded in the blob (1) and built in the kernel (2); with the default cap on the code
+    length (the kernels' branch-free form) and with plain Huffman (second level in use)."""
     w = synth.make(synth.config0()[0], seed=0).numpy().reshape(-1)
-    blob = ecf8.ecf8_encode(w, 1024, 1024, lane_syms=lane_syms, table_mode=table_mode)
+    blob = ecf8.ecf8_encode(w, 1024, 1024, lane_syms=lane_syms, table_mode=table_mode, max_code_len=max_code_len)
+    assert (max(blob.header.code_len) <= 7) == (max_code_len == 0)
     got, guards = _gpu_decode_guarded(blob.numpy(), blob.header)
     assert guards
     assert np.array_equal(got, _oracle_expected(orc, w))
@@ -58,7 +61,7 @@ def test_config0_parity(orc, lane_syms, table_mode):
 @pytest.mark.parametrize("n", [1, 15, 16, 17, 63, 2047, 2049, 4095, 4096, 4097, 8191, 8193, 3 * 8192 + 77, 1_000_003])
 def test_ragged_sizes(orc, lane_syms, n):
     x = _rand_bytes(n, 31 * n + lane_syms)
-    blob = ecf8.ecf8_encode(x, 1, n, lane_syms=lane_syms)
+    blob = ecf8.ecf8_encode(x, 1, n, lane_syms=lane_syms, max_code_len=15 if n % 2 else 0)
     got, guards = _gpu_decode_guarded(blob.numpy(), blob.header)
     assert guards
     assert np.array_equal(got, _oracle_expected(orc, x))
@@ -87,11 +90,12 @@ def _special_cases():
     }
 
 
+@pytest.mark.parametrize("cap", [0, 15])
 @pytest.mark.parametrize("lane_syms", [32, 64, 128])
 @pytest.mark.parametrize("name", sorted(_special_cases()))
-def test_degenerate_and_extreme_inputs(orc, name, lane_syms):
+def test_degenerate_and_extreme_inputs(orc, name, lane_syms, cap):
     x = _special_cases()[name]
-    blob = ecf8.ecf8_encode(x, 1, x.size, lane_syms=lane_syms, table_mode=1 + (lane_syms == 64))
+    blob = ecf8.ecf8_encode(x, 1, x.size, lane_syms=lane_syms, table_mode=1 + (lane_syms == 64), max_code_len=cap)
     got, guards = _gpu_decode_guarded(blob.numpy(), blob.header)
     assert guards
     assert np.array_equal(got, _oracle_expected(orc, x))
@@ -103,7 +107,8 @@ def test_group_widths(orc, lane_syms, group):
     chunk-major chunks, then a ragged last chunk."""
     n = 1_000_003 if group < 64 else 2_300_017
     x = _rand_bytes(n, 5 * lane_syms + group)
-    blob = ecf8.ecf8_encode(x, 1, n, lane_syms=lane_syms, group_chunks=group, table_mode=1 + (group % 3 == 1))
+    blob = ecf8.ecf8_encode(x, 1, n, lane_syms=lane_syms, group_chunks=group, table_mode=1 + (group % 3 == 1),
+                            max_code_len=15 if group in (2, 8) else 0)
     assert blob.header.group_chunks == group
     got, guards = _gpu_decode_guarded(blob.numpy(), blob.header)
     assert guards
@@ -136,11 +141,14 @@ def test_deterministic_and_on_side_stream(orc):
     assert np.array_equal(a.cpu().numpy().reshape(-1), _oracle_expected(orc, x))
 
 
-def test_batched_mixed_tensors(orc):
-    """Many tensors, each with its own code, sizes from one lane to many chunks, one launch."""
+@pytest.mark.parametrize("caps", [(0,), (0, 15, 9), (15,)])
+def test_batched_mixed_tensors(orc, caps):
+    """Many tensors, each with its own code, sizes from one lane to many chunks, one launch;
+    all under the default cap (branch-free kernel), mixed caps and plain Huffman (general kernel)."""
     sizes = [5, 4096, 70_000, 1, 333_333, 8192 * 3, 1_000_000, 17, 250_000]
     xs = [_rand_bytes(n, 100 + i, conc=0.2 + 0.1 * i) for i, n in enumerate(sizes)]
-    blobs = [ecf8.ecf8_encode(x, 1, x.size, table_mode=1 + (i % 2)) for i, x in enumerate(xs)]
+    blobs = [ecf8.ecf8_encode(x, 1, x.size, table_mode=1 + (i % 2), max_code_len=caps[i % len(caps)])
+             for i, x in enumerate(xs)]
     d_blobs = [b.to(DEV) for b in blobs]
     pad = 256
     bufs = [torch.full((pad + x.size + pad,), 0x5A, dtype=torch.uint8, device=DEV) for x in xs]
@@ -173,7 +181,7 @@ def test_batch_argument_errors():
 
 # ---------------------------------------------------------------- full-size cases
 
-def _full_size_case(orc, specs, oracle_checks):
+def _full_size_case(orc, specs, oracle_checks, max_code_len=0):
     """Encode/ decode `specs` (full-size tensors, generated on the GPU) in ONE batched launch, the
     launch configuration bench.py times.  Every output is compared with its input on the device
     (decode(encode(x)) == x is the plain definition of the result); the tensors named in
@@ -181,7 +189,7 @@ def _full_size_case(orc, specs, oracle_checks):
     ts = []
     for s in specs:
         w = synth.make(s, 0, device=DEV)
-        b = ecf8.ecf8_encode(w.cpu(), s["rows"], s["cols"])
+        b = ecf8.ecf8_encode(w.cpu(), s["rows"], s["cols"], max_code_len=max_code_len)
         ts.append((s, w, b.header, b.to(DEV), torch.full_like(w, 0xEE)))
     batch = ecf8.Batch([t[2] for t in ts], [t[3] for t in ts], [t[4] for t in ts])
     ecf8.ecf8_decode_batched(batch)
@@ -191,13 +199,17 @@ def _full_size_case(orc, specs, oracle_checks):
         if s["name"] in oracle_checks:
             x = w.cpu().numpy().reshape(-1)
             exp, nbits, _ = orc.roundtrip(x)
-            assert nbits == h.stream_bits
+            f = orc.histogram(x)
+            cap = max_code_len or 7
+            assert h.stream_bits == (nbits if cap >= 15 else orc.stream_bits(f, orc.huffman_lengths_limited(f, cap)))
             assert np.array_equal(out.cpu().numpy().reshape(-1), exp), s["name"]
 
 
-def test_config1_full_layer(orc):
-    """configs[1]: one full layer of the 8B-class stack (7 matrices, 218 M weights), one launch."""
-    _full_size_case(orc, synth.config1(0, 1), {"l0.k", "l0.q"})
+@pytest.mark.parametrize("max_code_len", [0, 15])
+def test_config1_full_layer(orc, max_code_len):
+    """configs[1]: one full layer of the 8B-class stack (7 matrices, 218 M weights), one launch;
+    under the default cap on the code length and with plain Huffman."""
+    _full_size_case(orc, synth.config1(0, 1), {"l0.k", "l0.q"}, max_code_len)
 
 
 def test_config2_experts_and_attention(orc):

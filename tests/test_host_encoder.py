@@ -31,17 +31,25 @@ def test_library_exports_every_declared_symbol():
     assert ecf8.version() == 1
 
 
+def _oracle_bits(orc, f, max_code_len):
+    """Cost of the cheapest code under the cap, from the oracle (0 = the encoder's default cap of 7)."""
+    cap = max_code_len or 7
+    return orc.stream_bits(f, orc.huffman_lengths(f) if cap >= 15 else orc.huffman_lengths_limited(f, cap))
+
+
+@pytest.mark.parametrize("max_code_len", [0, 15, 5])
 @pytest.mark.parametrize("lane_syms", [32, 64, 128])
 @pytest.mark.parametrize("n", [1, 7, 16, 2047, 2048, 4096, 4097, 8191, 8193, 100003])
-def test_encoder_container_read_by_oracle(orc, lane_syms, n):
+def test_encoder_container_read_by_oracle(orc, lane_syms, n, max_code_len):
     x = _rand_bytes(n, n + lane_syms)
-    blob = ecf8.ecf8_encode(x, 1, n, lane_syms=lane_syms)
+    blob = ecf8.ecf8_encode(x, 1, n, lane_syms=lane_syms, max_code_len=max_code_len)
     arr = blob.numpy()
     ecf8.blob_validate(arr)
     dec, bits = orc.container_decode(arr)
     assert np.array_equal(dec, x)
     f = orc.histogram(x)
-    assert bits == orc.stream_bits(f, orc.huffman_lengths(f)) == blob.header.stream_bits
+    assert max(blob.header.code_len) <= (max_code_len or 7)
+    assert bits == _oracle_bits(orc, f, max_code_len) == blob.header.stream_bits
     assert list(blob.header.freq) == [int(v) for v in f]
     assert blob.size == orc.lib().orc_container_size(n, bits, lane_syms)
 
@@ -129,11 +137,14 @@ def test_every_byte_value_and_special_histograms(orc):
     cases.append(deep)                                                  # code lengths up to 15
     for x in cases:
         for tm in (1, 2):
-            blob = ecf8.ecf8_encode(x, 1, x.size, table_mode=tm)
-            ecf8.blob_validate(blob.numpy())
-            dec, _ = orc.container_decode(blob.numpy())
-            assert np.array_equal(dec, x)
-    assert max(ecf8.ecf8_encode(deep, 1, deep.size).header.code_len) == 15
+            for cap in (0, 15):
+                blob = ecf8.ecf8_encode(x, 1, x.size, table_mode=tm, max_code_len=cap)
+                ecf8.blob_validate(blob.numpy())
+                dec, bits = orc.container_decode(blob.numpy())
+                assert np.array_equal(dec, x)
+                assert bits == _oracle_bits(orc, orc.histogram(x), cap)
+    assert max(ecf8.ecf8_encode(deep, 1, deep.size, max_code_len=15).header.code_len) == 15
+    assert max(ecf8.ecf8_encode(deep, 1, deep.size).header.code_len) == 7
 
 
 def test_hand_example_bytes_in_the_product_container():
@@ -172,6 +183,10 @@ def test_error_paths():
     for g in (3, 128):
         with pytest.raises(ecf8.Ecf8Error) as e:
             ecf8.ecf8_encode(x, 1, 1000, group_chunks=g)
+        assert e.value.code == ecf8.E_ARG
+    for cap in (3, 16):
+        with pytest.raises(ecf8.Ecf8Error) as e:
+            ecf8.ecf8_encode(x, 1, 1000, max_code_len=cap)
         assert e.value.code == ecf8.E_ARG
     good = ecf8.ecf8_encode(x, 10, 100).numpy().copy()
     ecf8.blob_validate(good)
