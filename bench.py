@@ -35,7 +35,7 @@ def algorithmic_bytes(h):
     return rd, h.n_elem
 
 
-def build_workload(name, seed, lane_syms, layers, launch="layer", group_chunks=0):
+def build_workload(name, seed, lane_syms, layers, launch="layer", group_chunks=0, max_code_len=0):
     from paper_2510_02676_amd import ecf8, synth
     if name == "config1":
         specs = synth.config1(seed, layers)
@@ -60,7 +60,8 @@ def build_workload(name, seed, lane_syms, layers, launch="layer", group_chunks=0
     t0 = time.time()
     for s in specs:
         w = synth.make(s, seed, device=dev)                       # uint8 (rows, cols) on the GPU
-        blob = ecf8.ecf8_encode(w.cpu(), s["rows"], s["cols"], lane_syms=lane_syms, group_chunks=group_chunks)
+        blob = ecf8.ecf8_encode(w.cpu(), s["rows"], s["cols"], lane_syms=lane_syms, group_chunks=group_chunks,
+                                max_code_len=max_code_len)
         d_blob = blob.to(dev)
         d_out = torch.empty((s["rows"], s["cols"]), dtype=torch.uint8, device=dev)
         groups.setdefault(group(s), []).append(dict(spec=s, w=w, hdr=blob.header, d_blob=d_blob, d_out=d_out))
@@ -102,7 +103,7 @@ def cpu_baseline(batches, budget_syms=440_000_000):
                 len(names), names[0], names[-1], tot_syms, tot_t)}
 
 
-def profiled_traffic(workload, launch, lane_syms, layers_full):
+def profiled_traffic(workload, launch, hdrs, layers_full):
     """HBM bytes per launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary of this
     exact workload, or None when no summary covers it."""
     if not layers_full:
@@ -112,7 +113,9 @@ def profiled_traffic(workload, launch, lane_syms, layers_full):
         text = open(path).read()
     except OSError:
         return None
-    if "workload=%s launch=%s lane_syms=%d" % (workload, launch, lane_syms) not in text:
+    key = "workload=%s launch=%s lane_syms=%d group_chunks=%d max_code_len=%d" % (
+        workload, launch, hdrs[0].lane_syms, hdrs[0].group_chunks, max(max(h.code_len) for h in hdrs))
+    if key not in text:
         return None
     for line in text.splitlines():
         if line.startswith("traffic_bytes_per_launch="):
@@ -207,6 +210,7 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="0 = the full stack of the workload")
     ap.add_argument("--lane-syms", type=int, default=0, help="0 = library default")
     ap.add_argument("--group-chunks", type=int, default=0, help="chunks interleaved per group, 0 = library default")
+    ap.add_argument("--max-code-len", type=int, default=0, help="cap on the code length, 0 = library default (7), 15 = plain Huffman")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--launch", default="stack", choices=["layer", "stack"],
                     help="stack: the whole stack in one launch per step; "
@@ -227,7 +231,7 @@ def main():
     if a.workload == "config4":
         return bench_config4(a)
     layers = a.layers or {"config1": 32, "config2": 256, "config3": 40, "config0": 1}[a.workload]
-    batches, desc, t_setup = build_workload(a.workload, a.seed, a.lane_syms, layers, a.launch, a.group_chunks)
+    batches, desc, t_setup = build_workload(a.workload, a.seed, a.lane_syms, layers, a.launch, a.group_chunks, a.max_code_len)
     hdrs = [t["hdr"] for _, ts in batches for t in ts]
     n_total = sum(h.n_elem for h in hdrs)
     blob_total = sum(h.total_size for h in hdrs)
@@ -275,7 +279,7 @@ def main():
         "dtype": "u8", "data": "synthetic",
         "config": {"workload": "%s: %s" % (a.workload, desc), "weights": n_total,
                    "launches_per_step": len(batches), "launch": a.launch, "lane_syms": hdrs[0].lane_syms,
-                   "group_chunks": hdrs[0].group_chunks,
+                   "group_chunks": hdrs[0].group_chunks, "max_code_len": max(max(h.code_len) for h in hdrs),
                    "seed": a.seed},
         "compression_ratio": round(blob_total / n_total, 5),
         "memory_saving_pct": round(100 * (1 - blob_total / n_total), 2),
@@ -289,7 +293,7 @@ def main():
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "avg_launch_us": round(launch_s * 1e6, 2),
                      "algorithmic_bytes_per_launch": int(alg_per_launch),
-                     "traffic": profiled_traffic(a.workload, a.launch, hdrs[0].lane_syms, a.layers == 0)},
+                     "traffic": profiled_traffic(a.workload, a.launch, hdrs, a.layers == 0)},
     }
     if a.launch == "stack" and not a.no_extra and len(batches[0][1]) > 1:
         out["per_layer_launch"] = per_layer_rates(batches[0][1], alg_total, n_total)
