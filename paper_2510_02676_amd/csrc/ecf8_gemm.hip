@@ -25,7 +25,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int GN = 64;                    // symbols per lane this kernel is built for
 constexpr int GK = 4096;                  // K: one chunk = one row of W
-constexpr int GWAVES = 8;
+constexpr int GWAVES_MAX = 16;
 constexpr int GSTAGE = GN * 32 + 64;      // as in the decode kernel
 constexpr int GSEGS = (GSTAGE / 16 + 63) / 64;
 constexpr int GPIECES = GN / 16;
@@ -34,9 +34,9 @@ constexpr int TILE_STRIDE = GK + 16;
 constexpr int G_OFF_TBL = 0;
 constexpr int G_OFF_SYM = G_OFF_TBL + TBL_ENTRIES * 2;
 constexpr int G_OFF_STAGE = G_OFF_SYM + 128;
-constexpr int G_OFF_TILE = G_OFF_STAGE + GWAVES * GSTAGE;
+constexpr int G_OFF_TILE = G_OFF_STAGE + GWAVES_MAX * GSTAGE;
 constexpr int G_TOTAL = G_OFF_TILE + TILE_ROWS * TILE_STRIDE;
-static_assert(GWAVES * GSTAGE + TILE_ROWS * TILE_STRIDE >= TBL_ENTRIES * 2, "table-build scratch");
+static_assert(GWAVES_MAX * GSTAGE + TILE_ROWS * TILE_STRIDE >= TBL_ENTRIES * 2, "table-build scratch");
 static_assert(G_TOTAL <= 160 * 1024, "LDS of one gfx950 CU");
 
 struct GArgs {
@@ -47,14 +47,15 @@ struct GArgs {
     uint32_t M;
 };
 
-constexpr int KSTEPS = GK / GWAVES / 32;  // MFMA steps of 32 over a wave's K slice
+constexpr int ksteps(int nw) { return GK / nw / 32; }  // MFMA steps of 32 over a wave's K slice
 
 // A operands of a wave: its K slice of X for every 16-row block, loaded once per workgroup and
 // kept in registers for all tiles (X is M x K <= 256 KiB: half of the CU's register file at
 // M = 64, but re-reading it from L2 for each of ~900 tiles costs more than everything else).
-template <int MT>
-__device__ __forceinline__ void load_x_slice(const GArgs &a, int tid, long (&areg)[MT][KSTEPS])
+template <int MT, int NW>
+__device__ __forceinline__ void load_x_slice(const GArgs &a, int tid, long (&areg)[MT][ksteps(NW)])
 {
+    constexpr int KSTEPS = ksteps(NW);
     const int lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, g = lane >> 4;
     const GLOBAL uint8_t *X = (const GLOBAL uint8_t *)a.d_x;
@@ -63,18 +64,19 @@ __device__ __forceinline__ void load_x_slice(const GArgs &a, int tid, long (&are
 #pragma unroll
         for (int s = 0; s < KSTEPS; s++) {
             const uint32_t m = 16 * mt + n;                                   // A row = lane & 15
-            const uint32_t k = wave * (GK / GWAVES) + 32 * s + 8 * g;
+            const uint32_t k = wave * (GK / NW) + 32 * s + 8 * g;
             areg[mt][s] = 0;
             if (m < a.M) areg[mt][s] = *(const GLOBAL long *)(X + (uint64_t)m * GK + k);
         }
 }
 
 // Multiply phase shared by both kernels: the tile in LDS times X, partial sums
-// reduced over the 8 waves, 16 x M results written.
-template <int MT>
+// reduced over the NW waves, 16 x M results written.
+template <int MT, int NW>
 __device__ __forceinline__ void multiply_tile(uint8_t *smem, const GArgs &a, uint64_t tile, int tid,
-                                              const long (&areg)[MT][KSTEPS])
+                                              const long (&areg)[MT][ksteps(NW)])
 {
+    constexpr int KSTEPS = ksteps(NW);
     const int lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, g = lane >> 4;
     uint8_t *tile_mem = smem + G_OFF_TILE;
@@ -84,7 +86,7 @@ __device__ __forceinline__ void multiply_tile(uint8_t *smem, const GArgs &a, uin
     f32x4 acc[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; mt++) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const uint32_t kbase = wave * (GK / GWAVES);
+    const uint32_t kbase = wave * (GK / NW);
 #pragma unroll
     for (int s = 0; s < KSTEPS; s++) {
         const uint32_t k = kbase + 32 * s + 8 * g;
@@ -100,20 +102,25 @@ __device__ __forceinline__ void multiply_tile(uint8_t *smem, const GArgs &a, uin
     __syncthreads();
     // a lane of the accumulator holds D[4*(lane>>4) + r][lane & 15], r = 0..3
     GLOBAL float *Y = (GLOBAL float *)a.d_y;
-    for (int o = tid; o < MT * 256; o += GWAVES * 64) {
+    for (int o = tid; o < MT * 256; o += NW * 64) {
         const int mt = o >> 8, l = (o >> 2) & 63, r = o & 3;
         float sum = 0.f;
 #pragma unroll
-        for (int w = 0; w < GWAVES; w++) sum += ((const float *)&red[(w * MT + mt) * 64 + l])[r];
+        for (int w = 0; w < NW; w++) sum += ((const float *)&red[(w * MT + mt) * 64 + l])[r];
         const uint32_t m = 16 * mt + 4 * (l >> 4) + r;
         if (m < a.M) Y[(uint64_t)m * a.rows + tile * TILE_ROWS + (l & 15)] = sum;
     }
     __syncthreads();                          // the tile area is free again
 }
 
-template <int MT>
-__global__ __launch_bounds__(GWAVES * 64) void ecf8_gemm_kernel(GArgs a)
+// NW waves per workgroup, each decoding RPW = 16 / NW rows of a tile.  The tile's metadata is
+// loaded two tiles ahead and its stream spans and nibble planes one tile ahead (into registers),
+// so the decode of a tile never waits for HBM.  PAIRFIT as in the decode kernel.
+template <int MT, int NW, bool PAIRFIT>
+__global__ __launch_bounds__(NW * 64) void ecf8_gemm_kernel(GArgs a)
 {
+    constexpr int RPW = TILE_ROWS / NW;
+    constexpr int KSTEPS = ksteps(NW);
     __shared__ __attribute__((aligned(16))) uint8_t smem[G_TOTAL];
     uint16_t *tbl = (uint16_t *)(smem + G_OFF_TBL);
     uint32_t *s_len = (uint32_t *)(smem + G_OFF_SYM);
@@ -128,82 +135,116 @@ __global__ __launch_bounds__(GWAVES * 64) void ecf8_gemm_kernel(GArgs a)
     const GLOBAL uint8_t *stream = (const GLOBAL uint8_t *)(a.d_blob + a.off_st);
     const GLOBAL uint8_t *plane = (const GLOBAL uint8_t *)(a.d_blob + a.off_pl);
 
+    struct Meta { uint64_t b0, b1; uint32_t lb; };
+    struct Payload { u32x4 seg[GSEGS]; u32x2 pl[GPIECES]; };
+    auto row_of = [&](uint64_t tile, int rr) -> uint64_t { return tile * TILE_ROWS + wave + NW * rr; };  // chunk = row
+    auto load_meta = [&](uint64_t cl) {
+        Meta m;
+        m.b0 = chunk_bit[cl];
+        m.b1 = chunk_bit[cl + 1];
+        m.lb = lane_bits[cl * 64 + lane];
+        return m;
+    };
+    auto span_of = [&](const Meta &m, uint64_t &byte0) {
+        uint64_t byte_end = ((m.b1 + 7) >> 3) + 8;
+        if (byte_end > a.st_bytes) byte_end = a.st_bytes;
+        byte0 = (m.b0 >> 3) & ~15ull;
+        if (byte0 > byte_end) byte0 = byte_end;
+        return byte_end - byte0;
+    };
+    auto load_payload = [&](uint64_t cl, const Meta &m) {
+        Payload p;
+        uint64_t byte0;
+        const uint64_t span = span_of(m, byte0);
+        const GLOBAL u32x2 *plane_c = (const GLOBAL u32x2 *)(plane + cl * (32ull * GN));
+#pragma unroll
+        for (int j = 0; j < GPIECES; j++) p.pl[j] = __builtin_nontemporal_load(&plane_c[j * 64 + lane]);
+#pragma unroll
+        for (int k = 0; k < GSEGS; k++) {
+            const uint32_t i = (lane + 64 * k) * 16;
+            p.seg[k] = u32x4{0, 0, 0, 0};
+            if (span <= (uint64_t)GSTAGE && i < (uint32_t)span)
+                p.seg[k] = __builtin_nontemporal_load((const GLOBAL u32x4 *)(stream + byte0 + i));
+        }
+        return p;
+    };
+
+    const uint64_t n_tiles = a.rows / TILE_ROWS;
+    uint64_t tile = blockIdx.x;
+    // start-up: the first tile's loads are in flight while the table is set up
+    Meta m_cur[RPW], m_next[RPW];
+    Payload p_cur[RPW];
+#pragma unroll
+    for (int rr = 0; rr < RPW; rr++) {
+        m_cur[rr] = Meta{0, 0, 0};
+        if (tile < n_tiles) m_cur[rr] = load_meta(row_of(tile, rr));
+        m_next[rr] = m_cur[rr];
+        if (tile + gridDim.x < n_tiles) m_next[rr] = load_meta(row_of(tile + gridDim.x, rr));
+    }
+#pragma unroll
+    for (int rr = 0; rr < RPW; rr++)
+        if (tile < n_tiles) p_cur[rr] = load_payload(row_of(tile, rr), m_cur[rr]);
+
     uint64_t len_lo, len_hi;
     __builtin_memcpy(&len_lo, a.code_len, 8);
     __builtin_memcpy(&len_hi, a.code_len + 8, 8);
     if (a.off_tbl) {
         const GLOBAL u32x4 *src = (const GLOBAL u32x4 *)(a.d_blob + a.off_tbl);
-        for (int i = tid; i < TBL_ENTRIES * 2 / 16; i += GWAVES * 64) ((u32x4 *)tbl)[i] = src[i];
+        for (int i = tid; i < TBL_ENTRIES * 2 / 16; i += NW * 64) ((u32x4 *)tbl)[i] = src[i];
         build_symbol_arrays(len_lo, len_hi, s_len, s_code, tid);
         __syncthreads();
     } else {
-        build_tables(len_lo, len_hi, tbl, s_len, s_code, (uint16_t *)(smem + G_OFF_STAGE), tid, GWAVES * 64);
+        build_tables(len_lo, len_hi, tbl, s_len, s_code, (uint16_t *)(smem + G_OFF_STAGE), tid, NW * 64);
     }
 
     long areg[MT][KSTEPS];
-    load_x_slice<MT>(a, tid, areg);
+    load_x_slice<MT, NW>(a, tid, areg);
 
-    const uint64_t n_tiles = a.rows / TILE_ROWS;
-    for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        // decode phase: this wave's two rows of the tile; both rows' loads are issued up front
-        uint64_t b0[2], b1[2], byte0[2], span[2];
-        uint32_t lb[2];
-        u32x4 seg[2][GSEGS];
-        u32x2 pl[2][GPIECES];
+    for (; tile < n_tiles; tile += gridDim.x) {
+        const uint64_t tile1 = tile + gridDim.x, tile2 = tile1 + gridDim.x;
 #pragma unroll
-        for (int rr = 0; rr < 2; rr++) {
-            const uint64_t cl = tile * TILE_ROWS + wave + 8 * rr;          // chunk = row
-            b0[rr] = chunk_bit[cl];
-            b1[rr] = chunk_bit[cl + 1];
-            lb[rr] = lane_bits[cl * 64 + lane];
-        }
+        for (int rr = 0; rr < RPW; rr++) {
+            const Meta m = m_cur[rr];
+            uint8_t *trow = tile_mem + (wave + NW * rr) * TILE_STRIDE;
+            uint64_t byte0;
+            const uint64_t span = span_of(m, byte0);
+            const uint32_t rel = wave_incl_scan(m.lb) - m.lb;
+            const uint64_t start = __builtin_amdgcn_readfirstlane((uint32_t)m.b0) |
+                                   ((uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)(m.b0 >> 32)) << 32);
+            const bool staged = __builtin_amdgcn_readfirstlane((uint32_t)(span <= (uint64_t)GSTAGE)) != 0;
+            u32x2 pl[GPIECES];
 #pragma unroll
-        for (int rr = 0; rr < 2; rr++) {
-            const uint64_t cl = tile * TILE_ROWS + wave + 8 * rr;
-            uint64_t byte_end = ((b1[rr] + 7) >> 3) + 8;
-            if (byte_end > a.st_bytes) byte_end = a.st_bytes;
-            byte0[rr] = (b0[rr] >> 3) & ~15ull;
-            if (byte0[rr] > byte_end) byte0[rr] = byte_end;
-            span[rr] = byte_end - byte0[rr];
-            const GLOBAL u32x2 *plane_c = (const GLOBAL u32x2 *)(plane + cl * (32ull * GN));
-#pragma unroll
-            for (int j = 0; j < GPIECES; j++) pl[rr][j] = plane_c[j * 64 + lane];
-#pragma unroll
-            for (int k = 0; k < GSEGS; k++) {
-                const uint32_t i = (lane + 64 * k) * 16;
-                seg[rr][k] = u32x4{0, 0, 0, 0};
-                if (span[rr] <= (uint64_t)GSTAGE && i < (uint32_t)span[rr])
-                    seg[rr][k] = *(const GLOBAL u32x4 *)(stream + byte0[rr] + i);
-            }
-        }
-#pragma unroll
-        for (int rr = 0; rr < 2; rr++) {
-            uint8_t *trow = tile_mem + (wave + 8 * rr) * TILE_STRIDE;
-            const uint32_t rel = wave_incl_scan(lb[rr]) - lb[rr];
-            const uint64_t start = __builtin_amdgcn_readfirstlane((uint32_t)b0[rr]) |
-                                   ((uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)(b0[rr] >> 32)) << 32);
-            const bool staged = __builtin_amdgcn_readfirstlane((uint32_t)(span[rr] <= (uint64_t)GSTAGE)) != 0;
+            for (int j = 0; j < GPIECES; j++) pl[j] = p_cur[rr].pl[j];
             if (staged) {
 #pragma unroll
                 for (int k = 0; k < GSEGS; k++) {
                     const uint32_t i = (lane + 64 * k) * 16;
-                    if (i < (uint32_t)GSTAGE) *(u32x4 *)(stage + i) = seg[rr][k];
+                    if (i < (uint32_t)GSTAGE) *(u32x4 *)(stage + i) = p_cur[rr].seg[k];
                 }
-                uint32_t bpA = stage_off * 8 + (uint32_t)(start - byte0[rr] * 8) + rel;
-                uint32_t bpB = bpA + lb[rr];
+            }
+            // this row's registers are free: fetch the same row of the next tile, and the
+            // metadata of the tile after it
+            Meta m_next2 = m_next[rr];
+            if (tile1 < n_tiles) {
+                p_cur[rr] = load_payload(row_of(tile1, rr), m_next[rr]);
+                if (tile2 < n_tiles) m_next2 = load_meta(row_of(tile2, rr));
+            }
+            if (staged) {
+                uint32_t bpA = stage_off * 8 + (uint32_t)(start - byte0 * 8) + rel;
+                uint32_t bpB = bpA + m.lb;
 #pragma unroll
                 for (int Q = 0; Q < GPIECES / 2; Q++) {
                     uint32_t dwA[4], dwB[4];
 #pragma unroll
-                    for (int t = 0; t < 4; t++) quad_step2<false>(smem, tbl, s_len, s_code, bpA, bpB, dwA[t], dwB[t]);
-                    *(u32x4 *)(trow + (Q * 64 + lane) * 16) = merge_piece(dwA, pl[rr][Q]);
-                    *(u32x4 *)(trow + ((Q + GPIECES / 2) * 64 + lane) * 16) = merge_piece(dwB, pl[rr][Q + GPIECES / 2]);
+                    for (int t = 0; t < 4; t++) quad_step2<PAIRFIT>(smem, tbl, s_len, s_code, bpA, bpB, dwA[t], dwB[t]);
+                    *(u32x4 *)(trow + (Q * 64 + lane) * 16) = merge_piece(dwA, pl[Q]);
+                    *(u32x4 *)(trow + ((Q + GPIECES / 2) * 64 + lane) * 16) = merge_piece(dwB, pl[Q + GPIECES / 2]);
                 }
             } else {
                 // span larger than the stage: symbol by symbol from HBM into the tile row
-                const GLOBAL uint8_t *sp = stream + byte0[rr];
-                uint64_t bA = (start - byte0[rr] * 8) + rel, bB = bA + lb[rr];
-                const uint64_t elem0 = (tile * TILE_ROWS + wave + 8 * rr) * (uint64_t)GK;
+                const GLOBAL uint8_t *sp = stream + byte0;
+                uint64_t bA = (start - byte0 * 8) + rel, bB = bA + m.lb;
+                const uint64_t elem0 = row_of(tile, rr) * (uint64_t)GK;
 #pragma unroll 1
                 for (int Q = 0; Q < GPIECES; Q++) {
                     const uint32_t o = (Q * 64 + lane) * 16;
@@ -220,36 +261,41 @@ __global__ __launch_bounds__(GWAVES * 64) void ecf8_gemm_kernel(GArgs a)
                     }
                 }
             }
+            m_cur[rr] = m_next[rr];
+            m_next[rr] = m_next2;
         }
         __syncthreads();
-        multiply_tile<MT>(smem, a, tile, tid, areg);
+        multiply_tile<MT, NW>(smem, a, tile, tid, areg);
     }
 }
 
-template <int MT>
-__global__ __launch_bounds__(GWAVES * 64) void ecf8_gemm_raw_kernel(GArgs a)
+// The same GEMM on uncompressed W, with the fused kernel's workgroup shape and K split, so that
+// the two agree bit for bit.
+template <int MT, int NW>
+__global__ __launch_bounds__(NW * 64) void ecf8_gemm_raw_kernel(GArgs a)
 {
+    constexpr int RPW = TILE_ROWS / NW, KSTEPS = ksteps(NW);
     __shared__ __attribute__((aligned(16))) uint8_t smem[G_TOTAL];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     uint8_t *tile_mem = smem + G_OFF_TILE;
     const GLOBAL uint8_t *W = (const GLOBAL uint8_t *)a.d_w;
     long areg[MT][KSTEPS];
-    load_x_slice<MT>(a, tid, areg);
+    load_x_slice<MT, NW>(a, tid, areg);
     const uint64_t n_tiles = a.rows / TILE_ROWS;
     for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        u32x4 v[2][GK / 1024];
+        u32x4 v[RPW][GK / 1024];
 #pragma unroll
-        for (int rr = 0; rr < 2; rr++)
-#pragma unroll
-            for (int j = 0; j < GK / 1024; j++)
-                v[rr][j] = *(const GLOBAL u32x4 *)(W + (tile * TILE_ROWS + wave + 8 * rr) * (uint64_t)GK + (j * 64 + lane) * 16);
-#pragma unroll
-        for (int rr = 0; rr < 2; rr++)
+        for (int rr = 0; rr < RPW; rr++)
 #pragma unroll
             for (int j = 0; j < GK / 1024; j++)
-                *(u32x4 *)(tile_mem + (wave + 8 * rr) * TILE_STRIDE + (j * 64 + lane) * 16) = v[rr][j];
+                v[rr][j] = *(const GLOBAL u32x4 *)(W + (tile * TILE_ROWS + wave + NW * rr) * (uint64_t)GK + (j * 64 + lane) * 16);
+#pragma unroll
+        for (int rr = 0; rr < RPW; rr++)
+#pragma unroll
+            for (int j = 0; j < GK / 1024; j++)
+                *(u32x4 *)(tile_mem + (wave + NW * rr) * TILE_STRIDE + (j * 64 + lane) * 16) = v[rr][j];
         __syncthreads();
-        multiply_tile<MT>(smem, a, tile, tid, areg);
+        multiply_tile<MT, NW>(smem, a, tile, tid, areg);
     }
 }
 
@@ -299,9 +345,19 @@ int ecf8_gemm_fp8(const ecf8_header *h, const void *d_blob, const void *d_x, uin
     const int grid = grid_for(a.rows / TILE_ROWS);
     if (grid <= 0) return ECF8_E_HIP;
     hipStream_t s = (hipStream_t)stream;
-    if (M <= 16) hipLaunchKernelGGL(ecf8_gemm_kernel<1>, dim3(grid), dim3(GWAVES * 64), 0, s, a);
-    else if (M <= 32) hipLaunchKernelGGL(ecf8_gemm_kernel<2>, dim3(grid), dim3(GWAVES * 64), 0, s, a);
-    else hipLaunchKernelGGL(ecf8_gemm_kernel<4>, dim3(grid), dim3(GWAVES * 64), 0, s, a);
+    uint32_t max_len = 0;
+    for (int i = 0; i < 16; i++) max_len = h->code_len[i] > max_len ? h->code_len[i] : max_len;
+    const bool pairfit = 2 * max_len <= (uint32_t)TB;
+    // 16 waves (one row of the tile each) while X fits their registers, 8 waves of two rows at M > 32
+#define ECF8_GEMM_LAUNCH(MT, NW)                                                                            \
+    do {                                                                                                   \
+        if (pairfit) hipLaunchKernelGGL((ecf8_gemm_kernel<MT, NW, true>), dim3(grid), dim3(NW * 64), 0, s, a);  \
+        else hipLaunchKernelGGL((ecf8_gemm_kernel<MT, NW, false>), dim3(grid), dim3(NW * 64), 0, s, a);         \
+    } while (0)
+    if (M <= 16) ECF8_GEMM_LAUNCH(1, 16);
+    else if (M <= 32) ECF8_GEMM_LAUNCH(2, 16);
+    else ECF8_GEMM_LAUNCH(4, 8);
+#undef ECF8_GEMM_LAUNCH
     return hipGetLastError() == hipSuccess ? ECF8_OK : ECF8_E_HIP;
 }
 
@@ -322,9 +378,9 @@ int ecf8_gemm_fp8_raw(const void *d_w, uint64_t rows, uint64_t cols, const void 
     const int grid = grid_for(rows / TILE_ROWS);
     if (grid <= 0) return ECF8_E_HIP;
     hipStream_t s = (hipStream_t)stream;
-    if (M <= 16) hipLaunchKernelGGL(ecf8_gemm_raw_kernel<1>, dim3(grid), dim3(GWAVES * 64), 0, s, a);
-    else if (M <= 32) hipLaunchKernelGGL(ecf8_gemm_raw_kernel<2>, dim3(grid), dim3(GWAVES * 64), 0, s, a);
-    else hipLaunchKernelGGL(ecf8_gemm_raw_kernel<4>, dim3(grid), dim3(GWAVES * 64), 0, s, a);
+    if (M <= 16) hipLaunchKernelGGL((ecf8_gemm_raw_kernel<1, 16>), dim3(grid), dim3(16 * 64), 0, s, a);
+    else if (M <= 32) hipLaunchKernelGGL((ecf8_gemm_raw_kernel<2, 16>), dim3(grid), dim3(16 * 64), 0, s, a);
+    else hipLaunchKernelGGL((ecf8_gemm_raw_kernel<4, 8>), dim3(grid), dim3(8 * 64), 0, s, a);
     return hipGetLastError() == hipSuccess ? ECF8_OK : ECF8_E_HIP;
 }
 
