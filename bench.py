@@ -169,8 +169,10 @@ def bench_config4(a):
 
     spec = synth.config4()[0]
     w = synth.make(spec, a.seed, device="cuda:0")
-    blob = ecf8.ecf8_encode(w.cpu(), spec["rows"], spec["cols"], lane_syms=64, group_chunks=1)
+    blob = ecf8.ecf8_encode(w.cpu(), spec["rows"], spec["cols"], lane_syms=64, tile_rows=16)
     h, d_blob, wout = blob.header, blob.to("cuda:0"), torch.empty_like(w)
+    lin = ecf8.ecf8_encode(w.cpu(), spec["rows"], spec["cols"])     # default layout, for the decode-then-GEMM leg
+    h_lin, d_lin = lin.header, lin.to("cuda:0")
     res = {}
     for M in (1, 16, 64):
         x = synth.activations(M, spec["cols"], seed=a.seed, device="cuda:0")
@@ -183,7 +185,7 @@ def bench_config4(a):
             raise SystemExit("fused GEMM differs from the GEMM on uncompressed weights at M=%d" % M)
 
         def two():
-            ecf8.ecf8_decode(h, d_blob, wout)
+            ecf8.ecf8_decode(h_lin, d_lin, wout)
             ecf8.ecf8_gemm_fp8_raw(wout, x, y2)
         tf = timeit(lambda: ecf8.ecf8_gemm_fp8(h, d_blob, x, y), a.steps, a.warmup)
         tr = timeit(lambda: ecf8.ecf8_gemm_fp8_raw(w, x, y2), a.steps, a.warmup)

@@ -56,6 +56,14 @@
  *               G > 1 interleaves the G chunks of a group KiB by KiB: the
  *               pieces a wavefront touches back to back lie G KiB apart and
  *               the wavefronts of a workgroup fill the gaps (see group_chunks).
+ *               Row-tiled layout (tile_rows = 16): with KC = cols / 4N chunks
+ *               per block of 16 rows, chunk c = b*KC + kc holds rows
+ *               16b .. 16b+15, columns 4N*kc .. 4N*(kc+1); the k-th symbol of
+ *               lane l is the matrix element
+ *                   row 16b + l%16,  column 4N*kc + 64*(k/16) + 16*(l/16) + k%16
+ *               i.e. element index row*cols + column: in every decode step lane
+ *               l holds 8 consecutive K-elements of row l%16, which is a lane's
+ *               share of the B operand of v_mfma_f32_16x16x32_fp8_fp8.
  *               Symbols k < N/2 are written forward
  *               from bit S upwards (a codeword's first = most significant bit
  *               lowest), symbols k >= N/2 backward from bit S + lane_bits - 1
@@ -99,10 +107,15 @@ typedef struct ecf8_header {
     uint64_t rows, cols;
     uint32_t lane_syms;       /* N: symbols per lane, one of 32, 64, 128         */
     uint16_t table_bits;      /* 0: no embedded table; 14: table section present */
-    uint16_t group_chunks;    /* G: chunks interleaved per group, a power of two */
+    uint8_t group_chunks;     /* G: chunks interleaved per group, a power of two */
                               /* <= 64.  HBM serves a wavefront's consecutive     */
                               /* 1 KiB accesses faster when they are >= 16 KiB    */
                               /* apart (measured: +15 % at G = 32 against G = 1)  */
+    uint8_t tile_rows;        /* 0: linear layout (above); 16: row-tiled layout,  */
+                              /* a chunk is a 16-row x 4N-column block of the     */
+                              /* matrix, laid out as the FP8 matrix cores read    */
+                              /* their B operand (see below); needs G == 1,       */
+                              /* rows % 16 == 0, cols % 4N == 0                   */
     uint64_t n_chunks;        /* ceil(n_elem / (64 N))                           */
     uint64_t stream_bits;     /* sum over elements of their code length          */
     uint8_t code_len[16];     /* code length of exponent field x, 0 = absent     */
@@ -116,7 +129,7 @@ typedef struct ecf8_encode_opts {
     uint32_t n_threads;  /* host threads for encoding, 0 = all hardware threads  */
     uint32_t table_mode; /* 0 = embed the table when n_elem >= 2^22 (32 KiB is   */
                          /* then < 0.8 % of the tensor), 1 = always, 2 = never   */
-    uint32_t group_chunks; /* 0 = default (32); 1 is what ecf8_gemm_fp8 needs      */
+    uint32_t group_chunks; /* 0 = default (32, or 1 in the row-tiled layout)       */
     uint32_t max_code_len; /* cap on the code length, 4..15; 0 = default (7 = half */
                            /* the decoder's table index, so that two codewords     */
                            /* always resolve in one lookup and the decode kernels  */
@@ -124,7 +137,9 @@ typedef struct ecf8_encode_opts {
                            /* length too (at 16, by adjusting frequencies); here   */
                            /* the capped code is the cheapest one (package-merge). */
                            /* 15 never binds: plain Huffman                        */
-    uint32_t reserved[3];
+    uint32_t tile_rows;    /* 0 = linear layout; 16 = row-tiled layout (what       */
+                           /* ecf8_gemm_fp8 needs; group_chunks must be 0 or 1)    */
+    uint32_t reserved[2];
 } ecf8_encode_opts;
 
 typedef struct ecf8_stats {
@@ -193,7 +208,8 @@ typedef struct ecf8_batch_item {
     uint8_t code_len[16];
     uint64_t off_table;    /* 0 = the blob holds no table                        */
     uint64_t group_chunks; /* G of the tensor's header                           */
-    uint64_t reserved[2];
+    uint64_t tile_cols;    /* 0: linear layout; else cols of a row-tiled tensor  */
+    uint64_t reserved[1];
 } ecf8_batch_item; /* 128 bytes */
 
 /* What a batched launch needs to know on the host. */
@@ -229,9 +245,10 @@ int ecf8_decode_batched(const ecf8_batch_item *d_items, uint32_t n_tensors,
  *   Y[m][n] = sum_k X[m][k] * W[n][k]   (fp32 accumulate)
  * W: the rows x cols tensor held by the blob (hdr / d_blob as for ecf8_decode);
  * d_x: DEVICE, M x cols FP8 E4M3 bytes, row-major, 16-byte aligned, 1 <= M <= 64;
- * d_y: DEVICE, M x rows fp32, row-major.  Supported shape for now: cols == 4096,
- * rows a multiple of 16, lane_syms == 64, group_chunks == 1 (one chunk = one row
- * of W; ECF8_E_ARG otherwise).  Values are
+ * d_y: DEVICE, M x rows fp32, row-major.  Supported for now: cols == 4096, rows a
+ * multiple of 16, a blob in the row-tiled layout (tile_rows == 16) with
+ * lane_syms == 64 and no codeword longer than 7 bits (the encoder's default
+ * cap); ECF8_E_ARG otherwise.  Values are
  * used as stored (unit scales); NaN encodings propagate as NaN.
  * ecf8_gemm_fp8_raw: the same GEMM on uncompressed W (d_w: DEVICE, rows x cols
  * bytes, 16-byte aligned), the baseline the fused call is compared with.

@@ -154,7 +154,7 @@ def roundtrip(x):
     return out, int(nbits.value), ln
 
 
-def container_encode(x, rows, cols, lane_syms, group_chunks=1, max_code_len=15):
+def container_encode(x, rows, cols, lane_syms, group_chunks=1, max_code_len=15, tile_rows=0):
     x = _u8(x)
     assert x.size == rows * cols
     cap = int(lib().orc_container_size(x.size, x.size * 15, lane_syms)) + 256
@@ -162,7 +162,7 @@ def container_encode(x, rows, cols, lane_syms, group_chunks=1, max_code_len=15):
     size = ctypes.c_uint64(0)
     rc = lib().orc_container_encode(_p(x), ctypes.c_uint64(rows), ctypes.c_uint64(cols),
                                     ctypes.c_uint32(lane_syms), ctypes.c_uint32(group_chunks),
-                                    ctypes.c_uint32(max_code_len), _p(blob),
+                                    ctypes.c_uint32(max_code_len), ctypes.c_uint32(tile_rows), _p(blob),
                                     ctypes.c_uint64(cap),
                                     ctypes.byref(size))
     if rc:

@@ -16,7 +16,9 @@
  *     8   u64 total_size                    16  u64 n_elem
  *     24  u64 rows                          32  u64 cols
  *     40  u32 lane_syms N                   44  u16 table_bits (0 or 14)
- *     46  u16 group_chunks G (power of two, 1..64)
+ *     46  u8  group_chunks G (power of two, 1..64)
+ *     47  u8  tile_rows (0: linear layout; 16: row-tiled layout, needs G = 1,
+ *             rows % 16 = 0, cols % 4N = 0)
  *     48  u64 n_chunks = ceil(n_elem/(64N)) 56  u64 stream_bits
  *     64  u8  code_len[16]
  *     80  u64 off_chunk_bit   88 u64 off_lane_bits
@@ -44,7 +46,12 @@
  *                 c >= G*F: base = c*64N,                      stride = 1024
  *               (inside a whole group the 1024-element blocks of its G chunks
  *               alternate; the rest of the tensor is chunk after chunk);
- *               elements >= n_elem do not exist and are skipped.  Symbols k < N/2 are coded FORWARD from
+ *               elements >= n_elem do not exist and are skipped.
+ *               Row-tiled layout: the matrix is cut into blocks of 16 rows x
+ *               4N columns, numbered along a row of blocks first; chunk c is
+ *               block c.  Lane l works on row l%16 of the block; its k-th
+ *               symbol is column 64*(k/16) + 16*(l/16) + k%16 of the block
+ *               (element index = row*cols + column of the whole matrix).  Symbols k < N/2 are coded FORWARD from
  *               bit S upwards (a codeword's first = most significant bit at
  *               the lowest position); symbols k >= N/2 are coded BACKWARD from
  *               bit S + lane_bits - 1 downwards (first bit at the highest
@@ -98,21 +105,38 @@ static void wr32(uint8_t *p, uint32_t v) { for (int i = 0; i < 4; i++) p[i] = (u
 static void wr16(uint8_t *p, uint32_t v) { p[0] = (uint8_t)v; p[1] = (uint8_t)(v >> 8); }
 static uint64_t up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 
-/* element coded by the k-th symbol of lane l of chunk c of an n-element tensor */
-static uint64_t lane_element(uint64_t c, uint64_t l, uint64_t k, uint32_t N, uint32_t G, uint64_t n)
+/* element coded by the k-th symbol of lane l of chunk c */
+typedef struct { uint32_t N, G, tile_rows; uint64_t n, cols; } orc_layout;
+
+static uint64_t lane_element(const orc_layout *L, uint64_t c, uint64_t l, uint64_t k)
 {
-    uint64_t chunk = 64ull * N;
-    uint64_t whole_groups = n / (G * chunk);
+    uint64_t chunk = 64ull * L->N;
+    if (L->tile_rows) {
+        uint64_t block_cols = 4ull * L->N;
+        uint64_t blocks_per_row = L->cols / block_cols;
+        uint64_t block_row = c / blocks_per_row, block_col = c % blocks_per_row;
+        uint64_t row = block_row * 16 + l % 16;
+        uint64_t col = block_col * block_cols + 64 * (k / 16) + 16 * (l / 16) + k % 16;
+        return row * L->cols + col;
+    }
+    uint64_t whole_groups = L->n / (L->G * chunk);
     uint64_t base, stride;
-    if (c < G * whole_groups) {
-        uint64_t slot = c % G;
+    if (c < L->G * whole_groups) {
+        uint64_t slot = c % L->G;
         base = (c - slot) * chunk + slot * 1024;
-        stride = (uint64_t)G * 1024;
+        stride = (uint64_t)L->G * 1024;
     } else {
         base = c * chunk;
         stride = 1024;
     }
     return base + (k / 16) * stride + l * 16 + (k % 16);
+}
+
+static int layout_ok(const orc_layout *L, uint64_t rows)
+{
+    if (L->G == 0 || L->G > 64 || (L->G & (L->G - 1))) return 0;
+    if (L->tile_rows == 0) return 1;
+    return L->tile_rows == 16 && L->G == 1 && rows % 16 == 0 && L->cols % (4ull * L->N) == 0;
 }
 
 static uint64_t plane_byte_index(uint64_t i) { return (i / 8) * 4 + (i % 4); }
@@ -135,11 +159,12 @@ uint64_t orc_container_size(uint64_t n, uint64_t stream_bits, uint32_t N)
 /* Writer: encodes x (rows*cols raw E4M3 bytes) into blob (capacity cap).
  * Follows Section 3.1 for histogram, optimal code and in-order stream. */
 int orc_container_encode(const uint8_t *x, uint64_t rows, uint64_t cols, uint32_t N, uint32_t G,
-                         uint32_t max_code_len, uint8_t *blob, uint64_t cap, uint64_t *size_out)
+                         uint32_t max_code_len, uint32_t tile_rows, uint8_t *blob, uint64_t cap, uint64_t *size_out)
 {
     uint64_t n = rows * cols;
     if (n == 0 || N == 0 || (N % 16) != 0 || N > 256) return ORC_E_ARG;
-    if (G == 0 || G > 64 || (G & (G - 1))) return ORC_E_ARG;
+    orc_layout lay = {N, G, tile_rows, n, cols};
+    if (!layout_ok(&lay, rows)) return ORC_E_ARG;
     uint64_t freq[ORC_NSYM];
     uint8_t len[ORC_NSYM];
     uint16_t code[ORC_NSYM];
@@ -172,7 +197,8 @@ int orc_container_encode(const uint8_t *x, uint64_t rows, uint64_t cols, uint32_
     wr64(blob + 32, cols);
     wr32(blob + 40, N);
     wr16(blob + 44, 0); /* this writer embeds no decoder table */
-    wr16(blob + 46, G);
+    blob[46] = (uint8_t)G;
+    blob[47] = (uint8_t)tile_rows;
     wr64(blob + 48, n_chunks);
     wr64(blob + 56, bits);
     for (int i = 0; i < ORC_NSYM; i++) blob[64 + i] = len[i];
@@ -193,7 +219,7 @@ int orc_container_encode(const uint8_t *x, uint64_t rows, uint64_t cols, uint32_
         for (uint64_t l = 0; l < 64; l++) {
             uint64_t lb = 0;
             for (uint64_t k = 0; k < N; k++) {
-                uint64_t e = lane_element(c, l, k, N, G, n);
+                uint64_t e = lane_element(&lay, c, l, k);
                 if (e >= n) continue;
                 uint8_t sg, ex, mn;
                 orc_split(x[e], &sg, &ex, &mn);
@@ -201,7 +227,7 @@ int orc_container_encode(const uint8_t *x, uint64_t rows, uint64_t cols, uint32_
             }
             uint64_t fwd = pos, bwd = pos + lb; /* bwd: one past the next bit to write */
             for (uint64_t k = 0; k < N; k++) {
-                uint64_t e = lane_element(c, l, k, N, G, n);
+                uint64_t e = lane_element(&lay, c, l, k);
                 if (e >= n) continue;
                 uint8_t sg, ex, mn;
                 orc_split(x[e], &sg, &ex, &mn);
@@ -245,7 +271,7 @@ int orc_container_decode(const uint8_t *blob, uint64_t size, uint8_t *out, uint6
     if (rd32(blob) != 0x38464345u || rd32(blob + 4) != 1) return ORC_E_FORMAT;
     uint64_t total = rd64(blob + 8), n = rd64(blob + 16);
     uint64_t rows = rd64(blob + 24), cols = rd64(blob + 32);
-    uint32_t N = rd32(blob + 40), TBITS = rd16(blob + 44), G = rd16(blob + 46);
+    uint32_t N = rd32(blob + 40), TBITS = rd16(blob + 44), G = blob[46], TR = blob[47];
     uint64_t n_chunks = rd64(blob + 48), bits = rd64(blob + 56);
     uint8_t len[ORC_NSYM];
     for (int i = 0; i < ORC_NSYM; i++) len[i] = blob[64 + i];
@@ -254,7 +280,8 @@ int orc_container_decode(const uint8_t *blob, uint64_t size, uint8_t *out, uint6
     uint64_t st_bytes = rd64(blob + 112), pl_bytes = rd64(blob + 120);
     if (total != size || n == 0 || rows * cols != n) return ORC_E_FORMAT;
     if ((TBITS != 0 && TBITS != 14) || N == 0 || (N % 16) != 0 || N > 256) return ORC_E_FORMAT;
-    if (G == 0 || G > 64 || (G & (G - 1))) return ORC_E_FORMAT;
+    orc_layout lay = {N, G, TR, n, cols};
+    if (!layout_ok(&lay, rows)) return ORC_E_FORMAT;
     uint64_t tbytes = TBITS ? (2ull << TBITS) : 0;
     uint64_t chunk = 64ull * N;
     if (n_chunks != (n + chunk - 1) / chunk) return ORC_E_FORMAT;
@@ -316,7 +343,7 @@ int orc_container_decode(const uint8_t *blob, uint64_t size, uint8_t *out, uint6
         for (uint64_t l = 0; l < 64 && rc == ORC_OK; l++) {
             uint64_t cntA = 0, cntB = 0;
             for (uint64_t k = 0; k < N; k++)
-                if (lane_element(c, l, k, N, G, n) < n) { if (k < N / 2) cntA++; else cntB++; }
+                if (lane_element(&lay, c, l, k) < n) { if (k < N / 2) cntA++; else cntB++; }
             uint64_t lb = rd16(blob + off_lb + 2 * (c * 64 + l));
             if (cntA + cntB == 0) { if (lb != 0) rc = ORC_E_META; continue; }
             if (pos + lb > bits) { rc = ORC_E_META; break; }
@@ -329,7 +356,7 @@ int orc_container_decode(const uint8_t *blob, uint64_t size, uint8_t *out, uint6
             if (r2 || endA != endB + 1) { rc = ORC_E_META; break; }
             uint64_t j = 0;
             for (uint64_t k = 0; k < N; k++) {
-                uint64_t e = lane_element(c, l, k, N, G, n);
+                uint64_t e = lane_element(&lay, c, l, k);
                 if (e < n) { sym[e] = lane_sym[j++]; done++; }
             }
             pos += lb;

@@ -101,7 +101,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
     while (c < c_end) {
         // which tensor holds chunk c (uniform)
         uint64_t d_blob, d_out, n_elem, n_chunks, first_chunk, off_cb, off_lb, off_st, off_pl, st_bytes;
-        uint64_t len_lo, len_hi, off_tbl, group;
+        uint64_t len_lo, len_hi, off_tbl, group, tcols;
         if (a.items) {
             uint32_t lo = 0, hi = a.n_items - 1;
             while (lo < hi) {
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
             d_blob = p->d_blob; d_out = p->d_out; n_elem = p->n_elem; n_chunks = p->n_chunks;
             first_chunk = p->first_chunk; off_cb = p->off_chunk_bit; off_lb = p->off_lane_bits;
             off_st = p->off_stream; off_pl = p->off_plane; st_bytes = p->stream_bytes;
-            off_tbl = p->off_table; group = p->group_chunks;
+            off_tbl = p->off_table; group = p->group_chunks; tcols = p->tile_cols;
             const GLOBAL uint64_t *cl8 = (const GLOBAL uint64_t *)p->code_len;
             len_lo = cl8[0]; len_hi = cl8[1];
         } else {
@@ -120,7 +120,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
             n_chunks = a.single.n_chunks; first_chunk = 0; off_cb = a.single.off_chunk_bit;
             off_lb = a.single.off_lane_bits; off_st = a.single.off_stream; off_pl = a.single.off_plane;
             st_bytes = a.single.stream_bytes;
-            off_tbl = a.single.off_table; group = a.single.group_chunks;
+            off_tbl = a.single.off_table; group = a.single.group_chunks; tcols = a.single.tile_cols;
             __builtin_memcpy(&len_lo, a.single.code_len, 8);
             __builtin_memcpy(&len_hi, a.single.code_len + 8, 8);
         }
@@ -137,13 +137,21 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
         // KiB by KiB (a wave's consecutive pieces lie group KiB apart, the other waves of
         // the workgroup fill the gaps: HBM serves that markedly faster than a wave
         // walking 1 KiB steps); the rest of the tensor is chunk-major.
+        // Row-tiled layout (tcols != 0): chunk cl is the block of 16 rows x 4N columns number cl
+        // of a tcols-wide matrix, lane l works on row l % 16, its piece q on columns
+        // 64 q + 16 (l / 16) of the block.  lane_off is the lane's share of all of this.
         if (group == 0) group = 1;
         const uint64_t grouped = (n_elem / (64ull * N)) & ~(group - 1);   // chunks in whole groups (group is a power of two)
+        const uint64_t blocks_per_row = tcols ? tcols / (4ull * N) : 1;
         auto chunk_base = [&](uint64_t cl) -> uint64_t {
+            if (tcols) return (cl / blocks_per_row) * 16 * tcols + (cl % blocks_per_row) * (4ull * N);
             const uint64_t w = cl & (group - 1);
             return cl < grouped ? (cl - w) * (64ull * N) + w * 1024 : cl * (64ull * N);
         };
-        auto chunk_stride = [&](uint64_t cl) -> uint32_t { return cl < grouped ? (uint32_t)group * 1024u : 1024u; };
+        auto chunk_stride = [&](uint64_t cl) -> uint32_t {
+            return tcols ? 64u : cl < grouped ? (uint32_t)group * 1024u : 1024u;
+        };
+        const uint64_t lane_off = tcols ? (uint64_t)(lane & 15) * tcols + (uint64_t)(lane >> 4) * 16 : (uint64_t)lane * 16;
 
         __syncthreads(); // every wave is done with the previous tensor's table and its scratch
         // the first two chunks of a wave are fixed (c + wave, c + WAVES + wave); later ones are drawn
@@ -174,7 +182,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
             Payload p;
             uint64_t byte0;
             const uint64_t span64 = span_of(m, byte0);
-            const GLOBAL uint8_t *plane_c = plane + chunk_base(cl) / 2 + lane * 8;
+            const GLOBAL uint8_t *plane_c = plane + (chunk_base(cl) + lane_off) / 2;
             const uint32_t pstride = chunk_stride(cl) / 2;
 #pragma unroll
             for (int j = 0; j < C::PIECES; j++) p.pl[j] = LD_STREAM((const GLOBAL u32x2 *)(plane_c + j * pstride));
@@ -247,7 +255,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
             __builtin_amdgcn_s_waitcnt(0x0F70);
             for (;;) {
                 const uint64_t cl = cg - first_chunk;            // chunk index inside the tensor
-                GLOBAL uint8_t *out_c = out + chunk_base(cl) + lane * 16;   // this lane's piece 0
+                GLOBAL uint8_t *out_c = out + chunk_base(cl) + lane_off;   // this lane's piece 0
                 const uint32_t ostride = chunk_stride(cl);
                 const uint64_t b0 = __builtin_amdgcn_readfirstlane((uint32_t)m_cur.b0) |
                                     ((uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)(m_cur.b0 >> 32)) << 32);
@@ -341,7 +349,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
                 uint64_t bB = bA + m.lb;                  // backward run: one past the next bit
 #pragma unroll 1
                 for (int Q = 0; Q < C::PIECES; Q++) {
-                    const uint64_t o = elem0 + (uint64_t)Q * estride + lane * 16;
+                    const uint64_t o = elem0 + (uint64_t)Q * estride + lane_off;
                     const bool fwd = Q < C::PIECES / 2;
 #pragma unroll 1
                     for (uint32_t i = 0; i < 16 && o + i < n_elem; i++) {
@@ -399,6 +407,9 @@ int ecf8_decode(const ecf8_header *h, const void *d_blob, void *d_out, uint64_t 
         (h->table_bits != 0 && h->table_bits != ECF8_TB) || h->group_chunks == 0 || h->group_chunks > 64 ||
         (h->group_chunks & (h->group_chunks - 1)))
         return ECF8_E_FORMAT;
+    if (h->tile_rows != 0 && (h->tile_rows != 16 || h->group_chunks != 1 || h->rows % 16 != 0 || h->cols == 0 ||
+                              h->cols % (4ull * h->lane_syms) != 0 || h->n_elem != h->rows * h->cols))
+        return ECF8_E_FORMAT;
     if (h->n_chunks != (h->n_elem + 64ull * h->lane_syms - 1) / (64ull * h->lane_syms)) return ECF8_E_FORMAT;
     if (h->off_plane + h->plane_bytes > h->total_size || h->off_stream + h->stream_bytes > h->off_plane ||
         h->plane_bytes != h->n_chunks * 32ull * h->lane_syms)
@@ -418,6 +429,7 @@ int ecf8_decode(const ecf8_header *h, const void *d_blob, void *d_out, uint64_t 
     a.single.stream_bytes = h->stream_bytes;
     a.single.off_table = h->table_bits ? 256 : 0;
     a.single.group_chunks = h->group_chunks;
+    a.single.tile_cols = h->tile_rows ? h->cols : 0;
     for (int i = 0; i < 16; i++) a.single.code_len[i] = h->code_len[i];
     a.items = nullptr;
     a.n_items = 1;

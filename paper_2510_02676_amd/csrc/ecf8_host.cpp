@@ -35,14 +35,28 @@ inline uint64_t round_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 bool lane_syms_ok(uint32_t n) { return n == 32 || n == 64 || n == 128; }
 bool group_ok(uint32_t g) { return g >= 1 && g <= 64 && (g & (g - 1)) == 0; }
 
-// Where chunk c's pieces lie: piece q of lane l starts at element base + q*stride + l*16.
-// Chunks of whole groups are interleaved KiB by KiB, the rest of the tensor is chunk-major.
+// Where chunk c's pieces lie: piece q of lane l is the 16 elements from piece(c, l, q).
+// Linear layout: chunks of whole groups are interleaved KiB by KiB, the rest of the tensor is
+// chunk-major.  Row-tiled layout: a chunk is a block of 16 rows x 4N columns, lane l works on
+// row l % 16, its piece q on columns 64 q + 16 (l / 16) of the block.
 struct ChunkMap {
     uint64_t E, G, grouped; // elements per chunk, chunks per group, chunks that lie in whole groups
-    ChunkMap(uint64_t n, uint32_t N, uint32_t group) : E(64ull * N), G(group), grouped(n / (group * 64ull * N) * group) {}
-    uint64_t base(uint64_t c) const { return c < grouped ? (c - c % G) * E + (c % G) * 1024 : c * E; }
-    uint64_t stride(uint64_t c) const { return c < grouped ? G * 1024 : 1024; }
+    uint64_t cols, KC;      // row-tiled: columns of the matrix, chunks per block of rows; KC = 0: linear
+    ChunkMap(uint64_t n, uint64_t cols_, uint32_t N, uint32_t group, uint32_t tile_rows)
+        : E(64ull * N), G(group), grouped(n / (group * 64ull * N) * group), cols(cols_),
+          KC(tile_rows ? cols_ / (4ull * N) : 0) {}
+    uint64_t piece(uint64_t c, uint32_t l, uint32_t q) const
+    {
+        if (KC) return ((c / KC) * 16 + (l & 15)) * cols + (c % KC) * (E / 16) + 64ull * q + 16ull * (l >> 4);
+        if (c < grouped) return (c - c % G) * E + (c % G) * 1024 + q * G * 1024 + l * 16ull;
+        return c * E + q * 1024ull + l * 16ull;
+    }
 };
+bool tiling_ok(uint32_t tile_rows, uint32_t group, uint64_t rows, uint64_t cols, uint32_t N)
+{
+    if (tile_rows == 0) return true;
+    return tile_rows == 16 && group == 1 && rows % 16 == 0 && cols % (4ull * N) == 0;
+}
 
 // Optimal prefix-code lengths by the two-queue method: leaves sorted by weight
 // in one queue, merged nodes (created in non-decreasing weight) in a second;
@@ -225,7 +239,8 @@ int check_header(const ecf8_header &h, uint64_t size)
     if (h.magic != ECF8_MAGIC || h.version != ECF8_VERSION) return ECF8_E_FORMAT;
     if (h.total_size != size || h.n_elem == 0) return ECF8_E_FORMAT;
     if (h.rows == 0 || h.cols == 0 || h.n_elem / h.rows != h.cols || h.n_elem % h.rows) return ECF8_E_FORMAT;
-    if ((h.table_bits != 0 && h.table_bits != ECF8_TB) || !lane_syms_ok(h.lane_syms) || !group_ok(h.group_chunks))
+    if ((h.table_bits != 0 && h.table_bits != ECF8_TB) || !lane_syms_ok(h.lane_syms) || !group_ok(h.group_chunks) ||
+        !tiling_ok(h.tile_rows, h.group_chunks, h.rows, h.cols, h.lane_syms))
         return ECF8_E_FORMAT;
     if (h.stream_bits > h.n_elem * 15 || h.stream_bits < h.n_elem) return ECF8_E_FORMAT;
     Layout L = make_layout(h.n_elem, h.stream_bits, h.lane_syms, h.table_bits);
@@ -256,10 +271,12 @@ int ecf8_encode(const uint8_t *x, uint64_t rows, uint64_t cols, const ecf8_encod
     if (rows > (1ull << 40) / cols) return ECF8_E_ARG;
     const uint64_t n = rows * cols;
     const uint32_t N = (opts && opts->lane_syms) ? opts->lane_syms : 128;
-    const uint32_t group = (opts && opts->group_chunks) ? opts->group_chunks : 32;
+    const uint32_t tile_rows = opts ? opts->tile_rows : 0;
+    const uint32_t group = (opts && opts->group_chunks) ? opts->group_chunks : (tile_rows ? 1 : 32);
     const uint32_t lmax = (opts && opts->max_code_len) ? opts->max_code_len : ECF8_TB / 2;
     if (!lane_syms_ok(N) || !group_ok(group) || lmax < 4 || lmax > 15) return ECF8_E_ARG;
-    const ChunkMap map(n, N, group);
+    if (!tiling_ok(tile_rows, group, rows, cols, N)) return ECF8_E_ARG;
+    const ChunkMap map(n, cols, N, group, tile_rows);
     unsigned nt = (opts && opts->n_threads) ? opts->n_threads : std::thread::hardware_concurrency();
     if (nt == 0) nt = 1;
     if (nt > 64) nt = 64;
@@ -313,7 +330,8 @@ int ecf8_encode(const uint8_t *x, uint64_t rows, uint64_t cols, const ecf8_encod
         h->cols = cols;
         h->lane_syms = N;
         h->table_bits = (uint16_t)table_bits;
-        h->group_chunks = (uint16_t)group;
+        h->group_chunks = (uint8_t)group;
+        h->tile_rows = (uint8_t)tile_rows;
         if (table_bits) build_pair_table(len, (uint16_t *)(blob + 256));
         h->n_chunks = L.n_chunks;
         h->stream_bits = bits;
@@ -339,7 +357,7 @@ int ecf8_encode(const uint8_t *x, uint64_t rows, uint64_t cols, const ecf8_encod
                 for (uint32_t l = 0; l < ECF8_LANES; l++) {
                     uint32_t lb = 0;
                     for (uint32_t q = 0; q < N / 16; q++) {
-                        uint64_t a = map.base(c) + q * map.stride(c) + l * 16;
+                        uint64_t a = map.piece(c, l, q);
                         uint64_t b = std::min<uint64_t>(a + 16, n);
                         for (uint64_t i = a; i < b; i++) lb += len[(x[i] >> 3) & 15];
                     }
@@ -379,7 +397,7 @@ int ecf8_encode(const uint8_t *x, uint64_t rows, uint64_t cols, const ecf8_encod
                         if ((at & 63) + nb > 64) lbuf[(at >> 6) + 1] |= (uint64_t)bits >> (64 - (at & 63));
                     };
                     for (uint32_t q = 0; q < P; q++) {
-                        uint64_t pa = map.base(c) + q * map.stride(c) + l * 16;
+                        uint64_t pa = map.piece(c, l, q);
                         uint64_t pb = std::min<uint64_t>(pa + 16, n);
                         for (uint64_t i = pa; i < pb; i++) {
                             uint32_t e = (x[i] >> 3) & 15;
@@ -458,7 +476,7 @@ int ecf8_blob_validate(const void *blob, uint64_t size)
         build_pair_table(h.code_len, want.data());
         if (std::memcmp(want.data(), p + 256, 2ull << h.table_bits) != 0) return ECF8_E_FORMAT;
     }
-    const ChunkMap map(h.n_elem, N, h.group_chunks);
+    const ChunkMap map(h.n_elem, h.cols, N, h.group_chunks, h.tile_rows);
     uint64_t prev;
     std::memcpy(&prev, p + h.off_chunk_bit, 8);
     if (prev != 0) return ECF8_E_FORMAT;
@@ -471,7 +489,7 @@ int ecf8_blob_validate(const void *blob, uint64_t size)
             std::memcpy(&lb, p + h.off_lane_bits + 2 * (c * ECF8_LANES + l), 2);
             uint64_t cnt = 0; // elements of the lane's pieces that exist
             for (uint32_t q = 0; q < N / 16; q++) {
-                uint64_t a = map.base(c) + q * map.stride(c) + l * 16;
+                uint64_t a = map.piece(c, l, q);
                 if (a < h.n_elem) cnt += std::min<uint64_t>(16, h.n_elem - a);
             }
             if (lb > 15 * cnt || lb < cnt) return ECF8_E_FORMAT;
@@ -541,6 +559,7 @@ int ecf8_batch_prepare(const ecf8_header *hdrs, const void *const *d_blobs, void
         it.stream_bytes = h.stream_bytes;
         it.off_table = h.table_bits ? 256 : 0;
         it.group_chunks = h.group_chunks;
+        it.tile_cols = h.tile_rows ? h.cols : 0;
         std::memcpy(it.code_len, h.code_len, 16);
         for (int s = 0; s < 16; s++) max_len = std::max<uint32_t>(max_len, h.code_len[s]);
         first += h.n_chunks;

@@ -27,7 +27,7 @@ class Header(ctypes.Structure):
     _fields_ = [("magic", ctypes.c_uint32), ("version", ctypes.c_uint32),
                 ("total_size", ctypes.c_uint64), ("n_elem", ctypes.c_uint64),
                 ("rows", ctypes.c_uint64), ("cols", ctypes.c_uint64),
-                ("lane_syms", ctypes.c_uint32), ("table_bits", ctypes.c_uint16), ("group_chunks", ctypes.c_uint16),
+                ("lane_syms", ctypes.c_uint32), ("table_bits", ctypes.c_uint16), ("group_chunks", ctypes.c_uint8), ("tile_rows", ctypes.c_uint8),
                 ("n_chunks", ctypes.c_uint64), ("stream_bits", ctypes.c_uint64),
                 ("code_len", ctypes.c_uint8 * 16),
                 ("off_chunk_bit", ctypes.c_uint64), ("off_lane_bits", ctypes.c_uint64),
@@ -39,7 +39,8 @@ class Header(ctypes.Structure):
 class EncodeOpts(ctypes.Structure):
     _fields_ = [("lane_syms", ctypes.c_uint32), ("n_threads", ctypes.c_uint32),
                 ("table_mode", ctypes.c_uint32), ("group_chunks", ctypes.c_uint32),
-                ("max_code_len", ctypes.c_uint32), ("reserved", ctypes.c_uint32 * 3)]
+                ("max_code_len", ctypes.c_uint32), ("tile_rows", ctypes.c_uint32),
+                ("reserved", ctypes.c_uint32 * 2)]
 
 
 class Stats(ctypes.Structure):
@@ -55,7 +56,7 @@ class BatchItem(ctypes.Structure):
                 ("off_stream", ctypes.c_uint64), ("off_plane", ctypes.c_uint64),
                 ("stream_bytes", ctypes.c_uint64), ("code_len", ctypes.c_uint8 * 16),
                 ("off_table", ctypes.c_uint64), ("group_chunks", ctypes.c_uint64),
-                ("reserved", ctypes.c_uint64 * 2)]
+                ("tile_cols", ctypes.c_uint64), ("reserved", ctypes.c_uint64 * 1)]
 
 
 class BatchInfo(ctypes.Structure):
@@ -141,17 +142,18 @@ class Blob:
 
 
 def ecf8_encode(fp8, rows=None, cols=None, lane_syms=0, n_threads=0, table_mode=0, group_chunks=0,
-                max_code_len=0):
+                max_code_len=0, tile_rows=0):
     """CPU encoder: raw E4M3 bytes (host tensor / array) -> Blob.
     table_mode: 0 embed the decode table for tensors of >= 2^22 weights, 1 always, 2 never.
     group_chunks: chunks interleaved per group (0 = default 32; 1 = chunk-major, what the fused GEMM needs).
-    max_code_len: cap on the code length (0 = default 7; 15 = plain Huffman)."""
+    max_code_len: cap on the code length (0 = default 7; 15 = plain Huffman).
+    tile_rows: 0 = linear layout; 16 = row-tiled layout (what ecf8_gemm_fp8 needs, with lane_syms=64)."""
     x = _host_u8(fp8)
     if rows is None:
         rows, cols = (x.shape if x.ndim == 2 else (1, x.size))
     if rows * cols != x.size:
         raise Ecf8Error("ecf8_encode", E_ARG)
-    opts = EncodeOpts(lane_syms, n_threads, table_mode, group_chunks, max_code_len)
+    opts = EncodeOpts(lane_syms, n_threads, table_mode, group_chunks, max_code_len, tile_rows)
     h = _vp()
     _check("ecf8_encode", _lib.ecf8_encode(x.ctypes.data, rows, cols, ctypes.byref(opts), ctypes.byref(h)))
     return Blob(h)

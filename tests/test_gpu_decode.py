@@ -115,6 +115,20 @@ def test_group_widths(orc, lane_syms, group):
     assert np.array_equal(got, _oracle_expected(orc, x))
 
 
+@pytest.mark.parametrize("lane_syms,rows,cols,cap", [(32, 16, 128, 0), (64, 64, 4096, 0), (64, 160, 1024, 15),
+                                                     (128, 48, 3584, 0), (128, 1024, 1024, 15)])
+def test_row_tiled_blobs_decode(orc, lane_syms, rows, cols, cap):
+    """ecf8_decode on the row-tiled layout the fused GEMM reads (a chunk = 16 rows x 4N columns)."""
+    x = _rand_bytes(rows * cols, rows + cols + lane_syms)
+    blob = ecf8.ecf8_encode(x, rows, cols, lane_syms=lane_syms, tile_rows=16, max_code_len=cap, table_mode=1 + (rows > 100))
+    assert blob.header.tile_rows == 16
+    got, guards = _gpu_decode_guarded(blob.numpy(), blob.header)
+    assert guards
+    assert np.array_equal(got, _oracle_expected(orc, x))
+    dec, _ = orc.container_decode(blob.numpy())
+    assert np.array_equal(got, dec)
+
+
 @pytest.mark.parametrize("lane_syms,group", [(64, 1), (64, 4), (128, 32)])
 def test_oracle_written_container_decodes_on_gpu(orc, lane_syms, group):
     """Interop: a container written by the oracle's writer (its own tie-breaks)."""

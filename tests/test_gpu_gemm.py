@@ -48,7 +48,7 @@ def test_one_tile_ocp_landmarks(orc):
     yref, mag = orc.gemm_ref(x, w)
     d_x = torch.from_numpy(x).to(DEV)
     raw = ecf8.ecf8_gemm_fp8_raw(torch.from_numpy(w).to(DEV), d_x)
-    blob = ecf8.ecf8_encode(w, 16, K, lane_syms=64, group_chunks=1)
+    blob = ecf8.ecf8_encode(w, 16, K, lane_syms=64, tile_rows=16)
     fused = ecf8.ecf8_gemm_fp8(blob.header, blob.to(DEV), d_x)
     torch.cuda.synchronize()
     assert not torch.isnan(raw).any() and not torch.isnan(fused).any()
@@ -66,7 +66,7 @@ def test_small_gemm_against_oracle(orc, M, table_mode):
     w = synth.make_weight(rows, K, 1.7, 0.02, 3).numpy()
     x = synth.activations(M, K, seed=M).numpy()
     yref, mag = orc.gemm_ref(x, w)
-    blob = ecf8.ecf8_encode(w, rows, K, lane_syms=64, group_chunks=1, table_mode=table_mode)
+    blob = ecf8.ecf8_encode(w, rows, K, lane_syms=64, tile_rows=16, table_mode=table_mode)
     d_x = torch.from_numpy(x).to(DEV)
     guard = torch.full((M + 2, rows), float("nan"), dtype=torch.float32, device=DEV)
     y = ecf8.ecf8_gemm_fp8(blob.header, blob.to(DEV), d_x, guard[1:M + 1])
@@ -86,7 +86,7 @@ def test_config4_full_size(orc, M):
     spec = synth.config4()[0]
     w = synth.make(spec, 0, device=DEV)
     x = synth.activations(M, 4096, seed=0, device=DEV)
-    blob = ecf8.ecf8_encode(w.cpu(), spec["rows"], spec["cols"], lane_syms=64, group_chunks=1)
+    blob = ecf8.ecf8_encode(w.cpu(), spec["rows"], spec["cols"], lane_syms=64, tile_rows=16)
     fused = ecf8.ecf8_gemm_fp8(blob.header, blob.to(DEV), x)
     raw = ecf8.ecf8_gemm_fp8_raw(w, x)
     torch.cuda.synchronize()
@@ -115,6 +115,17 @@ def test_gemm_argument_errors():
     b = ecf8.ecf8_encode(np.zeros((32, 4096), dtype=np.uint8), 32, 4096, lane_syms=128)
     with pytest.raises(ecf8.Ecf8Error):
         ecf8.ecf8_gemm_fp8(b.header, b.to(DEV), x)                      # lane_syms != 64
-    b = ecf8.ecf8_encode(np.zeros((64, 4096), dtype=np.uint8), 64, 4096, lane_syms=64, group_chunks=32)
-    with pytest.raises(ecf8.Ecf8Error):
-        ecf8.ecf8_gemm_fp8(b.header, b.to(DEV), x)                      # interleaved chunks: a chunk is not a row
+    z = np.zeros((64, 4096), dtype=np.uint8)
+    for kw in (dict(lane_syms=64), dict(lane_syms=64, group_chunks=1), dict(lane_syms=128, tile_rows=16)):
+        b = ecf8.ecf8_encode(z, 64, 4096, **kw)
+        with pytest.raises(ecf8.Ecf8Error) as e:
+            ecf8.ecf8_gemm_fp8(b.header, b.to(DEV), x)                  # not a row-tiled blob of 16 x 256 chunks
+        assert e.value.code == ecf8.E_ARG
+    fib = [1, 1]
+    while len(fib) < 16:
+        fib.append(fib[-1] + fib[-2])
+    deep = np.resize(np.repeat(np.arange(16, dtype=np.uint8) << 3, fib), 64 * 4096)
+    b = ecf8.ecf8_encode(deep, 64, 4096, lane_syms=64, tile_rows=16, max_code_len=15)
+    with pytest.raises(ecf8.Ecf8Error) as e:
+        ecf8.ecf8_gemm_fp8(b.header, b.to(DEV), x)                      # codewords longer than 7 bits
+    assert e.value.code == ecf8.E_ARG

@@ -76,6 +76,46 @@ def test_grouped_layout_read_by_oracle(orc, lane_syms, group, n):
     assert np.array_equal(dec2, x)
 
 
+@pytest.mark.parametrize("lane_syms,rows,cols,cap", [(32, 16, 128, 0), (64, 32, 512, 0), (64, 48, 4096, 15), (128, 16, 1024, 5)])
+def test_row_tiled_layout_read_by_oracle(orc, lane_syms, rows, cols, cap):
+    """Row-tiled layout (what the fused GEMM reads): product writer against the oracle's reader, the
+    oracle's writer against the product's validator, and lane ownership restated as a reshape."""
+    n = rows * cols
+    x = _rand_bytes(n, n + lane_syms)
+    blob = ecf8.ecf8_encode(x, rows, cols, lane_syms=lane_syms, tile_rows=16, max_code_len=cap)
+    h, arr = blob.header, blob.numpy()
+    assert h.tile_rows == 16 and h.group_chunks == 1 and h.n_chunks == n // (64 * lane_syms)
+    ecf8.blob_validate(arr)
+    dec, bits = orc.container_decode(arr)
+    assert np.array_equal(dec, x) and bits == h.stream_bits == _oracle_bits(orc, orc.histogram(x), cap)
+    theirs = orc.container_encode(x, rows, cols, lane_syms, 1, cap or 7, 16)
+    ecf8.blob_validate(theirs)
+    assert ecf8.blob_describe(theirs).tile_rows == 16
+    w = 4 * lane_syms
+    cost = np.array(list(h.code_len), dtype=np.int64)[(x >> 3) & 15].reshape(rows // 16, 16, cols // w, w // 64, 4, 16)
+    want = cost.sum(axis=(3, 5)).transpose(0, 2, 3, 1).reshape(-1, 64)
+    lb = arr[h.off_lane_bits:h.off_lane_bits + 128 * h.n_chunks].view("<u2").reshape(-1, 64)
+    assert np.array_equal(lb.astype(np.int64), want)
+
+
+def test_row_tiled_layout_argument_errors():
+    x = np.zeros(16 * 512, dtype=np.uint8)
+    with pytest.raises(ecf8.Ecf8Error):
+        ecf8.ecf8_encode(x, 8, 1024, lane_syms=64, tile_rows=16)          # rows not a multiple of 16
+    with pytest.raises(ecf8.Ecf8Error):
+        ecf8.ecf8_encode(x, 64, 128, lane_syms=64, tile_rows=16)          # cols not a multiple of 4 N
+    with pytest.raises(ecf8.Ecf8Error):
+        ecf8.ecf8_encode(x, 16, 512, lane_syms=64, tile_rows=16, group_chunks=4)
+    with pytest.raises(ecf8.Ecf8Error):
+        ecf8.ecf8_encode(x, 16, 512, lane_syms=64, tile_rows=8)
+    good = ecf8.ecf8_encode(x, 16, 512, lane_syms=64, tile_rows=16).numpy().copy()
+    ecf8.blob_validate(good)
+    bad = good.copy()
+    bad[47] = 8
+    with pytest.raises(ecf8.Ecf8Error):
+        ecf8.blob_validate(bad)
+
+
 def test_group_interleave_is_block_by_block():
     """The layout stated from scratch for one whole group of two chunks (N = 32): the four
     1024-element blocks alternate between the chunks, lane l owns elements [16 l, 16 l + 16) of

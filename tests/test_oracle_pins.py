@@ -375,6 +375,36 @@ def test_container_group_interleave(orc, lane_syms, group, n):
         orc.container_decode(bad)
 
 
+@pytest.mark.parametrize("lane_syms,rows,cols", [(16, 16, 64), (32, 32, 256), (64, 48, 512), (128, 16, 1024)])
+def test_container_row_tiled_layout(orc, lane_syms, rows, cols):
+    """Row-tiled layout: chunk = 16 rows x 4N columns; lane l owns row l % 16 and, in every 64-column
+    stripe of the block, the 16 columns starting at 16 (l / 16).  Stated as reshapes of the matrix
+    (axes: block row, row in block, block column, stripe, lane group, byte), not with index arithmetic."""
+    rng = np.random.default_rng(rows * cols + lane_syms)
+    p = rng.dirichlet(np.ones(16) * 0.4)
+    n = rows * cols
+    x = _bytes_from(rng.choice(16, size=n, p=p), rng)
+    blob = orc.container_encode(x, rows, cols, lane_syms, 1, 15, 16)
+    assert blob[46] == 1 and blob[47] == 16
+    dec, bits = orc.container_decode(blob)
+    assert np.array_equal(dec, x)
+    ln = orc.huffman_lengths(orc.histogram(x)).astype(np.int64)
+    w = 4 * lane_syms
+    cost = ln[(x >> 3) & 15].reshape(rows // 16, 16, cols // w, w // 64, 4, 16)
+    # -> [block row, block col, lane group, row in block] summed over stripes and bytes
+    want = cost.sum(axis=(3, 5)).transpose(0, 2, 3, 1).reshape(-1, 64)      # lane = 16 * group + row
+    n_chunks = n // (64 * lane_syms)
+    hdr = np.frombuffer(blob[:256].tobytes(), "<u8")
+    off_lb = int(hdr[11])
+    lb = np.frombuffer(blob[off_lb:off_lb + 128 * n_chunks].tobytes(), "<u2").reshape(n_chunks, 64)
+    assert np.array_equal(lb.astype(np.int64), want)
+    for bad_rows, bad_cols in ((rows + 8, cols), (rows, cols + 2 * lane_syms)):
+        with pytest.raises(ValueError):
+            orc.container_encode(np.zeros(bad_rows * bad_cols, np.uint8), bad_rows, bad_cols, lane_syms, 1, 15, 16)
+    with pytest.raises(ValueError):
+        orc.container_encode(x, rows, cols, lane_syms, 2, 15, 16)      # no interleave in this layout
+
+
 def test_container_reader_catches_tampering(orc):
     rng = np.random.default_rng(11)
     p = rng.dirichlet(np.ones(16) * 0.4)
