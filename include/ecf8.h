@@ -241,7 +241,8 @@ int ecf8_decode_batched(const ecf8_batch_item *d_items, uint32_t n_tensors,
 /*
  * ecf8_gemm_fp8: fused decode + FP8 GEMM for small batches.  The paper decodes a
  * layer into a buffer and lets the framework's GEMM read it back (Section 3.3);
- * here the decoded tile goes from LDS straight into the FP8 matrix cores.
+ * here decoded weights go from the registers they are decoded into straight
+ * into the FP8 matrix cores.
  *   Y[m][n] = sum_k X[m][k] * W[n][k]   (fp32 accumulate)
  * W: the rows x cols tensor held by the blob (hdr / d_blob as for ecf8_decode);
  * d_x: DEVICE, M x cols FP8 E4M3 bytes, row-major, 16-byte aligned, 1 <= M <= 64;

@@ -25,14 +25,21 @@
 //    bit, so every lane advances two independent dependency chains at once
 //    (twice the LDS latency hidden per wave).  Pairs that do not fit in TB bits and
 //    codewords longer than TB bits take a second level (per-symbol walk that
-//    reuses the table's first-symbol fields, then a 16-entry canonical match).
+//    reuses the table's first-symbol fields, then a 16-entry canonical match);
+//    a wave holds 256 pairs per step, so even a 1e-3 miss rate sends a third of
+//    the steps there.  Under the encoder's default cap of TB/2 bits per codeword
+//    every pair is a table hit and the PAIRFIT kernels carry no second level.
 //    The 32 KiB table is copied from the blob when the encoder embedded it (one
 //    L2-resident read per workgroup), else built in LDS from the 16 code lengths;
 //  * after four steps a lane holds one 16-byte piece; the 64 lanes' pieces are
 //    adjacent, so each dwordx4 store instruction of the wave writes 1 KiB of
 //    contiguous output, merged in registers with the nibble plane that was
 //    fetched (coalesced, 512 B per instruction) a whole chunk earlier.  Decoded
-//    bytes never pass through LDS;
+//    bytes never pass through LDS.  The PAIRFIT kernels hold a chunk's pieces
+//    and store them in one burst; with the container's group interleave (a
+//    wave's consecutive pieces G KiB apart, the workgroup's other waves in
+//    between) HBM takes such bursts about 15 % faster than 1 KiB stores
+//    trickling out of every wave;
 //  * persistent workgroups own contiguous chunk ranges, so a table is set up
 //    once per (workgroup, tensor); inside a workgroup the waves draw chunks
 //    from an LDS ticket counter (the hardware favours a SIMD's oldest wave, so
