@@ -61,9 +61,11 @@ struct KArgs {
     uint32_t max_code_len;                // longest codeword of any tensor of the launch
 };
 
-template <int N, int WAVES>
+template <int N, int WAVES, bool PAIRFIT>
 struct Cfg {
-    static constexpr int STAGE = N * 32 + 64;         // bytes of stream staged per chunk
+    // bytes of stream staged per chunk: under the cap of TB/2 bits per codeword the worst case
+    // (so no chunk of a PAIRFIT launch is ever oversize), else a good 4 bits per symbol
+    static constexpr int STAGE = PAIRFIT ? 64 * N * (TB / 2) / 8 + 64 : N * 32 + 64;
     static constexpr int PIECES = N / 16;             // 16-byte output pieces per lane
     static constexpr int SEGS = (STAGE / 16 + 63) / 64;  // dwordx4 loads per lane that cover STAGE
     // LDS map (byte offsets into one array)
@@ -81,7 +83,7 @@ struct Cfg {
 template <int N, int WAVES, bool PAIRFIT>
 __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
 {
-    using C = Cfg<N, WAVES>;
+    using C = Cfg<N, WAVES, PAIRFIT>;
     __shared__ __attribute__((aligned(16))) uint8_t smem[C::TOTAL];
     uint16_t *tbl = (uint16_t *)(smem + C::OFF_TBL);
     uint32_t *s_len = (uint32_t *)(smem + C::OFF_SYM);
@@ -278,7 +280,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
 #pragma unroll
                 for (int k = 0; k < C::SEGS; k++) {
                     const uint32_t i = (lane + 64 * k) * 16;
-                    if (i < (uint32_t)C::STAGE) *(u32x4 *)(stage + i) = p_cur.s[k];
+                    if (i < (uint32_t)C::STAGE && (!PAIRFIT || i < (uint32_t)span64)) *(u32x4 *)(stage + i) = p_cur.s[k];
                 }
                 u32x2 pl[C::PIECES];
 #pragma unroll
@@ -293,10 +295,11 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
                     if (cg2 < fast_end) m_next2 = load_meta(cg2 - first_chunk);
                 }
 
-                // bpA: LDS bit address (smem-relative) of the forward run's next codeword;
-                // bpB: one past the backward run's next codeword (its first bit is bpB - 1)
-                uint32_t bpA = stage_off * 8 + bit_in;   // oversize chunk: may point past LDS, reads return 0
-                uint32_t bpB = bpA + m_cur.lb;
+                // LDS bit addresses (smem-relative), kept one bit off as quad_step2 wants them:
+                // bpA = the forward run's next codeword - 1; bpB = one past the backward run's
+                // next codeword - 31
+                uint32_t bpA = stage_off * 8 + bit_in - 1;   // oversize chunk: may point past LDS, reads return 0
+                uint32_t bpB = bpA + m_cur.lb - 30;
                 // PAIRFIT: the chunk's pieces are kept in registers and stored in one burst at
                 // its end.  Together with the interleaved layout the workgroup's waves then
                 // write runs of adjacent KiBs close in time, which HBM takes ~15 % faster than

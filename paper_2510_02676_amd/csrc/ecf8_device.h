@@ -152,61 +152,77 @@ __device__ __forceinline__ uint32_t lds_window(const uint8_t *smem, uint32_t bp)
 // straight line, so their LDS round trips overlap; the second level for pairs
 // that do not fit TB bits is one shared, rarely taken branch.  Returns the four
 // exponent fields of each run in their output byte positions (other bits are
-// noise the merge masks off) and moves bpA / bpB past the codewords.
+// noise the merge masks off) and moves the runs past the codewords.
+// The runs' positions are kept one bit off, pa = (next bit of the forward run) - 1
+// and pb = (one past the next bit of the backward run) - 31: the windows read at
+// those positions are the stream bits shifted left by one, i.e. already the byte
+// offset of a 16-bit table entry once masked.
 // PAIRFIT: no codeword is longer than TB/2 bits, so every pair is in the table and
 // the second level is compiled out (a blob that breaks the promise decodes to wrong
 // bytes, in bounds).
 template <bool PAIRFIT>
 __device__ __forceinline__ void quad_step2(const uint8_t *smem, const uint16_t *tbl, const uint32_t *s_len,
-                                           const uint32_t *s_code, uint32_t &bpA, uint32_t &bpB,
+                                           const uint32_t *s_code, uint32_t &pa, uint32_t &pb,
                                            uint32_t &outA, uint32_t &outB)
 {
-    const uint32_t wA = lds_window<+1>(smem, bpA);
-    const uint32_t wB = lds_window<-1>(smem, bpB);
-    uint32_t eA1 = tbl[wA & TBL_MASK];
-    uint32_t eB1 = tbl[wB & TBL_MASK];
+    constexpr uint32_t OFF_MASK = TBL_MASK << 1;
+    const uint8_t *tb = (const uint8_t *)tbl;
+    const uint32_t aA = (pa >> 3) & ~3u, aB = (pb >> 3) & ~3u;
+    const uint32_t wA = __builtin_amdgcn_alignbit(*(const uint32_t *)(smem + aA + 4), *(const uint32_t *)(smem + aA), pa);
+    const uint32_t wB = __brev(__builtin_amdgcn_alignbit(*(const uint32_t *)(smem + aB + 4), *(const uint32_t *)(smem + aB), pb));
+    uint32_t eA1 = *(const uint16_t *)(tb + (wA & OFF_MASK));
+    uint32_t eB1 = *(const uint16_t *)(tb + (wB & OFF_MASK));
     uint32_t nA1 = (eA1 >> 7) & 15u;
     uint32_t nB1 = (eB1 >> 7) & 15u;
-    uint32_t eA2 = tbl[(wA >> nA1) & TBL_MASK];        // >= 18 valid bits left in the window
-    uint32_t eB2 = tbl[(wB >> nB1) & TBL_MASK];
+    uint32_t eA2 = *(const uint16_t *)(tb + ((wA >> nA1) & OFF_MASK));    // >= 17 valid bits left in the window
+    uint32_t eB2 = *(const uint16_t *)(tb + ((wB >> nB1) & OFF_MASK));
     uint32_t nA2 = (eA2 >> 7) & 15u;
     uint32_t nB2 = (eB2 >> 7) & 15u;
     // n1 == 0 makes the second lookup repeat the first, so n2 == 0 covers both pairs of a run
     if (!PAIRFIT && __builtin_expect(nA2 == 0 || nB2 == 0, 0)) {
         if (nA2 == 0) {
-            if (nA1 == 0) pair_second_level(wA, eA1, nA1, tbl, s_len, s_code);
+            if (nA1 == 0) pair_second_level(wA >> 1, eA1, nA1, tbl, s_len, s_code);   // 31 valid bits, 30 needed
             // the second level needs up to 30 bits: fresh window after the first pair
-            const uint32_t w2 = lds_window<+1>(smem, bpA + nA1);
+            const uint32_t w2 = lds_window<+1>(smem, pa + 1 + nA1);
             eA2 = tbl[w2 & TBL_MASK];
             nA2 = (eA2 >> 7) & 15u;
             if (nA2 == 0) pair_second_level(w2, eA2, nA2, tbl, s_len, s_code);
         }
         if (nB2 == 0) {
-            if (nB1 == 0) pair_second_level(wB, eB1, nB1, tbl, s_len, s_code);
-            const uint32_t w2 = lds_window<-1>(smem, bpB - nB1);
+            if (nB1 == 0) pair_second_level(wB >> 1, eB1, nB1, tbl, s_len, s_code);
+            const uint32_t w2 = lds_window<-1>(smem, pb + 31 - nB1);
             eB2 = tbl[w2 & TBL_MASK];
             nB2 = (eB2 >> 7) & 15u;
             if (nB2 == 0) pair_second_level(w2, eB2, nB2, tbl, s_len, s_code);
         }
     }
-    bpA += nA1 + nA2;
-    bpB -= nB1 + nB2;
-    outA = (eA1 & 0xffffu) | (eA2 << 16);
-    outB = (eB1 & 0xffffu) | (eB2 << 16);
+    pa += nA1 + nA2;
+    pb = pb - nB1 - nB2;
+    // bytes 0,1 of the first entry and bytes 0,1 of the second
+    outA = __builtin_amdgcn_perm(eA2, eA1, 0x05040100u);
+    outB = __builtin_amdgcn_perm(eB2, eB1, 0x05040100u);
 }
 
 // byte = exponent<<3 | sign<<7 | mantissa  (Algorithm 1, byte assembly) for one
 // 16-byte piece: dw = four dwords of exponent fields, pl = the piece's 8 bytes
 // of the nibble plane (byte j of a dword: low nibble element j, high nibble
 // element j + 4 of that 8-element group).
+// (a & mask) | (b & ~mask) in one v_bitop3_b32 (truth table over a = 0xF0, b = 0xCC, mask = 0xAA);
+// written as plain C the compiler expands the nested selects below into five operations per dword
+__device__ __forceinline__ uint32_t bit_select(uint32_t mask, uint32_t a, uint32_t b)
+{
+    return __builtin_amdgcn_bitop3_b32(a, b, mask, 0xE4);
+}
+
 __device__ __forceinline__ u32x4 merge_piece(const uint32_t dw[4], u32x2 pl)
 {
     const uint32_t p0 = pl.x, p1 = pl.y;
+    // per byte: bits 0..2 mantissa, bit 7 sign (bits 3..6 of the inner select are overwritten)
     u32x4 d;
-    d.x = (dw[0] & EXP_MASK) | (p0 & 0x07070707u) | ((p0 & 0x08080808u) << 4);
-    d.y = (dw[1] & EXP_MASK) | ((p0 >> 4) & 0x07070707u) | (p0 & 0x80808080u);
-    d.z = (dw[2] & EXP_MASK) | (p1 & 0x07070707u) | ((p1 & 0x08080808u) << 4);
-    d.w = (dw[3] & EXP_MASK) | ((p1 >> 4) & 0x07070707u) | (p1 & 0x80808080u);
+    d.x = bit_select(EXP_MASK, dw[0], bit_select(0x07070707u, p0, p0 << 4));
+    d.y = bit_select(EXP_MASK, dw[1], bit_select(0x07070707u, p0 >> 4, p0));
+    d.z = bit_select(EXP_MASK, dw[2], bit_select(0x07070707u, p1, p1 << 4));
+    d.w = bit_select(EXP_MASK, dw[3], bit_select(0x07070707u, p1 >> 4, p1));
     return d;
 }
 

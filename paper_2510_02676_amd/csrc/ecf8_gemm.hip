@@ -240,8 +240,8 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_kernel(GArgs a)
                 p_cur = load_payload(s + 1, m_next);
                 if (s + 2 < n_steps) m_next2 = load_meta(s + 2);
             }
-            uint32_t bpA = stage_off * 8 + (uint32_t)(start - byte0 * 8) + rel;
-            uint32_t bpB = bpA + m.lb;
+            uint32_t bpA = stage_off * 8 + (uint32_t)(start - byte0 * 8) + rel - 1;   // one bit off, see quad_step2
+            uint32_t bpB = bpA + m.lb - 30;
 #pragma unroll
             for (int Q = 0; Q < GPIECES / 2; Q++) {
                 uint32_t dwA[4], dwB[4];
