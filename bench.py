@@ -202,6 +202,112 @@ def bench_config4(a):
         "compression_ratio": round(h.total_size / w.numel(), 5), "bit_exact_vs_raw_weights_gemm": True,
         "gemm": res}))
 
+def bench_jit(a):
+    """Workload "jit" (paper Section 3.3): a forward pass over the config-1 stack with the weights
+    decoded just in time into shared buffers (ecf8_jit_*).  The per-layer compute is a stand-in that
+    reads every decoded byte once: the library's raw FP8 GEMM at M = 16 on each matrix (the
+    4096 x 14336 down projection is read as 14336 x 4096).  Three timings per pass: compute on
+    resident uncompressed weights; decode then compute on one stream and one buffer; decode of
+    layer l+1 overlapped with the compute of layer l on two buffers."""
+    from paper_2510_02676_amd import ecf8, synth
+    dev = "cuda:0"
+    layers = a.layers or 32
+    specs = synth.config1(a.seed, layers)
+    per_layer = {}
+    t0 = time.time()
+    for s in specs:
+        w = synth.make(s, a.seed, device=dev)
+        b = ecf8.ecf8_encode(w.cpu(), s["rows"], s["cols"])
+        per_layer.setdefault(s["layer"], []).append((w, b.header, b.to(dev)))
+    setup = time.time() - t0
+    packed = [([t[1] for t in per_layer[l]], [t[2] for t in per_layer[l]]) for l in range(layers)]
+    x = synth.activations(16, 4096, seed=a.seed, device=dev)
+    y = torch.empty((16, 14336), dtype=torch.float32, device=dev)
+
+    def gemm_stand_in(ws, stream):
+        for w in ws:
+            w2 = w if w.shape[1] == 4096 else w.view(-1, 4096)
+            ecf8.ecf8_gemm_fp8_raw(w2, x, y[:, :w2.shape[0]], stream=stream)
+
+    consumer = [gemm_stand_in]
+    compute = lambda ws, stream: consumer[0](ws, stream)
+
+    def timed(fn):
+        for _ in range(a.warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(a.steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / a.steps
+
+    main_stream = torch.cuda.current_stream()
+
+    def resident_pass():
+        for l in range(layers):
+            compute([t[0] for t in per_layer[l]], main_stream)
+
+    def make_pass(jit, overlap):
+        def one_pass():
+            jit.prefetch(0)
+            for l in range(layers):
+                if overlap and l + 1 < layers:
+                    jit.prefetch(l + 1)
+                ws = jit.acquire(l, main_stream)
+                compute(ws, main_stream)
+                jit.release(l, main_stream)
+                if not overlap and l + 1 < layers:
+                    jit.prefetch(l + 1)
+        return one_pass
+
+    # parity of what the consumer sees, once, before timing
+    jit2 = ecf8.Jit(packed, n_buffers=2)
+    jit2.prefetch(0)
+    for l in range(layers):
+        if l + 1 < layers:
+            jit2.prefetch(l + 1)
+        ws = jit2.acquire(l, main_stream)
+        if not all(torch.equal(v, t[0]) for v, t in zip(ws, per_layer[l])):
+            raise SystemExit("jit: layer %d differs from its weights" % l)
+        jit2.release(l, main_stream)
+    torch.cuda.synchronize()
+    t_res = timed(resident_pass)
+    jit1 = ecf8.Jit(packed, n_buffers=1)
+    t_serial = timed(make_pass(jit1, False))
+    t_jit = timed(make_pass(jit2, True))
+    n_total = sum(t[0].numel() for l in range(layers) for t in per_layer[l])
+    hidden = (t_serial - t_jit) / max(t_serial - t_res, 1e-9)
+
+    # the same three timings with a compute-bound consumer (one bf16 4096^3 matmul per layer that does
+    # not read the weights), and the decode confined to fewer workgroups so that the consumer's
+    # kernels find free compute units while it runs
+    ma = torch.randn(4096, 4096, device=dev, dtype=torch.bfloat16)
+    mb = torch.randn(4096, 4096, device=dev, dtype=torch.bfloat16)
+    mc = torch.empty_like(ma)
+    consumer[0] = lambda ws, stream: torch.matmul(ma, mb, out=mc)
+    mm = {"resident": round(timed(resident_pass), 4), "decode_then_compute_1_buffer": round(timed(make_pass(jit1, False)), 4)}
+    for cap in (0, 192, 128, 64):
+        jit2.set_decode_workgroups(cap)
+        mm["jit_2_buffers_decode_workgroups_%s" % (cap or "all")] = round(timed(make_pass(jit2, True)), 4)
+    jit2.set_decode_workgroups(0)
+    consumer[0] = gemm_stand_in
+    print(json.dumps({
+        "metric": "decoded FP8 GB/s inside a just-in-time forward pass (decode of layer l+1 overlapped with compute of layer l)",
+        "value": round(n_total / (t_jit * 1e-3) / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(t_jit, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "config": {"workload": "jit: config-1 stack, %d layers, per-layer decode into 2 shared buffers + raw FP8 GEMM stand-in (M=16)" % layers,
+                   "weights": n_total, "seed": a.seed},
+        "bit_exact": True, "setup_s": round(setup, 1),
+        "pass_ms": {"compute_on_resident_weights": round(t_res, 4), "decode_then_compute_1_buffer": round(t_serial, 4),
+                    "jit_2_buffers_overlapped": round(t_jit, 4)},
+        "decode_time_hidden_frac": round(hidden, 3),
+        "pass_ms_with_compute_bound_consumer": mm,
+        "buffer_bytes_each": jit2.buffer_bytes, "resident_compressed_bytes": sum(h.total_size for hs, _ in packed for h in hs)}))
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -232,6 +338,8 @@ def main():
 
     if a.workload == "config4":
         return bench_config4(a)
+    if a.workload == "jit":
+        return bench_jit(a)
     layers = a.layers or {"config1": 32, "config2": 256, "config3": 40, "config0": 1}[a.workload]
     batches, desc, t_setup = build_workload(a.workload, a.seed, a.lane_syms, layers, a.launch, a.group_chunks, a.max_code_len)
     hdrs = [t["hdr"] for _, ts in batches for t in ts]

@@ -217,6 +217,11 @@ typedef struct ecf8_batch_info {
     uint64_t total_chunks;  /* chunks of all tensors of the batch                 */
     uint32_t lane_syms;     /* N, shared by all tensors of the batch              */
     uint32_t max_code_len;  /* longest codeword of any tensor of the batch        */
+    uint32_t max_workgroups; /* 0 = one workgroup per compute unit (fastest decode); */
+                            /* else a cap, to leave compute units to kernels that   */
+                            /* run beside the decode (a decode workgroup fills its  */
+                            /* compute unit); batch_prepare sets 0                  */
+    uint32_t reserved;
 } ecf8_batch_info;
 
 /*
@@ -258,6 +263,48 @@ int ecf8_gemm_fp8(const ecf8_header *hdr, const void *d_blob, const void *d_x, u
                   float *d_y, void *stream);
 int ecf8_gemm_fp8_raw(const void *d_w, uint64_t rows, uint64_t cols, const void *d_x, uint32_t M,
                       float *d_y, void *stream);
+
+/*
+ * Just-in-time layer decode (Section 3.3: compressed layers stay resident, a
+ * layer is decoded into a pre-allocated buffer right before its forward pass
+ * and the buffer is reused by later layers).  The manager is host-side
+ * bookkeeping around ecf8_decode_batched: it owns one decode stream and a few
+ * events, no device memory.  Layer l uses buffer l % n_buffers; with two or
+ * more buffers the decode of layer l+1 overlaps the compute of layer l.
+ * Calls on one manager must come from one host thread at a time.
+ *
+ *   create        d_buffers: n_buffers DEVICE buffers of buffer_bytes each
+ *                 (16-byte aligned, caller-owned, must outlive the manager)
+ *   layer_prepare HOST: lays the layer's tensors out in its buffer (offsets[i]
+ *                 = byte offset of tensor i, multiples of 256) and fills
+ *                 items_host[0..n) for that placement; ECF8_E_CAPACITY if the
+ *                 layer does not fit.  The caller copies items_host to device
+ *                 memory and hands that copy over with layer_commit
+ *   prefetch      launches the layer's decode on the manager's stream, after
+ *                 the buffer's previous user has released it.  ECF8_E_ARG if
+ *                 the buffer is still ready/acquired for another layer
+ *   acquire       makes `stream` wait for the layer's decode; *d_base = the
+ *                 buffer (tensor i is at d_base + offsets[i]).  Work queued
+ *                 on `stream` after this call sees the decoded weights
+ *   release       records on `stream` that the layer's weights are no longer
+ *                 needed; the buffer's next prefetch waits for that point
+ *   set_decode_workgroups  cap on the decode launches' workgroups (0 = one
+ *                 per compute unit), to leave compute units to the consumer's
+ *                 kernels while a decode runs beside them
+ *   destroy       drains the decode stream and frees the host objects
+ */
+typedef struct ecf8_jit ecf8_jit;
+int ecf8_jit_create(uint32_t n_layers, uint32_t n_buffers, void *const *d_buffers,
+                    uint64_t buffer_bytes, ecf8_jit **out);
+void ecf8_jit_destroy(ecf8_jit *jit);
+int ecf8_jit_layer_prepare(ecf8_jit *jit, uint32_t layer, const ecf8_header *hdrs,
+                           const void *const *d_blobs, uint32_t n_tensors,
+                           ecf8_batch_item *items_host, uint64_t *offsets);
+int ecf8_jit_layer_commit(ecf8_jit *jit, uint32_t layer, const ecf8_batch_item *d_items);
+int ecf8_jit_set_decode_workgroups(ecf8_jit *jit, uint32_t max_workgroups);
+int ecf8_jit_prefetch(ecf8_jit *jit, uint32_t layer);
+int ecf8_jit_acquire(ecf8_jit *jit, uint32_t layer, void *stream, void **d_base);
+int ecf8_jit_release(ecf8_jit *jit, uint32_t layer, void *stream);
 
 const char *ecf8_strerror(int code);
 uint32_t ecf8_version(void);

@@ -59,6 +59,7 @@ struct KArgs {
     uint32_t n_items;
     uint64_t total_chunks;
     uint32_t max_code_len;                // longest codeword of any tensor of the launch
+    uint32_t max_workgroups;              // 0 = one per compute unit
 };
 
 template <int N, int WAVES, bool PAIRFIT>
@@ -385,6 +386,7 @@ int launch_as(const KArgs &a, int wgs_per_cu, hipStream_t s)
     if (cus <= 0) return ECF8_E_HIP;
     uint64_t want = (a.total_chunks + WAVES - 1) / WAVES;       // at least one chunk per wave
     uint64_t cap = (uint64_t)cus * wgs_per_cu;
+    if (a.max_workgroups && a.max_workgroups < cap) cap = a.max_workgroups;
     uint32_t grid = (uint32_t)(want < cap ? want : cap);
     if (grid == 0) grid = 1;
     hipLaunchKernelGGL((ecf8_decode_kernel<N, WAVES, PAIRFIT>), dim3(grid), dim3(WAVES * 64), 0, s, a);
@@ -458,6 +460,7 @@ int ecf8_decode_batched(const ecf8_batch_item *d_items, uint32_t n_tensors, cons
     a.n_items = n_tensors;
     a.total_chunks = info->total_chunks;
     a.max_code_len = info->max_code_len;
+    a.max_workgroups = info->max_workgroups;
     return dispatch(a, info->lane_syms, (hipStream_t)stream);
 }
 

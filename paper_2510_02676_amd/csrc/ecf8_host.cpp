@@ -567,6 +567,8 @@ int ecf8_batch_prepare(const ecf8_header *hdrs, const void *const *d_blobs, void
     info->total_chunks = first;
     info->lane_syms = hdrs[0].lane_syms;
     info->max_code_len = max_len;
+    info->max_workgroups = 0;
+    info->reserved = 0;
     return ECF8_OK;
 }
 

@@ -61,7 +61,8 @@ class BatchItem(ctypes.Structure):
 
 class BatchInfo(ctypes.Structure):
     _fields_ = [("total_chunks", ctypes.c_uint64), ("lane_syms", ctypes.c_uint32),
-                ("max_code_len", ctypes.c_uint32)]
+                ("max_code_len", ctypes.c_uint32), ("max_workgroups", ctypes.c_uint32),
+                ("reserved", ctypes.c_uint32)]
 
 
 assert ctypes.sizeof(Header) == 256 and ctypes.sizeof(BatchItem) == 128
@@ -84,6 +85,16 @@ _lib.ecf8_batch_prepare.argtypes = [ctypes.POINTER(Header), ctypes.POINTER(_vp),
 _lib.ecf8_decode_batched.argtypes = [_vp, _u32, ctypes.POINTER(BatchInfo), _vp]
 _lib.ecf8_gemm_fp8.argtypes = [ctypes.POINTER(Header), _vp, _vp, _u32, _vp, _vp]
 _lib.ecf8_gemm_fp8_raw.argtypes = [_vp, _u64, _u64, _vp, _u32, _vp, _vp]
+_lib.ecf8_jit_create.argtypes = [_u32, _u32, ctypes.POINTER(_vp), _u64, ctypes.POINTER(_vp)]
+_lib.ecf8_jit_destroy.argtypes = [_vp]
+_lib.ecf8_jit_destroy.restype = None
+_lib.ecf8_jit_layer_prepare.argtypes = [_vp, _u32, ctypes.POINTER(Header), ctypes.POINTER(_vp), _u32,
+                                        ctypes.POINTER(BatchItem), ctypes.POINTER(_u64)]
+_lib.ecf8_jit_layer_commit.argtypes = [_vp, _u32, _vp]
+_lib.ecf8_jit_prefetch.argtypes = [_vp, _u32]
+_lib.ecf8_jit_set_decode_workgroups.argtypes = [_vp, _u32]
+_lib.ecf8_jit_acquire.argtypes = [_vp, _u32, _vp, ctypes.POINTER(_vp)]
+_lib.ecf8_jit_release.argtypes = [_vp, _u32, _vp]
 _lib.ecf8_strerror.argtypes = [ctypes.c_int]
 _lib.ecf8_strerror.restype = ctypes.c_char_p
 _lib.ecf8_version.restype = _u32
@@ -218,6 +229,58 @@ class Batch:
 def ecf8_decode_batched(batch, stream=None):
     _check("ecf8_decode_batched", _lib.ecf8_decode_batched(batch.d_items.data_ptr(), batch.n,
                                                            ctypes.byref(batch.info), _stream_ptr(stream)))
+
+
+class Jit:
+    """Just-in-time layer decode over shared buffers (ecf8_jit_*): layers = list of (headers, device
+    blobs); layer l decodes into buffer l % n_buffers.  prefetch(l) queues the decode on the
+    manager's own stream, acquire(l) orders the caller's stream behind it and returns the layer's
+    tensors (views into the buffer), release(l) lets the buffer be reused."""
+
+    def __init__(self, layers, n_buffers=2, buffer_bytes=None):
+        dev = layers[0][1][0].device
+        need = max(sum((h.n_elem + 255) // 256 * 256 for h in hdrs) for hdrs, _ in layers)
+        self.buffer_bytes = buffer_bytes if buffer_bytes is not None else need
+        self.buffers = [torch.empty(self.buffer_bytes, dtype=torch.uint8, device=dev) for _ in range(n_buffers)]
+        B = (_vp * n_buffers)(*[b.data_ptr() for b in self.buffers])
+        self._h = _vp()
+        _check("ecf8_jit_create", _lib.ecf8_jit_create(len(layers), n_buffers, B, self.buffer_bytes,
+                                                       ctypes.byref(self._h)))
+        self._keep, self._views = [], []
+        for l, (hdrs, d_blobs) in enumerate(layers):
+            n = len(hdrs)
+            H = (Header * n)(*hdrs)
+            P = (_vp * n)(*[t.data_ptr() for t in d_blobs])
+            items = (BatchItem * n)()
+            offs = (_u64 * n)()
+            _check("ecf8_jit_layer_prepare", _lib.ecf8_jit_layer_prepare(self._h, l, H, P, n, items, offs))
+            d_items = torch.from_numpy(np.frombuffer(items, dtype=np.uint8).copy()).to(dev)
+            _check("ecf8_jit_layer_commit", _lib.ecf8_jit_layer_commit(self._h, l, d_items.data_ptr()))
+            self._keep.append((d_items, list(d_blobs)))
+            buf = self.buffers[l % n_buffers]
+            self._views.append([buf[int(o):int(o) + h.n_elem].view(h.rows, h.cols) for o, h in zip(offs, hdrs)])
+
+    def set_decode_workgroups(self, max_workgroups):
+        _check("ecf8_jit_set_decode_workgroups", _lib.ecf8_jit_set_decode_workgroups(self._h, max_workgroups))
+
+    def prefetch(self, layer):
+        _check("ecf8_jit_prefetch", _lib.ecf8_jit_prefetch(self._h, layer))
+
+    def acquire(self, layer, stream=None):
+        base = _vp()
+        _check("ecf8_jit_acquire", _lib.ecf8_jit_acquire(self._h, layer, _stream_ptr(stream), ctypes.byref(base)))
+        assert base.value == self.buffers[layer % len(self.buffers)].data_ptr()
+        return self._views[layer]
+
+    def release(self, layer, stream=None):
+        _check("ecf8_jit_release", _lib.ecf8_jit_release(self._h, layer, _stream_ptr(stream)))
+
+    def close(self, _destroy=_lib.ecf8_jit_destroy):
+        if getattr(self, "_h", None):
+            _destroy(self._h)
+            self._h = None
+
+    __del__ = close
 
 
 def ecf8_gemm_fp8(hdr, d_blob, d_x, d_y=None, stream=None):
