@@ -14,6 +14,7 @@
 // two independent dependency chains without any extra metadata.
 #include "ecf8.h"
 #include "ecf8_table.h"
+#include "ecf8_plan.h"
 
 #include <algorithm>
 #include <cmath>
@@ -262,20 +263,94 @@ int check_header(const ecf8_header &h, uint64_t size)
 
 } // namespace
 
+namespace ecf8_internal {
+
+int check_options(uint64_t rows, uint64_t cols, const ecf8_encode_opts *opts, uint32_t *lane_syms,
+                  uint32_t *group_chunks, uint32_t *max_code_len, uint32_t *tile_rows, uint32_t *table_mode)
+{
+    if (rows == 0 || cols == 0) return ECF8_E_ARG;
+    if (rows > (1ull << 40) / cols) return ECF8_E_ARG;
+    const uint32_t N = (opts && opts->lane_syms) ? opts->lane_syms : 128;
+    const uint32_t tr = opts ? opts->tile_rows : 0;
+    const uint32_t group = (opts && opts->group_chunks) ? opts->group_chunks : (tr ? 1 : 32);
+    const uint32_t lmax = (opts && opts->max_code_len) ? opts->max_code_len : ECF8_TB / 2;
+    const uint32_t tmode = opts ? opts->table_mode : 0;
+    if (!lane_syms_ok(N) || !group_ok(group) || lmax < 4 || lmax > 15 || tmode > 2) return ECF8_E_ARG;
+    if (!tiling_ok(tr, group, rows, cols, N)) return ECF8_E_ARG;
+    *lane_syms = N;
+    *group_chunks = group;
+    *max_code_len = lmax;
+    *tile_rows = tr;
+    *table_mode = tmode;
+    return ECF8_OK;
+}
+
+int plan_encode(const uint64_t freq[16], uint64_t rows, uint64_t cols, const ecf8_encode_opts *opts, Plan *out)
+{
+    uint32_t N, group, lmax, tile_rows, tmode;
+    int rc = check_options(rows, cols, opts, &N, &group, &lmax, &tile_rows, &tmode);
+    if (rc) return rc;
+    const uint64_t n = rows * cols;
+    uint64_t fsum = 0;
+    for (int s = 0; s < 16; s++) fsum += freq[s];
+    if (fsum != n) return ECF8_E_ARG;
+    uint8_t len[16];
+    capped_lengths(freq, lmax, len);
+    if (!canonical(len, out->rcode, out->code)) return ECF8_E_FORMAT;
+    uint64_t bits = 0;
+    for (int s = 0; s < 16; s++) bits += freq[s] * len[s];
+    const uint32_t table_bits = (tmode == 1 || (tmode == 0 && n >= (1ull << 22))) ? ECF8_TB : 0;
+    const Layout L = make_layout(n, bits, N, table_bits);
+    ecf8_header &h = out->hdr;
+    std::memset(&h, 0, sizeof(h));
+    h.magic = ECF8_MAGIC;
+    h.version = ECF8_VERSION;
+    h.total_size = L.total;
+    h.n_elem = n;
+    h.rows = rows;
+    h.cols = cols;
+    h.lane_syms = N;
+    h.table_bits = (uint16_t)table_bits;
+    h.group_chunks = (uint8_t)group;
+    h.tile_rows = (uint8_t)tile_rows;
+    h.n_chunks = L.n_chunks;
+    h.stream_bits = bits;
+    std::memcpy(h.code_len, len, 16);
+    h.off_chunk_bit = L.off_cb;
+    h.off_lane_bits = L.off_lb;
+    h.off_stream = L.off_st;
+    h.off_plane = L.off_pl;
+    h.stream_bytes = L.st_bytes;
+    h.plane_bytes = L.pl_bytes;
+    std::memcpy(h.freq, freq, 16 * sizeof(uint64_t));
+    return ECF8_OK;
+}
+
+int encode_bound(uint64_t rows, uint64_t cols, const ecf8_encode_opts *opts, uint64_t *bytes)
+{
+    uint32_t N, group, lmax, tile_rows, tmode;
+    int rc = check_options(rows, cols, opts, &N, &group, &lmax, &tile_rows, &tmode);
+    if (rc) return rc;
+    const uint64_t n = rows * cols;
+    // longest stream and an embedded table, whatever the histogram turns out to be
+    *bytes = make_layout(n, n * lmax, N, tmode == 2 ? 0 : ECF8_TB).total;
+    return ECF8_OK;
+}
+
+void build_pair_table_host(const uint8_t len[16], uint16_t *tbl) { build_pair_table(len, tbl); }
+
+} // namespace ecf8_internal
+
 extern "C" {
 
 int ecf8_encode(const uint8_t *x, uint64_t rows, uint64_t cols, const ecf8_encode_opts *opts,
                 ecf8_blob **out)
 {
-    if (!x || !out || rows == 0 || cols == 0) return ECF8_E_ARG;
-    if (rows > (1ull << 40) / cols) return ECF8_E_ARG;
+    if (!x || !out) return ECF8_E_ARG;
+    uint32_t N, group, lmax, tile_rows, tmode;
+    int orc = ecf8_internal::check_options(rows, cols, opts, &N, &group, &lmax, &tile_rows, &tmode);
+    if (orc) return orc;
     const uint64_t n = rows * cols;
-    const uint32_t N = (opts && opts->lane_syms) ? opts->lane_syms : 128;
-    const uint32_t tile_rows = opts ? opts->tile_rows : 0;
-    const uint32_t group = (opts && opts->group_chunks) ? opts->group_chunks : (tile_rows ? 1 : 32);
-    const uint32_t lmax = (opts && opts->max_code_len) ? opts->max_code_len : ECF8_TB / 2;
-    if (!lane_syms_ok(N) || !group_ok(group) || lmax < 4 || lmax > 15) return ECF8_E_ARG;
-    if (!tiling_ok(tile_rows, group, rows, cols, N)) return ECF8_E_ARG;
     const ChunkMap map(n, cols, N, group, tile_rows);
     unsigned nt = (opts && opts->n_threads) ? opts->n_threads : std::thread::hardware_concurrency();
     if (nt == 0) nt = 1;
@@ -307,42 +382,17 @@ int ecf8_encode(const uint8_t *x, uint64_t rows, uint64_t cols, const ecf8_encod
         for (unsigned t = 0; t < nt; t++)
             for (int s = 0; s < 16; s++) freq[s] += part[(size_t)t * 16 + s];
 
-        uint8_t len[16];
-        uint32_t rcode[16], code[16];
-        capped_lengths(freq, lmax, len);
-        if (!canonical(len, rcode, code)) return ECF8_E_FORMAT;
-        uint64_t bits = 0;
-        for (int s = 0; s < 16; s++) bits += freq[s] * len[s];
-
-        const uint32_t tmode = opts ? opts->table_mode : 0;
-        if (tmode > 2) return ECF8_E_ARG;
-        const uint32_t table_bits = (tmode == 1 || (tmode == 0 && n >= (1ull << 22))) ? ECF8_TB : 0;
-        Layout L = make_layout(n, bits, N, table_bits);
+        ecf8_internal::Plan plan;
+        int prc = ecf8_internal::plan_encode(freq, rows, cols, opts, &plan);
+        if (prc) return prc;
+        const uint8_t *len = plan.hdr.code_len;
+        const uint32_t *rcode = plan.rcode, *code = plan.code;
+        Layout L = make_layout(n, plan.hdr.stream_bits, N, plan.hdr.table_bits);
         uint8_t *blob = (uint8_t *)std::aligned_alloc(256, L.total);
         if (!blob) return ECF8_E_NOMEM;
         std::memset(blob, 0, L.off_st); // header and metadata; payload sections are zeroed by their writers
-        ecf8_header *h = (ecf8_header *)blob;
-        h->magic = ECF8_MAGIC;
-        h->version = ECF8_VERSION;
-        h->total_size = L.total;
-        h->n_elem = n;
-        h->rows = rows;
-        h->cols = cols;
-        h->lane_syms = N;
-        h->table_bits = (uint16_t)table_bits;
-        h->group_chunks = (uint8_t)group;
-        h->tile_rows = (uint8_t)tile_rows;
-        if (table_bits) build_pair_table(len, (uint16_t *)(blob + 256));
-        h->n_chunks = L.n_chunks;
-        h->stream_bits = bits;
-        std::memcpy(h->code_len, len, 16);
-        h->off_chunk_bit = L.off_cb;
-        h->off_lane_bits = L.off_lb;
-        h->off_stream = L.off_st;
-        h->off_plane = L.off_pl;
-        h->stream_bytes = L.st_bytes;
-        h->plane_bytes = L.pl_bytes;
-        std::memcpy(h->freq, freq, sizeof(freq));
+        std::memcpy(blob, &plan.hdr, sizeof(ecf8_header));
+        if (plan.hdr.table_bits) build_pair_table(len, (uint16_t *)(blob + 256));
 
         uint64_t *chunk_bit = (uint64_t *)(blob + L.off_cb);
         uint16_t *lane_bits = (uint16_t *)(blob + L.off_lb);
