@@ -309,6 +309,46 @@ def bench_jit(a):
         "buffer_bytes_each": jit2.buffer_bytes, "resident_compressed_bytes": sum(h.total_size for hs, _ in packed for h in hs)}))
 
 
+def bench_encode(a):
+    """Workload "encode": the GPU-side encoder (ecf8_encode_gpu) on the matrices of one config-1 layer,
+    each checked byte for byte against the CPU encoder's container, beside the CPU encoder's rate."""
+    from paper_2510_02676_amd import ecf8, synth
+    dev = "cuda:0"
+    specs = synth.config1(a.seed, 1)
+    rows = {}
+    n_total, t_gpu_total, t_cpu_total = 0, 0.0, 0.0
+    for s in specs:
+        w = synth.make(s, a.seed, device=dev)
+        t0 = time.time()
+        ref = ecf8.ecf8_encode(w.cpu().numpy(), s["rows"], s["cols"])
+        t_cpu = time.time() - t0
+        hdr, d_blob = ecf8.ecf8_encode_gpu(w)
+        torch.cuda.synchronize()
+        if bytes(hdr) != bytes(ref.header) or not torch.equal(d_blob.cpu(), torch.from_numpy(ref.numpy())):
+            raise SystemExit("GPU-encoded container of %s differs from the CPU encoder's" % s["name"])
+        buf = torch.empty(d_blob.numel() + 4096, dtype=torch.uint8, device=dev)
+        for _ in range(a.warmup):
+            ecf8.ecf8_encode_gpu(w, d_blob=buf)
+        torch.cuda.synchronize()
+        t0 = time.time()
+        for _ in range(a.steps):
+            ecf8.ecf8_encode_gpu(w, d_blob=buf)
+        torch.cuda.synchronize()
+        t_gpu = (time.time() - t0) / a.steps
+        rows[s["name"]] = {"weights": w.numel(), "gpu_encode_us": round(t_gpu * 1e6, 1),
+                           "gpu_GBps": round(w.numel() / t_gpu / 1e9, 1), "cpu_encode_ms": round(t_cpu * 1e3, 1)}
+        n_total += w.numel()
+        t_gpu_total += t_gpu
+        t_cpu_total += t_cpu
+    print(json.dumps({
+        "metric": "raw FP8 GB/s consumed by the GPU-side encoder (ecf8_encode_gpu)", "value": round(n_total / t_gpu_total / 1e9, 2),
+        "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(t_gpu_total * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": "encode: one config-1 layer (7 matrices), host wall clock incl. the one histogram read-back per tensor",
+                   "weights": n_total, "seed": a.seed},
+        "identical_to_cpu_encoder": True, "cpu_encoder_GBps": round(n_total / t_cpu_total / 1e9, 3), "tensors": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -340,6 +380,8 @@ def main():
         return bench_config4(a)
     if a.workload == "jit":
         return bench_jit(a)
+    if a.workload == "encode":
+        return bench_encode(a)
     layers = a.layers or {"config1": 32, "config2": 256, "config3": 40, "config0": 1}[a.workload]
     batches, desc, t_setup = build_workload(a.workload, a.seed, a.lane_syms, layers, a.launch, a.group_chunks, a.max_code_len)
     hdrs = [t["hdr"] for _, ts in batches for t in ts]

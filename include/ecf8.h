@@ -169,6 +169,22 @@ const void *ecf8_blob_data(const ecf8_blob *blob); /* host pointer, 256-byte ali
 uint64_t ecf8_blob_size(const ecf8_blob *blob);
 
 /*
+ * ecf8_encode_gpu (Section 3.1 on the device: the paper's encoding pipeline runs
+ * on the GPU).  d_fp8: DEVICE, rows*cols raw E4M3 bytes, 16-byte aligned;
+ * d_blob: DEVICE buffer of blob_capacity bytes, 256-byte aligned, that receives
+ * the container -- byte for byte the one ecf8_encode writes for the same input
+ * and options (n_threads is ignored).  ecf8_encode_bound gives a capacity that
+ * always suffices; ECF8_E_CAPACITY if the blob turns out larger than
+ * blob_capacity (at least 256 bytes are needed in any case).  *hdr_out receives
+ * the header.  The call synchronises `stream` ONCE (it reads the 16-bin
+ * histogram back to build the code on the host), then queues the rest
+ * asynchronously.  Uses no memory besides its input and output.
+ */
+int ecf8_encode_bound(uint64_t rows, uint64_t cols, const ecf8_encode_opts *opts, uint64_t *bytes);
+int ecf8_encode_gpu(const void *d_fp8, uint64_t rows, uint64_t cols, const ecf8_encode_opts *opts,
+                    void *d_blob, uint64_t blob_capacity, ecf8_header *hdr_out, void *stream);
+
+/*
  * Header parse + structural checks of a container held in HOST memory
  * (sizes, offsets, alignment, code lengths satisfy Kraft).  Fills *hdr, which
  * is what the decode calls need on the host at launch time.

@@ -69,6 +69,8 @@ assert ctypes.sizeof(Header) == 256 and ctypes.sizeof(BatchItem) == 128
 
 _vp, _u64, _u32 = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32
 _lib.ecf8_encode.argtypes = [_vp, _u64, _u64, ctypes.POINTER(EncodeOpts), ctypes.POINTER(_vp)]
+_lib.ecf8_encode_bound.argtypes = [_u64, _u64, ctypes.POINTER(EncodeOpts), ctypes.POINTER(_u64)]
+_lib.ecf8_encode_gpu.argtypes = [_vp, _u64, _u64, ctypes.POINTER(EncodeOpts), _vp, _u64, ctypes.POINTER(Header), _vp]
 _lib.ecf8_blob_free.argtypes = [_vp]
 _lib.ecf8_blob_free.restype = None
 _lib.ecf8_blob_data.argtypes = [_vp]
@@ -168,6 +170,25 @@ def ecf8_encode(fp8, rows=None, cols=None, lane_syms=0, n_threads=0, table_mode=
     h = _vp()
     _check("ecf8_encode", _lib.ecf8_encode(x.ctypes.data, rows, cols, ctypes.byref(opts), ctypes.byref(h)))
     return Blob(h)
+
+
+def ecf8_encode_gpu(d_fp8, rows=None, cols=None, lane_syms=0, table_mode=0, group_chunks=0, max_code_len=0,
+                    tile_rows=0, d_blob=None, stream=None):
+    """GPU encoder: uint8 device tensor of raw E4M3 bytes -> (Header, uint8 device tensor holding the blob).
+    Same options and same bytes as ecf8_encode."""
+    if rows is None:
+        rows, cols = (d_fp8.shape if d_fp8.dim() == 2 else (1, d_fp8.numel()))
+    if rows * cols != d_fp8.numel() or d_fp8.dtype != torch.uint8 or not d_fp8.is_contiguous():
+        raise Ecf8Error("ecf8_encode_gpu", E_ARG)
+    opts = EncodeOpts(lane_syms, 0, table_mode, group_chunks, max_code_len, tile_rows)
+    if d_blob is None:
+        bound = _u64(0)
+        _check("ecf8_encode_bound", _lib.ecf8_encode_bound(rows, cols, ctypes.byref(opts), ctypes.byref(bound)))
+        d_blob = torch.empty(int(bound.value), dtype=torch.uint8, device=d_fp8.device)
+    hdr = Header()
+    _check("ecf8_encode_gpu", _lib.ecf8_encode_gpu(d_fp8.data_ptr(), rows, cols, ctypes.byref(opts), d_blob.data_ptr(),
+                                                   d_blob.numel(), ctypes.byref(hdr), _stream_ptr(stream)))
+    return hdr, d_blob[:hdr.total_size]
 
 
 def blob_describe(ptr_or_array, size=None):
