@@ -187,11 +187,25 @@ def bench_config4(a):
         def two():
             ecf8.ecf8_decode(h_lin, d_lin, wout)
             ecf8.ecf8_gemm_fp8_raw(wout, x, y2)
+        # the vendor library's FP8 GEMM on the same uncompressed operands, as context for the raw twin
+        t_vendor = None
+        try:
+            mp = max(M, 16)
+            xp = torch.zeros((mp, spec["cols"]), dtype=torch.uint8, device="cuda:0")
+            xp[:M] = x
+            one = torch.ones((), device="cuda:0", dtype=torch.float32)
+            a8, b8 = xp.view(torch.float8_e4m3fn), w.view(torch.float8_e4m3fn).t()
+            vend = lambda: torch._scaled_mm(a8, b8, scale_a=one, scale_b=one, out_dtype=torch.float32)
+            if (vend()[:M] - y2).abs().max().item() <= 1e-4 * y2.abs().max().item():
+                t_vendor = timeit(vend, a.steps, a.warmup)
+        except Exception:
+            t_vendor = None
         tf = timeit(lambda: ecf8.ecf8_gemm_fp8(h, d_blob, x, y), a.steps, a.warmup)
         tr = timeit(lambda: ecf8.ecf8_gemm_fp8_raw(w, x, y2), a.steps, a.warmup)
         t2 = timeit(two, a.steps, a.warmup)
         res["M=%d" % M] = {"fused_us": round(tf * 1e6, 2), "raw_fp8_gemm_us": round(tr * 1e6, 2),
                            "decode_then_gemm_us": round(t2 * 1e6, 2),
+                           "vendor_fp8_gemm_us": None if t_vendor is None else round(t_vendor * 1e6, 2),
                            "fused_weight_GBps": round(w.numel() / tf / 1e9, 1)}
     t16 = res["M=16"]["fused_us"] * 1e-6
     print(json.dumps({
