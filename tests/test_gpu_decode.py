@@ -226,6 +226,13 @@ def test_config1_full_layer(orc, max_code_len):
     _full_size_case(orc, synth.config1(0, 1), {"l0.k", "l0.q"}, max_code_len)
 
 
+def test_config1_whole_stack_one_launch(orc):
+    """configs[1] at full size in the launch configuration bench.py times: all 32 layers (224
+    matrices, 6.98 G weights) through ONE ecf8_decode_batched launch; every output compared with
+    its input on the device, two matrices also with the oracle's own encode -> bit-serial decode."""
+    _full_size_case(orc, synth.config1(0, 32), {"l17.v", "l31.k"})
+
+
 def test_config2_experts_and_attention(orc):
     """configs[2]: six full-size expert matrices and the two attention projections in one launch."""
     specs = synth.config2(0, 2)
