@@ -72,8 +72,16 @@ struct Cfg {
     // LDS map (byte offsets into one array)
     static constexpr int OFF_TBL = 0;
     static constexpr int OFF_SYM = OFF_TBL + TBL_ENTRIES * 2;  // s_len[16], s_code[16]
-    static constexpr int OFF_CTL = OFF_SYM + 128;              // ticket counter, oversize flag
-    static constexpr int OFF_WAVES = OFF_CTL + 16;
+    static constexpr int OFF_CTL = OFF_SYM + 128;              // ticket counter, oversize count, oversize list
+    static constexpr int LIST_MAX = 60;                        // oversize chunks remembered per (workgroup, tensor)
+    static constexpr int OFF_WAVES = OFF_CTL + 16 + 4 * LIST_MAX;
+    // After the pipelined loop the waves' stages together serve as a few wide slots, each large
+    // enough for the longest span any code can produce (15 bits per symbol), for the chunks whose
+    // span did not fit a stage.
+    static constexpr int SLOT = 64 * N * 15 / 8 + 64;
+    static constexpr int SLOTS = (WAVES * STAGE / SLOT) < WAVES ? (WAVES * STAGE / SLOT) : WAVES;
+    static_assert(PAIRFIT || SLOTS >= 1, "wide slots must fit the stage area");
+    static_assert(OFF_WAVES % 16 == 0 && SLOT % 16 == 0, "16-byte LDS stores");
     static constexpr int WAVES_BYTES = WAVES * STAGE > TBL_ENTRIES * 2 ? WAVES * STAGE : TBL_ENTRIES * 2;
     static constexpr int TOTAL = OFF_WAVES + WAVES_BYTES;   // table-build scratch aliases the stages
     static_assert(TOTAL <= 160 * 1024, "LDS of one gfx950 CU");
@@ -90,7 +98,8 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
     uint32_t *s_len = (uint32_t *)(smem + C::OFF_SYM);
     uint32_t *s_code = s_len + 16;
     uint32_t *s_ticket = (uint32_t *)(smem + C::OFF_CTL);
-    uint32_t *s_oversize = s_ticket + 1;
+    uint32_t *s_oversize = s_ticket + 1;                  // number of oversize chunks met in the loop
+    uint32_t *s_list = s_ticket + 4;                      // their chunk numbers, relative to c
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -213,7 +222,6 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
         // in bounds) and redone by the generic pass below, as is a ragged last chunk.
         const bool ragged_tail = (n_elem % (64ull * N)) != 0;
         const uint64_t fast_end = (ragged_tail && seg_end == t_end) ? seg_end - 1 : seg_end;
-        bool any_oversize = false;
         // next chunk of this workgroup's range, drawn from the LDS ticket counter (wave-uniform)
         auto draw = [&]() -> uint64_t {
             uint32_t t = 0;
@@ -258,6 +266,44 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
             build_tables(len_lo, len_hi, tbl, s_len, s_code, (uint16_t *)(smem + C::OFF_WAVES), tid, WAVES * 64);
         }
 
+        // Decode of one full chunk whose span sits in LDS from bit `first_bit` (smem-relative) on,
+        // merge with the nibble plane, stores.
+        auto decode_store = [&](uint32_t first_bit, uint32_t lb, const u32x2 (&pl)[C::PIECES], GLOBAL uint8_t *out_c,
+                                uint32_t ostride) {
+            // LDS bit addresses, kept one bit off as quad_step2 wants them: bpA = the forward
+            // run's next codeword - 1; bpB = one past the backward run's next codeword - 31
+            uint32_t bpA = first_bit - 1;   // oversize chunk in the loop: may point past LDS, reads return 0
+            uint32_t bpB = bpA + lb - 30;
+            // PAIRFIT: the chunk's pieces are kept in registers and stored in one burst at
+            // its end.  Together with the interleaved layout the workgroup's waves then
+            // write runs of adjacent KiBs close in time, which HBM takes ~15 % faster than
+            // single KiBs trickling out of every wave as they are decoded; the general
+            // kernel has no registers to spare for that.
+            u32x4 ov[PAIRFIT ? C::PIECES : 1];
+#pragma unroll
+            for (int Q = 0; Q < C::PIECES / 2; Q++) {
+                uint32_t dwA[4], dwB[4];
+#pragma unroll
+                for (int t = 0; t < 4; t++) {
+                    quad_step2<PAIRFIT>(smem, tbl, s_len, s_code, bpA, bpB, dwA[t], dwB[t]);
+                }
+                if constexpr (PAIRFIT) {
+                    ov[Q] = merge_piece(dwA, pl[Q]);
+                    ov[Q + C::PIECES / 2] = merge_piece(dwB, pl[Q + C::PIECES / 2]);
+                } else {
+                    ST_STREAM(merge_piece(dwA, pl[Q]), (GLOBAL u32x4 *)(out_c + Q * ostride));
+                    ST_STREAM(merge_piece(dwB, pl[Q + C::PIECES / 2]),
+                              (GLOBAL u32x4 *)(out_c + (Q + C::PIECES / 2) * ostride));
+                }
+            }
+            if constexpr (PAIRFIT) {
+                __builtin_amdgcn_sched_barrier(0);   // keep the stores together, after the decode
+#pragma unroll
+                for (int Q = 0; Q < C::PIECES; Q++) ST_STREAM(ov[Q], (GLOBAL u32x4 *)(out_c + Q * ostride));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+
         if (cg < fast_end) {
             // Drain the prologue's loads here (vmcnt(0), other counters untouched), so that
             // the wait at the loop head is decided by the back edge alone, where the four
@@ -272,7 +318,6 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
                 uint64_t byte0;
                 const uint64_t span64 = span_of(m_cur, byte0);
                 const bool staged = __builtin_amdgcn_readfirstlane((uint32_t)(span64 <= (uint64_t)C::STAGE)) != 0;
-                any_oversize |= !staged;
 
                 // lane start bit = chunk start + exclusive DPP scan of the lanes' bit counts
                 const uint32_t rel = wave_incl_scan(m_cur.lb) - m_cur.lb;
@@ -296,39 +341,11 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
                     if (cg2 < fast_end) m_next2 = load_meta(cg2 - first_chunk);
                 }
 
-                // LDS bit addresses (smem-relative), kept one bit off as quad_step2 wants them:
-                // bpA = the forward run's next codeword - 1; bpB = one past the backward run's
-                // next codeword - 31
-                uint32_t bpA = stage_off * 8 + bit_in - 1;   // oversize chunk: may point past LDS, reads return 0
-                uint32_t bpB = bpA + m_cur.lb - 30;
-                // PAIRFIT: the chunk's pieces are kept in registers and stored in one burst at
-                // its end.  Together with the interleaved layout the workgroup's waves then
-                // write runs of adjacent KiBs close in time, which HBM takes ~15 % faster than
-                // single KiBs trickling out of every wave as they are decoded; the general
-                // kernel has no registers to spare for that.
-                u32x4 ov[PAIRFIT ? C::PIECES : 1];
-#pragma unroll
-                for (int Q = 0; Q < C::PIECES / 2; Q++) {
-                    uint32_t dwA[4], dwB[4];
-#pragma unroll
-                    for (int t = 0; t < 4; t++) {
-                        quad_step2<PAIRFIT>(smem, tbl, s_len, s_code, bpA, bpB, dwA[t], dwB[t]);
-                    }
-                    if constexpr (PAIRFIT) {
-                        ov[Q] = merge_piece(dwA, pl[Q]);
-                        ov[Q + C::PIECES / 2] = merge_piece(dwB, pl[Q + C::PIECES / 2]);
-                    } else {
-                        ST_STREAM(merge_piece(dwA, pl[Q]), (GLOBAL u32x4 *)(out_c + Q * ostride));
-                        ST_STREAM(merge_piece(dwB, pl[Q + C::PIECES / 2]),
-                                  (GLOBAL u32x4 *)(out_c + (Q + C::PIECES / 2) * ostride));
-                    }
+                if (!staged && lane == 0) {
+                    const uint32_t at = __hip_atomic_fetch_add(s_oversize, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    if (at < (uint32_t)C::LIST_MAX) s_list[at] = (uint32_t)(cg - c);
                 }
-                if constexpr (PAIRFIT) {
-                    __builtin_amdgcn_sched_barrier(0);   // keep the stores together, after the decode
-#pragma unroll
-                    for (int Q = 0; Q < C::PIECES; Q++) ST_STREAM(ov[Q], (GLOBAL u32x4 *)(out_c + Q * ostride));
-                    __builtin_amdgcn_sched_barrier(0);
-                }
+                decode_store(stage_off * 8 + bit_in, m_cur.lb, pl, out_c, ostride);
 
                 if (!has_next) break;
                 m_cur = m_next;
@@ -337,20 +354,65 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
                 cg1 = cg2;
             }
         }
-        if (any_oversize && lane == 0) *s_oversize = 1;
         __syncthreads();
 
-        // Generic pass, symbol by symbol with windows and nibbles read straight from HBM:
-        // the ragged last chunk of the tensor, and chunks that code so much worse than 4 bits
-        // per symbol that their span did not fit the stage.
-        if (*s_oversize || fast_end != seg_end) {
+        // Chunks whose span did not fit a stage (they code far worse than 4 bits per symbol; the
+        // loop decoded garbage for them, in bounds): the stage area now serves as SLOTS wide slots.
+        // Round by round the workgroup copies up to SLOTS such spans in, and one wave per slot
+        // decodes with the loop's own steps.  PAIRFIT launches never get here with a valid blob.
+        const uint32_t n_over = *s_oversize;
+        bool scan_all = fast_end != seg_end;          // the ragged last chunk always takes the symbol pass
+        if (n_over != 0) {
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");   // the loop's stores land first
+            if (PAIRFIT || n_over > (uint32_t)C::LIST_MAX) {
+                scan_all = true;                      // too many to remember: symbol pass over everything
+            } else {
+                for (uint32_t r0 = 0; r0 < n_over; r0 += C::SLOTS) {
+                    __syncthreads();                  // slots free (first round: every wave is out of the loop)
+                    for (uint32_t k = 0; k < (uint32_t)C::SLOTS && r0 + k < n_over; k++) {
+                        const uint64_t cl = c + s_list[r0 + k] - first_chunk;
+                        const uint64_t sb0 = chunk_bit[cl], sb1 = chunk_bit[cl + 1];
+                        uint64_t byte_end = ((sb1 + 7) >> 3) + 8;
+                        if (byte_end > st_bytes) byte_end = st_bytes;
+                        uint64_t byte0 = (sb0 >> 3) & ~15ull;
+                        if (byte0 > byte_end) byte0 = byte_end;
+                        const uint64_t span = byte_end - byte0;
+                        uint8_t *slot = smem + C::OFF_WAVES + k * C::SLOT;
+                        for (uint32_t i = tid * 16; i < (uint32_t)C::SLOT && i < span; i += WAVES * 64 * 16)
+                            *(u32x4 *)(slot + i) = *(const GLOBAL u32x4 *)(stream + byte0 + i);
+                    }
+                    __syncthreads();
+                    if ((uint32_t)wave < (uint32_t)C::SLOTS && r0 + wave < n_over) {
+                        const uint64_t cl = c + s_list[r0 + wave] - first_chunk;
+                        const Meta m = load_meta(cl);
+                        uint64_t byte0;
+                        const uint64_t span = span_of(m, byte0);
+                        if (span <= (uint64_t)C::SLOT) {          // else: a corrupt blob, left as decoded in the loop
+                            u32x2 pl[C::PIECES];
+                            const GLOBAL uint8_t *plane_c = plane + (chunk_base(cl) + lane_off) / 2;
+                            const uint32_t pstride = chunk_stride(cl) / 2;
+#pragma unroll
+                            for (int j = 0; j < C::PIECES; j++) pl[j] = *(const GLOBAL u32x2 *)(plane_c + j * pstride);
+                            const uint32_t rel = wave_incl_scan(m.lb) - m.lb;
+                            const uint64_t b0 = __builtin_amdgcn_readfirstlane((uint32_t)m.b0) |
+                                                ((uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)(m.b0 >> 32)) << 32);
+                            decode_store((C::OFF_WAVES + wave * C::SLOT) * 8 + (uint32_t)(b0 - byte0 * 8) + rel, m.lb, pl,
+                                         out + chunk_base(cl) + lane_off, chunk_stride(cl));
+                        }
+                    }
+                }
+            }
+        }
+        // Symbol pass, with windows and nibbles read straight from HBM: the ragged last chunk of
+        // the tensor (and everything oversize when the list above did not apply).
+        if (scan_all) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
             for (uint64_t cg2 = c + wave; cg2 < seg_end; cg2 += WAVES) {
                 const uint64_t cl = cg2 - first_chunk;
                 Meta m = load_meta(cl);
                 uint64_t byte0;
                 const uint64_t span64 = span_of(m, byte0);
-                const bool redo = cg2 >= fast_end || span64 > (uint64_t)C::STAGE;
+                const bool redo = cg2 >= fast_end || (span64 > (uint64_t)C::STAGE && (PAIRFIT || n_over > (uint32_t)C::LIST_MAX));
                 if (!__builtin_amdgcn_readfirstlane((uint32_t)redo)) continue;
                 const uint64_t elem0 = chunk_base(cl);
                 const uint32_t estride = chunk_stride(cl);

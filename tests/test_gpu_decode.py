@@ -101,6 +101,38 @@ def test_degenerate_and_extreme_inputs(orc, name, lane_syms, cap):
     assert np.array_equal(got, _oracle_expected(orc, x))
 
 
+@pytest.mark.parametrize("lane_syms", [32, 64, 128])
+@pytest.mark.parametrize("island_chunks,workgroups,group", [(6, 0, 1), (40, 1, 1), (150, 1, 1), (150, 0, 1), (150, 0, 32)])
+def test_islands_of_long_codes(orc, lane_syms, island_chunks, workgroups, group):
+    """Plain-Huffman blobs whose chunks code far worse than the stage allows: one exponent fills
+    90 % of the tensor (1-bit code), islands hold only the fifteen rare ones (5 bits and more per
+    symbol, spans larger than a wave's stage).  A few such chunks per workgroup go through the wide
+    slots, more than the kernel remembers (one workgroup, 150 chunks) through the symbol pass."""
+    rng = np.random.default_rng(lane_syms + island_chunks)
+    chunk = 64 * lane_syms
+    n = 40 * island_chunks * chunk + 12345
+    e = np.full(n, 7, dtype=np.uint8)
+    rare = np.array([v for v in range(16) if v != 7], dtype=np.uint8)
+    for start in (3 * chunk + 17, n // 2):                     # two islands, the first one unaligned
+        m = island_chunks * chunk // 2
+        e[start:start + m] = rng.choice(rare, size=m)
+    x = ((rng.integers(0, 2, n, dtype=np.uint8) << 7) | (e << 3) | rng.integers(0, 8, n, dtype=np.uint8)).astype(np.uint8)
+    blob = ecf8.ecf8_encode(x, 1, n, lane_syms=lane_syms, max_code_len=15, group_chunks=group)
+    h = blob.header
+    assert max(h.code_len) > 4 and min(v for v in h.code_len if v) == 1
+    cb = blob.numpy()[h.off_chunk_bit:h.off_chunk_bit + 8 * (h.n_chunks + 1)].view("<u8").astype(np.int64)
+    assert (np.diff(cb) / 8 > lane_syms * 32 + 64).sum() >= (island_chunks - 4 if group == 1 else 64)   # spans beyond a wave's stage
+    pad = 4096
+    buf = torch.full((pad + n + pad,), 0xA5, dtype=torch.uint8, device=DEV)
+    batch = ecf8.Batch([h], [blob.to(DEV)], [buf[pad:pad + n]])
+    batch.info.max_workgroups = workgroups
+    ecf8.ecf8_decode_batched(batch)
+    torch.cuda.synchronize()
+    host = buf.cpu().numpy()
+    assert (host[:pad] == 0xA5).all() and (host[pad + n:] == 0xA5).all()
+    assert np.array_equal(host[pad:pad + n], x)
+
+
 @pytest.mark.parametrize("lane_syms,group", [(32, 1), (32, 64), (64, 2), (64, 32), (128, 1), (128, 8), (128, 64)])
 def test_group_widths(orc, lane_syms, group):
     """Every interleave width the format allows next to the default: whole groups, then
