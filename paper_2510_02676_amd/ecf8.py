@@ -205,6 +205,21 @@ def blob_validate(arr):
     _check("ecf8_blob_validate", _lib.ecf8_blob_validate(arr.ctypes.data, arr.size))
 
 
+def save_blob(path, blob):
+    """Writes a container (Blob or uint8 array) to a file as is: the format is position independent."""
+    arr = blob.numpy() if isinstance(blob, Blob) else np.ascontiguousarray(blob, dtype=np.uint8)
+    blob_validate(arr)
+    with open(path, "wb") as f:
+        f.write(arr.tobytes())
+
+
+def load_blob(path):
+    """Reads a container file; returns (Header, uint8 array) after the full host-side check."""
+    arr = np.fromfile(path, dtype=np.uint8)
+    blob_validate(arr)
+    return blob_describe(arr), arr
+
+
 def blob_stats(hdr):
     st = Stats()
     _check("ecf8_blob_stats", _lib.ecf8_blob_stats(ctypes.byref(hdr), ctypes.byref(st)))

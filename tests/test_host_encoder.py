@@ -213,6 +213,22 @@ def test_synthetic_config0_compresses_like_the_paper_band(orc):
     assert np.array_equal(dec, w.reshape(-1))
 
 
+def test_container_files_round_trip(orc, tmp_path):
+    x = _rand_bytes(70001, 9)
+    b = ecf8.ecf8_encode(x, 1, x.size)
+    path = str(tmp_path / "w.ecf8")
+    ecf8.save_blob(path, b)
+    hdr, arr = ecf8.load_blob(path)
+    assert bytes(hdr) == bytes(b.header) and np.array_equal(arr, b.numpy())
+    dec, _ = orc.container_decode(arr)
+    assert np.array_equal(dec, x)
+    with open(path, "r+b") as f:                      # a damaged file is refused
+        f.seek(int(hdr.off_lane_bits))
+        f.write(b"\xff\xff")
+    with pytest.raises(ecf8.Ecf8Error):
+        ecf8.load_blob(path)
+
+
 def test_error_paths():
     x = _rand_bytes(1000, 1)
     with pytest.raises(ecf8.Ecf8Error) as e:
