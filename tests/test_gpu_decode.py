@@ -147,6 +147,49 @@ def test_group_widths(orc, lane_syms, group):
     assert np.array_equal(got, _oracle_expected(orc, x))
 
 
+@pytest.mark.parametrize("block", range(6))
+def test_seeded_sweep_of_shapes_and_options(orc, block):
+    """240 seeded combinations of size, lane_syms, group width, code cap, table mode and exponent
+    skew, each decoded alone (guarded buffer) and all of a block again in one mixed batch."""
+    rng = np.random.default_rng(9000 + block)
+    cases = []
+    for i in range(40):
+        lane_syms = int(rng.choice([32, 64, 128]))
+        chunk = 64 * lane_syms
+        kind = i % 5
+        if kind == 0:
+            n = int(rng.integers(1, 3 * chunk))
+        elif kind == 1:
+            n = int(rng.integers(1, 40)) * chunk + int(rng.choice([-1, 0, 1, 15, 16, 17]))
+        elif kind == 2:
+            g = int(rng.choice([2, 4, 8]))
+            n = g * chunk * int(rng.integers(1, 4)) + int(rng.integers(0, 2 * chunk))
+        else:
+            n = int(rng.integers(1, 400_000))
+        n = max(n, 1)
+        group = int(rng.choice([1, 2, 4, 8, 16, 32, 64]))
+        cap = int(rng.choice([0, 0, 15, 4, 9]))
+        conc = float(rng.choice([0.05, 0.2, 0.5, 2.0, 50.0]))
+        x = _rand_bytes(n, int(rng.integers(1 << 30)), conc=conc)
+        blob = ecf8.ecf8_encode(x, 1, n, lane_syms=lane_syms, group_chunks=group, max_code_len=cap,
+                                table_mode=int(rng.choice([1, 2])))
+        got, guards = _gpu_decode_guarded(blob.numpy(), blob.header, pad=512)
+        assert guards, (lane_syms, n, group, cap)
+        assert np.array_equal(got, x), (lane_syms, n, group, cap, conc)
+        cases.append((lane_syms, x, blob))
+    assert np.array_equal(_oracle_expected(orc, cases[0][1]), cases[0][1])
+    for lane_syms in (32, 64, 128):
+        sel = [(x, b) for ls, x, b in cases if ls == lane_syms]
+        if not sel:
+            continue
+        outs = [torch.full((x.size,), 0x33, dtype=torch.uint8, device=DEV) for x, _ in sel]
+        batch = ecf8.Batch([b.header for _, b in sel], [b.to(DEV) for _, b in sel], outs)
+        ecf8.ecf8_decode_batched(batch)
+        torch.cuda.synchronize()
+        for (x, _), o in zip(sel, outs):
+            assert np.array_equal(o.cpu().numpy(), x)
+
+
 @pytest.mark.parametrize("lane_syms,rows,cols,cap", [(32, 16, 128, 0), (64, 64, 4096, 0), (64, 160, 1024, 15),
                                                      (128, 48, 3584, 0), (128, 1024, 1024, 15)])
 def test_row_tiled_blobs_decode(orc, lane_syms, rows, cols, cap):

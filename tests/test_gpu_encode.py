@@ -60,6 +60,21 @@ def test_row_tiled_layout(orc, lane_syms, rows, cols):
     _check_same(orc, x, rows, cols, lane_syms=lane_syms, tile_rows=16)
 
 
+@pytest.mark.parametrize("block", range(4))
+def test_seeded_sweep_of_shapes_and_options(orc, block):
+    """120 seeded combinations of size, lane_syms, group width, cap, table mode and exponent skew:
+    the device writes the CPU encoder's container every time."""
+    rng = np.random.default_rng(7000 + block)
+    for i in range(30):
+        lane_syms = int(rng.choice([32, 64, 128]))
+        chunk = 64 * lane_syms
+        n = max(1, int(rng.integers(1, 40)) * chunk + int(rng.integers(-chunk, chunk)) if i % 2 else int(rng.integers(1, 300_000)))
+        x = _rand_bytes(n, int(rng.integers(1 << 30)), conc=float(rng.choice([0.05, 0.3, 2.0, 50.0])))
+        _check_same(orc, x, 1, n, oracle_read=(i % 5 == 0), lane_syms=lane_syms,
+                    group_chunks=int(rng.choice([1, 2, 8, 32, 64])), max_code_len=int(rng.choice([0, 15, 4, 10])),
+                    table_mode=int(rng.choice([1, 2])))
+
+
 def test_special_histograms(orc):
     fib = [1, 1]
     while len(fib) < 16:
