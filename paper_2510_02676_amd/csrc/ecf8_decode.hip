@@ -456,7 +456,7 @@ int launch_as(const KArgs &a, int wgs_per_cu, hipStream_t s)
 }
 
 // Workgroup shapes.  General kernel: as many waves as the registers allow (its second level
-// makes it latency-bound).  PAIRFIT kernel: N = 128 runs 8 waves of ~200 VGPRs, which is what
+// makes it latency-bound).  PAIRFIT kernel: N = 128 runs 8 waves of ~220 VGPRs, which is what
 // holding a chunk's 8 output pieces for the store burst takes; it has compute to spare.
 int dispatch(const KArgs &a, uint32_t lane_syms, hipStream_t s)
 {
