@@ -12,7 +12,7 @@ import subprocess
 import numpy as np
 
 _DIR = os.path.dirname(os.path.abspath(__file__))
-_SRC = [os.path.join(_DIR, f) for f in ("ecf8_oracle.c", "ecf8_container.c", "paper_alg1.c", "gemm_ref.c")]
+_SRC = [os.path.join(_DIR, f) for f in ("ecf8_oracle.c", "ecf8_container.c", "paper_alg1.c", "gemm_ref.c", "ecfw_oracle.c")]
 _LIB = os.path.join(_DIR, "libecf8_oracle.so")
 
 MSB_FIRST = 0
@@ -45,6 +45,9 @@ def lib():
         _lib.orc_stream_bits.restype = ctypes.c_uint64
         _lib.orc_container_size.restype = ctypes.c_uint64
         _lib.orc_container_size.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint32]
+        _lib.orw_container_size.restype = ctypes.c_uint64
+        _lib.orw_container_size.argtypes = [ctypes.c_int, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint32]
+        _lib.orw_stream_bits.restype = ctypes.c_uint64
     return _lib
 
 
@@ -253,3 +256,112 @@ def gemm_ref(X, W):
     A = np.zeros((M, N), dtype=np.float64)
     lib().orc_gemm_ref(_p(X), _p(W), ctypes.c_uint64(M), ctypes.c_uint64(N), ctypes.c_uint64(K), _p(Y), _p(A))
     return Y, A
+
+
+# ---- wide alphabets (E5M2, BF16): ecfw_oracle.c ----
+
+FMT_E5M2, FMT_BF16 = 1, 2
+W_ALPHABET = {FMT_E5M2: 32, FMT_BF16: 256}
+W_ELEM_BYTES = {FMT_E5M2: 1, FMT_BF16: 2}
+
+
+def _w_bytes(fmt, x):
+    """x: uint8 (E5M2) or uint16 (BF16 bit patterns) -> flat little-endian bytes, element count."""
+    x = np.ascontiguousarray(x)
+    if fmt == FMT_BF16:
+        assert x.dtype == np.uint16
+        return x.reshape(-1).view(np.uint8), x.size
+    assert x.dtype == np.uint8
+    return x.reshape(-1), x.size
+
+
+def w_split(fmt, x):
+    """(exponent fields, remaining bits sign-on-top) of every element."""
+    b, n = _w_bytes(fmt, x)
+    sym = np.zeros(n, dtype=np.uint8)
+    rem = np.zeros(n, dtype=np.uint8)
+    lib().orw_split(ctypes.c_int(fmt), _p(b), ctypes.c_uint64(n), _p(sym), _p(rem))
+    return sym, rem
+
+
+def w_histogram(fmt, x):
+    b, n = _w_bytes(fmt, x)
+    freq = np.zeros(W_ALPHABET[fmt], dtype=np.uint64)
+    rc = lib().orw_histogram(ctypes.c_int(fmt), _p(b), ctypes.c_uint64(n), _p(freq))
+    if rc:
+        raise ValueError("orw_histogram: %d" % rc)
+    return freq
+
+
+def w_huffman_lengths(freq):
+    freq = np.ascontiguousarray(freq, dtype=np.uint64)
+    ln = np.zeros(freq.size, dtype=np.uint8)
+    rc = lib().orw_huffman_lengths(_p(freq), ctypes.c_int(freq.size), _p(ln))
+    if rc:
+        raise ValueError("orw_huffman_lengths: %d" % rc)
+    return ln
+
+
+def w_lengths_limited(freq, max_len):
+    """(lengths, cost) of a cheapest prefix code with every length <= max_len."""
+    freq = np.ascontiguousarray(freq, dtype=np.uint64)
+    ln = np.zeros(freq.size, dtype=np.uint8)
+    cost = ctypes.c_uint64(0)
+    rc = lib().orw_lengths_limited(_p(freq), ctypes.c_int(freq.size), ctypes.c_int(max_len), _p(ln), ctypes.byref(cost))
+    if rc:
+        raise ValueError("orw_lengths_limited: %d" % rc)
+    return ln, int(cost.value)
+
+
+def w_canonical(lengths):
+    lengths = np.ascontiguousarray(lengths, dtype=np.uint8)
+    code = np.zeros(lengths.size, dtype=np.uint32)
+    rc = lib().orw_canonical(_p(lengths), ctypes.c_int(lengths.size), _p(code))
+    if rc:
+        raise ValueError("orw_canonical: %d" % rc)
+    return code
+
+
+def w_stream_bits(freq, lengths):
+    freq = np.ascontiguousarray(freq, dtype=np.uint64)
+    lengths = np.ascontiguousarray(lengths, dtype=np.uint8)
+    return int(lib().orw_stream_bits(_p(freq), _p(lengths), ctypes.c_int(freq.size)))
+
+
+def w_container_encode(fmt, x, rows, cols, lane_syms, group_chunks, lengths):
+    b, n = _w_bytes(fmt, x)
+    assert n == rows * cols
+    lengths = np.ascontiguousarray(lengths, dtype=np.uint8)
+    assert lengths.size == W_ALPHABET[fmt]
+    cap = int(lib().orw_container_size(fmt, n, n * 16, lane_syms)) + 256
+    if cap <= 256:
+        raise ValueError("orw_container_encode: %d" % E_ARG)
+    blob = np.zeros(cap, dtype=np.uint8)
+    size = ctypes.c_uint64(0)
+    rc = lib().orw_container_encode(ctypes.c_int(fmt), _p(b), ctypes.c_uint64(rows), ctypes.c_uint64(cols),
+                                    ctypes.c_uint32(lane_syms), ctypes.c_uint32(group_chunks), _p(lengths),
+                                    _p(blob), ctypes.c_uint64(cap), ctypes.byref(size))
+    if rc:
+        raise ValueError("orw_container_encode: %d" % rc)
+    return blob[: int(size.value)].copy()
+
+
+def w_container_decode(blob):
+    """Returns (elements as uint8 or uint16, stream_bits); ValueError(code) on any inconsistency."""
+    blob = _u8(blob)
+    if blob.size < 256:
+        raise ValueError("orw_container_decode: %d" % E_FORMAT)
+    n = int(np.frombuffer(blob[16:24].tobytes(), dtype="<u8")[0])
+    fmt = int(np.frombuffer(blob[40:44].tobytes(), dtype="<u4")[0])
+    eb = W_ELEM_BYTES.get(fmt, 1)
+    if n > blob.size * 64:
+        raise ValueError("orw_container_decode: %d" % E_FORMAT)
+    out = np.zeros(max(n, 1) * eb, dtype=np.uint8)
+    n_out = ctypes.c_uint64(0)
+    bits = ctypes.c_uint64(0)
+    rc = lib().orw_container_decode(_p(blob), ctypes.c_uint64(blob.size), _p(out), ctypes.c_uint64(max(n, 1)),
+                                    ctypes.byref(n_out), ctypes.byref(bits))
+    if rc:
+        raise ValueError("orw_container_decode: %d" % rc)
+    out = out[: int(n_out.value) * eb]
+    return (out.view(np.uint16) if fmt == FMT_BF16 else out), int(bits.value)

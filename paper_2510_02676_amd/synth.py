@@ -134,6 +134,24 @@ def config4():
     return [dict(name="w", rows=14336, cols=4096, alpha=1.7, scale=0.02, scaling="block128", tensor_id=400000)]
 
 
+def make_bf16(rows, cols, alpha, scale, seed, tensor_id=0, device="cpu"):
+    """One synthetic weight matrix as a uint16 tensor of BF16 bit patterns (unscaled weights)."""
+    gen = torch.Generator(device=device)
+    gen.manual_seed(_mix(seed, tensor_id))
+    w = alpha_stable(rows * cols, alpha, scale, gen, device).view(rows, cols)
+    return w.to(torch.bfloat16).view(torch.uint16)
+
+
+def make_e5m2(rows, cols, alpha, scale, seed, tensor_id=0, device="cpu"):
+    """The same weights scaled per tensor to the E5M2 range (largest magnitude -> 57344), as uint8."""
+    gen = torch.Generator(device=device)
+    gen.manual_seed(_mix(seed, tensor_id))
+    w = alpha_stable(rows * cols, alpha, scale, gen, device).view(rows, cols)
+    m = w.abs().max()
+    s = torch.where(m > 0, 57344.0 / m, torch.ones_like(m))
+    return (w * s).clamp(-57344.0, 57344.0).to(torch.float8_e5m2).view(torch.uint8)
+
+
 def make(spec, seed=0, device="cpu"):
     return make_weight(spec["rows"], spec["cols"], spec["alpha"], spec["scale"], seed,
                        spec["tensor_id"], spec["scaling"], device)
