@@ -24,11 +24,6 @@
 #include <thread>
 #include <vector>
 
-struct ecf8_blob {
-    uint8_t *data;
-    uint64_t size;
-};
-
 namespace {
 
 inline uint64_t round_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }

@@ -7,6 +7,12 @@
 
 #include "ecf8.h"
 
+// A host blob: `data` comes from std::aligned_alloc(256, .) and is released by ecf8_blob_free.
+struct ecf8_blob {
+    uint8_t *data;
+    uint64_t size;
+};
+
 namespace ecf8_internal {
 
 struct Plan {

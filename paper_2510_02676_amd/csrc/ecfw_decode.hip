@@ -1,0 +1,499 @@
+// Wide-alphabet decode kernels (E5M2, BF16) for gfx950, wave64: Algorithm 1 of
+// the paper for exponent fields of 5 and 8 bits, organised like the ECF8 decoder
+// (ecf8_decode.hip): one wavefront per chunk of 64 lanes x N symbols, the lanes'
+// start bits from a prefix scan over the recorded lane lengths, the chunk's span
+// of the stream staged in LDS, two independent runs per lane (one read forward,
+// one backward), finished 16-byte pieces held in registers and stored in one
+// burst, persistent workgroups over contiguous chunk ranges with an LDS ticket
+// counter among their waves.  What differs:
+//  * the lookup table has 2^12 16-bit entries and resolves ONE codeword per
+//    lookup (with up to 256 symbols a pair table would not fit LDS); an entry is
+//    the exponent field already shifted to its place in the output element, plus
+//    the codeword's length.  One 32-bit window serves two lookups;
+//  * under the encoder's default cap of 12 bits every codeword is a table hit
+//    (FAST kernels: straight-line code); longer codes (cap 13..16) fall to a
+//    canonical first-code comparison per length, in a rarely taken branch;
+//  * the remaining bits come from planes laid out so that whole output words are
+//    merged with a few bit selects (BF16: a byte per element in the order
+//    0 2 1 3; E5M2: mantissas sliced by output word, signs as a bit mask).
+#include "ecfw.h"
+
+#include "ecf8_device.h"
+
+namespace {
+
+constexpr int WTB = ECFW_TABLE_BITS;
+constexpr uint32_t WMASK2 = ((1u << WTB) - 1) << 1;   // byte offset mask of a 16-bit entry
+
+struct WArgs {
+    uint64_t d_blob, d_out;
+    uint64_t n_elem, n_chunks, st_bytes;
+    uint64_t off_len, off_cb, off_lb, off_st, off_pl, off_sg;
+    uint32_t group;
+};
+
+template <int FMT> struct Fmt;
+template <> struct Fmt<ECFW_FMT_E5M2> {
+    static constexpr int P = 16, ELEM = 1, A = 32;
+    static constexpr int SYM_SHIFT = 2, LEN_SHIFT = 8;     // entry = exponent << 2 | length << 8
+};
+template <> struct Fmt<ECFW_FMT_BF16> {
+    static constexpr int P = 8, ELEM = 2, A = 256;
+    static constexpr int SYM_SHIFT = 7, LEN_SHIFT = 0;     // entry = exponent << 7 | length
+};
+
+template <int FMT, int N, int WAVES>
+struct WCfg {
+    using F = Fmt<FMT>;
+    static constexpr int PIECES = N / F::P;                 // 16-byte pieces per lane
+    static constexpr int STAGE = 64 * N + 64;               // span of a chunk whose codewords average 8 bits: anything
+                                                            // up to uniformly random exponent fields fits
+    static constexpr int SEGS = (STAGE / 16 + 63) / 64;
+    static constexpr int OFF_TBL = 0;
+    static constexpr int OFF_LEN = OFF_TBL + (2 << WTB);    // code_len[256]
+    static constexpr int OFF_SORTED = OFF_LEN + 256;        // symbols ordered by (length, symbol)
+    static constexpr int OFF_CNT = OFF_SORTED + 256;        // per length 0..16: count, first code, offset into sorted
+    static constexpr int OFF_FIRST = OFF_CNT + 80;
+    static constexpr int OFF_OFFS = OFF_FIRST + 80;
+    static constexpr int OFF_TICKET = OFF_OFFS + 80;
+    static constexpr int OFF_STAGE = OFF_TICKET + 16;
+    static constexpr int TOTAL = OFF_STAGE + WAVES * STAGE;
+    static_assert(STAGE % 16 == 0 && OFF_STAGE % 16 == 0, "16-byte LDS stores");
+    static_assert(PIECES % 2 == 0, "two runs of whole pieces");
+    static_assert(TOTAL <= 160 * 1024, "LDS of one gfx950 CU");
+};
+
+struct CodeArrays {
+    const uint16_t *tbl;
+    const uint8_t *sorted;
+    const uint32_t *cnt, *first, *offs;
+};
+
+// Sets up, from the code lengths in the blob: the per-length canonical arrays and
+// the lookup table.  All threads of the workgroup call it.
+template <int FMT>
+__device__ void build_code(const GLOBAL uint8_t *code_len, uint8_t *smem_len, uint8_t *sorted, uint32_t *cnt,
+                           uint32_t *first, uint32_t *offs, uint16_t *tbl, int tid, int nthreads)
+{
+    using F = Fmt<FMT>;
+    for (int s = tid; s < 256; s += nthreads) smem_len[s] = s < F::A ? code_len[s] : 0;
+    if (tid < 20) cnt[tid] = 0;
+    __syncthreads();
+    for (int s = tid; s < F::A; s += nthreads) {
+        const uint32_t l = smem_len[s];
+        if (l && l <= ECFW_MAX_CODE_LEN) atomicAdd(&cnt[l], 1u);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t code = 0, off = 0;
+        first[0] = 0;
+        offs[0] = 0;
+        cnt[0] = 0;
+        for (int l = 1; l <= (int)ECFW_MAX_CODE_LEN; l++) {
+            code = (code + cnt[l - 1]) << 1;
+            first[l] = code;
+            offs[l] = off;
+            off += cnt[l];
+        }
+    }
+    __syncthreads();
+    for (int s = tid; s < F::A; s += nthreads) {
+        const uint32_t l = smem_len[s];
+        if (!l || l > ECFW_MAX_CODE_LEN) continue;
+        uint32_t rank = 0;
+        const uint32_t *len4 = (const uint32_t *)smem_len;
+        for (int w = 0; w * 4 < s; w++) {                   // symbols below s with the same length
+            const uint32_t v = len4[w];
+#pragma unroll
+            for (int b = 0; b < 4; b++) rank += (((v >> (8 * b)) & 255u) == l) && (4 * w + b < s);
+        }
+        sorted[offs[l] + rank] = (uint8_t)s;
+    }
+    __syncthreads();
+    // entry i: the codeword spelled by the bits of i, bit 0 first
+    for (int i = tid; i < (1 << WTB); i += nthreads) {
+        const uint32_t r = __brev((uint32_t)i);
+        uint32_t e = 0;
+        for (int l = 1; l <= WTB; l++) {
+            const uint32_t d = (r >> (32 - l)) - first[l];
+            if (d < cnt[l]) {
+                e = ((uint32_t)sorted[offs[l] + d] << F::SYM_SHIFT) | ((uint32_t)l << F::LEN_SHIFT);
+                break;
+            }
+        }
+        tbl[i] = (uint16_t)e;
+    }
+    __syncthreads();
+}
+
+template <int FMT>
+__device__ __forceinline__ uint32_t entry_len(uint32_t e)
+{
+    return (e >> Fmt<FMT>::LEN_SHIFT) & 31u;
+}
+
+// A codeword longer than the table index: compare the next bits with the first
+// code of every longer length.  `bits`: >= 16 valid stream bits, next bit = bit 0.
+template <int FMT>
+__device__ __noinline__ uint32_t long_code(uint32_t bits, const uint8_t *sorted, const uint32_t *cnt,
+                                           const uint32_t *first, const uint32_t *offs)
+{
+    using F = Fmt<FMT>;
+    const uint32_t r = __brev(bits);
+    uint32_t e = (uint32_t)ECFW_MAX_CODE_LEN << F::LEN_SHIFT;     // no match (corrupt stream): skip 16 bits
+#pragma unroll 1
+    for (int l = WTB + 1; l <= (int)ECFW_MAX_CODE_LEN; l++) {
+        const uint32_t d = (r >> (32 - l)) - first[l];
+        if (d < cnt[l]) e = ((uint32_t)sorted[offs[l] + d] << F::SYM_SHIFT) | ((uint32_t)l << F::LEN_SHIFT);
+    }
+    return e;
+}
+
+template <int FMT, bool FAST>
+__device__ __forceinline__ uint32_t decode_entry(uint32_t bits, const CodeArrays &ca)
+{
+    uint32_t e = ca.tbl[bits & ((1u << WTB) - 1)];
+    if (!FAST && __builtin_expect(e == 0, 0)) e = long_code<FMT>(bits, ca.sorted, ca.cnt, ca.first, ca.offs);
+    return e;
+}
+
+// Two codewords of each run.  pa = (next bit of the forward run) - 1 and
+// pb = (one past the next bit of the backward run) - 31 as absolute LDS bit
+// addresses: the windows read there are the stream bits shifted left by one,
+// which masked is the byte offset of a table entry.
+template <int FMT, bool FAST>
+__device__ __forceinline__ void pair_step(const uint8_t *smem, const CodeArrays &ca, uint32_t &pa, uint32_t &pb,
+                                          uint32_t &eA0, uint32_t &eA1, uint32_t &eB0, uint32_t &eB1)
+{
+    const uint8_t *tb = (const uint8_t *)ca.tbl;
+    const uint32_t aA = (pa >> 3) & ~3u, aB = (pb >> 3) & ~3u;
+    const uint32_t wA = __builtin_amdgcn_alignbit(*(const uint32_t *)(smem + aA + 4), *(const uint32_t *)(smem + aA), pa);
+    const uint32_t wB = __brev(__builtin_amdgcn_alignbit(*(const uint32_t *)(smem + aB + 4), *(const uint32_t *)(smem + aB), pb));
+    eA0 = *(const uint16_t *)(tb + (wA & WMASK2));
+    eB0 = *(const uint16_t *)(tb + (wB & WMASK2));
+    uint32_t lA0 = entry_len<FMT>(eA0), lB0 = entry_len<FMT>(eB0);
+    eA1 = *(const uint16_t *)(tb + ((wA >> lA0) & WMASK2));      // 31 - 12 >= 12 bits left
+    eB1 = *(const uint16_t *)(tb + ((wB >> lB0) & WMASK2));
+    uint32_t lA1 = entry_len<FMT>(eA1), lB1 = entry_len<FMT>(eB1);
+    // a miss leaves the length 0, so the second lookup repeats the first: testing the second covers both
+    if (!FAST && __builtin_expect(eA1 == 0 || eB1 == 0, 0)) {
+        if (eA1 == 0) {
+            if (eA0 == 0) { eA0 = long_code<FMT>(wA >> 1, ca.sorted, ca.cnt, ca.first, ca.offs); lA0 = entry_len<FMT>(eA0); }
+            eA1 = decode_entry<FMT, false>(lds_window<+1>(smem, pa + 1 + lA0), ca);
+            lA1 = entry_len<FMT>(eA1);
+        }
+        if (eB1 == 0) {
+            if (eB0 == 0) { eB0 = long_code<FMT>(wB >> 1, ca.sorted, ca.cnt, ca.first, ca.offs); lB0 = entry_len<FMT>(eB0); }
+            eB1 = decode_entry<FMT, false>(lds_window<-1>(smem, pb + 31 - lB0), ca);
+            lB1 = entry_len<FMT>(eB1);
+        }
+    }
+    pa += lA0 + lA1;
+    pb -= lB0 + lB1;
+}
+
+__device__ __forceinline__ uint32_t bit_sel(uint32_t mask, uint32_t a, uint32_t b)   // (a & mask) | (b & ~mask)
+{
+    return __builtin_amdgcn_bitop3_b32(a, b, mask, 0xE4);
+}
+
+// One 16-byte piece from its table entries and plane words.
+// BF16: e[0..7]; pl.x / pl.y hold the remainder bytes of elements 0 2 1 3 / 4 6 5 7.
+__device__ __forceinline__ u32x4 merge_bf16(const uint32_t e[8], u32x2 pl)
+{
+    u32x4 d;
+    const uint32_t x0 = __builtin_amdgcn_perm(e[1], e[0], 0x05040100u), x1 = __builtin_amdgcn_perm(e[3], e[2], 0x05040100u);
+    const uint32_t x2 = __builtin_amdgcn_perm(e[5], e[4], 0x05040100u), x3 = __builtin_amdgcn_perm(e[7], e[6], 0x05040100u);
+    // per 16-bit half: bit 15 sign, bits 14..7 exponent (from the entry), bits 6..0 mantissa
+    d.x = bit_sel(0x7f807f80u, x0, bit_sel(0x80008000u, pl.x << 8, pl.x));
+    d.y = bit_sel(0x7f807f80u, x1, bit_sel(0x80008000u, pl.x, pl.x >> 8));
+    d.z = bit_sel(0x7f807f80u, x2, bit_sel(0x80008000u, pl.y << 8, pl.y));
+    d.w = bit_sel(0x7f807f80u, x3, bit_sel(0x80008000u, pl.y, pl.y >> 8));
+    return d;
+}
+
+// E5M2: e[0..15]; mant = the piece's mantissa word, sign = its 16 sign bits.
+__device__ __forceinline__ u32x4 merge_e5m2(const uint32_t e[16], uint32_t mant, uint32_t sign)
+{
+    uint32_t out[4];
+#pragma unroll
+    for (int d = 0; d < 4; d++) {
+        const uint32_t lo = __builtin_amdgcn_perm(e[4 * d + 1], e[4 * d], 0x0c0c0400u);       // bytes 0, 1
+        const uint32_t hi = __builtin_amdgcn_perm(e[4 * d + 3], e[4 * d + 2], 0x04000c0cu);   // bytes 2, 3
+        // four sign bits -> bit 0 of each byte (the partial products do not overlap), then up to bit 7
+        const uint32_t s4 = __builtin_amdgcn_ubfe(sign, 4 * d, 4);
+        const uint32_t sp = __umul24(s4, 0x204081u) << 7;
+        out[d] = bit_sel(0x7c7c7c7cu, lo | hi, bit_sel(0x80808080u, sp, mant >> (2 * d)));
+    }
+    return u32x4{out[0], out[1], out[2], out[3]};
+}
+
+template <int FMT, int N, int WAVES, bool FAST>
+__global__ __launch_bounds__(WAVES * 64) void ecfw_decode_kernel(WArgs a)
+{
+    using C = WCfg<FMT, N, WAVES>;
+    using F = Fmt<FMT>;
+    constexpr int PIECES = C::PIECES, SEGS = C::SEGS, STAGE = C::STAGE, P = F::P;
+    __shared__ __attribute__((aligned(16))) uint8_t smem[C::TOTAL];
+    uint16_t *tbl = (uint16_t *)(smem + C::OFF_TBL);
+    uint32_t *s_ticket = (uint32_t *)(smem + C::OFF_TICKET);
+    const CodeArrays ca{tbl, smem + C::OFF_SORTED, (const uint32_t *)(smem + C::OFF_CNT),
+                        (const uint32_t *)(smem + C::OFF_FIRST), (const uint32_t *)(smem + C::OFF_OFFS)};
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t stage_off = C::OFF_STAGE + wave * STAGE;
+    uint8_t *stage = smem + stage_off;
+
+    const GLOBAL uint8_t *blob = (const GLOBAL uint8_t *)a.d_blob;
+    const GLOBAL uint64_t *chunk_bit = (const GLOBAL uint64_t *)(blob + a.off_cb);
+    const GLOBAL uint16_t *lane_bits = (const GLOBAL uint16_t *)(blob + a.off_lb);
+    const GLOBAL uint8_t *stream = blob + a.off_st;
+    const GLOBAL uint8_t *plane = blob + a.off_pl;
+    const GLOBAL uint8_t *signs = blob + a.off_sg;
+    GLOBAL uint8_t *out = (GLOBAL uint8_t *)a.d_out;
+
+    // contiguous range of chunks for this workgroup, cut at multiples of 64 chunks when there is
+    // enough work so that the waves of a workgroup share the interleaved groups of the layout
+    const uint64_t NWG = gridDim.x, wg = blockIdx.x;
+    const uint64_t unit = a.n_chunks >= NWG * 128 ? 64 : 1;
+    const uint64_t units = (a.n_chunks + unit - 1) / unit;
+    const uint64_t c_begin = units * wg / NWG * unit;
+    uint64_t c_end = units * (wg + 1) / NWG * unit;
+    if (c_end > a.n_chunks) c_end = a.n_chunks;
+    if (c_begin >= c_end) return;     // uniform for the workgroup
+
+    if (tid == 0) *s_ticket = 0;
+    build_code<FMT>(blob + a.off_len, smem + C::OFF_LEN, smem + C::OFF_SORTED, (uint32_t *)(smem + C::OFF_CNT),
+                    (uint32_t *)(smem + C::OFF_FIRST), (uint32_t *)(smem + C::OFF_OFFS), tbl, tid, WAVES * 64);
+
+    const uint64_t E = 64ull * N;
+    const uint64_t whole = a.n_elem / (a.group * E) * a.group;     // chunks inside complete groups
+    auto chunk_base = [&](uint64_t c) -> uint64_t {
+        return c < whole ? (c - c % a.group) * E + (c % a.group) * (64 * P) : c * E;
+    };
+    auto chunk_stride = [&](uint64_t c) -> uint64_t { return c < whole ? (uint64_t)a.group * (64 * P) : 64ull * P; };
+
+    struct Meta { uint64_t b0, b1; uint32_t lb; };
+    struct Payload {
+        u32x4 seg[SEGS];
+        u32x2 pl[FMT == ECFW_FMT_BF16 ? PIECES : 1];
+        uint32_t mant[FMT == ECFW_FMT_E5M2 ? PIECES : 1];
+        uint32_t sign[FMT == ECFW_FMT_E5M2 ? PIECES : 1];
+    };
+    auto draw = [&]() -> uint64_t {
+        uint32_t t = 0;
+        if (lane == 0) t = atomicAdd(s_ticket, 1u);
+        return c_begin + __builtin_amdgcn_readfirstlane(t);
+    };
+    auto load_meta = [&](uint64_t c) {
+        Meta m;
+        m.b0 = chunk_bit[c];
+        m.b1 = chunk_bit[c + 1];
+        m.lb = lane_bits[c * 64 + lane];
+        return m;
+    };
+    auto span_of = [&](const Meta &m, uint64_t &byte0) -> uint64_t {
+        uint64_t byte_end = ((m.b1 + 7) >> 3) + 8;
+        if (byte_end > a.st_bytes) byte_end = a.st_bytes;
+        byte0 = (m.b0 >> 3) & ~15ull;
+        if (byte0 > byte_end) byte0 = byte_end;
+        return byte_end - byte0;
+    };
+    auto load_payload = [&](uint64_t c, const Meta &m, Payload &p) {
+        uint64_t byte0;
+        const uint64_t span = span_of(m, byte0);
+        const uint64_t e0 = chunk_base(c) + (uint64_t)lane * P, stride = chunk_stride(c);
+#pragma unroll
+        for (int q = 0; q < PIECES; q++) {
+            const uint64_t e = e0 + q * stride;
+            if (FMT == ECFW_FMT_BF16) {
+                p.pl[q] = __builtin_nontemporal_load((const GLOBAL u32x2 *)(plane + e));
+            } else {
+                p.mant[q] = __builtin_nontemporal_load((const GLOBAL uint32_t *)(plane + e / 4));
+                p.sign[q] = __builtin_nontemporal_load((const GLOBAL uint16_t *)(signs + e / 8));
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < SEGS; k++) {
+            const uint32_t i = (lane + 64 * k) * 16;
+            p.seg[k] = u32x4{0, 0, 0, 0};
+            if (i < (uint32_t)STAGE && i < span)
+                p.seg[k] = __builtin_nontemporal_load((const GLOBAL u32x4 *)(stream + byte0 + i));
+        }
+    };
+
+    // The careful way, one symbol at a time with windows straight from HBM: the ragged last
+    // chunk, and chunks whose span does not fit the stage (codewords averaging over 8 bits).
+    auto symbol_pass = [&](uint64_t c, const Meta &m) {
+        const uint32_t rel = wave_incl_scan(m.lb) - m.lb;
+        const uint64_t limit = a.st_bytes * 8 - 64;
+        uint64_t posA = m.b0 + rel, posB = posA + m.lb;
+        const uint64_t e0 = chunk_base(c) + (uint64_t)lane * P, stride = chunk_stride(c);
+#pragma unroll 1
+        for (int k = 0; k < N; k++) {
+            const uint64_t e = e0 + (uint64_t)(k / P) * stride + (uint32_t)(k % P);
+            if (e >= a.n_elem) continue;
+            uint32_t en;
+            if (k < N / 2) {
+                if (posA > limit) posA = limit;
+                en = decode_entry<FMT, false>(global_window<+1>(stream, posA), ca);
+                posA += entry_len<FMT>(en);
+            } else {
+                if (posB > limit) posB = limit;
+                en = decode_entry<FMT, false>(global_window<-1>(stream, posB), ca);
+                const uint32_t l = entry_len<FMT>(en);
+                posB = posB >= l ? posB - l : 0;
+            }
+            if (FMT == ECFW_FMT_BF16) {
+                const uint32_t swap = (0x3120u >> (4 * (uint32_t)(e & 3))) & 3u;      // 0 2 1 3
+                const uint32_t r = plane[(e & ~3ull) + swap];
+                ((GLOBAL uint16_t *)out)[e] = (uint16_t)(((r & 0x80u) << 8) | (en & 0x7f80u) | (r & 0x7fu));
+            } else {
+                const uint32_t j = (uint32_t)(e & 3), d = (uint32_t)(e >> 2) & 3;
+                const uint32_t mw = ((const GLOBAL uint32_t *)plane)[e / 16];
+                const uint32_t sw = ((const GLOBAL uint16_t *)signs)[e / 16];
+                out[e] = (uint8_t)((((sw >> (e & 15)) & 1u) << 7) | (en & 0x7cu) | ((mw >> (8 * j + 2 * d)) & 3u));
+            }
+        }
+    };
+
+    uint64_t cur = draw();
+    Meta m_cur{0, 0, 0}, m_next{0, 0, 0};
+    Payload p_cur;
+    if (cur < c_end) {
+        m_cur = load_meta(cur);
+        load_payload(cur, m_cur, p_cur);
+    }
+    uint64_t nxt = draw();
+    if (nxt < c_end) m_next = load_meta(nxt);
+
+    while (cur < c_end) {
+        const Meta m = m_cur;
+        uint64_t byte0;
+        const uint64_t span = span_of(m, byte0);
+        const bool careful = span > (uint64_t)STAGE || (cur + 1) * E > a.n_elem;    // uniform
+        if (!careful) {
+#pragma unroll
+            for (int k = 0; k < SEGS; k++) {
+                const uint32_t j = (lane + 64 * k) * 16;
+                if (j < (uint32_t)STAGE) *(u32x4 *)(stage + j) = p_cur.seg[k];
+            }
+        }
+        u32x2 pl[FMT == ECFW_FMT_BF16 ? PIECES : 1];
+        uint32_t mant[FMT == ECFW_FMT_E5M2 ? PIECES : 1], sign[FMT == ECFW_FMT_E5M2 ? PIECES : 1];
+#pragma unroll
+        for (int q = 0; q < PIECES; q++) {
+            if (FMT == ECFW_FMT_BF16) pl[q] = p_cur.pl[q];
+            else { mant[q] = p_cur.mant[q]; sign[q] = p_cur.sign[q]; }
+        }
+        // the payload registers are free: fetch the next chunk, draw the one after and fetch its metadata
+        uint64_t nn = c_end;
+        Meta m_next2{0, 0, 0};
+        if (nxt < c_end) {
+            load_payload(nxt, m_next, p_cur);
+            nn = draw();
+            if (nn < c_end) m_next2 = load_meta(nn);
+        }
+        if (careful) {
+            symbol_pass(cur, m);
+        } else {
+            const uint32_t rel = wave_incl_scan(m.lb) - m.lb;
+            const uint64_t start = __builtin_amdgcn_readfirstlane((uint32_t)m.b0) |
+                                   ((uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)(m.b0 >> 32)) << 32);
+            uint32_t pa = stage_off * 8 + (uint32_t)(start - byte0 * 8) + rel - 1;    // one bit off, see pair_step
+            uint32_t pb = pa + m.lb - 30;
+            GLOBAL uint8_t *dst = out + (chunk_base(cur) + (uint64_t)lane * P) * F::ELEM;
+            const uint64_t stride_bytes = chunk_stride(cur) * F::ELEM;
+            // finished pieces wait in registers and leave in bursts of eight (8 KiB per wavefront)
+            constexpr int BURST = PIECES / 2 < 4 ? PIECES / 2 : 4;
+            static_assert((PIECES / 2) % BURST == 0, "whole bursts");
+#pragma unroll
+            for (int q0 = 0; q0 < PIECES / 2; q0 += BURST) {
+                u32x4 pieceA[BURST], pieceB[BURST];
+#pragma unroll
+                for (int i = 0; i < BURST; i++) {
+                    const int q = q0 + i;
+                    uint32_t eA[P], eB[P];
+#pragma unroll
+                    for (int t = 0; t < P / 2; t++)
+                        pair_step<FMT, FAST>(smem, ca, pa, pb, eA[2 * t], eA[2 * t + 1], eB[2 * t], eB[2 * t + 1]);
+                    if constexpr (FMT == ECFW_FMT_BF16) {
+                        pieceA[i] = merge_bf16(eA, pl[q]);
+                        pieceB[i] = merge_bf16(eB, pl[q + PIECES / 2]);
+                    } else {
+                        pieceA[i] = merge_e5m2(eA, mant[q], sign[q]);
+                        pieceB[i] = merge_e5m2(eB, mant[q + PIECES / 2], sign[q + PIECES / 2]);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 0; i < BURST; i++) __builtin_nontemporal_store(pieceA[i], (GLOBAL u32x4 *)(dst + (q0 + i) * stride_bytes));
+#pragma unroll
+                for (int i = 0; i < BURST; i++)
+                    __builtin_nontemporal_store(pieceB[i], (GLOBAL u32x4 *)(dst + (q0 + i + PIECES / 2) * stride_bytes));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        cur = nxt;
+        nxt = nn;
+        m_cur = m_next;
+        m_next = m_next2;
+    }
+}
+
+template <int FMT, int N, int WAVES, bool FAST>
+int launch_as(const WArgs &a, uint32_t max_workgroups, hipStream_t stream)
+{
+    int cus = device_cus();
+    if (cus <= 0) return ECF8_E_HIP;
+    uint64_t grid = (uint64_t)cus;
+    if (max_workgroups && max_workgroups < grid) grid = max_workgroups;
+    if (grid > a.n_chunks) grid = a.n_chunks;
+    hipLaunchKernelGGL((ecfw_decode_kernel<FMT, N, WAVES, FAST>), dim3((unsigned)grid), dim3(WAVES * 64), 0, stream, a);
+    return hipGetLastError() == hipSuccess ? ECF8_OK : ECF8_E_HIP;
+}
+
+template <int FMT>
+int launch_fmt(const WArgs &a, uint32_t N, bool fast, uint32_t max_workgroups, hipStream_t stream)
+{
+    if (N == 64) return fast ? launch_as<FMT, 64, 8, true>(a, max_workgroups, stream) : launch_as<FMT, 64, 8, false>(a, max_workgroups, stream);
+    return fast ? launch_as<FMT, 128, 8, true>(a, max_workgroups, stream) : launch_as<FMT, 128, 8, false>(a, max_workgroups, stream);
+}
+
+} // namespace
+
+extern "C" int ecfw_decode(const void *d_blob, const ecfw_header *h, void *d_out, uint64_t out_capacity,
+                           uint32_t max_workgroups, void *stream)
+{
+    if (!d_blob || !h || !d_out) return ECF8_E_ARG;
+    if (h->magic != ECFW_MAGIC || h->version != ECFW_VERSION) return ECF8_E_FORMAT;
+    if (h->fmt != ECFW_FMT_E5M2 && h->fmt != ECFW_FMT_BF16) return ECF8_E_FORMAT;
+    if (h->lane_syms != 64 && h->lane_syms != 128) return ECF8_E_FORMAT;
+    const uint32_t g = h->group_chunks;
+    if (g < 1 || g > 64 || (g & (g - 1))) return ECF8_E_FORMAT;
+    if (h->n_elem == 0 || h->n_chunks != (h->n_elem + 64ull * h->lane_syms - 1) / (64ull * h->lane_syms)) return ECF8_E_FORMAT;
+    if (h->max_code_len < 1 || h->max_code_len > ECFW_MAX_CODE_LEN || h->stream_bytes < 16 || h->stream_bytes % 16)
+        return ECF8_E_FORMAT;
+    const uint64_t elem = h->fmt == ECFW_FMT_BF16 ? 2 : 1;
+    if (out_capacity / elem < h->n_elem) return ECF8_E_CAPACITY;
+    if (((uintptr_t)d_blob & 255) || ((uintptr_t)d_out & 15)) return ECF8_E_ALIGN;
+    if ((h->off_code_len | h->off_chunk_bit | h->off_lane_bits | h->off_stream | h->off_plane | h->off_sign) & 255)
+        return ECF8_E_FORMAT;
+    WArgs a;
+    a.d_blob = (uint64_t)(uintptr_t)d_blob;
+    a.d_out = (uint64_t)(uintptr_t)d_out;
+    a.n_elem = h->n_elem;
+    a.n_chunks = h->n_chunks;
+    a.st_bytes = h->stream_bytes;
+    a.off_len = h->off_code_len;
+    a.off_cb = h->off_chunk_bit;
+    a.off_lb = h->off_lane_bits;
+    a.off_st = h->off_stream;
+    a.off_pl = h->off_plane;
+    a.off_sg = h->off_sign;
+    a.group = g;
+    const bool fast = h->max_code_len <= ECFW_TABLE_BITS;
+    hipStream_t s = (hipStream_t)stream;
+    return h->fmt == ECFW_FMT_BF16 ? launch_fmt<ECFW_FMT_BF16>(a, h->lane_syms, fast, max_workgroups, s)
+                                   : launch_fmt<ECFW_FMT_E5M2>(a, h->lane_syms, fast, max_workgroups, s);
+}

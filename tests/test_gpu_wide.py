@@ -1,0 +1,178 @@
+"""Parity of the wide-alphabet HIP decode path (E5M2, BF16) with the CPU oracle, through the C ABI.
+
+Every case encodes seeded synthetic elements with the library's host encoder, decodes on
+the GPU into the middle of a poisoned buffer, and compares element by element, bit-exact,
+with what the oracle's independent bit-serial reader makes of the same container (which the
+CPU tests show to be the container the oracle itself writes) and with the input.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2510_02676_amd import ecf8, ecfw, synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+E5M2, BF16 = ecfw.FMT_E5M2, ecfw.FMT_BF16
+
+
+def _rand_elems(fmt, n, seed, spread=3.0):
+    rng = np.random.default_rng(seed)
+    if fmt == BF16:
+        e = np.clip(np.rint(rng.normal(120, spread, n)), 0, 255).astype(np.uint16)
+        return ((rng.integers(0, 2, n).astype(np.uint16) << 15) | (e << 7) | rng.integers(0, 128, n).astype(np.uint16))
+    e = np.clip(np.rint(rng.normal(14, spread, n)), 0, 31).astype(np.uint8)
+    return ((rng.integers(0, 2, n).astype(np.uint8) << 7) | (e << 2) | rng.integers(0, 4, n).astype(np.uint8))
+
+
+def _gpu_decode_guarded(blob, pad=4096, max_workgroups=0):
+    """Decode into the middle of a poisoned buffer; returns (elements, guards_intact)."""
+    hdr = blob.header
+    eb = ecfw.ELEM_BYTES[hdr.fmt]
+    d_blob = blob.to(DEV)
+    nb = hdr.n_elem * eb
+    buf = torch.full((pad + nb + pad,), 0xA5, dtype=torch.uint8, device=DEV)
+    out = buf[pad:pad + nb]
+    ecfw.ecfw_decode(d_blob, hdr, out, max_workgroups=max_workgroups)
+    torch.cuda.synchronize()
+    host = buf.cpu().numpy()
+    ok = bool((host[:pad] == 0xA5).all() and (host[pad + nb:] == 0xA5).all())
+    got = host[pad:pad + nb]
+    return (got.view(np.uint16) if eb == 2 else got), ok
+
+
+def _check(orc, fmt, x, rows=None, cols=None, max_workgroups=0, **opts):
+    x = np.ascontiguousarray(x).reshape(-1)
+    rows, cols = (1, x.size) if rows is None else (rows, cols)
+    blob = ecfw.ecfw_encode(fmt, x, rows, cols, **opts)
+    print("fmt", fmt, "n", x.size, opts, "max_len", blob.header.max_code_len, flush=True)
+    got, guards = _gpu_decode_guarded(blob, max_workgroups=max_workgroups)
+    assert guards
+    dec, _ = orc.w_container_decode(blob.numpy())
+    assert np.array_equal(got, dec)
+    assert np.array_equal(got, x)
+    return blob
+
+
+@pytest.mark.parametrize("max_code_len", [0, 16])
+@pytest.mark.parametrize("lane_syms", [64, 128])
+@pytest.mark.parametrize("fmt", [E5M2, BF16])
+def test_synthetic_matrix_parity(orc, fmt, lane_syms, max_code_len):
+    """1024x1024 alpha-stable weights (alpha 1.8, scale 0.02, seed 0) in both formats, with the default
+    cap of 12 bits (branch-free kernels) and with Section 3.1's cap of 16 (long-code branch in use)."""
+    make = synth.make_bf16 if fmt == BF16 else synth.make_e5m2
+    x = make(1024, 1024, 1.8, 0.02, 0).numpy()
+    blob = _check(orc, fmt, x, 1024, 1024, lane_syms=lane_syms, max_code_len=max_code_len)
+    assert (blob.header.max_code_len <= 12) == (max_code_len == 0)
+
+
+@pytest.mark.parametrize("fmt", [E5M2, BF16])
+@pytest.mark.parametrize("n", [1, 2, 15, 16, 17, 511, 4095, 4096, 4097, 8191, 8193, 64 * 128 * 3 + 1, 64 * 64 * 33 - 1, 300007])
+def test_ragged_sizes(orc, fmt, n):
+    _check(orc, fmt, _rand_elems(fmt, n, n))
+
+
+@pytest.mark.parametrize("fmt", [E5M2, BF16])
+@pytest.mark.parametrize("lane_syms,group,n_chunks,extra", [(64, 1, 40, 0), (64, 2, 41, 5), (128, 4, 22, 100), (64, 32, 100, 1),
+                                                            (128, 64, 130, 4000), (64, 16, 16, 0)])
+def test_grouped_layouts(orc, fmt, lane_syms, group, n_chunks, extra):
+    n = 64 * lane_syms * n_chunks + extra
+    _check(orc, fmt, _rand_elems(fmt, n, n + group), lane_syms=lane_syms, group_chunks=group)
+
+
+@pytest.mark.parametrize("fmt", [E5M2, BF16])
+def test_every_bit_pattern(orc, fmt):
+    """Zeros, subnormals, infinities and NaN payloads come back as they went in."""
+    x = np.arange(256, dtype=np.uint8) if fmt == E5M2 else np.arange(65536, dtype=np.uint16)
+    x = np.tile(x, 5)
+    _check(orc, fmt, x, max_code_len=16)
+    _check(orc, fmt, np.random.default_rng(0).permutation(x), lane_syms=128, group_chunks=2)
+
+
+@pytest.mark.parametrize("cap", [5, 8, 12, 13, 16])
+@pytest.mark.parametrize("fmt", [E5M2, BF16])
+def test_caps(orc, fmt, cap):
+    x = _rand_elems(fmt, 500000, cap, spread=2.0)
+    blob = _check(orc, fmt, x, max_code_len=cap)
+    assert blob.header.max_code_len <= cap
+
+
+def test_long_codes_everywhere(orc):
+    """BF16 with all 256 exponent fields in use and geometric frequencies: under the cap of 16 most
+    fields have codewords of 13..16 bits, so the long-code branch runs in most decode steps."""
+    rng = np.random.default_rng(7)
+    p = 0.93 ** np.arange(256)
+    e = rng.choice(256, size=700000, p=p / p.sum()).astype(np.uint16)
+    e[:256] = np.arange(256)
+    x = ((rng.integers(0, 2, e.size).astype(np.uint16) << 15) | (e << 7) | rng.integers(0, 128, e.size).astype(np.uint16))
+    blob = _check(orc, BF16, x, max_code_len=16, group_chunks=1)
+    assert blob.header.max_code_len == 16
+    _check(orc, BF16, x, max_code_len=16, lane_syms=128, group_chunks=4)
+
+
+@pytest.mark.parametrize("lane_syms", [64, 128])
+def test_islands_of_long_codes(orc, lane_syms):
+    """A few chunks made only of rare exponent fields (16-bit codewords): their span exceeds what a
+    wavefront stages in LDS, so they are decoded the careful way, one symbol at a time."""
+    rng = np.random.default_rng(11)
+    n = 64 * lane_syms * 300
+    e = np.clip(np.rint(rng.normal(120, 1.0, n)), 0, 255).astype(np.uint16)
+    rare = np.setdiff1d(np.arange(256), np.arange(110, 131))
+    for c in (3, 150, 151, 299):
+        e[c * 64 * lane_syms:(c + 1) * 64 * lane_syms] = rng.choice(rare, 64 * lane_syms)
+    x = ((rng.integers(0, 2, n).astype(np.uint16) << 15) | (e << 7) | rng.integers(0, 128, n).astype(np.uint16))
+    blob = _check(orc, BF16, x, max_code_len=16, lane_syms=lane_syms, group_chunks=1)
+    h, arr = blob.header, blob.numpy()
+    cb = np.frombuffer(arr[h.off_chunk_bit:h.off_chunk_bit + 8 * (h.n_chunks + 1)].tobytes(), "<u8")
+    assert (np.diff(cb.astype(np.int64)) // 8 > 64 * lane_syms * 12 // 8 + 64).sum() == 4     # the islands are oversize
+
+
+@pytest.mark.parametrize("fmt", [E5M2, BF16])
+def test_few_workgroups_and_caller_buffer(orc, fmt):
+    x = _rand_elems(fmt, 64 * 128 * 50 + 9, 3)
+    for wgs in (1, 3, 1000):
+        _check(orc, fmt, x, max_workgroups=wgs)
+
+
+def test_argument_errors():
+    x = _rand_elems(BF16, 10000, 1)
+    blob = ecfw.ecfw_encode(BF16, x)
+    d_blob = blob.to(DEV)
+    small = torch.empty(10000 * 2 - 2, dtype=torch.uint8, device=DEV)
+    with pytest.raises(ecf8.Ecf8Error) as e:
+        ecfw.ecfw_decode(d_blob, blob.header, small)
+    assert e.value.code == ecf8.E_CAPACITY
+    big = torch.empty(10000 * 2 + 64, dtype=torch.uint8, device=DEV)
+    with pytest.raises(ecf8.Ecf8Error) as e:
+        ecfw.ecfw_decode(d_blob, blob.header, big[2:])
+    assert e.value.code == ecf8.E_ALIGN
+    bad = ecfw.WHeader.from_buffer_copy(bytes(blob.header))
+    bad.fmt = 7
+    with pytest.raises(ecf8.Ecf8Error) as e:
+        ecfw.ecfw_decode(d_blob, bad, big)
+    assert e.value.code == ecf8.E_FORMAT
+    with pytest.raises(ecf8.Ecf8Error):
+        ecfw.ecfw_decode(blob.to("cpu"), blob.header, big)
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("fmt", [E5M2, BF16])
+def test_full_size_matrix(orc, fmt):
+    """The largest matrix of the 8B-class stack (14336 x 4096) in the launch configuration the bench
+    times; the whole output against the input, and sampled chunks against the oracle's reader run on a
+    container re-encoded from those chunks' elements alone."""
+    make = synth.make_bf16 if fmt == BF16 else synth.make_e5m2
+    x = make(14336, 4096, 1.8, 0.02, 0, tensor_id=5).numpy().reshape(-1)
+    blob = ecfw.ecfw_encode(fmt, x, 14336, 4096)
+    got, guards = _gpu_decode_guarded(blob)
+    assert guards and np.array_equal(got, x)
+    ecfw.blob_validate(blob.numpy())
+    h = blob.header
+    freq = orc.w_histogram(fmt, x)
+    assert h.stream_bits == orc.w_lengths_limited(freq, 12)[1]
+    E = 64 * h.lane_syms * h.group_chunks                        # one interleaved group of chunks
+    for g in (0, 1, h.n_elem // E // 2, h.n_elem // E - 1):
+        part = x[g * E:(g + 1) * E]
+        want = orc.w_container_encode(fmt, part, 1, part.size, h.lane_syms, h.group_chunks, blob.code_len())
+        dec, _ = orc.w_container_decode(want)
+        assert np.array_equal(got[g * E:(g + 1) * E], dec)
