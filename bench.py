@@ -103,18 +103,19 @@ def cpu_baseline(batches, budget_syms=440_000_000):
                 len(names), names[0], names[-1], tot_syms, tot_t)}
 
 
-def profiled_traffic(workload, launch, hdrs, layers_full):
+def profiled_traffic(workload, launch, hdrs, layers_full, kernel="ecf8_decode_kernel"):
     """HBM bytes per launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary of this
     exact workload, or None when no summary covers it."""
     if not layers_full:
         return None
-    path = os.path.join(ROOT, "profiles", "ecf8_decode_kernel_%s_%s.txt" % (workload, launch))
+    path = os.path.join(ROOT, "profiles", "%s_%s_%s.txt" % (kernel, workload, launch))
     try:
         text = open(path).read()
     except OSError:
         return None
     key = "workload=%s launch=%s lane_syms=%d group_chunks=%d max_code_len=%d" % (
-        workload, launch, hdrs[0].lane_syms, hdrs[0].group_chunks, max(max(h.code_len) for h in hdrs))
+        workload, launch, hdrs[0].lane_syms, hdrs[0].group_chunks,
+        max(h.max_code_len if hasattr(h, "max_code_len") else max(h.code_len) for h in hdrs))
     if key not in text:
         return None
     for line in text.splitlines():
@@ -363,6 +364,88 @@ def bench_encode(a):
         "identical_to_cpu_encoder": True, "cpu_encoder_GBps": round(n_total / t_cpu_total / 1e9, 3), "tensors": rows}))
 
 
+def bench_wide(a):
+    """Workloads "wide_bf16" / "wide_e5m2": the wide-alphabet decoder (ecfw_decode) on eight MLP-sized
+    matrices (14336 x 4096) of the 8B-class stack in BF16 or E5M2, one launch per matrix."""
+    from paper_2510_02676_amd import ecfw, synth
+    import oracle
+    dev = "cuda:0"
+    fmt = ecfw.FMT_BF16 if a.workload == "wide_bf16" else ecfw.FMT_E5M2
+    make = synth.make_bf16 if fmt == ecfw.FMT_BF16 else synth.make_e5m2
+    eb = ecfw.ELEM_BYTES[fmt]
+    n_mats = a.layers or 8
+    t0 = time.time()
+    mats = []
+    for i in range(n_mats):
+        alpha, scale = synth._drawn(a.seed, 600000 + i)
+        w = make(14336, 4096, alpha, scale, a.seed, tensor_id=600000 + i, device=dev)
+        blob = ecfw.ecfw_encode(fmt, w.cpu(), 14336, 4096, lane_syms=a.lane_syms, group_chunks=a.group_chunks,
+                                max_code_len=a.max_code_len)
+        h = blob.header
+        d_out = torch.empty(h.n_elem * eb, dtype=torch.uint8, device=dev)
+        mats.append(dict(w=w.view(torch.uint8).reshape(-1), hdr=h, d_blob=blob.to(dev), d_out=d_out, blob=blob if i == 0 else None))
+    t_setup = time.time() - t0
+    hdrs = [m["hdr"] for m in mats]
+    n_total = sum(h.n_elem for h in hdrs)
+    out_total = n_total * eb
+    rd_total = sum((h.stream_bits + 7) // 8 + h.plane_bytes + h.sign_bytes + 8 * (h.n_chunks + 1) + 128 * h.n_chunks +
+                   256 + 9 * h.n_alphabet for h in hdrs)
+    alg_total = rd_total + out_total
+    stream = torch.cuda.current_stream()
+
+    def step():
+        for m in mats:
+            ecfw.ecfw_decode(m["d_blob"], m["hdr"], m["d_out"], stream=stream)
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    if any(not torch.equal(m["d_out"], m["w"]) for m in mats):
+        raise SystemExit("wide decode mismatch")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(a.steps):
+        step()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    sec_per_step = wall / a.steps
+    launch_s = e0.elapsed_time(e1) * 1e-3 / (a.steps * n_mats)
+    achieved = alg_total / n_mats / launch_s / 1e9
+    name = "BF16" if fmt == ecfw.FMT_BF16 else "E5M2"
+    out = {
+        "metric": "decoded %s GB/s (exponent-coded container -> exact %s elements)" % (name, name),
+        "value": round(out_total / sec_per_step / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(sec_per_step * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u16" if eb == 2 else "u8", "data": "synthetic",
+        "config": {"workload": "%s: %d matrices 14336x4096 of the 8B-class stack as %s, one ecfw_decode launch each"
+                               % (a.workload, n_mats, name),
+                   "elements": n_total, "lane_syms": hdrs[0].lane_syms, "group_chunks": hdrs[0].group_chunks,
+                   "max_code_len": max(h.max_code_len for h in hdrs), "seed": a.seed},
+        "compression_ratio": round(sum(h.total_size for h in hdrs) / out_total, 5),
+        "avg_code_bits": round(sum(h.stream_bits for h in hdrs) / n_total, 4),
+        "total_moved_GBps": round(alg_total / sec_per_step / 1e9, 2), "bit_exact": True, "setup_s": round(t_setup, 1),
+        "roofline": {"bound": "hbm", "kernel": "ecfw_decode_kernel", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "avg_launch_us": round(launch_s * 1e6, 2),
+                     "algorithmic_bytes_per_launch": int(alg_total / n_mats),
+                     "traffic": profiled_traffic(a.workload, "tensor", hdrs, a.layers == 0, "ecfw_decode_kernel")},
+    }
+    if not a.no_cpu_baseline:
+        # the oracle's bit-serial reader on the first 2^20 elements of the first matrix, re-encoded on their own
+        # with the same code lengths
+        x = mats[0]["w"][: (1 << 20) * eb].cpu().numpy()
+        x = x.view(np.uint16) if eb == 2 else x
+        part = oracle.w_container_encode(fmt, x, 1, x.size, hdrs[0].lane_syms, hdrs[0].group_chunks, mats[0]["blob"].code_len())
+        t0 = time.perf_counter()
+        dec, _ = oracle.w_container_decode(part)
+        dt = time.perf_counter() - t0
+        assert np.array_equal(dec, x)
+        out["cpu_baseline"] = {"value": round(x.size * eb / dt / 1e9, 5), "unit": "GB/s", "cores": 1, "kind": "oracle",
+                               "sample": "oracle container reader on the first 2^20 elements of matrix 0 (%.1f s)" % dt}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -396,6 +479,8 @@ def main():
         return bench_jit(a)
     if a.workload == "encode":
         return bench_encode(a)
+    if a.workload in ("wide_bf16", "wide_e5m2"):
+        return bench_wide(a)
     layers = a.layers or {"config1": 32, "config2": 256, "config3": 40, "config0": 1}[a.workload]
     batches, desc, t_setup = build_workload(a.workload, a.seed, a.lane_syms, layers, a.launch, a.group_chunks, a.max_code_len)
     hdrs = [t["hdr"] for _, ts in batches for t in ts]

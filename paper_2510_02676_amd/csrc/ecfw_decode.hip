@@ -20,6 +20,8 @@
 
 #include "ecf8_device.h"
 
+#include <cstdlib>
+
 namespace {
 
 constexpr int WTB = ECFW_TABLE_BITS;
@@ -50,8 +52,8 @@ struct WCfg {
                                                             // up to uniformly random exponent fields fits
     static constexpr int SEGS = (STAGE / 16 + 63) / 64;
     static constexpr int OFF_TBL = 0;
-    static constexpr int OFF_LEN = OFF_TBL + (2 << WTB);    // code_len[256]
-    static constexpr int OFF_SORTED = OFF_LEN + 256;        // symbols ordered by (length, symbol)
+    static constexpr int OFF_WCNT = OFF_TBL + (2 << WTB);   // symbols per (wavefront, length) while the code is set up
+    static constexpr int OFF_SORTED = OFF_WCNT + 320;       // symbols ordered by (length, symbol)
     static constexpr int OFF_CNT = OFF_SORTED + 256;        // per length 0..16: count, first code, offset into sorted
     static constexpr int OFF_FIRST = OFF_CNT + 80;
     static constexpr int OFF_OFFS = OFF_FIRST + 80;
@@ -69,58 +71,65 @@ struct CodeArrays {
     const uint32_t *cnt, *first, *offs;
 };
 
-// Sets up, from the code lengths in the blob: the per-length canonical arrays and
-// the lookup table.  All threads of the workgroup call it.
+// Sets up, from the code lengths in the blob: the per-length canonical arrays
+// (count, first code, offset into the list of symbols sorted by (length, symbol))
+// and the lookup table.  All threads of the workgroup call it; it needs at least
+// four wavefronts.  Symbols are ranked with wave ballots (wavefront w holds symbols
+// 64w..64w+63), so nothing here loops over the alphabet.
 template <int FMT>
-__device__ void build_code(const GLOBAL uint8_t *code_len, uint8_t *smem_len, uint8_t *sorted, uint32_t *cnt,
+__device__ void build_code(const GLOBAL uint8_t *code_len, uint32_t *wavecnt, uint8_t *sorted, uint32_t *cnt,
                            uint32_t *first, uint32_t *offs, uint16_t *tbl, int tid, int nthreads)
 {
     using F = Fmt<FMT>;
-    for (int s = tid; s < 256; s += nthreads) smem_len[s] = s < F::A ? code_len[s] : 0;
-    if (tid < 20) cnt[tid] = 0;
-    __syncthreads();
-    for (int s = tid; s < F::A; s += nthreads) {
-        const uint32_t l = smem_len[s];
-        if (l && l <= ECFW_MAX_CODE_LEN) atomicAdd(&cnt[l], 1u);
-    }
-    __syncthreads();
-    if (tid == 0) {
-        uint32_t code = 0, off = 0;
-        first[0] = 0;
-        offs[0] = 0;
-        cnt[0] = 0;
-        for (int l = 1; l <= (int)ECFW_MAX_CODE_LEN; l++) {
-            code = (code + cnt[l - 1]) << 1;
-            first[l] = code;
-            offs[l] = off;
-            off += cnt[l];
-        }
-    }
-    __syncthreads();
-    for (int s = tid; s < F::A; s += nthreads) {
-        const uint32_t l = smem_len[s];
-        if (!l || l > ECFW_MAX_CODE_LEN) continue;
-        uint32_t rank = 0;
-        const uint32_t *len4 = (const uint32_t *)smem_len;
-        for (int w = 0; w * 4 < s; w++) {                   // symbols below s with the same length
-            const uint32_t v = len4[w];
+    constexpr int L = (int)ECFW_MAX_CODE_LEN;
+    const int lane = tid & 63, wave = tid >> 6;
+    uint32_t my_len = 0, my_rank = 0;
+    if (tid < 256) {
+        my_len = tid < F::A ? code_len[tid] : 0;
+        if (my_len > (uint32_t)L) my_len = 0;
+        const uint64_t below = ((uint64_t)1 << lane) - 1;
 #pragma unroll
-            for (int b = 0; b < 4; b++) rank += (((v >> (8 * b)) & 255u) == l) && (4 * w + b < s);
+        for (int l = 1; l <= L; l++) {
+            const uint64_t m = __ballot(my_len == (uint32_t)l);
+            if (my_len == (uint32_t)l) my_rank = (uint32_t)__popcll(m & below);
+            if (lane == 0) wavecnt[wave * 20 + l] = (uint32_t)__popcll(m);
         }
-        sorted[offs[l] + rank] = (uint8_t)s;
     }
+    __syncthreads();
+    // every thread keeps the canonical arrays of the lengths the table covers in registers
+    uint32_t r_first[WTB + 1], r_offs[WTB + 1], r_limit[WTB + 1];   // limit: first code of the next length, left-aligned
+    {
+        uint32_t code = 0, off = 0, prev = 0;
+#pragma unroll
+        for (int l = 1; l <= L; l++) {
+            const uint32_t c = wavecnt[l] + wavecnt[20 + l] + wavecnt[40 + l] + wavecnt[60 + l];
+            code = (code + prev) << 1;
+            if (l <= WTB) {
+                r_first[l] = code;
+                r_offs[l] = off;
+                r_limit[l] = (code + c) << (WTB - l);
+            }
+            if (tid == 0) { cnt[l] = c; first[l] = code; offs[l] = off; }
+            if (my_len == (uint32_t)l) {
+                uint32_t before = 0;
+#pragma unroll
+                for (int w = 0; w < 4; w++) before += w < wave ? wavecnt[w * 20 + l] : 0;
+                my_rank += off + before;
+            }
+            off += c;
+            prev = c;
+        }
+    }
+    if (tid < 256 && my_len) sorted[my_rank] = (uint8_t)tid;
     __syncthreads();
     // entry i: the codeword spelled by the bits of i, bit 0 first
     for (int i = tid; i < (1 << WTB); i += nthreads) {
-        const uint32_t r = __brev((uint32_t)i);
+        const uint32_t v = __brev((uint32_t)i) >> (32 - WTB);       // the 12 bits, first bit most significant
         uint32_t e = 0;
-        for (int l = 1; l <= WTB; l++) {
-            const uint32_t d = (r >> (32 - l)) - first[l];
-            if (d < cnt[l]) {
-                e = ((uint32_t)sorted[offs[l] + d] << F::SYM_SHIFT) | ((uint32_t)l << F::LEN_SHIFT);
-                break;
-            }
-        }
+#pragma unroll
+        for (int l = WTB; l >= 1; l--)                              // the smallest length whose codes reach past v
+            if (v < r_limit[l]) e = ((uint32_t)l << 16) | (r_offs[l] + (v >> (WTB - l)) - r_first[l]);
+        if (e) e = ((uint32_t)sorted[e & 0xffffu] << F::SYM_SHIFT) | ((e >> 16) << F::LEN_SHIFT);
         tbl[i] = (uint16_t)e;
     }
     __syncthreads();
@@ -263,7 +272,8 @@ __global__ __launch_bounds__(WAVES * 64) void ecfw_decode_kernel(WArgs a)
     if (c_begin >= c_end) return;     // uniform for the workgroup
 
     if (tid == 0) *s_ticket = 0;
-    build_code<FMT>(blob + a.off_len, smem + C::OFF_LEN, smem + C::OFF_SORTED, (uint32_t *)(smem + C::OFF_CNT),
+    static_assert(WAVES >= 4, "the code set-up ranks 256 symbols with four wavefronts");
+    build_code<FMT>(blob + a.off_len, (uint32_t *)(smem + C::OFF_WCNT), smem + C::OFF_SORTED, (uint32_t *)(smem + C::OFF_CNT),
                     (uint32_t *)(smem + C::OFF_FIRST), (uint32_t *)(smem + C::OFF_OFFS), tbl, tid, WAVES * 64);
 
     const uint64_t E = 64ull * N;
@@ -456,6 +466,8 @@ int launch_as(const WArgs &a, uint32_t max_workgroups, hipStream_t stream)
 template <int FMT>
 int launch_fmt(const WArgs &a, uint32_t N, bool fast, uint32_t max_workgroups, hipStream_t stream)
 {
+    // the branch-free kernels at N = 64 need under 128 registers: 16 wavefronts hide more of the LDS latency
+    if (N == 64 && fast) return launch_as<FMT, 64, 16, true>(a, max_workgroups, stream);
     if (N == 64) return fast ? launch_as<FMT, 64, 8, true>(a, max_workgroups, stream) : launch_as<FMT, 64, 8, false>(a, max_workgroups, stream);
     return fast ? launch_as<FMT, 128, 8, true>(a, max_workgroups, stream) : launch_as<FMT, 128, 8, false>(a, max_workgroups, stream);
 }
