@@ -365,8 +365,9 @@ def bench_encode(a):
 
 
 def bench_wide(a):
-    """Workloads "wide_bf16" / "wide_e5m2": the wide-alphabet decoder (ecfw_decode) on eight MLP-sized
-    matrices (14336 x 4096) of the 8B-class stack in BF16 or E5M2, one launch per matrix."""
+    """Workloads "wide_bf16" / "wide_e5m2": the wide-alphabet decoder on eight MLP-sized matrices
+    (14336 x 4096) of the 8B-class stack in BF16 or E5M2: one ecfw_decode_batched launch per step, or with
+    --launch layer one ecfw_decode launch per matrix."""
     from paper_2510_02676_amd import ecfw, synth
     import oracle
     dev = "cuda:0"
@@ -393,10 +394,17 @@ def bench_wide(a):
     alg_total = rd_total + out_total
     stream = torch.cuda.current_stream()
 
-    def step():
-        for m in mats:
-            ecfw.ecfw_decode(m["d_blob"], m["hdr"], m["d_out"], stream=stream)
+    batch = ecfw.WBatch(hdrs, [m["d_blob"] for m in mats], [m["d_out"] for m in mats])
+    per_tensor = a.launch == "layer"          # --launch layer: one ecfw_decode launch per matrix instead
 
+    def step():
+        if per_tensor:
+            for m in mats:
+                ecfw.ecfw_decode(m["d_blob"], m["hdr"], m["d_out"], stream=stream)
+        else:
+            ecfw.ecfw_decode_batched(batch, stream)
+
+    n_launch = n_mats if per_tensor else 1
     for _ in range(a.warmup):
         step()
     torch.cuda.synchronize()
@@ -411,16 +419,18 @@ def bench_wide(a):
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     sec_per_step = wall / a.steps
-    launch_s = e0.elapsed_time(e1) * 1e-3 / (a.steps * n_mats)
-    achieved = alg_total / n_mats / launch_s / 1e9
+    launch_s = e0.elapsed_time(e1) * 1e-3 / (a.steps * n_launch)
+    achieved = alg_total / n_launch / launch_s / 1e9
     name = "BF16" if fmt == ecfw.FMT_BF16 else "E5M2"
     out = {
         "metric": "decoded %s GB/s (exponent-coded container -> exact %s elements)" % (name, name),
         "value": round(out_total / sec_per_step / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": round(sec_per_step * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u16" if eb == 2 else "u8", "data": "synthetic",
-        "config": {"workload": "%s: %d matrices 14336x4096 of the 8B-class stack as %s, one ecfw_decode launch each"
-                               % (a.workload, n_mats, name),
+        "config": {"workload": "%s: %d matrices 14336x4096 of the 8B-class stack as %s, %s"
+                               % (a.workload, n_mats, name, "one ecfw_decode launch each" if per_tensor else
+                                  "one ecfw_decode_batched launch"),
+                   "launch": "tensor" if per_tensor else "batch",
                    "elements": n_total, "lane_syms": hdrs[0].lane_syms, "group_chunks": hdrs[0].group_chunks,
                    "max_code_len": max(h.max_code_len for h in hdrs), "seed": a.seed},
         "compression_ratio": round(sum(h.total_size for h in hdrs) / out_total, 5),
@@ -428,8 +438,9 @@ def bench_wide(a):
         "total_moved_GBps": round(alg_total / sec_per_step / 1e9, 2), "bit_exact": True, "setup_s": round(t_setup, 1),
         "roofline": {"bound": "hbm", "kernel": "ecfw_decode_kernel", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "avg_launch_us": round(launch_s * 1e6, 2),
-                     "algorithmic_bytes_per_launch": int(alg_total / n_mats),
-                     "traffic": profiled_traffic(a.workload, "tensor", hdrs, a.layers == 0, "ecfw_decode_kernel")},
+                     "algorithmic_bytes_per_launch": int(alg_total / n_launch),
+                     "traffic": profiled_traffic(a.workload, "tensor" if per_tensor else "batch", hdrs, a.layers == 0,
+                                                 "ecfw_decode_kernel")},
     }
     if not a.no_cpu_baseline:
         # the oracle's bit-serial reader on the first 2^20 elements of the first matrix, re-encoded on their own

@@ -141,6 +141,39 @@ int ecfw_blob_validate(const void *blob_host, uint64_t size);
 int ecfw_decode(const void *d_blob, const ecfw_header *hdr, void *d_out, uint64_t out_capacity,
                 uint32_t max_workgroups, void *stream);
 
+/*
+ * Batched decode: many tensors of one format and one lane_syms in ONE launch, so
+ * that the per-launch costs (code set-up per workgroup, first loads, tail) are paid
+ * once per batch; a workgroup's contiguous range of chunks may cross tensors, and
+ * the code is set up again at each crossing.
+ * ecfw_batch_prepare: HOST.  Checks each header and buffer as ecfw_decode does and
+ * fills items_host[n] (the caller copies them to the device, 8-byte aligned) and
+ * *info (the caller may then set info->max_workgroups, 0 = one per compute unit).
+ * ecfw_decode_batched: asynchronous on `stream`; d_items is the DEVICE copy.
+ */
+typedef struct ecfw_batch_item {
+    uint64_t d_blob, d_out;      /* device addresses                                   */
+    uint64_t n_elem, n_chunks;
+    uint64_t first_chunk;        /* running sum of n_chunks over the earlier items     */
+    uint64_t stream_bytes;
+    uint64_t off_code_len, off_chunk_bit, off_lane_bits, off_stream, off_plane, off_sign;
+    uint64_t group_chunks;
+    uint64_t reserved[3];
+} ecfw_batch_item;
+
+typedef struct ecfw_batch_info {
+    uint64_t total_chunks;
+    uint32_t fmt, lane_syms;
+    uint32_t max_code_len;       /* longest codeword of any tensor of the batch        */
+    uint32_t max_workgroups;
+    uint64_t reserved;
+} ecfw_batch_info;
+
+int ecfw_batch_prepare(const ecfw_header *hdrs, const void *const *d_blobs, void *const *d_outs,
+                       const uint64_t *out_capacities, uint32_t n, ecfw_batch_item *items_host,
+                       ecfw_batch_info *info);
+int ecfw_decode_batched(const void *d_items, uint32_t n, const ecfw_batch_info *info, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

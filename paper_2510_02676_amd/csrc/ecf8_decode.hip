@@ -226,7 +226,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
         auto draw = [&]() -> uint64_t {
             uint32_t t = 0;
             if (lane == 0) t = __hip_atomic_fetch_add(s_ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            return c + __builtin_amdgcn_readfirstlane(t);
+            return c + uniform32(t);
         };
 
         // Start-up: the loads of the table, of the first chunks' metadata and of the first chunk's
@@ -313,8 +313,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
                 const uint64_t cl = cg - first_chunk;            // chunk index inside the tensor
                 GLOBAL uint8_t *out_c = out + chunk_base(cl) + lane_off;   // this lane's piece 0
                 const uint32_t ostride = chunk_stride(cl);
-                const uint64_t b0 = __builtin_amdgcn_readfirstlane((uint32_t)m_cur.b0) |
-                                    ((uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)(m_cur.b0 >> 32)) << 32);
+                const uint64_t b0 = uniform64(m_cur.b0);
                 uint64_t byte0;
                 const uint64_t span64 = span_of(m_cur, byte0);
                 const bool staged = __builtin_amdgcn_readfirstlane((uint32_t)(span64 <= (uint64_t)C::STAGE)) != 0;
@@ -394,8 +393,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
 #pragma unroll
                             for (int j = 0; j < C::PIECES; j++) pl[j] = *(const GLOBAL u32x2 *)(plane_c + j * pstride);
                             const uint32_t rel = wave_incl_scan(m.lb) - m.lb;
-                            const uint64_t b0 = __builtin_amdgcn_readfirstlane((uint32_t)m.b0) |
-                                                ((uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)(m.b0 >> 32)) << 32);
+                            const uint64_t b0 = uniform64(m.b0);
                             decode_store((C::OFF_WAVES + wave * C::SLOT) * 8 + (uint32_t)(b0 - byte0 * 8) + rel, m.lb, pl,
                                          out + chunk_base(cl) + lane_off, chunk_stride(cl));
                         }

@@ -39,6 +39,14 @@ __device__ __forceinline__ uint32_t len_of(uint64_t lo, uint64_t hi, int s)
     return (uint32_t)((s < 8 ? lo >> (8 * s) : hi >> (8 * (s - 8))) & 0xff);
 }
 
+// The first active lane's value, in scalar registers.  The builtin returns a signed int: widened
+// as it is, a low word with bit 31 set would smear ones over the high word.
+__device__ __forceinline__ uint32_t uniform32(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ uint64_t uniform64(uint64_t v)
+{
+    return (uint64_t)uniform32((uint32_t)v) | ((uint64_t)uniform32((uint32_t)(v >> 32)) << 32);
+}
+
 // Inclusive wave64 prefix sum with DPP row shifts and row broadcasts.
 __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x)
 {

@@ -224,8 +224,7 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_kernel(GArgs a)
             uint64_t byte0;
             span_of(m, byte0);
             const uint32_t rel = wave_incl_scan(m.lb) - m.lb;
-            const uint64_t start = __builtin_amdgcn_readfirstlane((uint32_t)m.b0) |
-                                   ((uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)(m.b0 >> 32)) << 32);
+            const uint64_t start = uniform64(m.b0);
 #pragma unroll
             for (int k = 0; k < GSEGS; k++) {
                 const uint32_t j = (lane + 64 * k) * 16;

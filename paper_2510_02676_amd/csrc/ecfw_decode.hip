@@ -20,6 +20,8 @@
 
 #include "ecf8_device.h"
 
+#include <cstring>
+
 #include <cstdlib>
 
 namespace {
@@ -27,11 +29,13 @@ namespace {
 constexpr int WTB = ECFW_TABLE_BITS;
 constexpr uint32_t WMASK2 = ((1u << WTB) - 1) << 1;   // byte offset mask of a 16-bit entry
 
-struct WArgs {
-    uint64_t d_blob, d_out;
-    uint64_t n_elem, n_chunks, st_bytes;
-    uint64_t off_len, off_cb, off_lb, off_st, off_pl, off_sg;
-    uint32_t group;
+typedef ecfw_batch_item WArgs;          // one tensor, as the kernel sees it
+
+struct BArgs {
+    WArgs single;                        // used when items == nullptr
+    const GLOBAL WArgs *items;           // device array for the batched call
+    uint32_t n_items;
+    uint64_t total_chunks;
 };
 
 template <int FMT> struct Fmt;
@@ -238,7 +242,7 @@ __device__ __forceinline__ u32x4 merge_e5m2(const uint32_t e[16], uint32_t mant,
 }
 
 template <int FMT, int N, int WAVES, bool FAST>
-__global__ __launch_bounds__(WAVES * 64) void ecfw_decode_kernel(WArgs a)
+__global__ __launch_bounds__(WAVES * 64) void ecfw_decode_kernel(BArgs b)
 {
     using C = WCfg<FMT, N, WAVES>;
     using F = Fmt<FMT>;
@@ -253,35 +257,54 @@ __global__ __launch_bounds__(WAVES * 64) void ecfw_decode_kernel(WArgs a)
     const uint32_t stage_off = C::OFF_STAGE + wave * STAGE;
     uint8_t *stage = smem + stage_off;
 
-    const GLOBAL uint8_t *blob = (const GLOBAL uint8_t *)a.d_blob;
-    const GLOBAL uint64_t *chunk_bit = (const GLOBAL uint64_t *)(blob + a.off_cb);
-    const GLOBAL uint16_t *lane_bits = (const GLOBAL uint16_t *)(blob + a.off_lb);
-    const GLOBAL uint8_t *stream = blob + a.off_st;
-    const GLOBAL uint8_t *plane = blob + a.off_pl;
-    const GLOBAL uint8_t *signs = blob + a.off_sg;
-    GLOBAL uint8_t *out = (GLOBAL uint8_t *)a.d_out;
-
     // contiguous range of chunks for this workgroup, cut at multiples of 64 chunks when there is
     // enough work so that the waves of a workgroup share the interleaved groups of the layout
     const uint64_t NWG = gridDim.x, wg = blockIdx.x;
-    const uint64_t unit = a.n_chunks >= NWG * 128 ? 64 : 1;
-    const uint64_t units = (a.n_chunks + unit - 1) / unit;
-    const uint64_t c_begin = units * wg / NWG * unit;
-    uint64_t c_end = units * (wg + 1) / NWG * unit;
-    if (c_end > a.n_chunks) c_end = a.n_chunks;
-    if (c_begin >= c_end) return;     // uniform for the workgroup
+    const uint64_t unit = b.total_chunks >= NWG * 128 ? 64 : 1;
+    const uint64_t units = (b.total_chunks + unit - 1) / unit;
+    uint64_t g = units * wg / NWG * unit;              // chunk numbers run through the whole batch
+    uint64_t g_end = units * (wg + 1) / NWG * unit;
+    if (g_end > b.total_chunks) g_end = b.total_chunks;
+
+    while (g < g_end) {                                // one round per tensor the range touches (uniform)
+    WArgs a;
+    if (b.items) {
+        uint32_t lo = 0, hi = b.n_items - 1;
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi + 1) >> 1;
+            if (uniform64(b.items[mid].first_chunk) <= g) lo = mid; else hi = mid - 1;
+        }
+        // the item is the same for every lane: say so, or its fields (and all the address arithmetic
+        // on them) would live in vector registers
+        const GLOBAL uint64_t *src = (const GLOBAL uint64_t *)(b.items + lo);
+        uint64_t *dst = (uint64_t *)&a;
+#pragma unroll
+        for (int i = 0; i < (int)(sizeof(WArgs) / 8); i++) dst[i] = uniform64(src[i]);
+    } else {
+        a = b.single;
+    }
+    const uint64_t c_begin = g - a.first_chunk;        // chunk numbers inside the tensor
+    const uint64_t c_end = g_end - a.first_chunk < a.n_chunks ? g_end - a.first_chunk : a.n_chunks;
+    const GLOBAL uint8_t *blob = (const GLOBAL uint8_t *)a.d_blob;
+    const GLOBAL uint64_t *chunk_bit = (const GLOBAL uint64_t *)(blob + a.off_chunk_bit);
+    const GLOBAL uint16_t *lane_bits = (const GLOBAL uint16_t *)(blob + a.off_lane_bits);
+    const GLOBAL uint8_t *stream = blob + a.off_stream;
+    const GLOBAL uint8_t *plane = blob + a.off_plane;
+    const GLOBAL uint8_t *signs = blob + a.off_sign;
+    GLOBAL uint8_t *out = (GLOBAL uint8_t *)a.d_out;
+
 
     if (tid == 0) *s_ticket = 0;
     static_assert(WAVES >= 4, "the code set-up ranks 256 symbols with four wavefronts");
-    build_code<FMT>(blob + a.off_len, (uint32_t *)(smem + C::OFF_WCNT), smem + C::OFF_SORTED, (uint32_t *)(smem + C::OFF_CNT),
+    build_code<FMT>(blob + a.off_code_len, (uint32_t *)(smem + C::OFF_WCNT), smem + C::OFF_SORTED, (uint32_t *)(smem + C::OFF_CNT),
                     (uint32_t *)(smem + C::OFF_FIRST), (uint32_t *)(smem + C::OFF_OFFS), tbl, tid, WAVES * 64);
 
     const uint64_t E = 64ull * N;
-    const uint64_t whole = a.n_elem / (a.group * E) * a.group;     // chunks inside complete groups
+    const uint64_t whole = a.n_elem / (a.group_chunks * E) * a.group_chunks;     // chunks inside complete groups
     auto chunk_base = [&](uint64_t c) -> uint64_t {
-        return c < whole ? (c - c % a.group) * E + (c % a.group) * (64 * P) : c * E;
+        return c < whole ? (c - c % a.group_chunks) * E + (c % a.group_chunks) * (64 * P) : c * E;
     };
-    auto chunk_stride = [&](uint64_t c) -> uint64_t { return c < whole ? (uint64_t)a.group * (64 * P) : 64ull * P; };
+    auto chunk_stride = [&](uint64_t c) -> uint64_t { return c < whole ? (uint64_t)a.group_chunks * (64 * P) : 64ull * P; };
 
     struct Meta { uint64_t b0, b1; uint32_t lb; };
     struct Payload {
@@ -293,7 +316,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecfw_decode_kernel(WArgs a)
     auto draw = [&]() -> uint64_t {
         uint32_t t = 0;
         if (lane == 0) t = atomicAdd(s_ticket, 1u);
-        return c_begin + __builtin_amdgcn_readfirstlane(t);
+        return c_begin + uniform32(t);
     };
     auto load_meta = [&](uint64_t c) {
         Meta m;
@@ -304,7 +327,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecfw_decode_kernel(WArgs a)
     };
     auto span_of = [&](const Meta &m, uint64_t &byte0) -> uint64_t {
         uint64_t byte_end = ((m.b1 + 7) >> 3) + 8;
-        if (byte_end > a.st_bytes) byte_end = a.st_bytes;
+        if (byte_end > a.stream_bytes) byte_end = a.stream_bytes;
         byte0 = (m.b0 >> 3) & ~15ull;
         if (byte0 > byte_end) byte0 = byte_end;
         return byte_end - byte0;
@@ -336,7 +359,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecfw_decode_kernel(WArgs a)
     // chunk, and chunks whose span does not fit the stage (codewords averaging over 8 bits).
     auto symbol_pass = [&](uint64_t c, const Meta &m) {
         const uint32_t rel = wave_incl_scan(m.lb) - m.lb;
-        const uint64_t limit = a.st_bytes * 8 - 64;
+        const uint64_t limit = a.stream_bytes * 8 - 64;
         uint64_t posA = m.b0 + rel, posB = posA + m.lb;
         const uint64_t e0 = chunk_base(c) + (uint64_t)lane * P, stride = chunk_stride(c);
 #pragma unroll 1
@@ -408,8 +431,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecfw_decode_kernel(WArgs a)
             symbol_pass(cur, m);
         } else {
             const uint32_t rel = wave_incl_scan(m.lb) - m.lb;
-            const uint64_t start = __builtin_amdgcn_readfirstlane((uint32_t)m.b0) |
-                                   ((uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)(m.b0 >> 32)) << 32);
+            const uint64_t start = uniform64(m.b0);
             uint32_t pa = stage_off * 8 + (uint32_t)(start - byte0 * 8) + rel - 1;    // one bit off, see pair_step
             uint32_t pb = pa + m.lb - 30;
             GLOBAL uint8_t *dst = out + (chunk_base(cur) + (uint64_t)lane * P) * F::ELEM;
@@ -449,33 +471,42 @@ __global__ __launch_bounds__(WAVES * 64) void ecfw_decode_kernel(WArgs a)
         m_cur = m_next;
         m_next = m_next2;
     }
+    g = a.first_chunk + c_end;
+    __syncthreads();                                   // every wave is done with this tensor's table and tickets
+    }
 }
 
 template <int FMT, int N, int WAVES, bool FAST>
-int launch_as(const WArgs &a, uint32_t max_workgroups, hipStream_t stream)
+int launch_as(const BArgs &a, uint32_t max_workgroups, hipStream_t stream)
 {
     int cus = device_cus();
     if (cus <= 0) return ECF8_E_HIP;
     uint64_t grid = (uint64_t)cus;
     if (max_workgroups && max_workgroups < grid) grid = max_workgroups;
-    if (grid > a.n_chunks) grid = a.n_chunks;
+    if (grid > a.total_chunks) grid = a.total_chunks;
     hipLaunchKernelGGL((ecfw_decode_kernel<FMT, N, WAVES, FAST>), dim3((unsigned)grid), dim3(WAVES * 64), 0, stream, a);
     return hipGetLastError() == hipSuccess ? ECF8_OK : ECF8_E_HIP;
 }
 
 template <int FMT>
-int launch_fmt(const WArgs &a, uint32_t N, bool fast, uint32_t max_workgroups, hipStream_t stream)
+int launch_fmt(const BArgs &a, uint32_t N, bool fast, uint32_t max_workgroups, hipStream_t stream)
 {
     // the branch-free kernels at N = 64 need under 128 registers: 16 wavefronts hide more of the LDS latency
     if (N == 64 && fast) return launch_as<FMT, 64, 16, true>(a, max_workgroups, stream);
-    if (N == 64) return fast ? launch_as<FMT, 64, 8, true>(a, max_workgroups, stream) : launch_as<FMT, 64, 8, false>(a, max_workgroups, stream);
+    if (N == 64) return launch_as<FMT, 64, 8, false>(a, max_workgroups, stream);
     return fast ? launch_as<FMT, 128, 8, true>(a, max_workgroups, stream) : launch_as<FMT, 128, 8, false>(a, max_workgroups, stream);
 }
 
-} // namespace
+int launch(const BArgs &a, uint32_t fmt, uint32_t N, uint32_t max_code_len, uint32_t max_workgroups, void *stream)
+{
+    const bool fast = max_code_len <= ECFW_TABLE_BITS;
+    hipStream_t s = (hipStream_t)stream;
+    return fmt == ECFW_FMT_BF16 ? launch_fmt<ECFW_FMT_BF16>(a, N, fast, max_workgroups, s)
+                                : launch_fmt<ECFW_FMT_E5M2>(a, N, fast, max_workgroups, s);
+}
 
-extern "C" int ecfw_decode(const void *d_blob, const ecfw_header *h, void *d_out, uint64_t out_capacity,
-                           uint32_t max_workgroups, void *stream)
+// Checks of one tensor's header and buffers; fills the kernel's view of it.
+int make_item(const ecfw_header *h, const void *d_blob, void *d_out, uint64_t out_capacity, WArgs *it)
 {
     if (!d_blob || !h || !d_out) return ECF8_E_ARG;
     if (h->magic != ECFW_MAGIC || h->version != ECFW_VERSION) return ECF8_E_FORMAT;
@@ -491,21 +522,69 @@ extern "C" int ecfw_decode(const void *d_blob, const ecfw_header *h, void *d_out
     if (((uintptr_t)d_blob & 255) || ((uintptr_t)d_out & 15)) return ECF8_E_ALIGN;
     if ((h->off_code_len | h->off_chunk_bit | h->off_lane_bits | h->off_stream | h->off_plane | h->off_sign) & 255)
         return ECF8_E_FORMAT;
-    WArgs a;
-    a.d_blob = (uint64_t)(uintptr_t)d_blob;
-    a.d_out = (uint64_t)(uintptr_t)d_out;
-    a.n_elem = h->n_elem;
-    a.n_chunks = h->n_chunks;
-    a.st_bytes = h->stream_bytes;
-    a.off_len = h->off_code_len;
-    a.off_cb = h->off_chunk_bit;
-    a.off_lb = h->off_lane_bits;
-    a.off_st = h->off_stream;
-    a.off_pl = h->off_plane;
-    a.off_sg = h->off_sign;
-    a.group = g;
-    const bool fast = h->max_code_len <= ECFW_TABLE_BITS;
-    hipStream_t s = (hipStream_t)stream;
-    return h->fmt == ECFW_FMT_BF16 ? launch_fmt<ECFW_FMT_BF16>(a, h->lane_syms, fast, max_workgroups, s)
-                                   : launch_fmt<ECFW_FMT_E5M2>(a, h->lane_syms, fast, max_workgroups, s);
+    std::memset(it, 0, sizeof(*it));
+    it->d_blob = (uint64_t)(uintptr_t)d_blob;
+    it->d_out = (uint64_t)(uintptr_t)d_out;
+    it->n_elem = h->n_elem;
+    it->n_chunks = h->n_chunks;
+    it->first_chunk = 0;
+    it->stream_bytes = h->stream_bytes;
+    it->off_code_len = h->off_code_len;
+    it->off_chunk_bit = h->off_chunk_bit;
+    it->off_lane_bits = h->off_lane_bits;
+    it->off_stream = h->off_stream;
+    it->off_plane = h->off_plane;
+    it->off_sign = h->off_sign;
+    it->group_chunks = g;
+    return ECF8_OK;
+}
+
+} // namespace
+
+extern "C" int ecfw_decode(const void *d_blob, const ecfw_header *h, void *d_out, uint64_t out_capacity,
+                           uint32_t max_workgroups, void *stream)
+{
+    BArgs a;
+    int rc = make_item(h, d_blob, d_out, out_capacity, &a.single);
+    if (rc) return rc;
+    a.items = nullptr;
+    a.n_items = 1;
+    a.total_chunks = h->n_chunks;
+    return launch(a, h->fmt, h->lane_syms, h->max_code_len, max_workgroups, stream);
+}
+
+extern "C" int ecfw_batch_prepare(const ecfw_header *hdrs, const void *const *d_blobs, void *const *d_outs,
+                                  const uint64_t *out_capacities, uint32_t n, ecfw_batch_item *items_host,
+                                  ecfw_batch_info *info)
+{
+    if (!hdrs || !d_blobs || !d_outs || !out_capacities || !items_host || !info || n == 0) return ECF8_E_ARG;
+    std::memset(info, 0, sizeof(*info));
+    uint64_t chunks = 0;
+    for (uint32_t i = 0; i < n; i++) {
+        int rc = make_item(&hdrs[i], d_blobs[i], d_outs[i], out_capacities[i], &items_host[i]);
+        if (rc) return rc;
+        if (hdrs[i].fmt != hdrs[0].fmt || hdrs[i].lane_syms != hdrs[0].lane_syms) return ECF8_E_ARG;
+        items_host[i].first_chunk = chunks;
+        chunks += hdrs[i].n_chunks;
+        if (hdrs[i].max_code_len > info->max_code_len) info->max_code_len = hdrs[i].max_code_len;
+    }
+    info->total_chunks = chunks;
+    info->fmt = hdrs[0].fmt;
+    info->lane_syms = hdrs[0].lane_syms;
+    return ECF8_OK;
+}
+
+extern "C" int ecfw_decode_batched(const void *d_items, uint32_t n, const ecfw_batch_info *info, void *stream)
+{
+    if (!d_items || !info || n == 0 || info->total_chunks == 0) return ECF8_E_ARG;
+    if (info->fmt != ECFW_FMT_E5M2 && info->fmt != ECFW_FMT_BF16) return ECF8_E_ARG;
+    if (info->lane_syms != 64 && info->lane_syms != 128) return ECF8_E_ARG;
+    if (info->max_code_len < 1 || info->max_code_len > ECFW_MAX_CODE_LEN) return ECF8_E_ARG;
+    if ((uintptr_t)d_items & 7) return ECF8_E_ALIGN;
+    BArgs a;
+    std::memset(&a.single, 0, sizeof(a.single));
+    a.items = (const GLOBAL WArgs *)d_items;
+    a.n_items = n;
+    a.total_chunks = info->total_chunks;
+    return launch(a, info->fmt, info->lane_syms, info->max_code_len, info->max_workgroups, stream);
 }

@@ -124,3 +124,43 @@ def ecfw_decode(d_blob, hdr, d_out=None, max_workgroups=0, stream=None):
                                               d_out.numel() * d_out.element_size(), max_workgroups,
                                               _e._stream_ptr(stream)))
     return d_out
+
+
+class WBatchItem(ctypes.Structure):
+    _fields_ = [("d_blob", _u64), ("d_out", _u64), ("n_elem", _u64), ("n_chunks", _u64), ("first_chunk", _u64),
+                ("stream_bytes", _u64), ("off_code_len", _u64), ("off_chunk_bit", _u64), ("off_lane_bits", _u64),
+                ("off_stream", _u64), ("off_plane", _u64), ("off_sign", _u64), ("group_chunks", _u64),
+                ("reserved", _u64 * 3)]
+
+
+class WBatchInfo(ctypes.Structure):
+    _fields_ = [("total_chunks", _u64), ("fmt", _u32), ("lane_syms", _u32), ("max_code_len", _u32),
+                ("max_workgroups", _u32), ("reserved", _u64)]
+
+
+assert ctypes.sizeof(WBatchItem) == 128 and ctypes.sizeof(WBatchInfo) == 32
+_lib.ecfw_batch_prepare.argtypes = [ctypes.POINTER(WHeader), ctypes.POINTER(_vp), ctypes.POINTER(_vp),
+                                    ctypes.POINTER(_u64), _u32, ctypes.POINTER(WBatchItem), ctypes.POINTER(WBatchInfo)]
+_lib.ecfw_decode_batched.argtypes = [_vp, _u32, ctypes.POINTER(WBatchInfo), _vp]
+
+
+class WBatch:
+    """Device-resident item table for ecfw_decode_batched (built once, reused)."""
+
+    def __init__(self, hdrs, d_blobs, d_outs):
+        n = len(hdrs)
+        H = (WHeader * n)(*hdrs)
+        B = (_vp * n)(*[t.data_ptr() for t in d_blobs])
+        O = (_vp * n)(*[t.data_ptr() for t in d_outs])
+        C = (_u64 * n)(*[t.numel() * t.element_size() for t in d_outs])
+        items = (WBatchItem * n)()
+        self.info = WBatchInfo()
+        _e._check("ecfw_batch_prepare", _lib.ecfw_batch_prepare(H, B, O, C, n, items, ctypes.byref(self.info)))
+        self.d_items = torch.from_numpy(np.frombuffer(items, dtype=np.uint8).copy()).to(d_blobs[0].device)
+        self.n = n
+        self._keep = (list(d_blobs), list(d_outs))
+
+
+def ecfw_decode_batched(batch, stream=None):
+    _e._check("ecfw_decode_batched", _lib.ecfw_decode_batched(batch.d_items.data_ptr(), batch.n,
+                                                              ctypes.byref(batch.info), _e._stream_ptr(stream)))

@@ -317,3 +317,23 @@ def test_config2_experts_and_attention(orc):
 def test_config3_full_block(orc):
     """configs[3]: one full DiT block (11 matrices, 509 M weights, per-tensor scaling), one launch."""
     _full_size_case(orc, synth.config3(1), {"b0.sa_q", "b0.ca_o"})
+
+
+def test_stream_longer_than_2_to_the_31_bits():
+    """2^30 weights in one tensor: chunk start bits pass 2^31, so bit positions need all 64 bits.  The
+    oracle cannot read a container of this size in reasonable time; the decoded tensor is compared with
+    the input (the container's content is pinned by the smaller cases)."""
+    n = 1 << 30
+    g = torch.Generator(device=DEV)
+    g.manual_seed(31)
+    e = torch.randn(n, generator=g, device=DEV).mul_(1.5).add_(7.0).round_().clamp_(0, 15).to(torch.int32)
+    low = torch.randint(0, 8, (n,), generator=g, device=DEV, dtype=torch.int32)
+    x = ((e << 3) | low | ((low & 1) << 7)).to(torch.uint8)
+    del e, low
+    blob = ecf8.ecf8_encode(x.cpu().numpy(), 1 << 15, 1 << 15)
+    assert blob.header.stream_bits > 1 << 31
+    d_blob = blob.to(DEV)
+    out = torch.empty_like(x)
+    ecf8.ecf8_decode(blob.header, d_blob, out)
+    torch.cuda.synchronize()
+    assert torch.equal(out, x)

@@ -134,6 +134,61 @@ def test_few_workgroups_and_caller_buffer(orc, fmt):
         _check(orc, fmt, x, max_workgroups=wgs)
 
 
+@pytest.mark.parametrize("fmt", [E5M2, BF16])
+def test_batched_matches_oracle(orc, fmt):
+    """Many tensors in one launch: sizes from a single element to hundreds of chunks, so that workgroup
+    ranges start and end inside tensors and run across several of them."""
+    sizes = [1, 64 * 64 * 3 + 5, 17, 300000, 4096, 64 * 64 * 200, 9, 123457, 64 * 64, 5]
+    blobs = [ecfw.ecfw_encode(fmt, _rand_elems(fmt, n, 1000 + i, spread=1.5 + i % 3), lane_syms=64,
+                              group_chunks=(1, 4, 32)[i % 3], max_code_len=(0, 9)[i % 2]) for i, n in enumerate(sizes)]
+    eb = ecfw.ELEM_BYTES[fmt]
+    d_blobs = [b.to(DEV) for b in blobs]
+    pad = 256
+    bufs = [torch.full((pad + b.header.n_elem * eb + pad,), 0x5A, dtype=torch.uint8, device=DEV) for b in blobs]
+    outs = [buf[pad:pad + b.header.n_elem * eb] for buf, b in zip(bufs, blobs)]
+    for wgs in (0, 1, 7):
+        for o in outs:
+            o.fill_(0x5A)
+        batch = ecfw.WBatch([b.header for b in blobs], d_blobs, outs)
+        batch.info.max_workgroups = wgs
+        print("fmt", fmt, "batched, max_workgroups", wgs, "chunks", batch.info.total_chunks, flush=True)
+        ecfw.ecfw_decode_batched(batch)
+        torch.cuda.synchronize()
+        for buf, b in zip(bufs, blobs):
+            host = buf.cpu().numpy()
+            nb = b.header.n_elem * eb
+            assert (host[:pad] == 0x5A).all() and (host[pad + nb:] == 0x5A).all()
+            got = host[pad:pad + nb]
+            dec, _ = orc.w_container_decode(b.numpy())
+            assert np.array_equal(got.view(np.uint16) if eb == 2 else got, dec)
+
+
+def test_batched_with_long_codes_and_argument_errors(orc):
+    xs = [_rand_elems(BF16, n, n, spread=6.0) for n in (50000, 200000)]
+    blobs = [ecfw.ecfw_encode(BF16, x, max_code_len=c) for x, c in zip(xs, (16, 0))]
+    assert blobs[0].header.max_code_len > 12 >= blobs[1].header.max_code_len
+    d_blobs = [b.to(DEV) for b in blobs]
+    outs = [torch.empty(b.header.n_elem, dtype=torch.bfloat16, device=DEV) for b in blobs]
+    batch = ecfw.WBatch([b.header for b in blobs], d_blobs, outs)
+    assert batch.info.max_code_len == blobs[0].header.max_code_len
+    ecfw.ecfw_decode_batched(batch)
+    torch.cuda.synchronize()
+    for o, x in zip(outs, xs):
+        assert np.array_equal(o.view(torch.int16).cpu().numpy().view(np.uint16), x)
+    other = ecfw.ecfw_encode(E5M2, _rand_elems(E5M2, 5000, 1))
+    with pytest.raises(ecf8.Ecf8Error) as e:       # formats do not mix in one launch
+        ecfw.WBatch([blobs[0].header, other.header], [d_blobs[0], other.to(DEV)],
+                    [outs[0], torch.empty(5000, dtype=torch.uint8, device=DEV)])
+    assert e.value.code == ecf8.E_ARG
+    n128 = ecfw.ecfw_encode(BF16, xs[0], lane_syms=128)
+    with pytest.raises(ecf8.Ecf8Error) as e:       # nor do chunk shapes
+        ecfw.WBatch([blobs[0].header, n128.header], [d_blobs[0], n128.to(DEV)], [outs[0], torch.empty_like(outs[0])])
+    assert e.value.code == ecf8.E_ARG
+    with pytest.raises(ecf8.Ecf8Error) as e:
+        ecfw.WBatch([blobs[0].header], [d_blobs[0]], [outs[0][:100]])
+    assert e.value.code == ecf8.E_CAPACITY
+
+
 def test_argument_errors():
     x = _rand_elems(BF16, 10000, 1)
     blob = ecfw.ecfw_encode(BF16, x)
@@ -176,3 +231,29 @@ def test_full_size_matrix(orc, fmt):
         want = orc.w_container_encode(fmt, part, 1, part.size, h.lane_syms, h.group_chunks, blob.code_len())
         dec, _ = orc.w_container_decode(want)
         assert np.array_equal(got[g * E:(g + 1) * E], dec)
+
+
+@pytest.mark.parametrize("fmt", [E5M2, BF16])
+def test_stream_longer_than_2_to_the_31_bits(fmt):
+    """2^30 elements: chunk start bits pass 2^31 and 2^32, device addresses and bit positions need all 64 bits.
+    The oracle cannot read a container of this size in reasonable time; the decoded tensor is compared
+    with the input (the container's content is pinned by the smaller cases)."""
+    n = 1 << 30
+    g = torch.Generator(device=DEV)
+    g.manual_seed(31)
+    e = torch.randn(n, generator=g, device=DEV).mul_(2.0).add_(120.0 if fmt == BF16 else 14.0).round_().clamp_(0, 255 if fmt == BF16 else 31)
+    if fmt == BF16:
+        low = torch.randint(0, 128, (n,), generator=g, device=DEV, dtype=torch.int32)
+        x = ((e.to(torch.int32) << 7) | low | ((low & 1) << 15)).to(torch.int16)
+    else:
+        low = torch.randint(0, 4, (n,), generator=g, device=DEV, dtype=torch.int32)
+        x = ((e.to(torch.int32) << 2) | low | ((low & 1) << 7)).to(torch.uint8)
+    del e, low
+    blob = ecfw.ecfw_encode(fmt, x.cpu().numpy().view(np.uint16 if fmt == BF16 else np.uint8), 1 << 15, 1 << 15)
+    assert blob.header.stream_bits > 1 << 31
+    print("fmt", fmt, "n", n, "stream bits", blob.header.stream_bits, flush=True)
+    d_blob = blob.to(DEV)
+    out = torch.empty_like(x)
+    ecfw.ecfw_decode(d_blob, blob.header, out)
+    torch.cuda.synchronize()
+    assert torch.equal(out, x)
