@@ -442,10 +442,16 @@ def bench_wide(a):
                      "traffic": profiled_traffic(a.workload, "tensor" if per_tensor else "batch", hdrs, a.layers == 0,
                                                  "ecfw_decode_kernel")},
     }
+    if a.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(7)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     if not a.no_cpu_baseline:
-        # the oracle's bit-serial reader on the first 2^20 elements of the first matrix, re-encoded on their own
+        # the oracle's bit-serial reader on the first 2^25 elements of the first matrix, re-encoded on their own
         # with the same code lengths
-        x = mats[0]["w"][: (1 << 20) * eb].cpu().numpy()
+        x = mats[0]["w"][: (1 << 25) * eb].cpu().numpy()
         x = x.view(np.uint16) if eb == 2 else x
         part = oracle.w_container_encode(fmt, x, 1, x.size, hdrs[0].lane_syms, hdrs[0].group_chunks, mats[0]["blob"].code_len())
         t0 = time.perf_counter()
@@ -453,7 +459,7 @@ def bench_wide(a):
         dt = time.perf_counter() - t0
         assert np.array_equal(dec, x)
         out["cpu_baseline"] = {"value": round(x.size * eb / dt / 1e9, 5), "unit": "GB/s", "cores": 1, "kind": "oracle",
-                               "sample": "oracle container reader on the first 2^20 elements of matrix 0 (%.1f s)" % dt}
+                               "sample": "oracle container reader on the first 2^25 elements of matrix 0 (%.1f s)" % dt}
     print(json.dumps(out))
 
 

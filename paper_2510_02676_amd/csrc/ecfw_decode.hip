@@ -494,6 +494,9 @@ int launch_fmt(const BArgs &a, uint32_t N, bool fast, uint32_t max_workgroups, h
     // the branch-free kernels at N = 64 need under 128 registers: 16 wavefronts hide more of the LDS latency
     if (N == 64 && fast) return launch_as<FMT, 64, 16, true>(a, max_workgroups, stream);
     if (N == 64) return launch_as<FMT, 64, 8, false>(a, max_workgroups, stream);
+    // E5M2 at N = 128 needs under 170 registers: three wavefronts per SIMD
+    if constexpr (FMT == ECFW_FMT_E5M2)
+        if (fast) return launch_as<FMT, 128, 12, true>(a, max_workgroups, stream);
     return fast ? launch_as<FMT, 128, 8, true>(a, max_workgroups, stream) : launch_as<FMT, 128, 8, false>(a, max_workgroups, stream);
 }
 
