@@ -258,6 +258,25 @@ def gemm_ref(X, W):
     return Y, A
 
 
+def gemm_ref_scaled(X, W, ws, xs=None):
+    """Y = (xs X) @ (ws W).T with one scale per 128 x 128 block of W and per row of X; returns (Y, sum |.|)."""
+    X = np.ascontiguousarray(X, dtype=np.uint8)
+    W = np.ascontiguousarray(W, dtype=np.uint8)
+    M, K = X.shape
+    N, K2 = W.shape
+    assert K == K2
+    ws = np.ascontiguousarray(ws, dtype=np.float32)
+    assert ws.shape == ((N + 127) // 128, (K + 127) // 128)
+    if xs is not None:
+        xs = np.ascontiguousarray(xs, dtype=np.float32)
+        assert xs.shape == (M,)
+    Y = np.zeros((M, N), dtype=np.float64)
+    A = np.zeros((M, N), dtype=np.float64)
+    lib().orc_gemm_ref_scaled(_p(X), _p(W), ctypes.c_uint64(M), ctypes.c_uint64(N), ctypes.c_uint64(K), _p(ws),
+                              _p(xs) if xs is not None else None, _p(Y), _p(A))
+    return Y, A
+
+
 # ---- wide alphabets (E5M2, BF16): ecfw_oracle.c ----
 
 FMT_E5M2, FMT_BF16 = 1, 2

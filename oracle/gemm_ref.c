@@ -42,3 +42,31 @@ void orc_gemm_ref(const uint8_t *X, const uint8_t *W, uint64_t M, uint64_t N, ui
             A[m * N + n] = mag;
         }
 }
+
+/*
+ * The same with block scales: W carries one scale per 128 x 128 block
+ * (ws[(n/128) * ceil(K/128) + k/128]), X one scale per row (xs[m], or NULL for
+ * ones); the dequantised product is
+ *   Y[m][n] = sum_k (xs[m] X[m][k]) * (ws[n/128][k/128] W[n][k]).
+ * Scales are given as binary32 and taken exactly; A is the same sum over
+ * absolute values.
+ */
+void orc_gemm_ref_scaled(const uint8_t *X, const uint8_t *W, uint64_t M, uint64_t N, uint64_t K,
+                         const float *ws, const float *xs, double *Y, double *A)
+{
+    double lut[256];
+    const uint64_t kb = (K + 127) / 128;
+    for (int i = 0; i < 256; i++) lut[i] = orc_e4m3_to_double((uint8_t)i);
+    for (uint64_t m = 0; m < M; m++)
+        for (uint64_t n = 0; n < N; n++) {
+            double acc = 0.0, mag = 0.0;
+            const uint8_t *x = X + m * K, *w = W + n * K;
+            for (uint64_t k = 0; k < K; k++) {
+                double p = ((xs ? (double)xs[m] : 1.0) * lut[x[k]]) * ((double)ws[(n / 128) * kb + k / 128] * lut[w[k]]);
+                acc += p;
+                mag += fabs(p);
+            }
+            Y[m * N + n] = acc;
+            A[m * N + n] = mag;
+        }
+}

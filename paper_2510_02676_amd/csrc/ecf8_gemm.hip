@@ -61,7 +61,21 @@ struct GArgs {
     uint64_t off_cb, off_lb, off_st, off_pl, st_bytes, off_tbl;
     uint8_t code_len[16];
     uint32_t M;
+    uint64_t d_ws, d_xs;                  // SCALED kernels: per-128x128-block scales of W, per-row scales of X (or 0)
 };
+
+constexpr int SCALE_BLOCK = 128;                // W carries one fp32 scale per 128 x 128 block
+constexpr int KBLOCKS = GK / SCALE_BLOCK;
+
+// acc += part * s, element by element, the same operation in the fused and in the raw kernel
+template <int MT>
+__device__ __forceinline__ void add_scaled(f32x4 (&acc)[MT], const f32x4 (&part)[MT], float s)
+{
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+        for (int r = 0; r < 4; r++) acc[mt][r] = __builtin_fmaf(part[mt][r], s, acc[mt][r]);
+}
 
 __device__ __forceinline__ long lo64(u32x4 v) { return (long)(((uint64_t)v.y << 32) | v.x); }
 __device__ __forceinline__ long hi64(u32x4 v) { return (long)(((uint64_t)v.w << 32) | v.z); }
@@ -107,7 +121,7 @@ __device__ __forceinline__ void load_x_slice(const GArgs &a, int tid,
 // Partial sums of the NW waves -> 16 x M outputs of block `block`.  `red` is the buffer of this
 // block's parity; the one barrier also orders its reuse two blocks later (a thread passes the
 // next block's barrier only after every thread has finished summing here).
-template <int MT, int NW>
+template <int MT, int NW, bool SCALED = false>
 __device__ __forceinline__ void reduce_block(f32x4 *red, const GArgs &a, uint64_t block, int tid, const f32x4 (&acc)[MT])
 {
     const int lane = tid & 63, wave = tid >> 6;
@@ -122,13 +136,17 @@ __device__ __forceinline__ void reduce_block(f32x4 *red, const GArgs &a, uint64_
 #pragma unroll
         for (int w = 0; w < NW; w++) sum += ((const float *)&red[(w * MT + mt) * 64 + l])[r];
         const uint32_t m = 16 * mt + 4 * (l >> 4) + r;
-        if (m < a.M) Y[(uint64_t)m * a.rows + block * BLOCK_ROWS + (l & 15)] = sum;
+        if (m < a.M) {
+            if (SCALED && a.d_xs) sum *= ((const GLOBAL float *)a.d_xs)[m];
+            Y[(uint64_t)m * a.rows + block * BLOCK_ROWS + (l & 15)] = sum;
+        }
     }
 }
 
-template <int MT, int NW, int N>
+template <int MT, int NW, int N, bool SCALED>
 __global__ __launch_bounds__(NW * 64) void ecf8_gemm_kernel(GArgs a)
 {
+    static_assert(!SCALED || 4 * N == 2 * SCALE_BLOCK, "a chunk spans two scale blocks of K");
     using C = GCfg<MT, NW, N>;
     constexpr int KPW = C::KPW, KCHUNKS = C::KCHUNKS, BLOCK_COLS = C::BLOCK_COLS;
     constexpr int GPIECES = C::PIECES, GSTAGE = C::STAGE, GSEGS = C::SEGS;
@@ -241,25 +259,42 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_kernel(GArgs a)
             }
             uint32_t bpA = stage_off * 8 + (uint32_t)(start - byte0 * 8) + rel - 1;   // one bit off, see quad_step2
             uint32_t bpB = bpA + m.lb - 30;
+            // SCALED: the chunk's two 128-column halves (forward run / backward run) are summed apart
+            // and enter the block's sum with the scale of their 128 x 128 block of W
+            f32x4 partA[SCALED ? MT : 1], partB[SCALED ? MT : 1];
+            float sA = 1.f, sB = 1.f;
+            if constexpr (SCALED) {
+                const GLOBAL float *ws = (const GLOBAL float *)a.d_ws + (block_of(s) * BLOCK_ROWS / SCALE_BLOCK) * KBLOCKS + 2 * kc_of(s);
+                sA = ws[0];
+                sB = ws[1];
+#pragma unroll
+                for (int mt = 0; mt < MT; mt++) partA[mt] = partB[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+            auto &dstA = *[&]() { if constexpr (SCALED) return &partA; else return &acc; }();
+            auto &dstB = *[&]() { if constexpr (SCALED) return &partB; else return &acc; }();
 #pragma unroll
             for (int Q = 0; Q < GPIECES / 2; Q++) {
                 uint32_t dwA[4], dwB[4];
 #pragma unroll
                 for (int t = 0; t < 4; t++) quad_step2<true>(smem, tbl, s_len, s_code, bpA, bpB, dwA[t], dwB[t]);
-                ECF8_MFMA_PIECE(acc, areg, i, Q, merge_piece(dwA, pl[Q]));
-                ECF8_MFMA_PIECE(acc, areg, i, Q + GPIECES / 2, merge_piece(dwB, pl[Q + GPIECES / 2]));
+                ECF8_MFMA_PIECE(dstA, areg, i, Q, merge_piece(dwA, pl[Q]));
+                ECF8_MFMA_PIECE(dstB, areg, i, Q + GPIECES / 2, merge_piece(dwB, pl[Q + GPIECES / 2]));
+            }
+            if constexpr (SCALED) {
+                add_scaled<MT>(acc, partA, sA);
+                add_scaled<MT>(acc, partB, sB);
             }
             m_cur = m_next;
             m_next = m_next2;
         }
-        reduce_block<MT, NW>((f32x4 *)(smem + C::OFF_RED + parity * C::RED_BYTES), a, block_of(s0), tid, acc);
+        reduce_block<MT, NW, SCALED>((f32x4 *)(smem + C::OFF_RED + parity * C::RED_BYTES), a, block_of(s0), tid, acc);
         parity ^= 1;
     }
 }
 
 // The same GEMM on uncompressed row-major W, with the fused kernel's workgroup shape, K split
 // and order of accumulation, so that the two agree bit for bit.
-template <int MT, int NW, int N>
+template <int MT, int NW, int N, bool SCALED>
 __global__ __launch_bounds__(NW * 64) void ecf8_gemm_raw_kernel(GArgs a)
 {
     using C = GCfg<MT, NW, N>;
@@ -291,15 +326,31 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_raw_kernel(GArgs a)
 #pragma unroll
             for (int q = 0; q < GPIECES; q++) w_next[q] = w_cur[q];
             if (s + 1 < n_steps) load_w(s + 1, w_next);
+            f32x4 partA[SCALED ? MT : 1], partB[SCALED ? MT : 1];
+            float sA = 1.f, sB = 1.f;
+            if constexpr (SCALED) {
+                const GLOBAL float *ws = (const GLOBAL float *)a.d_ws + (block_of(s) * BLOCK_ROWS / SCALE_BLOCK) * KBLOCKS +
+                                         2 * (wave + NW * (uint32_t)(s % KPW));
+                sA = ws[0];
+                sB = ws[1];
+#pragma unroll
+                for (int mt = 0; mt < MT; mt++) partA[mt] = partB[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+            auto &dstA = *[&]() { if constexpr (SCALED) return &partA; else return &acc; }();
+            auto &dstB = *[&]() { if constexpr (SCALED) return &partB; else return &acc; }();
 #pragma unroll
             for (int Q = 0; Q < GPIECES / 2; Q++) {
-                ECF8_MFMA_PIECE(acc, areg, i, Q, w_cur[Q]);
-                ECF8_MFMA_PIECE(acc, areg, i, Q + GPIECES / 2, w_cur[Q + GPIECES / 2]);
+                ECF8_MFMA_PIECE(dstA, areg, i, Q, w_cur[Q]);
+                ECF8_MFMA_PIECE(dstB, areg, i, Q + GPIECES / 2, w_cur[Q + GPIECES / 2]);
+            }
+            if constexpr (SCALED) {
+                add_scaled<MT>(acc, partA, sA);
+                add_scaled<MT>(acc, partB, sB);
             }
 #pragma unroll
             for (int q = 0; q < GPIECES; q++) w_cur[q] = w_next[q];
         }
-        reduce_block<MT, NW>((f32x4 *)(smem + parity * C::RED_BYTES), a, block_of(s0), tid, acc);
+        reduce_block<MT, NW, SCALED>((f32x4 *)(smem + parity * C::RED_BYTES), a, block_of(s0), tid, acc);
         parity ^= 1;
     }
 }
@@ -319,11 +370,8 @@ int check_gemm_args(uint64_t rows, uint64_t cols, const void *d_x, uint32_t M, c
     return ECF8_OK;
 }
 
-} // namespace
-
-extern "C" {
-
-int ecf8_gemm_fp8(const ecf8_header *h, const void *d_blob, const void *d_x, uint32_t M, float *d_y, void *stream)
+// Checks of the fused call's blob; fills the kernel arguments.
+int fused_args(const ecf8_header *h, const void *d_blob, const void *d_x, uint32_t M, float *d_y, GArgs *out)
 {
     if (!h || !d_blob) return ECF8_E_ARG;
     if (h->magic != ECF8_MAGIC || h->version != ECF8_VERSION || (h->table_bits != 0 && h->table_bits != ECF8_TB))
@@ -354,19 +402,11 @@ int ecf8_gemm_fp8(const ecf8_header *h, const void *d_blob, const void *d_x, uin
     a.off_tbl = h->table_bits ? 256 : 0;
     for (int i = 0; i < 16; i++) a.code_len[i] = h->code_len[i];
     a.M = M;
-    const int grid = grid_for(a.rows / BLOCK_ROWS);
-    if (grid <= 0) return ECF8_E_HIP;
-    hipStream_t s = (hipStream_t)stream;
-    // 16 waves (one K chunk of the block each) while X fits their registers, 8 waves of two chunks
-    // at M > 32.  (16 x 512 chunks with 8 waves were measured too: slower, 37.7 us against 25.5.)
-    if (M <= 16) hipLaunchKernelGGL((ecf8_gemm_kernel<1, 16, 64>), dim3(grid), dim3(16 * 64), 0, s, a);
-    else if (M <= 32) hipLaunchKernelGGL((ecf8_gemm_kernel<2, 16, 64>), dim3(grid), dim3(16 * 64), 0, s, a);
-    else hipLaunchKernelGGL((ecf8_gemm_kernel<4, 8, 64>), dim3(grid), dim3(8 * 64), 0, s, a);
-    return hipGetLastError() == hipSuccess ? ECF8_OK : ECF8_E_HIP;
+    *out = a;
+    return ECF8_OK;
 }
 
-int ecf8_gemm_fp8_raw(const void *d_w, uint64_t rows, uint64_t cols, const void *d_x, uint32_t M, float *d_y,
-                      void *stream)
+int raw_args(const void *d_w, uint64_t rows, uint64_t cols, const void *d_x, uint32_t M, float *d_y, GArgs *out)
 {
     if (!d_w) return ECF8_E_ARG;
     int rc = check_gemm_args(rows, cols, d_x, M, d_y);
@@ -378,13 +418,80 @@ int ecf8_gemm_fp8_raw(const void *d_w, uint64_t rows, uint64_t cols, const void 
     a.d_y = (uint64_t)(uintptr_t)d_y;
     a.rows = rows;
     a.M = M;
-    const int grid = grid_for(rows / BLOCK_ROWS);
+    *out = a;
+    return ECF8_OK;
+}
+
+int scale_args(const float *d_w_scale, const float *d_x_scale, GArgs *a)
+{
+    if (!d_w_scale) return ECF8_E_ARG;
+    if (((uintptr_t)d_w_scale & 3) || ((uintptr_t)d_x_scale & 3)) return ECF8_E_ALIGN;
+    a->d_ws = (uint64_t)(uintptr_t)d_w_scale;
+    a->d_xs = (uint64_t)(uintptr_t)d_x_scale;
+    return ECF8_OK;
+}
+
+// 16 waves (one K chunk of the block each) while X fits their registers, 8 waves of two chunks
+// at M > 32.  (16 x 512 chunks with 8 waves were measured too: slower, 37.7 us against 25.5.)
+template <bool SCALED>
+int launch_fused(const GArgs &a, void *stream)
+{
+    const int grid = grid_for(a.rows / BLOCK_ROWS);
     if (grid <= 0) return ECF8_E_HIP;
     hipStream_t s = (hipStream_t)stream;
-    if (M <= 16) hipLaunchKernelGGL((ecf8_gemm_raw_kernel<1, 16, 64>), dim3(grid), dim3(16 * 64), 0, s, a);
-    else if (M <= 32) hipLaunchKernelGGL((ecf8_gemm_raw_kernel<2, 16, 64>), dim3(grid), dim3(16 * 64), 0, s, a);
-    else hipLaunchKernelGGL((ecf8_gemm_raw_kernel<4, 8, 64>), dim3(grid), dim3(8 * 64), 0, s, a);
+    if (a.M <= 16) hipLaunchKernelGGL((ecf8_gemm_kernel<1, 16, 64, SCALED>), dim3(grid), dim3(16 * 64), 0, s, a);
+    else if (a.M <= 32) hipLaunchKernelGGL((ecf8_gemm_kernel<2, 16, 64, SCALED>), dim3(grid), dim3(16 * 64), 0, s, a);
+    else hipLaunchKernelGGL((ecf8_gemm_kernel<4, 8, 64, SCALED>), dim3(grid), dim3(8 * 64), 0, s, a);
     return hipGetLastError() == hipSuccess ? ECF8_OK : ECF8_E_HIP;
+}
+
+template <bool SCALED>
+int launch_raw(const GArgs &a, void *stream)
+{
+    const int grid = grid_for(a.rows / BLOCK_ROWS);
+    if (grid <= 0) return ECF8_E_HIP;
+    hipStream_t s = (hipStream_t)stream;
+    if (a.M <= 16) hipLaunchKernelGGL((ecf8_gemm_raw_kernel<1, 16, 64, SCALED>), dim3(grid), dim3(16 * 64), 0, s, a);
+    else if (a.M <= 32) hipLaunchKernelGGL((ecf8_gemm_raw_kernel<2, 16, 64, SCALED>), dim3(grid), dim3(16 * 64), 0, s, a);
+    else hipLaunchKernelGGL((ecf8_gemm_raw_kernel<4, 8, 64, SCALED>), dim3(grid), dim3(8 * 64), 0, s, a);
+    return hipGetLastError() == hipSuccess ? ECF8_OK : ECF8_E_HIP;
+}
+
+} // namespace
+
+extern "C" {
+
+int ecf8_gemm_fp8(const ecf8_header *h, const void *d_blob, const void *d_x, uint32_t M, float *d_y, void *stream)
+{
+    GArgs a;
+    int rc = fused_args(h, d_blob, d_x, M, d_y, &a);
+    return rc ? rc : launch_fused<false>(a, stream);
+}
+
+int ecf8_gemm_fp8_raw(const void *d_w, uint64_t rows, uint64_t cols, const void *d_x, uint32_t M, float *d_y,
+                      void *stream)
+{
+    GArgs a;
+    int rc = raw_args(d_w, rows, cols, d_x, M, d_y, &a);
+    return rc ? rc : launch_raw<false>(a, stream);
+}
+
+int ecf8_gemm_fp8_scaled(const ecf8_header *h, const void *d_blob, const void *d_x, uint32_t M, const float *d_w_scale,
+                         const float *d_x_scale, float *d_y, void *stream)
+{
+    GArgs a;
+    int rc = fused_args(h, d_blob, d_x, M, d_y, &a);
+    if (!rc) rc = scale_args(d_w_scale, d_x_scale, &a);
+    return rc ? rc : launch_fused<true>(a, stream);
+}
+
+int ecf8_gemm_fp8_raw_scaled(const void *d_w, uint64_t rows, uint64_t cols, const void *d_x, uint32_t M,
+                             const float *d_w_scale, const float *d_x_scale, float *d_y, void *stream)
+{
+    GArgs a;
+    int rc = raw_args(d_w, rows, cols, d_x, M, d_y, &a);
+    if (!rc) rc = scale_args(d_w_scale, d_x_scale, &a);
+    return rc ? rc : launch_raw<true>(a, stream);
 }
 
 } // extern "C"

@@ -129,3 +129,85 @@ def test_gemm_argument_errors():
     with pytest.raises(ecf8.Ecf8Error) as e:
         ecf8.ecf8_gemm_fp8(b.header, b.to(DEV), x)                      # codewords longer than 7 bits
     assert e.value.code == ecf8.E_ARG
+
+
+def _scales(rows, M, seed):
+    rng = np.random.default_rng(seed)
+    ws = np.exp(rng.normal(0.0, 0.7, size=((rows + 127) // 128, 32))).astype(np.float32)      # 2^-2 .. 2^2 or so
+    xs = np.exp(rng.normal(0.0, 0.5, size=M)).astype(np.float32)
+    return ws, xs
+
+
+@pytest.mark.parametrize("M", [1, 7, 16, 17, 32, 33, 64])
+def test_block_scaled_gemm_against_oracle(orc, M):
+    """One fp32 scale per 128 x 128 block of W and per row of X; rows = 208 leaves the second row of scale
+    blocks ragged.  Every 128-wide slice of K enters the sum through one fp32 multiply-add, which adds a
+    few 2^-24 relative to the matrix cores' own truncation: same tolerance as the unscaled case."""
+    rows, K = 208, 4096
+    w = synth.make_weight(rows, K, 1.7, 0.02, 5).numpy()
+    x = synth.activations(M, K, seed=100 + M).numpy()
+    ws, xs = _scales(rows, M, M)
+    d_w, d_x = torch.from_numpy(w).to(DEV), torch.from_numpy(x).to(DEV)
+    d_ws, d_xs = torch.from_numpy(ws).to(DEV), torch.from_numpy(xs).to(DEV)
+    blob = ecf8.ecf8_encode(w, rows, K, lane_syms=64, tile_rows=16)
+    d_blob = blob.to(DEV)
+    for use_xs in (True, False):
+        yref, mag = orc.gemm_ref_scaled(x, w, ws, xs if use_xs else None)
+        guard = torch.full((M + 2, rows), float("nan"), dtype=torch.float32, device=DEV)
+        y = ecf8.ecf8_gemm_fp8_scaled(blob.header, d_blob, d_x, d_ws, d_xs if use_xs else None, guard[1:M + 1])
+        raw = ecf8.ecf8_gemm_fp8_raw_scaled(d_w, d_x, d_ws, d_xs if use_xs else None)
+        torch.cuda.synchronize()
+        assert torch.isnan(guard[0]).all() and torch.isnan(guard[M + 1]).all()
+        _check(y.cpu().numpy(), yref, mag, "scaled fused M=%d" % M)
+        assert torch.equal(raw, y)           # same steps in the same order on the same bytes
+
+
+def test_block_scales_that_are_powers_of_two_scale_exactly():
+    """Doubling the scales of one column of scale blocks changes exactly that slice's contribution; doubling
+    all of them doubles every output bit for bit (fp32 multiply-adds by powers of two are exact)."""
+    rows, K, M = 256, 4096, 5
+    w = synth.make_weight(rows, K, 1.8, 0.02, 6).numpy()
+    x = synth.activations(M, K, seed=6).numpy()
+    blob = ecf8.ecf8_encode(w, rows, K, lane_syms=64, tile_rows=16)
+    d_blob, d_x = blob.to(DEV), torch.from_numpy(x).to(DEV)
+    ones = torch.ones((2, 32), dtype=torch.float32, device=DEV)
+    y1 = ecf8.ecf8_gemm_fp8_scaled(blob.header, d_blob, d_x, ones)
+    y2 = ecf8.ecf8_gemm_fp8_scaled(blob.header, d_blob, d_x, ones * 2)
+    y4 = ecf8.ecf8_gemm_fp8_scaled(blob.header, d_blob, d_x, ones, torch.full((M,), 4.0, device=DEV))
+    only_first_rows = ones.clone()
+    only_first_rows[1] = 0.0
+    y0 = ecf8.ecf8_gemm_fp8_scaled(blob.header, d_blob, d_x, only_first_rows)
+    torch.cuda.synchronize()
+    assert torch.equal(y2, y1 * 2) and torch.equal(y4, y1 * 4)
+    assert torch.equal(y0[:, :128], y1[:, :128]) and (y0[:, 128:] == 0).all()
+
+
+def test_block_scaled_full_size_and_argument_errors(orc):
+    spec = synth.config4()[0]
+    M = 16
+    w = synth.make(spec, 0, device=DEV)
+    x = synth.activations(M, 4096, seed=1, device=DEV)
+    ws, xs = _scales(spec["rows"], M, 9)
+    d_ws, d_xs = torch.from_numpy(ws).to(DEV), torch.from_numpy(xs).to(DEV)
+    blob = ecf8.ecf8_encode(w.cpu(), spec["rows"], spec["cols"], lane_syms=64, tile_rows=16)
+    d_blob = blob.to(DEV)
+    fused = ecf8.ecf8_gemm_fp8_scaled(blob.header, d_blob, x, d_ws, d_xs)
+    raw = ecf8.ecf8_gemm_fp8_raw_scaled(w, x, d_ws, d_xs)
+    torch.cuda.synchronize()
+    assert torch.equal(fused, raw)
+    cols = np.unique(np.concatenate([np.arange(100, 164), np.random.default_rng(2).integers(0, spec["rows"], 300),
+                                     np.arange(spec["rows"] - 16, spec["rows"])]))
+    wh = w.cpu().numpy()
+    # the oracle on the sampled rows of W: their scale rows are those of the rows' own blocks
+    yref = np.zeros((M, len(cols)))
+    mag = np.zeros((M, len(cols)))
+    for j, n in enumerate(cols):
+        yj, aj = orc.gemm_ref_scaled(x.cpu().numpy(), wh[n:n + 1], ws[n // 128:n // 128 + 1], xs)
+        yref[:, j], mag[:, j] = yj[:, 0], aj[:, 0]
+    _check(fused.cpu().numpy()[:, cols], yref, mag, "config4 scaled")
+    with pytest.raises(ecf8.Ecf8Error):
+        ecf8.ecf8_gemm_fp8_scaled(blob.header, d_blob, x, d_ws[:, :31].contiguous())      # scale table of the wrong shape
+    with pytest.raises(ecf8.Ecf8Error):
+        ecf8.ecf8_gemm_fp8_scaled(blob.header, d_blob, x, d_ws, d_xs[:5].contiguous())
+    with pytest.raises(ecf8.Ecf8Error):
+        ecf8.ecf8_gemm_fp8_scaled(blob.header, d_blob, x, d_ws.double())

@@ -37,3 +37,37 @@ def test_gemm_against_float64_matmul_and_hand_case(orc):
     X2 = rng.integers(0, 120, size=(2, 4), dtype=np.uint8)
     Y2, _ = orc.gemm_ref(X2, W2)
     assert Y2.shape == (2, 3)
+
+
+def test_scaled_gemm_against_dequantised_float64_matmul(orc):
+    """Block scales of W (128 x 128) and row scales of X: the reference equals the plain float64 product of
+    the dequantised matrices, written here with numpy broadcasting instead of the oracle's loops."""
+    rng = np.random.default_rng(1)
+    M, N, K = 3, 200, 384                     # two scale rows (the second ragged), three scale columns
+    X = rng.integers(0, 0x78, size=(M, K), dtype=np.uint8)
+    W = (rng.integers(0, 0x78, size=(N, K)) | (rng.integers(0, 2, size=(N, K)) << 7)).astype(np.uint8)
+    ws = rng.uniform(0.5, 2.0, size=(2, 3)).astype(np.float32)
+    xs = rng.uniform(0.1, 3.0, size=M).astype(np.float32)
+    xf = torch.from_numpy(X).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    wf = torch.from_numpy(W).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    wdq = wf * np.repeat(np.repeat(ws.astype(np.float64), 128, axis=0), 128, axis=1)[:N, :K]
+    xdq = xf * xs.astype(np.float64)[:, None]
+    Y, A = orc.gemm_ref_scaled(X, W, ws, xs)
+    assert np.allclose(Y, xdq @ wdq.T, rtol=1e-12, atol=0)
+    assert np.allclose(A, np.abs(xdq) @ np.abs(wdq).T, rtol=1e-12, atol=0)
+    # no row scales = ones; unit scales = the unscaled reference, exactly
+    Y1, _ = orc.gemm_ref_scaled(X, W, ws)
+    assert np.allclose(Y1, xf @ wdq.T, rtol=1e-12, atol=0)
+    Yu, Au = orc.gemm_ref_scaled(X, W, np.ones((2, 3), dtype=np.float32), np.ones(M, dtype=np.float32))
+    Y0, A0 = orc.gemm_ref(X, W)
+    assert np.array_equal(Yu, Y0) and np.array_equal(Au, A0)
+    # by hand: K = 256, x = 1 everywhere, w = 1 everywhere, scales 2 and 0.5 for the two halves of K, row scale 3
+    x = np.full((1, 256), 0x38, dtype=np.uint8)
+    w = np.full((1, 256), 0x38, dtype=np.uint8)
+    Yh, Ah = orc.gemm_ref_scaled(x, w, np.array([[2.0, 0.5]], dtype=np.float32), np.array([3.0], dtype=np.float32))
+    assert Yh[0, 0] == 3.0 * (128 * 2.0 + 128 * 0.5) and Ah[0, 0] == Yh[0, 0]
+    # a scale belongs to the block of ROWS n/128 and of COLUMNS k/128, not the other way round
+    ws2 = np.array([[1.0, 1.0, 1.0], [5.0, 1.0, 1.0]], dtype=np.float32)
+    Y2, _ = orc.gemm_ref_scaled(X, W, ws2)
+    Yb, _ = orc.gemm_ref_scaled(X, W, np.ones((2, 3), dtype=np.float32))
+    assert np.array_equal(Y2[:, :128], Yb[:, :128]) and not np.array_equal(Y2[:, 128:], Yb[:, 128:])
