@@ -267,7 +267,8 @@ int ecf8_decode_batched(const ecf8_batch_item *d_items, uint32_t n_tensors,
  *   Y[m][n] = sum_k X[m][k] * W[n][k]   (fp32 accumulate)
  * W: the rows x cols tensor held by the blob (hdr / d_blob as for ecf8_decode);
  * d_x: DEVICE, M x cols FP8 E4M3 bytes, row-major, 16-byte aligned, 1 <= M <= 64;
- * d_y: DEVICE, M x rows fp32, row-major.  Supported for now: cols == 4096, rows a
+ * d_y: DEVICE, M x rows fp32, row-major.  Supported for now: cols a multiple of 256
+ * (cols == 4096 keeps X in registers and is the fast case), rows a
  * multiple of 16, a blob in the row-tiled layout (tile_rows == 16) with
  * lane_syms == 64 and no codeword longer than 7 bits (the encoder's default
  * cap); ECF8_E_ARG otherwise.  Values are

@@ -62,6 +62,7 @@ struct GArgs {
     uint8_t code_len[16];
     uint32_t M;
     uint64_t d_ws, d_xs;                  // SCALED kernels: per-128x128-block scales of W, per-row scales of X (or 0)
+    uint64_t K;                           // any-K kernels: columns of W (a multiple of 256)
 };
 
 constexpr int SCALE_BLOCK = 128;                // W carries one fp32 scale per 128 x 128 block
@@ -355,6 +356,277 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_raw_kernel(GArgs a)
     }
 }
 
+// ---- any K (a multiple of 256) ----
+// The kernels above keep the wave's slice of X in registers, which is what makes K = 4096 fast
+// and what ties them to it.  These take any K: the K / 256 chunks of a block of rows are dealt
+// round-robin to the NW waves (some waves get one chunk fewer, or none when K / 256 < NW), and
+// the A operands of a chunk are fetched from X (L2-resident: M x K bytes) one chunk ahead, like
+// the chunk's payload.  Same decode, same MFMA order inside a chunk, same reduction.
+
+template <int MT, int N>
+struct XPieces { u32x4 v[MT][N / 16]; };
+
+// A operands for chunk kc: X[m][256 kc + 64 q + 16 g .. + 16) of lane (m = l % 16 (+ 16 mt), g = l / 16)
+template <int MT, int N>
+__device__ __forceinline__ void load_x_chunk(const GArgs &a, int lane, uint32_t kc, XPieces<MT, N> &x)
+{
+    const GLOBAL uint8_t *X = (const GLOBAL uint8_t *)a.d_x;
+    const int n = lane & 15, g = lane >> 4;
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+        for (int q = 0; q < N / 16; q++) {
+            const uint32_t m = 16 * mt + n;
+            x.v[mt][q] = u32x4{0, 0, 0, 0};
+            if (m < a.M) x.v[mt][q] = *(const GLOBAL u32x4 *)(X + (uint64_t)m * a.K + (uint64_t)kc * (4 * N) + 64 * q + 16 * g);
+        }
+}
+
+#define ECF8_MFMA_XPIECE(acc, x, p, w)                                                                   \
+    do {                                                                                                 \
+        const u32x4 w_ = (w);                                                                            \
+        _Pragma("unroll") for (int mt_ = 0; mt_ < MT; mt_++) {                                           \
+            acc[mt_] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(lo64(x.v[mt_][p]), lo64(w_), acc[mt_], 0, 0, 0); \
+            acc[mt_] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(hi64(x.v[mt_][p]), hi64(w_), acc[mt_], 0, 0, 0); \
+        }                                                                                                \
+    } while (0)
+
+// Position of a wave in its sequence of chunks: its i-th chunk of its b-th block of rows.
+struct Walk {
+    uint64_t b;
+    uint32_t i;
+};
+
+template <int MT, int NW, int N, bool SCALED>
+__global__ __launch_bounds__(NW * 64) void ecf8_gemm_anyk_kernel(GArgs a)
+{
+    using C = GCfg<MT, NW, N>;
+    constexpr int BLOCK_COLS = C::BLOCK_COLS, GPIECES = C::PIECES, GSTAGE = C::STAGE, GSEGS = C::SEGS;
+    static_assert(!SCALED || 4 * N == 2 * SCALE_BLOCK, "a chunk spans two scale blocks of K");
+    __shared__ __attribute__((aligned(16))) uint8_t smem[C::TOTAL];
+    uint16_t *tbl = (uint16_t *)(smem + C::OFF_TBL);
+    uint32_t *s_len = (uint32_t *)(smem + C::OFF_SYM);
+    uint32_t *s_code = s_len + 16;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t stage_off = C::OFF_STAGE + wave * GSTAGE;
+    uint8_t *stage = smem + stage_off;
+
+    const GLOBAL uint64_t *chunk_bit = (const GLOBAL uint64_t *)(a.d_blob + a.off_cb);
+    const GLOBAL uint16_t *lane_bits = (const GLOBAL uint16_t *)(a.d_blob + a.off_lb);
+    const GLOBAL uint8_t *stream = (const GLOBAL uint8_t *)(a.d_blob + a.off_st);
+    const GLOBAL uint8_t *plane = (const GLOBAL uint8_t *)(a.d_blob + a.off_pl);
+    const uint64_t lane_elem = (uint64_t)(lane & 15) * a.K + (uint64_t)(lane >> 4) * 16;
+    const uint32_t kchunks = (uint32_t)(a.K / BLOCK_COLS);
+    const uint32_t my_chunks = kchunks > (uint32_t)wave ? (kchunks - wave + NW - 1) / NW : 0;     // wave-uniform
+    const uint64_t n_blocks = a.rows / BLOCK_ROWS;
+    const uint64_t my_blocks = blockIdx.x < n_blocks ? (n_blocks - blockIdx.x + gridDim.x - 1) / gridDim.x : 0;
+
+    struct Meta { uint64_t b0, b1; uint32_t lb; };
+    struct Payload { u32x4 seg[GSEGS]; u32x2 pl[GPIECES]; };
+    auto block_of = [&](const Walk &w) -> uint64_t { return blockIdx.x + w.b * (uint64_t)gridDim.x; };
+    auto kc_of = [&](const Walk &w) -> uint32_t { return wave + NW * w.i; };
+    auto valid = [&](const Walk &w) { return my_chunks != 0 && w.b < my_blocks; };
+    auto next_of = [&](Walk w) { if (++w.i == my_chunks) { w.i = 0; w.b++; } return w; };
+    auto load_meta = [&](const Walk &w) {
+        const uint64_t c = block_of(w) * kchunks + kc_of(w);
+        Meta m;
+        m.b0 = chunk_bit[c];
+        m.b1 = chunk_bit[c + 1];
+        m.lb = lane_bits[c * 64 + lane];
+        return m;
+    };
+    auto span_of = [&](const Meta &m, uint64_t &byte0) {
+        uint64_t byte_end = ((m.b1 + 7) >> 3) + 8;
+        if (byte_end > a.st_bytes) byte_end = a.st_bytes;
+        byte0 = (m.b0 >> 3) & ~15ull;
+        if (byte0 > byte_end) byte0 = byte_end;
+        return byte_end - byte0;
+    };
+    auto load_payload = [&](const Walk &w, const Meta &m) {
+        Payload p;
+        uint64_t byte0;
+        const uint64_t span = span_of(m, byte0);
+        const uint64_t e0 = block_of(w) * BLOCK_ROWS * a.K + kc_of(w) * (uint64_t)BLOCK_COLS + lane_elem;
+#pragma unroll
+        for (int q = 0; q < GPIECES; q++)
+            p.pl[q] = __builtin_nontemporal_load((const GLOBAL u32x2 *)(plane + (e0 + 64 * q) / 2));
+#pragma unroll
+        for (int k = 0; k < GSEGS; k++) {
+            const uint32_t i = (lane + 64 * k) * 16;
+            p.seg[k] = u32x4{0, 0, 0, 0};
+            if (i < (uint32_t)GSTAGE && i < span)
+                p.seg[k] = __builtin_nontemporal_load((const GLOBAL u32x4 *)(stream + byte0 + i));
+        }
+        return p;
+    };
+
+    Walk cur{0, 0};
+    Meta m_cur{0, 0, 0}, m_next{0, 0, 0};
+    Payload p_cur;
+    XPieces<MT, N> x_cur;
+    if (valid(cur)) {
+        m_cur = load_meta(cur);
+        m_next = m_cur;
+        if (valid(next_of(cur))) m_next = load_meta(next_of(cur));
+        p_cur = load_payload(cur, m_cur);
+        load_x_chunk<MT, N>(a, lane, kc_of(cur), x_cur);
+    }
+
+    uint64_t len_lo, len_hi;
+    __builtin_memcpy(&len_lo, a.code_len, 8);
+    __builtin_memcpy(&len_hi, a.code_len + 8, 8);
+    if (a.off_tbl) {
+        const GLOBAL u32x4 *src = (const GLOBAL u32x4 *)(a.d_blob + a.off_tbl);
+        for (int i = tid; i < TBL_ENTRIES * 2 / 16; i += NW * 64) ((u32x4 *)tbl)[i] = src[i];
+        build_symbol_arrays(len_lo, len_hi, s_len, s_code, tid);
+        __syncthreads();
+    } else {
+        build_tables(len_lo, len_hi, tbl, s_len, s_code, (uint16_t *)(smem + C::OFF_STAGE), tid, NW * 64);
+    }
+
+    uint32_t parity = 0;
+    for (uint64_t b = 0; b < my_blocks; b++) {            // uniform for the workgroup: one barrier per block
+        f32x4 acc[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+        for (uint32_t i = 0; i < my_chunks; i++) {
+            const Meta m = m_cur;
+            uint64_t byte0;
+            span_of(m, byte0);
+            const uint32_t rel = wave_incl_scan(m.lb) - m.lb;
+            const uint64_t start = uniform64(m.b0);
+#pragma unroll
+            for (int k = 0; k < GSEGS; k++) {
+                const uint32_t j = (lane + 64 * k) * 16;
+                if (j < (uint32_t)GSTAGE) *(u32x4 *)(stage + j) = p_cur.seg[k];
+            }
+            u32x2 pl[GPIECES];
+#pragma unroll
+            for (int q = 0; q < GPIECES; q++) pl[q] = p_cur.pl[q];
+            const XPieces<MT, N> x = x_cur;
+            float sA = 1.f, sB = 1.f;
+            if constexpr (SCALED) {
+                const GLOBAL float *ws = (const GLOBAL float *)a.d_ws + (block_of(cur) * BLOCK_ROWS / SCALE_BLOCK) * (a.K / SCALE_BLOCK) +
+                                         2 * kc_of(cur);
+                sA = ws[0];
+                sB = ws[1];
+            }
+            // the payload registers are free: fetch the next chunk and its share of X, and the metadata of the one after
+            const Walk nxt = next_of(cur);
+            Meta m_next2 = m_next;
+            if (valid(nxt)) {
+                p_cur = load_payload(nxt, m_next);
+                load_x_chunk<MT, N>(a, lane, kc_of(nxt), x_cur);
+                if (valid(next_of(nxt))) m_next2 = load_meta(next_of(nxt));
+            }
+            uint32_t bpA = stage_off * 8 + (uint32_t)(start - byte0 * 8) + rel - 1;   // one bit off, see quad_step2
+            uint32_t bpB = bpA + m.lb - 30;
+            f32x4 partA[SCALED ? MT : 1], partB[SCALED ? MT : 1];
+            if constexpr (SCALED) {
+#pragma unroll
+                for (int mt = 0; mt < MT; mt++) partA[mt] = partB[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+            auto &dstA = *[&]() { if constexpr (SCALED) return &partA; else return &acc; }();
+            auto &dstB = *[&]() { if constexpr (SCALED) return &partB; else return &acc; }();
+#pragma unroll
+            for (int Q = 0; Q < GPIECES / 2; Q++) {
+                uint32_t dwA[4], dwB[4];
+#pragma unroll
+                for (int t = 0; t < 4; t++) quad_step2<true>(smem, tbl, s_len, s_code, bpA, bpB, dwA[t], dwB[t]);
+                ECF8_MFMA_XPIECE(dstA, x, Q, merge_piece(dwA, pl[Q]));
+                ECF8_MFMA_XPIECE(dstB, x, Q + GPIECES / 2, merge_piece(dwB, pl[Q + GPIECES / 2]));
+            }
+            if constexpr (SCALED) {
+                add_scaled<MT>(acc, partA, sA);
+                add_scaled<MT>(acc, partB, sB);
+            }
+            cur = nxt;
+            m_cur = m_next;
+            m_next = m_next2;
+        }
+        reduce_block<MT, NW, SCALED>((f32x4 *)(smem + C::OFF_RED + parity * C::RED_BYTES), a, blockIdx.x + b * (uint64_t)gridDim.x, tid, acc);
+        parity ^= 1;
+    }
+}
+
+// The any-K GEMM on uncompressed W: same deal of chunks, same order of accumulation.
+template <int MT, int NW, int N, bool SCALED>
+__global__ __launch_bounds__(NW * 64) void ecf8_gemm_raw_anyk_kernel(GArgs a)
+{
+    using C = GCfg<MT, NW, N>;
+    constexpr int BLOCK_COLS = C::BLOCK_COLS, GPIECES = C::PIECES;
+    __shared__ __attribute__((aligned(16))) uint8_t smem[2 * C::RED_BYTES];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const GLOBAL uint8_t *W = (const GLOBAL uint8_t *)a.d_w;
+    const uint64_t lane_elem = (uint64_t)(lane & 15) * a.K + (uint64_t)(lane >> 4) * 16;
+    const uint32_t kchunks = (uint32_t)(a.K / BLOCK_COLS);
+    const uint32_t my_chunks = kchunks > (uint32_t)wave ? (kchunks - wave + NW - 1) / NW : 0;
+    const uint64_t n_blocks = a.rows / BLOCK_ROWS;
+    const uint64_t my_blocks = blockIdx.x < n_blocks ? (n_blocks - blockIdx.x + gridDim.x - 1) / gridDim.x : 0;
+    auto block_of = [&](const Walk &w) -> uint64_t { return blockIdx.x + w.b * (uint64_t)gridDim.x; };
+    auto kc_of = [&](const Walk &w) -> uint32_t { return wave + NW * w.i; };
+    auto valid = [&](const Walk &w) { return my_chunks != 0 && w.b < my_blocks; };
+    auto next_of = [&](Walk w) { if (++w.i == my_chunks) { w.i = 0; w.b++; } return w; };
+    auto load_w = [&](const Walk &w, u32x4 (&v)[GPIECES]) {
+        const uint64_t e0 = block_of(w) * BLOCK_ROWS * a.K + kc_of(w) * (uint64_t)BLOCK_COLS + lane_elem;
+#pragma unroll
+        for (int q = 0; q < GPIECES; q++) v[q] = __builtin_nontemporal_load((const GLOBAL u32x4 *)(W + e0 + 64 * q));
+    };
+    Walk cur{0, 0};
+    u32x4 w_cur[GPIECES], w_next[GPIECES];
+    XPieces<MT, N> x_cur;
+    if (valid(cur)) {
+        load_w(cur, w_cur);
+        load_x_chunk<MT, N>(a, lane, kc_of(cur), x_cur);
+    }
+    uint32_t parity = 0;
+    for (uint64_t b = 0; b < my_blocks; b++) {
+        f32x4 acc[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+        for (uint32_t i = 0; i < my_chunks; i++) {
+            const XPieces<MT, N> x = x_cur;
+            float sA = 1.f, sB = 1.f;
+            if constexpr (SCALED) {
+                const GLOBAL float *ws = (const GLOBAL float *)a.d_ws + (block_of(cur) * BLOCK_ROWS / SCALE_BLOCK) * (a.K / SCALE_BLOCK) +
+                                         2 * kc_of(cur);
+                sA = ws[0];
+                sB = ws[1];
+            }
+            const Walk nxt = next_of(cur);
+#pragma unroll
+            for (int q = 0; q < GPIECES; q++) w_next[q] = w_cur[q];
+            if (valid(nxt)) {
+                load_w(nxt, w_next);
+                load_x_chunk<MT, N>(a, lane, kc_of(nxt), x_cur);
+            }
+            f32x4 partA[SCALED ? MT : 1], partB[SCALED ? MT : 1];
+            if constexpr (SCALED) {
+#pragma unroll
+                for (int mt = 0; mt < MT; mt++) partA[mt] = partB[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+            auto &dstA = *[&]() { if constexpr (SCALED) return &partA; else return &acc; }();
+            auto &dstB = *[&]() { if constexpr (SCALED) return &partB; else return &acc; }();
+#pragma unroll
+            for (int Q = 0; Q < GPIECES / 2; Q++) {
+                ECF8_MFMA_XPIECE(dstA, x, Q, w_cur[Q]);
+                ECF8_MFMA_XPIECE(dstB, x, Q + GPIECES / 2, w_cur[Q + GPIECES / 2]);
+            }
+            if constexpr (SCALED) {
+                add_scaled<MT>(acc, partA, sA);
+                add_scaled<MT>(acc, partB, sB);
+            }
+#pragma unroll
+            for (int q = 0; q < GPIECES; q++) w_cur[q] = w_next[q];
+            cur = nxt;
+        }
+        reduce_block<MT, NW, SCALED>((f32x4 *)(smem + parity * C::RED_BYTES), a, blockIdx.x + b * (uint64_t)gridDim.x, tid, acc);
+        parity ^= 1;
+    }
+}
+
 int grid_for(uint64_t n_blocks)
 {
     int cus = device_cus();
@@ -365,7 +637,7 @@ int grid_for(uint64_t n_blocks)
 int check_gemm_args(uint64_t rows, uint64_t cols, const void *d_x, uint32_t M, const void *d_y)
 {
     if (!d_x || !d_y || M == 0 || M > 64) return ECF8_E_ARG;
-    if (cols != GK || rows == 0 || rows % BLOCK_ROWS) return ECF8_E_ARG;
+    if (cols == 0 || cols % 256 || cols > (1u << 20) || rows == 0 || rows % BLOCK_ROWS) return ECF8_E_ARG;
     if (((uintptr_t)d_x & 15) || ((uintptr_t)d_y & 3)) return ECF8_E_ALIGN;
     return ECF8_OK;
 }
@@ -402,6 +674,7 @@ int fused_args(const ecf8_header *h, const void *d_blob, const void *d_x, uint32
     a.off_tbl = h->table_bits ? 256 : 0;
     for (int i = 0; i < 16; i++) a.code_len[i] = h->code_len[i];
     a.M = M;
+    a.K = h->cols;
     *out = a;
     return ECF8_OK;
 }
@@ -418,6 +691,7 @@ int raw_args(const void *d_w, uint64_t rows, uint64_t cols, const void *d_x, uin
     a.d_y = (uint64_t)(uintptr_t)d_y;
     a.rows = rows;
     a.M = M;
+    a.K = cols;
     *out = a;
     return ECF8_OK;
 }
@@ -439,6 +713,12 @@ int launch_fused(const GArgs &a, void *stream)
     const int grid = grid_for(a.rows / BLOCK_ROWS);
     if (grid <= 0) return ECF8_E_HIP;
     hipStream_t s = (hipStream_t)stream;
+    if (a.K != GK) {      // X does not stay in registers: fetched chunk by chunk
+        if (a.M <= 16) hipLaunchKernelGGL((ecf8_gemm_anyk_kernel<1, 16, 64, SCALED>), dim3(grid), dim3(16 * 64), 0, s, a);
+        else if (a.M <= 32) hipLaunchKernelGGL((ecf8_gemm_anyk_kernel<2, 8, 64, SCALED>), dim3(grid), dim3(8 * 64), 0, s, a);   // X pieces of two chunks: 8 waves' worth of registers
+        else hipLaunchKernelGGL((ecf8_gemm_anyk_kernel<4, 8, 64, SCALED>), dim3(grid), dim3(8 * 64), 0, s, a);
+        return hipGetLastError() == hipSuccess ? ECF8_OK : ECF8_E_HIP;
+    }
     if (a.M <= 16) hipLaunchKernelGGL((ecf8_gemm_kernel<1, 16, 64, SCALED>), dim3(grid), dim3(16 * 64), 0, s, a);
     else if (a.M <= 32) hipLaunchKernelGGL((ecf8_gemm_kernel<2, 16, 64, SCALED>), dim3(grid), dim3(16 * 64), 0, s, a);
     else hipLaunchKernelGGL((ecf8_gemm_kernel<4, 8, 64, SCALED>), dim3(grid), dim3(8 * 64), 0, s, a);
@@ -451,6 +731,12 @@ int launch_raw(const GArgs &a, void *stream)
     const int grid = grid_for(a.rows / BLOCK_ROWS);
     if (grid <= 0) return ECF8_E_HIP;
     hipStream_t s = (hipStream_t)stream;
+    if (a.K != GK) {
+        if (a.M <= 16) hipLaunchKernelGGL((ecf8_gemm_raw_anyk_kernel<1, 16, 64, SCALED>), dim3(grid), dim3(16 * 64), 0, s, a);
+        else if (a.M <= 32) hipLaunchKernelGGL((ecf8_gemm_raw_anyk_kernel<2, 8, 64, SCALED>), dim3(grid), dim3(8 * 64), 0, s, a);
+        else hipLaunchKernelGGL((ecf8_gemm_raw_anyk_kernel<4, 8, 64, SCALED>), dim3(grid), dim3(8 * 64), 0, s, a);
+        return hipGetLastError() == hipSuccess ? ECF8_OK : ECF8_E_HIP;
+    }
     if (a.M <= 16) hipLaunchKernelGGL((ecf8_gemm_raw_kernel<1, 16, 64, SCALED>), dim3(grid), dim3(16 * 64), 0, s, a);
     else if (a.M <= 32) hipLaunchKernelGGL((ecf8_gemm_raw_kernel<2, 16, 64, SCALED>), dim3(grid), dim3(16 * 64), 0, s, a);
     else hipLaunchKernelGGL((ecf8_gemm_raw_kernel<4, 8, 64, SCALED>), dim3(grid), dim3(8 * 64), 0, s, a);

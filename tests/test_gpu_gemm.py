@@ -102,9 +102,9 @@ def test_config4_full_size(orc, M):
 
 def test_gemm_argument_errors():
     x = torch.zeros((4, 4096), dtype=torch.uint8, device=DEV)
-    w = torch.zeros((32, 2048), dtype=torch.uint8, device=DEV)
+    w = torch.zeros((32, 2176), dtype=torch.uint8, device=DEV)
     with pytest.raises(ecf8.Ecf8Error) as e:
-        ecf8.ecf8_gemm_fp8_raw(w, x[:, :2048].contiguous())            # cols != 4096
+        ecf8.ecf8_gemm_fp8_raw(w, x[:, :2176].contiguous())            # cols not a multiple of 256
     assert e.value.code == ecf8.E_ARG
     w = torch.zeros((24, 4096), dtype=torch.uint8, device=DEV)
     with pytest.raises(ecf8.Ecf8Error):
@@ -211,3 +211,66 @@ def test_block_scaled_full_size_and_argument_errors(orc):
         ecf8.ecf8_gemm_fp8_scaled(blob.header, d_blob, x, d_ws, d_xs[:5].contiguous())
     with pytest.raises(ecf8.Ecf8Error):
         ecf8.ecf8_gemm_fp8_scaled(blob.header, d_blob, x, d_ws.double())
+
+
+@pytest.mark.parametrize("M", [1, 16, 17, 33, 64])
+@pytest.mark.parametrize("rows,K", [(48, 256), (32, 512), (128, 2048), (64, 5120), (48, 7168), (80, 14336)])
+def test_any_k_against_oracle(orc, rows, K, M):
+    """K other than 4096 (any multiple of 256): fewer chunks than waves (K = 256 .. 2048), an uneven deal
+    (K = 5120: 20 chunks over 16 waves; K = 14336: 56), the down-projection's K = 14336."""
+    w = synth.make_weight(rows, K, 1.7, 0.02, 7).numpy()
+    x = synth.activations(M, K, seed=200 + M).numpy()
+    yref, mag = orc.gemm_ref(x, w)
+    blob = ecf8.ecf8_encode(w, rows, K, lane_syms=64, tile_rows=16)
+    d_x, d_w = torch.from_numpy(x).to(DEV), torch.from_numpy(w).to(DEV)
+    guard = torch.full((M + 2, rows), float("nan"), dtype=torch.float32, device=DEV)
+    print("any K: rows", rows, "K", K, "M", M, flush=True)
+    y = ecf8.ecf8_gemm_fp8(blob.header, blob.to(DEV), d_x, guard[1:M + 1])
+    raw = ecf8.ecf8_gemm_fp8_raw(d_w, d_x)
+    torch.cuda.synchronize()
+    assert torch.isnan(guard[0]).all() and torch.isnan(guard[M + 1]).all()
+    # short sums do not average the matrix cores' truncation out: the worst-case bound applies below K = 4096
+    _check(y.cpu().numpy(), yref, mag, "any-K fused %dx%d M=%d" % (rows, K, M), rel=TOL if K >= 4096 else 7 * 2.0 ** -13)
+    assert torch.equal(raw, y)
+    # operands whose products and sums are exact in fp32 whatever the order and alignment (values 0, +-0.5, +-1,
+    # +-2): the result must equal the reference exactly
+    rng = np.random.default_rng(K + M)
+    vals = np.array([0x00, 0x30, 0xB0, 0x38, 0xB8, 0x40, 0xC0], dtype=np.uint8)
+    w2 = vals[rng.integers(0, len(vals), size=(rows, K))]
+    x2 = vals[rng.integers(0, len(vals), size=(M, K))]
+    yref2, _ = orc.gemm_ref(x2, w2)
+    blob2 = ecf8.ecf8_encode(w2, rows, K, lane_syms=64, tile_rows=16)
+    y2 = ecf8.ecf8_gemm_fp8(blob2.header, blob2.to(DEV), torch.from_numpy(x2).to(DEV))
+    torch.cuda.synchronize()
+    assert np.array_equal(y2.cpu().numpy().astype(np.float64), yref2)
+
+
+@pytest.mark.parametrize("M", [3, 40])
+def test_any_k_block_scaled_and_full_size(orc, M):
+    """The down projection of the 8B-class stack (4096 x 14336) with block scales: fused equals the twin on
+    uncompressed weights bit for bit; sampled outputs against the oracle."""
+    rows, K = 4096, 14336
+    w = synth.make_weight(rows, K, 1.8, 0.02, 8, device=DEV)
+    x = synth.activations(M, K, seed=300 + M, device=DEV)
+    rng = np.random.default_rng(M)
+    ws = np.exp(rng.normal(0.0, 0.7, size=(rows // 128, K // 128))).astype(np.float32)
+    xs = np.exp(rng.normal(0.0, 0.5, size=M)).astype(np.float32)
+    d_ws, d_xs = torch.from_numpy(ws).to(DEV), torch.from_numpy(xs).to(DEV)
+    blob = ecf8.ecf8_encode(w.cpu(), rows, K, lane_syms=64, tile_rows=16)
+    d_blob = blob.to(DEV)
+    fused = ecf8.ecf8_gemm_fp8_scaled(blob.header, d_blob, x, d_ws, d_xs)
+    raw = ecf8.ecf8_gemm_fp8_raw_scaled(w, x, d_ws, d_xs)
+    plain = ecf8.ecf8_gemm_fp8(blob.header, d_blob, x)
+    plain_raw = ecf8.ecf8_gemm_fp8_raw(w, x)
+    torch.cuda.synchronize()
+    assert torch.equal(fused, raw) and torch.equal(plain, plain_raw)
+    cols = np.unique(np.concatenate([np.arange(0, 20), rng.integers(0, rows, 100), np.arange(rows - 16, rows)]))
+    wh, xh = w.cpu().numpy(), x.cpu().numpy()
+    yref, mag = orc.gemm_ref(xh, wh[cols])
+    _check(plain.cpu().numpy()[:, cols], yref, mag, "down projection")
+    yref = np.zeros((M, len(cols)))
+    mag = np.zeros((M, len(cols)))
+    for j, n in enumerate(cols):
+        yj, aj = orc.gemm_ref_scaled(xh, wh[n:n + 1], ws[n // 128:n // 128 + 1], xs)
+        yref[:, j], mag[:, j] = yj[:, 0], aj[:, 0]
+    _check(fused.cpu().numpy()[:, cols], yref, mag, "down projection, block scales")
