@@ -257,3 +257,22 @@ def test_stream_longer_than_2_to_the_31_bits(fmt):
     ecfw.ecfw_decode(d_blob, blob.header, out)
     torch.cuda.synchronize()
     assert torch.equal(out, x)
+
+
+@pytest.mark.parametrize("fmt", [E5M2, BF16])
+def test_seeded_sweep(orc, fmt):
+    """Sixty seeded combinations of size, chunk shape, group width, cap and spread of the exponent field per format."""
+    rng = np.random.default_rng(4242 + fmt)
+    for case in range(60):
+        n = int(rng.choice([rng.integers(1, 200), rng.integers(200, 20000), rng.integers(20000, 400000)]))
+        lane_syms = int(rng.choice([64, 128]))
+        group = int(2 ** rng.integers(0, 7))
+        spread = float(rng.uniform(0.3, 9.0))
+        x = _rand_elems(fmt, n, 9000 + case, spread=spread)
+        distinct = len(np.unique((x >> 7) & 255 if fmt == BF16 else (x >> 2) & 31))
+        low = max(1, int(np.ceil(np.log2(max(distinct, 2)))))
+        cap = int(rng.choice([0, rng.integers(low, 17)]))
+        if cap and cap < low:
+            cap = low
+        wgs = int(rng.choice([0, 0, 1, 5, 64]))
+        _check(orc, fmt, x, lane_syms=lane_syms, group_chunks=group, max_code_len=cap, max_workgroups=wgs)

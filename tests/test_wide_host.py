@@ -150,3 +150,35 @@ def test_error_paths():
         ecfw.blob_describe(bad)                         # structure intact ...
         with pytest.raises(ecf8.Ecf8Error):
             ecfw.blob_validate(bad)                     # ... metadata or padding is not
+
+
+def test_batch_prepare_checks_on_the_host():
+    """ecfw_batch_prepare runs on the host alone: running chunk offsets, the launch facts, and the refusals."""
+    import ctypes
+    xs = [_rand_elems(BF16, n, n) for n in (5000, 70000, 9)]
+    blobs = [ecfw.ecfw_encode(BF16, x, max_code_len=c) for x, c in zip(xs, (0, 14, 0))]
+    n = len(blobs)
+    H = (ecfw.WHeader * n)(*[b.header for b in blobs])
+    fake = [0x7f0000000000 + 0x10000000 * i for i in range(n)]          # never dereferenced by prepare
+    B = (ctypes.c_void_p * n)(*fake)
+    O = (ctypes.c_void_p * n)(*[f + 0x1000000 for f in fake])
+    C = (ctypes.c_uint64 * n)(*[2 * b.header.n_elem for b in blobs])
+    items = (ecfw.WBatchItem * n)()
+    info = ecfw.WBatchInfo()
+    lib = ecfw._lib
+    assert lib.ecfw_batch_prepare(H, B, O, C, n, items, ctypes.byref(info)) == 0
+    assert info.total_chunks == sum(b.header.n_chunks for b in blobs) and info.fmt == BF16 and info.lane_syms == 64
+    assert info.max_code_len == max(b.header.max_code_len for b in blobs)
+    run = 0
+    for it, b in zip(items, blobs):
+        assert it.first_chunk == run and it.n_chunks == b.header.n_chunks and it.off_stream == b.header.off_stream
+        run += b.header.n_chunks
+    C[1] -= 1
+    assert lib.ecfw_batch_prepare(H, B, O, C, n, items, ctypes.byref(info)) == ecf8.E_CAPACITY
+    C[1] += 1
+    O[2] = O[2] + 8
+    assert lib.ecfw_batch_prepare(H, B, O, C, n, items, ctypes.byref(info)) == ecf8.E_ALIGN
+    O[2] = O[2] - 8
+    H[0].lane_syms = 128
+    assert lib.ecfw_batch_prepare(H, B, O, C, n, items, ctypes.byref(info)) != 0
+    assert lib.ecfw_batch_prepare(H, B, O, C, 0, items, ctypes.byref(info)) == ecf8.E_ARG
