@@ -118,8 +118,8 @@ __device__ __forceinline__ void build_symbol_arrays(uint64_t len_lo, uint64_t le
     }
 }
 
-__device__ void build_tables(uint64_t len_lo, uint64_t len_hi, uint16_t *tbl, uint32_t *s_len, uint32_t *s_code,
-                             uint16_t *tmp, int tid, int nthreads)
+__device__ __attribute__((unused)) void build_tables(uint64_t len_lo, uint64_t len_hi, uint16_t *tbl, uint32_t *s_len,
+                                                     uint32_t *s_code, uint16_t *tmp, int tid, int nthreads)
 {
     build_symbol_arrays(len_lo, len_hi, s_len, s_code, tid);
     for (int i = tid; i < TBL_ENTRIES; i += nthreads) tmp[i] = 0;
