@@ -48,13 +48,20 @@ template <> struct Fmt<ECFW_FMT_BF16> {
     static constexpr int SYM_SHIFT = 7, LEN_SHIFT = 0;     // entry = exponent << 7 | length
 };
 
-template <int FMT, int N, int WAVES>
+// COLS: after the chunk's span has landed in LDS, every lane copies the dwords of its own bits into a
+// column of its own (dword r of lane l at row r, column l: bank l % 32), so that the two window
+// reads of every decode step are free of bank conflicts; the copy reads each dword once instead.
+template <int FMT, int N, int WAVES, bool COLS>
 struct WCfg {
     using F = Fmt<FMT>;
     static constexpr int PIECES = N / F::P;                 // 16-byte pieces per lane
-    static constexpr int STAGE = 64 * N + 64;               // span of a chunk whose codewords average 8 bits: anything
-                                                            // up to uniformly random exponent fields fits
+    // span of a chunk whose codewords average AVG bits: uniformly random exponent fields still fit
+    static constexpr int AVG = COLS ? (FMT == ECFW_FMT_BF16 ? 8 : 5) : 8;
+    static constexpr int STAGE = 8 * AVG * N + 64;
     static constexpr int SEGS = (STAGE / 16 + 63) / 64;
+    // rows of a lane's column: its bits at up to AVG + 1/2 bits per codeword, the dword before, the
+    // dword after, and the misalignment of its first bit
+    static constexpr int ROWS = COLS ? ((2 * AVG + 1) * N / 64 + 3) : 0;
     static constexpr int OFF_TBL = 0;
     static constexpr int OFF_WCNT = OFF_TBL + (2 << WTB);   // symbols per (wavefront, length) while the code is set up
     static constexpr int OFF_SORTED = OFF_WCNT + 320;       // symbols ordered by (length, symbol)
@@ -62,8 +69,10 @@ struct WCfg {
     static constexpr int OFF_FIRST = OFF_CNT + 80;
     static constexpr int OFF_OFFS = OFF_FIRST + 80;
     static constexpr int OFF_TICKET = OFF_OFFS + 80;
-    static constexpr int OFF_STAGE = OFF_TICKET + 16;
-    static constexpr int TOTAL = OFF_STAGE + WAVES * STAGE;
+    static constexpr int OFF_STAGE = OFF_TICKET + 16 + 16;  // one spare slot below: a column's first row is the dword
+                                                            // before the lane's first one
+    static constexpr int OFF_COLS = OFF_STAGE + WAVES * STAGE;
+    static constexpr int TOTAL = OFF_COLS + WAVES * ROWS * 256;
     static_assert(STAGE % 16 == 0 && OFF_STAGE % 16 == 0, "16-byte LDS stores");
     static_assert(PIECES % 2 == 0, "two runs of whole pieces");
     static_assert(TOTAL <= 160 * 1024, "LDS of one gfx950 CU");
@@ -162,6 +171,19 @@ __device__ __noinline__ uint32_t long_code(uint32_t bits, const uint8_t *sorted,
     return e;
 }
 
+// Largest value of x over the wavefront (every lane gets it).
+__device__ __forceinline__ uint32_t wave_max(uint32_t x)
+{
+    uint32_t v = x;
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, 0x111, 0xf, 0xf, false));   // row_shr:1
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, 0x112, 0xf, 0xf, false));   // row_shr:2
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, 0x114, 0xf, 0xf, false));   // row_shr:4
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, 0x118, 0xf, 0xf, false));   // row_shr:8
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, 0x142, 0xa, 0xf, false));   // row_bcast:15
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, 0x143, 0xc, 0xf, false));   // row_bcast:31
+    return (uint32_t)__builtin_amdgcn_readlane(v, 63);
+}
+
 template <int FMT, bool FAST>
 __device__ __forceinline__ uint32_t decode_entry(uint32_t bits, const CodeArrays &ca)
 {
@@ -174,14 +196,18 @@ __device__ __forceinline__ uint32_t decode_entry(uint32_t bits, const CodeArrays
 // pb = (one past the next bit of the backward run) - 31 as absolute LDS bit
 // addresses: the windows read there are the stream bits shifted left by one,
 // which masked is the byte offset of a table entry.
-template <int FMT, bool FAST>
+// COLS: pa and pb count bits inside the lane's column (row = bit / 32), `smem` points at the lane's
+// slot of row 0, and consecutive dwords of the lane lie 256 bytes apart.
+template <int FMT, bool FAST, bool COLS>
 __device__ __forceinline__ void pair_step(const uint8_t *smem, const CodeArrays &ca, uint32_t &pa, uint32_t &pb,
                                           uint32_t &eA0, uint32_t &eA1, uint32_t &eB0, uint32_t &eB1)
 {
+    static_assert(!COLS || FAST, "the long-code branch reads windows from the linear stage");
     const uint8_t *tb = (const uint8_t *)ca.tbl;
-    const uint32_t aA = (pa >> 3) & ~3u, aB = (pb >> 3) & ~3u;
-    const uint32_t wA = __builtin_amdgcn_alignbit(*(const uint32_t *)(smem + aA + 4), *(const uint32_t *)(smem + aA), pa);
-    const uint32_t wB = __brev(__builtin_amdgcn_alignbit(*(const uint32_t *)(smem + aB + 4), *(const uint32_t *)(smem + aB), pb));
+    constexpr uint32_t NEXT = COLS ? 256 : 4;
+    const uint32_t aA = COLS ? (pa >> 5) << 8 : (pa >> 3) & ~3u, aB = COLS ? (pb >> 5) << 8 : (pb >> 3) & ~3u;
+    const uint32_t wA = __builtin_amdgcn_alignbit(*(const uint32_t *)(smem + aA + NEXT), *(const uint32_t *)(smem + aA), pa);
+    const uint32_t wB = __brev(__builtin_amdgcn_alignbit(*(const uint32_t *)(smem + aB + NEXT), *(const uint32_t *)(smem + aB), pb));
     eA0 = *(const uint16_t *)(tb + (wA & WMASK2));
     eB0 = *(const uint16_t *)(tb + (wB & WMASK2));
     uint32_t lA0 = entry_len<FMT>(eA0), lB0 = entry_len<FMT>(eB0);
@@ -244,9 +270,10 @@ __device__ __forceinline__ u32x4 merge_e5m2(const uint32_t e[16], uint32_t mant,
 template <int FMT, int N, int WAVES, bool FAST>
 __global__ __launch_bounds__(WAVES * 64) void ecfw_decode_kernel(BArgs b)
 {
-    using C = WCfg<FMT, N, WAVES>;
+    constexpr bool COLS = FAST;
+    using C = WCfg<FMT, N, WAVES, COLS>;
     using F = Fmt<FMT>;
-    constexpr int PIECES = C::PIECES, SEGS = C::SEGS, STAGE = C::STAGE, P = F::P;
+    constexpr int PIECES = C::PIECES, SEGS = C::SEGS, STAGE = C::STAGE, P = F::P, ROWS = C::ROWS;
     __shared__ __attribute__((aligned(16))) uint8_t smem[C::TOTAL];
     uint16_t *tbl = (uint16_t *)(smem + C::OFF_TBL);
     uint32_t *s_ticket = (uint32_t *)(smem + C::OFF_TICKET);
@@ -256,6 +283,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecfw_decode_kernel(BArgs b)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t stage_off = C::OFF_STAGE + wave * STAGE;
     uint8_t *stage = smem + stage_off;
+    uint8_t *column = smem + C::OFF_COLS + wave * (ROWS * 256) + lane * 4;      // this lane's slot of row 0
 
     // contiguous range of chunks for this workgroup, cut at multiples of 64 chunks when there is
     // enough work so that the waves of a workgroup share the interleaved groups of the layout
@@ -404,7 +432,12 @@ __global__ __launch_bounds__(WAVES * 64) void ecfw_decode_kernel(BArgs b)
         const Meta m = m_cur;
         uint64_t byte0;
         const uint64_t span = span_of(m, byte0);
-        const bool careful = span > (uint64_t)STAGE || (cur + 1) * E > a.n_elem;    // uniform
+        const uint32_t rel = wave_incl_scan(m.lb) - m.lb;
+        const uint64_t start = uniform64(m.b0);
+        const uint32_t first_bit = (uint32_t)(start - byte0 * 8) + rel;           // this lane's first bit, counted from byte0
+        // COLS: rows this lane's bits take (with the dword before and the one after), and the most any lane takes
+        const uint32_t rows_used = COLS ? wave_max(((32 + (first_bit & 31) + m.lb) >> 5) + 2) : 0;
+        const bool careful = span > (uint64_t)STAGE || (cur + 1) * E > a.n_elem || rows_used > (uint32_t)ROWS;    // uniform
         if (!careful) {
 #pragma unroll
             for (int k = 0; k < SEGS; k++) {
@@ -430,10 +463,18 @@ __global__ __launch_bounds__(WAVES * 64) void ecfw_decode_kernel(BArgs b)
         if (careful) {
             symbol_pass(cur, m);
         } else {
-            const uint32_t rel = wave_incl_scan(m.lb) - m.lb;
-            const uint64_t start = uniform64(m.b0);
-            uint32_t pa = stage_off * 8 + (uint32_t)(start - byte0 * 8) + rel - 1;    // one bit off, see pair_step
+            uint32_t pa = stage_off * 8 + first_bit - 1;    // one bit off, see pair_step
+            if constexpr (COLS) {
+                // row r of the column = dword (first_bit / 32) - 1 + r of the stage (row 0 of a lane that starts in the
+                // stage's first dword is the spare slot below the stage)
+                const uint8_t *src = stage + ((first_bit >> 5) << 2) - 4;
+#pragma unroll
+                for (int r = 0; r < ROWS; r++)
+                    if ((uint32_t)r < rows_used) *(uint32_t *)(column + r * 256) = *(const uint32_t *)(src + r * 4);
+                pa = 32 + (first_bit & 31) - 1;
+            }
             uint32_t pb = pa + m.lb - 30;
+            const uint8_t *bits = COLS ? column : smem;
             GLOBAL uint8_t *dst = out + (chunk_base(cur) + (uint64_t)lane * P) * F::ELEM;
             const uint64_t stride_bytes = chunk_stride(cur) * F::ELEM;
             // finished pieces wait in registers and leave in bursts of eight (8 KiB per wavefront)
@@ -448,7 +489,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecfw_decode_kernel(BArgs b)
                     uint32_t eA[P], eB[P];
 #pragma unroll
                     for (int t = 0; t < P / 2; t++)
-                        pair_step<FMT, FAST>(smem, ca, pa, pb, eA[2 * t], eA[2 * t + 1], eB[2 * t], eB[2 * t + 1]);
+                        pair_step<FMT, FAST, COLS>(bits, ca, pa, pb, eA[2 * t], eA[2 * t + 1], eB[2 * t], eB[2 * t + 1]);
                     if constexpr (FMT == ECFW_FMT_BF16) {
                         pieceA[i] = merge_bf16(eA, pl[q]);
                         pieceB[i] = merge_bf16(eB, pl[q + PIECES / 2]);
