@@ -60,6 +60,19 @@ __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x)
     return v;
 }
 
+// Largest value of x over the wavefront (every lane gets it).
+__device__ __forceinline__ uint32_t wave_max(uint32_t x)
+{
+    uint32_t v = x;
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, 0x111, 0xf, 0xf, false));   // row_shr:1
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, 0x112, 0xf, 0xf, false));   // row_shr:2
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, 0x114, 0xf, 0xf, false));   // row_shr:4
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, 0x118, 0xf, 0xf, false));   // row_shr:8
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, 0x142, 0xa, 0xf, false));   // row_bcast:15
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, 0x143, 0xc, 0xf, false));   // row_bcast:31
+    return (uint32_t)__builtin_amdgcn_readlane(v, 63);
+}
+
 // A codeword longer than TB bits (rarer than 2^-TB): match the next 15 stream
 // bits against the long canonical codes.  Returns exponent | length << 8.
 __device__ __noinline__ uint32_t decode_long(uint32_t bits, const uint32_t *s_len, const uint32_t *s_code)

@@ -171,19 +171,6 @@ __device__ __noinline__ uint32_t long_code(uint32_t bits, const uint8_t *sorted,
     return e;
 }
 
-// Largest value of x over the wavefront (every lane gets it).
-__device__ __forceinline__ uint32_t wave_max(uint32_t x)
-{
-    uint32_t v = x;
-    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, 0x111, 0xf, 0xf, false));   // row_shr:1
-    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, 0x112, 0xf, 0xf, false));   // row_shr:2
-    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, 0x114, 0xf, 0xf, false));   // row_shr:4
-    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, 0x118, 0xf, 0xf, false));   // row_shr:8
-    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, 0x142, 0xa, 0xf, false));   // row_bcast:15
-    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0u, v, 0x143, 0xc, 0xf, false));   // row_bcast:31
-    return (uint32_t)__builtin_amdgcn_readlane(v, 63);
-}
-
 template <int FMT, bool FAST>
 __device__ __forceinline__ uint32_t decode_entry(uint32_t bits, const CodeArrays &ca)
 {
