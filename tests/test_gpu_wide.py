@@ -276,3 +276,37 @@ def test_seeded_sweep(orc, fmt):
             cap = low
         wgs = int(rng.choice([0, 0, 1, 5, 64]))
         _check(orc, fmt, x, lane_syms=lane_syms, group_chunks=group, max_code_len=cap, max_workgroups=wgs)
+
+
+@pytest.mark.parametrize("fmt", [E5M2, BF16])
+def test_one_lane_of_long_codes_and_dense_islands(orc, fmt):
+    """Under the default cap (branch-free kernels, bits staged in per-lane columns): single lanes whose 12-bit
+    codewords overflow their column while the chunk's span is ordinary, and whole chunks of rare fields whose
+    span overflows the stage; both must fall back to the careful pass."""
+    N = 64 if fmt == BF16 else 128
+    P = 8 if fmt == BF16 else 16
+    A = 256 if fmt == BF16 else 32
+    centre = 120 if fmt == BF16 else 14
+    rng = np.random.default_rng(77 + fmt)
+    n = 64 * N * 40
+    e = np.clip(np.rint(rng.normal(centre, 0.8, n)), 0, A - 1).astype(np.int64)
+    common = np.unique(e)
+    rare = np.setdiff1d(np.arange(A), np.arange(centre - 4, centre + 5))
+    e[:rare.size] = rare                                           # every rare field occurs (a few times only)
+    chunk = 64 * N
+    for c, lane in ((5, 7), (5, 63), (17, 0)):                     # one lane of a chunk: its N symbols are rare
+        idx = c * chunk + (np.arange(N) // P) * (64 * P) + lane * P + np.arange(N) % P
+        e[idx] = rng.choice(rare, N)
+    for c in (9, 30):                                              # whole chunks of rare fields
+        e[c * chunk:(c + 1) * chunk] = rng.choice(rare, chunk)
+    e = e.astype(np.uint16 if fmt == BF16 else np.uint8)
+    if fmt == BF16:
+        x = ((rng.integers(0, 2, n).astype(np.uint16) << 15) | (e << 7) | rng.integers(0, 128, n).astype(np.uint16))
+    else:
+        x = ((rng.integers(0, 2, n).astype(np.uint8) << 7) | (e << 2) | rng.integers(0, 4, n).astype(np.uint8))
+    blob = _check(orc, fmt, x, lane_syms=N, group_chunks=1)
+    h, arr = blob.header, blob.numpy()
+    assert h.max_code_len <= 12
+    lb = np.frombuffer(arr[h.off_lane_bits:h.off_lane_bits + 128 * h.n_chunks].tobytes(), "<u2").reshape(-1, 64)
+    assert lb[5, 7] > 2 * np.median(lb) and lb[9].sum() > 2 * np.median(lb.sum(axis=1))    # the cases are what they claim
+    _check(orc, fmt, x, lane_syms=N, group_chunks=4)
