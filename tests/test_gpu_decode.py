@@ -337,3 +337,13 @@ def test_stream_longer_than_2_to_the_31_bits():
     ecf8.ecf8_decode(blob.header, d_blob, out)
     torch.cuda.synchronize()
     assert torch.equal(out, x)
+
+
+def test_e5m2_bytes_through_this_codec(orc):
+    """The codec never interprets its bytes: E5M2 weights go through unchanged (coded by the upper four bits of
+    their exponent field, the lowest one kept raw in the nibble plane) and come back exact."""
+    w = synth.make_e5m2(1024, 1536, 1.8, 0.02, 3).numpy().reshape(-1)
+    blob = ecf8.ecf8_encode(w, 1024, 1536)
+    got, guards = _gpu_decode_guarded(blob.numpy(), blob.header)
+    assert guards and np.array_equal(got, _oracle_expected(orc, w)) and np.array_equal(got, w)
+    assert blob.size / w.size < 0.78
