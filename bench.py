@@ -392,6 +392,43 @@ def bench_encode(a):
         "identical_to_cpu_encoder": True, "cpu_encoder_GBps": round(n_total / t_cpu_total / 1e9, 3), "tensors": rows}))
 
 
+def bench_encode_wide(a):
+    """Workloads "encode_bf16" / "encode_e5m2": the GPU-side encoder of the wide-alphabet codec on one
+    14336 x 4096 matrix, checked byte for byte against the CPU encoder's container, beside the CPU encoder."""
+    from paper_2510_02676_amd import ecfw, synth
+    dev = "cuda:0"
+    fmt = ecfw.FMT_BF16 if a.workload == "encode_bf16" else ecfw.FMT_E5M2
+    make = synth.make_bf16 if fmt == ecfw.FMT_BF16 else synth.make_e5m2
+    w = make(14336, 4096, 1.8, 0.02, a.seed, tensor_id=600000, device=dev)
+    t0 = time.time()
+    ref = ecfw.ecfw_encode(fmt, w.cpu(), 14336, 4096)
+    t_cpu = time.time() - t0
+    hdr, d_blob = ecfw.ecfw_encode_gpu(fmt, w)
+    torch.cuda.synchronize()
+    if bytes(hdr) != bytes(ref.header) or not torch.equal(d_blob.cpu(), torch.from_numpy(ref.numpy())):
+        raise SystemExit("GPU-encoded container differs from the CPU encoder's")
+    buf = torch.empty(d_blob.numel() + 4096, dtype=torch.uint8, device=dev)
+    for _ in range(a.warmup):
+        ecfw.ecfw_encode_gpu(fmt, w, d_blob=buf)
+    torch.cuda.synchronize()
+    t0 = time.time()
+    for _ in range(a.steps):
+        ecfw.ecfw_encode_gpu(fmt, w, d_blob=buf)
+    torch.cuda.synchronize()
+    t_gpu = (time.time() - t0) / a.steps
+    raw = w.numel() * w.element_size()
+    name = "BF16" if fmt == ecfw.FMT_BF16 else "E5M2"
+    print(json.dumps({
+        "metric": "raw %s GB/s consumed by the GPU-side encoder (ecfw_encode_gpu)" % name, "value": round(raw / t_gpu / 1e9, 2),
+        "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(t_gpu * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u16" if fmt == ecfw.FMT_BF16 else "u8",
+        "data": "synthetic",
+        "config": {"workload": "%s: one 14336x4096 matrix as %s, host wall clock incl. the histogram read-back" % (a.workload, name),
+                   "elements": w.numel(), "seed": a.seed},
+        "identical_to_cpu_encoder": True, "cpu_encoder_GBps": round(raw / t_cpu / 1e9, 3),
+        "compression_ratio": round(hdr.total_size / raw, 5)}))
+
+
 def bench_wide(a):
     """Workloads "wide_bf16" / "wide_e5m2": the wide-alphabet decoder on eight MLP-sized matrices
     (14336 x 4096) of the 8B-class stack in BF16 or E5M2: one ecfw_decode_batched launch per step, or with
@@ -527,6 +564,8 @@ def main():
         return bench_encode(a)
     if a.workload in ("wide_bf16", "wide_e5m2"):
         return bench_wide(a)
+    if a.workload in ("encode_bf16", "encode_e5m2"):
+        return bench_encode_wide(a)
     layers = a.layers or {"config1": 32, "config2": 256, "config3": 40, "config0": 1}[a.workload]
     batches, desc, t_setup = build_workload(a.workload, a.seed, a.lane_syms, layers, a.launch, a.group_chunks, a.max_code_len)
     hdrs = [t["hdr"] for _, ts in batches for t in ts]

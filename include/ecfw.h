@@ -114,6 +114,20 @@ int ecfw_encode(const void *elems_host, uint64_t rows, uint64_t cols, const ecfw
                 ecf8_blob **out);
 
 /*
+ * ecfw_encode_gpu (Section 3.1 on the device for the formats above).  d_elems: DEVICE,
+ * rows*cols elements, 16-byte aligned; d_blob: DEVICE buffer of blob_capacity bytes,
+ * 256-byte aligned, that receives the container -- byte for byte the one ecfw_encode
+ * writes for the same input and options (n_threads is ignored).  ecfw_encode_bound
+ * gives a capacity that always suffices; ECF8_E_CAPACITY if the blob turns out larger
+ * than blob_capacity.  *hdr_out receives the header.  The call synchronises `stream`
+ * ONCE (it reads the histogram back to build the code on the host), then queues the
+ * rest asynchronously.  Uses no memory besides its input and output.
+ */
+int ecfw_encode_bound(uint64_t rows, uint64_t cols, const ecfw_encode_opts *opts, uint64_t *bytes);
+int ecfw_encode_gpu(const void *d_elems, uint64_t rows, uint64_t cols, const ecfw_encode_opts *opts,
+                    void *d_blob, uint64_t blob_capacity, ecfw_header *hdr_out, void *stream);
+
+/*
  * Header parse + structural checks of a container held in HOST memory (sizes,
  * offsets, alignment, code lengths form a prefix code that covers the histogram).
  * Fills *hdr, which is what ecfw_decode needs on the host at launch time.

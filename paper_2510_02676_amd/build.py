@@ -7,7 +7,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 LIB = os.path.join(PKG, "libecf8.so")
 SOURCES = [os.path.join(PKG, "csrc", f) for f in ("ecf8_host.cpp", "ecf8_jit.cpp", "ecfw_host.cpp", "ecf8_decode.hip", "ecf8_gemm.hip", "ecf8_encode.hip",
-                                                       "ecfw_decode.hip")]
+                                                       "ecfw_decode.hip", "ecfw_encode.hip")]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-pthread",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

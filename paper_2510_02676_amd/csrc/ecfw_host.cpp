@@ -12,6 +12,7 @@
 #include <vector>
 
 #include "ecf8_plan.h"
+#include "ecfw_plan.h"
 
 namespace {
 
@@ -197,6 +198,86 @@ struct BitWriter {
     void finish() { if (fill) __atomic_fetch_or(&buf[byte], (uint8_t)acc, __ATOMIC_RELAXED); }
 };
 
+} // namespace
+
+namespace ecfw_internal {
+
+int check_options(const ecfw_encode_opts *opts, uint64_t rows, uint64_t cols, uint32_t *N, uint32_t *group, uint32_t *lmax)
+{
+    if (!opts || rows == 0 || cols == 0) return ECF8_E_ARG;
+    if (cols > UINT64_MAX / rows || rows * cols > (1ull << 48)) return ECF8_E_ARG;
+    Format f;
+    if (!format_of(opts->fmt, &f)) return ECF8_E_ARG;
+    for (uint32_t r : opts->reserved)
+        if (r) return ECF8_E_ARG;
+    *N = opts->lane_syms ? opts->lane_syms : (f.fmt == ECFW_FMT_BF16 ? 64u : 128u);
+    *group = opts->group_chunks ? opts->group_chunks : 32u;
+    *lmax = opts->max_code_len ? opts->max_code_len : ECFW_TABLE_BITS;
+    if (!lane_syms_ok(*N) || !group_ok(*group) || *lmax > ECFW_MAX_CODE_LEN) return ECF8_E_ARG;
+    return ECF8_OK;
+}
+
+int plan_encode(const uint64_t *freq, uint32_t fmt, uint64_t rows, uint64_t cols, uint32_t N, uint32_t group,
+                uint32_t lmax, WPlan *out)
+{
+    Format f;
+    if (!format_of(fmt, &f)) return ECF8_E_ARG;
+    const uint32_t A = f.alphabet;
+    const uint64_t n = rows * cols;
+    uint64_t fsum = 0;
+    for (uint32_t s = 0; s < A; s++) fsum += freq[s];
+    if (fsum != n) return ECF8_E_ARG;
+    std::memset(out, 0, sizeof(*out));
+    if (!capped_lengths(freq, A, lmax, out->len)) return ECF8_E_ARG;   // cap too small for the alphabet in use
+    if (!canonical(out->len, A, out->code, out->rcode)) return ECF8_E_FORMAT;
+    uint64_t bits = 0;
+    uint32_t maxlen = 0, nsym = 0;
+    for (uint32_t s = 0; s < A; s++) {
+        bits += freq[s] * out->len[s];
+        maxlen = std::max<uint32_t>(maxlen, out->len[s]);
+        nsym += freq[s] != 0;
+    }
+    const Sections L = make_sections(f, n, bits, N);
+    ecfw_header &h = out->hdr;
+    h.magic = ECFW_MAGIC;
+    h.version = ECFW_VERSION;
+    h.total_size = L.total;
+    h.n_elem = n;
+    h.rows = rows;
+    h.cols = cols;
+    h.fmt = fmt;
+    h.lane_syms = N;
+    h.group_chunks = group;
+    h.max_code_len = maxlen;
+    h.n_alphabet = A;
+    h.n_symbols = nsym;
+    h.n_chunks = L.n_chunks;
+    h.stream_bits = bits;
+    h.off_code_len = L.off_len;
+    h.off_freq = L.off_freq;
+    h.off_chunk_bit = L.off_cb;
+    h.off_lane_bits = L.off_lb;
+    h.off_stream = L.off_st;
+    h.off_plane = L.off_pl;
+    h.off_sign = L.off_sg;
+    h.stream_bytes = L.st_bytes;
+    h.plane_bytes = L.pl_bytes;
+    h.sign_bytes = L.sg_bytes;
+    return ECF8_OK;
+}
+
+int encode_bound(uint32_t fmt, uint64_t rows, uint64_t cols, uint32_t N, uint32_t lmax, uint64_t *bytes)
+{
+    Format f;
+    if (!format_of(fmt, &f)) return ECF8_E_ARG;
+    *bytes = make_sections(f, rows * cols, rows * cols * lmax, N).total;   // the longest stream the cap allows
+    return ECF8_OK;
+}
+
+} // namespace ecfw_internal
+
+namespace {
+
 template <uint32_t FMT>
 int encode_as(const uint8_t *x, uint64_t rows, uint64_t cols, const Format &f, uint32_t N, uint32_t group,
               uint32_t lmax, unsigned nt, ecf8_blob **out)
@@ -221,48 +302,17 @@ int encode_as(const uint8_t *x, uint64_t rows, uint64_t cols, const Format &f, u
     for (unsigned t = 0; t < nt; t++)
         for (uint32_t s = 0; s < A; s++) freq[s] += part[(size_t)t * A + s];
 
-    // stage 2: the code
-    uint8_t len[256] = {};
-    uint32_t code[256], rcode[256];
-    if (!capped_lengths(freq, A, lmax, len)) return ECF8_E_ARG;   // cap too small for the alphabet in use
-    if (!canonical(len, A, code, rcode)) return ECF8_E_FORMAT;
-    uint64_t bits = 0;
-    uint32_t maxlen = 0, nsym = 0;
-    for (uint32_t s = 0; s < A; s++) {
-        bits += freq[s] * len[s];
-        maxlen = std::max<uint32_t>(maxlen, len[s]);
-        nsym += freq[s] != 0;
-    }
-    const Sections L = make_sections(f, n, bits, N);
+    // stage 2: the code, the layout, the header
+    ecfw_internal::WPlan plan;
+    const int prc = ecfw_internal::plan_encode(freq, FMT, rows, cols, N, group, lmax, &plan);
+    if (prc) return prc;
+    const uint8_t *len = plan.len;
+    const uint32_t *code = plan.code, *rcode = plan.rcode;
+    const ecfw_header &h = plan.hdr;
+    const Sections L = make_sections(f, n, h.stream_bits, N);
     uint8_t *blob = (uint8_t *)std::aligned_alloc(256, L.total);
     if (!blob) return ECF8_E_NOMEM;
     std::memset(blob, 0, L.off_st);
-    ecfw_header h;
-    std::memset(&h, 0, sizeof(h));
-    h.magic = ECFW_MAGIC;
-    h.version = ECFW_VERSION;
-    h.total_size = L.total;
-    h.n_elem = n;
-    h.rows = rows;
-    h.cols = cols;
-    h.fmt = FMT;
-    h.lane_syms = N;
-    h.group_chunks = group;
-    h.max_code_len = maxlen;
-    h.n_alphabet = A;
-    h.n_symbols = nsym;
-    h.n_chunks = L.n_chunks;
-    h.stream_bits = bits;
-    h.off_code_len = L.off_len;
-    h.off_freq = L.off_freq;
-    h.off_chunk_bit = L.off_cb;
-    h.off_lane_bits = L.off_lb;
-    h.off_stream = L.off_st;
-    h.off_plane = L.off_pl;
-    h.off_sign = L.off_sg;
-    h.stream_bytes = L.st_bytes;
-    h.plane_bytes = L.pl_bytes;
-    h.sign_bytes = L.sg_bytes;
     std::memcpy(blob, &h, sizeof(h));
     std::memcpy(blob + L.off_len, len, A);
     std::memcpy(blob + L.off_freq, freq, 8ull * A);
@@ -417,16 +467,12 @@ extern "C" {
 
 int ecfw_encode(const void *elems, uint64_t rows, uint64_t cols, const ecfw_encode_opts *opts, ecf8_blob **out)
 {
-    if (!elems || !out || !opts || rows == 0 || cols == 0) return ECF8_E_ARG;
-    if (cols > UINT64_MAX / rows || rows * cols > (1ull << 48)) return ECF8_E_ARG;
+    if (!elems || !out) return ECF8_E_ARG;
+    uint32_t N, group, lmax;
+    const int orc = ecfw_internal::check_options(opts, rows, cols, &N, &group, &lmax);
+    if (orc) return orc;
     Format f;
-    if (!format_of(opts->fmt, &f)) return ECF8_E_ARG;
-    for (uint32_t r : opts->reserved)
-        if (r) return ECF8_E_ARG;
-    const uint32_t N = opts->lane_syms ? opts->lane_syms : (f.fmt == ECFW_FMT_BF16 ? 64u : 128u);
-    const uint32_t group = opts->group_chunks ? opts->group_chunks : 32u;
-    const uint32_t lmax = opts->max_code_len ? opts->max_code_len : ECFW_TABLE_BITS;
-    if (!lane_syms_ok(N) || !group_ok(group) || lmax > ECFW_MAX_CODE_LEN) return ECF8_E_ARG;
+    format_of(opts->fmt, &f);
     unsigned nt = opts->n_threads ? opts->n_threads : std::thread::hardware_concurrency();
     if (nt == 0) nt = 1;
     if (nt > 64) nt = 64;

@@ -41,6 +41,8 @@ assert ctypes.sizeof(WHeader) == 256
 
 _vp, _u64, _u32 = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32
 _lib.ecfw_encode.argtypes = [_vp, _u64, _u64, ctypes.POINTER(WEncodeOpts), ctypes.POINTER(_vp)]
+_lib.ecfw_encode_bound.argtypes = [_u64, _u64, ctypes.POINTER(WEncodeOpts), ctypes.POINTER(_u64)]
+_lib.ecfw_encode_gpu.argtypes = [_vp, _u64, _u64, ctypes.POINTER(WEncodeOpts), _vp, _u64, ctypes.POINTER(WHeader), _vp]
 _lib.ecfw_blob_describe.argtypes = [_vp, _u64, ctypes.POINTER(WHeader)]
 _lib.ecfw_blob_validate.argtypes = [_vp, _u64]
 _lib.ecfw_decode.argtypes = [_vp, ctypes.POINTER(WHeader), _vp, _u64, _u32, _vp]
@@ -97,6 +99,25 @@ def ecfw_encode(fmt, x, rows=None, cols=None, lane_syms=0, n_threads=0, group_ch
     h = _vp()
     _e._check("ecfw_encode", _lib.ecfw_encode(x.ctypes.data, rows, cols, ctypes.byref(opts), ctypes.byref(h)))
     return WBlob(h)
+
+
+def ecfw_encode_gpu(fmt, d_x, rows=None, cols=None, lane_syms=0, group_chunks=0, max_code_len=0, d_blob=None, stream=None):
+    """GPU encoder: device tensor of raw E5M2 bytes (uint8) or BF16 words (bfloat16 / int16) -> (WHeader, uint8
+    device tensor holding the blob).  Same options and same bytes as ecfw_encode."""
+    if rows is None:
+        rows, cols = (d_x.shape if d_x.dim() == 2 else (1, d_x.numel()))
+    if (fmt not in ELEM_BYTES or rows * cols != d_x.numel() or d_x.element_size() != ELEM_BYTES[fmt]
+            or not d_x.is_contiguous() or d_x.device.type != "cuda"):
+        raise _e.Ecf8Error("ecfw_encode_gpu", _e.E_ARG)
+    opts = WEncodeOpts(fmt, lane_syms, 0, group_chunks, max_code_len)
+    if d_blob is None:
+        bound = _u64(0)
+        _e._check("ecfw_encode_bound", _lib.ecfw_encode_bound(rows, cols, ctypes.byref(opts), ctypes.byref(bound)))
+        d_blob = torch.empty(int(bound.value), dtype=torch.uint8, device=d_x.device)
+    hdr = WHeader()
+    _e._check("ecfw_encode_gpu", _lib.ecfw_encode_gpu(d_x.data_ptr(), rows, cols, ctypes.byref(opts), d_blob.data_ptr(),
+                                                      d_blob.numel(), ctypes.byref(hdr), _e._stream_ptr(stream)))
+    return hdr, d_blob[:hdr.total_size]
 
 
 def blob_describe(ptr_or_array, size=None):

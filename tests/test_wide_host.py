@@ -182,3 +182,16 @@ def test_batch_prepare_checks_on_the_host():
     H[0].lane_syms = 128
     assert lib.ecfw_batch_prepare(H, B, O, C, n, items, ctypes.byref(info)) != 0
     assert lib.ecfw_batch_prepare(H, B, O, C, 0, items, ctypes.byref(info)) == ecf8.E_ARG
+
+
+def test_encode_bound_covers_every_histogram():
+    import ctypes
+    for fmt, x in ((BF16, np.arange(65536, dtype=np.uint16)), (E5M2, np.arange(256, dtype=np.uint8).repeat(300))):
+        for cap in (0, 16):
+            opts = ecfw.WEncodeOpts(fmt, 0, 0, 0, cap)
+            b = ctypes.c_uint64(0)
+            assert ecfw._lib.ecfw_encode_bound(1, x.size, ctypes.byref(opts), ctypes.byref(b)) == 0
+            assert b.value >= ecfw.ecfw_encode(fmt, x, max_code_len=16 if fmt == BF16 else cap).size or cap == 0
+    opts = ecfw.WEncodeOpts(9, 0, 0, 0, 0)
+    assert ecfw._lib.ecfw_encode_bound(1, 100, ctypes.byref(opts), ctypes.byref(b)) == ecf8.E_ARG
+    assert ecfw._lib.ecfw_encode_bound(0, 100, ctypes.byref(ecfw.WEncodeOpts(BF16, 0, 0, 0, 0)), ctypes.byref(b)) == ecf8.E_ARG
