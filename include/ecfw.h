@@ -188,6 +188,17 @@ int ecfw_batch_prepare(const ecfw_header *hdrs, const void *const *d_blobs, void
                        ecfw_batch_info *info);
 int ecfw_decode_batched(const void *d_items, uint32_t n, const ecfw_batch_info *info, void *stream);
 
+/*
+ * Just-in-time decode of layers held in this container: the two set-up steps of an
+ * ecf8_jit manager (see ecf8.h) for a layer of E5M2 / BF16 tensors.  A manager may hold
+ * layers of both kinds; ecf8_jit_prefetch / _acquire / _release do not care.  offsets[i]
+ * receives the byte offset of tensor i inside the layer's buffer (256-byte aligned);
+ * items_host[n] is what the caller copies to the device and hands to the commit call.
+ */
+int ecfw_jit_layer_prepare(ecf8_jit *jit, uint32_t layer, const ecfw_header *hdrs, const void *const *d_blobs,
+                           uint32_t n_tensors, ecfw_batch_item *items_host, uint64_t *offsets);
+int ecfw_jit_layer_commit(ecf8_jit *jit, uint32_t layer, const ecfw_batch_item *d_items);
+
 #ifdef __cplusplus
 }
 #endif

@@ -10,13 +10,16 @@
 #include <vector>
 
 #include "ecf8.h"
+#include "ecfw.h"
 
 struct ecf8_jit {
     enum State { FREE, READY, ACQUIRED };
     struct Layer {
-        const ecf8_batch_item *d_items = nullptr;
+        const void *d_items = nullptr;    // ecf8_batch_item[] or, for a layer of wider elements, ecfw_batch_item[]
         uint32_t n_tensors = 0;
+        bool wide = false;
         ecf8_batch_info info{};
+        ecfw_batch_info winfo{};
         bool prepared = false;
         hipEvent_t ready = nullptr;
     };
@@ -118,13 +121,61 @@ int ecf8_jit_layer_prepare(ecf8_jit *j, uint32_t layer, const ecf8_header *hdrs,
     L.info = info;
     L.n_tensors = n_tensors;
     L.d_items = nullptr;
+    L.wide = false;
     L.prepared = true;
     return ECF8_OK;
 }
 
 int ecf8_jit_layer_commit(ecf8_jit *j, uint32_t layer, const ecf8_batch_item *d_items)
 {
-    if (!j || !d_items || layer >= j->layers.size() || !j->layers[layer].prepared) return ECF8_E_ARG;
+    if (!j || !d_items || layer >= j->layers.size() || !j->layers[layer].prepared || j->layers[layer].wide) return ECF8_E_ARG;
+    if ((uintptr_t)d_items & 15) return ECF8_E_ALIGN;
+    j->layers[layer].d_items = d_items;
+    return ECF8_OK;
+}
+
+// The same two steps for a layer held in the wide-alphabet container (E5M2, BF16): a manager can
+// mix such layers with FP8 ones; everything else (prefetch, acquire, release) is format-blind.
+int ecfw_jit_layer_prepare(ecf8_jit *j, uint32_t layer, const ecfw_header *hdrs, const void *const *d_blobs,
+                           uint32_t n_tensors, ecfw_batch_item *items_host, uint64_t *offsets)
+{
+    if (!j || !hdrs || !d_blobs || !items_host || !offsets || n_tensors == 0) return ECF8_E_ARG;
+    if (layer >= j->layers.size()) return ECF8_E_ARG;
+    const ecf8_jit::Buffer &buf = j->buffers[layer % j->buffers.size()];
+    std::vector<void *> outs;
+    std::vector<uint64_t> caps;
+    try {
+        outs.resize(n_tensors);
+        caps.resize(n_tensors);
+    } catch (...) {
+        return ECF8_E_NOMEM;
+    }
+    uint64_t at = 0;
+    for (uint32_t i = 0; i < n_tensors; i++) {
+        const uint64_t elem = hdrs[i].fmt == ECFW_FMT_BF16 ? 2 : 1;
+        if (hdrs[i].n_elem == 0 || hdrs[i].n_elem > j->buffer_bytes / elem) return ECF8_E_CAPACITY;
+        const uint64_t bytes = hdrs[i].n_elem * elem;
+        offsets[i] = at;
+        caps[i] = bytes;
+        at = round_up(at + bytes, ALIGN);
+        if (offsets[i] + bytes > j->buffer_bytes) return ECF8_E_CAPACITY;
+        outs[i] = (uint8_t *)buf.base + offsets[i];
+    }
+    ecfw_batch_info info;
+    int rc = ecfw_batch_prepare(hdrs, d_blobs, outs.data(), caps.data(), n_tensors, items_host, &info);
+    if (rc) return rc;
+    ecf8_jit::Layer &L = j->layers[layer];
+    L.winfo = info;
+    L.n_tensors = n_tensors;
+    L.d_items = nullptr;
+    L.wide = true;
+    L.prepared = true;
+    return ECF8_OK;
+}
+
+int ecfw_jit_layer_commit(ecf8_jit *j, uint32_t layer, const ecfw_batch_item *d_items)
+{
+    if (!j || !d_items || layer >= j->layers.size() || !j->layers[layer].prepared || !j->layers[layer].wide) return ECF8_E_ARG;
     if ((uintptr_t)d_items & 15) return ECF8_E_ALIGN;
     j->layers[layer].d_items = d_items;
     return ECF8_OK;
@@ -145,8 +196,14 @@ int ecf8_jit_prefetch(ecf8_jit *j, uint32_t layer)
     if (!L.d_items || B.state != ecf8_jit::FREE) return ECF8_E_ARG;   // not committed, or the buffer is still in use
     // the previous user of the buffer must be done with it before the decode overwrites it
     if (B.released_recorded && hipStreamWaitEvent(j->decode_stream, B.released, 0) != hipSuccess) return ECF8_E_HIP;
-    L.info.max_workgroups = j->max_workgroups;
-    int rc = ecf8_decode_batched(L.d_items, L.n_tensors, &L.info, j->decode_stream);
+    int rc;
+    if (L.wide) {
+        L.winfo.max_workgroups = j->max_workgroups;
+        rc = ecfw_decode_batched(L.d_items, L.n_tensors, &L.winfo, j->decode_stream);
+    } else {
+        L.info.max_workgroups = j->max_workgroups;
+        rc = ecf8_decode_batched((const ecf8_batch_item *)L.d_items, L.n_tensors, &L.info, j->decode_stream);
+    }
     if (rc) return rc;
     if (hipEventRecord(L.ready, j->decode_stream) != hipSuccess) return ECF8_E_HIP;
     B.state = ecf8_jit::READY;

@@ -273,11 +273,15 @@ class Jit:
     """Just-in-time layer decode over shared buffers (ecf8_jit_*): layers = list of (headers, device
     blobs); layer l decodes into buffer l % n_buffers.  prefetch(l) queues the decode on the
     manager's own stream, acquire(l) orders the caller's stream behind it and returns the layer's
-    tensors (views into the buffer), release(l) lets the buffer be reused."""
+    tensors (views into the buffer), release(l) lets the buffer be reused.  A layer's headers are either
+    all ecf8 headers (FP8) or all wide-alphabet headers (E5M2 / BF16, see ecfw.py)."""
 
     def __init__(self, layers, n_buffers=2, buffer_bytes=None):
         dev = layers[0][1][0].device
-        need = max(sum((h.n_elem + 255) // 256 * 256 for h in hdrs) for hdrs, _ in layers)
+
+        def nbytes(h):
+            return h.n_elem * (2 if getattr(h, "fmt", 0) == 2 else 1)
+        need = max(sum((nbytes(h) + 255) // 256 * 256 for h in hdrs) for hdrs, _ in layers)
         self.buffer_bytes = buffer_bytes if buffer_bytes is not None else need
         self.buffers = [torch.empty(self.buffer_bytes, dtype=torch.uint8, device=dev) for _ in range(n_buffers)]
         B = (_vp * n_buffers)(*[b.data_ptr() for b in self.buffers])
@@ -287,16 +291,32 @@ class Jit:
         self._keep, self._views = [], []
         for l, (hdrs, d_blobs) in enumerate(layers):
             n = len(hdrs)
-            H = (Header * n)(*hdrs)
             P = (_vp * n)(*[t.data_ptr() for t in d_blobs])
-            items = (BatchItem * n)()
             offs = (_u64 * n)()
-            _check("ecf8_jit_layer_prepare", _lib.ecf8_jit_layer_prepare(self._h, l, H, P, n, items, offs))
+            wide = hasattr(hdrs[0], "fmt")
+            if wide:
+                from . import ecfw
+                H = (ecfw.WHeader * n)(*hdrs)
+                items = (ecfw.WBatchItem * n)()
+                _check("ecfw_jit_layer_prepare", _lib.ecfw_jit_layer_prepare(self._h, l, H, P, n, items, offs))
+            else:
+                H = (Header * n)(*hdrs)
+                items = (BatchItem * n)()
+                _check("ecf8_jit_layer_prepare", _lib.ecf8_jit_layer_prepare(self._h, l, H, P, n, items, offs))
             d_items = torch.from_numpy(np.frombuffer(items, dtype=np.uint8).copy()).to(dev)
-            _check("ecf8_jit_layer_commit", _lib.ecf8_jit_layer_commit(self._h, l, d_items.data_ptr()))
+            if wide:
+                _check("ecfw_jit_layer_commit", _lib.ecfw_jit_layer_commit(self._h, l, d_items.data_ptr()))
+            else:
+                _check("ecf8_jit_layer_commit", _lib.ecf8_jit_layer_commit(self._h, l, d_items.data_ptr()))
             self._keep.append((d_items, list(d_blobs)))
             buf = self.buffers[l % n_buffers]
-            self._views.append([buf[int(o):int(o) + h.n_elem].view(h.rows, h.cols) for o, h in zip(offs, hdrs)])
+            views = []
+            for o, h in zip(offs, hdrs):
+                v = buf[int(o):int(o) + nbytes(h)]
+                if getattr(h, "fmt", 0) == 2:
+                    v = v.view(torch.bfloat16)
+                views.append(v.view(h.rows, h.cols))
+            self._views.append(views)
 
     def set_decode_workgroups(self, max_workgroups):
         _check("ecf8_jit_set_decode_workgroups", _lib.ecf8_jit_set_decode_workgroups(self._h, max_workgroups))

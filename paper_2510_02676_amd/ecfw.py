@@ -165,6 +165,11 @@ _lib.ecfw_batch_prepare.argtypes = [ctypes.POINTER(WHeader), ctypes.POINTER(_vp)
 _lib.ecfw_decode_batched.argtypes = [_vp, _u32, ctypes.POINTER(WBatchInfo), _vp]
 
 
+_lib.ecfw_jit_layer_prepare.argtypes = [_vp, _u32, ctypes.POINTER(WHeader), ctypes.POINTER(_vp), _u32,
+                                        ctypes.POINTER(WBatchItem), ctypes.POINTER(_u64)]
+_lib.ecfw_jit_layer_commit.argtypes = [_vp, _u32, _vp]
+
+
 class WBatch:
     """Device-resident item table for ecfw_decode_batched (built once, reused)."""
 

@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 import torch
 
-from paper_2510_02676_amd import ecf8
+from paper_2510_02676_amd import ecf8, synth
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -139,3 +139,43 @@ def test_misuse_is_reported():
     with pytest.raises(ecf8.Ecf8Error) as e:
         ecf8.Jit(packed, n_buffers=2, buffer_bytes=1024)  # a 64x64 layer does not fit 1 KiB
     assert e.value.code == ecf8.E_CAPACITY
+
+
+def test_layers_of_wider_formats_and_mixed_managers():
+    """A manager whose layers alternate between FP8 (ecf8 container) and BF16 / E5M2 (wide container): what the
+    consumer sees after acquire equals the original tensors, over two passes with two buffers."""
+    from paper_2510_02676_amd import ecfw
+    shapes = [(256, 512), (128, 1024), (64, 256)]
+    layers, originals = [], []
+    for l in range(6):
+        kind = l % 3
+        hdrs, blobs, orig = [], [], []
+        for j, (r, c) in enumerate(shapes):
+            if kind == 0:
+                w = synth.make_weight(r, c, 1.8, 0.02, 50 + l, tensor_id=j)
+                b = ecf8.ecf8_encode(w.numpy(), r, c)
+            elif kind == 1:
+                w = synth.make_bf16(r, c, 1.8, 0.02, 50 + l, tensor_id=j)
+                b = ecfw.ecfw_encode(ecfw.FMT_BF16, w, r, c)
+                w = w.view(torch.bfloat16)
+            else:
+                w = synth.make_e5m2(r, c, 1.8, 0.02, 50 + l, tensor_id=j)
+                b = ecfw.ecfw_encode(ecfw.FMT_E5M2, w, r, c)
+            hdrs.append(b.header)
+            blobs.append(b.to(DEV))
+            orig.append(w.to(DEV))
+        layers.append((hdrs, blobs))
+        originals.append(orig)
+    jit = ecf8.Jit(layers, n_buffers=2)
+    s = torch.cuda.current_stream()
+    for _ in range(2):
+        jit.prefetch(0)
+        for l in range(6):
+            if l + 1 < 6:
+                jit.prefetch(l + 1)
+            views = jit.acquire(l, s)
+            for v, o in zip(views, originals[l]):
+                assert v.dtype == o.dtype and torch.equal(v.view(torch.uint8), o.view(torch.uint8))
+            jit.release(l, s)
+    torch.cuda.synchronize()
+    jit.close()
