@@ -179,3 +179,56 @@ def test_layers_of_wider_formats_and_mixed_managers():
             jit.release(l, s)
     torch.cuda.synchronize()
     jit.close()
+
+
+def test_decode_launches_replay_from_a_hip_graph():
+    """The decode calls allocate nothing, synchronise nothing and clear nothing with memsets, so a caller may
+    capture them into a HIP graph: four per-layer FP8 launches and one BF16 launch are captured once and
+    replayed three times, with the outputs poisoned and eager work in between; every replay must reproduce
+    the eager result."""
+    from paper_2510_02676_amd import ecfw
+    orig, packed = _layers(4, [(256, 1024), (64, 4096), (512, 512)], seed=9)
+    batches, outs = [], []
+    for hdrs, blobs in packed:
+        o = [torch.empty((h.rows, h.cols), dtype=torch.uint8, device=DEV) for h in hdrs]
+        batches.append(ecf8.Batch(hdrs, blobs, o))
+        outs.append(o)
+    wb = synth.make_bf16(300, 700, 1.8, 0.02, 4)
+    wblob = ecfw.ecfw_encode(ecfw.FMT_BF16, wb, 300, 700)
+    d_wblob, wout = wblob.to(DEV), torch.empty(300 * 700, dtype=torch.bfloat16, device=DEV)
+    d_wb = wb.view(torch.bfloat16).reshape(-1).to(DEV)
+
+    def poison():
+        for o in outs:
+            for t in o:
+                t.fill_(0xEE)
+        wout.view(torch.int16).fill_(0x1111)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):            # warm-up outside the capture, as graph capture asks for
+        for b in batches:
+            ecf8.ecf8_decode_batched(b, side)
+        ecfw.ecfw_decode(d_wblob, wblob.header, wout, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        s = torch.cuda.current_stream()
+        for b in batches:
+            ecf8.ecf8_decode_batched(b, s)
+        ecfw.ecfw_decode(d_wblob, wblob.header, wout, stream=s)
+    for _ in range(3):
+        poison()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for o, ws in zip(outs, orig):
+            for t, w in zip(o, ws):
+                assert torch.equal(t, w)
+        assert torch.equal(wout.view(torch.int16), d_wb.view(torch.int16))
+        # eager work between replays
+        poison()
+        ecf8.ecf8_decode_batched(batches[0])
+        torch.cuda.synchronize()
+        assert all(torch.equal(t, w) for t, w in zip(outs[0], orig[0]))
