@@ -6,7 +6,7 @@ stack is decoded from its resident compressed blob to exact FP8 bytes.  By
 default the whole stack goes through ONE ecf8_decode_batched launch per step
 (--launch stack); --launch layer issues one batched launch per layer/block
 instead, on --streams streams round-robin.  Inputs are seeded synthetic
-alpha-stable FP8 weights; blobs and output buffers are resident
+alpha-stable FP8 weights (recipe in paper_2510_02676_amd/synth.py); blobs and output buffers are resident
 in HBM before the timed region starts.
 
 Prints ONE JSON line: decoded FP8 GB/s as `value`, the roofline of the decode
@@ -551,7 +551,7 @@ def main():
     a = ap.parse_args()
     if a.gpus != 1:
         raise SystemExit("this build runs on ONE GPU: tensors are independent and shard with no exchange "
-                         "(see DESIGN.md); --gpus %d is not supported" % a.gpus)
+                         "or collective; --gpus %d is not supported" % a.gpus)
     if not torch.cuda.is_available():
         raise SystemExit("no GPU visible: the decode path has no CPU fallback")
     from paper_2510_02676_amd import ecf8

@@ -15,7 +15,14 @@
 //    canonical first-code comparison per length, in a rarely taken branch;
 //  * the remaining bits come from planes laid out so that whole output words are
 //    merged with a few bit selects (BF16: a byte per element in the order
-//    0 2 1 3; E5M2: mantissas sliced by output word, signs as a bit mask).
+//    0 2 1 3; E5M2: mantissas sliced by output word, signs as a bit mask);
+//  * these kernels are bound by the LDS, not by HBM, unless the window reads are
+//    kept off each other's banks: the FAST kernels move every lane's bits from
+//    the linear image of the span into a column of its own before decoding
+//    (dword r of lane l at row r, column l), see WCfg;
+//  * one launch may cover many tensors (ecfw_decode_batched): a workgroup's
+//    range of chunks runs through the batch and the code is set up again where
+//    it crosses into another tensor.
 #include "ecfw.h"
 
 #include "ecf8_device.h"
