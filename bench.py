@@ -214,8 +214,17 @@ def bench_config4(a):
             raise SystemExit("block-scaled fused GEMM differs from its twin on uncompressed weights at M=%d" % M)
         tfs = timeit(lambda: ecf8.ecf8_gemm_fp8_scaled(h, d_blob, x, ws, xs, y), a.steps, a.warmup)
         trs = timeit(lambda: ecf8.ecf8_gemm_fp8_raw_scaled(w, x, ws, xs, y2), a.steps, a.warmup)
+        # ... and one scale per row of X and 128 columns (activations quantised in 1 x 128 groups)
+        xg = torch.rand((M, spec["cols"] // 128), device="cuda:0") + 0.5
+        ecf8.ecf8_gemm_fp8_scaled(h, d_blob, x, ws, xg, y)
+        ecf8.ecf8_gemm_fp8_raw_scaled(w, x, ws, xg, y2)
+        torch.cuda.synchronize()
+        if not torch.equal(y, y2):
+            raise SystemExit("group-scaled fused GEMM differs from its twin on uncompressed weights at M=%d" % M)
+        tfg = timeit(lambda: ecf8.ecf8_gemm_fp8_scaled(h, d_blob, x, ws, xg, y), a.steps, a.warmup)
         res["M=%d" % M] = {"fused_us": round(tf * 1e6, 2), "raw_fp8_gemm_us": round(tr * 1e6, 2),
                            "fused_block_scaled_us": round(tfs * 1e6, 2), "raw_block_scaled_us": round(trs * 1e6, 2),
+                           "fused_block_and_group_scaled_us": round(tfg * 1e6, 2),
                            "decode_then_gemm_us": round(t2 * 1e6, 2),
                            "vendor_fp8_gemm_us": None if t_vendor is None else round(t_vendor * 1e6, 2),
                            "fused_weight_GBps": round(w.numel() / tf / 1e9, 1)}

@@ -285,18 +285,23 @@ int ecf8_gemm_fp8_raw(const void *d_w, uint64_t rows, uint64_t cols, const void 
  * The same two calls with the scales block-quantised FP8 checkpoints carry (the
  * paper's models store one scale per 128 x 128 block of W beside the FP8 bytes;
  * the codec itself never touches them, Section 3):
- *   Y[m][n] = x_scale[m] * sum_kb w_scale[n/128][kb] * sum_{k in block kb} X[m][k] * W[n][k]
+ *   Y[m][n] = sum_kb x_scale[m][kb] * w_scale[n/128][kb] * sum_{k in block kb} X[m][k] * W[n][k]
  * d_w_scale: DEVICE, fp32 [ceil(rows/128)][cols/128], row-major; d_x_scale: DEVICE,
- * fp32 [M], or NULL for ones.  Each 128-wide slice of K is summed by the matrix
- * cores on its own and enters the fp32 sum through one multiply-add with its
- * scale; the row scale multiplies the finished sum.  Other arguments, limits and
- * errors as above.  The raw twin takes the same steps in the same order: the two
- * agree bit for bit.
+ * fp32 [M][x_scale_cols], row-major, with x_scale_cols = 1 (one scale per row of X,
+ * x_scale[m][kb] = x_scale[m]) or cols/128 (one per row and 128 columns, as
+ * activations quantised in 1 x 128 groups carry them); NULL with x_scale_cols = 0 for
+ * ones.  Each 128-wide slice of K is summed by the matrix cores on its own and enters
+ * the fp32 sum through one multiply-add with its scale (the product of the two scales,
+ * rounded to fp32, where X has one per slice); a single row scale multiplies the
+ * finished sum.  Other arguments, limits and errors as above.  The raw twin takes the
+ * same steps in the same order: the two agree bit for bit.
  */
 int ecf8_gemm_fp8_scaled(const ecf8_header *hdr, const void *d_blob, const void *d_x, uint32_t M,
-                         const float *d_w_scale, const float *d_x_scale, float *d_y, void *stream);
+                         const float *d_w_scale, const float *d_x_scale, uint32_t x_scale_cols,
+                         float *d_y, void *stream);
 int ecf8_gemm_fp8_raw_scaled(const void *d_w, uint64_t rows, uint64_t cols, const void *d_x, uint32_t M,
-                             const float *d_w_scale, const float *d_x_scale, float *d_y, void *stream);
+                             const float *d_w_scale, const float *d_x_scale, uint32_t x_scale_cols,
+                             float *d_y, void *stream);
 
 /*
  * Just-in-time layer decode (Section 3.3: compressed layers stay resident, a

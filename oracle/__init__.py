@@ -259,7 +259,8 @@ def gemm_ref(X, W):
 
 
 def gemm_ref_scaled(X, W, ws, xs=None):
-    """Y = (xs X) @ (ws W).T with one scale per 128 x 128 block of W and per row of X; returns (Y, sum |.|)."""
+    """Y = (xs X) @ (ws W).T with one scale per 128 x 128 block of W and, for X, one per row (xs of shape (M,))
+    or one per row and 128 columns (shape (M, ceil(K/128))); returns (Y, sum |.|)."""
     X = np.ascontiguousarray(X, dtype=np.uint8)
     W = np.ascontiguousarray(W, dtype=np.uint8)
     M, K = X.shape
@@ -267,13 +268,15 @@ def gemm_ref_scaled(X, W, ws, xs=None):
     assert K == K2
     ws = np.ascontiguousarray(ws, dtype=np.float32)
     assert ws.shape == ((N + 127) // 128, (K + 127) // 128)
+    xs_cols = 0
     if xs is not None:
         xs = np.ascontiguousarray(xs, dtype=np.float32)
-        assert xs.shape == (M,)
+        assert xs.shape in ((M,), (M, (K + 127) // 128))
+        xs_cols = 1 if xs.ndim == 1 else xs.shape[1]
     Y = np.zeros((M, N), dtype=np.float64)
     A = np.zeros((M, N), dtype=np.float64)
     lib().orc_gemm_ref_scaled(_p(X), _p(W), ctypes.c_uint64(M), ctypes.c_uint64(N), ctypes.c_uint64(K), _p(ws),
-                              _p(xs) if xs is not None else None, _p(Y), _p(A))
+                              _p(xs) if xs is not None else None, ctypes.c_uint64(xs_cols), _p(Y), _p(A))
     return Y, A
 
 

@@ -45,14 +45,15 @@ void orc_gemm_ref(const uint8_t *X, const uint8_t *W, uint64_t M, uint64_t N, ui
 
 /*
  * The same with block scales: W carries one scale per 128 x 128 block
- * (ws[(n/128) * ceil(K/128) + k/128]), X one scale per row (xs[m], or NULL for
- * ones); the dequantised product is
- *   Y[m][n] = sum_k (xs[m] X[m][k]) * (ws[n/128][k/128] W[n][k]).
+ * (ws[(n/128) * ceil(K/128) + k/128]), X xs_cols scales per row: one (xs[m]) or
+ * one per 128 columns (xs[m * xs_cols + k/128]); xs = NULL for ones.  The
+ * dequantised product is
+ *   Y[m][n] = sum_k (xs[m][k/128] X[m][k]) * (ws[n/128][k/128] W[n][k]).
  * Scales are given as binary32 and taken exactly; A is the same sum over
  * absolute values.
  */
 void orc_gemm_ref_scaled(const uint8_t *X, const uint8_t *W, uint64_t M, uint64_t N, uint64_t K,
-                         const float *ws, const float *xs, double *Y, double *A)
+                         const float *ws, const float *xs, uint64_t xs_cols, double *Y, double *A)
 {
     double lut[256];
     const uint64_t kb = (K + 127) / 128;
@@ -62,7 +63,8 @@ void orc_gemm_ref_scaled(const uint8_t *X, const uint8_t *W, uint64_t M, uint64_
             double acc = 0.0, mag = 0.0;
             const uint8_t *x = X + m * K, *w = W + n * K;
             for (uint64_t k = 0; k < K; k++) {
-                double p = ((xs ? (double)xs[m] : 1.0) * lut[x[k]]) * ((double)ws[(n / 128) * kb + k / 128] * lut[w[k]]);
+                const double sx = !xs ? 1.0 : (double)xs[m * xs_cols + (xs_cols > 1 ? k / 128 : 0)];
+                double p = (sx * lut[x[k]]) * ((double)ws[(n / 128) * kb + k / 128] * lut[w[k]]);
                 acc += p;
                 mag += fabs(p);
             }

@@ -61,7 +61,8 @@ struct GArgs {
     uint64_t off_cb, off_lb, off_st, off_pl, st_bytes, off_tbl;
     uint8_t code_len[16];
     uint32_t M;
-    uint64_t d_ws, d_xs;                  // SCALED kernels: per-128x128-block scales of W, per-row scales of X (or 0)
+    uint64_t d_ws, d_xs;                  // SCALED kernels: per-128x128-block scales of W, scales of X (or 0)
+    uint32_t xs_cols;                     // scales per row of X: 1, or K / 128 (one per 128 columns)
     uint64_t K;                           // any-K kernels: columns of W (a multiple of 256)
 };
 
@@ -69,6 +70,28 @@ constexpr int SCALE_BLOCK = 128;                // W carries one fp32 scale per 
 constexpr int KBLOCKS = GK / SCALE_BLOCK;
 
 // acc += part * s, element by element, the same operation in the fused and in the raw kernel
+// acc += part * (s * x-scale), element by element, where X carries one scale per row and 128 columns: the
+// scales of block kb for the accumulator rows of this lane (row m = 16 mt + 4 (lane / 16) + r) are
+// fetched one tile of 16 rows at a time.
+template <int MT>
+__device__ __forceinline__ void add_scaled_group(f32x4 (&acc)[MT], const f32x4 (&part)[MT], float s, const GArgs &a,
+                                                 int lane, uint32_t kb)
+{
+    const GLOBAL float *xs = (const GLOBAL float *)a.d_xs;
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++) {
+        float v[4];
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            const uint32_t m = 16 * mt + 4 * (lane >> 4) + r;
+            v[r] = m < a.M ? xs[(uint64_t)m * a.xs_cols + kb] : 0.f;
+        }
+#pragma unroll
+        for (int r = 0; r < 4; r++) acc[mt][r] = __builtin_fmaf(part[mt][r], s * v[r], acc[mt][r]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
 template <int MT>
 __device__ __forceinline__ void add_scaled(f32x4 (&acc)[MT], const f32x4 (&part)[MT], float s)
 {
@@ -138,15 +161,16 @@ __device__ __forceinline__ void reduce_block(f32x4 *red, const GArgs &a, uint64_
         for (int w = 0; w < NW; w++) sum += ((const float *)&red[(w * MT + mt) * 64 + l])[r];
         const uint32_t m = 16 * mt + 4 * (l >> 4) + r;
         if (m < a.M) {
-            if (SCALED && a.d_xs) sum *= ((const GLOBAL float *)a.d_xs)[m];
+            if (SCALED && a.d_xs && a.xs_cols == 1) sum *= ((const GLOBAL float *)a.d_xs)[m];
             Y[(uint64_t)m * a.rows + block * BLOCK_ROWS + (l & 15)] = sum;
         }
     }
 }
 
-template <int MT, int NW, int N, bool SCALED>
+template <int MT, int NW, int N, int SC>       // SC: 0 no scales, 1 scales of W (and one per row of X), 2 also one per row and 128 columns of X
 __global__ __launch_bounds__(NW * 64) void ecf8_gemm_kernel(GArgs a)
 {
+    constexpr bool SCALED = SC != 0, XGROUPS = SC == 2;
     static_assert(!SCALED || 4 * N == 2 * SCALE_BLOCK, "a chunk spans two scale blocks of K");
     using C = GCfg<MT, NW, N>;
     constexpr int KPW = C::KPW, KCHUNKS = C::KCHUNKS, BLOCK_COLS = C::BLOCK_COLS;
@@ -264,10 +288,12 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_kernel(GArgs a)
             // and enter the block's sum with the scale of their 128 x 128 block of W
             f32x4 partA[SCALED ? MT : 1], partB[SCALED ? MT : 1];
             float sA = 1.f, sB = 1.f;
+            uint32_t kbA = 0;              // the chunk's first 128-column block of K
             if constexpr (SCALED) {
                 const GLOBAL float *ws = (const GLOBAL float *)a.d_ws + (block_of(s) * BLOCK_ROWS / SCALE_BLOCK) * KBLOCKS + 2 * kc_of(s);
                 sA = ws[0];
                 sB = ws[1];
+                kbA = 2 * kc_of(s);
 #pragma unroll
                 for (int mt = 0; mt < MT; mt++) partA[mt] = partB[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
@@ -282,8 +308,13 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_kernel(GArgs a)
                 ECF8_MFMA_PIECE(dstB, areg, i, Q + GPIECES / 2, merge_piece(dwB, pl[Q + GPIECES / 2]));
             }
             if constexpr (SCALED) {
-                add_scaled<MT>(acc, partA, sA);
-                add_scaled<MT>(acc, partB, sB);
+                if constexpr (XGROUPS) {    // fetched late: held over the decode they would cost it registers
+                    add_scaled_group<MT>(acc, partA, sA, a, lane, kbA);
+                    add_scaled_group<MT>(acc, partB, sB, a, lane, kbA + 1);
+                } else {
+                    add_scaled<MT>(acc, partA, sA);
+                    add_scaled<MT>(acc, partB, sB);
+                }
             }
             m_cur = m_next;
             m_next = m_next2;
@@ -295,9 +326,10 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_kernel(GArgs a)
 
 // The same GEMM on uncompressed row-major W, with the fused kernel's workgroup shape, K split
 // and order of accumulation, so that the two agree bit for bit.
-template <int MT, int NW, int N, bool SCALED>
+template <int MT, int NW, int N, int SC>       // SC: 0 no scales, 1 scales of W (and one per row of X), 2 also one per row and 128 columns of X
 __global__ __launch_bounds__(NW * 64) void ecf8_gemm_raw_kernel(GArgs a)
 {
+    constexpr bool SCALED = SC != 0, XGROUPS = SC == 2;
     using C = GCfg<MT, NW, N>;
     constexpr int KPW = C::KPW, BLOCK_COLS = C::BLOCK_COLS, GPIECES = C::PIECES;
     __shared__ __attribute__((aligned(16))) uint8_t smem[2 * C::RED_BYTES];
@@ -329,11 +361,13 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_raw_kernel(GArgs a)
             if (s + 1 < n_steps) load_w(s + 1, w_next);
             f32x4 partA[SCALED ? MT : 1], partB[SCALED ? MT : 1];
             float sA = 1.f, sB = 1.f;
+            uint32_t kbA = 0;              // the chunk's first 128-column block of K
             if constexpr (SCALED) {
                 const GLOBAL float *ws = (const GLOBAL float *)a.d_ws + (block_of(s) * BLOCK_ROWS / SCALE_BLOCK) * KBLOCKS +
                                          2 * (wave + NW * (uint32_t)(s % KPW));
                 sA = ws[0];
                 sB = ws[1];
+                kbA = 2 * (wave + NW * (uint32_t)(s % KPW));
 #pragma unroll
                 for (int mt = 0; mt < MT; mt++) partA[mt] = partB[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
@@ -345,8 +379,13 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_raw_kernel(GArgs a)
                 ECF8_MFMA_PIECE(dstB, areg, i, Q + GPIECES / 2, w_cur[Q + GPIECES / 2]);
             }
             if constexpr (SCALED) {
-                add_scaled<MT>(acc, partA, sA);
-                add_scaled<MT>(acc, partB, sB);
+                if constexpr (XGROUPS) {    // fetched late: held over the decode they would cost it registers
+                    add_scaled_group<MT>(acc, partA, sA, a, lane, kbA);
+                    add_scaled_group<MT>(acc, partB, sB, a, lane, kbA + 1);
+                } else {
+                    add_scaled<MT>(acc, partA, sA);
+                    add_scaled<MT>(acc, partB, sB);
+                }
             }
 #pragma unroll
             for (int q = 0; q < GPIECES; q++) w_cur[q] = w_next[q];
@@ -397,9 +436,10 @@ struct Walk {
     uint32_t i;
 };
 
-template <int MT, int NW, int N, bool SCALED>
+template <int MT, int NW, int N, int SC>       // SC: 0 no scales, 1 scales of W (and one per row of X), 2 also one per row and 128 columns of X
 __global__ __launch_bounds__(NW * 64) void ecf8_gemm_anyk_kernel(GArgs a)
 {
+    constexpr bool SCALED = SC != 0, XGROUPS = SC == 2;
     using C = GCfg<MT, NW, N>;
     constexpr int BLOCK_COLS = C::BLOCK_COLS, GPIECES = C::PIECES, GSTAGE = C::STAGE, GSEGS = C::SEGS;
     static_assert(!SCALED || 4 * N == 2 * SCALE_BLOCK, "a chunk spans two scale blocks of K");
@@ -506,11 +546,13 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_anyk_kernel(GArgs a)
             for (int q = 0; q < GPIECES; q++) pl[q] = p_cur.pl[q];
             const XPieces<MT, N> x = x_cur;
             float sA = 1.f, sB = 1.f;
+            uint32_t kbA = 0;              // the chunk's first 128-column block of K
             if constexpr (SCALED) {
                 const GLOBAL float *ws = (const GLOBAL float *)a.d_ws + (block_of(cur) * BLOCK_ROWS / SCALE_BLOCK) * (a.K / SCALE_BLOCK) +
                                          2 * kc_of(cur);
                 sA = ws[0];
                 sB = ws[1];
+                kbA = 2 * kc_of(cur);
             }
             // the payload registers are free: fetch the next chunk and its share of X, and the metadata of the one after
             const Walk nxt = next_of(cur);
@@ -538,8 +580,13 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_anyk_kernel(GArgs a)
                 ECF8_MFMA_XPIECE(dstB, x, Q + GPIECES / 2, merge_piece(dwB, pl[Q + GPIECES / 2]));
             }
             if constexpr (SCALED) {
-                add_scaled<MT>(acc, partA, sA);
-                add_scaled<MT>(acc, partB, sB);
+                if constexpr (XGROUPS) {    // fetched late: held over the decode they would cost it registers
+                    add_scaled_group<MT>(acc, partA, sA, a, lane, kbA);
+                    add_scaled_group<MT>(acc, partB, sB, a, lane, kbA + 1);
+                } else {
+                    add_scaled<MT>(acc, partA, sA);
+                    add_scaled<MT>(acc, partB, sB);
+                }
             }
             cur = nxt;
             m_cur = m_next;
@@ -551,9 +598,10 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_anyk_kernel(GArgs a)
 }
 
 // The any-K GEMM on uncompressed W: same deal of chunks, same order of accumulation.
-template <int MT, int NW, int N, bool SCALED>
+template <int MT, int NW, int N, int SC>       // SC: 0 no scales, 1 scales of W (and one per row of X), 2 also one per row and 128 columns of X
 __global__ __launch_bounds__(NW * 64) void ecf8_gemm_raw_anyk_kernel(GArgs a)
 {
+    constexpr bool SCALED = SC != 0, XGROUPS = SC == 2;
     using C = GCfg<MT, NW, N>;
     constexpr int BLOCK_COLS = C::BLOCK_COLS, GPIECES = C::PIECES;
     __shared__ __attribute__((aligned(16))) uint8_t smem[2 * C::RED_BYTES];
@@ -589,11 +637,13 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_raw_anyk_kernel(GArgs a)
         for (uint32_t i = 0; i < my_chunks; i++) {
             const XPieces<MT, N> x = x_cur;
             float sA = 1.f, sB = 1.f;
+            uint32_t kbA = 0;              // the chunk's first 128-column block of K
             if constexpr (SCALED) {
                 const GLOBAL float *ws = (const GLOBAL float *)a.d_ws + (block_of(cur) * BLOCK_ROWS / SCALE_BLOCK) * (a.K / SCALE_BLOCK) +
                                          2 * kc_of(cur);
                 sA = ws[0];
                 sB = ws[1];
+                kbA = 2 * kc_of(cur);
             }
             const Walk nxt = next_of(cur);
 #pragma unroll
@@ -615,8 +665,13 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_raw_anyk_kernel(GArgs a)
                 ECF8_MFMA_XPIECE(dstB, x, Q + GPIECES / 2, w_cur[Q + GPIECES / 2]);
             }
             if constexpr (SCALED) {
-                add_scaled<MT>(acc, partA, sA);
-                add_scaled<MT>(acc, partB, sB);
+                if constexpr (XGROUPS) {    // fetched late: held over the decode they would cost it registers
+                    add_scaled_group<MT>(acc, partA, sA, a, lane, kbA);
+                    add_scaled_group<MT>(acc, partB, sB, a, lane, kbA + 1);
+                } else {
+                    add_scaled<MT>(acc, partA, sA);
+                    add_scaled<MT>(acc, partB, sB);
+                }
             }
 #pragma unroll
             for (int q = 0; q < GPIECES; q++) w_cur[q] = w_next[q];
@@ -696,9 +751,11 @@ int raw_args(const void *d_w, uint64_t rows, uint64_t cols, const void *d_x, uin
     return ECF8_OK;
 }
 
-int scale_args(const float *d_w_scale, const float *d_x_scale, GArgs *a)
+int scale_args(const float *d_w_scale, const float *d_x_scale, uint32_t x_scale_cols, GArgs *a)
 {
     if (!d_w_scale) return ECF8_E_ARG;
+    if (d_x_scale ? (x_scale_cols != 1 && x_scale_cols != a->K / SCALE_BLOCK) : x_scale_cols != 0) return ECF8_E_ARG;
+    a->xs_cols = x_scale_cols;
     if (((uintptr_t)d_w_scale & 3) || ((uintptr_t)d_x_scale & 3)) return ECF8_E_ALIGN;
     a->d_ws = (uint64_t)(uintptr_t)d_w_scale;
     a->d_xs = (uint64_t)(uintptr_t)d_x_scale;
@@ -707,13 +764,15 @@ int scale_args(const float *d_w_scale, const float *d_x_scale, GArgs *a)
 
 // 16 waves (one K chunk of the block each) while X fits their registers, 8 waves of two chunks
 // at M > 32.  (16 x 512 chunks with 8 waves were measured too: slower, 37.7 us against 25.5.)
-template <bool SCALED>
+template <int SCALED>
 int launch_fused(const GArgs &a, void *stream)
 {
     const int grid = grid_for(a.rows / BLOCK_ROWS);
     if (grid <= 0) return ECF8_E_HIP;
     hipStream_t s = (hipStream_t)stream;
-    if (a.K != GK) {      // X does not stay in registers: fetched chunk by chunk
+    // any K: X does not stay in registers, fetched chunk by chunk.  Also with a scale per row and 128 columns of X
+    // at M > 32: beside four tiles of X in registers the scales do not fit (93 us against 83 at M = 64)
+    if (a.K != GK || (SCALED == 2 && a.M > 32)) {
         if (a.M <= 16) hipLaunchKernelGGL((ecf8_gemm_anyk_kernel<1, 16, 64, SCALED>), dim3(grid), dim3(16 * 64), 0, s, a);
         else if (a.M <= 32) hipLaunchKernelGGL((ecf8_gemm_anyk_kernel<2, 8, 64, SCALED>), dim3(grid), dim3(8 * 64), 0, s, a);   // X pieces of two chunks: 8 waves' worth of registers
         else hipLaunchKernelGGL((ecf8_gemm_anyk_kernel<4, 8, 64, SCALED>), dim3(grid), dim3(8 * 64), 0, s, a);
@@ -725,13 +784,13 @@ int launch_fused(const GArgs &a, void *stream)
     return hipGetLastError() == hipSuccess ? ECF8_OK : ECF8_E_HIP;
 }
 
-template <bool SCALED>
+template <int SCALED>
 int launch_raw(const GArgs &a, void *stream)
 {
     const int grid = grid_for(a.rows / BLOCK_ROWS);
     if (grid <= 0) return ECF8_E_HIP;
     hipStream_t s = (hipStream_t)stream;
-    if (a.K != GK) {
+    if (a.K != GK || (SCALED == 2 && a.M > 32)) {      // the same routes as the fused call: same order of accumulation
         if (a.M <= 16) hipLaunchKernelGGL((ecf8_gemm_raw_anyk_kernel<1, 16, 64, SCALED>), dim3(grid), dim3(16 * 64), 0, s, a);
         else if (a.M <= 32) hipLaunchKernelGGL((ecf8_gemm_raw_anyk_kernel<2, 8, 64, SCALED>), dim3(grid), dim3(8 * 64), 0, s, a);
         else hipLaunchKernelGGL((ecf8_gemm_raw_anyk_kernel<4, 8, 64, SCALED>), dim3(grid), dim3(8 * 64), 0, s, a);
@@ -751,7 +810,7 @@ int ecf8_gemm_fp8(const ecf8_header *h, const void *d_blob, const void *d_x, uin
 {
     GArgs a;
     int rc = fused_args(h, d_blob, d_x, M, d_y, &a);
-    return rc ? rc : launch_fused<false>(a, stream);
+    return rc ? rc : launch_fused<0>(a, stream);
 }
 
 int ecf8_gemm_fp8_raw(const void *d_w, uint64_t rows, uint64_t cols, const void *d_x, uint32_t M, float *d_y,
@@ -759,25 +818,27 @@ int ecf8_gemm_fp8_raw(const void *d_w, uint64_t rows, uint64_t cols, const void 
 {
     GArgs a;
     int rc = raw_args(d_w, rows, cols, d_x, M, d_y, &a);
-    return rc ? rc : launch_raw<false>(a, stream);
+    return rc ? rc : launch_raw<0>(a, stream);
 }
 
 int ecf8_gemm_fp8_scaled(const ecf8_header *h, const void *d_blob, const void *d_x, uint32_t M, const float *d_w_scale,
-                         const float *d_x_scale, float *d_y, void *stream)
+                         const float *d_x_scale, uint32_t x_scale_cols, float *d_y, void *stream)
 {
     GArgs a;
     int rc = fused_args(h, d_blob, d_x, M, d_y, &a);
-    if (!rc) rc = scale_args(d_w_scale, d_x_scale, &a);
-    return rc ? rc : launch_fused<true>(a, stream);
+    if (!rc) rc = scale_args(d_w_scale, d_x_scale, x_scale_cols, &a);
+    if (rc) return rc;
+    return a.xs_cols > 1 ? launch_fused<2>(a, stream) : launch_fused<1>(a, stream);
 }
 
 int ecf8_gemm_fp8_raw_scaled(const void *d_w, uint64_t rows, uint64_t cols, const void *d_x, uint32_t M,
-                             const float *d_w_scale, const float *d_x_scale, float *d_y, void *stream)
+                             const float *d_w_scale, const float *d_x_scale, uint32_t x_scale_cols, float *d_y, void *stream)
 {
     GArgs a;
     int rc = raw_args(d_w, rows, cols, d_x, M, d_y, &a);
-    if (!rc) rc = scale_args(d_w_scale, d_x_scale, &a);
-    return rc ? rc : launch_raw<true>(a, stream);
+    if (!rc) rc = scale_args(d_w_scale, d_x_scale, x_scale_cols, &a);
+    if (rc) return rc;
+    return a.xs_cols > 1 ? launch_raw<2>(a, stream) : launch_raw<1>(a, stream);
 }
 
 } // extern "C"

@@ -87,8 +87,8 @@ _lib.ecf8_batch_prepare.argtypes = [ctypes.POINTER(Header), ctypes.POINTER(_vp),
 _lib.ecf8_decode_batched.argtypes = [_vp, _u32, ctypes.POINTER(BatchInfo), _vp]
 _lib.ecf8_gemm_fp8.argtypes = [ctypes.POINTER(Header), _vp, _vp, _u32, _vp, _vp]
 _lib.ecf8_gemm_fp8_raw.argtypes = [_vp, _u64, _u64, _vp, _u32, _vp, _vp]
-_lib.ecf8_gemm_fp8_scaled.argtypes = [ctypes.POINTER(Header), _vp, _vp, _u32, _vp, _vp, _vp, _vp]
-_lib.ecf8_gemm_fp8_raw_scaled.argtypes = [_vp, _u64, _u64, _vp, _u32, _vp, _vp, _vp, _vp]
+_lib.ecf8_gemm_fp8_scaled.argtypes = [ctypes.POINTER(Header), _vp, _vp, _u32, _vp, _vp, _u32, _vp, _vp]
+_lib.ecf8_gemm_fp8_raw_scaled.argtypes = [_vp, _u64, _u64, _vp, _u32, _vp, _vp, _u32, _vp, _vp]
 _lib.ecf8_jit_create.argtypes = [_u32, _u32, ctypes.POINTER(_vp), _u64, ctypes.POINTER(_vp)]
 _lib.ecf8_jit_destroy.argtypes = [_vp]
 _lib.ecf8_jit_destroy.restype = None
@@ -366,31 +366,39 @@ def _scale_ptrs(fn, rows, cols, M, w_scale, x_scale):
     if (w_scale.dtype != torch.float32 or not w_scale.is_contiguous()
             or tuple(w_scale.shape) != ((rows + 127) // 128, cols // 128)):
         raise Ecf8Error(fn, E_ARG)
-    if x_scale is not None and (x_scale.dtype != torch.float32 or not x_scale.is_contiguous()
-                                or tuple(x_scale.shape) != (M,)):
-        raise Ecf8Error(fn, E_ARG)
-    return w_scale.data_ptr(), (x_scale.data_ptr() if x_scale is not None else None)
+    xs_cols = 0
+    if x_scale is not None:
+        if x_scale.dtype != torch.float32 or not x_scale.is_contiguous():
+            raise Ecf8Error(fn, E_ARG)
+        if tuple(x_scale.shape) == (M,):
+            xs_cols = 1
+        elif tuple(x_scale.shape) == (M, cols // 128):
+            xs_cols = cols // 128
+        else:
+            raise Ecf8Error(fn, E_ARG)
+    return w_scale.data_ptr(), (x_scale.data_ptr() if x_scale is not None else None), xs_cols
 
 
 def ecf8_gemm_fp8_scaled(hdr, d_blob, d_x, w_scale, x_scale=None, d_y=None, stream=None):
-    """Y = (x_scale X) @ (w_scale W).T: w_scale fp32 (ceil(rows/128), cols/128), x_scale fp32 (M,) or None."""
+    """Y = (x_scale X) @ (w_scale W).T: w_scale fp32 (ceil(rows/128), cols/128); x_scale fp32 (M,) for one scale
+    per row of X, (M, cols/128) for one per row and 128 columns, or None."""
     M = d_x.shape[0]
-    ws, xs = _scale_ptrs("ecf8_gemm_fp8_scaled", hdr.rows, hdr.cols, M, w_scale, x_scale)
+    ws, xs, xc = _scale_ptrs("ecf8_gemm_fp8_scaled", hdr.rows, hdr.cols, M, w_scale, x_scale)
     if d_y is None:
         d_y = torch.empty((M, hdr.rows), dtype=torch.float32, device=d_x.device)
     _check("ecf8_gemm_fp8_scaled", _lib.ecf8_gemm_fp8_scaled(ctypes.byref(hdr), d_blob.data_ptr(), d_x.data_ptr(), M,
-                                                             ws, xs, d_y.data_ptr(), _stream_ptr(stream)))
+                                                             ws, xs, xc, d_y.data_ptr(), _stream_ptr(stream)))
     return d_y
 
 
 def ecf8_gemm_fp8_raw_scaled(d_w, d_x, w_scale, x_scale=None, d_y=None, stream=None):
     M = d_x.shape[0]
     rows, cols = d_w.shape
-    ws, xs = _scale_ptrs("ecf8_gemm_fp8_raw_scaled", rows, cols, M, w_scale, x_scale)
+    ws, xs, xc = _scale_ptrs("ecf8_gemm_fp8_raw_scaled", rows, cols, M, w_scale, x_scale)
     if d_y is None:
         d_y = torch.empty((M, rows), dtype=torch.float32, device=d_x.device)
     _check("ecf8_gemm_fp8_raw_scaled", _lib.ecf8_gemm_fp8_raw_scaled(d_w.data_ptr(), rows, cols, d_x.data_ptr(), M,
-                                                                     ws, xs, d_y.data_ptr(), _stream_ptr(stream)))
+                                                                     ws, xs, xc, d_y.data_ptr(), _stream_ptr(stream)))
     return d_y
 
 

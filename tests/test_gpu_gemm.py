@@ -151,11 +151,13 @@ def test_block_scaled_gemm_against_oracle(orc, M):
     d_ws, d_xs = torch.from_numpy(ws).to(DEV), torch.from_numpy(xs).to(DEV)
     blob = ecf8.ecf8_encode(w, rows, K, lane_syms=64, tile_rows=16)
     d_blob = blob.to(DEV)
-    for use_xs in (True, False):
-        yref, mag = orc.gemm_ref_scaled(x, w, ws, xs if use_xs else None)
+    xg = np.exp(np.random.default_rng(M + 50).normal(0.0, 0.5, size=(M, K // 128))).astype(np.float32)
+    d_xg = torch.from_numpy(xg).to(DEV)
+    for xs_h, xs_d in ((xs, d_xs), (None, None), (xg, d_xg)):      # one scale per row, none, one per row and 128 columns
+        yref, mag = orc.gemm_ref_scaled(x, w, ws, xs_h)
         guard = torch.full((M + 2, rows), float("nan"), dtype=torch.float32, device=DEV)
-        y = ecf8.ecf8_gemm_fp8_scaled(blob.header, d_blob, d_x, d_ws, d_xs if use_xs else None, guard[1:M + 1])
-        raw = ecf8.ecf8_gemm_fp8_raw_scaled(d_w, d_x, d_ws, d_xs if use_xs else None)
+        y = ecf8.ecf8_gemm_fp8_scaled(blob.header, d_blob, d_x, d_ws, xs_d, guard[1:M + 1])
+        raw = ecf8.ecf8_gemm_fp8_raw_scaled(d_w, d_x, d_ws, xs_d)
         torch.cuda.synchronize()
         assert torch.isnan(guard[0]).all() and torch.isnan(guard[M + 1]).all()
         _check(y.cpu().numpy(), yref, mag, "scaled fused M=%d" % M)
@@ -254,7 +256,7 @@ def test_any_k_block_scaled_and_full_size(orc, M):
     x = synth.activations(M, K, seed=300 + M, device=DEV)
     rng = np.random.default_rng(M)
     ws = np.exp(rng.normal(0.0, 0.7, size=(rows // 128, K // 128))).astype(np.float32)
-    xs = np.exp(rng.normal(0.0, 0.5, size=M)).astype(np.float32)
+    xs = np.exp(rng.normal(0.0, 0.5, size=(M, K // 128))).astype(np.float32)      # activations quantised in 1 x 128 groups
     d_ws, d_xs = torch.from_numpy(ws).to(DEV), torch.from_numpy(xs).to(DEV)
     blob = ecf8.ecf8_encode(w.cpu(), rows, K, lane_syms=64, tile_rows=16)
     d_blob = blob.to(DEV)

@@ -55,6 +55,13 @@ def test_scaled_gemm_against_dequantised_float64_matmul(orc):
     Y, A = orc.gemm_ref_scaled(X, W, ws, xs)
     assert np.allclose(Y, xdq @ wdq.T, rtol=1e-12, atol=0)
     assert np.allclose(A, np.abs(xdq) @ np.abs(wdq).T, rtol=1e-12, atol=0)
+    # one scale per row of X and 128 columns
+    xg = rng.uniform(0.1, 3.0, size=(M, 3)).astype(np.float32)
+    xdg = xf * np.repeat(xg.astype(np.float64), 128, axis=1)[:, :K]
+    Yg, Ag = orc.gemm_ref_scaled(X, W, ws, xg)
+    mag = np.abs(xdg) @ np.abs(wdq).T                       # sums cancel: compare against the sum of magnitudes
+    assert np.all(np.abs(Yg - xdg @ wdq.T) <= 1e-13 * mag) and np.allclose(Ag, mag, rtol=1e-12, atol=0)
+    assert not np.allclose(Yg, Y)
     # no row scales = ones; unit scales = the unscaled reference, exactly
     Y1, _ = orc.gemm_ref_scaled(X, W, ws)
     assert np.allclose(Y1, xf @ wdq.T, rtol=1e-12, atol=0)
