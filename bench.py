@@ -333,6 +333,28 @@ def bench_jit(a):
     n_total = sum(t[0].numel() for l in range(layers) for t in per_layer[l])
     hidden = (t_serial - t_jit) / max(t_serial - t_res, 1e-9)
 
+    # no buffer at all: the same GEMMs with the weights decoded inside them (ecf8_gemm_fp8 on row-tiled blobs)
+    tiled = {}
+    for l in range(layers):
+        for w, _, _ in per_layer[l]:
+            w2 = w if w.shape[1] == 4096 else w.view(-1, 4096)
+            hdr_t, d_t = ecf8.ecf8_encode_gpu(w2, lane_syms=64, tile_rows=16)
+            tiled.setdefault(l, []).append((hdr_t, d_t.clone(), w2))
+    for hdr_t, d_t, w2 in tiled[0]:
+        ya = ecf8.ecf8_gemm_fp8(hdr_t, d_t, x)
+        yb = ecf8.ecf8_gemm_fp8_raw(w2, x)
+        torch.cuda.synchronize()
+        if not torch.equal(ya, yb):
+            raise SystemExit("jit: fused GEMM differs from the GEMM on resident weights")
+
+    def fused_pass():
+        for l in range(layers):
+            for hdr_t, d_t, w2 in tiled[l]:
+                ecf8.ecf8_gemm_fp8(hdr_t, d_t, x, y[:, :w2.shape[0]], stream=main_stream)
+    t_fused = timed(fused_pass)
+    tiled_bytes = sum(h.total_size for l in tiled for h, _, _ in tiled[l])
+    del tiled
+
     # the same three timings with a compute-bound consumer (one bf16 4096^3 matmul per layer that does
     # not read the weights), and the decode confined to fewer workgroups so that the consumer's
     # kernels find free compute units while it runs
@@ -355,7 +377,9 @@ def bench_jit(a):
                    "weights": n_total, "seed": a.seed},
         "bit_exact": True, "setup_s": round(setup, 1),
         "pass_ms": {"compute_on_resident_weights": round(t_res, 4), "decode_then_compute_1_buffer": round(t_serial, 4),
-                    "jit_2_buffers_overlapped": round(t_jit, 4)},
+                    "jit_2_buffers_overlapped": round(t_jit, 4),
+                    "fused_decode_gemm_no_buffer": round(t_fused, 4)},
+        "resident_compressed_bytes_row_tiled": tiled_bytes,
         "decode_time_hidden_frac": round(hidden, 3),
         "pass_ms_with_compute_bound_consumer": mm,
         "buffer_bytes_each": jit2.buffer_bytes, "resident_compressed_bytes": sum(h.total_size for hs, _ in packed for h in hs)}))
