@@ -228,6 +228,34 @@ def bench_config4(a):
                            "decode_then_gemm_us": round(t2 * 1e6, 2),
                            "vendor_fp8_gemm_us": None if t_vendor is None else round(t_vendor * 1e6, 2),
                            "fused_weight_GBps": round(w.numel() / tf / 1e9, 1)}
+    # beyond the fused call's M: two calls of 64 rows against decoding W once and calling the vendor library's GEMM
+    crossover = None
+    try:
+        x128 = synth.activations(128, spec["cols"], seed=a.seed, device="cuda:0")
+        y128 = torch.empty((128, spec["rows"]), dtype=torch.float32, device="cuda:0")
+        one = torch.ones((), device="cuda:0", dtype=torch.float32)
+
+        def fused_twice():
+            ecf8.ecf8_gemm_fp8(h, d_blob, x128[:64], y128[:64])
+            ecf8.ecf8_gemm_fp8(h, d_blob, x128[64:], y128[64:])
+
+        def decode_then_vendor():
+            ecf8.ecf8_decode(h_lin, d_lin, wout)
+            return torch._scaled_mm(x128.view(torch.float8_e4m3fn), wout.view(torch.float8_e4m3fn).t(), scale_a=one,
+                                    scale_b=one, out_dtype=torch.float32)
+        fused_twice()
+        ref = decode_then_vendor()
+        torch.cuda.synchronize()
+        if (ref - y128).abs().max().item() <= 1e-4 * y128.abs().max().item():
+            crossover = {"M": 128, "fused_two_calls_us": round(timeit(fused_twice, a.steps, a.warmup) * 1e6, 2),
+                         "decode_then_vendor_gemm_us": round(timeit(decode_then_vendor, a.steps, a.warmup) * 1e6, 2)}
+            x64 = x128[:64].contiguous()
+            v64 = lambda: (ecf8.ecf8_decode(h_lin, d_lin, wout), torch._scaled_mm(
+                x64.view(torch.float8_e4m3fn), wout.view(torch.float8_e4m3fn).t(), scale_a=one, scale_b=one,
+                out_dtype=torch.float32))
+            crossover["decode_then_vendor_gemm_us_at_M64"] = round(timeit(v64, a.steps, a.warmup) * 1e6, 2)
+    except Exception:
+        crossover = None
     # the any-K kernels on the down projection of the same stack (4096 x 14336; X is fetched chunk by chunk)
     wd = synth.make_weight(4096, 14336, 1.7, 0.02, a.seed, tensor_id=400001, device="cuda:0")
     bd = ecf8.ecf8_encode(wd.cpu(), 4096, 14336, lane_syms=64, tile_rows=16)
@@ -252,7 +280,7 @@ def bench_config4(a):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "fp8 x fp8 -> f32", "data": "synthetic",
         "config": {"workload": "config4: fused decode + FP8 MFMA GEMM, W 14336x4096, M in {1,16,64}", "seed": a.seed},
         "compression_ratio": round(h.total_size / w.numel(), 5), "bit_exact_vs_raw_weights_gemm": True,
-        "gemm": res, "gemm_down_4096x14336_any_k": res_down}))
+        "gemm": res, "beyond_M64": crossover, "gemm_down_4096x14336_any_k": res_down}))
 
 def bench_jit(a):
     """Workload "jit" (paper Section 3.3): a forward pass over the config-1 stack with the weights
