@@ -63,11 +63,10 @@ struct GArgs {
     uint32_t M;
     uint64_t d_ws, d_xs;                  // SCALED kernels: per-128x128-block scales of W, scales of X (or 0)
     uint32_t xs_cols;                     // scales per row of X: 1, or K / 128 (one per 128 columns)
-    uint64_t K;                           // any-K kernels: columns of W (a multiple of 256)
+    uint64_t K;                           // columns of W (a multiple of 256; 4096 for the fixed-K kernels)
 };
 
 constexpr int SCALE_BLOCK = 128;                // W carries one fp32 scale per 128 x 128 block
-constexpr int KBLOCKS = GK / SCALE_BLOCK;
 
 // acc += part * s, element by element, the same operation in the fused and in the raw kernel
 // acc += part * (s * x-scale), element by element, where X carries one scale per row and 128 columns: the
@@ -129,6 +128,43 @@ __device__ __forceinline__ void load_x_slice(const GArgs &a, int tid,
             }
 }
 
+// The sums of one chunk (16 rows x 256 columns).  Without scales a chunk adds straight into the block's
+// accumulators.  With scales its two 128-column halves -- exactly its forward and its backward run --
+// are summed by the matrix cores apart and enter the block's sum through one multiply-add each, with
+// the scale of their 128 x 128 block of W (times the scale of X for that row and slice, if X has those).
+template <int MT, int SC>
+struct ChunkSums {
+    static constexpr bool SCALED = SC != 0, XGROUPS = SC == 2;
+    f32x4 partA[SCALED ? MT : 1], partB[SCALED ? MT : 1];
+    float sA = 1.f, sB = 1.f;
+    uint32_t kbA = 0;              // the chunk's first 128-column block of K
+
+    __device__ __forceinline__ void begin(const GArgs &a, uint64_t block, uint32_t kc)
+    {
+        if constexpr (SCALED) {
+            const GLOBAL float *ws = (const GLOBAL float *)a.d_ws + (block * BLOCK_ROWS / SCALE_BLOCK) * (a.K / SCALE_BLOCK) + 2 * kc;
+            sA = ws[0];
+            sB = ws[1];
+            kbA = 2 * kc;
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++) partA[mt] = partB[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+    }
+    // where the MFMAs of the forward / backward run accumulate
+    __device__ __forceinline__ auto &first(f32x4 (&acc)[MT]) { if constexpr (SCALED) return partA; else return acc; }
+    __device__ __forceinline__ auto &second(f32x4 (&acc)[MT]) { if constexpr (SCALED) return partB; else return acc; }
+    __device__ __forceinline__ void end(f32x4 (&acc)[MT], const GArgs &a, int lane)
+    {
+        if constexpr (XGROUPS) {   // the scales of X are fetched here: held over the decode they would cost it registers
+            add_scaled_group<MT>(acc, partA, sA, a, lane, kbA);
+            add_scaled_group<MT>(acc, partB, sB, a, lane, kbA + 1);
+        } else if constexpr (SCALED) {
+            add_scaled<MT>(acc, partA, sA);
+            add_scaled<MT>(acc, partB, sB);
+        }
+    }
+};
+
 // One piece (16 K-elements of this lane's row of W, in w) times the matching 16 columns of X.
 // Note on accuracy: the FP8 matrix core aligns each lane's 8 products to the largest of them and
 // truncates what lies more than about 13 bits below it, so a result can be off by up to
@@ -170,7 +206,7 @@ __device__ __forceinline__ void reduce_block(f32x4 *red, const GArgs &a, uint64_
 template <int MT, int NW, int N, int SC>       // SC: 0 no scales, 1 scales of W (and one per row of X), 2 also one per row and 128 columns of X
 __global__ __launch_bounds__(NW * 64) void ecf8_gemm_kernel(GArgs a)
 {
-    constexpr bool SCALED = SC != 0, XGROUPS = SC == 2;
+    constexpr bool SCALED = SC != 0;
     static_assert(!SCALED || 4 * N == 2 * SCALE_BLOCK, "a chunk spans two scale blocks of K");
     using C = GCfg<MT, NW, N>;
     constexpr int KPW = C::KPW, KCHUNKS = C::KCHUNKS, BLOCK_COLS = C::BLOCK_COLS;
@@ -284,21 +320,10 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_kernel(GArgs a)
             }
             uint32_t bpA = stage_off * 8 + (uint32_t)(start - byte0 * 8) + rel - 1;   // one bit off, see quad_step2
             uint32_t bpB = bpA + m.lb - 30;
-            // SCALED: the chunk's two 128-column halves (forward run / backward run) are summed apart
-            // and enter the block's sum with the scale of their 128 x 128 block of W
-            f32x4 partA[SCALED ? MT : 1], partB[SCALED ? MT : 1];
-            float sA = 1.f, sB = 1.f;
-            uint32_t kbA = 0;              // the chunk's first 128-column block of K
-            if constexpr (SCALED) {
-                const GLOBAL float *ws = (const GLOBAL float *)a.d_ws + (block_of(s) * BLOCK_ROWS / SCALE_BLOCK) * KBLOCKS + 2 * kc_of(s);
-                sA = ws[0];
-                sB = ws[1];
-                kbA = 2 * kc_of(s);
-#pragma unroll
-                for (int mt = 0; mt < MT; mt++) partA[mt] = partB[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-            }
-            auto &dstA = *[&]() { if constexpr (SCALED) return &partA; else return &acc; }();
-            auto &dstB = *[&]() { if constexpr (SCALED) return &partB; else return &acc; }();
+            ChunkSums<MT, SC> sums;
+            sums.begin(a, block_of(s), kc_of(s));
+            auto &dstA = sums.first(acc);
+            auto &dstB = sums.second(acc);
 #pragma unroll
             for (int Q = 0; Q < GPIECES / 2; Q++) {
                 uint32_t dwA[4], dwB[4];
@@ -307,15 +332,7 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_kernel(GArgs a)
                 ECF8_MFMA_PIECE(dstA, areg, i, Q, merge_piece(dwA, pl[Q]));
                 ECF8_MFMA_PIECE(dstB, areg, i, Q + GPIECES / 2, merge_piece(dwB, pl[Q + GPIECES / 2]));
             }
-            if constexpr (SCALED) {
-                if constexpr (XGROUPS) {    // fetched late: held over the decode they would cost it registers
-                    add_scaled_group<MT>(acc, partA, sA, a, lane, kbA);
-                    add_scaled_group<MT>(acc, partB, sB, a, lane, kbA + 1);
-                } else {
-                    add_scaled<MT>(acc, partA, sA);
-                    add_scaled<MT>(acc, partB, sB);
-                }
-            }
+            sums.end(acc, a, lane);
             m_cur = m_next;
             m_next = m_next2;
         }
@@ -329,7 +346,7 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_kernel(GArgs a)
 template <int MT, int NW, int N, int SC>       // SC: 0 no scales, 1 scales of W (and one per row of X), 2 also one per row and 128 columns of X
 __global__ __launch_bounds__(NW * 64) void ecf8_gemm_raw_kernel(GArgs a)
 {
-    constexpr bool SCALED = SC != 0, XGROUPS = SC == 2;
+    constexpr bool SCALED = SC != 0;
     using C = GCfg<MT, NW, N>;
     constexpr int KPW = C::KPW, BLOCK_COLS = C::BLOCK_COLS, GPIECES = C::PIECES;
     __shared__ __attribute__((aligned(16))) uint8_t smem[2 * C::RED_BYTES];
@@ -359,34 +376,16 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_raw_kernel(GArgs a)
 #pragma unroll
             for (int q = 0; q < GPIECES; q++) w_next[q] = w_cur[q];
             if (s + 1 < n_steps) load_w(s + 1, w_next);
-            f32x4 partA[SCALED ? MT : 1], partB[SCALED ? MT : 1];
-            float sA = 1.f, sB = 1.f;
-            uint32_t kbA = 0;              // the chunk's first 128-column block of K
-            if constexpr (SCALED) {
-                const GLOBAL float *ws = (const GLOBAL float *)a.d_ws + (block_of(s) * BLOCK_ROWS / SCALE_BLOCK) * KBLOCKS +
-                                         2 * (wave + NW * (uint32_t)(s % KPW));
-                sA = ws[0];
-                sB = ws[1];
-                kbA = 2 * (wave + NW * (uint32_t)(s % KPW));
-#pragma unroll
-                for (int mt = 0; mt < MT; mt++) partA[mt] = partB[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-            }
-            auto &dstA = *[&]() { if constexpr (SCALED) return &partA; else return &acc; }();
-            auto &dstB = *[&]() { if constexpr (SCALED) return &partB; else return &acc; }();
+            ChunkSums<MT, SC> sums;
+            sums.begin(a, block_of(s), wave + NW * (uint32_t)(s % KPW));
+            auto &dstA = sums.first(acc);
+            auto &dstB = sums.second(acc);
 #pragma unroll
             for (int Q = 0; Q < GPIECES / 2; Q++) {
                 ECF8_MFMA_PIECE(dstA, areg, i, Q, w_cur[Q]);
                 ECF8_MFMA_PIECE(dstB, areg, i, Q + GPIECES / 2, w_cur[Q + GPIECES / 2]);
             }
-            if constexpr (SCALED) {
-                if constexpr (XGROUPS) {    // fetched late: held over the decode they would cost it registers
-                    add_scaled_group<MT>(acc, partA, sA, a, lane, kbA);
-                    add_scaled_group<MT>(acc, partB, sB, a, lane, kbA + 1);
-                } else {
-                    add_scaled<MT>(acc, partA, sA);
-                    add_scaled<MT>(acc, partB, sB);
-                }
-            }
+            sums.end(acc, a, lane);
 #pragma unroll
             for (int q = 0; q < GPIECES; q++) w_cur[q] = w_next[q];
         }
@@ -439,7 +438,7 @@ struct Walk {
 template <int MT, int NW, int N, int SC>       // SC: 0 no scales, 1 scales of W (and one per row of X), 2 also one per row and 128 columns of X
 __global__ __launch_bounds__(NW * 64) void ecf8_gemm_anyk_kernel(GArgs a)
 {
-    constexpr bool SCALED = SC != 0, XGROUPS = SC == 2;
+    constexpr bool SCALED = SC != 0;
     using C = GCfg<MT, NW, N>;
     constexpr int BLOCK_COLS = C::BLOCK_COLS, GPIECES = C::PIECES, GSTAGE = C::STAGE, GSEGS = C::SEGS;
     static_assert(!SCALED || 4 * N == 2 * SCALE_BLOCK, "a chunk spans two scale blocks of K");
@@ -545,15 +544,8 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_anyk_kernel(GArgs a)
 #pragma unroll
             for (int q = 0; q < GPIECES; q++) pl[q] = p_cur.pl[q];
             const XPieces<MT, N> x = x_cur;
-            float sA = 1.f, sB = 1.f;
-            uint32_t kbA = 0;              // the chunk's first 128-column block of K
-            if constexpr (SCALED) {
-                const GLOBAL float *ws = (const GLOBAL float *)a.d_ws + (block_of(cur) * BLOCK_ROWS / SCALE_BLOCK) * (a.K / SCALE_BLOCK) +
-                                         2 * kc_of(cur);
-                sA = ws[0];
-                sB = ws[1];
-                kbA = 2 * kc_of(cur);
-            }
+            ChunkSums<MT, SC> sums;
+            sums.begin(a, block_of(cur), kc_of(cur));
             // the payload registers are free: fetch the next chunk and its share of X, and the metadata of the one after
             const Walk nxt = next_of(cur);
             Meta m_next2 = m_next;
@@ -564,13 +556,8 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_anyk_kernel(GArgs a)
             }
             uint32_t bpA = stage_off * 8 + (uint32_t)(start - byte0 * 8) + rel - 1;   // one bit off, see quad_step2
             uint32_t bpB = bpA + m.lb - 30;
-            f32x4 partA[SCALED ? MT : 1], partB[SCALED ? MT : 1];
-            if constexpr (SCALED) {
-#pragma unroll
-                for (int mt = 0; mt < MT; mt++) partA[mt] = partB[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-            }
-            auto &dstA = *[&]() { if constexpr (SCALED) return &partA; else return &acc; }();
-            auto &dstB = *[&]() { if constexpr (SCALED) return &partB; else return &acc; }();
+            auto &dstA = sums.first(acc);
+            auto &dstB = sums.second(acc);
 #pragma unroll
             for (int Q = 0; Q < GPIECES / 2; Q++) {
                 uint32_t dwA[4], dwB[4];
@@ -579,15 +566,7 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_anyk_kernel(GArgs a)
                 ECF8_MFMA_XPIECE(dstA, x, Q, merge_piece(dwA, pl[Q]));
                 ECF8_MFMA_XPIECE(dstB, x, Q + GPIECES / 2, merge_piece(dwB, pl[Q + GPIECES / 2]));
             }
-            if constexpr (SCALED) {
-                if constexpr (XGROUPS) {    // fetched late: held over the decode they would cost it registers
-                    add_scaled_group<MT>(acc, partA, sA, a, lane, kbA);
-                    add_scaled_group<MT>(acc, partB, sB, a, lane, kbA + 1);
-                } else {
-                    add_scaled<MT>(acc, partA, sA);
-                    add_scaled<MT>(acc, partB, sB);
-                }
-            }
+            sums.end(acc, a, lane);
             cur = nxt;
             m_cur = m_next;
             m_next = m_next2;
@@ -601,7 +580,7 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_anyk_kernel(GArgs a)
 template <int MT, int NW, int N, int SC>       // SC: 0 no scales, 1 scales of W (and one per row of X), 2 also one per row and 128 columns of X
 __global__ __launch_bounds__(NW * 64) void ecf8_gemm_raw_anyk_kernel(GArgs a)
 {
-    constexpr bool SCALED = SC != 0, XGROUPS = SC == 2;
+    constexpr bool SCALED = SC != 0;
     using C = GCfg<MT, NW, N>;
     constexpr int BLOCK_COLS = C::BLOCK_COLS, GPIECES = C::PIECES;
     __shared__ __attribute__((aligned(16))) uint8_t smem[2 * C::RED_BYTES];
@@ -636,15 +615,8 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_raw_anyk_kernel(GArgs a)
 #pragma unroll 1
         for (uint32_t i = 0; i < my_chunks; i++) {
             const XPieces<MT, N> x = x_cur;
-            float sA = 1.f, sB = 1.f;
-            uint32_t kbA = 0;              // the chunk's first 128-column block of K
-            if constexpr (SCALED) {
-                const GLOBAL float *ws = (const GLOBAL float *)a.d_ws + (block_of(cur) * BLOCK_ROWS / SCALE_BLOCK) * (a.K / SCALE_BLOCK) +
-                                         2 * kc_of(cur);
-                sA = ws[0];
-                sB = ws[1];
-                kbA = 2 * kc_of(cur);
-            }
+            ChunkSums<MT, SC> sums;
+            sums.begin(a, block_of(cur), kc_of(cur));
             const Walk nxt = next_of(cur);
 #pragma unroll
             for (int q = 0; q < GPIECES; q++) w_next[q] = w_cur[q];
@@ -652,27 +624,14 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_raw_anyk_kernel(GArgs a)
                 load_w(nxt, w_next);
                 load_x_chunk<MT, N>(a, lane, kc_of(nxt), x_cur);
             }
-            f32x4 partA[SCALED ? MT : 1], partB[SCALED ? MT : 1];
-            if constexpr (SCALED) {
-#pragma unroll
-                for (int mt = 0; mt < MT; mt++) partA[mt] = partB[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-            }
-            auto &dstA = *[&]() { if constexpr (SCALED) return &partA; else return &acc; }();
-            auto &dstB = *[&]() { if constexpr (SCALED) return &partB; else return &acc; }();
+            auto &dstA = sums.first(acc);
+            auto &dstB = sums.second(acc);
 #pragma unroll
             for (int Q = 0; Q < GPIECES / 2; Q++) {
                 ECF8_MFMA_XPIECE(dstA, x, Q, w_cur[Q]);
                 ECF8_MFMA_XPIECE(dstB, x, Q + GPIECES / 2, w_cur[Q + GPIECES / 2]);
             }
-            if constexpr (SCALED) {
-                if constexpr (XGROUPS) {    // fetched late: held over the decode they would cost it registers
-                    add_scaled_group<MT>(acc, partA, sA, a, lane, kbA);
-                    add_scaled_group<MT>(acc, partB, sB, a, lane, kbA + 1);
-                } else {
-                    add_scaled<MT>(acc, partA, sA);
-                    add_scaled<MT>(acc, partB, sB);
-                }
-            }
+            sums.end(acc, a, lane);
 #pragma unroll
             for (int q = 0; q < GPIECES; q++) w_cur[q] = w_next[q];
             cur = nxt;
@@ -780,7 +739,7 @@ int launch_fused(const GArgs &a, void *stream)
     }
     if (a.M <= 16) hipLaunchKernelGGL((ecf8_gemm_kernel<1, 16, 64, SCALED>), dim3(grid), dim3(16 * 64), 0, s, a);
     else if (a.M <= 32) hipLaunchKernelGGL((ecf8_gemm_kernel<2, 16, 64, SCALED>), dim3(grid), dim3(16 * 64), 0, s, a);
-    else hipLaunchKernelGGL((ecf8_gemm_kernel<4, 8, 64, SCALED>), dim3(grid), dim3(8 * 64), 0, s, a);
+    else if constexpr (SCALED != 2) hipLaunchKernelGGL((ecf8_gemm_kernel<4, 8, 64, SCALED>), dim3(grid), dim3(8 * 64), 0, s, a);
     return hipGetLastError() == hipSuccess ? ECF8_OK : ECF8_E_HIP;
 }
 
@@ -798,7 +757,7 @@ int launch_raw(const GArgs &a, void *stream)
     }
     if (a.M <= 16) hipLaunchKernelGGL((ecf8_gemm_raw_kernel<1, 16, 64, SCALED>), dim3(grid), dim3(16 * 64), 0, s, a);
     else if (a.M <= 32) hipLaunchKernelGGL((ecf8_gemm_raw_kernel<2, 16, 64, SCALED>), dim3(grid), dim3(16 * 64), 0, s, a);
-    else hipLaunchKernelGGL((ecf8_gemm_raw_kernel<4, 8, 64, SCALED>), dim3(grid), dim3(8 * 64), 0, s, a);
+    else if constexpr (SCALED != 2) hipLaunchKernelGGL((ecf8_gemm_raw_kernel<4, 8, 64, SCALED>), dim3(grid), dim3(8 * 64), 0, s, a);
     return hipGetLastError() == hipSuccess ? ECF8_OK : ECF8_E_HIP;
 }
 
