@@ -304,6 +304,45 @@ int ecf8_gemm_fp8_raw_scaled(const void *d_w, uint64_t rows, uint64_t cols, cons
                              float *d_y, void *stream);
 
 /*
+ * Split K, for matrices of few rows and long K (rows / 16 well below the number
+ * of compute units: low-rank projections, routers).  The calls above give a block
+ * of 16 rows of W to one workgroup, so such a matrix would leave most of the chip
+ * idle; here `slices` workgroups share a block, each takes an equal part of its
+ * K / 256 chunks, writes its partial sums to the workspace, and the workgroup that
+ * arrives last adds the parts up in slice order (the result does not depend on the
+ * order of arrival; the raw twin takes the same steps and agrees bit for bit) and
+ * writes Y.  No workgroup waits for another.  Same operation, arguments, limits
+ * and errors as ecf8_gemm_fp8_scaled, with d_w_scale = d_x_scale = NULL and
+ * x_scale_cols = 0 for the unscaled product.
+ *   ecf8_gemm_splitk_slices           slices the calls will use for this shape on the
+ *                                     current device: the largest divisor of cols / 256
+ *                                     with rows / 16 * slices <= compute units (1 = the
+ *                                     matrix has blocks enough and the calls fall through
+ *                                     to the plain kernels; 0 = bad shape or no device)
+ *   ecf8_gemm_splitk_workspace_bytes  size the calls need for (rows, cols, M) on the
+ *                                     current device: 0 when slices <= 1, else
+ *                                     4096 + rows / 16 * slices * 1024 * (1, 2 or 4 for M <= 16, 32, 64)
+ *   ecf8_gemm_splitk_workspace_init   zeroes a workspace (a kernel on `stream`): once
+ *                                     after allocating it
+ * d_workspace: DEVICE, 16-byte aligned, caller-owned, workspace_bytes >= the size
+ * above (ECF8_E_CAPACITY otherwise; may be NULL when that size is 0).  Its first
+ * 4096 bytes are the arrival counters, which every call leaves at zero as it found them, so
+ * one workspace serves any number of calls of any shapes it is large enough for,
+ * one after the other; calls that overlap in time need a workspace each.  A call
+ * that did not run to its end (a device error) leaves the counters undefined:
+ * initialise again.
+ */
+uint32_t ecf8_gemm_splitk_slices(uint64_t rows, uint64_t cols);
+uint64_t ecf8_gemm_splitk_workspace_bytes(uint64_t rows, uint64_t cols, uint32_t M);
+int ecf8_gemm_splitk_workspace_init(void *d_workspace, uint64_t workspace_bytes, void *stream);
+int ecf8_gemm_fp8_splitk(const ecf8_header *hdr, const void *d_blob, const void *d_x, uint32_t M,
+                         const float *d_w_scale, const float *d_x_scale, uint32_t x_scale_cols,
+                         float *d_y, void *d_workspace, uint64_t workspace_bytes, void *stream);
+int ecf8_gemm_fp8_raw_splitk(const void *d_w, uint64_t rows, uint64_t cols, const void *d_x, uint32_t M,
+                             const float *d_w_scale, const float *d_x_scale, uint32_t x_scale_cols,
+                             float *d_y, void *d_workspace, uint64_t workspace_bytes, void *stream);
+
+/*
  * Just-in-time layer decode (Section 3.3: compressed layers stay resident, a
  * layer is decoded into a pre-allocated buffer right before its forward pass
  * and the buffer is reused by later layers).  The manager is host-side

@@ -64,6 +64,8 @@ struct GArgs {
     uint64_t d_ws, d_xs;                  // SCALED kernels: per-128x128-block scales of W, scales of X (or 0)
     uint32_t xs_cols;                     // scales per row of X: 1, or K / 128 (one per 128 columns)
     uint64_t K;                           // columns of W (a multiple of 256; 4096 for the fixed-K kernels)
+    uint32_t slices;                      // split K: workgroups that share a block of rows (divides K / 256), else 1
+    uint64_t d_part, d_ctr;               // split K: partial sums [block][slice][MT * 256] fp32, arrival counters [block] u32
 };
 
 constexpr int SCALE_BLOCK = 128;                // W carries one fp32 scale per 128 x 128 block
@@ -201,6 +203,49 @@ __device__ __forceinline__ void reduce_block(f32x4 *red, const GArgs &a, uint64_
             Y[(uint64_t)m * a.rows + block * BLOCK_ROWS + (l & 15)] = sum;
         }
     }
+}
+
+// Split K: the partial sums of the unit (block of rows, slice of K) go to the workspace, and the
+// workgroup that brings a block's last slice adds the slices up -- in slice order, so the result
+// does not depend on which one that was -- and writes the outputs.  No workgroup waits for
+// another.  The partial sums travel through agent-coherent stores and loads, ordered against the
+// arrival counter by fences; the last workgroup leaves the counter at zero for the next call.
+template <int MT, int NW, bool SCALED>
+__device__ __forceinline__ void reduce_split(f32x4 *red, uint32_t *s_flag, const GArgs &a, uint32_t block, uint32_t slice,
+                                             int tid, const f32x4 (&acc)[MT])
+{
+    const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++) red[(wave * MT + mt) * 64 + lane] = acc[mt];
+    __syncthreads();
+    GLOBAL uint32_t *part = (GLOBAL uint32_t *)a.d_part + (uint64_t)block * a.slices * (MT * 256);
+    GLOBAL uint32_t *ctr = (GLOBAL uint32_t *)a.d_ctr + block;
+    for (int o = tid; o < MT * 256; o += NW * 64) {
+        const int mt = o >> 8, l = (o >> 2) & 63, r = o & 3;
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; w++) sum += ((const float *)&red[(w * MT + mt) * 64 + l])[r];
+        __hip_atomic_store(part + (uint64_t)slice * (MT * 256) + o, __float_as_uint(sum), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) *s_flag = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (*s_flag != a.slices - 1) return;          // uniform: the same LDS word for every thread
+    __threadfence();
+    GLOBAL float *Y = (GLOBAL float *)a.d_y;
+    for (int o = tid; o < MT * 256; o += NW * 64) {
+        const int mt = o >> 8, l = (o >> 2) & 63, r = o & 3;
+        float sum = 0.f;
+        for (uint32_t sl = 0; sl < a.slices; sl++)
+            sum += __uint_as_float(__hip_atomic_load(part + (uint64_t)sl * (MT * 256) + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        const uint32_t m = 16 * mt + 4 * (l >> 4) + r;
+        if (m < a.M) {
+            if (SCALED && a.d_xs && a.xs_cols == 1) sum *= ((const GLOBAL float *)a.d_xs)[m];
+            Y[(uint64_t)m * a.rows + (uint64_t)block * BLOCK_ROWS + (l & 15)] = sum;
+        }
+    }
+    if (tid == 0) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 template <int MT, int NW, int N, int SC>       // SC: 0 no scales, 1 scales of W (and one per row of X), 2 also one per row and 128 columns of X
@@ -429,15 +474,21 @@ __device__ __forceinline__ void load_x_chunk(const GArgs &a, int lane, uint32_t 
         }                                                                                                \
     } while (0)
 
-// Position of a wave in its sequence of chunks: its i-th chunk of its b-th block of rows.
+// Position of a wave in its sequence of chunks: its i-th chunk of its workgroup's b-th unit.  A unit
+// is a block of 16 rows of W, or with split K one of the `slices` equal parts of its chunks: `block`
+// is the unit's block of rows, k0 its first chunk.
 struct Walk {
     uint64_t b;
     uint32_t i;
+    uint64_t block;
+    uint32_t k0;
 };
 
-template <int MT, int NW, int N, int SC>       // SC: 0 no scales, 1 scales of W (and one per row of X), 2 also one per row and 128 columns of X
+template <int MT, int NW, int N, int SC, bool SPLIT = false>   // SC: 0 no scales, 1 scales of W (and one per row of X), 2 also one per row and 128 columns of X
 __global__ __launch_bounds__(NW * 64) void ecf8_gemm_anyk_kernel(GArgs a)
 {
+    __shared__ uint32_t s_flag;                   // split K: the arrival count this workgroup drew
+    (void)s_flag;
     constexpr bool SCALED = SC != 0;
     using C = GCfg<MT, NW, N>;
     constexpr int BLOCK_COLS = C::BLOCK_COLS, GPIECES = C::PIECES, GSTAGE = C::STAGE, GSEGS = C::SEGS;
@@ -456,16 +507,26 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_anyk_kernel(GArgs a)
     const GLOBAL uint8_t *plane = (const GLOBAL uint8_t *)(a.d_blob + a.off_pl);
     const uint64_t lane_elem = (uint64_t)(lane & 15) * a.K + (uint64_t)(lane >> 4) * 16;
     const uint32_t kchunks = (uint32_t)(a.K / BLOCK_COLS);
-    const uint32_t my_chunks = kchunks > (uint32_t)wave ? (kchunks - wave + NW - 1) / NW : 0;     // wave-uniform
-    const uint64_t n_blocks = a.rows / BLOCK_ROWS;
-    const uint64_t my_blocks = blockIdx.x < n_blocks ? (n_blocks - blockIdx.x + gridDim.x - 1) / gridDim.x : 0;
+    const uint32_t unit_chunks = SPLIT ? kchunks / a.slices : kchunks;                                     // chunks of K per unit
+    const uint32_t my_chunks = unit_chunks > (uint32_t)wave ? (unit_chunks - wave + NW - 1) / NW : 0;     // wave-uniform
+    const uint64_t n_units = a.rows / BLOCK_ROWS * (SPLIT ? a.slices : 1u);
+    const uint64_t my_blocks = blockIdx.x < n_units ? (n_units - blockIdx.x + gridDim.x - 1) / gridDim.x : 0;   // units of this workgroup
 
     struct Meta { uint64_t b0, b1; uint32_t lb; };
     struct Payload { u32x4 seg[GSEGS]; u32x2 pl[GPIECES]; };
-    auto block_of = [&](const Walk &w) -> uint64_t { return blockIdx.x + w.b * (uint64_t)gridDim.x; };
-    auto kc_of = [&](const Walk &w) -> uint32_t { return wave + NW * w.i; };
+    auto at_unit = [&](uint64_t b) {
+        Walk w{b, 0, blockIdx.x + b * (uint64_t)gridDim.x, 0};
+        if constexpr (SPLIT) {
+            const uint32_t u = (uint32_t)w.block;            // units < 2^31, checked on the host
+            w.block = u / a.slices;
+            w.k0 = (u % a.slices) * unit_chunks;
+        }
+        return w;
+    };
+    auto block_of = [&](const Walk &w) -> uint64_t { return w.block; };
+    auto kc_of = [&](const Walk &w) -> uint32_t { return w.k0 + wave + NW * w.i; };
     auto valid = [&](const Walk &w) { return my_chunks != 0 && w.b < my_blocks; };
-    auto next_of = [&](Walk w) { if (++w.i == my_chunks) { w.i = 0; w.b++; } return w; };
+    auto next_of = [&](Walk w) { if (++w.i == my_chunks) w = at_unit(w.b + 1); return w; };
     auto load_meta = [&](const Walk &w) {
         const uint64_t c = block_of(w) * kchunks + kc_of(w);
         Meta m;
@@ -499,7 +560,7 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_anyk_kernel(GArgs a)
         return p;
     };
 
-    Walk cur{0, 0};
+    Walk cur = at_unit(0);
     Meta m_cur{0, 0, 0}, m_next{0, 0, 0};
     Payload p_cur;
     XPieces<MT, N> x_cur;
@@ -571,15 +632,20 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_anyk_kernel(GArgs a)
             m_cur = m_next;
             m_next = m_next2;
         }
-        reduce_block<MT, NW, SCALED>((f32x4 *)(smem + C::OFF_RED + parity * C::RED_BYTES), a, blockIdx.x + b * (uint64_t)gridDim.x, tid, acc);
+        f32x4 *red = (f32x4 *)(smem + C::OFF_RED + parity * C::RED_BYTES);
+        const Walk unit = at_unit(b);
+        if constexpr (SPLIT) reduce_split<MT, NW, SCALED>(red, &s_flag, a, (uint32_t)unit.block, unit.k0 / unit_chunks, tid, acc);
+        else reduce_block<MT, NW, SCALED>(red, a, unit.block, tid, acc);
         parity ^= 1;
     }
 }
 
 // The any-K GEMM on uncompressed W: same deal of chunks, same order of accumulation.
-template <int MT, int NW, int N, int SC>       // SC: 0 no scales, 1 scales of W (and one per row of X), 2 also one per row and 128 columns of X
+template <int MT, int NW, int N, int SC, bool SPLIT = false>   // SC: 0 no scales, 1 scales of W (and one per row of X), 2 also one per row and 128 columns of X
 __global__ __launch_bounds__(NW * 64) void ecf8_gemm_raw_anyk_kernel(GArgs a)
 {
+    __shared__ uint32_t s_flag;                   // split K: the arrival count this workgroup drew
+    (void)s_flag;
     constexpr bool SCALED = SC != 0;
     using C = GCfg<MT, NW, N>;
     constexpr int BLOCK_COLS = C::BLOCK_COLS, GPIECES = C::PIECES;
@@ -588,19 +654,29 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_raw_anyk_kernel(GArgs a)
     const GLOBAL uint8_t *W = (const GLOBAL uint8_t *)a.d_w;
     const uint64_t lane_elem = (uint64_t)(lane & 15) * a.K + (uint64_t)(lane >> 4) * 16;
     const uint32_t kchunks = (uint32_t)(a.K / BLOCK_COLS);
-    const uint32_t my_chunks = kchunks > (uint32_t)wave ? (kchunks - wave + NW - 1) / NW : 0;
-    const uint64_t n_blocks = a.rows / BLOCK_ROWS;
-    const uint64_t my_blocks = blockIdx.x < n_blocks ? (n_blocks - blockIdx.x + gridDim.x - 1) / gridDim.x : 0;
-    auto block_of = [&](const Walk &w) -> uint64_t { return blockIdx.x + w.b * (uint64_t)gridDim.x; };
-    auto kc_of = [&](const Walk &w) -> uint32_t { return wave + NW * w.i; };
+    const uint32_t unit_chunks = SPLIT ? kchunks / a.slices : kchunks;
+    const uint32_t my_chunks = unit_chunks > (uint32_t)wave ? (unit_chunks - wave + NW - 1) / NW : 0;
+    const uint64_t n_units = a.rows / BLOCK_ROWS * (SPLIT ? a.slices : 1u);
+    const uint64_t my_blocks = blockIdx.x < n_units ? (n_units - blockIdx.x + gridDim.x - 1) / gridDim.x : 0;
+    auto at_unit = [&](uint64_t b) {
+        Walk w{b, 0, blockIdx.x + b * (uint64_t)gridDim.x, 0};
+        if constexpr (SPLIT) {
+            const uint32_t u = (uint32_t)w.block;
+            w.block = u / a.slices;
+            w.k0 = (u % a.slices) * unit_chunks;
+        }
+        return w;
+    };
+    auto block_of = [&](const Walk &w) -> uint64_t { return w.block; };
+    auto kc_of = [&](const Walk &w) -> uint32_t { return w.k0 + wave + NW * w.i; };
     auto valid = [&](const Walk &w) { return my_chunks != 0 && w.b < my_blocks; };
-    auto next_of = [&](Walk w) { if (++w.i == my_chunks) { w.i = 0; w.b++; } return w; };
+    auto next_of = [&](Walk w) { if (++w.i == my_chunks) w = at_unit(w.b + 1); return w; };
     auto load_w = [&](const Walk &w, u32x4 (&v)[GPIECES]) {
         const uint64_t e0 = block_of(w) * BLOCK_ROWS * a.K + kc_of(w) * (uint64_t)BLOCK_COLS + lane_elem;
 #pragma unroll
         for (int q = 0; q < GPIECES; q++) v[q] = __builtin_nontemporal_load((const GLOBAL u32x4 *)(W + e0 + 64 * q));
     };
-    Walk cur{0, 0};
+    Walk cur = at_unit(0);
     u32x4 w_cur[GPIECES], w_next[GPIECES];
     XPieces<MT, N> x_cur;
     if (valid(cur)) {
@@ -636,7 +712,10 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_raw_anyk_kernel(GArgs a)
             for (int q = 0; q < GPIECES; q++) w_cur[q] = w_next[q];
             cur = nxt;
         }
-        reduce_block<MT, NW, SCALED>((f32x4 *)(smem + parity * C::RED_BYTES), a, blockIdx.x + b * (uint64_t)gridDim.x, tid, acc);
+        f32x4 *red = (f32x4 *)(smem + parity * C::RED_BYTES);
+        const Walk unit = at_unit(b);
+        if constexpr (SPLIT) reduce_split<MT, NW, SCALED>(red, &s_flag, a, (uint32_t)unit.block, unit.k0 / unit_chunks, tid, acc);
+        else reduce_block<MT, NW, SCALED>(red, a, unit.block, tid, acc);
         parity ^= 1;
     }
 }
@@ -761,6 +840,89 @@ int launch_raw(const GArgs &a, void *stream)
     return hipGetLastError() == hipSuccess ? ECF8_OK : ECF8_E_HIP;
 }
 
+// The counters (one per block of rows; a split matrix has at most compute units / 2 blocks) take a fixed
+// area at the start of the workspace whatever the shape, so that the partial sums of one call never
+// land where another shape's call keeps its counters.
+constexpr uint64_t CTR_BYTES = 4096;
+
+// Split K.  Workgroups that share a block of rows: the largest divisor of the K / 256 chunks that
+// still gives every workgroup a compute unit of its own (1 = the matrix has blocks enough).
+uint32_t pick_slices(uint64_t rows, uint64_t cols, int cus)
+{
+    const uint64_t n_blocks = rows / BLOCK_ROWS, kchunks = cols / 256;
+    uint32_t best = 1;
+    if (n_blocks * 4 > CTR_BYTES) return 1;
+    for (uint64_t sl = 2; sl <= kchunks && n_blocks * sl <= (uint64_t)cus; sl++)
+        if (kchunks % sl == 0) best = (uint32_t)sl;
+    return best;
+}
+
+int tiles_of(uint32_t M) { return M <= 16 ? 1 : M <= 32 ? 2 : 4; }
+uint64_t workspace_bytes(uint64_t rows, uint32_t M, uint32_t slices)
+{
+    return slices <= 1 ? 0 : CTR_BYTES + rows / BLOCK_ROWS * slices * tiles_of(M) * 256 * 4;
+}
+
+int split_args(GArgs *a, void *d_workspace, uint64_t bytes, uint32_t *slices)
+{
+    const int cus = device_cus();
+    if (cus <= 0) return ECF8_E_HIP;
+    *slices = pick_slices(a->rows, a->K, cus);
+    if (*slices <= 1) return ECF8_OK;
+    if (!d_workspace) return ECF8_E_ARG;
+    if ((uintptr_t)d_workspace & 15) return ECF8_E_ALIGN;
+    if (bytes < workspace_bytes(a->rows, a->M, *slices)) return ECF8_E_CAPACITY;
+    a->slices = *slices;
+    a->d_ctr = (uint64_t)(uintptr_t)d_workspace;
+    a->d_part = a->d_ctr + CTR_BYTES;
+    return ECF8_OK;
+}
+
+template <int SCALED, bool RAW>
+int launch_split(const GArgs &a, void *stream)
+{
+    const int grid = grid_for(a.rows / BLOCK_ROWS * a.slices);      // <= the compute units by the choice of slices
+    if (grid <= 0) return ECF8_E_HIP;
+    hipStream_t s = (hipStream_t)stream;
+    if constexpr (RAW) {
+        if (a.M <= 16) hipLaunchKernelGGL((ecf8_gemm_raw_anyk_kernel<1, 16, 64, SCALED, true>), dim3(grid), dim3(16 * 64), 0, s, a);
+        else if (a.M <= 32) hipLaunchKernelGGL((ecf8_gemm_raw_anyk_kernel<2, 8, 64, SCALED, true>), dim3(grid), dim3(8 * 64), 0, s, a);
+        else hipLaunchKernelGGL((ecf8_gemm_raw_anyk_kernel<4, 8, 64, SCALED, true>), dim3(grid), dim3(8 * 64), 0, s, a);
+    } else {
+        if (a.M <= 16) hipLaunchKernelGGL((ecf8_gemm_anyk_kernel<1, 16, 64, SCALED, true>), dim3(grid), dim3(16 * 64), 0, s, a);
+        else if (a.M <= 32) hipLaunchKernelGGL((ecf8_gemm_anyk_kernel<2, 8, 64, SCALED, true>), dim3(grid), dim3(8 * 64), 0, s, a);
+        else hipLaunchKernelGGL((ecf8_gemm_anyk_kernel<4, 8, 64, SCALED, true>), dim3(grid), dim3(8 * 64), 0, s, a);
+    }
+    return hipGetLastError() == hipSuccess ? ECF8_OK : ECF8_E_HIP;
+}
+
+// the common tail of the two split-K calls: scales (or none), workspace, route
+template <bool RAW>
+int run_split(GArgs &a, const float *d_w_scale, const float *d_x_scale, uint32_t x_scale_cols, void *d_workspace,
+              uint64_t bytes, void *stream)
+{
+    int sc = 0;
+    if (d_w_scale || d_x_scale || x_scale_cols) {
+        const int rc = scale_args(d_w_scale, d_x_scale, x_scale_cols, &a);
+        if (rc) return rc;
+        sc = a.xs_cols > 1 ? 2 : 1;
+    }
+    uint32_t slices;
+    const int rc = split_args(&a, d_workspace, bytes, &slices);
+    if (rc) return rc;
+    if (slices <= 1) {      // blocks enough: the plain kernels
+        if constexpr (RAW) return sc == 0 ? launch_raw<0>(a, stream) : sc == 1 ? launch_raw<1>(a, stream) : launch_raw<2>(a, stream);
+        else return sc == 0 ? launch_fused<0>(a, stream) : sc == 1 ? launch_fused<1>(a, stream) : launch_fused<2>(a, stream);
+    }
+    return sc == 0 ? launch_split<0, RAW>(a, stream) : sc == 1 ? launch_split<1, RAW>(a, stream) : launch_split<2, RAW>(a, stream);
+}
+
+__global__ void gemm_fill_zero_kernel(uint64_t p, uint64_t n_dwords)
+{
+    const uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
+    if (i < n_dwords) ((GLOBAL uint32_t *)p)[i] = 0u;
+}
+
 } // namespace
 
 extern "C" {
@@ -798,6 +960,49 @@ int ecf8_gemm_fp8_raw_scaled(const void *d_w, uint64_t rows, uint64_t cols, cons
     if (!rc) rc = scale_args(d_w_scale, d_x_scale, x_scale_cols, &a);
     if (rc) return rc;
     return a.xs_cols > 1 ? launch_raw<2>(a, stream) : launch_raw<1>(a, stream);
+}
+
+uint32_t ecf8_gemm_splitk_slices(uint64_t rows, uint64_t cols)
+{
+    if (cols == 0 || cols % 256 || rows == 0 || rows % BLOCK_ROWS) return 0;
+    const int cus = device_cus();
+    return cus <= 0 ? 0 : pick_slices(rows, cols, cus);
+}
+
+uint64_t ecf8_gemm_splitk_workspace_bytes(uint64_t rows, uint64_t cols, uint32_t M)
+{
+    const uint32_t slices = ecf8_gemm_splitk_slices(rows, cols);
+    return slices == 0 || M == 0 || M > 64 ? 0 : workspace_bytes(rows, M, slices);
+}
+
+int ecf8_gemm_splitk_workspace_init(void *d_workspace, uint64_t bytes, void *stream)
+{
+    if (bytes == 0) return ECF8_OK;
+    if (!d_workspace) return ECF8_E_ARG;
+    if (((uintptr_t)d_workspace & 15) || (bytes & 3)) return ECF8_E_ALIGN;
+    const uint64_t n = bytes / 4;
+    if ((n + 255) / 256 > 0x7fffffffull) return ECF8_E_ARG;
+    hipLaunchKernelGGL(gemm_fill_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                       (uint64_t)(uintptr_t)d_workspace, n);
+    return hipGetLastError() == hipSuccess ? ECF8_OK : ECF8_E_HIP;
+}
+
+int ecf8_gemm_fp8_splitk(const ecf8_header *h, const void *d_blob, const void *d_x, uint32_t M, const float *d_w_scale,
+                         const float *d_x_scale, uint32_t x_scale_cols, float *d_y, void *d_workspace,
+                         uint64_t workspace_bytes_, void *stream)
+{
+    GArgs a;
+    const int rc = fused_args(h, d_blob, d_x, M, d_y, &a);
+    return rc ? rc : run_split<false>(a, d_w_scale, d_x_scale, x_scale_cols, d_workspace, workspace_bytes_, stream);
+}
+
+int ecf8_gemm_fp8_raw_splitk(const void *d_w, uint64_t rows, uint64_t cols, const void *d_x, uint32_t M,
+                             const float *d_w_scale, const float *d_x_scale, uint32_t x_scale_cols, float *d_y,
+                             void *d_workspace, uint64_t workspace_bytes_, void *stream)
+{
+    GArgs a;
+    const int rc = raw_args(d_w, rows, cols, d_x, M, d_y, &a);
+    return rc ? rc : run_split<true>(a, d_w_scale, d_x_scale, x_scale_cols, d_workspace, workspace_bytes_, stream);
 }
 
 } // extern "C"

@@ -89,6 +89,13 @@ _lib.ecf8_gemm_fp8.argtypes = [ctypes.POINTER(Header), _vp, _vp, _u32, _vp, _vp]
 _lib.ecf8_gemm_fp8_raw.argtypes = [_vp, _u64, _u64, _vp, _u32, _vp, _vp]
 _lib.ecf8_gemm_fp8_scaled.argtypes = [ctypes.POINTER(Header), _vp, _vp, _u32, _vp, _vp, _u32, _vp, _vp]
 _lib.ecf8_gemm_fp8_raw_scaled.argtypes = [_vp, _u64, _u64, _vp, _u32, _vp, _vp, _u32, _vp, _vp]
+_lib.ecf8_gemm_splitk_slices.argtypes = [_u64, _u64]
+_lib.ecf8_gemm_splitk_slices.restype = _u32
+_lib.ecf8_gemm_splitk_workspace_bytes.argtypes = [_u64, _u64, _u32]
+_lib.ecf8_gemm_splitk_workspace_bytes.restype = _u64
+_lib.ecf8_gemm_splitk_workspace_init.argtypes = [_vp, _u64, _vp]
+_lib.ecf8_gemm_fp8_splitk.argtypes = [ctypes.POINTER(Header), _vp, _vp, _u32, _vp, _vp, _u32, _vp, _vp, _u64, _vp]
+_lib.ecf8_gemm_fp8_raw_splitk.argtypes = [_vp, _u64, _u64, _vp, _u32, _vp, _vp, _u32, _vp, _vp, _u64, _vp]
 _lib.ecf8_jit_create.argtypes = [_u32, _u32, ctypes.POINTER(_vp), _u64, ctypes.POINTER(_vp)]
 _lib.ecf8_jit_destroy.argtypes = [_vp]
 _lib.ecf8_jit_destroy.restype = None
@@ -399,6 +406,52 @@ def ecf8_gemm_fp8_raw_scaled(d_w, d_x, w_scale, x_scale=None, d_y=None, stream=N
         d_y = torch.empty((M, rows), dtype=torch.float32, device=d_x.device)
     _check("ecf8_gemm_fp8_raw_scaled", _lib.ecf8_gemm_fp8_raw_scaled(d_w.data_ptr(), rows, cols, d_x.data_ptr(), M,
                                                                      ws, xs, xc, d_y.data_ptr(), _stream_ptr(stream)))
+    return d_y
+
+
+def gemm_splitk_slices(rows, cols):
+    """Workgroups per block of 16 rows the split-K calls use for this shape on the current device (1 = no split)."""
+    return int(_lib.ecf8_gemm_splitk_slices(rows, cols))
+
+
+def gemm_splitk_workspace(rows, cols, M, device, stream=None):
+    """A zeroed workspace for the split-K calls on a rows x cols matrix with up to M rows of X (uint8 tensor; it may
+    be reused for any later call it is large enough for, one call at a time)."""
+    n = int(_lib.ecf8_gemm_splitk_workspace_bytes(rows, cols, M))
+    ws = torch.empty((max(n, 16),), dtype=torch.uint8, device=device)
+    _check("ecf8_gemm_splitk_workspace_init", _lib.ecf8_gemm_splitk_workspace_init(ws.data_ptr(), ws.numel(), _stream_ptr(stream)))
+    return ws
+
+
+def _opt_scale_ptrs(fn, rows, cols, M, w_scale, x_scale):
+    if w_scale is None and x_scale is None:
+        return None, None, 0
+    if w_scale is None:
+        raise Ecf8Error(fn, E_ARG)
+    return _scale_ptrs(fn, rows, cols, M, w_scale, x_scale)
+
+
+def ecf8_gemm_fp8_splitk(hdr, d_blob, d_x, workspace, w_scale=None, x_scale=None, d_y=None, stream=None):
+    """ecf8_gemm_fp8 / ecf8_gemm_fp8_scaled with K split among workgroups (matrices of few rows)."""
+    M = d_x.shape[0]
+    ws, xs, xc = _opt_scale_ptrs("ecf8_gemm_fp8_splitk", hdr.rows, hdr.cols, M, w_scale, x_scale)
+    if d_y is None:
+        d_y = torch.empty((M, hdr.rows), dtype=torch.float32, device=d_x.device)
+    _check("ecf8_gemm_fp8_splitk", _lib.ecf8_gemm_fp8_splitk(ctypes.byref(hdr), d_blob.data_ptr(), d_x.data_ptr(), M, ws, xs, xc,
+                                                             d_y.data_ptr(), workspace.data_ptr(), workspace.numel(),
+                                                             _stream_ptr(stream)))
+    return d_y
+
+
+def ecf8_gemm_fp8_raw_splitk(d_w, d_x, workspace, w_scale=None, x_scale=None, d_y=None, stream=None):
+    M = d_x.shape[0]
+    rows, cols = d_w.shape
+    ws, xs, xc = _opt_scale_ptrs("ecf8_gemm_fp8_raw_splitk", rows, cols, M, w_scale, x_scale)
+    if d_y is None:
+        d_y = torch.empty((M, rows), dtype=torch.float32, device=d_x.device)
+    _check("ecf8_gemm_fp8_raw_splitk", _lib.ecf8_gemm_fp8_raw_splitk(d_w.data_ptr(), rows, cols, d_x.data_ptr(), M, ws, xs, xc,
+                                                                     d_y.data_ptr(), workspace.data_ptr(), workspace.numel(),
+                                                                     _stream_ptr(stream)))
     return d_y
 
 

@@ -276,3 +276,120 @@ def test_any_k_block_scaled_and_full_size(orc, M):
         yj, aj = orc.gemm_ref_scaled(xh, wh[n:n + 1], ws[n // 128:n // 128 + 1], xs)
         yref[:, j], mag[:, j] = yj[:, 0], aj[:, 0]
     _check(fused.cpu().numpy()[:, cols], yref, mag, "down projection, block scales")
+
+
+# ---- split K ----
+
+SPLIT_SHAPES = [(256, 14336), (576, 7168), (1024, 4096), (1536, 7168), (32, 512), (48, 5120), (16, 256)]
+
+
+def _split_workspace():
+    """One workspace for every split-K test, sized for the largest shape: the calls leave its counters at zero."""
+    global _WS
+    try:
+        return _WS
+    except NameError:
+        n = max(ecf8._lib.ecf8_gemm_splitk_workspace_bytes(r, k, 64) for r, k in SPLIT_SHAPES)
+        _WS = ecf8.gemm_splitk_workspace(1, 1, 1, DEV)          # the minimum, then one of the full size
+        assert _WS.numel() == 16
+        _WS = torch.full((n,), 0xA5, dtype=torch.uint8, device=DEV)
+        ecf8._check("init", ecf8._lib.ecf8_gemm_splitk_workspace_init(_WS.data_ptr(), _WS.numel(), None))
+        torch.cuda.synchronize()
+        assert int(_WS.count_nonzero()) == 0
+        return _WS
+
+
+@pytest.mark.parametrize("M", [1, 16, 17, 64])
+@pytest.mark.parametrize("rows,K", SPLIT_SHAPES)
+def test_split_k_against_oracle(orc, rows, K, M):
+    """Matrices of few rows: `slices` workgroups share a block of 16 rows.  Against the oracle, against the twin
+    on uncompressed weights (bit for bit), call after call on one workspace (bit for bit: the slices are
+    added in slice order whoever arrives last), with and without scales; (16, 256) and, on a chip of 256
+    compute units, nothing else here falls through to the plain kernels."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    slices = ecf8.gemm_splitk_slices(rows, K)
+    assert slices >= 1 and (K // 256) % slices == 0 and (slices == 1 or rows // 16 * slices <= cus)
+    assert all((K // 256) % s or rows // 16 * s > cus for s in range(slices + 1, K // 256 + 1))     # the largest such
+    need = ecf8._lib.ecf8_gemm_splitk_workspace_bytes(rows, K, M)
+    tiles = 1 if M <= 16 else 2 if M <= 32 else 4
+    assert need == (0 if slices == 1 else 4096 + rows // 16 * slices * tiles * 1024)
+    wsp = _split_workspace()
+    print("split K: rows", rows, "K", K, "M", M, "slices", slices, flush=True)
+    w = synth.make_weight(rows, K, 1.7, 0.02, 9).numpy()
+    x = synth.activations(M, K, seed=400 + M).numpy()
+    blob = ecf8.ecf8_encode(w, rows, K, lane_syms=64, tile_rows=16)
+    d_blob, d_x, d_w = blob.to(DEV), torch.from_numpy(x).to(DEV), torch.from_numpy(w).to(DEV)
+    rel = TOL if K >= 4096 else 7 * 2.0 ** -13
+    yref, mag = orc.gemm_ref(x, w)
+    guard = torch.full((M + 2, rows), float("nan"), dtype=torch.float32, device=DEV)
+    y = ecf8.ecf8_gemm_fp8_splitk(blob.header, d_blob, d_x, wsp, d_y=guard[1:M + 1])
+    raw = ecf8.ecf8_gemm_fp8_raw_splitk(d_w, d_x, wsp)
+    again = [ecf8.ecf8_gemm_fp8_splitk(blob.header, d_blob, d_x, wsp) for _ in range(5)]
+    torch.cuda.synchronize()
+    assert torch.isnan(guard[0]).all() and torch.isnan(guard[M + 1]).all()
+    _check(y.cpu().numpy(), yref, mag, "split-K fused %dx%d M=%d" % (rows, K, M), rel=rel)
+    assert torch.equal(raw, y) and all(torch.equal(a, y) for a in again)
+    # against the plain call: the same chunk sums added in another order, a few fp32 roundings apart
+    plain = ecf8.ecf8_gemm_fp8(blob.header, d_blob, d_x)
+    torch.cuda.synchronize()
+    _check(y.cpu().numpy(), plain.cpu().numpy().astype(np.float64), mag, "split-K against the plain call", rel=2e-6)
+    n_ctr = 4096
+    assert int(wsp[:n_ctr].count_nonzero()) == 0                  # counters back at zero
+    # scales of W alone, with one per row of X, with one per row and 128 columns of X
+    rng = np.random.default_rng(rows + M)
+    ws = np.exp(rng.normal(0.0, 0.7, size=((rows + 127) // 128, K // 128))).astype(np.float32)
+    xr = np.exp(rng.normal(0.0, 0.5, size=M)).astype(np.float32)
+    xg = np.exp(rng.normal(0.0, 0.5, size=(M, K // 128))).astype(np.float32)
+    d_ws = torch.from_numpy(ws).to(DEV)
+    for xs in (None, xr, xg):
+        d_xs = None if xs is None else torch.from_numpy(xs).to(DEV)
+        yref, mag = orc.gemm_ref_scaled(x, w, ws, xs)
+        y = ecf8.ecf8_gemm_fp8_splitk(blob.header, d_blob, d_x, wsp, d_ws, d_xs)
+        raw = ecf8.ecf8_gemm_fp8_raw_splitk(d_w, d_x, wsp, d_ws, d_xs)
+        torch.cuda.synchronize()
+        # the scaled sums are 128 products long each: the matrix cores' truncation averages out less, and
+        # over these many outputs its tail passes the 5e-5 of the unscaled tests (seen: 5.2e-5)
+        _check(y.cpu().numpy(), yref, mag, "split-K scaled %dx%d M=%d" % (rows, K, M), rel=max(rel, 1e-4))
+        assert torch.equal(raw, y)
+        plain = ecf8.ecf8_gemm_fp8_scaled(blob.header, d_blob, d_x, d_ws, d_xs)
+        torch.cuda.synchronize()
+        _check(y.cpu().numpy(), plain.cpu().numpy().astype(np.float64), mag, "split-K scaled against the plain call", rel=2e-6)
+    # operands whose products and sums are exact in fp32 in any order: equal to the reference, and to the plain call
+    vals = np.array([0x00, 0x30, 0xB0, 0x38, 0xB8, 0x40, 0xC0], dtype=np.uint8)
+    w2 = vals[rng.integers(0, len(vals), size=(rows, K))]
+    x2 = vals[rng.integers(0, len(vals), size=(M, K))]
+    yref2, _ = orc.gemm_ref(x2, w2)
+    blob2 = ecf8.ecf8_encode(w2, rows, K, lane_syms=64, tile_rows=16)
+    d_x2 = torch.from_numpy(x2).to(DEV)
+    y2 = ecf8.ecf8_gemm_fp8_splitk(blob2.header, blob2.to(DEV), d_x2, wsp)
+    plain = ecf8.ecf8_gemm_fp8(blob2.header, blob2.to(DEV), d_x2)
+    torch.cuda.synchronize()
+    assert np.array_equal(y2.cpu().numpy().astype(np.float64), yref2) and torch.equal(plain, y2)
+    assert int(wsp[:n_ctr].count_nonzero()) == 0
+
+
+def test_split_k_argument_errors():
+    rows, K, M = 256, 14336, 4
+    if ecf8.gemm_splitk_slices(rows, K) <= 1:
+        pytest.skip("this device has too few compute units to split this shape")
+    w = synth.make_weight(rows, K, 1.7, 0.02, 9).numpy()
+    blob = ecf8.ecf8_encode(w, rows, K, lane_syms=64, tile_rows=16)
+    d_blob, d_x = blob.to(DEV), synth.activations(M, K, seed=1).to(DEV)
+    need = ecf8._lib.ecf8_gemm_splitk_workspace_bytes(rows, K, M)
+    wsp = torch.zeros((need + 16,), dtype=torch.uint8, device=DEV)
+    y = torch.full((M, rows), 7.0, dtype=torch.float32, device=DEV)
+    for ws_arg, code in ((wsp[:need - 1], ecf8.E_CAPACITY), (wsp[1:], ecf8.E_ALIGN)):
+        with pytest.raises(ecf8.Ecf8Error) as e:
+            ecf8.ecf8_gemm_fp8_splitk(blob.header, d_blob, d_x, ws_arg, d_y=y)
+        assert e.value.code == code
+    rc = ecf8._lib.ecf8_gemm_fp8_splitk(blob.header, d_blob.data_ptr(), d_x.data_ptr(), M, None, None, 0, y.data_ptr(), None, 0, None)
+    assert rc == ecf8.E_ARG
+    xs = torch.ones((M,), dtype=torch.float32, device=DEV)
+    with pytest.raises(ecf8.Ecf8Error):                 # scales of X without scales of W
+        ecf8.ecf8_gemm_fp8_splitk(blob.header, d_blob, d_x, wsp, None, xs, d_y=y)
+    assert ecf8.gemm_splitk_slices(250, K) == 0 and ecf8.gemm_splitk_slices(rows, 1000) == 0
+    torch.cuda.synchronize()
+    assert bool((y == 7.0).all()) and int(wsp.count_nonzero()) == 0      # nothing ran
+    ecf8.ecf8_gemm_fp8_splitk(blob.header, d_blob, d_x, wsp[:need], d_y=y)   # exactly the size asked for
+    torch.cuda.synchronize()
+    assert bool((y != 7.0).any())
