@@ -273,6 +273,30 @@ def bench_config4(a):
         tf = timeit(lambda: ecf8.ecf8_gemm_fp8(hd, d_bd, x, y), a.steps, a.warmup)
         tr = timeit(lambda: ecf8.ecf8_gemm_fp8_raw(wd, x, y2), a.steps, a.warmup)
         res_down["M=%d" % M] = {"fused_us": round(tf * 1e6, 2), "raw_fp8_gemm_us": round(tr * 1e6, 2)}
+    # split K on matrices of few rows (low-rank projections of 576 and 1536 rows, a 256-row slice of a down projection,
+    # a grouped-query K/V projection): the plain calls against the split ones, fused and on uncompressed weights
+    res_split = {}
+    for rows, cols in ((256, 14336), (576, 7168), (1536, 7168), (1024, 4096)):
+        ww = synth.make_weight(rows, cols, 1.7, 0.02, a.seed, tensor_id=400002, device="cuda:0")
+        bb = ecf8.ecf8_encode(ww.cpu(), rows, cols, lane_syms=64, tile_rows=16, table_mode=1)
+        hh, d_bb = bb.header, bb.to("cuda:0")
+        entry = {"slices": ecf8.gemm_splitk_slices(rows, cols)}
+        for M in (1, 16, 64):
+            wsp = ecf8.gemm_splitk_workspace(rows, cols, M, "cuda:0")
+            x = synth.activations(M, cols, seed=a.seed, device="cuda:0")
+            y = torch.empty((M, rows), dtype=torch.float32, device="cuda:0")
+            y2 = torch.empty_like(y)
+            ecf8.ecf8_gemm_fp8_splitk(hh, d_bb, x, wsp, d_y=y)
+            ecf8.ecf8_gemm_fp8_raw_splitk(ww, x, wsp, d_y=y2)
+            torch.cuda.synchronize()
+            if not torch.equal(y, y2):
+                raise SystemExit("split-K fused GEMM differs from its twin on uncompressed weights at M=%d" % M)
+            entry["M=%d" % M] = {
+                "fused_us": round(timeit(lambda: ecf8.ecf8_gemm_fp8(hh, d_bb, x, y), a.steps, a.warmup) * 1e6, 2),
+                "fused_split_us": round(timeit(lambda: ecf8.ecf8_gemm_fp8_splitk(hh, d_bb, x, wsp, d_y=y), a.steps, a.warmup) * 1e6, 2),
+                "raw_us": round(timeit(lambda: ecf8.ecf8_gemm_fp8_raw(ww, x, y2), a.steps, a.warmup) * 1e6, 2),
+                "raw_split_us": round(timeit(lambda: ecf8.ecf8_gemm_fp8_raw_splitk(ww, x, wsp, d_y=y2), a.steps, a.warmup) * 1e6, 2)}
+        res_split["%dx%d" % (rows, cols)] = entry
     t16 = res["M=16"]["fused_us"] * 1e-6
     print(json.dumps({
         "metric": "decoded FP8 GB/s consumed by the fused decode+GEMM (M=16)", "value": round(w.numel() / t16 / 1e9, 2),
@@ -280,7 +304,7 @@ def bench_config4(a):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "fp8 x fp8 -> f32", "data": "synthetic",
         "config": {"workload": "config4: fused decode + FP8 MFMA GEMM, W 14336x4096, M in {1,16,64}", "seed": a.seed},
         "compression_ratio": round(h.total_size / w.numel(), 5), "bit_exact_vs_raw_weights_gemm": True,
-        "gemm": res, "beyond_M64": crossover, "gemm_down_4096x14336_any_k": res_down}))
+        "gemm": res, "beyond_M64": crossover, "gemm_down_4096x14336_any_k": res_down, "split_k": res_split}))
 
 def bench_jit(a):
     """Workload "jit" (paper Section 3.3): a forward pass over the config-1 stack with the weights

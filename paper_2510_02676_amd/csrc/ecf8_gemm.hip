@@ -208,8 +208,15 @@ __device__ __forceinline__ void reduce_block(f32x4 *red, const GArgs &a, uint64_
 // Split K: the partial sums of the unit (block of rows, slice of K) go to the workspace, and the
 // workgroup that brings a block's last slice adds the slices up -- in slice order, so the result
 // does not depend on which one that was -- and writes the outputs.  No workgroup waits for
-// another.  The partial sums travel through agent-coherent stores and loads, ordered against the
-// arrival counter by fences; the last workgroup leaves the counter at zero for the next call.
+// another; the last one leaves the counter at zero for the next call.
+// Memory order.  Partial sums and counter are only ever touched by agent-scope atomic stores, loads
+// and adds (sc1 accesses: performed at the level all compute units share, never served from or left
+// in a cache that is private to a part of the chip), so no cache write-back or invalidate is
+// needed -- a release / acquire pair at agent scope would add them (buffer_wbl2 / buffer_inv of the
+// whole L2, measured: 2 us per launch) for the sake of plain accesses, of which there are none.
+// What is left of release is that a workgroup's stores have completed before its add is issued:
+// every wave waits for its own (vmcnt), then the barrier, then thread 0 adds.  What is left of
+// acquire is that the loads are issued after the add has returned: they depend on its value.
 template <int MT, int NW, bool SCALED>
 __device__ __forceinline__ void reduce_split(f32x4 *red, uint32_t *s_flag, const GArgs &a, uint32_t block, uint32_t slice,
                                              int tid, const f32x4 (&acc)[MT])
@@ -227,12 +234,11 @@ __device__ __forceinline__ void reduce_split(f32x4 *red, uint32_t *s_flag, const
         for (int w = 0; w < NW; w++) sum += ((const float *)&red[(w * MT + mt) * 64 + l])[r];
         __hip_atomic_store(part + (uint64_t)slice * (MT * 256) + o, __float_as_uint(sum), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) *s_flag = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // this wave's stores have completed ...
+    __syncthreads();                                        // ... and so have every wave's
+    if (tid == 0) *s_flag = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (*s_flag != a.slices - 1) return;          // uniform: the same LDS word for every thread
-    __threadfence();
     GLOBAL float *Y = (GLOBAL float *)a.d_y;
     for (int o = tid; o < MT * 256; o += NW * 64) {
         const int mt = o >> 8, l = (o >> 2) & 63, r = o & 3;

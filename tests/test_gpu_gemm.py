@@ -393,3 +393,34 @@ def test_split_k_argument_errors():
     ecf8.ecf8_gemm_fp8_splitk(blob.header, d_blob, d_x, wsp[:need], d_y=y)   # exactly the size asked for
     torch.cuda.synchronize()
     assert bool((y != 7.0).any())
+
+
+def test_split_k_calls_with_changing_inputs_share_a_workspace():
+    """A long run of calls on one workspace whose inputs change from call to call (two activations, two weight
+    matrices, unscaled and scaled in turn): every result equals the one the same call gave on a fresh
+    workspace.  A partial sum read from an earlier call, or a counter left off zero, would show here."""
+    rows, K, M = 576, 7168, 16
+    if ecf8.gemm_splitk_slices(rows, K) <= 1:
+        pytest.skip("this device has too few compute units to split this shape")
+    ws_h = np.exp(np.random.default_rng(3).normal(0.0, 0.7, size=((rows + 127) // 128, K // 128))).astype(np.float32)
+    d_ws = torch.from_numpy(ws_h).to(DEV)
+    cases = []
+    for i in range(2):
+        w = synth.make_weight(rows, K, 1.7, 0.02, 20 + i).numpy()
+        blob = ecf8.ecf8_encode(w, rows, K, lane_syms=64, tile_rows=16)
+        for j in range(2):
+            d_x = synth.activations(M, K, seed=500 + j).to(DEV)
+            for scale in (None, d_ws):
+                fresh = ecf8.gemm_splitk_workspace(rows, K, M, DEV)
+                want = ecf8.ecf8_gemm_fp8_splitk(blob.header, blob.to(DEV), d_x, fresh, scale)
+                cases.append((blob.header, blob.to(DEV), d_x, scale, want))
+    torch.cuda.synchronize()
+    assert not torch.equal(cases[0][4], cases[2][4]) and not torch.equal(cases[0][4], cases[4][4])
+    wsp = ecf8.gemm_splitk_workspace(rows, K, M, DEV)
+    rng = np.random.default_rng(0)
+    order = rng.integers(0, len(cases), size=300)
+    got = [ecf8.ecf8_gemm_fp8_splitk(cases[c][0], cases[c][1], cases[c][2], wsp, cases[c][3]) for c in order]
+    torch.cuda.synchronize()
+    bad = [int(k) for k, c in enumerate(order) if not torch.equal(got[k], cases[c][4])]
+    assert not bad, "calls %s of 300 differ from the same call on a fresh workspace" % bad[:10]
+    assert int(wsp[:4096].count_nonzero()) == 0
