@@ -15,9 +15,10 @@
  * Boundary: plain pointers and sizes only.  "host" pointers are ordinary CPU
  * memory; "device" pointers are HIP device memory of the current device that
  * the CALLER owns (e.g. a PyTorch tensor's data_ptr()).  The library keeps no
- * device memory of its own, never allocates or frees device memory, never
- * synchronises the device, and uses no global atomics outside the workspace
- * the caller hands to the split-K calls.  `stream` arguments are
+ * device memory of its own and never allocates or frees device memory; the
+ * decode calls never synchronise the device and use no global atomics (the
+ * device encoder reads its histogram back once and uses atomics on its own
+ * output; the split-K GEMM calls use them on the counters in their workspace).  `stream` arguments are
  * a hipStream_t passed as void* (NULL = the default stream).
  *
  * All functions return ECF8_OK (0) or a negative ECF8_E_* code; nothing throws
