@@ -701,11 +701,16 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     e0.record(stream)
+    marks = []
     for _ in range(a.steps):
         step()
+        if len(side) == 1 or a.launch == "stack":       # one event per step: median and fastest step beside the mean
+            marks.append(torch.cuda.Event(enable_timing=True))
+            marks[-1].record(stream)
     e1.record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    per_step = sorted(p.elapsed_time(q) for p, q in zip([e0] + marks[:-1], marks))
     dev_s = e0.elapsed_time(e1) * 1e-3 if len(side) == 1 or a.launch == "stack" else wall
     sec_per_step = wall / a.steps
     n_launch = len(batches) * a.steps
@@ -721,6 +726,8 @@ def main():
         "ms_per_step": round(sec_per_step * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u8", "data": "synthetic",
+        "ms_per_step_median": round(per_step[len(per_step) // 2], 4) if per_step else None,
+        "ms_per_step_min": round(per_step[0], 4) if per_step else None,
         "config": {"workload": "%s: %s" % (a.workload, desc), "weights": n_total,
                    "launches_per_step": len(batches), "launch": a.launch, "lane_syms": hdrs[0].lane_syms,
                    "group_chunks": hdrs[0].group_chunks, "max_code_len": max(max(h.code_len) for h in hdrs),
