@@ -271,3 +271,43 @@ def test_error_paths():
     assert lib.ecf8_decode(ctypes.byref(h), ctypes.c_void_p(4096), ctypes.c_void_p(8192), ctypes.c_uint64(10), None) == ecf8.E_CAPACITY
     assert lib.ecf8_decode(ctypes.byref(h), ctypes.c_void_p(4097), ctypes.c_void_p(8192), ctypes.c_uint64(1000), None) == ecf8.E_ALIGN
     assert lib.ecf8_decode_batched(None, 1, 1, 64, None) == ecf8.E_ARG
+
+
+@pytest.mark.parametrize("wide", [False, True])
+def test_validate_survives_random_corruption(wide):
+    """Single-byte damage anywhere in a container: the validator returns (accepts or rejects, never crashes or
+    reads out of bounds), rejects every change to the metadata the kernels index with (chunk_bit, lane_bits)
+    and every truncation, and accepts changes to the payload, which it cannot and need not judge."""
+    rng = np.random.default_rng(11)
+    if wide:
+        from paper_2510_02676_amd import ecfw
+        x = synth.make_bf16(300, 700, 1.8, 0.02, 3).numpy()
+        good = ecfw.ecfw_encode(ecfw.FMT_BF16, x).numpy().copy()
+        validate, h = ecfw.blob_validate, ecfw.blob_describe(good)
+        Err = ecfw.EcfwError if hasattr(ecfw, "EcfwError") else ecf8.Ecf8Error
+    else:
+        x = synth.make_weight(300, 700, 1.8, 0.02, 3).numpy()
+        good = ecf8.ecf8_encode(x, table_mode=1).numpy().copy()
+        validate, h = ecf8.blob_validate, ecf8.blob_describe(good)
+        Err = ecf8.Ecf8Error
+    validate(good)
+    verdicts = {"accepted": 0, "rejected": 0}
+    for _ in range(1500):
+        bad = good.copy()
+        off = int(rng.integers(0, min(good.size, h.off_stream + 64)))        # header, tables, metadata, start of the stream
+        bad[off] ^= np.uint8(1 << int(rng.integers(0, 8)))
+        try:
+            validate(bad)
+            verdicts["accepted"] += 1
+            assert not (h.off_chunk_bit <= off < h.off_chunk_bit + 8 * (h.n_chunks + 1)), off
+            assert not (h.off_lane_bits <= off < h.off_lane_bits + 128 * h.n_chunks), off
+        except Err:
+            verdicts["rejected"] += 1
+    assert verdicts["rejected"] > 100
+    for cut in (1, 16, 255, 256, 4096, good.size // 2, good.size - 8):
+        with pytest.raises(Err):
+            validate(good[:good.size - cut].copy())
+    for off in rng.integers(h.off_stream + 64, good.size, size=50):          # payload
+        bad = good.copy()
+        bad[int(off)] ^= 0x10
+        validate(bad)

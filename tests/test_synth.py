@@ -79,7 +79,7 @@ def test_block_scaling_hits_448_in_every_block_and_is_seeded():
     e = ((w >> 3) & 15).flatten().numpy()
     f = np.bincount(e, minlength=16) / e.size
     h = -(f[f > 0] * np.log2(f[f > 0])).sum()
-    assert 2.0 < h < 3.5  # "around 2-3 bits" (Section 1 / Figure 1)
+    assert 2.0 < h < 3.5  # the exponent entropy of trained FP8 weights lies between two and three bits (Section 1, Figure 1)
 
 
 def test_config_shapes():
