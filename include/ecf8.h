@@ -345,6 +345,61 @@ int ecf8_gemm_fp8_raw_splitk(const void *d_w, uint64_t rows, uint64_t cols, cons
                              float *d_y, void *d_workspace, uint64_t workspace_bytes, void *stream);
 
 /*
+ * A group of small products in ONE launch, each with its own W, X, M and Y: the
+ * experts that a batch of tokens is routed to in a mixture-of-experts layer (the
+ * largest model of the paper's Table 1 is one).  A launch per matrix is bound by
+ * launches and leaves most of the chip idle (a 2048 x 7168 expert is 128 blocks
+ * of rows); here the blocks of all matrices form one sequence, weighted by their
+ * K / 256 chunks, which the workgroups share evenly.  Every product is computed
+ * as ecf8_gemm_fp8 / _scaled (or the raw twins) compute it, under the same limits
+ * on each matrix.  A group of compressed and the same group of uncompressed matrices
+ * agree bit for bit.  Against the single calls a member agrees bit for bit when that
+ * call runs workgroups of the group's shape (cols != 4096, and M on the same side of
+ * 16 as the group's largest M: the shape follows the largest M, and with it the order
+ * in which a block's chunk sums are added) and to a few fp32 roundings otherwise.
+ *   ecf8_gemm_group_prepare  HOST: checks the n descriptions and fills items_host[n]
+ *                            (copy them to DEVICE memory, 8-byte aligned, caller-
+ *                            owned) and *info (stays on the host).  All matrices of
+ *                            a group are compressed (hdr != NULL, d_w = the blob) or
+ *                            all uncompressed (hdr == NULL, d_w = rows x cols bytes),
+ *                            and carry the same kind of scales (none; d_w_scale with
+ *                            no or one x scale per row; d_w_scale with x scales per
+ *                            row and 128 columns), ECF8_E_ARG otherwise.  M may
+ *                            differ from matrix to matrix (1 <= M <= 64).
+ *   ecf8_gemm_fp8_grouped    DEVICE, asynchronous on `stream`; the items may be reused
+ *                            for any number of launches while the buffers they
+ *                            point to live.
+ */
+typedef struct ecf8_gemm_group_desc {
+    const ecf8_header *hdr;   /* HOST; NULL for an uncompressed matrix              */
+    const void *d_w;          /* DEVICE: the blob, or rows x cols FP8 bytes          */
+    uint64_t rows, cols;      /* uncompressed matrices only (else taken from hdr)    */
+    const void *d_x;          /* DEVICE: M x cols FP8 bytes                          */
+    float *d_y;               /* DEVICE: M x rows fp32                               */
+    const float *d_w_scale;   /* DEVICE or NULL, as for ecf8_gemm_fp8_scaled         */
+    const float *d_x_scale;
+    uint32_t x_scale_cols;
+    uint32_t M;
+} ecf8_gemm_group_desc;
+
+typedef struct ecf8_gemm_group_item {
+    uint64_t opaque[32];      /* the kernel's view of one matrix                     */
+} ecf8_gemm_group_item;
+
+typedef struct ecf8_gemm_group_info {
+    uint64_t total_work;      /* chunks of 16 x 256 weights over all matrices        */
+    uint32_t n_items;
+    uint32_t max_M;
+    uint32_t scale_mode;      /* 0 none, 1 W blocks (+ X rows), 2 W blocks + X groups */
+    uint32_t raw;             /* 1: uncompressed matrices                            */
+} ecf8_gemm_group_info;
+
+int ecf8_gemm_group_prepare(const ecf8_gemm_group_desc *descs, uint32_t n,
+                            ecf8_gemm_group_item *items_host, ecf8_gemm_group_info *info);
+int ecf8_gemm_fp8_grouped(const ecf8_gemm_group_item *d_items, const ecf8_gemm_group_info *info,
+                          void *stream);
+
+/*
  * Just-in-time layer decode (Section 3.3: compressed layers stay resident, a
  * layer is decoded into a pre-allocated buffer right before its forward pass
  * and the buffer is reused by later layers).  The manager is host-side

@@ -27,6 +27,8 @@
 // level and no fallback path.
 #include "ecf8_device.h"
 
+#include <cstring>
+
 namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -490,16 +492,17 @@ struct Walk {
     uint32_t k0;
 };
 
-template <int MT, int NW, int N, int SC, bool SPLIT = false>   // SC: 0 no scales, 1 scales of W (and one per row of X), 2 also one per row and 128 columns of X
-__global__ __launch_bounds__(NW * 64) void ecf8_gemm_anyk_kernel(GArgs a)
+// The work of one workgroup on one matrix: its units first_unit, first_unit + unit_stride, ... (my_units
+// of them), table set-up included.  `parity` says which of the two reduction buffers comes next and is
+// carried on to the caller's next matrix.
+template <int MT, int NW, int N, int SC, bool SPLIT>   // SC: 0 no scales, 1 scales of W (and one per row of X), 2 also one per row and 128 columns of X
+__device__ __forceinline__ void anyk_walk(const GArgs &a, uint8_t *smem, uint32_t *s_flag, uint64_t first_unit, uint64_t unit_stride,
+                                          uint64_t my_units, uint32_t &parity)
 {
-    __shared__ uint32_t s_flag;                   // split K: the arrival count this workgroup drew
-    (void)s_flag;
     constexpr bool SCALED = SC != 0;
     using C = GCfg<MT, NW, N>;
     constexpr int BLOCK_COLS = C::BLOCK_COLS, GPIECES = C::PIECES, GSTAGE = C::STAGE, GSEGS = C::SEGS;
     static_assert(!SCALED || 4 * N == 2 * SCALE_BLOCK, "a chunk spans two scale blocks of K");
-    __shared__ __attribute__((aligned(16))) uint8_t smem[C::TOTAL];
     uint16_t *tbl = (uint16_t *)(smem + C::OFF_TBL);
     uint32_t *s_len = (uint32_t *)(smem + C::OFF_SYM);
     uint32_t *s_code = s_len + 16;
@@ -515,13 +518,12 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_anyk_kernel(GArgs a)
     const uint32_t kchunks = (uint32_t)(a.K / BLOCK_COLS);
     const uint32_t unit_chunks = SPLIT ? kchunks / a.slices : kchunks;                                     // chunks of K per unit
     const uint32_t my_chunks = unit_chunks > (uint32_t)wave ? (unit_chunks - wave + NW - 1) / NW : 0;     // wave-uniform
-    const uint64_t n_units = a.rows / BLOCK_ROWS * (SPLIT ? a.slices : 1u);
-    const uint64_t my_blocks = blockIdx.x < n_units ? (n_units - blockIdx.x + gridDim.x - 1) / gridDim.x : 0;   // units of this workgroup
+    const uint64_t my_blocks = my_units;
 
     struct Meta { uint64_t b0, b1; uint32_t lb; };
     struct Payload { u32x4 seg[GSEGS]; u32x2 pl[GPIECES]; };
     auto at_unit = [&](uint64_t b) {
-        Walk w{b, 0, blockIdx.x + b * (uint64_t)gridDim.x, 0};
+        Walk w{b, 0, first_unit + b * unit_stride, 0};
         if constexpr (SPLIT) {
             const uint32_t u = (uint32_t)w.block;            // units < 2^31, checked on the host
             w.block = u / a.slices;
@@ -590,7 +592,6 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_anyk_kernel(GArgs a)
         build_tables(len_lo, len_hi, tbl, s_len, s_code, (uint16_t *)(smem + C::OFF_STAGE), tid, NW * 64);
     }
 
-    uint32_t parity = 0;
     for (uint64_t b = 0; b < my_blocks; b++) {            // uniform for the workgroup: one barrier per block
         f32x4 acc[MT];
 #pragma unroll
@@ -640,32 +641,45 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_anyk_kernel(GArgs a)
         }
         f32x4 *red = (f32x4 *)(smem + C::OFF_RED + parity * C::RED_BYTES);
         const Walk unit = at_unit(b);
-        if constexpr (SPLIT) reduce_split<MT, NW, SCALED>(red, &s_flag, a, (uint32_t)unit.block, unit.k0 / unit_chunks, tid, acc);
+        if constexpr (SPLIT) reduce_split<MT, NW, SCALED>(red, s_flag, a, (uint32_t)unit.block, unit.k0 / unit_chunks, tid, acc);
         else reduce_block<MT, NW, SCALED>(red, a, unit.block, tid, acc);
         parity ^= 1;
     }
 }
 
-// The any-K GEMM on uncompressed W: same deal of chunks, same order of accumulation.
-template <int MT, int NW, int N, int SC, bool SPLIT = false>   // SC: 0 no scales, 1 scales of W (and one per row of X), 2 also one per row and 128 columns of X
-__global__ __launch_bounds__(NW * 64) void ecf8_gemm_raw_anyk_kernel(GArgs a)
+// units of workgroup blockIdx.x when n_units are dealt round-robin to the grid
+__device__ __forceinline__ uint64_t units_of_workgroup(uint64_t n_units)
 {
+    return blockIdx.x < n_units ? (n_units - blockIdx.x + gridDim.x - 1) / gridDim.x : 0;
+}
+
+template <int MT, int NW, int N, int SC, bool SPLIT = false>
+__global__ __launch_bounds__(NW * 64) void ecf8_gemm_anyk_kernel(GArgs a)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t smem[GCfg<MT, NW, N>::TOTAL];
     __shared__ uint32_t s_flag;                   // split K: the arrival count this workgroup drew
-    (void)s_flag;
+    uint32_t parity = 0;
+    anyk_walk<MT, NW, N, SC, SPLIT>(a, smem, &s_flag, blockIdx.x, gridDim.x,
+                                    units_of_workgroup(a.rows / BLOCK_ROWS * (SPLIT ? a.slices : 1u)), parity);
+}
+
+// The any-K GEMM on uncompressed W: same deal of chunks, same order of accumulation.
+template <int MT, int NW, int N, int SC, bool SPLIT>
+__device__ __forceinline__ void raw_anyk_walk(const GArgs &a, uint8_t *smem, uint32_t *s_flag, uint64_t first_unit, uint64_t unit_stride,
+                                              uint64_t my_units, uint32_t &parity)
+{
     constexpr bool SCALED = SC != 0;
     using C = GCfg<MT, NW, N>;
     constexpr int BLOCK_COLS = C::BLOCK_COLS, GPIECES = C::PIECES;
-    __shared__ __attribute__((aligned(16))) uint8_t smem[2 * C::RED_BYTES];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const GLOBAL uint8_t *W = (const GLOBAL uint8_t *)a.d_w;
     const uint64_t lane_elem = (uint64_t)(lane & 15) * a.K + (uint64_t)(lane >> 4) * 16;
     const uint32_t kchunks = (uint32_t)(a.K / BLOCK_COLS);
     const uint32_t unit_chunks = SPLIT ? kchunks / a.slices : kchunks;
     const uint32_t my_chunks = unit_chunks > (uint32_t)wave ? (unit_chunks - wave + NW - 1) / NW : 0;
-    const uint64_t n_units = a.rows / BLOCK_ROWS * (SPLIT ? a.slices : 1u);
-    const uint64_t my_blocks = blockIdx.x < n_units ? (n_units - blockIdx.x + gridDim.x - 1) / gridDim.x : 0;
+    const uint64_t my_blocks = my_units;
     auto at_unit = [&](uint64_t b) {
-        Walk w{b, 0, blockIdx.x + b * (uint64_t)gridDim.x, 0};
+        Walk w{b, 0, first_unit + b * unit_stride, 0};
         if constexpr (SPLIT) {
             const uint32_t u = (uint32_t)w.block;
             w.block = u / a.slices;
@@ -689,7 +703,6 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_raw_anyk_kernel(GArgs a)
         load_w(cur, w_cur);
         load_x_chunk<MT, N>(a, lane, kc_of(cur), x_cur);
     }
-    uint32_t parity = 0;
     for (uint64_t b = 0; b < my_blocks; b++) {
         f32x4 acc[MT];
 #pragma unroll
@@ -720,9 +733,76 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_raw_anyk_kernel(GArgs a)
         }
         f32x4 *red = (f32x4 *)(smem + parity * C::RED_BYTES);
         const Walk unit = at_unit(b);
-        if constexpr (SPLIT) reduce_split<MT, NW, SCALED>(red, &s_flag, a, (uint32_t)unit.block, unit.k0 / unit_chunks, tid, acc);
+        if constexpr (SPLIT) reduce_split<MT, NW, SCALED>(red, s_flag, a, (uint32_t)unit.block, unit.k0 / unit_chunks, tid, acc);
         else reduce_block<MT, NW, SCALED>(red, a, unit.block, tid, acc);
         parity ^= 1;
+    }
+}
+
+template <int MT, int NW, int N, int SC, bool SPLIT = false>
+__global__ __launch_bounds__(NW * 64) void ecf8_gemm_raw_anyk_kernel(GArgs a)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t smem[2 * GCfg<MT, NW, N>::RED_BYTES];
+    __shared__ uint32_t s_flag;
+    uint32_t parity = 0;
+    raw_anyk_walk<MT, NW, N, SC, SPLIT>(a, smem, &s_flag, blockIdx.x, gridDim.x,
+                                        units_of_workgroup(a.rows / BLOCK_ROWS * (SPLIT ? a.slices : 1u)), parity);
+}
+
+// ---- a group of matrices in one launch ----
+// Many small products at once, each with its own W, X, M and Y (the experts a batch of tokens is
+// routed to): a launch per matrix would be bound by launches and would leave the chip half empty
+// (a 2048 x 7168 expert has 128 blocks of rows).  The blocks of all matrices form one sequence,
+// weighted by their K / 256 chunks; every workgroup takes an equal share of it, a contiguous run
+// of blocks that may cross from one matrix into the next, and works through it with the any-K loop,
+// setting up the code again where the matrix changes.  Inside a block nothing differs from the
+// single call with the same number of waves, so the results are the same bit for bit.
+struct GItem {
+    uint64_t first_work;        // chunks of the matrices before this one
+    GArgs a;
+};
+static_assert(sizeof(GItem) % 8 == 0 && sizeof(GItem) <= sizeof(ecf8_gemm_group_item), "item fits its public slot");
+
+struct GGArgs {
+    uint64_t d_items;           // device array of ecf8_gemm_group_item
+    uint32_t n_items;
+    uint64_t total_work;
+};
+
+template <int MT, int NW, int N, int SC, bool RAW>
+__global__ __launch_bounds__(NW * 64) void ecf8_gemm_grouped_kernel(GGArgs g)
+{
+    using C = GCfg<MT, NW, N>;
+    __shared__ __attribute__((aligned(16))) uint8_t smem[RAW ? 2 * C::RED_BYTES : C::TOTAL];
+    __shared__ uint32_t s_flag;
+    constexpr uint32_t WORDS = sizeof(ecf8_gemm_group_item) / 8;
+    const GLOBAL uint64_t *items = (const GLOBAL uint64_t *)g.d_items;
+    // this workgroup takes the blocks whose first chunk lies in [pos, end) of the sequence
+    uint64_t pos = g.total_work * blockIdx.x / gridDim.x;
+    const uint64_t end = g.total_work * (blockIdx.x + 1) / gridDim.x;
+    uint32_t parity = 0;
+    while (pos < end) {                                 // one round per matrix the share touches (uniform)
+        uint32_t lo = 0, hi = g.n_items - 1;
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi + 1) >> 1;
+            if (uniform64(items[(uint64_t)mid * WORDS]) <= pos) lo = mid; else hi = mid - 1;
+        }
+        GItem it;
+        {
+            uint64_t *dst = (uint64_t *)&it;
+#pragma unroll
+            for (int i = 0; i < (int)(sizeof(GItem) / 8); i++) dst[i] = uniform64(items[(uint64_t)lo * WORDS + i]);
+        }
+        const uint64_t kchunks = it.a.K / C::BLOCK_COLS, n_blocks = it.a.rows / BLOCK_ROWS;
+        const uint64_t b0 = (pos - it.first_work + kchunks - 1) / kchunks;
+        uint64_t b1 = (end - it.first_work + kchunks - 1) / kchunks;
+        if (b1 > n_blocks) b1 = n_blocks;
+        __syncthreads();                                // the last matrix's table and reduction buffers are out of use
+        if (b0 < b1) {
+            if constexpr (RAW) raw_anyk_walk<MT, NW, N, SC, false>(it.a, smem, &s_flag, b0, 1, b1 - b0, parity);
+            else anyk_walk<MT, NW, N, SC, false>(it.a, smem, &s_flag, b0, 1, b1 - b0, parity);
+        }
+        pos = it.first_work + n_blocks * kchunks;       // on to the next matrix (or past `end`)
     }
 }
 
@@ -923,6 +1003,22 @@ int run_split(GArgs &a, const float *d_w_scale, const float *d_x_scale, uint32_t
     return sc == 0 ? launch_split<0, RAW>(a, stream) : sc == 1 ? launch_split<1, RAW>(a, stream) : launch_split<2, RAW>(a, stream);
 }
 
+template <int SCALED, bool RAW>
+int launch_grouped(const GGArgs &g, uint32_t max_M, void *stream)
+{
+    const int cus = device_cus();
+    if (cus <= 0) return ECF8_E_HIP;
+    // no more workgroups than blocks of 16 chunks: below that a share is less than a block's worth of the waves' work
+    uint64_t grid = (g.total_work + 15) / 16;
+    if (grid > (uint64_t)cus) grid = (uint64_t)cus;
+    if (grid == 0) grid = 1;
+    hipStream_t s = (hipStream_t)stream;
+    if (max_M <= 16) hipLaunchKernelGGL((ecf8_gemm_grouped_kernel<1, 16, 64, SCALED, RAW>), dim3((unsigned)grid), dim3(16 * 64), 0, s, g);
+    else if (max_M <= 32) hipLaunchKernelGGL((ecf8_gemm_grouped_kernel<2, 8, 64, SCALED, RAW>), dim3((unsigned)grid), dim3(8 * 64), 0, s, g);
+    else hipLaunchKernelGGL((ecf8_gemm_grouped_kernel<4, 8, 64, SCALED, RAW>), dim3((unsigned)grid), dim3(8 * 64), 0, s, g);
+    return hipGetLastError() == hipSuccess ? ECF8_OK : ECF8_E_HIP;
+}
+
 __global__ void gemm_fill_zero_kernel(uint64_t p, uint64_t n_dwords)
 {
     const uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
@@ -1009,6 +1105,57 @@ int ecf8_gemm_fp8_raw_splitk(const void *d_w, uint64_t rows, uint64_t cols, cons
     GArgs a;
     const int rc = raw_args(d_w, rows, cols, d_x, M, d_y, &a);
     return rc ? rc : run_split<true>(a, d_w_scale, d_x_scale, x_scale_cols, d_workspace, workspace_bytes_, stream);
+}
+
+int ecf8_gemm_group_prepare(const ecf8_gemm_group_desc *descs, uint32_t n, ecf8_gemm_group_item *items_host,
+                            ecf8_gemm_group_info *info)
+{
+    if (!descs || !items_host || !info || n == 0) return ECF8_E_ARG;
+    std::memset(info, 0, sizeof(*info));
+    std::memset(items_host, 0, sizeof(*items_host) * n);
+    const bool raw = descs[0].hdr == nullptr;
+    uint32_t mode = 0, max_M = 0;
+    uint64_t work = 0;
+    for (uint32_t i = 0; i < n; i++) {
+        const ecf8_gemm_group_desc &d = descs[i];
+        if ((d.hdr == nullptr) != raw) return ECF8_E_ARG;           // all compressed, or all uncompressed
+        GItem it{};
+        int rc = raw ? raw_args(d.d_w, d.rows, d.cols, d.d_x, d.M, d.d_y, &it.a) : fused_args(d.hdr, d.d_w, d.d_x, d.M, d.d_y, &it.a);
+        if (rc) return rc;
+        uint32_t m = 0;
+        if (d.d_w_scale || d.d_x_scale || d.x_scale_cols) {
+            rc = scale_args(d.d_w_scale, d.d_x_scale, d.x_scale_cols, &it.a);
+            if (rc) return rc;
+            m = it.a.xs_cols > 1 ? 2 : 1;
+        }
+        if (i == 0) mode = m;
+        else if (m != mode) return ECF8_E_ARG;                      // one kind of scales per group
+        it.first_work = work;
+        work += it.a.rows / BLOCK_ROWS * (it.a.K / 256);
+        if (d.M > max_M) max_M = d.M;
+        std::memcpy(&items_host[i], &it, sizeof(it));
+    }
+    info->total_work = work;
+    info->n_items = n;
+    info->max_M = max_M;
+    info->scale_mode = mode;
+    info->raw = raw ? 1u : 0u;
+    return ECF8_OK;
+}
+
+int ecf8_gemm_fp8_grouped(const ecf8_gemm_group_item *d_items, const ecf8_gemm_group_info *info, void *stream)
+{
+    if (!d_items || !info || info->n_items == 0 || info->total_work == 0 || info->max_M == 0 || info->max_M > 64 ||
+        info->scale_mode > 2 || info->raw > 1)
+        return ECF8_E_ARG;
+    if ((uintptr_t)d_items & 7) return ECF8_E_ALIGN;
+    GGArgs g{(uint64_t)(uintptr_t)d_items, info->n_items, info->total_work};
+    const uint32_t M = info->max_M;
+    if (info->raw)
+        return info->scale_mode == 0 ? launch_grouped<0, true>(g, M, stream)
+             : info->scale_mode == 1 ? launch_grouped<1, true>(g, M, stream) : launch_grouped<2, true>(g, M, stream);
+    return info->scale_mode == 0 ? launch_grouped<0, false>(g, M, stream)
+         : info->scale_mode == 1 ? launch_grouped<1, false>(g, M, stream) : launch_grouped<2, false>(g, M, stream);
 }
 
 } // extern "C"

@@ -65,7 +65,23 @@ class BatchInfo(ctypes.Structure):
                 ("reserved", ctypes.c_uint32)]
 
 
-assert ctypes.sizeof(Header) == 256 and ctypes.sizeof(BatchItem) == 128
+class GemmGroupDesc(ctypes.Structure):
+    _fields_ = [("hdr", ctypes.POINTER(Header)), ("d_w", ctypes.c_void_p), ("rows", ctypes.c_uint64),
+                ("cols", ctypes.c_uint64), ("d_x", ctypes.c_void_p), ("d_y", ctypes.c_void_p),
+                ("d_w_scale", ctypes.c_void_p), ("d_x_scale", ctypes.c_void_p), ("x_scale_cols", ctypes.c_uint32),
+                ("M", ctypes.c_uint32)]
+
+
+class GemmGroupItem(ctypes.Structure):
+    _fields_ = [("opaque", ctypes.c_uint64 * 32)]
+
+
+class GemmGroupInfo(ctypes.Structure):
+    _fields_ = [("total_work", ctypes.c_uint64), ("n_items", ctypes.c_uint32), ("max_M", ctypes.c_uint32),
+                ("scale_mode", ctypes.c_uint32), ("raw", ctypes.c_uint32)]
+
+
+assert ctypes.sizeof(Header) == 256 and ctypes.sizeof(BatchItem) == 128 and ctypes.sizeof(GemmGroupItem) == 256
 
 _vp, _u64, _u32 = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32
 _lib.ecf8_encode.argtypes = [_vp, _u64, _u64, ctypes.POINTER(EncodeOpts), ctypes.POINTER(_vp)]
@@ -96,6 +112,9 @@ _lib.ecf8_gemm_splitk_workspace_bytes.restype = _u64
 _lib.ecf8_gemm_splitk_workspace_init.argtypes = [_vp, _u64, _vp]
 _lib.ecf8_gemm_fp8_splitk.argtypes = [ctypes.POINTER(Header), _vp, _vp, _u32, _vp, _vp, _u32, _vp, _vp, _u64, _vp]
 _lib.ecf8_gemm_fp8_raw_splitk.argtypes = [_vp, _u64, _u64, _vp, _u32, _vp, _vp, _u32, _vp, _vp, _u64, _vp]
+_lib.ecf8_gemm_group_prepare.argtypes = [ctypes.POINTER(GemmGroupDesc), _u32, ctypes.POINTER(GemmGroupItem),
+                                         ctypes.POINTER(GemmGroupInfo)]
+_lib.ecf8_gemm_fp8_grouped.argtypes = [_vp, ctypes.POINTER(GemmGroupInfo), _vp]
 _lib.ecf8_jit_create.argtypes = [_u32, _u32, ctypes.POINTER(_vp), _u64, ctypes.POINTER(_vp)]
 _lib.ecf8_jit_destroy.argtypes = [_vp]
 _lib.ecf8_jit_destroy.restype = None
@@ -453,6 +472,47 @@ def ecf8_gemm_fp8_raw_splitk(d_w, d_x, workspace, w_scale=None, x_scale=None, d_
                                                                      d_y.data_ptr(), workspace.data_ptr(), workspace.numel(),
                                                                      _stream_ptr(stream)))
     return d_y
+
+
+class GemmGroup:
+    """Device-resident item table for ecf8_gemm_fp8_grouped (built once, reused).  members: a list of dicts with
+    either hdr + blob (compressed W) or w (uncompressed (rows, cols) uint8 tensor), x ((M, cols) uint8), optional
+    w_scale / x_scale as for ecf8_gemm_fp8_scaled, optional y ((M, rows) fp32, allocated when absent).
+    self.y holds the outputs in order."""
+
+    def __init__(self, members):
+        n = len(members)
+        descs = (GemmGroupDesc * n)()
+        self.y, self._keep = [], []
+        for d, m in zip(descs, members):
+            x = m["x"]
+            M = x.shape[0]
+            if "hdr" in m:
+                hdr, rows, cols, w = m["hdr"], m["hdr"].rows, m["hdr"].cols, m["blob"]
+                d.hdr = ctypes.pointer(hdr)
+            else:
+                w = m["w"]
+                rows, cols = w.shape
+                d.rows, d.cols = rows, cols
+            y = m.get("y")
+            if y is None:
+                y = torch.empty((M, rows), dtype=torch.float32, device=x.device)
+            ws, xs, xc = _opt_scale_ptrs("ecf8_gemm_group_prepare", rows, cols, M, m.get("w_scale"), m.get("x_scale"))
+            d.d_w, d.d_x, d.d_y, d.M = w.data_ptr(), x.data_ptr(), y.data_ptr(), M
+            d.d_w_scale, d.d_x_scale, d.x_scale_cols = ws, xs, xc
+            self.y.append(y)
+            self._keep.append((w, x, m.get("w_scale"), m.get("x_scale"), m.get("hdr")))
+        items = (GemmGroupItem * n)()
+        self.info = GemmGroupInfo()
+        _check("ecf8_gemm_group_prepare", _lib.ecf8_gemm_group_prepare(descs, n, items, ctypes.byref(self.info)))
+        self.d_items = torch.from_numpy(np.frombuffer(items, dtype=np.uint8).copy()).to(members[0]["x"].device)
+
+
+def ecf8_gemm_fp8_grouped(group, stream=None):
+    """All products of a GemmGroup in one launch; returns group.y."""
+    _check("ecf8_gemm_fp8_grouped", _lib.ecf8_gemm_fp8_grouped(group.d_items.data_ptr(), ctypes.byref(group.info),
+                                                               _stream_ptr(stream)))
+    return group.y
 
 
 def version():

@@ -424,3 +424,105 @@ def test_split_k_calls_with_changing_inputs_share_a_workspace():
     bad = [int(k) for k, c in enumerate(order) if not torch.equal(got[k], cases[c][4])]
     assert not bad, "calls %s of 300 differ from the same call on a fresh workspace" % bad[:10]
     assert int(wsp[:4096].count_nonzero()) == 0
+
+
+# ---- a group of matrices in one launch ----
+
+def _group_members(shapes, Ms, seed, scale_mode=0, raw=False):
+    members, singles = [], []
+    for i, ((rows, K), M) in enumerate(zip(shapes, Ms)):
+        w = synth.make_weight(rows, K, 1.7, 0.02, seed, tensor_id=i).numpy()
+        x = synth.activations(M, K, seed=seed + 31 * i).numpy()
+        rng = np.random.default_rng(seed + i)
+        ws = np.exp(rng.normal(0.0, 0.7, size=((rows + 127) // 128, K // 128))).astype(np.float32)
+        xs = (np.exp(rng.normal(0.0, 0.5, size=M)) if scale_mode == 1 else np.exp(rng.normal(0.0, 0.5, size=(M, K // 128)))).astype(np.float32)
+        m = {"x": torch.from_numpy(x).to(DEV), "host": (x, w, ws, xs)}
+        if scale_mode:
+            m["w_scale"], m["x_scale"] = torch.from_numpy(ws).to(DEV), torch.from_numpy(xs).to(DEV)
+        if raw:
+            m["w"] = torch.from_numpy(w).to(DEV)
+        else:
+            blob = ecf8.ecf8_encode(w, rows, K, lane_syms=64, tile_rows=16, table_mode=1 + i % 2)   # with and without a table
+            m["hdr"], m["blob"] = blob.header, blob.to(DEV)
+        members.append(m)
+    return members
+
+
+def _single_call(m):
+    if "hdr" in m:
+        if "w_scale" in m:
+            return ecf8.ecf8_gemm_fp8_scaled(m["hdr"], m["blob"], m["x"], m["w_scale"], m["x_scale"])
+        return ecf8.ecf8_gemm_fp8(m["hdr"], m["blob"], m["x"])
+    if "w_scale" in m:
+        return ecf8.ecf8_gemm_fp8_raw_scaled(m["w"], m["x"], m["w_scale"], m["x_scale"])
+    return ecf8.ecf8_gemm_fp8_raw(m["w"], m["x"])
+
+
+GROUPS = {
+    "experts": ([(128, 1792), (128, 1792), (448, 512), (128, 1792), (448, 512), (64, 7168)], [3, 16, 1, 9, 16, 2]),
+    "one": ([(208, 4096)], [7]),
+    "many_tiny": ([(16, 256)] * 37 + [(32, 512)] * 5, [1 + (i * 7) % 16 for i in range(42)]),
+    "tall_M": ([(96, 2048), (48, 5120), (256, 4096)], [33, 64, 17]),
+    "mid_M": ([(96, 2048), (48, 5120), (160, 1024)], [32, 5, 20]),
+}
+
+
+@pytest.mark.parametrize("scale_mode", [0, 1, 2])
+@pytest.mark.parametrize("name", sorted(GROUPS))
+def test_grouped_gemm_equals_the_single_calls(orc, name, scale_mode):
+    """A group on compressed weights equals the same group on uncompressed weights bit for bit, launch after
+    launch.  Every product equals its single call bit for bit where that call runs the any-K kernels with
+    workgroups of the group's shape (K != 4096, and M on the same side of 16 as the group's largest M: the
+    same blocks computed the same way, only by other workgroups) and to a few fp32 roundings otherwise (the
+    same chunk sums added in another order).  Rows outside M stay untouched; one product of each group is
+    checked against the oracle as well."""
+    shapes, Ms = GROUPS[name]
+    members = _group_members(shapes, Ms, seed=11, scale_mode=scale_mode)
+    twins = _group_members(shapes, Ms, seed=11, scale_mode=scale_mode, raw=True)
+    guards = []
+    for m, (rows, K), M in zip(members, shapes, Ms):
+        g = torch.full((M + 2, rows), float("nan"), dtype=torch.float32, device=DEV)
+        m["y"] = g[1:M + 1]
+        guards.append(g)
+    print("group", name, "scales", scale_mode, flush=True)
+    group, twin = ecf8.GemmGroup(members), ecf8.GemmGroup(twins)
+    assert group.info.n_items == len(shapes) and group.info.max_M == max(Ms) and group.info.raw == 0 and twin.info.raw == 1
+    assert group.info.total_work == sum(r // 16 * (k // 256) for r, k in shapes) == twin.info.total_work
+    ys = [y.clone() for y in ecf8.ecf8_gemm_fp8_grouped(group)]
+    want = [_single_call(m) for m in members]
+    again = ecf8.ecf8_gemm_fp8_grouped(group)
+    raw = ecf8.ecf8_gemm_fp8_grouped(twin)
+    torch.cuda.synchronize()
+    for i, (y, w_, g) in enumerate(zip(ys, want, guards)):
+        assert torch.isnan(g[0]).all() and torch.isnan(g[-1]).all(), i
+        assert torch.equal(y, again[i]) and torch.equal(y, raw[i]), i
+        if shapes[i][1] != 4096 and (Ms[i] <= 16) == (max(Ms) <= 16):
+            assert torch.equal(y, w_), "member %d of %s" % (i, name)
+        else:
+            x, w, ws, xs = members[i]["host"]
+            _, mag = orc.gemm_ref_scaled(x, w, ws, xs) if scale_mode else orc.gemm_ref(x, w)
+            _check(y.cpu().numpy(), w_.cpu().numpy().astype(np.float64), mag, "member %d of %s against its single call" % (i, name), rel=2e-6)
+    x, w, ws, xs = members[-1]["host"]
+    yref, mag = orc.gemm_ref_scaled(x, w, ws, xs) if scale_mode else orc.gemm_ref(x, w)
+    _check(ys[-1].cpu().numpy(), yref, mag, "grouped, last member", rel=7 * 2.0 ** -13)
+
+
+def test_grouped_gemm_argument_errors():
+    shapes, Ms = GROUPS["mid_M"]
+    fused = _group_members(shapes, Ms, seed=3)
+    rawm = _group_members(shapes, Ms, seed=3, raw=True)
+    scaled = _group_members(shapes, Ms, seed=3, scale_mode=1)
+    for bad in ([fused[0], rawm[1]], [fused[0], scaled[1]], [scaled[0], _group_members(shapes, Ms, seed=3, scale_mode=2)[1]]):
+        with pytest.raises(ecf8.Ecf8Error) as e:
+            ecf8.GemmGroup(bad)
+        assert e.value.code == ecf8.E_ARG
+    lin = ecf8.ecf8_encode(synth.make_weight(64, 512, 1.7, 0.02, 1).numpy())           # not row-tiled
+    with pytest.raises(ecf8.Ecf8Error):
+        ecf8.GemmGroup([{"hdr": lin.header, "blob": lin.to(DEV), "x": fused[0]["x"][:, :512].contiguous()}])
+    group = ecf8.GemmGroup(fused)
+    info = ecf8.GemmGroupInfo.from_buffer_copy(group.info)
+    info.max_M = 65
+    assert ecf8._lib.ecf8_gemm_fp8_grouped(group.d_items.data_ptr(), info, None) == ecf8.E_ARG
+    assert ecf8._lib.ecf8_gemm_fp8_grouped(None, group.info, None) == ecf8.E_ARG
+    assert ecf8._lib.ecf8_gemm_fp8_grouped(group.d_items.data_ptr() + 4, group.info, None) == ecf8.E_ALIGN
+    assert ecf8._lib.ecf8_gemm_group_prepare(None, 1, None, None) == ecf8.E_ARG
