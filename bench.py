@@ -297,6 +297,39 @@ def bench_config4(a):
                 "raw_us": round(timeit(lambda: ecf8.ecf8_gemm_fp8_raw(ww, x, y2), a.steps, a.warmup) * 1e6, 2),
                 "raw_split_us": round(timeit(lambda: ecf8.ecf8_gemm_fp8_raw_splitk(ww, x, wsp, d_y=y2), a.steps, a.warmup) * 1e6, 2)}
         res_split["%dx%d" % (rows, cols)] = entry
+    # a group of experts in one launch (config 2's shapes: 8 experts a token batch is routed to, gate / up 2048 x 7168
+    # and down 7168 x 2048 each) against one call per matrix
+    res_group = {}
+    experts = []
+    for e in range(8):
+        for j, (rows, cols) in enumerate(((2048, 7168), (2048, 7168), (7168, 2048))):
+            ww = synth.make_weight(rows, cols, 1.7, 0.02, a.seed, tensor_id=410000 + 3 * e + j, device="cuda:0")
+            bb = ecf8.ecf8_encode(ww.cpu(), rows, cols, lane_syms=64, tile_rows=16)
+            experts.append((ww, bb.header, bb.to("cuda:0")))
+    for M in (1, 4, 16, 64):
+        fused_m = [{"hdr": h_, "blob": b_, "x": synth.activations(M, h_.cols, seed=a.seed + i, device="cuda:0")}
+                   for i, (w_, h_, b_) in enumerate(experts)]
+        raw_m = [{"w": w_, "x": f_["x"]} for (w_, h_, b_), f_ in zip(experts, fused_m)]
+        gf, gr = ecf8.GemmGroup(fused_m), ecf8.GemmGroup(raw_m)
+        yf, yr = ecf8.ecf8_gemm_fp8_grouped(gf), ecf8.ecf8_gemm_fp8_grouped(gr)
+        torch.cuda.synchronize()
+        if not all(torch.equal(p_, q_) for p_, q_ in zip(yf, yr)):
+            raise SystemExit("grouped fused GEMM differs from its twin on uncompressed weights at M=%d" % M)
+
+        def singles_fused():
+            for f_, y_ in zip(fused_m, yf):
+                ecf8.ecf8_gemm_fp8(f_["hdr"], f_["blob"], f_["x"], y_)
+
+        def singles_raw():
+            for r_, y_ in zip(raw_m, yr):
+                ecf8.ecf8_gemm_fp8_raw(r_["w"], r_["x"], y_)
+        res_group["M=%d" % M] = {
+            "grouped_fused_us": round(timeit(lambda: ecf8.ecf8_gemm_fp8_grouped(gf), a.steps, a.warmup) * 1e6, 2),
+            "grouped_raw_us": round(timeit(lambda: ecf8.ecf8_gemm_fp8_grouped(gr), a.steps, a.warmup) * 1e6, 2),
+            "24_fused_calls_us": round(timeit(singles_fused, a.steps, a.warmup) * 1e6, 2),
+            "24_raw_calls_us": round(timeit(singles_raw, a.steps, a.warmup) * 1e6, 2)}
+    res_group["weights"] = sum(w_.numel() for w_, _, _ in experts)
+    del experts
     t16 = res["M=16"]["fused_us"] * 1e-6
     print(json.dumps({
         "metric": "decoded FP8 GB/s consumed by the fused decode+GEMM (M=16)", "value": round(w.numel() / t16 / 1e9, 2),
@@ -304,7 +337,8 @@ def bench_config4(a):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "fp8 x fp8 -> f32", "data": "synthetic",
         "config": {"workload": "config4: fused decode + FP8 MFMA GEMM, W 14336x4096, M in {1,16,64}", "seed": a.seed},
         "compression_ratio": round(h.total_size / w.numel(), 5), "bit_exact_vs_raw_weights_gemm": True,
-        "gemm": res, "beyond_M64": crossover, "gemm_down_4096x14336_any_k": res_down, "split_k": res_split}))
+        "gemm": res, "beyond_M64": crossover, "gemm_down_4096x14336_any_k": res_down, "split_k": res_split,
+        "grouped_8_experts": res_group}))
 
 def bench_jit(a):
     """Workload "jit" (paper Section 3.3): a forward pass over the config-1 stack with the weights

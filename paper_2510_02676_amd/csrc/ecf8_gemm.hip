@@ -207,6 +207,60 @@ __device__ __forceinline__ void reduce_block(f32x4 *red, const GArgs &a, uint64_
     }
 }
 
+// How the NW waves of a workgroup share the work of a unit in the any-K kernels.  Long K: a unit is one
+// block of rows and its chunks are dealt round-robin to all waves.  Short K (at most NW / 2 chunks per
+// block): the waves form `groups` groups of `wpb`, and each group takes a block of rows of its own --
+// blocks j, j + 1, ... of the workgroup's sequence -- so that no wave is left without work (at K = 2048,
+// 8 chunks, half of 16 waves would be).
+struct Deal {
+    uint32_t groups, wpb;       // blocks per unit; waves per block
+    uint32_t gi, kw;            // this wave: its group, its place in the group
+    uint32_t my_chunks;         // chunks of a block (or slice) that fall to this wave
+};
+
+template <int NW>
+__device__ __forceinline__ Deal deal_chunks(uint32_t unit_chunks, bool split, int wave)
+{
+    Deal d;
+    const uint32_t w = uniform32((uint32_t)wave);       // the same for every lane: keep all of this in scalar registers
+    d.groups = (!split && 2 * unit_chunks <= (uint32_t)NW) ? (uint32_t)NW / unit_chunks : 1u;
+    d.wpb = (uint32_t)NW / d.groups;
+    d.gi = w / d.wpb;
+    d.kw = w % d.wpb;
+    d.my_chunks = (d.gi < d.groups && unit_chunks > d.kw) ? (unit_chunks - d.kw + d.wpb - 1) / d.wpb : 0u;
+    return d;
+}
+
+// reduce_block for a unit of d.groups blocks: blocks j0 .. j0 + groups - 1 of the sequence first + j * stride
+// (those below `count`), each summed over the waves of its group -- in the order reduce_block takes them,
+// so that a block's result does not depend on how many blocks shared the unit.
+template <int MT, int NW, bool SCALED>
+__device__ __forceinline__ void reduce_groups(f32x4 *red, const GArgs &a, uint64_t first, uint64_t stride, uint64_t j0, uint64_t count,
+                                              const Deal &d, int tid, const f32x4 (&acc)[MT])
+{
+    if (d.groups == 1) {
+        reduce_block<MT, NW, SCALED>(red, a, first + j0 * stride, tid, acc);
+        return;
+    }
+    const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++) red[(wave * MT + mt) * 64 + lane] = acc[mt];
+    __syncthreads();
+    GLOBAL float *Y = (GLOBAL float *)a.d_y;
+    for (uint32_t o = tid; o < d.groups * (MT * 256); o += NW * 64) {
+        const uint32_t g = o / (MT * 256), oo = o % (MT * 256);
+        const uint32_t mt = oo >> 8, l = (oo >> 2) & 63, r = oo & 3;
+        if (j0 + g >= count) break;                     // the sequence ended inside this unit
+        float sum = 0.f;
+        for (uint32_t w = g * d.wpb; w < (g + 1) * d.wpb; w++) sum += ((const float *)&red[(w * MT + mt) * 64 + l])[r];
+        const uint32_t m = 16 * mt + 4 * (l >> 4) + r;
+        if (m < a.M) {
+            if (SCALED && a.d_xs && a.xs_cols == 1) sum *= ((const GLOBAL float *)a.d_xs)[m];
+            Y[(uint64_t)m * a.rows + (first + (j0 + g) * stride) * BLOCK_ROWS + (l & 15)] = sum;
+        }
+    }
+}
+
 // Split K: the partial sums of the unit (block of rows, slice of K) go to the workspace, and the
 // workgroup that brings a block's last slice adds the slices up -- in slice order, so the result
 // does not depend on which one that was -- and writes the outputs.  No workgroup waits for
@@ -450,7 +504,8 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_raw_kernel(GArgs a)
 // ---- any K (a multiple of 256) ----
 // The kernels above keep the wave's slice of X in registers, which is what makes K = 4096 fast
 // and what ties them to it.  These take any K: the K / 256 chunks of a block of rows are dealt
-// round-robin to the NW waves (some waves get one chunk fewer, or none when K / 256 < NW), and
+// round-robin to the NW waves (some waves get one chunk fewer; where a block has at most NW / 2
+// chunks the waves split into groups with a block each, see Deal), and
 // the A operands of a chunk are fetched from X (L2-resident: M x K bytes) one chunk ahead, like
 // the chunk's payload.  Same decode, same MFMA order inside a chunk, same reduction.
 
@@ -517,13 +572,14 @@ __device__ __forceinline__ void anyk_walk(const GArgs &a, uint8_t *smem, uint32_
     const uint64_t lane_elem = (uint64_t)(lane & 15) * a.K + (uint64_t)(lane >> 4) * 16;
     const uint32_t kchunks = (uint32_t)(a.K / BLOCK_COLS);
     const uint32_t unit_chunks = SPLIT ? kchunks / a.slices : kchunks;                                     // chunks of K per unit
-    const uint32_t my_chunks = unit_chunks > (uint32_t)wave ? (unit_chunks - wave + NW - 1) / NW : 0;     // wave-uniform
-    const uint64_t my_blocks = my_units;
+    const Deal deal = deal_chunks<NW>(unit_chunks, SPLIT, wave);
+    const uint32_t my_chunks = deal.my_chunks;                                                             // wave-uniform
+    const uint64_t my_blocks = (my_units + deal.groups - 1) / deal.groups;                                 // units of `groups` blocks
 
     struct Meta { uint64_t b0, b1; uint32_t lb; };
     struct Payload { u32x4 seg[GSEGS]; u32x2 pl[GPIECES]; };
     auto at_unit = [&](uint64_t b) {
-        Walk w{b, 0, first_unit + b * unit_stride, 0};
+        Walk w{b, 0, first_unit + (b * deal.groups + deal.gi) * unit_stride, 0};
         if constexpr (SPLIT) {
             const uint32_t u = (uint32_t)w.block;            // units < 2^31, checked on the host
             w.block = u / a.slices;
@@ -532,8 +588,8 @@ __device__ __forceinline__ void anyk_walk(const GArgs &a, uint8_t *smem, uint32_
         return w;
     };
     auto block_of = [&](const Walk &w) -> uint64_t { return w.block; };
-    auto kc_of = [&](const Walk &w) -> uint32_t { return w.k0 + wave + NW * w.i; };
-    auto valid = [&](const Walk &w) { return my_chunks != 0 && w.b < my_blocks; };
+    auto kc_of = [&](const Walk &w) -> uint32_t { return w.k0 + deal.kw + deal.wpb * w.i; };
+    auto valid = [&](const Walk &w) { return my_chunks != 0 && w.b * deal.groups + deal.gi < my_units; };
     auto next_of = [&](Walk w) { if (++w.i == my_chunks) w = at_unit(w.b + 1); return w; };
     auto load_meta = [&](const Walk &w) {
         const uint64_t c = block_of(w) * kchunks + kc_of(w);
@@ -596,8 +652,9 @@ __device__ __forceinline__ void anyk_walk(const GArgs &a, uint8_t *smem, uint32_
         f32x4 acc[MT];
 #pragma unroll
         for (int mt = 0; mt < MT; mt++) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        const uint32_t n_mine = valid(at_unit(b)) ? my_chunks : 0;       // the sequence may end inside the last unit
 #pragma unroll 1
-        for (uint32_t i = 0; i < my_chunks; i++) {
+        for (uint32_t i = 0; i < n_mine; i++) {
             const Meta m = m_cur;
             uint64_t byte0;
             span_of(m, byte0);
@@ -642,7 +699,7 @@ __device__ __forceinline__ void anyk_walk(const GArgs &a, uint8_t *smem, uint32_
         f32x4 *red = (f32x4 *)(smem + C::OFF_RED + parity * C::RED_BYTES);
         const Walk unit = at_unit(b);
         if constexpr (SPLIT) reduce_split<MT, NW, SCALED>(red, s_flag, a, (uint32_t)unit.block, unit.k0 / unit_chunks, tid, acc);
-        else reduce_block<MT, NW, SCALED>(red, a, unit.block, tid, acc);
+        else reduce_groups<MT, NW, SCALED>(red, a, first_unit, unit_stride, b * deal.groups, my_units, deal, tid, acc);
         parity ^= 1;
     }
 }
@@ -676,10 +733,11 @@ __device__ __forceinline__ void raw_anyk_walk(const GArgs &a, uint8_t *smem, uin
     const uint64_t lane_elem = (uint64_t)(lane & 15) * a.K + (uint64_t)(lane >> 4) * 16;
     const uint32_t kchunks = (uint32_t)(a.K / BLOCK_COLS);
     const uint32_t unit_chunks = SPLIT ? kchunks / a.slices : kchunks;
-    const uint32_t my_chunks = unit_chunks > (uint32_t)wave ? (unit_chunks - wave + NW - 1) / NW : 0;
-    const uint64_t my_blocks = my_units;
+    const Deal deal = deal_chunks<NW>(unit_chunks, SPLIT, wave);
+    const uint32_t my_chunks = deal.my_chunks;
+    const uint64_t my_blocks = (my_units + deal.groups - 1) / deal.groups;
     auto at_unit = [&](uint64_t b) {
-        Walk w{b, 0, first_unit + b * unit_stride, 0};
+        Walk w{b, 0, first_unit + (b * deal.groups + deal.gi) * unit_stride, 0};
         if constexpr (SPLIT) {
             const uint32_t u = (uint32_t)w.block;
             w.block = u / a.slices;
@@ -688,8 +746,8 @@ __device__ __forceinline__ void raw_anyk_walk(const GArgs &a, uint8_t *smem, uin
         return w;
     };
     auto block_of = [&](const Walk &w) -> uint64_t { return w.block; };
-    auto kc_of = [&](const Walk &w) -> uint32_t { return w.k0 + wave + NW * w.i; };
-    auto valid = [&](const Walk &w) { return my_chunks != 0 && w.b < my_blocks; };
+    auto kc_of = [&](const Walk &w) -> uint32_t { return w.k0 + deal.kw + deal.wpb * w.i; };
+    auto valid = [&](const Walk &w) { return my_chunks != 0 && w.b * deal.groups + deal.gi < my_units; };
     auto next_of = [&](Walk w) { if (++w.i == my_chunks) w = at_unit(w.b + 1); return w; };
     auto load_w = [&](const Walk &w, u32x4 (&v)[GPIECES]) {
         const uint64_t e0 = block_of(w) * BLOCK_ROWS * a.K + kc_of(w) * (uint64_t)BLOCK_COLS + lane_elem;
@@ -707,8 +765,9 @@ __device__ __forceinline__ void raw_anyk_walk(const GArgs &a, uint8_t *smem, uin
         f32x4 acc[MT];
 #pragma unroll
         for (int mt = 0; mt < MT; mt++) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        const uint32_t n_mine = valid(at_unit(b)) ? my_chunks : 0;
 #pragma unroll 1
-        for (uint32_t i = 0; i < my_chunks; i++) {
+        for (uint32_t i = 0; i < n_mine; i++) {
             const XPieces<MT, N> x = x_cur;
             ChunkSums<MT, SC> sums;
             sums.begin(a, block_of(cur), kc_of(cur));
@@ -734,7 +793,7 @@ __device__ __forceinline__ void raw_anyk_walk(const GArgs &a, uint8_t *smem, uin
         f32x4 *red = (f32x4 *)(smem + parity * C::RED_BYTES);
         const Walk unit = at_unit(b);
         if constexpr (SPLIT) reduce_split<MT, NW, SCALED>(red, s_flag, a, (uint32_t)unit.block, unit.k0 / unit_chunks, tid, acc);
-        else reduce_block<MT, NW, SCALED>(red, a, unit.block, tid, acc);
+        else reduce_groups<MT, NW, SCALED>(red, a, first_unit, unit_stride, b * deal.groups, my_units, deal, tid, acc);
         parity ^= 1;
     }
 }
