@@ -337,6 +337,12 @@ def bench_config4(a):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "fp8 x fp8 -> f32", "data": "synthetic",
         "config": {"workload": "config4: fused decode + FP8 MFMA GEMM, W 14336x4096, M in {1,16,64}", "seed": a.seed},
         "compression_ratio": round(h.total_size / w.numel(), 5), "bit_exact_vs_raw_weights_gemm": True,
+        # the fused kernel reads the blob and X and writes Y: far from the memory roof, it is bound by the decode arithmetic
+        "roofline": {"bound": "hbm", "kernel": "ecf8_gemm_kernel<1, 16, 64, 0>", "achieved": round((h.total_size + 16 * (spec["cols"] + 4 * spec["rows"])) / t16 / 1e9, 2),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round((h.total_size + 16 * (spec["cols"] + 4 * spec["rows"])) / t16 / 1e9 / HBM_PEAK_GBPS, 4),
+                     "avg_launch_us": round(t16 * 1e6, 2),
+                     "algorithmic_bytes_per_launch": int(h.total_size + 16 * (spec["cols"] + 4 * spec["rows"])), "traffic": None},
         "gemm": res, "beyond_M64": crossover, "gemm_down_4096x14336_any_k": res_down, "split_k": res_split,
         "grouped_8_experts": res_group}))
 
