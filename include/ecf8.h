@@ -239,7 +239,9 @@ typedef struct ecf8_batch_info {
                             /* else a cap, to leave compute units to kernels that   */
                             /* run beside the decode (a decode workgroup fills its  */
                             /* compute unit); batch_prepare sets 0                  */
-    uint32_t reserved;
+    uint32_t row_tiled;     /* 1: every tensor of the batch is in the row-tiled layout */
+                            /* (their chunks then leave the kernel as whole row       */
+                            /* segments); batch_prepare sets it                       */
 } ecf8_batch_info;
 
 /*

@@ -60,9 +60,10 @@ struct KArgs {
     uint64_t total_chunks;
     uint32_t max_code_len;                // longest codeword of any tensor of the launch
     uint32_t max_workgroups;              // 0 = one per compute unit
+    uint32_t row_tiled;                   // every tensor of the launch is in the row-tiled layout
 };
 
-template <int N, int WAVES, bool PAIRFIT>
+template <int N, int WAVES, bool PAIRFIT, bool TILED = false>
 struct Cfg {
     // bytes of stream staged per chunk: under the cap of TB/2 bits per codeword the worst case
     // (so no chunk of a PAIRFIT launch is ever oversize), else a good 4 bits per symbol
@@ -83,16 +84,21 @@ struct Cfg {
     static_assert(PAIRFIT || SLOTS >= 1, "wide slots must fit the stage area");
     static_assert(OFF_WAVES % 16 == 0 && SLOT % 16 == 0, "16-byte LDS stores");
     static constexpr int WAVES_BYTES = WAVES * STAGE > TBL_ENTRIES * 2 ? WAVES * STAGE : TBL_ENTRIES * 2;
-    static constexpr int TOTAL = OFF_WAVES + WAVES_BYTES;   // table-build scratch aliases the stages
+    // TILED: a 16 x 256-byte tile per wave in which a decoded chunk of a row-tiled blob is turned from the
+    // lanes' pieces (16 bytes of row l % 16 each) into whole 256-byte row segments before it is stored
+    static constexpr int OFF_TILE = OFF_WAVES + WAVES_BYTES;  // table-build scratch aliases the stages
+    static constexpr int TILE_BYTES = 16 * 4 * N;
+    static_assert(!TILED || (PAIRFIT && N == 64), "the tile turn is built for the fused GEMM's layout");
+    static constexpr int TOTAL = OFF_TILE + (TILED ? WAVES * TILE_BYTES : 0);
     static_assert(TOTAL <= 160 * 1024, "LDS of one gfx950 CU");
 };
 
 // PAIRFIT: every tensor of the launch has codewords of at most TB/2 bits (the encoder's
 // default cap), so the pipelined loop needs no second level and is one straight line.
-template <int N, int WAVES, bool PAIRFIT>
+template <int N, int WAVES, bool PAIRFIT, bool TILED = false>
 __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
 {
-    using C = Cfg<N, WAVES, PAIRFIT>;
+    using C = Cfg<N, WAVES, PAIRFIT, TILED>;
     __shared__ __attribute__((aligned(16))) uint8_t smem[C::TOTAL];
     uint16_t *tbl = (uint16_t *)(smem + C::OFF_TBL);
     uint32_t *s_len = (uint32_t *)(smem + C::OFF_SYM);
@@ -296,7 +302,23 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
                               (GLOBAL u32x4 *)(out_c + (Q + C::PIECES / 2) * ostride));
                 }
             }
-            if constexpr (PAIRFIT) {
+            if constexpr (TILED) {
+                // Row-tiled blob: lane (r = l % 16, g = l / 16) holds columns 64 Q + 16 g of row r, so a store of
+                // piece Q as it is would cover 16 rows x 64 bytes.  Through the wave's tile the pieces become whole
+                // row segments: store j covers rows 4 j .. 4 j + 3 x 256 bytes, lane l row 4 j + l / 16, columns
+                // 16 (l % 16).  The 16-byte units of a row are swizzled by the row number against bank conflicts.
+                uint8_t *tile = smem + C::OFF_TILE + wave * C::TILE_BYTES;
+                const uint32_t r = lane & 15, g = lane >> 4;
+#pragma unroll
+                for (int Q = 0; Q < C::PIECES; Q++) *(u32x4 *)(tile + r * 256 + (((4 * Q + g) ^ r) & 15) * 16) = ov[Q];
+                GLOBAL uint8_t *out_t = out_c - lane_off + (uint64_t)g * tcols + r * 16;       // row l / 16, columns 16 (l % 16)
+#pragma unroll
+                for (int j = 0; j < 4; j++) ov[j] = *(const u32x4 *)(tile + (4 * j + g) * 256 + ((r ^ (4 * j + g)) & 15) * 16);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int j = 0; j < 4; j++) ST_STREAM(ov[j], (GLOBAL u32x4 *)(out_t + (uint64_t)(4 * j) * tcols));
+                __builtin_amdgcn_sched_barrier(0);
+            } else if constexpr (PAIRFIT) {
                 __builtin_amdgcn_sched_barrier(0);   // keep the stores together, after the decode
 #pragma unroll
                 for (int Q = 0; Q < C::PIECES; Q++) ST_STREAM(ov[Q], (GLOBAL u32x4 *)(out_c + Q * ostride));
@@ -439,7 +461,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
     }
 }
 
-template <int N, int WAVES, bool PAIRFIT>
+template <int N, int WAVES, bool PAIRFIT, bool TILED = false>
 int launch_as(const KArgs &a, int wgs_per_cu, hipStream_t s)
 {
     int cus = device_cus();
@@ -449,7 +471,7 @@ int launch_as(const KArgs &a, int wgs_per_cu, hipStream_t s)
     if (a.max_workgroups && a.max_workgroups < cap) cap = a.max_workgroups;
     uint32_t grid = (uint32_t)(want < cap ? want : cap);
     if (grid == 0) grid = 1;
-    hipLaunchKernelGGL((ecf8_decode_kernel<N, WAVES, PAIRFIT>), dim3(grid), dim3(WAVES * 64), 0, s, a);
+    hipLaunchKernelGGL((ecf8_decode_kernel<N, WAVES, PAIRFIT, TILED>), dim3(grid), dim3(WAVES * 64), 0, s, a);
     return hipGetLastError() == hipSuccess ? ECF8_OK : ECF8_E_HIP;
 }
 
@@ -462,7 +484,10 @@ int dispatch(const KArgs &a, uint32_t lane_syms, hipStream_t s)
     const bool pairfit = 2 * a.max_code_len <= (uint32_t)TB;
     switch (lane_syms) {
     case 32: return pairfit ? launch_as<32, 16, true>(a, 1, s) : launch_as<32, 16, false>(a, 1, s);
-    case 64: return pairfit ? launch_as<64, 16, true>(a, 1, s) : launch_as<64, 16, false>(a, 1, s);
+    case 64:
+        // the fused GEMM's blobs (row-tiled, capped codes): decoded chunks leave as whole row segments
+        if (pairfit && a.row_tiled) return launch_as<64, 16, true, true>(a, 1, s);
+        return pairfit ? launch_as<64, 16, true>(a, 1, s) : launch_as<64, 16, false>(a, 1, s);
     case 128: return pairfit ? launch_as<128, 8, true>(a, 1, s) : launch_as<128, 12, false>(a, 1, s);
     default: return ECF8_E_ARG;
     }
@@ -506,6 +531,7 @@ int ecf8_decode(const ecf8_header *h, const void *d_blob, void *d_out, uint64_t 
     a.items = nullptr;
     a.n_items = 1;
     a.total_chunks = h->n_chunks;
+    a.row_tiled = h->tile_rows != 0;
     for (int i = 0; i < 16; i++) a.max_code_len = h->code_len[i] > a.max_code_len ? h->code_len[i] : a.max_code_len;
     return dispatch(a, h->lane_syms, (hipStream_t)stream);
 }
@@ -521,6 +547,7 @@ int ecf8_decode_batched(const ecf8_batch_item *d_items, uint32_t n_tensors, cons
     a.total_chunks = info->total_chunks;
     a.max_code_len = info->max_code_len;
     a.max_workgroups = info->max_workgroups;
+    a.row_tiled = info->row_tiled;
     return dispatch(a, info->lane_syms, (hipStream_t)stream);
 }
 

@@ -582,6 +582,7 @@ int ecf8_batch_prepare(const ecf8_header *hdrs, const void *const *d_blobs, void
     if (!hdrs || !d_blobs || !d_outs || !caps || !items || !info || n == 0) return ECF8_E_ARG;
     uint64_t first = 0;
     uint32_t max_len = 0;
+    bool all_tiled = true;
     for (uint32_t i = 0; i < n; i++) {
         const ecf8_header &h = hdrs[i];
         int rc = check_header(h, h.total_size);
@@ -607,13 +608,14 @@ int ecf8_batch_prepare(const ecf8_header *hdrs, const void *const *d_blobs, void
         it.tile_cols = h.tile_rows ? h.cols : 0;
         std::memcpy(it.code_len, h.code_len, 16);
         for (int s = 0; s < 16; s++) max_len = std::max<uint32_t>(max_len, h.code_len[s]);
+        if (!h.tile_rows) all_tiled = false;
         first += h.n_chunks;
     }
     info->total_chunks = first;
     info->lane_syms = hdrs[0].lane_syms;
     info->max_code_len = max_len;
     info->max_workgroups = 0;
-    info->reserved = 0;
+    info->row_tiled = all_tiled ? 1u : 0u;
     return ECF8_OK;
 }
 

@@ -62,7 +62,7 @@ class BatchItem(ctypes.Structure):
 class BatchInfo(ctypes.Structure):
     _fields_ = [("total_chunks", ctypes.c_uint64), ("lane_syms", ctypes.c_uint32),
                 ("max_code_len", ctypes.c_uint32), ("max_workgroups", ctypes.c_uint32),
-                ("reserved", ctypes.c_uint32)]
+                ("row_tiled", ctypes.c_uint32)]
 
 
 class GemmGroupDesc(ctypes.Structure):

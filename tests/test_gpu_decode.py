@@ -204,6 +204,35 @@ def test_row_tiled_blobs_decode(orc, lane_syms, rows, cols, cap):
     assert np.array_equal(got, dec)
 
 
+@pytest.mark.parametrize("rows,cols", [(16, 256), (48, 512), (1040, 4096), (272, 14336), (4096, 1024)])
+def test_row_tiled_blobs_of_the_fused_gemm_decode_as_row_segments(orc, rows, cols):
+    """The fused GEMM's blobs (row-tiled, N = 64, codes capped at 7 bits) through ecf8_decode and through a
+    batch: the kernel variant that turns a decoded chunk into whole 256-byte row segments in LDS before
+    storing it.  Against the input, the oracle's reader (small cases) and with guard bytes around the output;
+    a batch that mixes such a blob with a linear one takes the general route and must agree as well."""
+    x = synth.make_weight(rows, cols, 1.7, 0.02, rows + cols).numpy()
+    blob = ecf8.ecf8_encode(x, rows, cols, lane_syms=64, tile_rows=16, table_mode=1 + (rows > 100))
+    assert blob.header.tile_rows == 16 and max(blob.header.code_len) <= 7
+    got, guards = _gpu_decode_guarded(blob.numpy(), blob.header)
+    assert guards
+    assert np.array_equal(got, x.reshape(-1))
+    if rows * cols <= 1 << 22:
+        dec, _ = orc.container_decode(blob.numpy())
+        assert np.array_equal(got, dec)
+    x2 = synth.make_weight(rows, cols, 1.9, 0.015, 5).numpy()
+    blob2 = ecf8.ecf8_encode(x2, rows, cols, lane_syms=64, tile_rows=16)
+    lin = ecf8.ecf8_encode(x2, rows, cols, lane_syms=64)
+    for members, tiled in (((x, blob), (x2, blob2)), True), (((x, blob), (x2, lin)), False):
+        outs = [torch.full((rows * cols + 64,), 0xEE, dtype=torch.uint8, device=DEV) for _ in members]
+        batch = ecf8.Batch([b.header for _, b in members], [b.to(DEV) for _, b in members], [o[32:32 + rows * cols] for o in outs])
+        assert batch.info.row_tiled == int(tiled)
+        ecf8.ecf8_decode_batched(batch)
+        torch.cuda.synchronize()
+        for (want, _), o in zip(members, outs):
+            assert np.array_equal(o[32:32 + rows * cols].cpu().numpy(), want.reshape(-1))
+            assert bool((o[:32] == 0xEE).all()) and bool((o[32 + rows * cols:] == 0xEE).all())
+
+
 @pytest.mark.parametrize("lane_syms,group", [(64, 1), (64, 4), (128, 32)])
 def test_oracle_written_container_decodes_on_gpu(orc, lane_syms, group):
     """Interop: a container written by the oracle's writer (its own tie-breaks)."""
