@@ -445,6 +445,16 @@ def bench_jit(a):
                 ecf8.ecf8_gemm_fp8(hdr_t, d_t, x, y[:, :w2.shape[0]], stream=main_stream)
     t_fused = timed(fused_pass)
     tiled_bytes = sum(h.total_size for l in tiled for h, _, _ in tiled[l])
+    # one compressed copy for both regimes: the same row-tiled blobs decoded just in time into the two buffers
+    jit_t = ecf8.Jit([([t[0] for t in tiled[l]], [t[1] for t in tiled[l]]) for l in range(layers)], n_buffers=2)
+    jit_t.prefetch(0)
+    ws = jit_t.acquire(0, main_stream)
+    if not all(torch.equal(v.reshape(-1), t[2].reshape(-1)) for v, t in zip(ws, tiled[0])):
+        raise SystemExit("jit: layer 0 decoded from row-tiled blobs differs from its weights")
+    jit_t.release(0, main_stream)
+    torch.cuda.synchronize()
+    t_jit_tiled = timed(make_pass(jit_t, True))
+    del jit_t
     del tiled
     # the way serving stacks hold these layers: Q, K, V as one matrix and gate, up as one (they share their input),
     # which fills the chip better with blocks of rows; resident and fused alike
@@ -492,6 +502,7 @@ def bench_jit(a):
         "pass_ms": {"compute_on_resident_weights": round(t_res, 4), "decode_then_compute_1_buffer": round(t_serial, 4),
                     "jit_2_buffers_overlapped": round(t_jit, 4),
                     "fused_decode_gemm_no_buffer": round(t_fused, 4),
+                    "jit_2_buffers_from_the_fused_calls_row_tiled_blobs": round(t_jit_tiled, 4),
                     "qkv_and_gate_up_merged": {"compute_on_resident_weights": round(t_res_m, 4),
                                                "fused_decode_gemm_no_buffer": round(t_fused_m, 4)}},
         "resident_compressed_bytes_row_tiled": tiled_bytes,
