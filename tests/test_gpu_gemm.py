@@ -526,3 +526,60 @@ def test_grouped_gemm_argument_errors():
     assert ecf8._lib.ecf8_gemm_fp8_grouped(None, group.info, None) == ecf8.E_ARG
     assert ecf8._lib.ecf8_gemm_fp8_grouped(group.d_items.data_ptr() + 4, group.info, None) == ecf8.E_ALIGN
     assert ecf8._lib.ecf8_gemm_group_prepare(None, 1, None, None) == ecf8.E_ARG
+
+
+def test_gemm_calls_replay_from_a_hip_graph():
+    """The GEMM calls allocate nothing, synchronise nothing and clear nothing with memsets (the split-K counters
+    are put back to zero by the kernel itself), so a decoding loop may capture them into a HIP graph: a plain, a
+    scaled, a split-K and a grouped call are captured once and replayed three times with new activations
+    written into the same buffers and eager calls in between; every replay equals the eager result."""
+    rows, K, M = 576, 7168, 8
+    w = synth.make_weight(rows, K, 1.7, 0.02, 41).numpy()
+    blob = ecf8.ecf8_encode(w, rows, K, lane_syms=64, tile_rows=16)
+    d_blob = blob.to(DEV)
+    ws = torch.from_numpy(np.exp(np.random.default_rng(2).normal(0.0, 0.7, size=((rows + 127) // 128, K // 128))).astype(np.float32)).to(DEV)
+    x = synth.activations(M, K, seed=600).to(DEV)
+    wsp = ecf8.gemm_splitk_workspace(rows, K, M, DEV)
+    shapes, Ms = GROUPS["experts"]
+    members = _group_members(shapes, Ms, seed=17)
+    group = ecf8.GemmGroup(members)
+    y_plain = torch.empty((M, rows), dtype=torch.float32, device=DEV)
+    y_scaled, y_split = torch.empty_like(y_plain), torch.empty_like(y_plain)
+
+    def run(s):
+        ecf8.ecf8_gemm_fp8(blob.header, d_blob, x, y_plain, stream=s)
+        ecf8.ecf8_gemm_fp8_scaled(blob.header, d_blob, x, ws, None, y_scaled, stream=s)
+        ecf8.ecf8_gemm_fp8_splitk(blob.header, d_blob, x, wsp, d_y=y_split, stream=s)
+        ecf8.ecf8_gemm_fp8_grouped(group, stream=s)
+
+    def results():
+        return [y_plain.clone(), y_scaled.clone(), y_split.clone()] + [y.clone() for y in group.y]
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):            # warm-up outside the capture
+        run(side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run(torch.cuda.current_stream())
+    for rep in range(3):
+        x.copy_(synth.activations(M, K, seed=601 + rep).to(DEV))
+        for i, m in enumerate(members):
+            m["x"].copy_(synth.activations(m["x"].shape[0], m["x"].shape[1], seed=700 + 10 * rep + i).to(DEV))
+        torch.cuda.synchronize()
+        run(None)                            # eager, on the new activations
+        torch.cuda.synchronize()
+        want = results()
+        for t in [y_plain, y_scaled, y_split] + group.y:
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = results()
+        assert all(torch.equal(p, q) for p, q in zip(got, want)), rep
+        assert int(wsp[:4096].count_nonzero()) == 0
+        if rep:
+            assert not torch.equal(want[0], first[0])
+        first = want
