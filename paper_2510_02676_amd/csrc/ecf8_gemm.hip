@@ -25,6 +25,14 @@
 // The kernels need capped codes (no codeword over TB/2 bits: every pair is one
 // table hit, and a chunk's span always fits its stage), so they have no second
 // level and no fallback path.
+//
+// In this file: the K = 4096 kernels (X resident in registers) and their twins on
+// uncompressed W; the any-K kernels (X fetched chunk by chunk; at short K the waves
+// form groups with a block of rows each); scales per 128 x 128 block of W and per
+// row or 1 x 128 group of X (ChunkSums); split K for matrices of few rows
+// (reduce_split: partial sums and arrival counters in a caller-provided workspace);
+// a group of matrices in one launch (ecf8_gemm_grouped_kernel); the host side of
+// all of them.
 #include "ecf8_device.h"
 
 #include <cstring>
