@@ -311,3 +311,48 @@ def test_validate_survives_random_corruption(wide):
         bad = good.copy()
         bad[int(off)] ^= 0x10
         validate(bad)
+
+
+def test_gemm_group_prepare_is_pure_host_logic():
+    """ecf8_gemm_group_prepare touches no device: with made-up (aligned) device addresses it lays the members out
+    by their chunks of 16 x 256 weights, records the largest M and the kind of scales, and rejects mixed groups."""
+    shapes, Ms = [(64, 512), (32, 7168), (160, 2048)], [3, 64, 16]
+    hdrs = []
+    for i, (rows, cols) in enumerate(shapes):
+        w = synth.make_weight(rows, cols, 1.7, 0.02, i).numpy()
+        hdrs.append(ecf8.ecf8_encode(w, rows, cols, lane_syms=64, tile_rows=16).header)
+    n = len(shapes)
+
+    def descs(raw=(False,) * 3, scaled=(0,) * 3):
+        d = (ecf8.GemmGroupDesc * n)()
+        for i in range(n):
+            if raw[i]:
+                d[i].rows, d[i].cols = shapes[i]
+            else:
+                d[i].hdr = ctypes.pointer(hdrs[i])
+            d[i].d_w, d[i].d_x, d[i].d_y, d[i].M = 0x10000 * (i + 1), 0x2000000 + 0x10000 * i, 0x4000000 + 0x10000 * i, Ms[i]
+            if scaled[i]:
+                d[i].d_w_scale = 0x6000000
+                if scaled[i] == 2:
+                    d[i].d_x_scale, d[i].x_scale_cols = 0x7000000, shapes[i][1] // 128
+        return d
+    items, info = (ecf8.GemmGroupItem * n)(), ecf8.GemmGroupInfo()
+    assert ecf8._lib.ecf8_gemm_group_prepare(descs(), n, items, ctypes.byref(info)) == ecf8.OK
+    assert (info.total_work, info.n_items, info.max_M, info.scale_mode, info.raw) == (4 * 2 + 2 * 28 + 10 * 8, 3, 64, 0, 0)
+    first_work = [items[i].opaque[0] for i in range(n)]
+    assert first_work == [0, 8, 8 + 56]
+    assert ecf8._lib.ecf8_gemm_group_prepare(descs(raw=(True,) * 3, scaled=(2,) * 3), n, items, ctypes.byref(info)) == ecf8.OK
+    assert (info.scale_mode, info.raw) == (2, 1)
+    for bad in (descs(raw=(False, True, False)), descs(scaled=(1, 0, 1)), descs(scaled=(1, 2, 1))):
+        assert ecf8._lib.ecf8_gemm_group_prepare(bad, n, items, ctypes.byref(info)) == ecf8.E_ARG
+    d = descs()
+    d[1].M = 65
+    assert ecf8._lib.ecf8_gemm_group_prepare(d, n, items, ctypes.byref(info)) == ecf8.E_ARG
+    d = descs()
+    d[2].d_x += 8
+    assert ecf8._lib.ecf8_gemm_group_prepare(d, n, items, ctypes.byref(info)) == ecf8.E_ALIGN
+    lin = ecf8.ecf8_encode(synth.make_weight(64, 512, 1.7, 0.02, 0).numpy(), 64, 512).header      # not row-tiled
+    d = descs()
+    d[0].hdr = ctypes.pointer(lin)
+    assert ecf8._lib.ecf8_gemm_group_prepare(d, n, items, ctypes.byref(info)) == ecf8.E_ARG
+    assert ecf8._lib.ecf8_gemm_group_prepare(descs(), 0, items, ctypes.byref(info)) == ecf8.E_ARG
