@@ -318,6 +318,11 @@ int ecf8_gemm_fp8_raw_scaled(const void *d_w, uint64_t rows, uint64_t cols, cons
  * writes Y.  No workgroup waits for another.  Same operation, arguments, limits
  * and errors as ecf8_gemm_fp8_scaled, with d_w_scale = d_x_scale = NULL and
  * x_scale_cols = 0 for the unscaled product.
+ *   ecf8_gemm_splitk_plan             HOST: slices and workspace size for (rows, cols, M) on a
+ *                                     device of `compute_units` compute units (0 = the current
+ *                                     device; any other value needs no device); either output
+ *                                     pointer may be NULL.  ECF8_E_ARG for a shape or M the
+ *                                     calls do not take
  *   ecf8_gemm_splitk_slices           slices the calls will use for this shape on the
  *                                     current device: the largest divisor of cols / 256
  *                                     with rows / 16 * slices <= compute units (1 = the
@@ -336,6 +341,8 @@ int ecf8_gemm_fp8_raw_scaled(const void *d_w, uint64_t rows, uint64_t cols, cons
  * that did not run to its end (a device error) leaves the counters undefined:
  * initialise again.
  */
+int ecf8_gemm_splitk_plan(uint64_t rows, uint64_t cols, uint32_t M, uint32_t compute_units,
+                          uint32_t *slices, uint64_t *workspace_bytes);
 uint32_t ecf8_gemm_splitk_slices(uint64_t rows, uint64_t cols);
 uint64_t ecf8_gemm_splitk_workspace_bytes(uint64_t rows, uint64_t cols, uint32_t M);
 int ecf8_gemm_splitk_workspace_init(void *d_workspace, uint64_t workspace_bytes, void *stream);

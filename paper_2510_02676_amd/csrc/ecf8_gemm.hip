@@ -1131,17 +1131,29 @@ int ecf8_gemm_fp8_raw_scaled(const void *d_w, uint64_t rows, uint64_t cols, cons
     return a.xs_cols > 1 ? launch_raw<2>(a, stream) : launch_raw<1>(a, stream);
 }
 
+int ecf8_gemm_splitk_plan(uint64_t rows, uint64_t cols, uint32_t M, uint32_t compute_units, uint32_t *slices,
+                          uint64_t *workspace_bytes_out)
+{
+    if (cols == 0 || cols % 256 || cols > (1u << 20) || rows == 0 || rows % BLOCK_ROWS || M == 0 || M > 64) return ECF8_E_ARG;
+    int cus = (int)compute_units;
+    if (cus == 0) cus = device_cus();
+    if (cus <= 0) return ECF8_E_HIP;
+    const uint32_t sl = pick_slices(rows, cols, cus);
+    if (slices) *slices = sl;
+    if (workspace_bytes_out) *workspace_bytes_out = workspace_bytes(rows, M, sl);
+    return ECF8_OK;
+}
+
 uint32_t ecf8_gemm_splitk_slices(uint64_t rows, uint64_t cols)
 {
-    if (cols == 0 || cols % 256 || rows == 0 || rows % BLOCK_ROWS) return 0;
-    const int cus = device_cus();
-    return cus <= 0 ? 0 : pick_slices(rows, cols, cus);
+    uint32_t sl = 0;
+    return ecf8_gemm_splitk_plan(rows, cols, 1, 0, &sl, nullptr) == ECF8_OK ? sl : 0;
 }
 
 uint64_t ecf8_gemm_splitk_workspace_bytes(uint64_t rows, uint64_t cols, uint32_t M)
 {
-    const uint32_t slices = ecf8_gemm_splitk_slices(rows, cols);
-    return slices == 0 || M == 0 || M > 64 ? 0 : workspace_bytes(rows, M, slices);
+    uint64_t bytes = 0;
+    return ecf8_gemm_splitk_plan(rows, cols, M, 0, nullptr, &bytes) == ECF8_OK ? bytes : 0;
 }
 
 int ecf8_gemm_splitk_workspace_init(void *d_workspace, uint64_t bytes, void *stream)

@@ -105,6 +105,7 @@ _lib.ecf8_gemm_fp8.argtypes = [ctypes.POINTER(Header), _vp, _vp, _u32, _vp, _vp]
 _lib.ecf8_gemm_fp8_raw.argtypes = [_vp, _u64, _u64, _vp, _u32, _vp, _vp]
 _lib.ecf8_gemm_fp8_scaled.argtypes = [ctypes.POINTER(Header), _vp, _vp, _u32, _vp, _vp, _u32, _vp, _vp]
 _lib.ecf8_gemm_fp8_raw_scaled.argtypes = [_vp, _u64, _u64, _vp, _u32, _vp, _vp, _u32, _vp, _vp]
+_lib.ecf8_gemm_splitk_plan.argtypes = [_u64, _u64, _u32, _u32, ctypes.POINTER(_u32), ctypes.POINTER(_u64)]
 _lib.ecf8_gemm_splitk_slices.argtypes = [_u64, _u64]
 _lib.ecf8_gemm_splitk_slices.restype = _u32
 _lib.ecf8_gemm_splitk_workspace_bytes.argtypes = [_u64, _u64, _u32]
@@ -431,6 +432,14 @@ def ecf8_gemm_fp8_raw_scaled(d_w, d_x, w_scale, x_scale=None, d_y=None, stream=N
 def gemm_splitk_slices(rows, cols):
     """Workgroups per block of 16 rows the split-K calls use for this shape on the current device (1 = no split)."""
     return int(_lib.ecf8_gemm_splitk_slices(rows, cols))
+
+
+def gemm_splitk_plan(rows, cols, M, compute_units=0):
+    """(slices, workspace bytes) of the split-K calls for this shape on a device of that many compute units
+    (0 = the current device)."""
+    sl, nb = _u32(), _u64()
+    _check("ecf8_gemm_splitk_plan", _lib.ecf8_gemm_splitk_plan(rows, cols, M, compute_units, ctypes.byref(sl), ctypes.byref(nb)))
+    return int(sl.value), int(nb.value)
 
 
 def gemm_splitk_workspace(rows, cols, M, device, stream=None):

@@ -356,3 +356,22 @@ def test_gemm_group_prepare_is_pure_host_logic():
     d[0].hdr = ctypes.pointer(lin)
     assert ecf8._lib.ecf8_gemm_group_prepare(d, n, items, ctypes.byref(info)) == ecf8.E_ARG
     assert ecf8._lib.ecf8_gemm_group_prepare(descs(), 0, items, ctypes.byref(info)) == ecf8.E_ARG
+
+
+def test_split_k_plan_is_pure_host_logic():
+    """Slices = the largest divisor of cols / 256 with rows / 16 * slices <= compute units; workspace = 4096 bytes
+    of counters + rows / 16 * slices * (1, 2, 4 KiB for M <= 16, 32, 64); nothing when the matrix has blocks enough."""
+    want = {(256, 14336): 14, (576, 7168): 7, (1536, 7168): 2, (1024, 4096): 4, (4096, 4096): 1, (16, 256): 1,
+            (2048, 7168): 2, (32, 512): 2, (48, 5120): 20, (16400, 4096): 1}
+    for (rows, cols), sl in want.items():
+        assert ecf8.gemm_splitk_plan(rows, cols, 1, 256) == (sl, 0 if sl == 1 else 4096 + rows // 16 * sl * 1024), (rows, cols)
+        for s2 in range(sl + 1, cols // 256 + 1):
+            assert (cols // 256) % s2 or rows // 16 * s2 > 256
+    assert ecf8.gemm_splitk_plan(256, 14336, 17, 256)[1] == 4096 + 16 * 14 * 2048
+    assert ecf8.gemm_splitk_plan(256, 14336, 64, 256)[1] == 4096 + 16 * 14 * 4096
+    assert ecf8.gemm_splitk_plan(256, 14336, 64, 64) == (4, 4096 + 16 * 4 * 4096)      # a smaller chip splits less
+    assert ecf8.gemm_splitk_plan(256, 14336, 64, 8)[0] == 1
+    for bad in ((250, 14336, 1), (256, 1000, 1), (256, 14336, 0), (256, 14336, 65), (0, 256, 1)):
+        with pytest.raises(ecf8.Ecf8Error) as e:
+            ecf8.gemm_splitk_plan(*bad, 256)
+        assert e.value.code == ecf8.E_ARG
