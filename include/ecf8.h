@@ -378,6 +378,12 @@ int ecf8_gemm_fp8_raw_splitk(const void *d_w, uint64_t rows, uint64_t cols, cons
  *   ecf8_gemm_fp8_grouped    DEVICE, asynchronous on `stream`; the items may be reused
  *                            for any number of launches while the buffers they
  *                            point to live.
+ * Errors: prepare returns what the single call would return for the first member it
+ * rejects (ECF8_E_ARG, _E_FORMAT, _E_ALIGN) and ECF8_E_ARG for a mixed group; it
+ * writes nothing the caller can use in that case.  The launch checks *info
+ * (ECF8_E_ARG), the alignment of d_items (ECF8_E_ALIGN) and the launch itself
+ * (ECF8_E_HIP); it trusts the items, which only prepare writes.  Outputs of members
+ * are independent: rows of Y beyond a member's M are never written.
  */
 typedef struct ecf8_gemm_group_desc {
     const ecf8_header *hdr;   /* HOST; NULL for an uncompressed matrix              */
