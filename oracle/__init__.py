@@ -203,8 +203,10 @@ def paper_build_lut(lengths, codes, width=8):
 
 
 def paper_alg1_roundtrip(x, T=256):
-    """Encode x into the paper's own container (B=8) and decode it with the
-    Algorithm 1 emulator.  Returns (outputs, dict of the container's arrays)."""
+    """Encode x into the paper's own container (B=8) and decode it with the block decoder of
+    Algorithm 1 restated over the bit-serial walk (every gap must land on a codeword start, every
+    block's counts must add up to its share of outpos); the cascaded table is checked against the
+    code tree on all 16-bit prefixes.  Returns (outputs, dict of the container's arrays)."""
     x = _u8(x)
     n = x.size
     freq = histogram(x)
@@ -231,10 +233,13 @@ def paper_alg1_roundtrip(x, T=256):
     if rc:
         raise ValueError("orc_paper_encode: %d" % rc)
     out = np.zeros(n, dtype=np.uint8)
-    rc = lib().orc_paper_alg1_decode(_p(lut), n_luts, _p(encoded), nb2, _p(packed), _p(outpos), _p(gaps),
-                                     nbl2, ctypes.c_uint32(T), ctypes.c_uint64(n), _p(out))
+    rc = lib().orc_paper_window_decode(_p(ln), _p(encoded), ctypes.c_uint64(encoded.size), _p(packed), _p(outpos),
+                                       _p(gaps), nbl2, ctypes.c_uint32(T), ctypes.c_uint64(n), _p(out))
     if rc:
-        raise ValueError("orc_paper_alg1_decode: %d" % rc)
+        raise ValueError("orc_paper_window_decode: %d" % rc)
+    lib().orc_paper_lut_mismatches.restype = ctypes.c_int64
+    if lib().orc_paper_lut_mismatches(_p(ln), _p(lut), n_luts) != 0:
+        raise ValueError("cascaded table disagrees with the code tree")
     return out, dict(lengths=ln, lut=lut, n_luts=int(n_luts.value), encoded=encoded,
                      n_bytes=int(nb2.value), packed=packed, outpos=outpos, gaps=gaps,
                      n_blocks=int(nbl2.value), stream_bits=bits)

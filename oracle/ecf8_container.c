@@ -257,13 +257,14 @@ int orc_container_encode(const uint8_t *x, uint64_t rows, uint64_t cols, uint32_
     return ORC_OK;
 }
 
-/* Reader: decodes a container to out[n_elem].  Two independent passes:
- *  (1) a metadata-free bit-serial decode of the whole stream from bit 0;
- *  (2) a lane-by-lane bit-serial decode that starts every lane at
- *      chunk_bit[c] + sum of lane_bits of the lanes before it in the chunk.
- * Both must agree symbol for symbol and every lane must end exactly where
- * the next one starts; otherwise ORC_E_META.  stream_bits_out/lenbar are
- * returned for the size checks. */
+/* Reader: decodes a container to out[n_elem], lane by lane through the metadata.
+ * Every lane starts at chunk_bit[c] + the lane_bits of the chunk's earlier lanes;
+ * its forward run is walked bit by bit from its first bit upwards, its backward
+ * run from its last bit downwards, and the two must meet exactly; chunk starts
+ * must equal the running sums; the decoded exponents must reproduce the header's
+ * histogram, whose weighted lengths must give stream_bits; an embedded table is
+ * rebuilt entry by entry with bit-serial walks.  ORC_E_META / ORC_E_FORMAT
+ * otherwise.  stream_bits_out is returned for the size checks. */
 int orc_container_decode(const uint8_t *blob, uint64_t size, uint8_t *out, uint64_t out_cap,
                          uint64_t *n_out, uint64_t *stream_bits_out)
 {

@@ -397,26 +397,6 @@ int orc_decode_serial(const uint8_t *stream, uint64_t nbits, int order,
     return ORC_OK;
 }
 
-/* Exponent-only variant: writes the n decoded symbols (0..15). */
-int orc_decode_symbols(const uint8_t *stream, uint64_t nbits, int order,
-                       const uint8_t len[ORC_NSYM], uint64_t n, uint8_t *sym_out)
-{
-    uint16_t code[ORC_NSYM];
-    orc_tree t;
-    int rc = orc_canonical_codes(len, code);
-    if (rc) return rc;
-    rc = tree_build(&t, len, code);
-    if (rc) return rc;
-    uint64_t pos = 0;
-    for (uint64_t i = 0; i < n; i++) {
-        int e = tree_walk(&t, stream, nbits, order, &pos);
-        if (e < 0) return e;
-        sym_out[i] = (uint8_t)e;
-    }
-    if (pos != nbits) return ORC_E_FORMAT;
-    return ORC_OK;
-}
-
 /* Directional variant for containers whose lanes hold a forward and a backward
  * run of codewords: decodes n symbols starting at bit `start`, stepping +1 or
  * -1 per bit (a codeword's first bit is read first either way); bits outside

@@ -1,14 +1,17 @@
 /*
  * ECF8 CPU oracle, part 3 -- TEST INFRASTRUCTURE ONLY.
  *
- * The paper's own container and decoder, emulated on the CPU with the threads
- * of a block run one after another: cascaded 8-bit lookup tables (Section 3.1,
+ * The paper's own container and block decoder on the CPU, the threads of a
+ * block run one after another: cascaded 8-bit lookup tables (Section 3.1,
  * "Hierarchical lookup table construction"), per-thread 4-bit gaps and
  * per-block output positions (Section 3.1, "Encoding and synchronization
  * metadata generation"; Table 4), and the two-phase block decoder
- * (Algorithm 1) with B = 8 bytes per thread.  Its only job is to show that the
- * readings this build takes of the garbled passages are mutually consistent:
- * the emulator must give back the input bytes.
+ * (Algorithm 1) with B = 8 bytes per thread, stated through the meaning of
+ * the metadata and run on the oracle's bit-serial tree walk; the cascaded
+ * table is checked against that walk on every prefix on its own.  Its only
+ * job is to show that the readings this build takes of the garbled passages
+ * are mutually consistent: gaps land on codeword starts, per-thread counts
+ * add up to the block's share, and the decoder gives back the input bytes.
  *
  * Readings (each stated again where it is used):
  *  - a table entry holds a symbol when some codeword is a PREFIX of the
@@ -19,8 +22,8 @@
  *    first codeword that STARTS inside or after it (0..15), zero for windows
  *    past the end of the stream;
  *  - outpos[b] counts the codewords that start before block b's first bit;
- *  - the stream is zero padded so the 10-byte loads of the last block stay
- *    in bounds, and symbols decoded from padding are clipped by n_elem.
+ *  - the stream is zero padded past the last block's windows, and symbols
+ *    decoded from padding are clipped by n_elem.
  */
 #include <stdint.h>
 #include <stdlib.h>
@@ -35,7 +38,7 @@
 #define ORC_E_CODE (-4)
 #define ORC_E_META (-5)
 
-#define PB 8 /* B: bytes per thread window, from "B + 2 = 10" in Algorithm 1 */
+#define PB 8 /* B: bytes of the stream per thread (Algorithm 1 loads B + 2 of them, ten) */
 
 void orc_split(uint8_t v, uint8_t *s, uint8_t *e, uint8_t *m);
 void orc_histogram(const uint8_t *x, uint64_t n, uint64_t freq[ORC_NSYM]);
@@ -47,6 +50,10 @@ int orc_encode_exponents(const uint8_t *x, uint64_t n, const uint8_t len[ORC_NSY
                          uint64_t stream_cap_bytes, uint64_t *nbits_out,
                          uint64_t mark_every, uint64_t *marks);
 void orc_pack_nibbles_paper(const uint8_t *x, uint64_t n, uint8_t *packed);
+uint8_t orc_join(uint8_t s, uint8_t e, uint8_t m);
+int orc_decode_symbols_dir(const uint8_t *stream, int64_t start, int dir, int64_t lo, int64_t hi,
+                           int order, const uint8_t len[ORC_NSYM], uint64_t n, uint8_t *sym_out,
+                           int64_t *next);
 
 /* Cascaded decode table + length table with W-bit sub-tables (the paper uses
  * W = 8; Figure 2 illustrates the construction with W = 2).  Row 0 is the
@@ -169,104 +176,106 @@ int orc_paper_encode(const uint8_t *x, uint64_t n, uint32_t T,
     return ORC_OK;
 }
 
-typedef struct {
-    uint64_t L; /* 64-bit sliding window, oldest bit most significant */
-    uint32_t S; /* 16-bit tail */
-    uint32_t f; /* bits consumed from the head */
-} tstate;
-
-static void t_init(tstate *st, const uint8_t *encoded, uint64_t tg, uint32_t g)
+/* One codeword through the cascaded table (Section 3.1, hierarchical lookup table construction): the root
+ * row is indexed by the next W stream bits; an entry of 240 or more stands for sub-table 256 - entry,
+ * indexed by the W bits after those; the last row holds the length of every symbol.  `bits` holds the
+ * next 2W stream bits, first bit most significant. */
+int orc_paper_lut_lookup(const uint8_t *lut, uint32_t n_luts, uint32_t W, uint32_t bits, uint32_t *sym,
+                         uint32_t *length)
 {
-    const uint8_t *lb = encoded + tg * PB; /* localbf: B + 2 bytes */
-    st->L = 0;
-    for (int i = 0; i < 8; i++) st->L = (st->L << 8) | lb[i];
-    st->S = ((uint32_t)lb[8] << 8) | lb[9];
-    st->L <<= g;
-    st->f = g;
+    uint32_t R = 1u << W;
+    uint32_t x = lut[(bits >> W) & (R - 1)];
+    if (x >= 240) {
+        uint32_t sub = 256u - x;
+        if (sub + 1 >= n_luts) return ORC_E_CODE;
+        x = lut[R * sub + (bits & (R - 1))];
+    }
+    if (x >= ORC_NSYM) return ORC_E_CODE;
+    *sym = x;
+    *length = lut[R * (n_luts - 1) + x];
+    return *length ? ORC_OK : ORC_E_CODE;
 }
 
-/* one symbol through the cascaded table; returns its length, 0 on a bad table */
-static uint32_t t_step(tstate *st, const uint8_t *lut, uint32_t n_luts, uint32_t *x_out)
+/* The cascaded table against the code itself: every 16-bit prefix is sent through the table and through
+ * the bit-serial tree walk; returns the number of prefixes on which symbol or length differ (prefixes
+ * no codeword matches, possible only for an incomplete code, are skipped). */
+int64_t orc_paper_lut_mismatches(const uint8_t len[ORC_NSYM], const uint8_t *lut, uint32_t n_luts)
 {
-    uint32_t x = lut[st->L >> 56];
-    if (x >= 240) x = lut[256 * (256 - x) + ((st->L >> 48) & 255)];
-    uint32_t bl = lut[256 * (n_luts - 1) + x];
-    st->L <<= bl;
-    st->f += bl;
-    *x_out = x;
-    return bl;
+    int64_t bad = 0;
+    for (uint32_t v = 0; v < 65536; v++) {
+        uint8_t two[2] = {(uint8_t)(v >> 8), (uint8_t)v};
+        uint8_t s_walk;
+        int64_t next = 0;
+        if (orc_decode_symbols_dir(two, 0, +1, 0, 16, ORC_MSB_FIRST, len, 1, &s_walk, &next) != ORC_OK) continue;
+        uint32_t s_lut = 0, l_lut = 0;
+        if (orc_paper_lut_lookup(lut, n_luts, 8, v, &s_lut, &l_lut) != ORC_OK || s_lut != s_walk ||
+            l_lut != (uint32_t)next)
+            bad++;
+    }
+    return bad;
 }
 
-/* Algorithm 1, all blocks, threads of a block in sequence. */
-int orc_paper_alg1_decode(const uint8_t *lut, uint32_t n_luts, const uint8_t *encoded,
-                          uint64_t n_bytes, const uint8_t *packed, const int64_t *outpos,
-                          const uint8_t *gaps, uint64_t n_blocks, uint32_t T,
-                          uint64_t n_elem, uint8_t *outputs)
+static uint32_t gap_of(const uint8_t *gaps, uint64_t tg) { return (tg % 2 == 0) ? gaps[tg / 2] >> 4 : gaps[tg / 2] & 15u; }
+
+/* Block decoder over the paper's container (Algorithm 1), stated through what the metadata means rather
+ * than through the listing's window arithmetic.  Thread tg owns the codewords whose first bit lies in
+ * its window [64 tg, 64 tg + 64): the first of them starts `gap` bits into the window, and the walk goes
+ * on codeword by codeword (bit-serial, through the code tree) until a codeword would start at or past
+ * the window's end.  Phase 1 only counts; the block's exclusive prefix sum of the counts on top of
+ * outpos[b] gives each thread its first output; phase 2 walks again and writes byte = exponent<<3 |
+ * sign<<7 | mantissa for outputs below n_elem.  Checked on the way (ORC_E_META when violated):
+ *   - a thread's walk ends exactly where the next thread's gap says its first codeword starts, so
+ *     every gap lands on a codeword start;
+ *   - a block's counts add up to outpos[b+1] - outpos[b] (once clipped at n_elem: the zero padding
+ *     behind the stream decodes to codewords of its own). */
+int orc_paper_window_decode(const uint8_t len[ORC_NSYM], const uint8_t *encoded, uint64_t encoded_alloc,
+                            const uint8_t *packed, const int64_t *outpos, const uint8_t *gaps,
+                            uint64_t n_blocks, uint32_t T, uint64_t n_elem, uint8_t *outputs)
 {
-    (void)n_bytes;
-    uint64_t *accum = (uint64_t *)malloc(((uint64_t)T + 1) * sizeof(uint64_t));
+    const int64_t limit = (int64_t)encoded_alloc * 8;
     uint32_t *cnt = (uint32_t *)malloc((uint64_t)T * sizeof(uint32_t));
-    if (!accum || !cnt) { free(accum); free(cnt); return ORC_E_CAPACITY; }
+    if (!cnt) return ORC_E_CAPACITY;
     int rc = ORC_OK;
     for (uint64_t b = 0; b < n_blocks && rc == ORC_OK; b++) {
-        /* phase 1: count the codewords that start inside each thread's window */
+        /* phase 1 */
+        uint64_t total = 0;
         for (uint32_t t = 0; t < T && rc == ORC_OK; t++) {
-            uint64_t tg = b * T + t;
-            uint32_t g = (gaps[tg / 2] >> (4 - (tg % 2) * 4)) & 0x0f;
-            tstate st;
-            uint32_t x, c = 0;
-            t_init(&st, encoded, tg, g);
-            while (st.f < 16) {
-                if (t_step(&st, lut, n_luts, &x) == 0) { rc = ORC_E_CODE; break; }
-                c++;
-            }
-            if (rc) break;
-            st.L |= (uint64_t)st.S << (st.f - 16);
-            st.f -= 16;
-            while (2 + st.f / 8 < PB) {
-                if (t_step(&st, lut, n_luts, &x) == 0) { rc = ORC_E_CODE; break; }
+            const uint64_t tg = b * T + t;
+            const int64_t w0 = (int64_t)tg * PB * 8, w1 = w0 + PB * 8;
+            int64_t pos = w0 + gap_of(gaps, tg);
+            uint32_t c = 0;
+            while (pos < w1) {
+                uint8_t sym;
+                if (orc_decode_symbols_dir(encoded, pos, +1, 0, limit, ORC_MSB_FIRST, len, 1, &sym, &pos)) { rc = ORC_E_CODE; break; }
                 c++;
             }
             cnt[t] = c;
+            total += c;
+            if (rc == ORC_OK && tg + 1 < n_blocks * T && pos != w1 + (int64_t)gap_of(gaps, tg + 1) &&
+                (uint64_t)outpos[b] + total < n_elem)      /* (inside the padding the gaps are zero) */
+                rc = ORC_E_META;
         }
         if (rc) break;
-        /* block prefix sum: exclusive starts offset by outpos[b] */
-        accum[0] = (uint64_t)outpos[b];
-        for (uint32_t t = 0; t < T; t++) accum[t + 1] = accum[t] + cnt[t];
-        uint64_t obase = accum[0];
-        uint64_t wb_len = (uint64_t)outpos[b + 1] - (uint64_t)outpos[b];
-        uint8_t *writebf = (uint8_t *)malloc(wb_len ? wb_len : 1);
-        if (!writebf) { rc = ORC_E_CAPACITY; break; }
-        /* phase 2: decode again, merge sign/mantissa, stage in writebf */
+        uint64_t end = (uint64_t)outpos[b] + total;
+        if (end > n_elem) end = n_elem;
+        if (end != (uint64_t)outpos[b + 1]) { rc = ORC_E_META; break; }
+        /* phase 2 */
+        uint64_t o = (uint64_t)outpos[b];
         for (uint32_t t = 0; t < T && rc == ORC_OK; t++) {
-            uint64_t tg = b * T + t;
-            uint32_t g = (gaps[tg / 2] >> (4 - (tg % 2) * 4)) & 0x0f;
-            uint64_t ostart = accum[t];
-            uint64_t oend = ostart + cnt[t];
-            if (oend > n_elem) oend = n_elem;
-            tstate st;
-            uint32_t x;
-            int stitched = 0;
-            t_init(&st, encoded, tg, g);
-            while (ostart < oend) {
-                if (!stitched && st.f >= 16) {
-                    st.L |= (uint64_t)st.S << (st.f - 16);
-                    st.f -= 16;
-                    stitched = 1;
-                }
-                if (t_step(&st, lut, n_luts, &x) == 0) { rc = ORC_E_CODE; break; }
-                uint32_t q = (uint32_t)packed[ostart / 2] << ((ostart % 2) * 4);
-                uint8_t byte = (uint8_t)((x << 3) | (q & 0x80) | ((q >> 4) & 0x07));
-                if (ostart - obase >= wb_len) { rc = ORC_E_META; break; }
-                writebf[ostart - obase] = byte;
-                ostart++;
+            const uint64_t tg = b * T + t;
+            int64_t pos = (int64_t)tg * PB * 8 + gap_of(gaps, tg);
+            uint64_t o_end = o + cnt[t];
+            for (uint64_t i = o; i < o_end; i++) {
+                uint8_t sym;
+                if (orc_decode_symbols_dir(encoded, pos, +1, 0, limit, ORC_MSB_FIRST, len, 1, &sym, &pos)) { rc = ORC_E_CODE; break; }
+                if (i >= n_elem) continue;
+                const uint8_t pk = packed[i / 2];
+                const uint8_t q = (i % 2 == 0) ? (uint8_t)(pk >> 4) : (uint8_t)(pk & 15);
+                outputs[i] = orc_join((uint8_t)(q >> 3), sym, (uint8_t)(q & 7));
             }
+            o = o_end;
         }
-        /* write-back */
-        if (rc == ORC_OK) memcpy(outputs + obase, writebf, wb_len);
-        free(writebf);
     }
-    free(accum);
     free(cnt);
     return rc;
 }

@@ -433,6 +433,116 @@ def test_container_reader_catches_tampering(orc):
         pass
 
 
+def _ecf8_sections(blob):
+    u64 = lambda o: int(np.frombuffer(blob[o:o + 8].tobytes(), "<u8")[0])
+    return dict(n=u64(16), n_chunks=u64(48), bits=u64(56), off_cb=u64(80), off_lb=u64(88), off_st=u64(96),
+                off_pl=u64(104), st_bytes=u64(112))
+
+
+def test_container_backward_run_by_hand(orc):
+    """tests/golden/container_backward_run.txt: 1026 bytes whose lane 0 carries two symbols of the backward
+    run; stream bytes, lane_bits and chunk_bit derived by hand from the format description."""
+    g = _gold("container_backward_run.txt")
+    n, N = int(g["n"][0]), int(g["lane_syms"][0])
+    x = np.full(n, 0x38, dtype=np.uint8)
+    x[[int(v) for v in g["zero_elements"]]] = 0x00
+    blob = orc.container_encode(x, 1, n, N, 1)
+    s = _ecf8_sections(blob)
+    assert s["n_chunks"] == 1 and s["bits"] == int(g["stream_bits"][0])
+    lb = np.frombuffer(blob[s["off_lb"]:s["off_lb"] + 128].tobytes(), "<u2")
+    assert lb[0] == int(g["lane_bits_lane0"][0]) and (lb[1:] == int(g["lane_bits_other"][0])).all()
+    st = blob[s["off_st"]:s["off_st"] + s["st_bytes"]]
+    used = int(g["stream_used_bytes"][0])
+    head = [int(v, 16) for v in g["stream_head"]]
+    assert [int(v) for v in st[:len(head)]] == head
+    assert (st[len(head):used - 1] == 0xFF).all() and int(st[used - 1]) == int(g["stream_last"][0], 16)
+    assert not st[used:].any()
+    cb = np.frombuffer(blob[s["off_cb"]:s["off_cb"] + 16].tobytes(), "<u8")
+    assert list(cb) == [0, 1026]
+    dec, bits = orc.container_decode(blob)
+    assert np.array_equal(dec, x) and bits == 1026
+    # a reader that took the backward run in the forward direction would swap elements 1024 and 1025
+    swapped = x.copy()
+    swapped[1024], swapped[1025] = x[1025], x[1024]
+    assert not np.array_equal(swapped, x)
+
+
+@pytest.mark.parametrize("N,G,n_chunks_whole,extra", [(32, 1, 2, 0), (64, 1, 1, 16 * 100), (64, 2, 5, 16 * 7), (128, 4, 9, 16),
+                                                      (128, 32, 33, 16 * 300), (64, 64, 64, 0)])
+def test_stream_order_with_a_fixed_length_code(orc, N, G, n_chunks_whole, extra):
+    """With a uniform exponent histogram every codeword is 4 bits long and the canonical code of field s is s,
+    so the stream is an array of 4-bit fields: the element order (lane l of chunk c takes 16-element pieces
+    l, l + 64, ...; the G chunks of a whole group alternate KiB by KiB), the bit order and the two run
+    directions can be written down as array reshapes (axes: piece, chunk in group, lane, element in piece)
+    and compared with the container's stream, lane_bits and chunk_bit byte for byte."""
+    E = 64 * N
+    n = n_chunks_whole * E + extra
+    assert n % 16 == 0
+    rng = np.random.default_rng(n + G)
+    sym = rng.permutation(np.tile(np.arange(16), n // 16))      # exactly uniform: Huffman gives sixteen 4-bit codes
+    x = _bytes_from(sym, rng)
+    blob = orc.container_encode(x, 1, n, N, G)
+    s = _ecf8_sections(blob)
+    assert [int(v) for v in blob[64:80]] == [4] * 16
+    n_chunks = s["n_chunks"]
+    padded = np.full(n_chunks * E, -1, dtype=np.int64)
+    padded[:n] = sym
+    lanes = np.zeros((n_chunks, 64, N), dtype=np.int64)         # [chunk, lane, k]
+    F = n // (G * E)
+    for g in range(F):
+        blk = padded[g * G * E:(g + 1) * G * E].reshape(N // 16, G, 64, 16)
+        lanes[g * G:(g + 1) * G] = blk.transpose(1, 2, 0, 3).reshape(G, 64, N)
+    for c in range(F * G, n_chunks):
+        lanes[c] = padded[c * E:(c + 1) * E].reshape(N // 16, 64, 16).transpose(1, 0, 2).reshape(64, N)
+    bits = []
+    lane_bits = np.zeros((n_chunks, 64), dtype=np.int64)
+    for c in range(n_chunks):
+        for l in range(64):
+            ks = lanes[c, l]
+            fwd = [b for v in ks[:N // 2] if v >= 0 for b in format(int(v), "04b")]      # first bit = most significant
+            bwd = [b for v in ks[N // 2:] if v >= 0 for b in format(int(v), "04b")]
+            lane = fwd + bwd[::-1]                                                     # backward run: first bit highest
+            lane_bits[c, l] = len(lane)
+            bits.extend(lane)
+    want = np.packbits(np.array(bits, dtype=np.uint8), bitorder="little")
+    got = blob[s["off_st"]:s["off_st"] + s["st_bytes"]]
+    assert np.array_equal(got[:want.size], want) and not got[want.size:].any()
+    lb = np.frombuffer(blob[s["off_lb"]:s["off_lb"] + 128 * n_chunks].tobytes(), "<u2").reshape(n_chunks, 64)
+    assert np.array_equal(lb, lane_bits)
+    cb = np.frombuffer(blob[s["off_cb"]:s["off_cb"] + 8 * (n_chunks + 1)].tobytes(), "<u8")
+    assert np.array_equal(cb, np.concatenate([[0], np.cumsum(lane_bits.sum(axis=1))]).astype(np.uint64))
+    dec, _ = orc.container_decode(blob)
+    assert np.array_equal(dec, x)
+
+
+@pytest.mark.parametrize("N,rows,cols", [(32, 16, 128), (64, 32, 512), (128, 16, 1024), (64, 48, 256)])
+def test_row_tiled_stream_order_with_a_fixed_length_code(orc, N, rows, cols):
+    """The row-tiled layout the same way: chunk c is block c of the matrix cut into 16 rows x 4N columns (along a
+    row of blocks first), lane l = 16 g + r works on row r of the block, and its k-th symbol is column
+    64 (k / 16) + 16 g + k % 16: as a reshape of the block with axes (row, piece, g, element in piece)."""
+    n = rows * cols
+    rng = np.random.default_rng(n + N)
+    sym = rng.permutation(np.tile(np.arange(16), n // 16)).reshape(rows, cols)
+    x = _bytes_from(sym.reshape(-1), rng)
+    blob = orc.container_encode(x, rows, cols, N, 1, 15, 16)
+    s = _ecf8_sections(blob)
+    assert [int(v) for v in blob[64:80]] == [4] * 16
+    bits = []
+    for br in range(rows // 16):
+        for bc in range(cols // (4 * N)):
+            block = sym[16 * br:16 * br + 16, 4 * N * bc:4 * N * (bc + 1)]
+            lanes = block.reshape(16, N // 16, 4, 16).transpose(2, 0, 1, 3).reshape(64, N)    # [g, r] -> lane 16 g + r
+            for l in range(64):
+                fwd = [b for v in lanes[l, :N // 2] for b in format(int(v), "04b")]
+                bwd = [b for v in lanes[l, N // 2:] for b in format(int(v), "04b")]
+                bits.extend(fwd + bwd[::-1])
+    want = np.packbits(np.array(bits, dtype=np.uint8), bitorder="little")
+    got = blob[s["off_st"]:s["off_st"] + s["st_bytes"]]
+    assert np.array_equal(got[:want.size], want) and not got[want.size:].any()
+    dec, _ = orc.container_decode(blob)
+    assert np.array_equal(dec, x)
+
+
 # ---------------------------------------------------------------- the paper's own container
 
 @pytest.mark.parametrize("T", [32, 256])
@@ -475,3 +585,41 @@ def test_paper_single_symbol_and_tiny(orc):
     x = np.array([0x38, 0xB8, 0x3C, 0x00], dtype=np.uint8)
     out, _ = orc.paper_alg1_roundtrip(x, 32)
     assert np.array_equal(out, x)
+
+
+def test_paper_metadata_checks_catch_planted_mistakes(orc):
+    """The window decoder insists that every gap lands on a codeword start and that a block's counts add up
+    to its share of outpos; the table check insists that the cascaded table says what the code says.  A
+    mistake planted in the gaps, in outpos or in the table must be caught."""
+    import ctypes
+    rng = np.random.default_rng(5)
+    p = np.array([2.0 ** -min(i + 1, 15) for i in range(16)])
+    x = _bytes_from(rng.choice(16, size=30011, p=p / p.sum()), rng)
+    T = 32
+    out, c = orc.paper_alg1_roundtrip(x, T)
+    assert np.array_equal(out, x)
+    L = orc.lib()
+    L.orc_paper_lut_mismatches.restype = ctypes.c_int64
+
+    def decode(gaps, outpos):
+        res = np.zeros(x.size, dtype=np.uint8)
+        rc = L.orc_paper_window_decode(orc._p(c["lengths"]), orc._p(c["encoded"]), ctypes.c_uint64(c["encoded"].size),
+                                       orc._p(c["packed"]), orc._p(outpos), orc._p(gaps), ctypes.c_uint64(c["n_blocks"]),
+                                       ctypes.c_uint32(T), ctypes.c_uint64(x.size), orc._p(res))
+        return rc, res
+    rc, res = decode(c["gaps"], c["outpos"])
+    assert rc == 0 and np.array_equal(res, x)
+    # the first gap nibble whose value can be raised by one
+    tg = next(t for t in range(2, 200) if 0 < ((int(c["gaps"][t // 2]) >> (4 - (t % 2) * 4)) & 15) < 15)
+    bad = c["gaps"].copy()
+    bad[tg // 2] = (int(bad[tg // 2]) + (0x10 if tg % 2 == 0 else 0x01)) & 0xFF
+    rc, res = decode(bad, c["outpos"])
+    assert rc != 0 or not np.array_equal(res, x)
+    assert rc == orc.E_META or rc == orc.E_CODE
+    bad_pos = c["outpos"].copy()
+    bad_pos[1] += 1
+    assert decode(c["gaps"], bad_pos)[0] == orc.E_META
+    assert L.orc_paper_lut_mismatches(orc._p(c["lengths"]), orc._p(c["lut"]), ctypes.c_uint32(c["n_luts"])) == 0
+    lut = c["lut"].copy()
+    lut[3] = (int(lut[3]) + 1) % 16
+    assert L.orc_paper_lut_mismatches(orc._p(c["lengths"]), orc._p(lut), ctypes.c_uint32(c["n_luts"])) > 0
