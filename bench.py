@@ -203,6 +203,24 @@ def bench_config4(a):
             t_vendor = None
         tf = timeit(lambda: ecf8.ecf8_gemm_fp8(h, d_blob, x, y), a.steps, a.warmup)
         tr = timeit(lambda: ecf8.ecf8_gemm_fp8_raw(w, x, y2), a.steps, a.warmup)
+        # the same products on the F16 matrix cores (exact products, fp32 sums), and how far either kind of call
+        # is from the fp64 product of the dequantised operands, as a fraction of sum |x w| per output
+        # (the configuration asks for 1e-5; the reference here is torch's fp64 matmul on the device, the
+        # oracle's own comparison is in tests/test_gpu_gemm.py)
+        ye, ye2 = torch.empty_like(y), torch.empty_like(y)
+        ecf8.ecf8_gemm_fp8_exact(h, d_blob, x, d_y=ye)
+        ecf8.ecf8_gemm_fp8_raw_exact(w, x, d_y=ye2)
+        ecf8.ecf8_gemm_fp8(h, d_blob, x, y)
+        torch.cuda.synchronize()
+        if not torch.equal(ye, ye2):
+            raise SystemExit("exact fused GEMM differs from its twin on uncompressed weights at M=%d" % M)
+        xd, wd_ = x.view(torch.float8_e4m3fn).double(), w.view(torch.float8_e4m3fn).double()
+        yref, mag = xd @ wd_.t(), xd.abs() @ wd_.abs().t()
+        err_fp8 = float(((y.double() - yref).abs() / mag).max())
+        err_exact = float(((ye.double() - yref).abs() / mag).max())
+        del xd, wd_, yref, mag
+        te = timeit(lambda: ecf8.ecf8_gemm_fp8_exact(h, d_blob, x, d_y=ye), a.steps, a.warmup)
+        ter = timeit(lambda: ecf8.ecf8_gemm_fp8_raw_exact(w, x, d_y=ye2), a.steps, a.warmup)
         t2 = timeit(two, a.steps, a.warmup)
         # with one scale per 128 x 128 block of W and per row of X
         ws = torch.rand((spec["rows"] // 128, spec["cols"] // 128), device="cuda:0") + 0.5
@@ -223,6 +241,10 @@ def bench_config4(a):
             raise SystemExit("group-scaled fused GEMM differs from its twin on uncompressed weights at M=%d" % M)
         tfg = timeit(lambda: ecf8.ecf8_gemm_fp8_scaled(h, d_blob, x, ws, xg, y), a.steps, a.warmup)
         res["M=%d" % M] = {"fused_us": round(tf * 1e6, 2), "raw_fp8_gemm_us": round(tr * 1e6, 2),
+                           "fused_exact_us": round(te * 1e6, 2), "raw_exact_us": round(ter * 1e6, 2),
+                           "max_err_over_sum_abs_fp8_core": float("%.3g" % err_fp8),
+                           "max_err_over_sum_abs_exact": float("%.3g" % err_exact),
+                           "meets_1e-5": {"fp8_core": err_fp8 <= 1e-5, "exact": err_exact <= 1e-5},
                            "fused_block_scaled_us": round(tfs * 1e6, 2), "raw_block_scaled_us": round(trs * 1e6, 2),
                            "fused_block_and_group_scaled_us": round(tfg * 1e6, 2),
                            "decode_then_gemm_us": round(t2 * 1e6, 2),

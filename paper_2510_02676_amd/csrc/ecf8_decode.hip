@@ -278,7 +278,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
                                 uint32_t ostride) {
             // LDS bit addresses, kept one bit off as quad_step2 wants them: bpA = the forward
             // run's next codeword - 1; bpB = one past the backward run's next codeword - 31
-            uint32_t bpA = first_bit - 1;   // oversize chunk in the loop: may point past LDS, reads return 0
+            uint32_t bpA = first_bit - 1;
             uint32_t bpB = bpA + lb - 30;
             // PAIRFIT: the chunk's pieces are kept in registers and stored in one burst at
             // its end.  Together with the interleaved layout the workgroup's waves then
@@ -366,7 +366,9 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
                     const uint32_t at = __hip_atomic_fetch_add(s_oversize, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                     if (at < (uint32_t)C::LIST_MAX) s_list[at] = (uint32_t)(cg - c);
                 }
-                decode_store(stage_off * 8 + bit_in, m_cur.lb, pl, out_c, ostride);
+                // a chunk whose span was not staged decodes stale bits (redone after the loop): its runs are
+                // pinned to the start of the wave's stage, so that every window stays inside this kernel's LDS
+                decode_store(stage_off * 8 + (staged ? bit_in : 64u), staged ? m_cur.lb : 0u, pl, out_c, ostride);
 
                 if (!has_next) break;
                 m_cur = m_next;
@@ -426,7 +428,11 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
         // Symbol pass, with windows and nibbles read straight from HBM: the ragged last chunk of
         // the tensor (and everything oversize when the list above did not apply).
         if (scan_all) {
+            // The chunks redone here were stored (as garbage) by whichever wave drew them in the loop, not
+            // necessarily by the wave that redoes them: every wave's loop stores are complete (fence)
+            // before any wave issues a store of this pass (barrier; scan_all is uniform).
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            __syncthreads();
             for (uint64_t cg2 = c + wave; cg2 < seg_end; cg2 += WAVES) {
                 const uint64_t cl = cg2 - first_chunk;
                 Meta m = load_meta(cl);
