@@ -374,6 +374,22 @@ int ecf8_gemm_fp8_raw_splitk(const void *d_w, uint64_t rows, uint64_t cols, cons
                              float *d_y, void *d_workspace, uint64_t workspace_bytes, void *stream);
 
 /*
+ * ecf8_gemm_fp8_splitk_static: ecf8_gemm_fp8_splitk for callers that cannot provide or
+ * allocate a workspace (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc).  Same operation, arguments, results (bit for bit) and errors, without
+ * the workspace arguments: counters and partial sums live in an array inside the library's
+ * device code, 4096 + 256 * 4096 bytes = 1 052 672 bytes per GPU, held until the process
+ * ends.  ECF8_E_CAPACITY when the shape would need more (only on devices of more than 256
+ * compute units).  The call allocates nothing and synchronises nothing.  All calls on one
+ * GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two
+ * threads) race, issue them one after the other.  The first call on a GPU also clears the
+ * counters with a small kernel on `stream`; every completed call leaves them at zero.
+ */
+int ecf8_gemm_fp8_splitk_static(const ecf8_header *hdr, const void *d_blob, const void *d_x, uint32_t M,
+                                const float *d_w_scale, const float *d_x_scale, uint32_t x_scale_cols,
+                                float *d_y, void *stream);
+
+/*
  * A group of small products in ONE launch, each with its own W, X, M and Y: the
  * experts that a batch of tokens is routed to in a mixture-of-experts layer (the
  * largest model of the paper's Table 1 is one).  A launch per matrix is bound by

@@ -35,6 +35,37 @@
 // all of them.
 #include "ecf8_gemm_kernels.h"
 
+namespace {
+
+// Split K without a caller workspace (ecf8_gemm_fp8_splitk_static): the arrival counters and partial sums
+// live in this array, one copy per GPU, held until the process ends.  Size: the counters plus the largest
+// workspace any shape can ask for on a device of up to 256 compute units (blocks x slices <= compute
+// units, four tiles of 16 x 16 fp32 at M = 64).  Zero when the module is loaded, and every completed call
+// leaves the counters at zero.
+constexpr uint64_t STATIC_WS_BYTES = CTR_BYTES + 256ull * 4 * 1024;
+static __device__ __align__(256) uint8_t scratch[STATIC_WS_BYTES];
+
+// Device address of `scratch` on the current device (the array's name is only a host-side handle), looked
+// up once per device; *first tells the caller that this device's copy has not been used yet.
+void *static_scratch(bool *first)
+{
+    static std::mutex m;
+    static void *ptr[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    std::lock_guard<std::mutex> lk(m);
+    *first = false;
+    if (!ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+        ptr[dev] = p;
+        *first = true;
+    }
+    return ptr[dev];
+}
+
+} // namespace
+
 extern "C" {
 
 int ecf8_gemm_fp8(const ecf8_header *h, const void *d_blob, const void *d_x, uint32_t M, float *d_y, void *stream)
@@ -116,6 +147,26 @@ int ecf8_gemm_fp8_splitk(const ecf8_header *h, const void *d_blob, const void *d
     GArgs a;
     const int rc = fused_args(h, d_blob, d_x, M, d_y, &a);
     return rc ? rc : run_split<false>(a, d_w_scale, d_x_scale, x_scale_cols, d_workspace, workspace_bytes_, stream);
+}
+
+int ecf8_gemm_fp8_splitk_static(const ecf8_header *h, const void *d_blob, const void *d_x, uint32_t M, const float *d_w_scale,
+                                const float *d_x_scale, uint32_t x_scale_cols, float *d_y, void *stream)
+{
+    GArgs a;
+    const int rc = fused_args(h, d_blob, d_x, M, d_y, &a);
+    if (rc) return rc;
+    const int cus = device_cus();
+    if (cus <= 0) return ECF8_E_HIP;
+    if (workspace_bytes(a.rows, M, pick_slices(a.rows, a.K, cus)) > STATIC_WS_BYTES) return ECF8_E_CAPACITY;
+    bool first = false;
+    void *ws = static_scratch(&first);
+    if (!ws) return ECF8_E_HIP;
+    if (first) {      // counters start at zero (a fill kernel, not a memset: the call may be under graph capture)
+        hipLaunchKernelGGL(gemm_fill_zero_kernel, dim3((unsigned)(CTR_BYTES / 4 / 256)), dim3(256), 0, (hipStream_t)stream,
+                           (uint64_t)(uintptr_t)ws, CTR_BYTES / 4);
+        if (hipGetLastError() != hipSuccess) return ECF8_E_HIP;
+    }
+    return run_split<false>(a, d_w_scale, d_x_scale, x_scale_cols, ws, STATIC_WS_BYTES, stream);
 }
 
 int ecf8_gemm_fp8_raw_splitk(const void *d_w, uint64_t rows, uint64_t cols, const void *d_x, uint32_t M,

@@ -113,6 +113,7 @@ _lib.ecf8_gemm_splitk_workspace_bytes.restype = _u64
 _lib.ecf8_gemm_splitk_workspace_init.argtypes = [_vp, _u64, _vp]
 _lib.ecf8_gemm_fp8_splitk.argtypes = [ctypes.POINTER(Header), _vp, _vp, _u32, _vp, _vp, _u32, _vp, _vp, _u64, _vp]
 _lib.ecf8_gemm_fp8_raw_splitk.argtypes = [_vp, _u64, _u64, _vp, _u32, _vp, _vp, _u32, _vp, _vp, _u64, _vp]
+_lib.ecf8_gemm_fp8_splitk_static.argtypes = [ctypes.POINTER(Header), _vp, _vp, _u32, _vp, _vp, _u32, _vp, _vp]
 _lib.ecf8_gemm_fp8_exact.argtypes = [ctypes.POINTER(Header), _vp, _vp, _u32, _vp, _vp, _u32, _vp, _vp]
 _lib.ecf8_gemm_fp8_raw_exact.argtypes = [_vp, _u64, _u64, _vp, _u32, _vp, _vp, _u32, _vp, _vp]
 _lib.ecf8_gemm_group_prepare.argtypes = [ctypes.POINTER(GemmGroupDesc), _u32, ctypes.POINTER(GemmGroupItem),
@@ -482,6 +483,17 @@ def ecf8_gemm_fp8_raw_splitk(d_w, d_x, workspace, w_scale=None, x_scale=None, d_
     _check("ecf8_gemm_fp8_raw_splitk", _lib.ecf8_gemm_fp8_raw_splitk(d_w.data_ptr(), rows, cols, d_x.data_ptr(), M, ws, xs, xc,
                                                                      d_y.data_ptr(), workspace.data_ptr(), workspace.numel(),
                                                                      _stream_ptr(stream)))
+    return d_y
+
+
+def ecf8_gemm_fp8_splitk_static(hdr, d_blob, d_x, w_scale=None, x_scale=None, d_y=None, stream=None):
+    """ecf8_gemm_fp8_splitk with the workspace inside the library (nothing to allocate; one call at a time per GPU)."""
+    M = d_x.shape[0]
+    ws, xs, xc = _opt_scale_ptrs("ecf8_gemm_fp8_splitk_static", hdr.rows, hdr.cols, M, w_scale, x_scale)
+    if d_y is None:
+        d_y = torch.empty((M, hdr.rows), dtype=torch.float32, device=d_x.device)
+    _check("ecf8_gemm_fp8_splitk_static", _lib.ecf8_gemm_fp8_splitk_static(ctypes.byref(hdr), d_blob.data_ptr(), d_x.data_ptr(), M,
+                                                                           ws, xs, xc, d_y.data_ptr(), _stream_ptr(stream)))
     return d_y
 
 
