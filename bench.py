@@ -9,9 +9,17 @@ instead, on --streams streams round-robin.  Inputs are seeded synthetic
 alpha-stable FP8 weights (recipe in paper_2510_02676_amd/synth.py); blobs and output buffers are resident
 in HBM before the timed region starts.
 
+With no --workload the headline is the largest single-GPU configuration, the
+40-block diffusion-transformer stack (config3, 20.3 G weights); the same JSON
+line carries the 8B-class LLM stack (config1, with its per-layer-launch rates)
+and the 256-expert MoE layer (config2) under "configs", the LLM stack coded
+with the plain Huffman code (no cap on the code length) under "plain_huffman",
+each with its own roofline object, and the CPU oracle timed on a bounded sample,
+on one core and on all of the machine's cores.  --workload configN times one
+configuration alone (what the rocprofv3 summaries under profiles/ were made with).
+
 Prints ONE JSON line: decoded FP8 GB/s as `value`, the roofline of the decode
-kernel, the per-layer-launch rates measured after the timed region, and the CPU
-oracle timed on a bounded sample.
+kernel, and the extras above.
 """
 import argparse
 import json
@@ -35,7 +43,7 @@ def algorithmic_bytes(h):
     return rd, h.n_elem
 
 
-def build_workload(name, seed, lane_syms, layers, launch="layer", group_chunks=0, max_code_len=0):
+def build_workload(name, seed, lane_syms, layers, launch="layer", group_chunks=0, max_code_len=0, cpu_encode=False):
     from paper_2510_02676_amd import ecf8, synth
     if name == "config1":
         specs = synth.config1(seed, layers)
@@ -60,11 +68,17 @@ def build_workload(name, seed, lane_syms, layers, launch="layer", group_chunks=0
     t0 = time.time()
     for s in specs:
         w = synth.make(s, seed, device=dev)                       # uint8 (rows, cols) on the GPU
-        blob = ecf8.ecf8_encode(w.cpu(), s["rows"], s["cols"], lane_syms=lane_syms, group_chunks=group_chunks,
-                                max_code_len=max_code_len)
-        d_blob = blob.to(dev)
+        if cpu_encode:
+            blob = ecf8.ecf8_encode(w.cpu(), s["rows"], s["cols"], lane_syms=lane_syms, group_chunks=group_chunks,
+                                    max_code_len=max_code_len)
+            hdr, d_blob = blob.header, blob.to(dev)
+        else:       # the device encoder writes the same container byte for byte (tests/test_gpu_encode.py), much faster
+            hdr, big = ecf8.ecf8_encode_gpu(w, s["rows"], s["cols"], lane_syms=lane_syms, group_chunks=group_chunks,
+                                            max_code_len=max_code_len)
+            d_blob = big.clone()                                   # drops the encoder's worst-case allocation
+            del big
         d_out = torch.empty((s["rows"], s["cols"]), dtype=torch.uint8, device=dev)
-        groups.setdefault(group(s), []).append(dict(spec=s, w=w, hdr=blob.header, d_blob=d_blob, d_out=d_out))
+        groups.setdefault(group(s), []).append(dict(spec=s, w=w, hdr=hdr, d_blob=d_blob, d_out=d_out))
     if launch == "stack":      # every tensor of the stack in ONE ecf8_decode_batched launch
         groups = {0: [t for g in sorted(groups) for t in groups[g]]}
     batches = []
@@ -74,33 +88,59 @@ def build_workload(name, seed, lane_syms, layers, launch="layer", group_chunks=0
     return batches, desc, time.time() - t0
 
 
-def cpu_baseline(batches, budget_syms=870_000_000):
-    """The oracle's bit-serial tree-walk decoder, single thread, on the first
-    tensors of the workload (about 10 s of decoding, as much again to prepare its inputs)."""
+def cpu_baseline(batches, budget_syms=440_000_000):
+    """The oracle's bit-serial tree-walk decoder on tensors of the workload: on one core (the first
+    tensors, about 5 s of decoding), then on all of the machine's cores, one tensor per thread (tensors are
+    independent; the C oracle runs outside the interpreter lock).  Only the decode is timed; preparing
+    the oracle's inputs (its own encoder) takes about as long again."""
     import oracle
+    from concurrent.futures import ThreadPoolExecutor
+    oracle.lib()
+
+    def prepare(t):
+        x = t["w"].cpu().numpy().reshape(-1)
+        ln = oracle.huffman_lengths(oracle.histogram(x))
+        stream, nbits = oracle.encode_exponents(x, ln, oracle.canonical_codes(ln), oracle.MSB_FIRST)
+        return x, ln, stream, nbits, oracle.pack_nibbles_paper(x)
+
+    def decode(p):
+        x, ln, stream, nbits, packed = p
+        t0 = time.perf_counter()
+        out = oracle.decode_serial(stream, nbits, ln, packed, x.size, oracle.MSB_FIRST)
+        dt = time.perf_counter() - t0
+        if not np.array_equal(out, x):
+            raise SystemExit("oracle round trip failed")
+        return dt
+
+    tensors = [t for _, ts in batches for t in ts]
     tot_syms, tot_t, names = 0, 0.0, []
-    for _, ts in batches:
-        for t in ts:
-            if tot_syms >= budget_syms:
-                break
-            x = t["w"].cpu().numpy().reshape(-1)
-            f = oracle.histogram(x)
-            ln = oracle.huffman_lengths(f)
-            codes = oracle.canonical_codes(ln)
-            stream, nbits = oracle.encode_exponents(x, ln, codes, oracle.MSB_FIRST)
-            packed = oracle.pack_nibbles_paper(x)
-            t0 = time.perf_counter()
-            out = oracle.decode_serial(stream, nbits, ln, packed, x.size, oracle.MSB_FIRST)
-            tot_t += time.perf_counter() - t0
-            if not np.array_equal(out, x):
-                raise SystemExit("oracle round trip failed on " + t["spec"]["name"])
-            tot_syms += x.size
-            names.append(t["spec"]["name"])
+    for t in tensors:
         if tot_syms >= budget_syms:
             break
-    return {"value": round(tot_syms / tot_t / 1e9, 4), "unit": "GB/s decoded FP8", "cores": 1, "kind": "oracle",
-            "sample": "bit-serial decode of %d tensors (%s..%s), %d weights, %.1f s" % (
-                len(names), names[0], names[-1], tot_syms, tot_t)}
+        p = prepare(t)
+        tot_t += decode(p)
+        tot_syms += p[0].size
+        names.append(t["spec"]["name"])
+    single = {"value": round(tot_syms / tot_t / 1e9, 4), "unit": "GB/s decoded FP8", "cores": 1,
+              "sample": "bit-serial decode of %d tensors (%s..%s), %d weights, %.1f s" % (
+                  len(names), names[0], names[-1], tot_syms, tot_t)}
+    # all cores: the box's share of the host is 16 cores per GPU, whatever the machine shows
+    cores = max(1, min(16, os.cpu_count() or 1))
+    big = sorted(tensors, key=lambda t: -t["w"].numel())[:cores]
+    with ThreadPoolExecutor(max_workers=cores) as pool:
+        prepared = list(pool.map(prepare, big))
+        t0 = time.perf_counter()
+        list(pool.map(decode, prepared))
+        wall = time.perf_counter() - t0
+    n_all = sum(p[0].size for p in prepared)
+    try:
+        model = next(l.split(":", 1)[1].strip() for l in open("/proc/cpuinfo") if l.startswith("model name"))
+    except Exception:
+        model = "unknown"
+    return {"value": round(n_all / wall / 1e9, 4), "unit": "GB/s decoded FP8", "cores": cores, "kind": "oracle",
+            "sample": "bit-serial decode of the %d largest tensors of the workload, one per thread, %d weights, %.1f s wall"
+                      % (len(prepared), n_all, wall),
+            "host": {"cpu_model": model, "cpu_count_seen": os.cpu_count()}, "single_core": single}
 
 
 def profiled_traffic(workload, launch, hdrs, layers_full, kernel="ecf8_decode_kernel"):
@@ -108,19 +148,21 @@ def profiled_traffic(workload, launch, hdrs, layers_full, kernel="ecf8_decode_ke
     exact workload, or None when no summary covers it."""
     if not layers_full:
         return None
-    path = os.path.join(ROOT, "profiles", "%s_%s_%s.txt" % (kernel, workload, launch))
-    try:
-        text = open(path).read()
-    except OSError:
-        return None
     key = "workload=%s launch=%s lane_syms=%d group_chunks=%d max_code_len=%d" % (
         workload, launch, hdrs[0].lane_syms, hdrs[0].group_chunks,
         max(h.max_code_len if hasattr(h, "max_code_len") else max(h.code_len) for h in hdrs))
-    if key not in text:
+    prefix = "%s_%s_%s" % (kernel, workload, launch)
+    try:
+        names = sorted(f for f in os.listdir(os.path.join(ROOT, "profiles")) if f.startswith(prefix) and f.endswith(".txt"))
+    except OSError:
         return None
-    for line in text.splitlines():
-        if line.startswith("traffic_bytes_per_launch="):
-            return int(line.split("=")[1])
+    for name in names:          # e.g. ..._config1_stack.txt (default cap) and ..._config1_stack_plain_huffman.txt
+        text = open(os.path.join(ROOT, "profiles", name)).read()
+        if key not in text:
+            continue
+        for line in text.splitlines():
+            if line.startswith("traffic_bytes_per_launch="):
+                return int(line.split("=")[1])
     return None
 
 
@@ -714,7 +756,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config1")
+    ap.add_argument("--workload", default="all",
+                    help="all (default): config3 headline with config1, config2 and plain Huffman beside it; or one of "
+                         "config0..config4, jit, encode, wide_bf16, wide_e5m2, encode_bf16, encode_e5m2")
+    ap.add_argument("--cpu-encode", action="store_true", help="set the stacks up with the CPU encoder instead of the device encoder")
     ap.add_argument("--layers", type=int, default=0, help="0 = the full stack of the workload")
     ap.add_argument("--lane-syms", type=int, default=0, help="0 = library default")
     ap.add_argument("--group-chunks", type=int, default=0, help="chunks interleaved per group, 0 = library default")
@@ -747,8 +792,44 @@ def main():
         return bench_wide(a)
     if a.workload in ("encode_bf16", "encode_e5m2"):
         return bench_encode_wide(a)
-    layers = a.layers or {"config1": 32, "config2": 256, "config3": 40, "config0": 1}[a.workload]
-    batches, desc, t_setup = build_workload(a.workload, a.seed, a.lane_syms, layers, a.launch, a.group_chunks, a.max_code_len)
+    if a.workload != "all":
+        out, batches = run_stack(a, a.workload, a.max_code_len, per_layer=not a.no_extra, copy_kernel=True)
+        if not a.no_cpu_baseline:
+            out["cpu_baseline"] = cpu_baseline(batches)
+        print(json.dumps(out))
+        return
+    # default: headline on the largest configuration, the others beside it in the same line
+    out, batches = run_stack(a, "config3", 0, per_layer=False, copy_kernel=True)
+    del batches
+    torch.cuda.empty_cache()
+    keep = ("value", "unit", "ms_per_step", "ms_per_step_median", "ms_per_step_min", "config", "compression_ratio",
+            "memory_saving_pct", "avg_code_bits", "compressed_read_GBps", "total_moved_GBps", "pct_of_hbm_peak", "bit_exact",
+            "setup_s", "roofline", "per_layer_launch")
+    out["configs"] = {}
+    r2, batches = run_stack(a, "config2", 0, per_layer=False, copy_kernel=False)
+    out["configs"]["config2"] = {k: r2[k] for k in keep if k in r2}
+    del batches
+    torch.cuda.empty_cache()
+    # the paper's own code (Section 3.1: the optimal Huffman code; its cap of 16 bits never binds on 16 symbols) ...
+    rh, batches = run_stack(a, "config1", 15, per_layer=False, copy_kernel=False)
+    out["plain_huffman"] = {k: rh[k] for k in keep if k in rh}
+    del batches
+    torch.cuda.empty_cache()
+    # ... and the same stack under this library's default cap of 7 bits per codeword (a declared extension)
+    r1, batches = run_stack(a, "config1", 0, per_layer=not a.no_extra, copy_kernel=False)
+    out["configs"]["config1"] = {k: r1[k] for k in keep if k in r1}
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(batches)
+    print(json.dumps(out))
+
+
+def run_stack(a, workload, max_code_len, per_layer, copy_kernel):
+    """Builds one stack workload, checks every decoded tensor against its input on the device, times a.steps
+    steps after a.warmup warm-up steps.  Returns (the result object, the batches with their tensors)."""
+    from paper_2510_02676_amd import ecf8
+    layers = a.layers or {"config1": 32, "config2": 256, "config3": 40, "config0": 1}[workload]
+    batches, desc, t_setup = build_workload(workload, a.seed, a.lane_syms, layers, a.launch, a.group_chunks, max_code_len,
+                                            a.cpu_encode)
     hdrs = [t["hdr"] for _, ts in batches for t in ts]
     n_total = sum(h.n_elem for h in hdrs)
     blob_total = sum(h.total_size for h in hdrs)
@@ -790,6 +871,7 @@ def main():
     launch_s = dev_s / n_launch                       # average duration of one decode launch (HIP events)
     alg_per_launch = alg_total / len(batches)
     achieved = alg_per_launch / launch_s / 1e9
+    cap = max(max(h.code_len) for h in hdrs)
 
     out = {
         "metric": "decoded FP8 GB/s (ECF8 -> exact FP8 E4M3 bytes)",
@@ -801,9 +883,11 @@ def main():
         "dtype": "u8", "data": "synthetic",
         "ms_per_step_median": round(per_step[len(per_step) // 2], 4) if per_step else None,
         "ms_per_step_min": round(per_step[0], 4) if per_step else None,
-        "config": {"workload": "%s: %s" % (a.workload, desc), "weights": n_total,
+        "config": {"workload": "%s: %s" % (workload, desc), "weights": n_total, "tensors": len(hdrs),
                    "launches_per_step": len(batches), "launch": a.launch, "lane_syms": hdrs[0].lane_syms,
-                   "group_chunks": hdrs[0].group_chunks, "max_code_len": max(max(h.code_len) for h in hdrs),
+                   "group_chunks": hdrs[0].group_chunks, "max_code_len": cap,
+                   "code": "plain Huffman (the paper's code)" if max_code_len >= 15 else
+                           "cheapest code with codewords of at most %d bits (this library's default)" % (max_code_len or 7),
                    "seed": a.seed},
         "compression_ratio": round(blob_total / n_total, 5),
         "memory_saving_pct": round(100 * (1 - blob_total / n_total), 2),
@@ -813,33 +897,33 @@ def main():
         "pct_of_hbm_peak": round(100 * alg_total / sec_per_step / 1e9 / HBM_PEAK_GBPS, 2),
         "bit_exact": True,
         "setup_s": round(t_setup, 1),
-        "roofline": {"bound": "hbm", "kernel": "ecf8_decode_kernel", "achieved": round(achieved, 2),
+        "roofline": {"bound": "hbm", "kernel": "ecf8_decode_kernel<%d, %s>" % (hdrs[0].lane_syms, "pairs always fit" if 2 * cap <= 14 else "general"),
+                     "achieved": round(achieved, 2),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "avg_launch_us": round(launch_s * 1e6, 2),
                      "algorithmic_bytes_per_launch": int(alg_per_launch),
-                     "traffic": profiled_traffic(a.workload, a.launch, hdrs, a.layers == 0)},
+                     "traffic": profiled_traffic(workload, a.launch, hdrs, a.layers == 0)},
     }
-    if a.launch == "stack" and not a.no_extra and len(batches[0][1]) > 1:
+    if a.launch == "stack" and per_layer and len(batches[0][1]) > 1:
         out["per_layer_launch"] = per_layer_rates(batches[0][1], alg_total, n_total)
-    # the achievable ceiling on this machine: a plain device-to-device copy of 1 GiB (read + written bytes per second);
-    # it doubles as the kernel of known traffic that the profiler counters are scaled by
-    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(7)
-    dst = torch.empty_like(src)
-    for _ in range(3):
-        dst.copy_(src)
-    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    c0.record()
-    for _ in range(5):
-        dst.copy_(src)
-    c1.record()
-    torch.cuda.synchronize()
-    copy_gbps = 5 * 2 * (1 << 30) / (c0.elapsed_time(c1) * 1e-3) / 1e9
-    out["copy_kernel_GBps"] = round(copy_gbps, 1)
-    out["pct_of_copy_kernel"] = round(100 * out["total_moved_GBps"] / copy_gbps, 1)
-    del src, dst
-    if not a.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(batches)
-    print(json.dumps(out))
+    if copy_kernel:
+        # the achievable ceiling on this machine: a plain device-to-device copy of 1 GiB (read + written bytes per second);
+        # it doubles as the kernel of known traffic that the profiler counters are scaled by
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(7)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        c0.record()
+        for _ in range(5):
+            dst.copy_(src)
+        c1.record()
+        torch.cuda.synchronize()
+        copy_gbps = 5 * 2 * (1 << 30) / (c0.elapsed_time(c1) * 1e-3) / 1e9
+        out["copy_kernel_GBps"] = round(copy_gbps, 1)
+        out["pct_of_copy_kernel"] = round(100 * out["total_moved_GBps"] / copy_gbps, 1)
+        del src, dst
+    return out, batches
 
 
 if __name__ == "__main__":

@@ -299,53 +299,92 @@ def test_batch_argument_errors():
 
 # ---------------------------------------------------------------- full-size cases
 
-def _full_size_case(orc, specs, oracle_checks, max_code_len=0):
+def _full_size_case(orc, specs, oracle_checks, max_code_len=0, reader_checks=(), gpu_encode=False):
     """Encode/ decode `specs` (full-size tensors, generated on the GPU) in ONE batched launch, the
     launch configuration bench.py times.  Every output is compared with its input on the device
     (decode(encode(x)) == x is the plain definition of the result); the tensors named in
-    `oracle_checks` are also compared with the oracle's own encode -> bit-serial decode."""
+    `oracle_checks` are also compared with the oracle's own encode -> bit-serial decode (and the
+    container's stream length with the oracle's optimum), and for those in `reader_checks` the
+    oracle's reader decodes the very container the GPU decoded.  gpu_encode: containers written by the
+    device encoder (byte for byte the CPU encoder's, tests/test_gpu_encode.py), which keeps the
+    largest stacks inside the suite's time."""
     ts = []
     for s in specs:
         w = synth.make(s, 0, device=DEV)
-        b = ecf8.ecf8_encode(w.cpu(), s["rows"], s["cols"], max_code_len=max_code_len)
-        ts.append((s, w, b.header, b.to(DEV), torch.full_like(w, 0xEE)))
+        if gpu_encode:
+            h, big = ecf8.ecf8_encode_gpu(w, s["rows"], s["cols"], max_code_len=max_code_len)
+            d_blob = big.clone()
+            del big
+        else:
+            b = ecf8.ecf8_encode(w.cpu(), s["rows"], s["cols"], max_code_len=max_code_len)
+            h, d_blob = b.header, b.to(DEV)
+        ts.append((s, w, h, d_blob, torch.full_like(w, 0xEE)))
+    print("full-size case: %d tensors, %d weights, one launch" % (len(ts), sum(t[1].numel() for t in ts)), flush=True)
     batch = ecf8.Batch([t[2] for t in ts], [t[3] for t in ts], [t[4] for t in ts])
     ecf8.ecf8_decode_batched(batch)
     torch.cuda.synchronize()
-    for s, w, h, _, out in ts:
+    seen = set()
+    for s, w, h, d_blob, out in ts:
         assert torch.equal(out, w), s["name"]
         if s["name"] in oracle_checks:
+            seen.add(s["name"])
             x = w.cpu().numpy().reshape(-1)
             exp, nbits, _ = orc.roundtrip(x)
             f = orc.histogram(x)
             cap = max_code_len or 7
             assert h.stream_bits == (nbits if cap >= 15 else orc.stream_bits(f, orc.huffman_lengths_limited(f, cap)))
-            assert np.array_equal(out.cpu().numpy().reshape(-1), exp), s["name"]
+            got = out.cpu().numpy().reshape(-1)
+            assert np.array_equal(got, exp), s["name"]
+            if s["name"] in reader_checks:
+                dec, bits = orc.container_decode(d_blob.cpu().numpy())
+                assert bits == h.stream_bits and np.array_equal(dec, got), s["name"]
+    assert seen == set(oracle_checks)
 
 
 @pytest.mark.parametrize("max_code_len", [0, 15])
 def test_config1_full_layer(orc, max_code_len):
     """configs[1]: one full layer of the 8B-class stack (7 matrices, 218 M weights), one launch;
-    under the default cap on the code length and with plain Huffman."""
-    _full_size_case(orc, synth.config1(0, 1), {"l0.k", "l0.q"}, max_code_len)
+    under the default cap on the code length and with plain Huffman.  The oracle decodes the whole
+    layer, and its reader the K projection's container."""
+    specs = synth.config1(0, 1)
+    _full_size_case(orc, specs, {s["name"] for s in specs}, max_code_len, reader_checks={"l0.k"})
 
 
 def test_config1_whole_stack_one_launch(orc):
     """configs[1] at full size in the launch configuration bench.py times: all 32 layers (224
     matrices, 6.98 G weights) through ONE ecf8_decode_batched launch; every output compared with
     its input on the device, two matrices also with the oracle's own encode -> bit-serial decode."""
-    _full_size_case(orc, synth.config1(0, 32), {"l17.v", "l31.k"})
+    _full_size_case(orc, synth.config1(0, 32), {"l17.v", "l31.k"}, gpu_encode=True)
 
 
 def test_config2_experts_and_attention(orc):
-    """configs[2]: six full-size expert matrices and the two attention projections in one launch."""
+    """configs[2]: six full-size expert matrices and the two attention projections in one launch,
+    containers from the CPU encoder."""
     specs = synth.config2(0, 2)
     _full_size_case(orc, specs, {"e0.gate", "e1.down"})
 
 
+def test_config2_whole_layer_one_launch(orc):
+    """configs[2] at full size: the 768 expert matrices and the two attention projections (770 tensors,
+    11.6 G weights) through ONE ecf8_decode_batched launch; every output compared with its input on the
+    device; the oracle decodes one expert's three matrices and an attention projection, and its reader
+    one expert container."""
+    _full_size_case(orc, synth.config2(0, 256), {"e137.gate", "e137.up", "e137.down", "attn_b"},
+                    reader_checks={"e137.down"}, gpu_encode=True)
+
+
 def test_config3_full_block(orc):
-    """configs[3]: one full DiT block (11 matrices, 509 M weights, per-tensor scaling), one launch."""
-    _full_size_case(orc, synth.config3(1), {"b0.sa_q", "b0.ca_o"})
+    """configs[3]: one full DiT block (11 matrices, 509 M weights, per-tensor scaling), one launch,
+    containers from the CPU encoder; the oracle decodes the whole block."""
+    specs = synth.config3(1)
+    _full_size_case(orc, specs, {s["name"] for s in specs}, reader_checks={"b0.sa_q"})
+
+
+def test_config3_whole_stack_one_launch(orc):
+    """configs[3] at full size: all 40 blocks (440 matrices, 20.3 G weights) through ONE
+    ecf8_decode_batched launch; every output compared with its input on the device, three matrices of
+    a late block also with the oracle."""
+    _full_size_case(orc, synth.config3(40), {"b33.ca_k", "b33.ffn2", "b39.sa_o"}, gpu_encode=True)
 
 
 def test_stream_longer_than_2_to_the_31_bits():
