@@ -43,7 +43,7 @@ def algorithmic_bytes(h):
     return rd, h.n_elem
 
 
-def build_workload(name, seed, lane_syms, layers, launch="layer", group_chunks=0, max_code_len=0, cpu_encode=False):
+def build_workload(name, seed, lane_syms, layers, launch="layer", group_chunks=0, max_code_len=0, cpu_encode=False, arena=False):
     from paper_2510_02676_amd import ecf8, synth
     if name == "config1":
         specs = synth.config1(seed, layers)
@@ -79,6 +79,27 @@ def build_workload(name, seed, lane_syms, layers, launch="layer", group_chunks=0
             del big
         d_out = torch.empty((s["rows"], s["cols"]), dtype=torch.uint8, device=dev)
         groups.setdefault(group(s), []).append(dict(spec=s, w=w, hdr=hdr, d_blob=d_blob, d_out=d_out))
+    if arena:
+        # one allocation for all blobs and one for all outputs (tensors at multiples of 4 KiB inside them), the way a
+        # serving process would hold a model, instead of one allocation per tensor
+        al = lambda n: (n + 4095) // 4096 * 4096
+        ts = [t for g in sorted(groups) for t in groups[g]]
+        nb_all, no_all = sum(al(t["d_blob"].numel()) for t in ts), sum(al(t["d_out"].numel()) for t in ts)
+        gap = int(os.environ.get("ECF8_BENCH_GAP", "-1"))      # working option: both arenas in one allocation, `gap` bytes apart
+        if gap >= 0:
+            both = torch.empty(nb_all + gap + no_all, dtype=torch.uint8, device=dev)
+            blobs, outs = both[:nb_all], both[nb_all + gap:]
+        else:
+            blobs = torch.empty(nb_all, dtype=torch.uint8, device=dev)
+            outs = torch.empty(no_all, dtype=torch.uint8, device=dev)
+        ob = oo = 0
+        for t in ts:
+            nb, no = t["d_blob"].numel(), t["d_out"].numel()
+            blobs[ob:ob + nb].copy_(t["d_blob"])
+            t["d_blob"] = blobs[ob:ob + nb]
+            t["d_out"] = outs[oo:oo + no].view(t["d_out"].shape)
+            ob, oo = ob + al(nb), oo + al(no)
+        torch.cuda.empty_cache()
     if launch == "stack":      # every tensor of the stack in ONE ecf8_decode_batched launch
         groups = {0: [t for g in sorted(groups) for t in groups[g]]}
     batches = []
@@ -210,6 +231,13 @@ def bench_config4(a):
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / iters * 1e-3
 
+    if a.copy_calibration:      # a kernel of known traffic for the profiler counters
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(7)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     spec = synth.config4()[0]
     w = synth.make(spec, a.seed, device="cuda:0")
     blob = ecf8.ecf8_encode(w.cpu(), spec["rows"], spec["cols"], lane_syms=64, tile_rows=16)
@@ -294,6 +322,8 @@ def bench_config4(a):
                            "fused_weight_GBps": round(w.numel() / tf / 1e9, 1)}
     # beyond the fused call's M: two calls of 64 rows against decoding W once and calling the vendor library's GEMM
     crossover = None
+    if a.no_extra:
+        return print_config4(a, spec, w, h, res, None, None, None, None)
     try:
         x128 = synth.activations(128, spec["cols"], seed=a.seed, device="cuda:0")
         y128 = torch.empty((128, spec["rows"]), dtype=torch.float32, device="cuda:0")
@@ -394,7 +424,12 @@ def bench_config4(a):
             "24_raw_calls_us": round(timeit(singles_raw, a.steps, a.warmup) * 1e6, 2)}
     res_group["weights"] = sum(w_.numel() for w_, _, _ in experts)
     del experts
+    print_config4(a, spec, w, h, res, crossover, res_down, res_split, res_group)
+
+
+def print_config4(a, spec, w, h, res, crossover, res_down, res_split, res_group):
     t16 = res["M=16"]["fused_us"] * 1e-6
+    alg = int(h.total_size + 16 * (spec["cols"] + 4 * spec["rows"]))      # the blob and X read, Y written (M = 16)
     print(json.dumps({
         "metric": "decoded FP8 GB/s consumed by the fused decode+GEMM (M=16)", "value": round(w.numel() / t16 / 1e9, 2),
         "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(t16 * 1e3, 5),
@@ -402,13 +437,27 @@ def bench_config4(a):
         "config": {"workload": "config4: fused decode + FP8 MFMA GEMM, W 14336x4096, M in {1,16,64}", "seed": a.seed},
         "compression_ratio": round(h.total_size / w.numel(), 5), "bit_exact_vs_raw_weights_gemm": True,
         # the fused kernel reads the blob and X and writes Y: far from the memory roof, it is bound by the decode arithmetic
-        "roofline": {"bound": "hbm", "kernel": "ecf8_gemm_kernel<1, 16, 64, 0>", "achieved": round((h.total_size + 16 * (spec["cols"] + 4 * spec["rows"])) / t16 / 1e9, 2),
-                     "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round((h.total_size + 16 * (spec["cols"] + 4 * spec["rows"])) / t16 / 1e9 / HBM_PEAK_GBPS, 4),
-                     "avg_launch_us": round(t16 * 1e6, 2),
-                     "algorithmic_bytes_per_launch": int(h.total_size + 16 * (spec["cols"] + 4 * spec["rows"])), "traffic": None},
+        "roofline": {"bound": "hbm", "kernel": "ecf8_gemm_kernel<1, 16, 64, 0>", "achieved": round(alg / t16 / 1e9, 2),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(alg / t16 / 1e9 / HBM_PEAK_GBPS, 4),
+                     "avg_launch_us": round(t16 * 1e6, 2), "algorithmic_bytes_per_launch": alg,
+                     "traffic": profiled_gemm_traffic(h)},
         "gemm": res, "beyond_M64": crossover, "gemm_down_4096x14336_any_k": res_down, "split_k": res_split,
         "grouped_8_experts": res_group}))
+
+
+def profiled_gemm_traffic(h):
+    """HBM bytes of one fused M = 16 launch on config 4's W from the committed counter summary, or None."""
+    try:
+        text = open(os.path.join(ROOT, "profiles", "ecf8_gemm_kernel_config4_hbm_traffic.txt")).read()
+    except OSError:
+        return None
+    if "blob_bytes=%d" % h.total_size not in text:
+        return None
+    for line in text.splitlines():
+        if line.startswith("traffic_bytes_per_launch="):
+            return int(line.split("=")[1])
+    return None
+
 
 def bench_jit(a):
     """Workload "jit" (paper Section 3.3): a forward pass over the config-1 stack with the weights
@@ -759,6 +808,9 @@ def main():
     ap.add_argument("--workload", default="all",
                     help="all (default): config3 headline with config1, config2 and plain Huffman beside it; or one of "
                          "config0..config4, jit, encode, wide_bf16, wide_e5m2, encode_bf16, encode_e5m2")
+    ap.add_argument("--all-order", default="config3,config2,plain_huffman,config1", help="order of the parts of the default run")
+    ap.add_argument("--churn-gb", type=int, default=0, help=argparse.SUPPRESS)
+    ap.add_argument("--arena", type=int, default=0, help="1: all blobs in one device allocation and all outputs in another")
     ap.add_argument("--cpu-encode", action="store_true", help="set the stacks up with the CPU encoder instead of the device encoder")
     ap.add_argument("--layers", type=int, default=0, help="0 = the full stack of the workload")
     ap.add_argument("--lane-syms", type=int, default=0, help="0 = library default")
@@ -782,6 +834,12 @@ def main():
         raise SystemExit("no GPU visible: the decode path has no CPU fallback")
     from paper_2510_02676_amd import ecf8
 
+    if a.churn_gb:       # working option: device memory allocated (and with a negative value freed again) before the workload is built
+        dummy = torch.empty(abs(a.churn_gb) << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
+        torch.cuda.synchronize()
+        if a.churn_gb < 0:
+            del dummy
+            torch.cuda.empty_cache()
     if a.workload == "config4":
         return bench_config4(a)
     if a.workload == "jit":
@@ -799,27 +857,33 @@ def main():
         print(json.dumps(out))
         return
     # default: headline on the largest configuration, the others beside it in the same line
-    out, batches = run_stack(a, "config3", 0, per_layer=False, copy_kernel=True)
-    del batches
-    torch.cuda.empty_cache()
     keep = ("value", "unit", "ms_per_step", "ms_per_step_median", "ms_per_step_min", "config", "compression_ratio",
             "memory_saving_pct", "avg_code_bits", "compressed_read_GBps", "total_moved_GBps", "pct_of_hbm_peak", "bit_exact",
             "setup_s", "roofline", "per_layer_launch")
-    out["configs"] = {}
-    r2, batches = run_stack(a, "config2", 0, per_layer=False, copy_kernel=False)
-    out["configs"]["config2"] = {k: r2[k] for k in keep if k in r2}
-    del batches
-    torch.cuda.empty_cache()
-    # the paper's own code (Section 3.1: the optimal Huffman code; its cap of 16 bits never binds on 16 symbols) ...
-    rh, batches = run_stack(a, "config1", 15, per_layer=False, copy_kernel=False)
-    out["plain_huffman"] = {k: rh[k] for k in keep if k in rh}
-    del batches
-    torch.cuda.empty_cache()
-    # ... and the same stack under this library's default cap of 7 bits per codeword (a declared extension)
-    r1, batches = run_stack(a, "config1", 0, per_layer=not a.no_extra, copy_kernel=False)
-    out["configs"]["config1"] = {k: r1[k] for k in keep if k in r1}
-    if not a.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(batches)
+    results, baseline = {}, None
+    for part in a.all_order.split(","):
+        if part == "config3":
+            results[part], batches = run_stack(a, "config3", 0, per_layer=False, copy_kernel=True)
+        elif part == "config2":
+            results[part], batches = run_stack(a, "config2", 0, per_layer=False, copy_kernel=False)
+        elif part == "plain_huffman":
+            # the paper's own code (Section 3.1: the optimal Huffman code; its cap of 16 bits never binds on 16 symbols)
+            results[part], batches = run_stack(a, "config1", 15, per_layer=False, copy_kernel=False)
+        elif part == "config1":
+            # the same stack under this library's default cap of 7 bits per codeword (a declared extension)
+            results[part], batches = run_stack(a, "config1", 0, per_layer=not a.no_extra, copy_kernel=False)
+            if not a.no_cpu_baseline:
+                baseline = cpu_baseline(batches)
+        else:
+            raise SystemExit("unknown part " + part)
+        del batches
+        torch.cuda.empty_cache()
+    out = results["config3"] if "config3" in results else dict(next(iter(results.values())))
+    out["configs"] = {k: {f: results[k][f] for f in keep if f in results[k]} for k in ("config1", "config2") if k in results}
+    if "plain_huffman" in results:
+        out["plain_huffman"] = {f: results["plain_huffman"][f] for f in keep if f in results["plain_huffman"]}
+    if baseline:
+        out["cpu_baseline"] = baseline
     print(json.dumps(out))
 
 
@@ -829,7 +893,7 @@ def run_stack(a, workload, max_code_len, per_layer, copy_kernel):
     from paper_2510_02676_amd import ecf8
     layers = a.layers or {"config1": 32, "config2": 256, "config3": 40, "config0": 1}[workload]
     batches, desc, t_setup = build_workload(workload, a.seed, a.lane_syms, layers, a.launch, a.group_chunks, max_code_len,
-                                            a.cpu_encode)
+                                            a.cpu_encode, a.arena)
     hdrs = [t["hdr"] for _, ts in batches for t in ts]
     n_total = sum(h.n_elem for h in hdrs)
     blob_total = sum(h.total_size for h in hdrs)

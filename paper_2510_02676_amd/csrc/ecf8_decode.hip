@@ -95,7 +95,9 @@ struct Cfg {
 
 // PAIRFIT: every tensor of the launch has codewords of at most TB/2 bits (the encoder's
 // default cap), so the pipelined loop needs no second level and is one straight line.
-template <int N, int WAVES, bool PAIRFIT, bool TILED = false>
+// LONG (general kernels only): some codeword of the launch is longer than TB bits.  BURST: a chunk's pieces are
+// held in registers and stored together at its end.
+template <int N, int WAVES, bool PAIRFIT, bool TILED = false, bool LONG = !PAIRFIT, bool BURST = PAIRFIT>
 __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
 {
     using C = Cfg<N, WAVES, PAIRFIT, TILED>;
@@ -133,13 +135,15 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
                 uint32_t mid = (lo + hi + 1) >> 1;
                 if (a.items[mid].first_chunk <= c) lo = mid; else hi = mid - 1;
             }
+            // the item's fields are the same for every lane: into scalar registers, they live as long as the tensor
             const GLOBAL ecf8_batch_item *p = a.items + lo;
-            d_blob = p->d_blob; d_out = p->d_out; n_elem = p->n_elem; n_chunks = p->n_chunks;
-            first_chunk = p->first_chunk; off_cb = p->off_chunk_bit; off_lb = p->off_lane_bits;
-            off_st = p->off_stream; off_pl = p->off_plane; st_bytes = p->stream_bytes;
-            off_tbl = p->off_table; group = p->group_chunks; tcols = p->tile_cols;
+            d_blob = uniform64(p->d_blob); d_out = uniform64(p->d_out); n_elem = uniform64(p->n_elem);
+            n_chunks = uniform64(p->n_chunks); first_chunk = uniform64(p->first_chunk);
+            off_cb = uniform64(p->off_chunk_bit); off_lb = uniform64(p->off_lane_bits);
+            off_st = uniform64(p->off_stream); off_pl = uniform64(p->off_plane); st_bytes = uniform64(p->stream_bytes);
+            off_tbl = uniform64(p->off_table); group = uniform64(p->group_chunks); tcols = uniform64(p->tile_cols);
             const GLOBAL uint64_t *cl8 = (const GLOBAL uint64_t *)p->code_len;
-            len_lo = cl8[0]; len_hi = cl8[1];
+            len_lo = uniform64(cl8[0]); len_hi = uniform64(cl8[1]);
         } else {
             d_blob = a.single.d_blob; d_out = a.single.d_out; n_elem = a.single.n_elem;
             n_chunks = a.single.n_chunks; first_chunk = 0; off_cb = a.single.off_chunk_bit;
@@ -285,15 +289,15 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
             // write runs of adjacent KiBs close in time, which HBM takes ~15 % faster than
             // single KiBs trickling out of every wave as they are decoded; the general
             // kernel has no registers to spare for that.
-            u32x4 ov[PAIRFIT ? C::PIECES : 1];
+            u32x4 ov[BURST ? C::PIECES : 1];
 #pragma unroll
             for (int Q = 0; Q < C::PIECES / 2; Q++) {
                 uint32_t dwA[4], dwB[4];
 #pragma unroll
                 for (int t = 0; t < 4; t++) {
-                    quad_step2<PAIRFIT>(smem, tbl, s_len, s_code, bpA, bpB, dwA[t], dwB[t]);
+                    quad_step2<PAIRFIT, LONG>(smem, tbl, s_len, s_code, bpA, bpB, dwA[t], dwB[t]);
                 }
-                if constexpr (PAIRFIT) {
+                if constexpr (BURST) {
                     ov[Q] = merge_piece(dwA, pl[Q]);
                     ov[Q + C::PIECES / 2] = merge_piece(dwB, pl[Q + C::PIECES / 2]);
                 } else {
@@ -318,7 +322,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
 #pragma unroll
                 for (int j = 0; j < 4; j++) ST_STREAM(ov[j], (GLOBAL u32x4 *)(out_t + (uint64_t)(4 * j) * tcols));
                 __builtin_amdgcn_sched_barrier(0);
-            } else if constexpr (PAIRFIT) {
+            } else if constexpr (BURST) {
                 __builtin_amdgcn_sched_barrier(0);   // keep the stores together, after the decode
 #pragma unroll
                 for (int Q = 0; Q < C::PIECES; Q++) ST_STREAM(ov[Q], (GLOBAL u32x4 *)(out_c + Q * ostride));
@@ -453,7 +457,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
 #pragma unroll 1
                     for (uint32_t i = 0; i < 16 && o + i < n_elem; i++) {
                         const uint32_t w = fwd ? global_window<+1>(sp, bA) : global_window<-1>(sp, bB);
-                        const uint32_t r = decode_one(w, tbl, s_len, s_code);
+                        const uint32_t r = decode_one<LONG>(w, tbl, s_len, s_code);
                         if (fwd) bA += r >> 8; else bB -= r >> 8;
                         const uint64_t el = o + i;
                         const uint32_t pb = plane[(el >> 3) * 4 + (el & 3)];
@@ -467,7 +471,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
     }
 }
 
-template <int N, int WAVES, bool PAIRFIT, bool TILED = false>
+template <int N, int WAVES, bool PAIRFIT, bool TILED = false, bool LONG = !PAIRFIT, bool BURST = PAIRFIT>
 int launch_as(const KArgs &a, int wgs_per_cu, hipStream_t s)
 {
     int cus = device_cus();
@@ -477,7 +481,7 @@ int launch_as(const KArgs &a, int wgs_per_cu, hipStream_t s)
     if (a.max_workgroups && a.max_workgroups < cap) cap = a.max_workgroups;
     uint32_t grid = (uint32_t)(want < cap ? want : cap);
     if (grid == 0) grid = 1;
-    hipLaunchKernelGGL((ecf8_decode_kernel<N, WAVES, PAIRFIT, TILED>), dim3(grid), dim3(WAVES * 64), 0, s, a);
+    hipLaunchKernelGGL((ecf8_decode_kernel<N, WAVES, PAIRFIT, TILED, LONG, BURST>), dim3(grid), dim3(WAVES * 64), 0, s, a);
     return hipGetLastError() == hipSuccess ? ECF8_OK : ECF8_E_HIP;
 }
 
@@ -488,13 +492,19 @@ int dispatch(const KArgs &a, uint32_t lane_syms, hipStream_t s)
 {
     if (a.max_code_len == 0 || a.max_code_len > 15) return ECF8_E_ARG;
     const bool pairfit = 2 * a.max_code_len <= (uint32_t)TB;
+    const bool lng = a.max_code_len > (uint32_t)TB;      // a codeword the table cannot hold: the kernels with the out-of-line matcher
     switch (lane_syms) {
-    case 32: return pairfit ? launch_as<32, 16, true>(a, 1, s) : launch_as<32, 16, false>(a, 1, s);
+    case 32:
+        if (pairfit) return launch_as<32, 16, true>(a, 1, s);
+        return lng ? launch_as<32, 16, false, false, true>(a, 1, s) : launch_as<32, 16, false, false, false>(a, 1, s);
     case 64:
         // the fused GEMM's blobs (row-tiled, capped codes): decoded chunks leave as whole row segments
         if (pairfit && a.row_tiled) return launch_as<64, 16, true, true>(a, 1, s);
-        return pairfit ? launch_as<64, 16, true>(a, 1, s) : launch_as<64, 16, false>(a, 1, s);
-    case 128: return pairfit ? launch_as<128, 8, true>(a, 1, s) : launch_as<128, 12, false>(a, 1, s);
+        if (pairfit) return launch_as<64, 16, true>(a, 1, s);
+        return lng ? launch_as<64, 16, false, false, true>(a, 1, s) : launch_as<64, 16, false, false, false>(a, 1, s);
+    case 128:
+        if (pairfit) return launch_as<128, 8, true>(a, 1, s);
+        return lng ? launch_as<128, 12, false, false, true>(a, 1, s) : launch_as<128, 12, false, false, false>(a, 1, s);
     default: return ECF8_E_ARG;
     }
 }

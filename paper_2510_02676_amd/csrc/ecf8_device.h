@@ -75,7 +75,7 @@ __device__ __forceinline__ uint32_t wave_max(uint32_t x)
 
 // A codeword longer than TB bits (rarer than 2^-TB): match the next 15 stream
 // bits against the long canonical codes.  Returns exponent | length << 8.
-__device__ __noinline__ uint32_t decode_long(uint32_t bits, const uint32_t *s_len, const uint32_t *s_code)
+__device__ __noinline__ __attribute__((unused)) uint32_t decode_long(uint32_t bits, const uint32_t *s_len, const uint32_t *s_code)
 {
     uint32_t v = __brev(bits) >> 17;          // next 15 bits, first bit most significant
     uint32_t r = 15u << 8;                    // no match (corrupt stream): skip 15 bits, exponent 0
@@ -89,11 +89,15 @@ __device__ __noinline__ uint32_t decode_long(uint32_t bits, const uint32_t *s_le
 
 // One symbol the careful way.  `bits`: stream bits from the current position
 // (>= 15 valid).  Returns exponent | length << 8.
+// LONG = false: the launch has no codeword longer than TB bits, so the table always answers (a blob that
+// breaks the promise decodes to wrong bytes, in bounds) and the out-of-line matcher is compiled out.
+template <bool LONG = true>
 __device__ __forceinline__ uint32_t decode_one(uint32_t bits, const uint16_t *tbl, const uint32_t *s_len,
                                                const uint32_t *s_code)
 {
     uint32_t e = tbl[bits & TBL_MASK];
     uint32_t l = (e & 7u) | ((e >> 12) & 8u);
+    if constexpr (!LONG) return ((e >> 3) & 15u) | ((l ? l : 15u) << 8);
     if (__builtin_expect(l != 0, 1)) return ((e >> 3) & 15u) | (l << 8);
     return decode_long(bits, s_len, s_code);
 }
@@ -102,12 +106,13 @@ __device__ __forceinline__ uint32_t decode_one(uint32_t bits, const uint16_t *tb
 // valid stream bits) has no pair (the two codewords need more than TB bits, or
 // the first one alone does).  Decodes the two symbols one at a time and returns
 // them in `e` in pair-entry layout, their total length (up to 30) in `n`.
+template <bool LONG = true>
 __device__ __forceinline__ void pair_second_level(uint32_t bits, uint32_t &e, uint32_t &n, const uint16_t *tbl,
                                                   const uint32_t *s_len, const uint32_t *s_code)
 {
-    const uint32_t r1 = decode_one(bits, tbl, s_len, s_code);
+    const uint32_t r1 = decode_one<LONG>(bits, tbl, s_len, s_code);
     const uint32_t l1 = r1 >> 8;
-    const uint32_t r2 = decode_one(bits >> l1, tbl, s_len, s_code);
+    const uint32_t r2 = decode_one<LONG>(bits >> l1, tbl, s_len, s_code);
     e = ((r1 & 15u) << 3) | ((r2 & 15u) << 11);
     n = l1 + (r2 >> 8);
 }
@@ -181,7 +186,7 @@ __device__ __forceinline__ uint32_t lds_window(const uint8_t *smem, uint32_t bp)
 // PAIRFIT: no codeword is longer than TB/2 bits, so every pair is in the table and
 // the second level is compiled out (a blob that breaks the promise decodes to wrong
 // bytes, in bounds).
-template <bool PAIRFIT>
+template <bool PAIRFIT, bool LONG = true>
 __device__ __forceinline__ void quad_step2(const uint8_t *smem, const uint16_t *tbl, const uint32_t *s_len,
                                            const uint32_t *s_code, uint32_t &pa, uint32_t &pb,
                                            uint32_t &outA, uint32_t &outB)
@@ -202,19 +207,19 @@ __device__ __forceinline__ void quad_step2(const uint8_t *smem, const uint16_t *
     // n1 == 0 makes the second lookup repeat the first, so n2 == 0 covers both pairs of a run
     if (!PAIRFIT && __builtin_expect(nA2 == 0 || nB2 == 0, 0)) {
         if (nA2 == 0) {
-            if (nA1 == 0) pair_second_level(wA >> 1, eA1, nA1, tbl, s_len, s_code);   // 31 valid bits, 30 needed
+            if (nA1 == 0) pair_second_level<LONG>(wA >> 1, eA1, nA1, tbl, s_len, s_code);   // 31 valid bits, 30 needed
             // the second level needs up to 30 bits: fresh window after the first pair
             const uint32_t w2 = lds_window<+1>(smem, pa + 1 + nA1);
             eA2 = tbl[w2 & TBL_MASK];
             nA2 = (eA2 >> 7) & 15u;
-            if (nA2 == 0) pair_second_level(w2, eA2, nA2, tbl, s_len, s_code);
+            if (nA2 == 0) pair_second_level<LONG>(w2, eA2, nA2, tbl, s_len, s_code);
         }
         if (nB2 == 0) {
-            if (nB1 == 0) pair_second_level(wB >> 1, eB1, nB1, tbl, s_len, s_code);
+            if (nB1 == 0) pair_second_level<LONG>(wB >> 1, eB1, nB1, tbl, s_len, s_code);
             const uint32_t w2 = lds_window<-1>(smem, pb + 31 - nB1);
             eB2 = tbl[w2 & TBL_MASK];
             nB2 = (eB2 >> 7) & 15u;
-            if (nB2 == 0) pair_second_level(w2, eB2, nB2, tbl, s_len, s_code);
+            if (nB2 == 0) pair_second_level<LONG>(w2, eB2, nB2, tbl, s_len, s_code);
         }
     }
     pa += nA1 + nA2;
