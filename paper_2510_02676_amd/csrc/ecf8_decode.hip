@@ -46,6 +46,8 @@
 //    equal static shares would finish up to 50 % apart).  No global atomics.
 #include "ecf8_device.h"
 
+#include <cstddef>
+
 namespace {
 
 // Stream, plane and output are touched exactly once: nontemporal accesses keep them from
@@ -124,26 +126,68 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
     uint64_t c = units * wg / NWG * unit;
     uint64_t c_end = units * (wg + 1) / NWG * unit;
     if (c_end > a.total_chunks) c_end = a.total_chunks;
+    // A launch over a handful of tensors with not much work per workgroup (one layer's matrices): a range that
+    // crosses from one tensor into the next pays the code set-up twice, a few microseconds that the whole launch
+    // then waits for.  Where it costs at most 6 % in balance, the workgroups are dealt to the tensors instead
+    // (tensor t gets the workgroups [B(t-1), B(t)), B(t) = its share of the chunks so far, rounded) and share a
+    // tensor's chunks evenly, so that no range crosses a tensor boundary.  Every workgroup reaches the same
+    // decision from the same numbers: lane l looks at tensor l.
+    uint32_t hint = 0xffffffffu;      // the tensor this workgroup starts in, when known
+    if (a.items && unit == 1 && a.n_items > 1 && a.n_items <= 64 && a.total_chunks < (1ull << 31) && NWG >= 2ull * a.n_items) {
+        const uint32_t nwg = (uint32_t)NWG, total = (uint32_t)a.total_chunks;
+        const uint32_t nc = (uint32_t)lane < a.n_items ? (uint32_t)a.items[lane].n_chunks : 0u;
+        const uint32_t cum = wave_incl_scan(nc);
+        const uint32_t B = (uint32_t)(((uint64_t)cum * nwg + total / 2) / total);
+        uint32_t Bprev = (uint32_t)__builtin_amdgcn_ds_bpermute(((lane + 63) & 63) * 4, (int)B);
+        if (lane == 0) Bprev = 0;
+        const uint32_t wgs = B - Bprev;
+        const uint32_t load = wgs ? (nc + wgs - 1) / wgs : (nc ? 0x7fffffffu : 0u);
+        const uint32_t even = (total + nwg - 1) / nwg;
+        if (wave_max(load) <= even + even / 16) {
+            const uint64_t mine = __builtin_amdgcn_ballot_w64((uint32_t)lane < a.n_items && (uint32_t)wg >= Bprev && (uint32_t)wg < B);
+            if (mine) {       // always: the B(t) run from 0 to NWG
+                const int t = __builtin_ctzll(mine);
+                const uint32_t nc_t = (uint32_t)__builtin_amdgcn_readlane((int)nc, t), cum_t = (uint32_t)__builtin_amdgcn_readlane((int)cum, t);
+                const uint32_t b0 = (uint32_t)__builtin_amdgcn_readlane((int)Bprev, t), w_t = (uint32_t)__builtin_amdgcn_readlane((int)wgs, t);
+                const uint32_t j = (uint32_t)wg - b0;
+                c = (uint64_t)(cum_t - nc_t) + (uint64_t)nc_t * j / w_t;
+                c_end = (uint64_t)(cum_t - nc_t) + (uint64_t)nc_t * (j + 1) / w_t;
+                hint = (uint32_t)t;
+            }
+        }
+    }
 
     while (c < c_end) {
         // which tensor holds chunk c (uniform)
         uint64_t d_blob, d_out, n_elem, n_chunks, first_chunk, off_cb, off_lb, off_st, off_pl, st_bytes;
         uint64_t len_lo, len_hi, off_tbl, group, tcols;
         if (a.items) {
-            uint32_t lo = 0, hi = a.n_items - 1;
-            while (lo < hi) {
-                uint32_t mid = (lo + hi + 1) >> 1;
-                if (a.items[mid].first_chunk <= c) lo = mid; else hi = mid - 1;
+            // 64-way search, a round trip to memory per level instead of one per halving: lane l probes the
+            // l-th of 64 evenly spaced items of the remaining range (first_chunk is increasing, so the lanes
+            // that pass form a prefix)
+            uint32_t lo = 0, n = a.n_items;
+            if (hint != 0xffffffffu) { lo = hint; n = 1; hint = 0xffffffffu; }
+            while (n > 1) {
+                const uint32_t stride = (n + 63) / 64;
+                const uint32_t at = (uint32_t)lane * stride;
+                const bool pass = at < n && a.items[lo + at].first_chunk <= c;
+                const uint32_t k = (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(pass));
+                const uint32_t step = k ? (k - 1) * stride : 0;       // k >= 1 for a valid table: items[lo].first_chunk <= c
+                lo += step;
+                n = n - step < stride ? n - step : stride;
             }
-            // the item's fields are the same for every lane: into scalar registers, they live as long as the tensor
-            const GLOBAL ecf8_batch_item *p = a.items + lo;
-            d_blob = uniform64(p->d_blob); d_out = uniform64(p->d_out); n_elem = uniform64(p->n_elem);
-            n_chunks = uniform64(p->n_chunks); first_chunk = uniform64(p->first_chunk);
-            off_cb = uniform64(p->off_chunk_bit); off_lb = uniform64(p->off_lane_bits);
-            off_st = uniform64(p->off_stream); off_pl = uniform64(p->off_plane); st_bytes = uniform64(p->stream_bytes);
-            off_tbl = uniform64(p->off_table); group = uniform64(p->group_chunks); tcols = uniform64(p->tile_cols);
-            const GLOBAL uint64_t *cl8 = (const GLOBAL uint64_t *)p->code_len;
-            len_lo = uniform64(cl8[0]); len_hi = uniform64(cl8[1]);
+            // the item's 16 words by one load of 16 lanes, then into scalar registers: the fields are the same
+            // for every lane and live as long as the tensor
+            const uint64_t word = ((const GLOBAL uint64_t *)(a.items + lo))[lane & 15];
+            auto field = [&](int k) -> uint64_t {
+                return (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)word, k) |
+                       ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(word >> 32), k) << 32);
+            };
+            static_assert(sizeof(ecf8_batch_item) == 128 && offsetof(ecf8_batch_item, code_len) == 80 &&
+                          offsetof(ecf8_batch_item, tile_cols) == 112, "field numbers below");
+            d_blob = field(0); d_out = field(1); n_elem = field(2); n_chunks = field(3); first_chunk = field(4);
+            off_cb = field(5); off_lb = field(6); off_st = field(7); off_pl = field(8); st_bytes = field(9);
+            len_lo = field(10); len_hi = field(11); off_tbl = field(12); group = field(13); tcols = field(14);
         } else {
             d_blob = a.single.d_blob; d_out = a.single.d_out; n_elem = a.single.n_elem;
             n_chunks = a.single.n_chunks; first_chunk = 0; off_cb = a.single.off_chunk_bit;

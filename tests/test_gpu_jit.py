@@ -232,3 +232,40 @@ def test_decode_launches_replay_from_a_hip_graph():
         ecf8.ecf8_decode_batched(batches[0])
         torch.cuda.synchronize()
         assert all(torch.equal(t, w) for t, w in zip(outs[0], orig[0]))
+
+
+def test_forward_hooks_decode_just_in_time():
+    """Section 3.3 as the paper states it: per-layer decode from PyTorch forward hooks.  A stack of synthetic
+    layers (two FP8 matrices each, multiplied by this library's GEMM on uncompressed weights) holds no weights
+    of its own; JitHooks decodes each layer right before its forward pass into one of two shared buffers and
+    queues the next layer's decode.  Outputs equal those of the same stack on resident weights bit for bit,
+    over three passes, and outside a layer's forward pass its weight attributes are empty."""
+    from paper_2510_02676_amd.jit_hooks import JitHooks
+
+    class Layer(torch.nn.Module):
+        def __init__(self, up=None, down=None):
+            super().__init__()
+            self.up, self.down = up, down
+
+        def forward(self, x):                      # x: (M, 1024) E4M3 bytes
+            assert self.up.numel() and self.down.numel()
+            h = ecf8.ecf8_gemm_fp8_raw(self.up, x)                               # (M, 512) fp32
+            hq = (h / h.abs().amax(dim=1, keepdim=True).clamp(min=1e-30) * 448.0).to(torch.float8_e4m3fn).view(torch.uint8)
+            y = ecf8.ecf8_gemm_fp8_raw(self.down, hq.contiguous())               # (M, 1024) fp32
+            return (y / y.abs().amax(dim=1, keepdim=True).clamp(min=1e-30) * 448.0).to(torch.float8_e4m3fn).view(torch.uint8).contiguous()
+
+    L, M = 5, 8
+    orig, packed = _layers(L, [(512, 1024), (1024, 512)], seed=77)
+    resident = torch.nn.Sequential(*[Layer(*ws) for ws in orig])
+    lazy = torch.nn.Sequential(*[Layer() for _ in range(L)])
+    jit = ecf8.Jit(packed, n_buffers=2)
+    hooks = JitHooks(list(lazy), [["up", "down"]] * L, jit)
+    for rep in range(3):
+        x = synth.activations(M, 1024, seed=900 + rep).to(DEV)
+        want = resident(x)
+        got = lazy(x)
+        torch.cuda.synchronize()
+        assert torch.equal(got, want), rep
+        assert all(layer.up.numel() == 0 and layer.down.numel() == 0 for layer in lazy)
+    hooks.remove()
+    jit.close()
