@@ -13,6 +13,18 @@
  * the index width of the decoder's lookup table, every codeword resolves in one
  * lookup (measured cost on synthetic weights: 0.004 bits per element).
  *
+ * E5M2, second way of storing it (declared here, implemented by ecf8.h): the FP8
+ * container of ecf8.h never interprets its bytes -- it codes bits 6..3 of a byte and
+ * keeps bits 7, 2, 1, 0 raw -- so an E5M2 tensor given to ecf8_encode /
+ * ecf8_encode_gpu is stored with the UPPER FOUR of its five exponent bits as the
+ * coded symbol and the sign, the lowest exponent bit and the mantissa in the raw
+ * nibble; ecf8_decode / ecf8_decode_batched return the exact bytes.  One exponent
+ * bit goes uncoded (0.750 of the raw size against 0.726 for ECFW_FMT_E5M2 on the
+ * synthetic weights), and the decoder is the pair-table one of ecf8.h, two symbols
+ * per lookup, which this chip runs about 1.4 x faster than the one-symbol-per-lookup
+ * decoder a 32-symbol alphabet needs.  Use ECFW_FMT_E5M2 for the smaller blob, the
+ * FP8 container for the faster decode.
+ *
  * Boundary rules are those of ecf8.h: plain pointers and sizes, "host" = CPU
  * memory, "device" = HIP memory of the current device owned by the caller, no
  * allocation or synchronisation of the device by the library, return value

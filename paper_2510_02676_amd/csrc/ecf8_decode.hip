@@ -126,37 +126,6 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
     uint64_t c = units * wg / NWG * unit;
     uint64_t c_end = units * (wg + 1) / NWG * unit;
     if (c_end > a.total_chunks) c_end = a.total_chunks;
-    // A launch over a handful of tensors with not much work per workgroup (one layer's matrices): a range that
-    // crosses from one tensor into the next pays the code set-up twice, a few microseconds that the whole launch
-    // then waits for.  Where it costs at most 6 % in balance, the workgroups are dealt to the tensors instead
-    // (tensor t gets the workgroups [B(t-1), B(t)), B(t) = its share of the chunks so far, rounded) and share a
-    // tensor's chunks evenly, so that no range crosses a tensor boundary.  Every workgroup reaches the same
-    // decision from the same numbers: lane l looks at tensor l.
-    uint32_t hint = 0xffffffffu;      // the tensor this workgroup starts in, when known
-    if (a.items && unit == 1 && a.n_items > 1 && a.n_items <= 64 && a.total_chunks < (1ull << 31) && NWG >= 2ull * a.n_items) {
-        const uint32_t nwg = (uint32_t)NWG, total = (uint32_t)a.total_chunks;
-        const uint32_t nc = (uint32_t)lane < a.n_items ? (uint32_t)a.items[lane].n_chunks : 0u;
-        const uint32_t cum = wave_incl_scan(nc);
-        const uint32_t B = (uint32_t)(((uint64_t)cum * nwg + total / 2) / total);
-        uint32_t Bprev = (uint32_t)__builtin_amdgcn_ds_bpermute(((lane + 63) & 63) * 4, (int)B);
-        if (lane == 0) Bprev = 0;
-        const uint32_t wgs = B - Bprev;
-        const uint32_t load = wgs ? (nc + wgs - 1) / wgs : (nc ? 0x7fffffffu : 0u);
-        const uint32_t even = (total + nwg - 1) / nwg;
-        if (wave_max(load) <= even + even / 16) {
-            const uint64_t mine = __builtin_amdgcn_ballot_w64((uint32_t)lane < a.n_items && (uint32_t)wg >= Bprev && (uint32_t)wg < B);
-            if (mine) {       // always: the B(t) run from 0 to NWG
-                const int t = __builtin_ctzll(mine);
-                const uint32_t nc_t = (uint32_t)__builtin_amdgcn_readlane((int)nc, t), cum_t = (uint32_t)__builtin_amdgcn_readlane((int)cum, t);
-                const uint32_t b0 = (uint32_t)__builtin_amdgcn_readlane((int)Bprev, t), w_t = (uint32_t)__builtin_amdgcn_readlane((int)wgs, t);
-                const uint32_t j = (uint32_t)wg - b0;
-                c = (uint64_t)(cum_t - nc_t) + (uint64_t)nc_t * j / w_t;
-                c_end = (uint64_t)(cum_t - nc_t) + (uint64_t)nc_t * (j + 1) / w_t;
-                hint = (uint32_t)t;
-            }
-        }
-    }
-
     while (c < c_end) {
         // which tensor holds chunk c (uniform)
         uint64_t d_blob, d_out, n_elem, n_chunks, first_chunk, off_cb, off_lb, off_st, off_pl, st_bytes;
@@ -166,7 +135,6 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
             // l-th of 64 evenly spaced items of the remaining range (first_chunk is increasing, so the lanes
             // that pass form a prefix)
             uint32_t lo = 0, n = a.n_items;
-            if (hint != 0xffffffffu) { lo = hint; n = 1; hint = 0xffffffffu; }
             while (n > 1) {
                 const uint32_t stride = (n + 63) / 64;
                 const uint32_t at = (uint32_t)lane * stride;
