@@ -85,13 +85,8 @@ def build_workload(name, seed, lane_syms, layers, launch="layer", group_chunks=0
         al = lambda n: (n + 4095) // 4096 * 4096
         ts = [t for g in sorted(groups) for t in groups[g]]
         nb_all, no_all = sum(al(t["d_blob"].numel()) for t in ts), sum(al(t["d_out"].numel()) for t in ts)
-        gap = int(os.environ.get("ECF8_BENCH_GAP", "-1"))      # working option: both arenas in one allocation, `gap` bytes apart
-        if gap >= 0:
-            both = torch.empty(nb_all + gap + no_all, dtype=torch.uint8, device=dev)
-            blobs, outs = both[:nb_all], both[nb_all + gap:]
-        else:
-            blobs = torch.empty(nb_all, dtype=torch.uint8, device=dev)
-            outs = torch.empty(no_all, dtype=torch.uint8, device=dev)
+        blobs = torch.empty(nb_all, dtype=torch.uint8, device=dev)
+        outs = torch.empty(no_all, dtype=torch.uint8, device=dev)
         ob = oo = 0
         for t in ts:
             nb, no = t["d_blob"].numel(), t["d_out"].numel()
@@ -839,8 +834,9 @@ def main():
                     help="all (default): config3 headline with config1, config2 and plain Huffman beside it; or one of "
                          "config0..config4, jit, encode, wide_bf16, wide_e5m2, encode_bf16, encode_e5m2")
     ap.add_argument("--all-order", default="config3,config2,plain_huffman,config1", help="order of the parts of the default run")
-    ap.add_argument("--churn-gb", type=int, default=0, help=argparse.SUPPRESS)
-    ap.add_argument("--arena", type=int, default=0, help="1: all blobs in one device allocation and all outputs in another")
+    ap.add_argument("--arena", type=int, default=1,
+                    help="1 (default): all blobs of a stack in one device allocation and all outputs in another, the way a serving "
+                         "process holds a model; 0: one allocation per tensor (1-2 points of HBM peak slower)")
     ap.add_argument("--cpu-encode", action="store_true", help="set the stacks up with the CPU encoder instead of the device encoder")
     ap.add_argument("--layers", type=int, default=0, help="0 = the full stack of the workload")
     ap.add_argument("--lane-syms", type=int, default=0, help="0 = library default")
@@ -864,12 +860,6 @@ def main():
         raise SystemExit("no GPU visible: the decode path has no CPU fallback")
     from paper_2510_02676_amd import ecf8
 
-    if a.churn_gb:       # working option: device memory allocated (and with a negative value freed again) before the workload is built
-        dummy = torch.empty(abs(a.churn_gb) << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
-        torch.cuda.synchronize()
-        if a.churn_gb < 0:
-            del dummy
-            torch.cuda.empty_cache()
     if a.workload == "config4":
         return bench_config4(a)
     if a.workload == "jit":
