@@ -344,11 +344,11 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_kernel(GArgs a)
     const uint64_t lane_elem = (uint64_t)(lane & 15) * GK + (uint64_t)(lane >> 4) * 16;
 
     struct Meta { uint64_t b0, b1; uint32_t lb; };
-    struct Payload { u32x4 seg[GSEGS]; u32x2 pl[GPIECES]; };
     const uint64_t n_blocks = a.rows / BLOCK_ROWS;
+    const uint32_t wave_s = uniform32((uint32_t)wave);             // the same for every lane: chunk addresses stay in scalar registers
     // the wave's chunks in the order it meets them: step s = its (s % KPW)-th chunk of its (s / KPW)-th block
     auto block_of = [&](uint64_t s) -> uint64_t { return blockIdx.x + (s / KPW) * (uint64_t)gridDim.x; };
-    auto kc_of = [&](uint64_t s) -> uint32_t { return wave + NW * (uint32_t)(s % KPW); };
+    auto kc_of = [&](uint64_t s) -> uint32_t { return wave_s + NW * (uint32_t)(s % KPW); };
     auto load_meta = [&](uint64_t s) {
         const uint64_t c = block_of(s) * KCHUNKS + kc_of(s);
         Meta m;
@@ -357,40 +357,51 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_kernel(GArgs a)
         m.lb = lane_bits[c * 64 + lane];
         return m;
     };
+    // A chunk's span of the stream (16-byte aligned start, 8 bytes of look-ahead), from the chunk's two start
+    // bits: values every lane holds alike, so the arithmetic is done once, in scalar registers.
     auto span_of = [&](const Meta &m, uint64_t &byte0) {
-        uint64_t byte_end = ((m.b1 + 7) >> 3) + 8;
+        const uint64_t b0 = uniform64(m.b0), b1 = uniform64(m.b1);
+        uint64_t byte_end = ((b1 + 7) >> 3) + 8;
         if (byte_end > a.st_bytes) byte_end = a.st_bytes;
-        byte0 = (m.b0 >> 3) & ~15ull;
+        byte0 = (b0 >> 3) & ~15ull;
         if (byte0 > byte_end) byte0 = byte_end;
         return byte_end - byte0;
     };
-    auto load_payload = [&](uint64_t s, const Meta &m) {
-        Payload p;
+    // The span's 16-byte units into `seg` (unit lane + 64 k into seg[k]); units beyond the span keep what they
+    // held: the lanes' codewords never reach into them.
+    const uint32_t lane16 = (uint32_t)lane * 16;
+    auto load_stream = [&](const Meta &m, u32x4 (&seg)[GSEGS]) {
         uint64_t byte0;
-        const uint64_t span = span_of(m, byte0);
-        const uint64_t e0 = block_of(s) * BLOCK_ROWS * (uint64_t)GK + kc_of(s) * (uint64_t)BLOCK_COLS + lane_elem;
-#pragma unroll
-        for (int q = 0; q < GPIECES; q++)
-            p.pl[q] = __builtin_nontemporal_load((const GLOBAL u32x2 *)(plane + (e0 + 64 * q) / 2));
+        const uint32_t span = (uint32_t)span_of(m, byte0);          // at most GSTAGE under the cap on codewords
+        const GLOBAL uint8_t *sp = stream + byte0;
 #pragma unroll
         for (int k = 0; k < GSEGS; k++) {
-            const uint32_t i = (lane + 64 * k) * 16;
-            p.seg[k] = u32x4{0, 0, 0, 0};
-            if (i < (uint32_t)GSTAGE && i < span)
-                p.seg[k] = __builtin_nontemporal_load((const GLOBAL u32x4 *)(stream + byte0 + i));
+            const uint32_t i = lane16 + 1024 * k;
+            if (i < (uint32_t)GSTAGE && i < span) seg[k] = __builtin_nontemporal_load((const GLOBAL u32x4 *)(sp + i));
         }
-        return p;
+    };
+    // nibble plane of step s: piece q of this lane at plane_of(s) + lane_plane + 32 q
+    const uint32_t lane_plane = (uint32_t)(lane_elem / 2);
+    auto plane_of = [&](uint64_t s) -> const GLOBAL uint8_t * {
+        return plane + (block_of(s) * BLOCK_ROWS * (uint64_t)GK + kc_of(s) * (uint64_t)BLOCK_COLS) / 2;
     };
 
     // start-up: the first chunks' loads and those of X are in flight while the table is set up
     const uint64_t n_steps = blockIdx.x < n_blocks ? ((n_blocks - blockIdx.x + gridDim.x - 1) / gridDim.x) * KPW : 0;
     Meta m_cur{0, 0, 0}, m_next{0, 0, 0};
-    Payload p_cur;
+    u32x4 seg[GSEGS];
+    u32x2 pl[GPIECES];
+#pragma unroll
+    for (int k = 0; k < GSEGS; k++) seg[k] = u32x4{0, 0, 0, 0};
+#pragma unroll
+    for (int q = 0; q < GPIECES; q++) pl[q] = u32x2{0, 0};
     if (n_steps > 0) {
         m_cur = load_meta(0);
-        m_next = m_cur;
-        if (n_steps > 1) m_next = load_meta(1);
-        p_cur = load_payload(0, m_cur);
+        m_next = load_meta(n_steps > 1 ? 1 : 0);
+        load_stream(m_cur, seg);
+        const GLOBAL uint8_t *pp = plane_of(0);
+#pragma unroll
+        for (int q = 0; q < GPIECES; q++) pl[q] = __builtin_nontemporal_load((const GLOBAL u32x2 *)(pp + lane_plane + 32 * q));
     }
 
     u32x4 areg[MT][KPW][GPIECES];
@@ -423,18 +434,15 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_kernel(GArgs a)
             const uint64_t start = uniform64(m.b0);
 #pragma unroll
             for (int k = 0; k < GSEGS; k++) {
-                const uint32_t j = (lane + 64 * k) * 16;
-                if (j < (uint32_t)GSTAGE) *(u32x4 *)(stage + j) = p_cur.seg[k];
+                const uint32_t j = lane16 + 1024 * k;
+                if (j < (uint32_t)GSTAGE) *(u32x4 *)(stage + j) = seg[k];
             }
-            u32x2 pl[GPIECES];
-#pragma unroll
-            for (int q = 0; q < GPIECES; q++) pl[q] = p_cur.pl[q];
-            // the payload registers are free: fetch the next chunk, and the metadata of the one after
-            Meta m_next2 = m_next;
-            if (s + 1 < n_steps) {
-                p_cur = load_payload(s + 1, m_next);
-                if (s + 2 < n_steps) m_next2 = load_meta(s + 2);
-            }
+            // The stream registers are free: fetch the next chunk's span, and the metadata of the chunk after it.
+            // The last steps fetch their own chunk again instead of branching around the loads (sn, sn2).
+            const uint64_t sn = s + 1 < n_steps ? s + 1 : s, sn2 = s + 2 < n_steps ? s + 2 : sn;
+            load_stream(m_next, seg);
+            const Meta m_next2 = load_meta(sn2);
+            const GLOBAL uint8_t *pp = plane_of(sn);
             uint32_t bpA = stage_off * 8 + (uint32_t)(start - byte0 * 8) + rel - 1;   // one bit off, see quad_step2
             uint32_t bpB = bpA + m.lb - 30;
             ChunkSums<MT, SC> sums;
@@ -446,8 +454,13 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_kernel(GArgs a)
                 uint32_t dwA[4], dwB[4];
 #pragma unroll
                 for (int t = 0; t < 4; t++) quad_step2<true>(smem, tbl, s_len, s_code, bpA, bpB, dwA[t], dwB[t]);
-                ECF8_MFMA_PIECE(dstA, areg, i, Q, merge_piece(dwA, pl[Q]));
-                ECF8_MFMA_PIECE(dstB, areg, i, Q + GPIECES / 2, merge_piece(dwB, pl[Q + GPIECES / 2]));
+                // a piece of the nibble plane is merged, and its registers take the same piece of the next chunk
+                const u32x4 wA = merge_piece(dwA, pl[Q]);
+                pl[Q] = __builtin_nontemporal_load((const GLOBAL u32x2 *)(pp + lane_plane + 32 * Q));
+                ECF8_MFMA_PIECE(dstA, areg, i, Q, wA);
+                const u32x4 wB = merge_piece(dwB, pl[Q + GPIECES / 2]);
+                pl[Q + GPIECES / 2] = __builtin_nontemporal_load((const GLOBAL u32x2 *)(pp + lane_plane + 32 * (Q + GPIECES / 2)));
+                ECF8_MFMA_PIECE(dstB, areg, i, Q + GPIECES / 2, wB);
             }
             sums.end(acc, a, lane);
             m_cur = m_next;
@@ -564,7 +577,8 @@ __device__ __forceinline__ void anyk_walk(const GArgs &a, uint8_t *smem, uint32_
     uint16_t *tbl = (uint16_t *)(smem + C::OFF_TBL);
     uint32_t *s_len = (uint32_t *)(smem + C::OFF_SYM);
     uint32_t *s_code = s_len + 16;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = (int)uniform32((uint32_t)tid >> 6);           // the same for every lane: what follows from it stays in scalar registers
     const uint32_t stage_off = C::OFF_STAGE + wave * GSTAGE;
     uint8_t *stage = smem + stage_off;
 
@@ -580,7 +594,6 @@ __device__ __forceinline__ void anyk_walk(const GArgs &a, uint8_t *smem, uint32_
     const uint64_t my_blocks = (my_units + deal.groups - 1) / deal.groups;                                 // units of `groups` blocks
 
     struct Meta { uint64_t b0, b1; uint32_t lb; };
-    struct Payload { u32x4 seg[GSEGS]; u32x2 pl[GPIECES]; };
     auto at_unit = [&](uint64_t b) {
         Walk w{b, 0, first_unit + (b * deal.groups + deal.gi) * unit_stride, 0};
         if constexpr (SPLIT) {
@@ -602,40 +615,52 @@ __device__ __forceinline__ void anyk_walk(const GArgs &a, uint8_t *smem, uint32_
         m.lb = lane_bits[c * 64 + lane];
         return m;
     };
+    // A chunk's span of the stream (16-byte aligned start, 8 bytes of look-ahead), from the chunk's two start
+    // bits: values every lane holds alike, so the arithmetic is done once, in scalar registers.
     auto span_of = [&](const Meta &m, uint64_t &byte0) {
-        uint64_t byte_end = ((m.b1 + 7) >> 3) + 8;
+        const uint64_t b0 = uniform64(m.b0), b1 = uniform64(m.b1);
+        uint64_t byte_end = ((b1 + 7) >> 3) + 8;
         if (byte_end > a.st_bytes) byte_end = a.st_bytes;
-        byte0 = (m.b0 >> 3) & ~15ull;
+        byte0 = (b0 >> 3) & ~15ull;
         if (byte0 > byte_end) byte0 = byte_end;
         return byte_end - byte0;
     };
-    auto load_payload = [&](const Walk &w, const Meta &m) {
-        Payload p;
+    // The span's 16-byte units into `seg` (unit lane + 64 k into seg[k]); units beyond the span keep what they
+    // held: the lanes' codewords never reach into them.
+    const uint32_t lane16 = (uint32_t)lane * 16;
+    auto load_stream = [&](const Meta &m, u32x4 (&seg)[GSEGS]) {
         uint64_t byte0;
-        const uint64_t span = span_of(m, byte0);
-        const uint64_t e0 = block_of(w) * BLOCK_ROWS * a.K + kc_of(w) * (uint64_t)BLOCK_COLS + lane_elem;
-#pragma unroll
-        for (int q = 0; q < GPIECES; q++)
-            p.pl[q] = __builtin_nontemporal_load((const GLOBAL u32x2 *)(plane + (e0 + 64 * q) / 2));
+        const uint32_t span = (uint32_t)span_of(m, byte0);          // at most GSTAGE under the cap on codewords
+        const GLOBAL uint8_t *sp = stream + byte0;
 #pragma unroll
         for (int k = 0; k < GSEGS; k++) {
-            const uint32_t i = (lane + 64 * k) * 16;
-            p.seg[k] = u32x4{0, 0, 0, 0};
-            if (i < (uint32_t)GSTAGE && i < span)
-                p.seg[k] = __builtin_nontemporal_load((const GLOBAL u32x4 *)(stream + byte0 + i));
+            const uint32_t i = lane16 + 1024 * k;
+            if (i < (uint32_t)GSTAGE && i < span) seg[k] = __builtin_nontemporal_load((const GLOBAL u32x4 *)(sp + i));
         }
-        return p;
+    };
+    // nibble plane of a chunk: piece q of this lane at plane_of(w) + lane_plane + 32 q
+    const uint64_t lane_plane = lane_elem / 2;
+    auto plane_of = [&](const Walk &w) -> const GLOBAL uint8_t * {
+        return plane + (block_of(w) * BLOCK_ROWS * a.K + kc_of(w) * (uint64_t)BLOCK_COLS) / 2;
     };
 
     Walk cur = at_unit(0);
     Meta m_cur{0, 0, 0}, m_next{0, 0, 0};
-    Payload p_cur;
+    u32x4 seg[GSEGS];
+    u32x2 pl[GPIECES];
+#pragma unroll
+    for (int k = 0; k < GSEGS; k++) seg[k] = u32x4{0, 0, 0, 0};
+#pragma unroll
+    for (int q = 0; q < GPIECES; q++) pl[q] = u32x2{0, 0};
     XPieces<MT, N> x_cur;
     if (valid(cur)) {
         m_cur = load_meta(cur);
         m_next = m_cur;
         if (valid(next_of(cur))) m_next = load_meta(next_of(cur));
-        p_cur = load_payload(cur, m_cur);
+        load_stream(m_cur, seg);
+        const GLOBAL uint8_t *pp = plane_of(cur) + lane_plane;
+#pragma unroll
+        for (int q = 0; q < GPIECES; q++) pl[q] = __builtin_nontemporal_load((const GLOBAL u32x2 *)(pp + 32 * q));
         load_x_chunk<MT, N>(a, lane, kc_of(cur), x_cur);
     }
 
@@ -665,23 +690,23 @@ __device__ __forceinline__ void anyk_walk(const GArgs &a, uint8_t *smem, uint32_
             const uint64_t start = uniform64(m.b0);
 #pragma unroll
             for (int k = 0; k < GSEGS; k++) {
-                const uint32_t j = (lane + 64 * k) * 16;
-                if (j < (uint32_t)GSTAGE) *(u32x4 *)(stage + j) = p_cur.seg[k];
+                const uint32_t j = lane16 + 1024 * k;
+                if (j < (uint32_t)GSTAGE) *(u32x4 *)(stage + j) = seg[k];
             }
-            u32x2 pl[GPIECES];
-#pragma unroll
-            for (int q = 0; q < GPIECES; q++) pl[q] = p_cur.pl[q];
             const XPieces<MT, N> x = x_cur;
             ChunkSums<MT, SC> sums;
             sums.begin(a, block_of(cur), kc_of(cur));
-            // the payload registers are free: fetch the next chunk and its share of X, and the metadata of the one after
+            // The stream registers are free: fetch the next chunk's span and its share of X, and the metadata of the
+            // chunk after it.  After the last chunk the plane pieces are fetched from that chunk again, not around a branch.
             const Walk nxt = next_of(cur);
+            const bool more = valid(nxt);
             Meta m_next2 = m_next;
-            if (valid(nxt)) {
-                p_cur = load_payload(nxt, m_next);
+            if (more) {
+                load_stream(m_next, seg);
                 load_x_chunk<MT, N>(a, lane, kc_of(nxt), x_cur);
                 if (valid(next_of(nxt))) m_next2 = load_meta(next_of(nxt));
             }
+            const GLOBAL uint8_t *pp = plane_of(more ? nxt : cur) + lane_plane;
             uint32_t bpA = stage_off * 8 + (uint32_t)(start - byte0 * 8) + rel - 1;   // one bit off, see quad_step2
             uint32_t bpB = bpA + m.lb - 30;
             auto &dstA = sums.first(acc);
@@ -691,8 +716,13 @@ __device__ __forceinline__ void anyk_walk(const GArgs &a, uint8_t *smem, uint32_
                 uint32_t dwA[4], dwB[4];
 #pragma unroll
                 for (int t = 0; t < 4; t++) quad_step2<true>(smem, tbl, s_len, s_code, bpA, bpB, dwA[t], dwB[t]);
-                ECF8_MFMA_XPIECE(dstA, x, Q, merge_piece(dwA, pl[Q]));
-                ECF8_MFMA_XPIECE(dstB, x, Q + GPIECES / 2, merge_piece(dwB, pl[Q + GPIECES / 2]));
+                // a piece of the nibble plane is merged, and its registers take the same piece of the next chunk
+                const u32x4 wA = merge_piece(dwA, pl[Q]);
+                pl[Q] = __builtin_nontemporal_load((const GLOBAL u32x2 *)(pp + 32 * Q));
+                ECF8_MFMA_XPIECE(dstA, x, Q, wA);
+                const u32x4 wB = merge_piece(dwB, pl[Q + GPIECES / 2]);
+                pl[Q + GPIECES / 2] = __builtin_nontemporal_load((const GLOBAL u32x2 *)(pp + 32 * (Q + GPIECES / 2)));
+                ECF8_MFMA_XPIECE(dstB, x, Q + GPIECES / 2, wB);
             }
             sums.end(acc, a, lane);
             cur = nxt;
