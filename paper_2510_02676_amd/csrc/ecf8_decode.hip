@@ -47,6 +47,7 @@
 #include "ecf8_device.h"
 
 #include <cstddef>
+#include <type_traits>
 
 namespace {
 
@@ -113,7 +114,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = (int)uniform32((uint32_t)tid >> 6);         // the same for every lane: chunk numbers and addresses stay in scalar registers
     const uint32_t stage_off = C::OFF_WAVES + wave * C::STAGE;   // byte offset into smem
     uint8_t *stage = smem + stage_off;
 
@@ -203,7 +204,6 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
         // ahead (into registers), so HBM latency is covered by the decode of the
         // chunk in hand.
         struct Meta { uint64_t b0, b1; uint32_t lb; };
-        struct Payload { u32x4 s[C::SEGS]; u32x2 pl[C::PIECES]; };
         auto load_meta = [&](uint64_t cl) {
             Meta m;
             m.b0 = chunk_bit[cl];
@@ -211,31 +211,33 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
             m.lb = lane_bits[cl * 64 + lane];
             return m;
         };
-        // span of the stream a chunk needs: 16-byte aligned start, 8 bytes of look-ahead
+        // span of the stream a chunk needs: 16-byte aligned start, 8 bytes of look-ahead.  The chunk's two
+        // start bits are the same in every lane, so the arithmetic is done once, in scalar registers.
         auto span_of = [&](const Meta &m, uint64_t &byte0) {
-            uint64_t byte_end = ((m.b1 + 7) >> 3) + 8;
+            const uint64_t b0 = uniform64(m.b0), b1 = uniform64(m.b1);
+            uint64_t byte_end = ((b1 + 7) >> 3) + 8;
             if (byte_end > st_bytes) byte_end = st_bytes;
-            byte0 = (m.b0 >> 3) & ~15ull;
+            byte0 = (b0 >> 3) & ~15ull;
             if (byte0 > byte_end) byte0 = byte_end;
             return byte_end - byte0;
         };
-        auto issue_payload = [&](uint64_t cl, const Meta &m) {
-            Payload p;
+        // The span's 16-byte units into `seg` (unit lane + 64 k into seg[k]).  Units beyond the span keep what
+        // they held, and so does all of `seg` when the span does not fit a stage: no codeword of a chunk that the
+        // loop decodes for good reaches into them.
+        const uint32_t lane16 = (uint32_t)lane * 16;
+        auto load_stream = [&](const Meta &m, u32x4 (&seg)[C::SEGS]) {
             uint64_t byte0;
             const uint64_t span64 = span_of(m, byte0);
-            const GLOBAL uint8_t *plane_c = plane + (chunk_base(cl) + lane_off) / 2;
-            const uint32_t pstride = chunk_stride(cl) / 2;
-#pragma unroll
-            for (int j = 0; j < C::PIECES; j++) p.pl[j] = LD_STREAM((const GLOBAL u32x2 *)(plane_c + j * pstride));
+            const uint32_t span = span64 <= (uint64_t)C::STAGE ? (uint32_t)span64 : 0u;
+            const GLOBAL uint8_t *sp = stream + byte0;
 #pragma unroll
             for (int k = 0; k < C::SEGS; k++) {
-                const uint32_t i = (lane + 64 * k) * 16;
-                p.s[k] = u32x4{0, 0, 0, 0};
-                if (span64 <= (uint64_t)C::STAGE && i < (uint32_t)span64)
-                    p.s[k] = LD_STREAM((const GLOBAL u32x4 *)(stream + byte0 + i));
+                const uint32_t i = lane16 + 1024 * k;
+                if (i < span) seg[k] = LD_STREAM((const GLOBAL u32x4 *)(sp + i));
             }
-            return p;
         };
+        // nibble plane of chunk cl: this lane's piece j at plane_of(cl) + j * (chunk_stride(cl) / 2)
+        auto plane_of = [&](uint64_t cl) -> const GLOBAL uint8_t * { return plane + chunk_base(cl) / 2 + lane_off / 2; };
 
         // The pipelined loop takes only chunks that are entirely inside the tensor, so its
         // stores are unconditional: between the issue of a prefetch and its use every path
@@ -269,12 +271,21 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
             }
         }
         Meta m_cur{0, 0, 0}, m_next{0, 0, 0};
-        Payload p_cur;
+        u32x4 seg[C::SEGS];
+        u32x2 pl[C::PIECES];
+#pragma unroll
+        for (int k = 0; k < C::SEGS; k++) seg[k] = u32x4{0, 0, 0, 0};
+#pragma unroll
+        for (int j = 0; j < C::PIECES; j++) pl[j] = u32x2{0, 0};
         if (cg < fast_end) {
             m_cur = load_meta(cg - first_chunk);
             m_next = m_cur;
             if (cg1 < fast_end) m_next = load_meta(cg1 - first_chunk);
-            p_cur = issue_payload(cg - first_chunk, m_cur);
+            load_stream(m_cur, seg);
+            const GLOBAL uint8_t *pp = plane_of(cg - first_chunk);
+            const uint32_t pstride = chunk_stride(cg - first_chunk) / 2;
+#pragma unroll
+            for (int j = 0; j < C::PIECES; j++) pl[j] = LD_STREAM((const GLOBAL u32x2 *)(pp + j * pstride));
         }
         if (off_tbl) {
 #pragma unroll
@@ -289,9 +300,11 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
         }
 
         // Decode of one full chunk whose span sits in LDS from bit `first_bit` (smem-relative) on,
-        // merge with the nibble plane, stores.
-        auto decode_store = [&](uint32_t first_bit, uint32_t lb, const u32x2 (&pl)[C::PIECES], GLOBAL uint8_t *out_c,
-                                uint32_t ostride) {
+        // merge with the nibble plane, stores.  With `reload` set, each piece of the nibble plane gives its
+        // registers, once merged, to the same piece of the chunk whose plane starts at next_pl.
+        auto decode_store = [&](auto reload, uint32_t first_bit, uint32_t lb, u32x2 (&pl)[C::PIECES], GLOBAL uint8_t *out_c,
+                                uint32_t ostride, const GLOBAL uint8_t *next_pl, uint32_t next_pstride) {
+            constexpr bool RELOAD = decltype(reload)::value;
             // LDS bit addresses, kept one bit off as quad_step2 wants them: bpA = the forward
             // run's next codeword - 1; bpB = one past the backward run's next codeword - 31
             uint32_t bpA = first_bit - 1;
@@ -309,13 +322,18 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
                 for (int t = 0; t < 4; t++) {
                     quad_step2<PAIRFIT, LONG>(smem, tbl, s_len, s_code, bpA, bpB, dwA[t], dwB[t]);
                 }
+                const u32x4 oA = merge_piece(dwA, pl[Q]);
+                const u32x4 oB = merge_piece(dwB, pl[Q + C::PIECES / 2]);
+                if constexpr (RELOAD) {
+                    pl[Q] = LD_STREAM((const GLOBAL u32x2 *)(next_pl + Q * next_pstride));
+                    pl[Q + C::PIECES / 2] = LD_STREAM((const GLOBAL u32x2 *)(next_pl + (Q + C::PIECES / 2) * next_pstride));
+                }
                 if constexpr (BURST) {
-                    ov[Q] = merge_piece(dwA, pl[Q]);
-                    ov[Q + C::PIECES / 2] = merge_piece(dwB, pl[Q + C::PIECES / 2]);
+                    ov[Q] = oA;
+                    ov[Q + C::PIECES / 2] = oB;
                 } else {
-                    ST_STREAM(merge_piece(dwA, pl[Q]), (GLOBAL u32x4 *)(out_c + Q * ostride));
-                    ST_STREAM(merge_piece(dwB, pl[Q + C::PIECES / 2]),
-                              (GLOBAL u32x4 *)(out_c + (Q + C::PIECES / 2) * ostride));
+                    ST_STREAM(oA, (GLOBAL u32x4 *)(out_c + Q * ostride));
+                    ST_STREAM(oB, (GLOBAL u32x4 *)(out_c + (Q + C::PIECES / 2) * ostride));
                 }
             }
             if constexpr (TILED) {
@@ -362,21 +380,21 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
 
 #pragma unroll
                 for (int k = 0; k < C::SEGS; k++) {
-                    const uint32_t i = (lane + 64 * k) * 16;
-                    if (i < (uint32_t)C::STAGE && (!PAIRFIT || i < (uint32_t)span64)) *(u32x4 *)(stage + i) = p_cur.s[k];
+                    const uint32_t i = lane16 + 1024 * k;
+                    if (i < (uint32_t)C::STAGE && (!PAIRFIT || i < (uint32_t)span64)) *(u32x4 *)(stage + i) = seg[k];
                 }
-                u32x2 pl[C::PIECES];
-#pragma unroll
-                for (int j = 0; j < C::PIECES; j++) pl[j] = p_cur.pl[j];
 
-                // prefetch: next chunk's payload, next-next chunk's metadata
+                // prefetch: the next chunk's span of the stream into the registers just written out, the metadata
+                // of the chunk after it; the next chunk's nibble plane follows piece by piece inside the decode
+                // (after the last chunk: this chunk's plane again, not a branch around the loads)
                 const bool has_next = cg1 < fast_end;
                 Meta m_next2 = m_next;
                 if (has_next) {
-                    p_cur = issue_payload(cg1 - first_chunk, m_next);
+                    load_stream(m_next, seg);
                     cg2 = draw();
                     if (cg2 < fast_end) m_next2 = load_meta(cg2 - first_chunk);
                 }
+                const uint64_t cl_pl = (has_next ? cg1 : cg) - first_chunk;
 
                 if (!staged && lane == 0) {
                     const uint32_t at = __hip_atomic_fetch_add(s_oversize, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -384,7 +402,8 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
                 }
                 // a chunk whose span was not staged decodes stale bits (redone after the loop): its runs are
                 // pinned to the start of the wave's stage, so that every window stays inside this kernel's LDS
-                decode_store(stage_off * 8 + (staged ? bit_in : 64u), staged ? m_cur.lb : 0u, pl, out_c, ostride);
+                decode_store(std::true_type{}, stage_off * 8 + (staged ? bit_in : 64u), staged ? m_cur.lb : 0u, pl, out_c, ostride,
+                             plane_of(cl_pl), chunk_stride(cl_pl) / 2);
 
                 if (!has_next) break;
                 m_cur = m_next;
@@ -427,15 +446,15 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
                         uint64_t byte0;
                         const uint64_t span = span_of(m, byte0);
                         if (span <= (uint64_t)C::SLOT) {          // else: a corrupt blob, left as decoded in the loop
-                            u32x2 pl[C::PIECES];
-                            const GLOBAL uint8_t *plane_c = plane + (chunk_base(cl) + lane_off) / 2;
+                            u32x2 pl_s[C::PIECES];
+                            const GLOBAL uint8_t *plane_c = plane_of(cl);
                             const uint32_t pstride = chunk_stride(cl) / 2;
 #pragma unroll
-                            for (int j = 0; j < C::PIECES; j++) pl[j] = *(const GLOBAL u32x2 *)(plane_c + j * pstride);
+                            for (int j = 0; j < C::PIECES; j++) pl_s[j] = *(const GLOBAL u32x2 *)(plane_c + j * pstride);
                             const uint32_t rel = wave_incl_scan(m.lb) - m.lb;
                             const uint64_t b0 = uniform64(m.b0);
-                            decode_store((C::OFF_WAVES + wave * C::SLOT) * 8 + (uint32_t)(b0 - byte0 * 8) + rel, m.lb, pl,
-                                         out + chunk_base(cl) + lane_off, chunk_stride(cl));
+                            decode_store(std::false_type{}, (C::OFF_WAVES + wave * C::SLOT) * 8 + (uint32_t)(b0 - byte0 * 8) + rel, m.lb, pl_s,
+                                         out + chunk_base(cl) + lane_off, chunk_stride(cl), plane_c, 0u);
                         }
                     }
                 }
