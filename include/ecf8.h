@@ -127,7 +127,8 @@ typedef struct ecf8_header {
 } ecf8_header;
 
 typedef struct ecf8_encode_opts {
-    uint32_t lane_syms;  /* 0 = default (128); 64 is what ecf8_gemm_fp8 needs    */
+    uint32_t lane_syms;  /* 0 = default (128; 64 when max_code_len is above 7);  */
+                         /* 64 is what ecf8_gemm_fp8 needs                       */
     uint32_t n_threads;  /* host threads for encoding, 0 = all hardware threads  */
     uint32_t table_mode; /* 0 = embed the table when n_elem >= 2^22 (32 KiB is   */
                          /* then < 0.8 % of the tensor), 1 = always, 2 = never   */

@@ -92,15 +92,16 @@ struct Cfg {
     static constexpr int OFF_TILE = OFF_WAVES + WAVES_BYTES;  // table-build scratch aliases the stages
     static constexpr int TILE_BYTES = 16 * 4 * N;
     static_assert(!TILED || (PAIRFIT && N == 64), "the tile turn is built for the fused GEMM's layout");
-    static constexpr int TOTAL = OFF_TILE + (TILED ? WAVES * TILE_BYTES : 0);
+    // general kernels: the second level reads one dword past a window's two, so the last stage is followed by a pad
+    static constexpr int TOTAL = OFF_TILE + (TILED ? WAVES * TILE_BYTES : 0) + (PAIRFIT ? 0 : 16);
     static_assert(TOTAL <= 160 * 1024, "LDS of one gfx950 CU");
 };
 
 // PAIRFIT: every tensor of the launch has codewords of at most TB/2 bits (the encoder's
 // default cap), so the pipelined loop needs no second level and is one straight line.
-// LONG (general kernels only): some codeword of the launch is longer than TB bits.  BURST: a chunk's pieces are
-// held in registers and stored together at its end.
-template <int N, int WAVES, bool PAIRFIT, bool TILED = false, bool LONG = !PAIRFIT, bool BURST = PAIRFIT>
+// LONG (general kernels only): some codeword of the launch is longer than TB bits.  BURST: 1 = a chunk's pieces are
+// held in registers and stored together at its end, 2 = half the chunk's pieces at a time, 0 = each piece as it is decoded.
+template <int N, int WAVES, bool PAIRFIT, bool TILED = false, bool LONG = !PAIRFIT, int BURST = PAIRFIT>
 __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
 {
     using C = Cfg<N, WAVES, PAIRFIT, TILED>;
@@ -309,12 +310,12 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
             // run's next codeword - 1; bpB = one past the backward run's next codeword - 31
             uint32_t bpA = first_bit - 1;
             uint32_t bpB = bpA + lb - 30;
-            // PAIRFIT: the chunk's pieces are kept in registers and stored in one burst at
-            // its end.  Together with the interleaved layout the workgroup's waves then
-            // write runs of adjacent KiBs close in time, which HBM takes ~15 % faster than
-            // single KiBs trickling out of every wave as they are decoded; the general
-            // kernel has no registers to spare for that.
-            u32x4 ov[BURST ? C::PIECES : 1];
+            // BURST: the chunk's pieces (or half of them) are kept in registers and stored
+            // together.  With the interleaved layout the workgroup's waves then write runs of
+            // adjacent KiBs close in time, which HBM takes ~15 % faster than single KiBs
+            // trickling out of every wave as they are decoded.  The general kernels have the
+            // registers for a full burst at N = 64 and for half bursts at N = 128.
+            u32x4 ov[BURST == 1 ? C::PIECES : BURST == 2 ? 4 : 1];
 #pragma unroll
             for (int Q = 0; Q < C::PIECES / 2; Q++) {
                 uint32_t dwA[4], dwB[4];
@@ -328,9 +329,21 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
                     pl[Q] = LD_STREAM((const GLOBAL u32x2 *)(next_pl + Q * next_pstride));
                     pl[Q + C::PIECES / 2] = LD_STREAM((const GLOBAL u32x2 *)(next_pl + (Q + C::PIECES / 2) * next_pstride));
                 }
-                if constexpr (BURST) {
+                if constexpr (BURST == 1) {
                     ov[Q] = oA;
                     ov[Q + C::PIECES / 2] = oB;
+                } else if constexpr (BURST == 2) {
+                    // half bursts: the pieces of two steps leave together
+                    ov[2 * (Q & 1)] = oA;
+                    ov[2 * (Q & 1) + 1] = oB;
+                    if (Q & 1) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        ST_STREAM(ov[0], (GLOBAL u32x4 *)(out_c + (Q - 1) * ostride));
+                        ST_STREAM(ov[1], (GLOBAL u32x4 *)(out_c + (Q - 1 + C::PIECES / 2) * ostride));
+                        ST_STREAM(ov[2], (GLOBAL u32x4 *)(out_c + Q * ostride));
+                        ST_STREAM(ov[3], (GLOBAL u32x4 *)(out_c + (Q + C::PIECES / 2) * ostride));
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                 } else {
                     ST_STREAM(oA, (GLOBAL u32x4 *)(out_c + Q * ostride));
                     ST_STREAM(oB, (GLOBAL u32x4 *)(out_c + (Q + C::PIECES / 2) * ostride));
@@ -352,7 +365,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
 #pragma unroll
                 for (int j = 0; j < 4; j++) ST_STREAM(ov[j], (GLOBAL u32x4 *)(out_t + (uint64_t)(4 * j) * tcols));
                 __builtin_amdgcn_sched_barrier(0);
-            } else if constexpr (BURST) {
+            } else if constexpr (BURST == 1) {
                 __builtin_amdgcn_sched_barrier(0);   // keep the stores together, after the decode
 #pragma unroll
                 for (int Q = 0; Q < C::PIECES; Q++) ST_STREAM(ov[Q], (GLOBAL u32x4 *)(out_c + Q * ostride));
@@ -502,7 +515,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
     }
 }
 
-template <int N, int WAVES, bool PAIRFIT, bool TILED = false, bool LONG = !PAIRFIT, bool BURST = PAIRFIT>
+template <int N, int WAVES, bool PAIRFIT, bool TILED = false, bool LONG = !PAIRFIT, int BURST = PAIRFIT>
 int launch_as(const KArgs &a, int wgs_per_cu, hipStream_t s)
 {
     int cus = device_cus();
@@ -516,9 +529,10 @@ int launch_as(const KArgs &a, int wgs_per_cu, hipStream_t s)
     return hipGetLastError() == hipSuccess ? ECF8_OK : ECF8_E_HIP;
 }
 
-// Workgroup shapes.  General kernel: as many waves as the registers allow (its second level
-// makes it latency-bound).  PAIRFIT kernel: N = 128 runs 8 waves of ~220 VGPRs, which is what
-// holding a chunk's 8 output pieces for the store burst takes; it has compute to spare.
+// Workgroup shapes.  PAIRFIT kernels: N = 128 runs 8 waves of ~200 VGPRs, which is what holding a chunk's 8
+// output pieces for the store burst takes; it has compute to spare.  General kernels: 12 waves, the most that
+// leaves registers for a burst (N = 64: the whole chunk; N = 128: half a chunk at a time); N = 32 runs 16 waves
+// and stores piece by piece, which measured faster there.
 int dispatch(const KArgs &a, uint32_t lane_syms, hipStream_t s)
 {
     if (a.max_code_len == 0 || a.max_code_len > 15) return ECF8_E_ARG;
@@ -527,15 +541,15 @@ int dispatch(const KArgs &a, uint32_t lane_syms, hipStream_t s)
     switch (lane_syms) {
     case 32:
         if (pairfit) return launch_as<32, 16, true>(a, 1, s);
-        return lng ? launch_as<32, 16, false, false, true>(a, 1, s) : launch_as<32, 16, false, false, false>(a, 1, s);
+        return lng ? launch_as<32, 16, false, false, true, 0>(a, 1, s) : launch_as<32, 16, false, false, false, 0>(a, 1, s);
     case 64:
         // the fused GEMM's blobs (row-tiled, capped codes): decoded chunks leave as whole row segments
         if (pairfit && a.row_tiled) return launch_as<64, 16, true, true>(a, 1, s);
         if (pairfit) return launch_as<64, 16, true>(a, 1, s);
-        return lng ? launch_as<64, 16, false, false, true>(a, 1, s) : launch_as<64, 16, false, false, false>(a, 1, s);
+        return lng ? launch_as<64, 12, false, false, true, 1>(a, 1, s) : launch_as<64, 12, false, false, false, 1>(a, 1, s);
     case 128:
         if (pairfit) return launch_as<128, 8, true>(a, 1, s);
-        return lng ? launch_as<128, 12, false, false, true>(a, 1, s) : launch_as<128, 12, false, false, false>(a, 1, s);
+        return lng ? launch_as<128, 12, false, false, true, 2>(a, 1, s) : launch_as<128, 12, false, false, false, 2>(a, 1, s);
     default: return ECF8_E_ARG;
     }
 }

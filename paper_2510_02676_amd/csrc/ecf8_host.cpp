@@ -265,10 +265,12 @@ int check_options(uint64_t rows, uint64_t cols, const ecf8_encode_opts *opts, ui
 {
     if (rows == 0 || cols == 0) return ECF8_E_ARG;
     if (rows > (1ull << 40) / cols) return ECF8_E_ARG;
-    const uint32_t N = (opts && opts->lane_syms) ? opts->lane_syms : 128;
     const uint32_t tr = opts ? opts->tile_rows : 0;
     const uint32_t group = (opts && opts->group_chunks) ? opts->group_chunks : (tr ? 1 : 32);
     const uint32_t lmax = (opts && opts->max_code_len) ? opts->max_code_len : ECF8_TB / 2;
+    // symbols per lane: 128 under the default cap; 64 where longer codewords are allowed, the shape the
+    // decode kernels for such codes run fastest at (more waves, a chunk's pieces stored in one burst)
+    const uint32_t N = (opts && opts->lane_syms) ? opts->lane_syms : (lmax > ECF8_TB / 2 ? 64 : 128);
     const uint32_t tmode = opts ? opts->table_mode : 0;
     if (!lane_syms_ok(N) || !group_ok(group) || lmax < 4 || lmax > 15 || tmode > 2) return ECF8_E_ARG;
     if (!tiling_ok(tr, group, rows, cols, N)) return ECF8_E_ARG;

@@ -259,13 +259,14 @@ def test_deterministic_and_on_side_stream(orc):
     assert np.array_equal(a.cpu().numpy().reshape(-1), _oracle_expected(orc, x))
 
 
-@pytest.mark.parametrize("caps", [(0,), (0, 15, 9), (15,)])
-def test_batched_mixed_tensors(orc, caps):
+@pytest.mark.parametrize("caps,lane_syms", [((0,), 0), ((0, 15, 9), 128), ((0, 15, 9), 64), ((15,), 0), ((15,), 128)])
+def test_batched_mixed_tensors(orc, caps, lane_syms):
     """Many tensors, each with its own code, sizes from one lane to many chunks, one launch;
-    all under the default cap (branch-free kernel), mixed caps and plain Huffman (general kernel)."""
+    all under the default cap (branch-free kernel), mixed caps and plain Huffman (general kernels).
+    A batch shares one lane size, and the encoder's default depends on the cap: mixed caps name theirs."""
     sizes = [5, 4096, 70_000, 1, 333_333, 8192 * 3, 1_000_000, 17, 250_000]
     xs = [_rand_bytes(n, 100 + i, conc=0.2 + 0.1 * i) for i, n in enumerate(sizes)]
-    blobs = [ecf8.ecf8_encode(x, 1, x.size, table_mode=1 + (i % 2), max_code_len=caps[i % len(caps)])
+    blobs = [ecf8.ecf8_encode(x, 1, x.size, table_mode=1 + (i % 2), max_code_len=caps[i % len(caps)], lane_syms=lane_syms)
              for i, x in enumerate(xs)]
     d_blobs = [b.to(DEV) for b in blobs]
     pad = 256
