@@ -119,11 +119,11 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
     const uint32_t stage_off = C::OFF_WAVES + wave * C::STAGE;   // byte offset into smem
     uint8_t *stage = smem + stage_off;
 
-    // contiguous range of the batch's chunks for this workgroup
-    // (cut at multiples of 64 chunks when there is enough work, so that the waves of a
-    // workgroup share the interleaved groups of the layout)
+    // contiguous range of the batch's chunks for this workgroup, cut at multiples of 64 or 8 chunks
+    // where that leaves every workgroup at least 16 such units (shares then differ by 1/16 at most),
+    // so that the waves of a workgroup share the interleaved groups of the layout
     const uint64_t NWG = gridDim.x, wg = blockIdx.x;
-    const uint64_t unit = a.total_chunks >= NWG * 128 ? 64 : 1;
+    const uint64_t unit = a.total_chunks >= NWG * 1024 ? 64 : a.total_chunks >= NWG * 128 ? 8 : 1;   // >= 16 units each: shares differ by 1/16 at most
     const uint64_t units = (a.total_chunks + unit - 1) / unit;
     uint64_t c = units * wg / NWG * unit;
     uint64_t c_end = units * (wg + 1) / NWG * unit;
@@ -530,7 +530,8 @@ int launch_as(const KArgs &a, int wgs_per_cu, hipStream_t s)
 }
 
 // Workgroup shapes.  PAIRFIT kernels: N = 128 runs 8 waves of ~200 VGPRs, which is what holding a chunk's 8
-// output pieces for the store burst takes; it has compute to spare.  General kernels: 12 waves, the most that
+// output pieces for the store burst takes; it has compute to spare (6 waves measured the same, 4 a sixth slower);
+// N = 64 runs 12 waves (2 % faster than 16).  General kernels: 12 waves, the most that
 // leaves registers for a burst (N = 64: the whole chunk; N = 128: half a chunk at a time); N = 32 runs 16 waves
 // and stores piece by piece, which measured faster there.
 int dispatch(const KArgs &a, uint32_t lane_syms, hipStream_t s)
@@ -545,7 +546,7 @@ int dispatch(const KArgs &a, uint32_t lane_syms, hipStream_t s)
     case 64:
         // the fused GEMM's blobs (row-tiled, capped codes): decoded chunks leave as whole row segments
         if (pairfit && a.row_tiled) return launch_as<64, 16, true, true>(a, 1, s);
-        if (pairfit) return launch_as<64, 16, true>(a, 1, s);
+        if (pairfit) return launch_as<64, 12, true>(a, 1, s);
         return lng ? launch_as<64, 12, false, false, true, 1>(a, 1, s) : launch_as<64, 12, false, false, false, 1>(a, 1, s);
     case 128:
         if (pairfit) return launch_as<128, 8, true>(a, 1, s);

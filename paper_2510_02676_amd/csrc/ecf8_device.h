@@ -208,49 +208,50 @@ __device__ __forceinline__ void quad_step2(const uint8_t *smem, const uint16_t *
     uint32_t nB2 = (eB2 >> 7) & 15u;
     // n1 == 0 makes the second lookup repeat the first, so n2 == 0 covers both pairs of a run
     if (!PAIRFIT && __builtin_expect(nA2 == 0 || nB2 == 0, 0)) {
-        if constexpr (!LONG) {
-            // Some lane has a pair that needs more than TB bits.  Every codeword fits the table, so an entry without
-            // a pair still names its first symbol and that symbol's length, and the pair's other symbol is the first
-            // symbol of the entry that many bits on.  The whole wave redoes both runs branch-free (a wave takes this
-            // path far more often than a lane needs it): three rounds of lookups, both runs side by side, over
-            // windows of 63 bits made with one more dword each.
-            const uint32_t dA2 = *(const uint32_t *)(smem + aA + 8), dBm = *(const uint32_t *)(smem + aB - 4);
-            const uint64_t WA = wA | ((uint64_t)__builtin_amdgcn_alignbit(dA2, dA1, pa) << 32);
-            const uint64_t WB = wB | ((uint64_t)__brev(__builtin_amdgcn_alignbit(dB0, dBm, pb)) << 32);
-            auto first_len = [](uint32_t e) { return (e & 7u) | ((e >> 12) & 8u); };
-            auto two_firsts = [](uint32_t e, uint32_t x) { return (e & 0x78u) | ((x & 0x78u) << 8); };   // as a pair entry
-            auto entry_at = [&](uint64_t W, uint32_t bits) { return (uint32_t) * (const uint16_t *)(tb + ((uint32_t)(W >> bits) & OFF_MASK)); };
-            // first pairs (at most 28 bits, inside the 31 of the short windows)
-            const uint32_t lA1 = first_len(eA1), lB1 = first_len(eB1);
-            const uint32_t xA1 = *(const uint16_t *)(tb + ((wA >> lA1) & OFF_MASK));
-            const uint32_t xB1 = *(const uint16_t *)(tb + ((wB >> lB1) & OFF_MASK));
-            if (nA1 == 0) { eA1 = two_firsts(eA1, xA1); nA1 = lA1 + first_len(xA1); }
-            if (nB1 == 0) { eB1 = two_firsts(eB1, xB1); nB1 = lB1 + first_len(xB1); }
-            // second pairs, from where the first ones now end (at most 28 + 28 + TB bits from the windows' start)
-            eA2 = entry_at(WA, nA1);
-            eB2 = entry_at(WB, nB1);
-            nA2 = (eA2 >> 7) & 15u;
-            nB2 = (eB2 >> 7) & 15u;
-            const uint32_t lA2 = first_len(eA2), lB2 = first_len(eB2);
-            const uint32_t xA2 = entry_at(WA, nA1 + lA2);
-            const uint32_t xB2 = entry_at(WB, nB1 + lB2);
-            if (nA2 == 0) { eA2 = two_firsts(eA2, xA2); nA2 = lA2 + first_len(xA2); }
-            if (nB2 == 0) { eB2 = two_firsts(eB2, xB2); nB2 = lB2 + first_len(xB2); }
-        } else {
-            if (nA2 == 0) {
-                if (nA1 == 0) pair_second_level<LONG>(wA >> 1, eA1, nA1, tbl, s_len, s_code);   // 31 valid bits, 30 needed
-                // the second level needs up to 30 bits: fresh window after the first pair
-                const uint32_t w2 = lds_window<+1>(smem, pa + 1 + nA1);
+        // Some lane has a pair that needs more than TB bits.  An entry without a pair still names its first symbol
+        // and that symbol's length (unless that codeword alone is longer than TB bits), and the pair's other symbol
+        // is the first symbol of the entry that many bits on.  The whole wave redoes both runs branch-free (a wave
+        // takes this path far more often than a lane needs it): three rounds of lookups, both runs side by side,
+        // over windows of 63 bits made with one more dword each.
+        const uint32_t oA1 = eA1, oB1 = eB1, mA1 = nA1, mB1 = nB1;      // as looked up, for the lanes that start over below
+        const uint32_t dA2 = *(const uint32_t *)(smem + aA + 8), dBm = *(const uint32_t *)(smem + aB - 4);
+        const uint64_t WA = wA | ((uint64_t)__builtin_amdgcn_alignbit(dA2, dA1, pa) << 32);
+        const uint64_t WB = wB | ((uint64_t)__brev(__builtin_amdgcn_alignbit(dB0, dBm, pb)) << 32);
+        auto first_len = [](uint32_t e) { return (e & 7u) | ((e >> 12) & 8u); };
+        auto two_firsts = [](uint32_t e, uint32_t x) { return (e & 0x78u) | ((x & 0x78u) << 8); };   // as a pair entry
+        auto entry_at = [&](uint64_t W, uint32_t bits) { return (uint32_t) * (const uint16_t *)(tb + ((uint32_t)(W >> bits) & OFF_MASK)); };
+        bool beyond = false;                  // LONG: a codeword longer than TB bits is in the way
+        // first pairs (at most 28 bits, inside the 31 of the short windows)
+        const uint32_t lA1 = first_len(eA1), lB1 = first_len(eB1);
+        const uint32_t xA1 = *(const uint16_t *)(tb + ((wA >> lA1) & OFF_MASK));
+        const uint32_t xB1 = *(const uint16_t *)(tb + ((wB >> lB1) & OFF_MASK));
+        if (nA1 == 0) { eA1 = two_firsts(eA1, xA1); nA1 = lA1 + first_len(xA1); beyond |= lA1 == 0 || first_len(xA1) == 0; }
+        if (nB1 == 0) { eB1 = two_firsts(eB1, xB1); nB1 = lB1 + first_len(xB1); beyond |= lB1 == 0 || first_len(xB1) == 0; }
+        // second pairs, from where the first ones now end (at most 28 + 28 + TB bits from the windows' start)
+        eA2 = entry_at(WA, nA1);
+        eB2 = entry_at(WB, nB1);
+        nA2 = (eA2 >> 7) & 15u;
+        nB2 = (eB2 >> 7) & 15u;
+        const uint32_t lA2 = first_len(eA2), lB2 = first_len(eB2);
+        const uint32_t xA2 = entry_at(WA, nA1 + lA2);
+        const uint32_t xB2 = entry_at(WB, nB1 + lB2);
+        if (nA2 == 0) { eA2 = two_firsts(eA2, xA2); nA2 = lA2 + first_len(xA2); beyond |= lA2 == 0 || first_len(xA2) == 0; }
+        if (nB2 == 0) { eB2 = two_firsts(eB2, xB2); nB2 = lB2 + first_len(xB2); beyond |= lB2 == 0 || first_len(xB2) == 0; }
+        if constexpr (LONG) {
+            // rarer than 2^-TB per symbol: such a lane starts over, symbol by symbol, with the matcher for long codewords
+            if (__builtin_expect(beyond, 0)) {
+                eA1 = oA1; nA1 = mA1;
+                if (nA1 == 0) pair_second_level<true>(wA >> 1, eA1, nA1, tbl, s_len, s_code);   // 31 valid bits, 30 needed
+                uint32_t w2 = lds_window<+1>(smem, pa + 1 + nA1);                                // fresh window after the first pair
                 eA2 = tbl[w2 & TBL_MASK];
                 nA2 = (eA2 >> 7) & 15u;
-                if (nA2 == 0) pair_second_level<LONG>(w2, eA2, nA2, tbl, s_len, s_code);
-            }
-            if (nB2 == 0) {
-                if (nB1 == 0) pair_second_level<LONG>(wB >> 1, eB1, nB1, tbl, s_len, s_code);
-                const uint32_t w2 = lds_window<-1>(smem, pb + 31 - nB1);
+                if (nA2 == 0) pair_second_level<true>(w2, eA2, nA2, tbl, s_len, s_code);
+                eB1 = oB1; nB1 = mB1;
+                if (nB1 == 0) pair_second_level<true>(wB >> 1, eB1, nB1, tbl, s_len, s_code);
+                w2 = lds_window<-1>(smem, pb + 31 - nB1);
                 eB2 = tbl[w2 & TBL_MASK];
                 nB2 = (eB2 >> 7) & 15u;
-                if (nB2 == 0) pair_second_level<LONG>(w2, eB2, nB2, tbl, s_len, s_code);
+                if (nB2 == 0) pair_second_level<true>(w2, eB2, nB2, tbl, s_len, s_code);
             }
         }
     }

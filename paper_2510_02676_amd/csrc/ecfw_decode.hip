@@ -282,7 +282,7 @@ __global__ __launch_bounds__(WAVES * 64) void ecfw_decode_kernel(BArgs b)
     // contiguous range of chunks for this workgroup, cut at multiples of 64 chunks when there is
     // enough work so that the waves of a workgroup share the interleaved groups of the layout
     const uint64_t NWG = gridDim.x, wg = blockIdx.x;
-    const uint64_t unit = b.total_chunks >= NWG * 128 ? 64 : 1;
+    const uint64_t unit = b.total_chunks >= NWG * 1024 ? 64 : b.total_chunks >= NWG * 128 ? 8 : 1;   // >= 16 units each: shares differ by 1/16 at most
     const uint64_t units = (b.total_chunks + unit - 1) / unit;
     uint64_t g = units * wg / NWG * unit;              // chunk numbers run through the whole batch
     uint64_t g_end = units * (wg + 1) / NWG * unit;

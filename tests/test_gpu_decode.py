@@ -101,6 +101,29 @@ def test_degenerate_and_extreme_inputs(orc, name, lane_syms, cap):
     assert np.array_equal(got, _oracle_expected(orc, x))
 
 
+@pytest.mark.parametrize("cap", [9, 12, 14])
+@pytest.mark.parametrize("lane_syms", [32, 64, 128])
+def test_long_codes_that_fit_the_table(orc, lane_syms, cap):
+    """Codes between 8 and 14 bits: every codeword is in the table, many pairs of codewords are not, in the first and
+    in the second lookup of a step, in the forward and in the backward run.  Four frequent exponents and a geometric tail
+    of twelve: plain Huffman is 15 deep there, so the cap binds and the tail's codes crowd just under it."""
+    rng = np.random.default_rng(300 + cap)
+    tail = 0.5 ** np.arange(12.0)
+    p = np.concatenate([[0.3, 0.28, 0.2, 0.1], 0.12 * tail / tail.sum()])
+    n = 1_500_000 + lane_syms + 3
+    x = (rng.choice(16, size=n, p=p / p.sum()).astype(np.uint8) << 3) | rng.integers(0, 8, n, dtype=np.uint8) | \
+        (rng.integers(0, 2, n, dtype=np.uint8) << 7)
+    blob = ecf8.ecf8_encode(x, 1, x.size, lane_syms=lane_syms, max_code_len=cap, table_mode=1 + (cap % 2))
+    lens = np.array(list(blob.header.code_len), dtype=np.int64)
+    assert lens.max() == cap                     # the cap binds: plain Huffman is 15 deep on this histogram
+    q = np.bincount((x >> 3) & 15, minlength=16) / x.size
+    pair_too_long = sum(q[i] * q[j] for i in range(16) for j in range(16) if lens[i] + lens[j] > 14)
+    assert pair_too_long * x.size / 2 > 200      # hundreds of such pairs
+    got, guards = _gpu_decode_guarded(blob.numpy(), blob.header)
+    assert guards
+    assert np.array_equal(got, _oracle_expected(orc, x))
+
+
 @pytest.mark.parametrize("lane_syms", [32, 64, 128])
 @pytest.mark.parametrize("island_chunks,workgroups,group", [(6, 0, 1), (40, 1, 1), (150, 1, 1), (150, 0, 1), (150, 0, 32)])
 def test_islands_of_long_codes(orc, lane_syms, island_chunks, workgroups, group):
