@@ -92,8 +92,8 @@ struct Cfg {
     static constexpr int OFF_TILE = OFF_WAVES + WAVES_BYTES;  // table-build scratch aliases the stages
     static constexpr int TILE_BYTES = 16 * 4 * N;
     static_assert(!TILED || (PAIRFIT && N == 64), "the tile turn is built for the fused GEMM's layout");
-    // general kernels: the second level reads one dword past a window's two, so the last stage is followed by a pad
-    static constexpr int TOTAL = OFF_TILE + (TILED ? WAVES * TILE_BYTES : 0) + (PAIRFIT ? 0 : 16);
+    // the decode steps read one dword past a window's two, so the last stage is followed by a pad
+    static constexpr int TOTAL = OFF_TILE + (TILED ? WAVES * TILE_BYTES : 0) + 16;
     static_assert(TOTAL <= 160 * 1024, "LDS of one gfx950 CU");
 };
 
@@ -310,6 +310,8 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
             // run's next codeword - 1; bpB = one past the backward run's next codeword - 31
             uint32_t bpA = first_bit - 1;
             uint32_t bpB = bpA + lb - 30;
+            HeldRuns runs;                 // PAIRFIT: the runs' windows stay in registers
+            if constexpr (PAIRFIT) runs.begin(smem, bpA, bpB);
             // BURST: the chunk's pieces (or half of them) are kept in registers and stored
             // together.  With the interleaved layout the workgroup's waves then write runs of
             // adjacent KiBs close in time, which HBM takes ~15 % faster than single KiBs
@@ -321,7 +323,8 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
                 uint32_t dwA[4], dwB[4];
 #pragma unroll
                 for (int t = 0; t < 4; t++) {
-                    quad_step2<PAIRFIT, LONG>(smem, tbl, s_len, s_code, bpA, bpB, dwA[t], dwB[t]);
+                    if constexpr (PAIRFIT) quad_step_held(smem, tbl, runs, dwA[t], dwB[t]);
+                    else quad_step2<PAIRFIT, LONG>(smem, tbl, s_len, s_code, bpA, bpB, dwA[t], dwB[t]);
                 }
                 const u32x4 oA = merge_piece(dwA, pl[Q]);
                 const u32x4 oB = merge_piece(dwB, pl[Q + C::PIECES / 2]);

@@ -173,50 +173,23 @@ __device__ __forceinline__ uint32_t lds_window(const uint8_t *smem, uint32_t bp)
     return DIR > 0 ? w : __brev(w);
 }
 
-// One decode step of both runs of a lane: four symbols each = two table
-// lookups each.  The two runs are independent, and the common path is one
-// straight line, so their LDS round trips overlap; the second level for pairs
-// that do not fit TB bits is one shared, rarely taken branch.  Returns the four
-// exponent fields of each run in their output byte positions (other bits are
-// noise the merge masks off) and moves the runs past the codewords.
-// The runs' positions are kept one bit off, pa = (next bit of the forward run) - 1
-// and pb = (one past the next bit of the backward run) - 31: the windows read at
-// those positions are the stream bits shifted left by one, i.e. already the byte
-// offset of a 16-bit table entry once masked.
-// PAIRFIT: no codeword is longer than TB/2 bits, so every pair is in the table and
-// the second level is compiled out (a blob that breaks the promise decodes to wrong
-// bytes, in bounds).
-template <bool PAIRFIT, bool LONG = true>
-__device__ __forceinline__ void quad_step2(const uint8_t *smem, const uint16_t *tbl, const uint32_t *s_len,
-                                           const uint32_t *s_code, uint32_t &pa, uint32_t &pb,
-                                           uint32_t &outA, uint32_t &outB)
+// Second level of a decode step: some lane of the wave has a pair that needs more than TB bits.  wA, wB: the runs'
+// 32-bit windows at pa, pb (one bit off, as in quad_step2), WA, WB: the same windows 64 bits long; e and n: the two
+// entries of each run as looked up and their pair lengths, replaced by entries in pair layout and the lengths used.
+// An entry without a pair still names its first symbol and that symbol's length (unless that codeword alone is
+// longer than TB bits), and the pair's other symbol is the first symbol of the entry that many bits on.  The whole
+// wave redoes both runs branch-free (a wave takes this path far more often than a lane needs it): three rounds of
+// lookups, both runs side by side.
+template <bool LONG>
+__device__ __forceinline__ void second_level(const uint8_t *smem, const uint16_t *tbl, const uint32_t *s_len, const uint32_t *s_code,
+                                             uint32_t pa, uint32_t pb, uint32_t wA, uint32_t wB, uint64_t WA, uint64_t WB,
+                                             uint32_t &eA1, uint32_t &nA1, uint32_t &eA2, uint32_t &nA2,
+                                             uint32_t &eB1, uint32_t &nB1, uint32_t &eB2, uint32_t &nB2)
 {
     constexpr uint32_t OFF_MASK = TBL_MASK << 1;
     const uint8_t *tb = (const uint8_t *)tbl;
-    const uint32_t aA = (pa >> 3) & ~3u, aB = (pb >> 3) & ~3u;
-    const uint32_t dA0 = *(const uint32_t *)(smem + aA), dA1 = *(const uint32_t *)(smem + aA + 4);
-    const uint32_t dB0 = *(const uint32_t *)(smem + aB), dB1 = *(const uint32_t *)(smem + aB + 4);
-    const uint32_t wA = __builtin_amdgcn_alignbit(dA1, dA0, pa);
-    const uint32_t wB = __brev(__builtin_amdgcn_alignbit(dB1, dB0, pb));
-    uint32_t eA1 = *(const uint16_t *)(tb + (wA & OFF_MASK));
-    uint32_t eB1 = *(const uint16_t *)(tb + (wB & OFF_MASK));
-    uint32_t nA1 = (eA1 >> 7) & 15u;
-    uint32_t nB1 = (eB1 >> 7) & 15u;
-    uint32_t eA2 = *(const uint16_t *)(tb + ((wA >> nA1) & OFF_MASK));    // >= 17 valid bits left in the window
-    uint32_t eB2 = *(const uint16_t *)(tb + ((wB >> nB1) & OFF_MASK));
-    uint32_t nA2 = (eA2 >> 7) & 15u;
-    uint32_t nB2 = (eB2 >> 7) & 15u;
-    // n1 == 0 makes the second lookup repeat the first, so n2 == 0 covers both pairs of a run
-    if (!PAIRFIT && __builtin_expect(nA2 == 0 || nB2 == 0, 0)) {
-        // Some lane has a pair that needs more than TB bits.  An entry without a pair still names its first symbol
-        // and that symbol's length (unless that codeword alone is longer than TB bits), and the pair's other symbol
-        // is the first symbol of the entry that many bits on.  The whole wave redoes both runs branch-free (a wave
-        // takes this path far more often than a lane needs it): three rounds of lookups, both runs side by side,
-        // over windows of 63 bits made with one more dword each.
+    {
         const uint32_t oA1 = eA1, oB1 = eB1, mA1 = nA1, mB1 = nB1;      // as looked up, for the lanes that start over below
-        const uint32_t dA2 = *(const uint32_t *)(smem + aA + 8), dBm = *(const uint32_t *)(smem + aB - 4);
-        const uint64_t WA = wA | ((uint64_t)__builtin_amdgcn_alignbit(dA2, dA1, pa) << 32);
-        const uint64_t WB = wB | ((uint64_t)__brev(__builtin_amdgcn_alignbit(dB0, dBm, pb)) << 32);
         auto first_len = [](uint32_t e) { return (e & 7u) | ((e >> 12) & 8u); };
         auto two_firsts = [](uint32_t e, uint32_t x) { return (e & 0x78u) | ((x & 0x78u) << 8); };   // as a pair entry
         auto entry_at = [&](uint64_t W, uint32_t bits) { return (uint32_t) * (const uint16_t *)(tb + ((uint32_t)(W >> bits) & OFF_MASK)); };
@@ -255,9 +228,106 @@ __device__ __forceinline__ void quad_step2(const uint8_t *smem, const uint16_t *
             }
         }
     }
+}
+
+// One decode step of both runs of a lane: four symbols each = two table
+// lookups each.  The two runs are independent, and the common path is one
+// straight line, so their LDS round trips overlap; the second level for pairs
+// that do not fit TB bits is one shared, rarely taken branch.  Returns the four
+// exponent fields of each run in their output byte positions (other bits are
+// noise the merge masks off) and moves the runs past the codewords.
+// The runs' positions are kept one bit off, pa = (next bit of the forward run) - 1
+// and pb = (one past the next bit of the backward run) - 31: the windows read at
+// those positions are the stream bits shifted left by one, i.e. already the byte
+// offset of a 16-bit table entry once masked.
+// PAIRFIT: no codeword is longer than TB/2 bits, so every pair is in the table and
+// the second level is compiled out (a blob that breaks the promise decodes to wrong
+// bytes, in bounds).
+template <bool PAIRFIT, bool LONG = true>
+__device__ __forceinline__ void quad_step2(const uint8_t *smem, const uint16_t *tbl, const uint32_t *s_len,
+                                           const uint32_t *s_code, uint32_t &pa, uint32_t &pb,
+                                           uint32_t &outA, uint32_t &outB)
+{
+    constexpr uint32_t OFF_MASK = TBL_MASK << 1;
+    const uint8_t *tb = (const uint8_t *)tbl;
+    const uint32_t aA = (pa >> 3) & ~3u, aB = (pb >> 3) & ~3u;
+    const uint32_t dA0 = *(const uint32_t *)(smem + aA), dA1 = *(const uint32_t *)(smem + aA + 4);
+    const uint32_t dB0 = *(const uint32_t *)(smem + aB), dB1 = *(const uint32_t *)(smem + aB + 4);
+    const uint32_t wA = __builtin_amdgcn_alignbit(dA1, dA0, pa);
+    const uint32_t wB = __brev(__builtin_amdgcn_alignbit(dB1, dB0, pb));
+    uint32_t eA1 = *(const uint16_t *)(tb + (wA & OFF_MASK));
+    uint32_t eB1 = *(const uint16_t *)(tb + (wB & OFF_MASK));
+    uint32_t nA1 = (eA1 >> 7) & 15u;
+    uint32_t nB1 = (eB1 >> 7) & 15u;
+    uint32_t eA2 = *(const uint16_t *)(tb + ((wA >> nA1) & OFF_MASK));    // >= 17 valid bits left in the window
+    uint32_t eB2 = *(const uint16_t *)(tb + ((wB >> nB1) & OFF_MASK));
+    uint32_t nA2 = (eA2 >> 7) & 15u;
+    uint32_t nB2 = (eB2 >> 7) & 15u;
+    // n1 == 0 makes the second lookup repeat the first, so n2 == 0 covers both pairs of a run
+    if (!PAIRFIT && __builtin_expect(nA2 == 0 || nB2 == 0, 0)) {
+        const uint32_t dA2 = *(const uint32_t *)(smem + aA + 8), dBm = *(const uint32_t *)(smem + aB - 4);
+        second_level<LONG>(smem, tbl, s_len, s_code, pa, pb, wA, wB, wA | ((uint64_t)__builtin_amdgcn_alignbit(dA2, dA1, pa) << 32),
+                           wB | ((uint64_t)__brev(__builtin_amdgcn_alignbit(dB0, dBm, pb)) << 32), eA1, nA1, eA2, nA2, eB1, nB1, eB2, nB2);
+    }
     pa += nA1 + nA2;
     pb = pb - nB1 - nB2;
     // bytes 0,1 of the first entry and bytes 0,1 of the second
+    outA = __builtin_amdgcn_perm(eA2, eA1, 0x05040100u);
+    outB = __builtin_amdgcn_perm(eB2, eB1, 0x05040100u);
+}
+
+// The two runs of a lane with their windows held in registers: three consecutive dwords of the LDS image per run
+// (the two a window is made of and the one the run moves into next).  A step then has two LDS round trips on
+// its critical path, the two table lookups, instead of three: the dword that refills the spare is fetched at the
+// end of a step and first needed at the end of the next one.  Positions are kept one bit off as in quad_step2.
+struct HeldRuns {
+    uint32_t pa, pb;           // forward run: next bit - 1; backward run: one past its next bit - 31
+    uint32_t a0, a1, a2;       // dwords at A, A + 4, A + 8 with A = (pa / 8) & ~3
+    uint32_t bm, b0, b1;       // dwords at B - 4, B, B + 4 with B = (pb / 8) & ~3
+
+    __device__ __forceinline__ void begin(const uint8_t *smem, uint32_t pa_, uint32_t pb_)
+    {
+        pa = pa_;
+        pb = pb_;
+        const uint32_t A = (pa >> 3) & ~3u, B = (pb >> 3) & ~3u;
+        a0 = *(const uint32_t *)(smem + A);
+        a1 = *(const uint32_t *)(smem + A + 4);
+        a2 = *(const uint32_t *)(smem + A + 8);
+        bm = *(const uint32_t *)(smem + B - 4);
+        b0 = *(const uint32_t *)(smem + B);
+        b1 = *(const uint32_t *)(smem + B + 4);
+    }
+};
+
+// quad_step2 over held windows, for launches whose pairs always fit the table (PAIRFIT; with a second level in
+// the way the general kernels measured faster on windows fetched per step).  A step moves a run by at most 28 bits,
+// so by at most one dword: bit 5 of the position tells.  The refill reads past the stage of the last wave by up to
+// 8 bytes and before the first one by up to 4: the caller's LDS map has something there.
+__device__ __forceinline__ void quad_step_held(const uint8_t *smem, const uint16_t *tbl, HeldRuns &r, uint32_t &outA, uint32_t &outB)
+{
+    constexpr uint32_t OFF_MASK = TBL_MASK << 1;
+    const uint8_t *tb = (const uint8_t *)tbl;
+    const uint32_t wA = __builtin_amdgcn_alignbit(r.a1, r.a0, r.pa);
+    const uint32_t wB = __brev(__builtin_amdgcn_alignbit(r.b1, r.b0, r.pb));
+    const uint32_t eA1 = *(const uint16_t *)(tb + (wA & OFF_MASK));
+    const uint32_t eB1 = *(const uint16_t *)(tb + (wB & OFF_MASK));
+    const uint32_t nA1 = (eA1 >> 7) & 15u;
+    const uint32_t nB1 = (eB1 >> 7) & 15u;
+    const uint32_t eA2 = *(const uint16_t *)(tb + ((wA >> nA1) & OFF_MASK));    // >= 17 valid bits left in the window
+    const uint32_t eB2 = *(const uint16_t *)(tb + ((wB >> nB1) & OFF_MASK));
+    const uint32_t pa = r.pa + nA1 + ((eA2 >> 7) & 15u);
+    const uint32_t pb = r.pb - nB1 - ((eB2 >> 7) & 15u);
+    const uint32_t ldA = *(const uint32_t *)(smem + ((pa >> 3) & ~3u) + 8);
+    const uint32_t ldB = *(const uint32_t *)(smem + ((pb >> 3) & ~3u) - 4);
+    const bool upA = ((pa ^ r.pa) & 32u) != 0, downB = ((pb ^ r.pb) & 32u) != 0;
+    r.a0 = upA ? r.a1 : r.a0;
+    r.a1 = upA ? r.a2 : r.a1;
+    r.a2 = ldA;                     // the dword at the new A + 8 either way
+    r.b1 = downB ? r.b0 : r.b1;
+    r.b0 = downB ? r.bm : r.b0;
+    r.bm = ldB;
+    r.pa = pa;
+    r.pb = pb;
     outA = __builtin_amdgcn_perm(eA2, eA1, 0x05040100u);
     outB = __builtin_amdgcn_perm(eB2, eB1, 0x05040100u);
 }

@@ -443,8 +443,9 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_kernel(GArgs a)
             load_stream(m_next, seg);
             const Meta m_next2 = load_meta(sn2);
             const GLOBAL uint8_t *pp = plane_of(sn);
-            uint32_t bpA = stage_off * 8 + (uint32_t)(start - byte0 * 8) + rel - 1;   // one bit off, see quad_step2
-            uint32_t bpB = bpA + m.lb - 30;
+            const uint32_t bpA = stage_off * 8 + (uint32_t)(start - byte0 * 8) + rel - 1;   // one bit off, see quad_step2
+            HeldRuns runs;
+            runs.begin(smem, bpA, bpA + m.lb - 30);
             ChunkSums<MT, SC> sums;
             sums.begin(a, block_of(s), kc_of(s));
             auto &dstA = sums.first(acc);
@@ -453,7 +454,7 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_kernel(GArgs a)
             for (int Q = 0; Q < GPIECES / 2; Q++) {
                 uint32_t dwA[4], dwB[4];
 #pragma unroll
-                for (int t = 0; t < 4; t++) quad_step2<true>(smem, tbl, s_len, s_code, bpA, bpB, dwA[t], dwB[t]);
+                for (int t = 0; t < 4; t++) quad_step_held(smem, tbl, runs, dwA[t], dwB[t]);
                 // a piece of the nibble plane is merged, and its registers take the same piece of the next chunk
                 const u32x4 wA = merge_piece(dwA, pl[Q]);
                 pl[Q] = __builtin_nontemporal_load((const GLOBAL u32x2 *)(pp + lane_plane + 32 * Q));
@@ -707,15 +708,16 @@ __device__ __forceinline__ void anyk_walk(const GArgs &a, uint8_t *smem, uint32_
                 if (valid(next_of(nxt))) m_next2 = load_meta(next_of(nxt));
             }
             const GLOBAL uint8_t *pp = plane_of(more ? nxt : cur) + lane_plane;
-            uint32_t bpA = stage_off * 8 + (uint32_t)(start - byte0 * 8) + rel - 1;   // one bit off, see quad_step2
-            uint32_t bpB = bpA + m.lb - 30;
+            const uint32_t bpA = stage_off * 8 + (uint32_t)(start - byte0 * 8) + rel - 1;   // one bit off, see quad_step2
+            HeldRuns runs;
+            runs.begin(smem, bpA, bpA + m.lb - 30);
             auto &dstA = sums.first(acc);
             auto &dstB = sums.second(acc);
 #pragma unroll
             for (int Q = 0; Q < GPIECES / 2; Q++) {
                 uint32_t dwA[4], dwB[4];
 #pragma unroll
-                for (int t = 0; t < 4; t++) quad_step2<true>(smem, tbl, s_len, s_code, bpA, bpB, dwA[t], dwB[t]);
+                for (int t = 0; t < 4; t++) quad_step_held(smem, tbl, runs, dwA[t], dwB[t]);
                 // a piece of the nibble plane is merged, and its registers take the same piece of the next chunk
                 const u32x4 wA = merge_piece(dwA, pl[Q]);
                 pl[Q] = __builtin_nontemporal_load((const GLOBAL u32x2 *)(pp + 32 * Q));
