@@ -33,9 +33,14 @@ struct GCfg {
     static constexpr int OFF_SYM = OFF_TBL + TBL_ENTRIES * 2;
     static constexpr int OFF_STAGE = OFF_SYM + 128;
     static constexpr int OFF_RED = OFF_STAGE + NW * STAGE;
-    static constexpr int RED_BYTES = NW * MT * 64 * 16;            // one buffer of partial sums
-    static constexpr int TOTAL = OFF_RED + 2 * RED_BYTES;
-    static_assert(NW * STAGE + 2 * RED_BYTES >= TBL_ENTRIES * 2, "table-build scratch");
+    static constexpr int RED_BYTES = NW * MT * 64 * 16;            // one buffer of partial sums: one block of rows, every wave
+    // Blocks per barrier.  Up to 16 columns of X with one chunk per wave and block, the workgroup's barrier per block
+    // of rows is a fifth of the loop: there the waves park the partial sums of four blocks in a row in LDS and
+    // meet once to add them up.  Else one block per barrier, in two buffers used in turn.
+    static constexpr int BPB = (MT == 1 && KPW == 1) ? 4 : 1;
+    static constexpr int RED_BUFS = BPB == 1 ? 2 : BPB;
+    static constexpr int TOTAL = OFF_RED + RED_BUFS * RED_BYTES;
+    static_assert(NW * STAGE + RED_BUFS * RED_BYTES >= TBL_ENTRIES * 2, "table-build scratch");
     static_assert(TOTAL <= 160 * 1024, "LDS of one gfx950 CU");
 };
 
@@ -213,6 +218,26 @@ __device__ __forceinline__ void reduce_block(f32x4 *red, const GArgs &a, uint64_
         if (m < a.M) {
             if (SCALED && a.d_xs && a.xs_cols == 1) sum *= ((const GLOBAL float *)a.d_xs)[m];
             Y[(uint64_t)m * a.rows + block * BLOCK_ROWS + (l & 15)] = sum;
+        }
+    }
+}
+
+// reduce_block for `count` blocks of rows at once (up to 16 columns of X): the waves have parked their partial sums of
+// blocks first, first + stride, ... in buffers 0, 1, ... of `red`; the caller's barrier lies between that and this.
+// Every output is summed over the waves in reduce_block's order.
+template <int NW, bool SCALED>
+__device__ __forceinline__ void reduce_parked(const f32x4 *red, const GArgs &a, uint64_t first, uint64_t stride, uint32_t count, int tid)
+{
+    GLOBAL float *Y = (GLOBAL float *)a.d_y;
+    for (uint32_t o = tid; o < count * 256; o += NW * 64) {
+        const uint32_t j = o >> 8, l = (o >> 2) & 63, r = o & 3;
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; w++) sum += ((const float *)&red[(j * NW + w) * 64 + l])[r];
+        const uint32_t m = 4 * (l >> 4) + r;
+        if (m < a.M) {
+            if (SCALED && a.d_xs && a.xs_cols == 1) sum *= ((const GLOBAL float *)a.d_xs)[m];
+            Y[(uint64_t)m * a.rows + (first + j * stride) * BLOCK_ROWS + (l & 15)] = sum;
         }
     }
 }
@@ -467,8 +492,21 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_kernel(GArgs a)
             m_cur = m_next;
             m_next = m_next2;
         }
-        reduce_block<MT, NW, SCALED>((f32x4 *)(smem + C::OFF_RED + parity * C::RED_BYTES), a, block_of(s0), tid, acc);
-        parity ^= 1;
+        if constexpr (C::BPB == 1) {
+            reduce_block<MT, NW, SCALED>((f32x4 *)(smem + C::OFF_RED + parity * C::RED_BYTES), a, block_of(s0), tid, acc);
+            parity ^= 1;
+        } else {
+            // park this block's partial sums; the workgroup meets after every BPB-th block and after the last one
+            f32x4 *red = (f32x4 *)(smem + C::OFF_RED);
+            const uint32_t j = (uint32_t)((s0 / KPW) % C::BPB);
+            red[(j * NW + wave_s) * 64 + lane] = acc[0];
+            const bool last = s0 + KPW >= n_steps;           // the same for the whole workgroup
+            if (j == C::BPB - 1 || last) {
+                __syncthreads();
+                reduce_parked<NW, SCALED>(red, a, block_of(s0 - j * KPW), gridDim.x, j + 1, tid);
+                if (!last) __syncthreads();                  // the buffers are free again
+            }
+        }
     }
 }
 
@@ -480,7 +518,7 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_raw_kernel(GArgs a)
     constexpr bool SCALED = SC != 0;
     using C = GCfg<MT, NW, N>;
     constexpr int KPW = C::KPW, BLOCK_COLS = C::BLOCK_COLS, GPIECES = C::PIECES;
-    __shared__ __attribute__((aligned(16))) uint8_t smem[2 * C::RED_BYTES];
+    __shared__ __attribute__((aligned(16))) uint8_t smem[C::RED_BUFS * C::RED_BYTES];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const GLOBAL uint8_t *W = (const GLOBAL uint8_t *)a.d_w;
     const uint64_t lane_elem = (uint64_t)(lane & 15) * GK + (uint64_t)(lane >> 4) * 16;
@@ -520,8 +558,20 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_raw_kernel(GArgs a)
 #pragma unroll
             for (int q = 0; q < GPIECES; q++) w_cur[q] = w_next[q];
         }
-        reduce_block<MT, NW, SCALED>((f32x4 *)(smem + parity * C::RED_BYTES), a, block_of(s0), tid, acc);
-        parity ^= 1;
+        if constexpr (C::BPB == 1) {
+            reduce_block<MT, NW, SCALED>((f32x4 *)(smem + parity * C::RED_BYTES), a, block_of(s0), tid, acc);
+            parity ^= 1;
+        } else {
+            f32x4 *red = (f32x4 *)smem;                      // as in the fused kernel
+            const uint32_t j = (uint32_t)((s0 / KPW) % C::BPB);
+            red[(j * NW + wave) * 64 + lane] = acc[0];
+            const bool last = s0 + KPW >= n_steps;
+            if (j == C::BPB - 1 || last) {
+                __syncthreads();
+                reduce_parked<NW, SCALED>(red, a, block_of(s0 - j * KPW), gridDim.x, j + 1, tid);
+                if (!last) __syncthreads();
+            }
+        }
     }
 }
 
