@@ -395,9 +395,10 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_kernel(GArgs a)
     // The span's 16-byte units into `seg` (unit lane + 64 k into seg[k]); units beyond the span keep what they
     // held: the lanes' codewords never reach into them.
     const uint32_t lane16 = (uint32_t)lane * 16;
-    auto load_stream = [&](const Meta &m, u32x4 (&seg)[GSEGS]) {
+    auto load_stream = [&](const Meta &m, u32x4 (&seg)[GSEGS], bool wanted = true) {
         uint64_t byte0;
-        const uint32_t span = (uint32_t)span_of(m, byte0);          // at most GSTAGE under the cap on codewords
+        const uint32_t whole = (uint32_t)span_of(m, byte0);         // at most GSTAGE under the cap on codewords
+        const uint32_t span = wanted ? whole : 0u;
         const GLOBAL uint8_t *sp = stream + byte0;
 #pragma unroll
         for (int k = 0; k < GSEGS; k++) {
@@ -463,11 +464,13 @@ __global__ __launch_bounds__(NW * 64) void ecf8_gemm_kernel(GArgs a)
                 if (j < (uint32_t)GSTAGE) *(u32x4 *)(stage + j) = seg[k];
             }
             // The stream registers are free: fetch the next chunk's span, and the metadata of the chunk after it.
-            // The last steps fetch their own chunk again instead of branching around the loads (sn, sn2).
-            const uint64_t sn = s + 1 < n_steps ? s + 1 : s, sn2 = s + 2 < n_steps ? s + 2 : sn;
-            load_stream(m_next, seg);
+            // The last steps have nothing to fetch and no branch around the loads either: the metadata of the last
+            // chunk again (12 bytes), a span of no bytes, and the plane's first chunk, which every wave then asks for.
+            const bool more = s + 1 < n_steps;                 // the same for every lane
+            const uint64_t sn = more ? s + 1 : s, sn2 = s + 2 < n_steps ? s + 2 : sn;
+            load_stream(m_next, seg, more);
             const Meta m_next2 = load_meta(sn2);
-            const GLOBAL uint8_t *pp = plane_of(sn);
+            const GLOBAL uint8_t *pp = more ? plane_of(sn) : plane;
             const uint32_t bpA = stage_off * 8 + (uint32_t)(start - byte0 * 8) + rel - 1;   // one bit off, see quad_step2
             HeldRuns runs;
             runs.begin(smem, bpA, bpA + m.lb - 30);
@@ -679,9 +682,10 @@ __device__ __forceinline__ void anyk_walk(const GArgs &a, uint8_t *smem, uint32_
     // The span's 16-byte units into `seg` (unit lane + 64 k into seg[k]); units beyond the span keep what they
     // held: the lanes' codewords never reach into them.
     const uint32_t lane16 = (uint32_t)lane * 16;
-    auto load_stream = [&](const Meta &m, u32x4 (&seg)[GSEGS]) {
+    auto load_stream = [&](const Meta &m, u32x4 (&seg)[GSEGS], bool wanted = true) {
         uint64_t byte0;
-        const uint32_t span = (uint32_t)span_of(m, byte0);          // at most GSTAGE under the cap on codewords
+        const uint32_t whole = (uint32_t)span_of(m, byte0);         // at most GSTAGE under the cap on codewords
+        const uint32_t span = wanted ? whole : 0u;
         const GLOBAL uint8_t *sp = stream + byte0;
 #pragma unroll
         for (int k = 0; k < GSEGS; k++) {
@@ -748,7 +752,7 @@ __device__ __forceinline__ void anyk_walk(const GArgs &a, uint8_t *smem, uint32_
             ChunkSums<MT, SC> sums;
             sums.begin(a, block_of(cur), kc_of(cur));
             // The stream registers are free: fetch the next chunk's span and its share of X, and the metadata of the
-            // chunk after it.  After the last chunk the plane pieces are fetched from that chunk again, not around a branch.
+            // chunk after it.
             const Walk nxt = next_of(cur);
             const bool more = valid(nxt);
             Meta m_next2 = m_next;
@@ -757,7 +761,8 @@ __device__ __forceinline__ void anyk_walk(const GArgs &a, uint8_t *smem, uint32_
                 load_x_chunk<MT, N>(a, lane, kc_of(nxt), x_cur);
                 if (valid(next_of(nxt))) m_next2 = load_meta(next_of(nxt));
             }
-            const GLOBAL uint8_t *pp = plane_of(more ? nxt : cur) + lane_plane;
+            // after the last chunk the plane pieces are fetched from the plane's first chunk (every wave's last fetch: cached)
+            const GLOBAL uint8_t *pp = (more ? plane_of(nxt) : plane) + lane_plane;
             const uint32_t bpA = stage_off * 8 + (uint32_t)(start - byte0 * 8) + rel - 1;   // one bit off, see quad_step2
             HeldRuns runs;
             runs.begin(smem, bpA, bpA + m.lb - 30);
