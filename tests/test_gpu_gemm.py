@@ -137,6 +137,42 @@ def test_config4_full_size(orc, M):
     _check(fused.cpu().numpy()[:, cols], yref, mag, "config4 M=%d" % M)
 
 
+@pytest.mark.parametrize("rows,M", [(16 * 1300, 1), (16 * 2200, 16), (16 * 2051, 7)])
+def test_tall_matrices_at_k_4096(orc, rows, M):
+    """More than four blocks of 16 rows per workgroup at K = 4096 and up to 16 columns of X: the workgroups park the
+    partial sums of four blocks per barrier, so here the buffers are reused (two or three rounds, the last one with
+    one to four blocks).  Fused equals the twin on uncompressed weights bit for bit, with and without scales; rows
+    from the first, a middle and the last round are checked against the oracle."""
+    K = 4096
+    w = synth.make_weight(rows, K, 1.8, 0.015, 11, device=DEV)
+    x = synth.activations(M, K, seed=rows % 97, device=DEV)
+    hdr, d_blob = ecf8.ecf8_encode_gpu(w.view(torch.uint8), rows, K, lane_syms=64, tile_rows=16)
+    guard = torch.full((M + 2, rows), float("nan"), dtype=torch.float32, device=DEV)
+    fused = ecf8.ecf8_gemm_fp8(hdr, d_blob, x, guard[1:M + 1])
+    raw = ecf8.ecf8_gemm_fp8_raw(w.view(torch.uint8), x)
+    exact = ecf8.ecf8_gemm_fp8_exact(hdr, d_blob, x)
+    exact_raw = ecf8.ecf8_gemm_fp8_raw_exact(w.view(torch.uint8), x)
+    torch.cuda.synchronize()
+    assert torch.isnan(guard[0]).all() and torch.isnan(guard[M + 1]).all()
+    assert torch.equal(fused, raw) and torch.equal(exact, exact_raw)
+    ws, xs = _scales(rows, M, M)
+    d_ws, d_xs = torch.from_numpy(ws).to(DEV), torch.from_numpy(xs).to(DEV)
+    ys = ecf8.ecf8_gemm_fp8_scaled(hdr, d_blob, x, d_ws, d_xs)
+    ys_raw = ecf8.ecf8_gemm_fp8_raw_scaled(w.view(torch.uint8), x, d_ws, d_xs)
+    torch.cuda.synchronize()
+    assert torch.equal(ys, ys_raw)
+    cols = np.unique(np.concatenate([np.arange(0, 48), np.random.default_rng(M).integers(0, rows, 300),
+                                     np.arange(16 * 256 * 4 - 16, 16 * 256 * 4 + 32), np.arange(rows - 48, rows)]))
+    wh = w.view(torch.uint8).cpu().numpy()
+    xh = x.cpu().numpy()
+    yref, mag = orc.gemm_ref(xh, wh[cols])
+    _check(exact.cpu().numpy()[:, cols], yref, mag, "tall exact M=%d" % M, rel=EXACT)
+    _check(fused.cpu().numpy()[:, cols], yref, mag, "tall M=%d" % M)
+    sub = np.arange(0, 256)                      # the first two rows of scale blocks, whole
+    yref_s, mag_s = orc.gemm_ref_scaled(xh, wh[sub], ws[:2], xs)
+    _check(ys.cpu().numpy()[:, sub], yref_s, mag_s, "tall scaled M=%d" % M)
+
+
 def test_gemm_argument_errors():
     x = torch.zeros((4, 4096), dtype=torch.uint8, device=DEV)
     w = torch.zeros((32, 2176), dtype=torch.uint8, device=DEV)
