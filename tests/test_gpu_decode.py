@@ -323,7 +323,7 @@ def test_batch_argument_errors():
 
 # ---------------------------------------------------------------- full-size cases
 
-def _full_size_case(orc, specs, oracle_checks, max_code_len=0, reader_checks=(), gpu_encode=False):
+def _full_size_case(orc, specs, oracle_checks, max_code_len=0, reader_checks=(), gpu_encode=False, arenas=False):
     """Encode/ decode `specs` (full-size tensors, generated on the GPU) in ONE batched launch, the
     launch configuration bench.py times.  Every output is compared with its input on the device
     (decode(encode(x)) == x is the plain definition of the result); the tensors named in
@@ -331,7 +331,8 @@ def _full_size_case(orc, specs, oracle_checks, max_code_len=0, reader_checks=(),
     container's stream length with the oracle's optimum), and for those in `reader_checks` the
     oracle's reader decodes the very container the GPU decoded.  gpu_encode: containers written by the
     device encoder (byte for byte the CPU encoder's, tests/test_gpu_encode.py), which keeps the
-    largest stacks inside the suite's time."""
+    largest stacks inside the suite's time.  arenas: all blobs in one device allocation and all outputs in another,
+    tensors at multiples of 4 KiB, which is how bench.py holds a stack by default."""
     ts = []
     for s in specs:
         w = synth.make(s, 0, device=DEV)
@@ -342,7 +343,19 @@ def _full_size_case(orc, specs, oracle_checks, max_code_len=0, reader_checks=(),
         else:
             b = ecf8.ecf8_encode(w.cpu(), s["rows"], s["cols"], max_code_len=max_code_len)
             h, d_blob = b.header, b.to(DEV)
-        ts.append((s, w, h, d_blob, torch.full_like(w, 0xEE)))
+        ts.append((s, w, h, d_blob, None if arenas else torch.full_like(w, 0xEE)))
+    if arenas:
+        al = lambda n: (n + 4095) // 4096 * 4096
+        blobs = torch.empty(sum(al(t[3].numel()) for t in ts), dtype=torch.uint8, device=DEV)
+        outs = torch.full((sum(al(t[1].numel()) for t in ts),), 0xEE, dtype=torch.uint8, device=DEV)
+        ob = oo = 0
+        for i, (s, w, h, d_blob, _) in enumerate(ts):
+            nb, no = d_blob.numel(), w.numel()
+            blobs[ob:ob + nb].copy_(d_blob)
+            ts[i] = (s, w, h, blobs[ob:ob + nb], outs[oo:oo + no].view(w.shape))
+            ob, oo = ob + al(nb), oo + al(no)
+        del d_blob
+        torch.cuda.empty_cache()
     print("full-size case: %d tensors, %d weights, one launch" % (len(ts), sum(t[1].numel() for t in ts)), flush=True)
     batch = ecf8.Batch([t[2] for t in ts], [t[3] for t in ts], [t[4] for t in ts])
     ecf8.ecf8_decode_batched(batch)
@@ -375,10 +388,10 @@ def test_config1_full_layer(orc, max_code_len):
 
 
 def test_config1_whole_stack_one_launch(orc):
-    """configs[1] at full size in the launch configuration bench.py times: all 32 layers (224
+    """configs[1] at full size in the launch configuration and memory layout bench.py times: all 32 layers (224
     matrices, 6.98 G weights) through ONE ecf8_decode_batched launch; every output compared with
     its input on the device, two matrices also with the oracle's own encode -> bit-serial decode."""
-    _full_size_case(orc, synth.config1(0, 32), {"l17.v", "l31.k"}, gpu_encode=True)
+    _full_size_case(orc, synth.config1(0, 32), {"l17.v", "l31.k"}, gpu_encode=True, arenas=True)
 
 
 def test_config2_experts_and_attention(orc):
@@ -408,7 +421,7 @@ def test_config3_whole_stack_one_launch(orc):
     """configs[3] at full size: all 40 blocks (440 matrices, 20.3 G weights) through ONE
     ecf8_decode_batched launch; every output compared with its input on the device, three matrices of
     a late block also with the oracle."""
-    _full_size_case(orc, synth.config3(40), {"b33.ca_k", "b33.ffn2", "b39.sa_o"}, gpu_encode=True)
+    _full_size_case(orc, synth.config3(40), {"b33.ca_k", "b33.ffn2", "b39.sa_o"}, gpu_encode=True, arenas=True)
 
 
 def test_stream_longer_than_2_to_the_31_bits():
