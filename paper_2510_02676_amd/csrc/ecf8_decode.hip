@@ -186,8 +186,22 @@ __global__ __launch_bounds__(WAVES * 64) void ecf8_decode_kernel(KArgs a)
         if (group == 0) group = 1;
         const uint64_t grouped = (n_elem / (64ull * N)) & ~(group - 1);   // chunks in whole groups (group is a power of two)
         const uint64_t blocks_per_row = tcols ? tcols / (4ull * N) : 1;
+        // Row-tiled: chunk number -> (block of rows, block of columns) is a division by blocks_per_row, which the
+        // hardware does not have: a 64-bit one takes more instructions than the decode of a chunk.  Chunk numbers
+        // and blocks_per_row fit 32 bits (n_elem <= 2^40, checked by the encoder), so the division is a
+        // multiplication by a reciprocal worked out once per tensor (Granlund and Montgomery's round-up method:
+        // q = (t + ((n - t) >> sh1)) >> sh2 with t = mulhi(n, mul), exact for every 32-bit n).
+        const uint32_t bpr32 = (uint32_t)blocks_per_row;
+        uint32_t dv_l = 0;
+        while (dv_l < 32 && (1ull << dv_l) < bpr32) dv_l++;
+        const uint32_t dv_mul = (uint32_t)((((1ull << dv_l) - bpr32) << 32) / bpr32 + 1);
+        const uint32_t dv_sh1 = dv_l < 1 ? dv_l : 1, dv_sh2 = dv_l > 1 ? dv_l - 1 : 0;
         auto chunk_base = [&](uint64_t cl) -> uint64_t {
-            if (tcols) return (cl / blocks_per_row) * 16 * tcols + (cl % blocks_per_row) * (4ull * N);
+            if (tcols) {
+                const uint32_t t = __umulhi((uint32_t)cl, dv_mul);
+                const uint32_t rb = (t + (((uint32_t)cl - t) >> dv_sh1)) >> dv_sh2;
+                return (uint64_t)rb * 16 * tcols + ((uint32_t)cl - rb * bpr32) * (4ull * N);
+            }
             const uint64_t w = cl & (group - 1);
             return cl < grouped ? (cl - w) * (64ull * N) + w * 1024 : cl * (64ull * N);
         };
@@ -570,7 +584,7 @@ int ecf8_decode(const ecf8_header *h, const void *d_blob, void *d_out, uint64_t 
         (h->group_chunks & (h->group_chunks - 1)))
         return ECF8_E_FORMAT;
     if (h->tile_rows != 0 && (h->tile_rows != 16 || h->group_chunks != 1 || h->rows % 16 != 0 || h->cols == 0 ||
-                              h->cols % (4ull * h->lane_syms) != 0 || h->n_elem != h->rows * h->cols))
+                              h->cols % (4ull * h->lane_syms) != 0 || h->rows > (1ull << 40) / h->cols || h->n_elem != h->rows * h->cols))
         return ECF8_E_FORMAT;
     if (h->n_chunks != (h->n_elem + 64ull * h->lane_syms - 1) / (64ull * h->lane_syms)) return ECF8_E_FORMAT;
     if (h->off_plane + h->plane_bytes > h->total_size || h->off_stream + h->stream_bytes > h->off_plane ||

@@ -51,7 +51,8 @@ struct ChunkMap {
 bool tiling_ok(uint32_t tile_rows, uint32_t group, uint64_t rows, uint64_t cols, uint32_t N)
 {
     if (tile_rows == 0) return true;
-    return tile_rows == 16 && group == 1 && rows % 16 == 0 && cols % (4ull * N) == 0;
+    // at most 2^40 elements: the decode kernels number a row-tiled tensor's chunks in 32 bits
+    return tile_rows == 16 && group == 1 && rows % 16 == 0 && cols != 0 && cols % (4ull * N) == 0 && rows <= (1ull << 40) / cols;
 }
 
 // Optimal prefix-code lengths by the two-queue method: leaves sorted by weight
