@@ -196,6 +196,16 @@ def test_hand_example_bytes_in_the_product_container():
     assert list(a[h.off_plane:h.off_plane + 4]) == [0x00, 0x08, 0x04, 0x00]
 
 
+def test_default_symbols_per_lane_follow_the_cap():
+    """lane_syms = 0: 128 under a cap of up to 7 bits (the kernels without a second level), 64 where longer codewords
+    are allowed (what the general kernels decode fastest); a given value is kept; row-tiled blobs name theirs."""
+    x = np.random.default_rng(5).integers(0, 256, 20_000, dtype=np.uint8)
+    for cap, want in ((0, 128), (4, 128), (7, 128), (8, 64), (12, 64), (15, 64)):
+        assert ecf8.ecf8_encode(x, 1, x.size, max_code_len=cap).header.lane_syms == want
+        for given in (32, 64, 128):
+            assert ecf8.ecf8_encode(x, 1, x.size, max_code_len=cap, lane_syms=given).header.lane_syms == given
+
+
 def test_threads_do_not_change_the_blob():
     x = _rand_bytes(1_500_001, 5)
     a = ecf8.ecf8_encode(x, 1, x.size, n_threads=1).numpy().copy()
